@@ -1,0 +1,176 @@
+"""ctypes loader for the CPU oracle (oracle/hsadmm_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  The product package never imports this module,
+and this module never imports the product package.
+
+Functions take and return numpy arrays; all arithmetic happens in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hsadmm_oracle.c")
+_LIB = os.path.join(_HERE, "libhsadmm_oracle.so")
+_lib = None
+
+CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (a no-op when the library is newer than its source)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    tmp = _LIB + ".tmp.%d" % os.getpid()
+    subprocess.check_call(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm"])
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    lib.oracle_set_threads.argtypes = [ctypes.c_int]
+    lib.oracle_set_threads.restype = None
+    lib.oracle_get_threads.restype = ctypes.c_int
+    lib.oracle_project.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p, i32p,
+                                   ctypes.POINTER(f32p), ctypes.c_int32, f32p, f32p, f32p, u8p, f64p]
+    lib.oracle_project.restype = ctypes.c_int
+    lib.oracle_compact.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p, ctypes.c_int32,
+                                   f32p, u8p, f32p, i64p, i32p, i64p]
+    lib.oracle_compact.restype = ctypes.c_int
+    lib.oracle_expand.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p, ctypes.c_int32,
+                                  f32p, u8p, f32p]
+    lib.oracle_expand.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def set_threads(t: int) -> None:
+    _load().oracle_set_threads(int(t))
+
+
+def get_threads() -> int:
+    return int(_load().oracle_get_threads())
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def _cols(table):
+    out = {}
+    for name, dt in (("elem_off", np.int64), ("c_out", np.int32), ("c_in", np.int32),
+                     ("khw", np.int32), ("mode", np.int32), ("k", np.int32)):
+        out[name] = np.ascontiguousarray(table[name], dtype=dt)
+    return out
+
+
+def _poisoned_arena(t, n_arena):
+    """Output arena pre-filled with NaN inside layers (so a write the C code forgets shows) and +0 in padding."""
+    a = np.zeros(int(n_arena), dtype=np.float32)
+    n = t["c_out"].astype(np.int64) * t["c_in"] * t["khw"]
+    for off, cnt in zip(t["elem_off"], n):
+        a[int(off):int(off) + int(cnt)] = np.nan
+    return a
+
+
+def groups_total(table) -> int:
+    t = _cols(table)
+    return int(np.where(t["mode"] == 2, t["c_in"], t["c_out"]).sum())
+
+
+def project(table, W, U, want_wbar: bool = False):
+    """Steps (a)-(d).  W: [R, n_arena] float32; U: [n_arena] float32 (not modified).
+
+    Returns dict(U=new U, Z, mask uint8[groups_total], key float64[groups_total], Wbar or None).
+    """
+    lib = _load()
+    t = _cols(table)
+    L = len(t["c_out"])
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    assert W.ndim == 2
+    R, n_arena = W.shape
+    U_new = np.array(U, dtype=np.float32, copy=True, order="C")
+    assert U_new.shape == (n_arena,)
+    Z = _poisoned_arena(t, n_arena)
+    Wbar = _poisoned_arena(t, n_arena) if want_wbar else None
+    gt = groups_total(t)
+    mask = np.zeros(gt, dtype=np.uint8)
+    key = np.zeros(gt, dtype=np.float64)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    ptrs = (f32p * R)(*[_p(W[r], ctypes.c_float) for r in range(R)])
+    rc = lib.oracle_project(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                            _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
+                            _p(t["mode"], ctypes.c_int32), _p(t["k"], ctypes.c_int32),
+                            ptrs, R, _p(U_new, ctypes.c_float), _p(Z, ctypes.c_float),
+                            _p(Wbar, ctypes.c_float) if want_wbar else None,
+                            _p(mask, ctypes.c_uint8), _p(key, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("oracle_project failed with code %d" % rc)
+    return {"U": U_new, "Z": Z, "mask": mask, "key": key, "Wbar": Wbar}
+
+
+def packed_capacity(table) -> int:
+    t = _cols(table)
+    return int((t["c_out"].astype(np.int64) * t["c_in"] * t["khw"]).sum())
+
+
+def compact(table, src, mask, pack_align: int = 1):
+    """Step (e1).  Returns dict(packed (trimmed to its used length), layer_off int64[L+1], kept_idx int32)."""
+    lib = _load()
+    t = _cols(table)
+    L = len(t["c_out"])
+    src = np.ascontiguousarray(src, dtype=np.float32)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    gt = groups_total(t)
+    assert mask.shape == (gt,)
+    cap = packed_capacity(t) + L * (pack_align - 1)
+    packed = np.zeros(cap, dtype=np.float32)
+    layer_off = np.zeros(L + 1, dtype=np.int64)
+    kept_idx = np.zeros(gt, dtype=np.int32)
+    nk = ctypes.c_int64(0)
+    rc = lib.oracle_compact(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                            _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
+                            _p(t["mode"], ctypes.c_int32), int(pack_align),
+                            _p(src, ctypes.c_float), _p(mask, ctypes.c_uint8),
+                            _p(packed, ctypes.c_float), _p(layer_off, ctypes.c_int64),
+                            _p(kept_idx, ctypes.c_int32), ctypes.byref(nk))
+    if rc != 0:
+        raise ValueError("oracle_compact failed with code %d" % rc)
+    return {"packed": packed[:int(layer_off[L])], "layer_off": layer_off,
+            "kept_idx": kept_idx[:nk.value]}
+
+
+def expand(table, packed, mask, n_arena: int, pack_align: int = 1):
+    """Step (e2).  Returns dst float32[n_arena] (padding between layers stays +0)."""
+    lib = _load()
+    t = _cols(table)
+    L = len(t["c_out"])
+    packed = np.ascontiguousarray(packed, dtype=np.float32)
+    if packed.size == 0:
+        packed = np.zeros(1, dtype=np.float32)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    dst = _poisoned_arena(t, n_arena)
+    rc = lib.oracle_expand(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                           _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
+                           _p(t["mode"], ctypes.c_int32), int(pack_align),
+                           _p(packed, ctypes.c_float), _p(mask, ctypes.c_uint8),
+                           _p(dst, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("oracle_expand failed with code %d" % rc)
+    return dst

@@ -1,0 +1,269 @@
+/*
+ * CPU oracle for the per-layer structured-sparsity step of H-SADMM.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain definition of what the
+ * step computes, written as scalar loops so it can be checked against the
+ * paper by eye.  It shares no code, header, table or constant with the HIP
+ * library and must never be called from the product path: only the tests, the
+ * smoke check and the benchmark's cpu_baseline leg load it.
+ *
+ * Build:  gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC  (no -ffast-math)
+ *
+ * Layer l is the row-major fp32 array W[c_out][c_in][khw] (Section 2, first
+ * paragraph; linear layers have khw = 1) stored at elem_off[l] in every
+ * full-layout arena.  Groups (Section 2.1, "Structured Sparsity Constraints"):
+ *     mode 1, filter  g:  W[g, :, :]   (G = c_out)
+ *     mode 2, channel g:  W[:, g, :]   (G = c_in)
+ *     mode 0, none:       unconstrained layer (Section 2.1, last sentence);
+ *                         its c_out filters are all kept.
+ * Mask and key arrays hold the groups of all layers, concatenated in table
+ * order.
+ *
+ * OpenMP only distributes independent elements / groups / rows over threads;
+ * the order of floating-point operations inside every element and every group
+ * is the same for any thread count, so results are bit-identical to a
+ * single-threaded run.
+ *
+ * Parity pins: tests/test_oracle_*.py (hand-worked layers, brute-force
+ * projection optimality, rank-count vs stable sort, library-routine special
+ * cases, invariants).  No function here is "parity unpinned".
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_NONE = 0, ORACLE_FILTER = 1, ORACLE_CHANNEL = 2 };
+
+static int g_threads = 1;
+
+void oracle_set_threads(int t)
+{
+    g_threads = t < 1 ? 1 : t;
+#ifdef _OPENMP
+    omp_set_num_threads(g_threads);
+#endif
+}
+
+int oracle_get_threads(void) { return g_threads; }
+
+static int64_t n_groups(int mode, int c_out, int c_in)
+{
+    return mode == ORACLE_CHANNEL ? c_in : c_out;
+}
+
+/*
+ * Steps (a)-(d) for every layer.
+ *
+ *  (a) consensus average: Eq. (9) with lambda = 0 and rho_2 = 0 is the plain
+ *      mean over the node's replicas; summed left to right in fp32, then
+ *      multiplied by fl32(1/R).
+ *  (b) candidate V = Wbar + U (the buffer of Algorithm 1, Phase 2) and the
+ *      squared Frobenius norm of each group (Section 2.1), accumulated
+ *      sequentially in fp64 in increasing memory order.  No square root is
+ *      taken: the ranking is the same and no two distinct keys can merge.
+ *  (c) Euclidean projection onto "at most k nonzero groups" (Eq. (10) and the
+ *      paragraph after it): keep the k groups of largest norm; equal norms
+ *      are ranked by lower group index.  Z = V on kept groups, +0 elsewhere.
+ *  (d) dual update U <- U + (Wbar - Z), parenthesised as in Eq. (12).
+ *
+ * W: array of R pointers to full-layout arenas.  U: in/out.  Z, mask, key:
+ * out.  Wbar: out, may be NULL.  Returns 0, or -1 on a bad argument, -2 on a
+ * non-finite input.
+ */
+int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                   const int32_t *khw, const int32_t *mode, const int32_t *k,
+                   const float *const *W, int32_t R, float *U, float *Z, float *Wbar,
+                   uint8_t *mask, double *key)
+{
+    if (L < 1 || R < 1 || !W || !U || !Z || !mask || !key) return -1;
+    const float inv_R = 1.0f / (float)R;
+    int64_t gbase = 0;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
+        const int64_t n = co * ci * s;
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
+        if (co < 1 || ci < 1 || s < 1) return -1;
+        if (mode[l] != ORACLE_NONE && (k[l] < 1 || k[l] > G)) return -1;
+        const int64_t off = elem_off[l];
+        float *wbar = (float *)malloc(sizeof(float) * (size_t)n);
+        float *v = (float *)malloc(sizeof(float) * (size_t)n);
+        if (!wbar || !v) { free(wbar); free(v); return -1; }
+        int bad = 0;
+
+        /* (a), (b): elementwise mean and candidate */
+#pragma omp parallel for schedule(static) reduction(| : bad)
+        for (int64_t e = 0; e < n; ++e) {
+            float acc = W[0][off + e];
+            for (int32_t r = 1; r < R; ++r) acc = acc + W[r][off + e];
+            wbar[e] = acc * inv_R;
+            v[e] = wbar[e] + U[off + e];
+            if (!isfinite(v[e])) bad = 1;
+        }
+        if (bad) { free(wbar); free(v); return -2; }
+
+        /* (b): one fp64 key per group */
+        double *kl = key + gbase;
+        if (mode[l] == ORACLE_CHANNEL) {
+#pragma omp parallel for schedule(static)
+            for (int64_t g = 0; g < G; ++g) {
+                double acc = 0.0;
+                for (int64_t o = 0; o < co; ++o)
+                    for (int64_t t = 0; t < s; ++t) {
+                        const double x = (double)v[(o * ci + g) * s + t];
+                        acc += x * x;
+                    }
+                kl[g] = acc;
+            }
+        } else {
+            const int64_t gs = ci * s;
+#pragma omp parallel for schedule(static)
+            for (int64_t g = 0; g < G; ++g) {
+                double acc = 0.0;
+                for (int64_t t = 0; t < gs; ++t) {
+                    const double x = (double)v[g * gs + t];
+                    acc += x * x;
+                }
+                kl[g] = acc;
+            }
+        }
+
+        /* (c): rank count. Group g is kept iff fewer than k groups precede it
+         * in the order "larger key first, lower index first among equals". */
+        uint8_t *ml = mask + gbase;
+        if (mode[l] == ORACLE_NONE) {
+            for (int64_t g = 0; g < G; ++g) ml[g] = 1;
+        } else {
+            const int64_t kk = k[l];
+#pragma omp parallel for schedule(static)
+            for (int64_t g = 0; g < G; ++g) {
+                int64_t before = 0;
+                for (int64_t h = 0; h < G; ++h)
+                    if (kl[h] > kl[g] || (kl[h] == kl[g] && h < g)) ++before;
+                ml[g] = before < kk ? 1 : 0;
+            }
+        }
+
+        /* (c) projection and (d) dual update */
+#pragma omp parallel for schedule(static)
+        for (int64_t e = 0; e < n; ++e) {
+            int64_t g;
+            if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;
+            else g = e / (ci * s);
+            const float z = ml[g] ? v[e] : 0.0f;
+            Z[off + e] = z;
+            U[off + e] = U[off + e] + (wbar[e] - z);
+            if (Wbar) Wbar[off + e] = wbar[e];
+        }
+        free(wbar);
+        free(v);
+        gbase += G;
+    }
+    return 0;
+}
+
+/* Index sets of Section 4.4.1 ("Tensor Shrinkage"): the kept filters and kept channels of layer l,
+ * ascending (the order nonzero-extraction gives).  A filter mask keeps all
+ * channels, a channel mask keeps all filters, mode none keeps both whole. */
+static void index_sets(int mode, int64_t co, int64_t ci, const uint8_t *ml,
+                       int32_t *k_out, int64_t *n_out, int32_t *k_in, int64_t *n_in)
+{
+    int64_t a = 0, b = 0;
+    for (int64_t o = 0; o < co; ++o)
+        if (mode != ORACLE_FILTER || ml[o]) k_out[a++] = (int32_t)o;
+    for (int64_t c = 0; c < ci; ++c)
+        if (mode != ORACLE_CHANNEL || ml[c]) k_in[b++] = (int32_t)c;
+    *n_out = a;
+    *n_in = b;
+}
+
+/*
+ * Step (e1), tensor shrinkage (Section 4.4.1, Eq. (15)): for every layer
+ *     packed[layer_off[l] + (p*|K_in| + q)*khw + t] = src[l][K_out[p]][K_in[q]][t]
+ * with layer_off[0] = 0 and layer_off[l+1] = roundup(layer_off[l] + size_l,
+ * pack_align).  Offsets are in elements.  kept_idx receives, layer after
+ * layer, the ascending layer-local indices of the kept groups (for mode none:
+ * 0..c_out-1).  Padding elements of `packed` are not written.  The number of
+ * kept groups comes from the mask, not from a k.
+ * Returns 0 or -1.  *n_kept_idx (may be NULL) receives the entries written
+ * to kept_idx.
+ */
+int oracle_compact(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                   const int32_t *khw, const int32_t *mode, int32_t pack_align,
+                   const float *src, const uint8_t *mask,
+                   float *packed, int64_t *layer_off, int32_t *kept_idx, int64_t *n_kept_idx)
+{
+    if (L < 1 || pack_align < 1 || !src || !mask || !packed || !layer_off || !kept_idx) return -1;
+    int64_t gbase = 0, pos = 0, nk = 0;
+    layer_off[0] = 0;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
+        int32_t *k_out = (int32_t *)malloc(sizeof(int32_t) * (size_t)co);
+        int32_t *k_in = (int32_t *)malloc(sizeof(int32_t) * (size_t)ci);
+        if (!k_out || !k_in) { free(k_out); free(k_in); return -1; }
+        int64_t n_out, n_in;
+        index_sets(mode[l], co, ci, mask + gbase, k_out, &n_out, k_in, &n_in);
+        const float *sl = src + elem_off[l];
+        float *pl = packed + pos;
+#pragma omp parallel for schedule(static)
+        for (int64_t p = 0; p < n_out; ++p)
+            for (int64_t q = 0; q < n_in; ++q)
+                for (int64_t t = 0; t < s; ++t)
+                    pl[(p * n_in + q) * s + t] = sl[((int64_t)k_out[p] * ci + k_in[q]) * s + t];
+        if (mode[l] == ORACLE_CHANNEL)
+            for (int64_t q = 0; q < n_in; ++q) kept_idx[nk++] = k_in[q];
+        else
+            for (int64_t p = 0; p < n_out; ++p) kept_idx[nk++] = k_out[p];
+        pos += n_out * n_in * s;
+        pos = (pos + pack_align - 1) / pack_align * pack_align;
+        layer_off[l + 1] = pos;
+        free(k_out);
+        free(k_in);
+        gbase += G;
+    }
+    if (n_kept_idx) *n_kept_idx = nk;
+    return 0;
+}
+
+/*
+ * Step (e2), recovery (Section 4.4.3, "Recovery and Consistency", and its unnumbered equation): dst is
+ * set to +0 everywhere, then dst[l][K_out[p]][K_in[q]][t] = packed[...p,q,t].
+ * Layer offsets inside `packed` are recomputed from the mask exactly as in
+ * oracle_compact.
+ */
+int oracle_expand(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                  const int32_t *khw, const int32_t *mode, int32_t pack_align,
+                  const float *packed, const uint8_t *mask, float *dst)
+{
+    if (L < 1 || pack_align < 1 || !packed || !mask || !dst) return -1;
+    int64_t gbase = 0, pos = 0;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
+        int32_t *k_out = (int32_t *)malloc(sizeof(int32_t) * (size_t)co);
+        int32_t *k_in = (int32_t *)malloc(sizeof(int32_t) * (size_t)ci);
+        if (!k_out || !k_in) { free(k_out); free(k_in); return -1; }
+        int64_t n_out, n_in;
+        index_sets(mode[l], co, ci, mask + gbase, k_out, &n_out, k_in, &n_in);
+        float *dl = dst + elem_off[l];
+        const float *pl = packed + pos;
+        const int64_t n = co * ci * s;
+#pragma omp parallel for schedule(static)
+        for (int64_t e = 0; e < n; ++e) dl[e] = 0.0f;
+#pragma omp parallel for schedule(static)
+        for (int64_t p = 0; p < n_out; ++p)
+            for (int64_t q = 0; q < n_in; ++q)
+                for (int64_t t = 0; t < s; ++t)
+                    dl[((int64_t)k_out[p] * ci + k_in[q]) * s + t] = pl[(p * n_in + q) * s + t];
+        pos += n_out * n_in * s;
+        pos = (pos + pack_align - 1) / pack_align * pack_align;
+        free(k_out);
+        free(k_in);
+        gbase += G;
+    }
+    return 0;
+}

@@ -1,0 +1,78 @@
+"""Planted-mistake check of the pins themselves, entirely on the CPU.
+
+Each mutation is a plausible slip in oracle/hsadmm_oracle.c.  The mutated source is compiled to a
+temporary library, swapped in for the oracle, and the pin tests are re-run in-process: at least one of
+them must fail.  The mistakes are planted in the oracle only; nothing here touches the GPU path.
+"""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+import oracle
+from tests import test_oracle_pins as pins
+
+MUTATIONS = [
+    ("tie_goes_to_higher_index", "(kl[h] == kl[g] && h < g)", "(kl[h] == kl[g] && h > g)"),
+    ("ties_ignored", "kl[h] > kl[g] || (kl[h] == kl[g] && h < g)", "kl[h] > kl[g]"),
+    ("keeps_smallest", "if (kl[h] > kl[g] ||", "if (kl[h] < kl[g] ||"),
+    ("keeps_k_plus_one", "ml[g] = before < kk ? 1 : 0;", "ml[g] = before <= kk ? 1 : 0;"),
+    ("channel_index_transposed", "v[(o * ci + g) * s + t]", "v[(g * co + o) * s + t]"),
+    ("channel_of_element_wrong", "g = (e / s) % ci;", "g = (e % (ci * s)) % ci;"),
+    ("dual_regrouped", "U[off + e] = U[off + e] + (wbar[e] - z);", "U[off + e] = (U[off + e] + wbar[e]) - z;"),
+    ("dual_sign", "U[off + e] = U[off + e] + (wbar[e] - z);", "U[off + e] = U[off + e] - (wbar[e] - z);"),
+    ("mean_by_division", "wbar[e] = acc * inv_R;", "wbar[e] = acc / (float)R;"),
+    ("mean_drops_last_replica", "for (int32_t r = 1; r < R; ++r) acc", "for (int32_t r = 1; r < R - 1; ++r) acc"),
+    ("candidate_drops_dual", "v[e] = wbar[e] + U[off + e];", "v[e] = wbar[e];"),
+    ("key_in_fp32", "const double x = (double)v[g * gs + t];\n                    acc += x * x;",
+     "const float x = v[g * gs + t];\n                    acc += (double)(x * x);"),
+    ("key_is_abs_sum", "const double x = (double)v[g * gs + t];\n                    acc += x * x;",
+     "const double x = (double)v[g * gs + t];\n                    acc += fabs(x);"),
+    ("pack_transposed", "pl[(p * n_in + q) * s + t] = sl[", "pl[(q * n_out + p) * s + t] = sl["),
+    ("pack_align_ignored", "pos = (pos + pack_align - 1) / pack_align * pack_align;\n        layer_off[l + 1] = pos;",
+     "layer_off[l + 1] = pos;"),
+    ("expand_no_zero_fill", "for (int64_t e = 0; e < n; ++e) dl[e] = 0.0f;", "for (int64_t e = 0; e < 0; ++e) dl[e] = 0.0f;"),
+    ("none_layer_is_pruned", "if (mode[l] == ORACLE_NONE) {\n            for (int64_t g = 0; g < G; ++g) ml[g] = 1;",
+     "if (0) {\n            for (int64_t g = 0; g < G; ++g) ml[g] = 1;"),
+    ("filter_mask_prunes_channels_too", "if (mode != ORACLE_CHANNEL || ml[c]) k_in[b++]", "if (mode == ORACLE_NONE || ml[c % co]) k_in[b++]"),
+]
+
+PIN_FUNCS = [
+    lambda: [pins.test_handworked_layer(c) for c in pins.CASES],
+    pins.test_handworked_two_layer_offsets_and_alignment,
+    lambda: [pins.test_projection_is_the_euclidean_projection_by_brute_force(m, 0) for m in (1, 2)],
+    lambda: [pins.test_against_numpy_library_routines(s) for s in range(3)],
+    pins.test_compact_takes_an_arbitrary_source_and_mask,
+    pins.test_ties_identical_groups_resolve_by_lower_index,
+    pins.test_dual_update_parenthesisation_of_eq_12,
+    pins.test_mean_is_left_to_right_sum_times_reciprocal,
+    pins.test_eq_9_reduces_to_plain_mean_plus_mean_dual,
+    pins.test_invariants_on_tiny_and_random_workloads,
+    pins.test_identity_cases,
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_a_planted_mistake_in_the_oracle_fails_a_pin(name, old, new, tmp_path, monkeypatch):
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "hsadmm_oracle.c")).read()
+    assert src.count(old) >= 1, "mutation target not found: %s" % name
+    mutated = src.replace(old, new, 1)
+    c_file = tmp_path / "mut.c"
+    so_file = tmp_path / "libmut.so"
+    c_file.write_text(mutated)
+    subprocess.check_call(["gcc", *[f for f in oracle.CFLAGS if f not in ("-Wall", "-Wextra")], "-w",
+                           "-o", str(so_file), str(c_file), "-lm"])
+    good = oracle._load()
+    lib = ctypes.CDLL(str(so_file))
+    for fn in ("oracle_project", "oracle_compact", "oracle_expand", "oracle_set_threads", "oracle_get_threads"):
+        getattr(lib, fn).argtypes = getattr(good, fn).argtypes
+        getattr(lib, fn).restype = getattr(good, fn).restype
+    monkeypatch.setattr(oracle, "_lib", lib)
+    failed = 0
+    for f in PIN_FUNCS:
+        try:
+            f()
+        except (AssertionError, ValueError):
+            failed += 1
+    assert failed >= 1, "no pin noticed the planted mistake %r" % name
