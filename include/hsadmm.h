@@ -1,0 +1,179 @@
+/*
+ * hsadmm.h -- C ABI of the MI355X (gfx950) library for the per-layer
+ * structured-sparsity step of H-SADMM (PruneX, arXiv 2512.14628).
+ *
+ * The step is what a node runs between local training and inter-node
+ * synchronisation (Algorithm 1, Phases 2-5, restricted to one device):
+ *
+ *   (a) consensus average of R replica weight buffers     Eq. (9) with lambda = 0, rho_2 = 0
+ *   (b) candidate V = Wbar + U and per-group squared norm  Algorithm 1 Phase 2; Section 2.1
+ *   (c) per-layer top-k group selection, Z = Pi_S(V)       Eq. (10) and the paragraph after it
+ *   (d) dual update U <- U + (Wbar - Z)                    Eq. (12)
+ *   (e) tensor shrinkage / recovery of the kept groups     Section 4.4.1 Eq. (15); Section 4.4.3
+ *
+ * Data layout.  A layer is the row-major fp32 array W[c_out][c_in][khw]
+ * (Section 2, first paragraph; khw = K_H*K_W, 1 for linear layers).  A
+ * "full-layout arena" is one device buffer that holds every layer at the
+ * element offset `elem_off` of its table entry; all arenas passed to one plan
+ * (each replica, U, Z, Wbar, src, dst) share that table.  Groups (Section
+ * 2.1): FILTER group g = W[g,:,:] (G = c_out), CHANNEL group g = W[:,g,:]
+ * (G = c_in); a NONE layer is unconstrained and contributes G = c_out groups
+ * that are always kept.  `mask` and `sqnorm` hold the groups of all layers
+ * concatenated in table order.
+ *
+ * Ownership.  The caller owns every device buffer and the stream.  The
+ * library owns only the plan (host tables plus a device copy, allocated in
+ * hsadmm_plan_create on the current device and released in
+ * hsadmm_plan_destroy).  The three hot calls allocate nothing, never
+ * synchronise the device, and enqueue all their work on `hip_stream`
+ * (a hipStream_t passed as void*; NULL is the default stream).  Outputs are
+ * valid once the caller has synchronised that stream.
+ *
+ * Errors.  Every call returns HSADMM_OK (0) or a negative code.  Arguments
+ * are validated before anything is enqueued, so a call that returns an
+ * argument error has had no effect on device memory.  No exceptions cross
+ * the boundary.  Calls on one plan from several host threads are safe when
+ * each uses its own workspace.
+ *
+ * Preconditions that are not checked: all input values are finite; buffers
+ * do not alias except where stated.
+ */
+#ifndef HSADMM_H
+#define HSADMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HSADMM_OK                     0
+#define HSADMM_ERR_INVALID_ARGUMENT  -1   /* null pointer, bad size, bad table entry, misaligned pointer */
+#define HSADMM_ERR_WORKSPACE         -2   /* workspace_bytes smaller than hsadmm_plan_sizes reports */
+#define HSADMM_ERR_HIP               -3   /* a HIP runtime call or a kernel launch failed */
+#define HSADMM_ERR_UNSUPPORTED       -4   /* valid request beyond a compiled limit (R > HSADMM_MAX_REPLICAS, ...) */
+
+#define HSADMM_MODE_NONE     0
+#define HSADMM_MODE_FILTER   1
+#define HSADMM_MODE_CHANNEL  2
+
+#define HSADMM_MAX_REPLICAS  16
+#define HSADMM_MAX_LAYERS    4096
+
+/* One table entry per layer.  Host memory, caller-owned, copied by hsadmm_plan_create. */
+typedef struct {
+    int64_t elem_off;   /* offset of the layer, in elements, in every full-layout arena; multiple of 4 */
+    int32_t c_out;      /* >= 1 */
+    int32_t c_in;       /* >= 1 */
+    int32_t khw;        /* >= 1; K_H*K_W, 1 for linear layers */
+    int32_t mode;       /* HSADMM_MODE_* */
+    int32_t k;          /* groups kept (the paper's alpha), 1 <= k <= G; ignored for MODE_NONE */
+} hsadmm_layer_t;
+
+typedef struct hsadmm_plan hsadmm_plan_t;   /* opaque, immutable after creation */
+
+/*
+ * Build a plan for a table of L layers (1 <= L <= HSADMM_MAX_LAYERS).
+ * Layers must not overlap and must appear in increasing elem_off order.
+ * pack_align_elems >= 1: every layer's segment of the packed buffer starts
+ * at a multiple of this many elements (1 = tight packing).
+ * Needs a HIP device (tables are copied to the current device).
+ * Errors: INVALID_ARGUMENT (table), HIP (no device / allocation failure).
+ */
+int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_align_elems,
+                       hsadmm_plan_t** out);
+
+/* Releases the plan's host and device memory.  NULL is ignored.  The caller
+ * must have synchronised every stream that still runs work of this plan. */
+void hsadmm_plan_destroy(hsadmm_plan_t* plan);
+
+/*
+ * Sizes a caller needs to allocate buffers (any output pointer may be NULL):
+ *   arena_elems            minimum length of a full-layout arena, in elements
+ *   groups_total           length of mask / sqnorm / kept_idx
+ *   packed_capacity_elems  length of `packed` that fits any mask
+ *   workspace_bytes        size of the scratch buffer the three hot calls take
+ */
+int hsadmm_plan_sizes(const hsadmm_plan_t* plan, int64_t* arena_elems, int64_t* groups_total,
+                      int64_t* packed_capacity_elems, size_t* workspace_bytes);
+
+/*
+ * Steps (a)-(d) for every layer of the plan.
+ *
+ *   W_replicas  HOST array of R DEVICE pointers, each a full-layout arena (read only)
+ *   R           1 <= R <= HSADMM_MAX_REPLICAS
+ *   U           device, in/out: the (replica-mean) scaled dual variable, updated in place
+ *   Z           device, out: the projected node consensus; +0 on pruned groups
+ *   Wbar        device, out, may be NULL: the consensus average
+ *   mask        device, out, groups_total bytes: 1 = group kept; exactly k ones per constrained layer
+ *   sqnorm      device, out, may be NULL, groups_total doubles: squared Frobenius norm of each group of V
+ *   workspace   device scratch of workspace_bytes >= hsadmm_plan_sizes' figure, 256-byte aligned
+ *
+ * Arithmetic (fp32 unless stated; no fused multiply-add across these steps):
+ *   Wbar = ((W_0 + W_1) + ... + W_{R-1}) * fl32(1/R);  V = Wbar + U;
+ *   sqnorm_g = sum over the group of (double)V^2, in fp64 (summation order is
+ *   fixed per layer shape, the same for every group of a layer);
+ *   a group is kept iff fewer than k groups of its layer have a larger
+ *   sqnorm, or an equal sqnorm and a lower index;
+ *   Z = V on kept groups, +0 elsewhere;  U <- U + (Wbar - Z).
+ *
+ * All arena pointers must be 16-byte aligned.  Z, Wbar, mask, sqnorm and the
+ * workspace must not alias each other or any input.  Padding elements of the
+ * arenas (outside every layer) are neither read nor written.
+ * Errors: INVALID_ARGUMENT, WORKSPACE, UNSUPPORTED, HIP.
+ */
+int hsadmm_project(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                   float* U, float* Z, float* Wbar, uint8_t* mask, double* sqnorm,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Step (e1), tensor shrinkage: packs the kept slices of `src` into one
+ * contiguous dense buffer, layer after layer,
+ *     packed[layer_off[l] + (p*|K_in| + q)*khw + t] = src[l][K_out[p]][K_in[q]][t]
+ * where K_out / K_in are the ascending kept filter / channel indices the mask
+ * gives (FILTER: K_in is every channel; CHANNEL: K_out is every filter; NONE:
+ * both are everything).  The number of kept groups is read from the mask (any
+ * count 0..G), not from the plan's k, so a union of several masks is valid.
+ *
+ *   src        device, full-layout arena (read only), 16-byte aligned
+ *   mask       device, groups_total bytes, nonzero = kept
+ *   packed     device, out, at least packed_capacity_elems elements; only
+ *              layer_off[L] elements are meaningful; alignment padding between
+ *              segments is not written
+ *   layer_off  device, out, L+1 int64: start of every layer's segment in
+ *              elements; layer_off[0] = 0, layer_off[l+1] =
+ *              roundup(layer_off[l] + size_l, pack_align_elems)
+ *   kept_idx   device, out, groups_total int32 capacity: per layer, the
+ *              ascending layer-local indices of its kept groups, concatenated
+ *              without gaps (entries past the total kept count are not written)
+ * Errors: INVALID_ARGUMENT, WORKSPACE, HIP.
+ */
+int hsadmm_compact(const hsadmm_plan_t* plan, const float* src, const uint8_t* mask,
+                   float* packed, int64_t* layer_off, int32_t* kept_idx,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Step (e2), recovery: the inverse scatter.  Every element of every layer of
+ * `dst` is written: kept positions receive their packed value, all others
+ * exactly +0 (dst need not be cleared beforehand).  Segment offsets inside
+ * `packed` are recomputed from the mask as in hsadmm_compact.
+ *
+ *   packed     device, read only, as produced by hsadmm_compact for this mask
+ *   mask       device, groups_total bytes
+ *   dst        device, out, full-layout arena, 16-byte aligned
+ * Errors: INVALID_ARGUMENT, WORKSPACE, HIP.
+ */
+int hsadmm_expand(const hsadmm_plan_t* plan, const float* packed, const uint8_t* mask,
+                  float* dst, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Static string for an error code (never NULL). */
+const char* hsadmm_strerror(int code);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int hsadmm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HSADMM_H */

@@ -1,0 +1,11 @@
+"""MI355X-native H-SADMM structured-sparsity step: thin Python binding over libhsadmm.so.
+
+Every step of the path runs in the HIP kernels of csrc/hsadmm.hip; this package only marshals
+arguments (see include/hsadmm.h for the contract).  There is no CPU fallback: loading fails loudly when
+the library has not been built.
+"""
+from .binding import (  # noqa: F401
+    HsadmmError, Plan, LIB_PATH, load_library, build_library, exported_symbols,
+    hsadmm_project, hsadmm_compact, hsadmm_expand, hsadmm_strerror, hsadmm_version,
+    MODE_NONE, MODE_FILTER, MODE_CHANNEL, MAX_REPLICAS,
+)

@@ -1,0 +1,205 @@
+"""ctypes binding of the C ABI declared in include/hsadmm.h (argument marshalling only).
+
+Device buffers are torch tensors (or raw integer device addresses); torch is used for device memory
+and streams and for nothing else.  torch is imported before the library is loaded so that the HIP
+runtime the library links against is the one already in the process.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+SRC_PATH = os.path.join(_HERE, "csrc", "hsadmm.hip")
+INCLUDE_DIR = os.path.join(_ROOT, "include")
+LIB_PATH = os.path.join(_HERE, "libhsadmm.so")
+
+MODE_NONE, MODE_FILTER, MODE_CHANNEL = 0, 1, 2
+MAX_REPLICAS = 16
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-fPIC", "-shared",
+]
+
+EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hsadmm_project",
+           "hsadmm_compact", "hsadmm_expand", "hsadmm_strerror", "hsadmm_version")
+
+
+class HsadmmError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__("%s failed: %s (code %d)" % (what, hsadmm_strerror(code), code))
+        self.code = code
+
+
+class _Layer(ctypes.Structure):
+    _fields_ = [("elem_off", ctypes.c_int64), ("c_out", ctypes.c_int32), ("c_in", ctypes.c_int32),
+                ("khw", ctypes.c_int32), ("mode", ctypes.c_int32), ("k", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile csrc/hsadmm.hip for gfx950 with hipcc into libhsadmm.so (in-tree)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = LIB_PATH + ".tmp.%d" % os.getpid()
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE_DIR, "-o", tmp, SRC_PATH]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if verbose or res.returncode != 0:
+        print(res.stdout)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed (%d): %s" % (res.returncode, " ".join(cmd)))
+    os.replace(tmp, LIB_PATH)
+    return LIB_PATH
+
+
+def load_library():
+    """Load libhsadmm.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libhsadmm.so is missing at %s: build it first "
+                           "(python -c 'import __graft_entry__ as g; g.build()')" % LIB_PATH)
+    import torch  # noqa: F401  (brings the HIP runtime into the process first)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp = ctypes.c_void_p
+    lib.hsadmm_plan_create.argtypes = [ctypes.POINTER(_Layer), ctypes.c_int32, ctypes.c_int32,
+                                       ctypes.POINTER(vp)]
+    lib.hsadmm_plan_create.restype = ctypes.c_int
+    lib.hsadmm_plan_destroy.argtypes = [vp]
+    lib.hsadmm_plan_destroy.restype = None
+    lib.hsadmm_plan_sizes.argtypes = [vp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
+                                      ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_size_t)]
+    lib.hsadmm_plan_sizes.restype = ctypes.c_int
+    lib.hsadmm_project.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp,
+                                   ctypes.c_size_t, vp]
+    lib.hsadmm_project.restype = ctypes.c_int
+    lib.hsadmm_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_compact.restype = ctypes.c_int
+    lib.hsadmm_expand.argtypes = [vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_expand.restype = ctypes.c_int
+    lib.hsadmm_strerror.argtypes = [ctypes.c_int]
+    lib.hsadmm_strerror.restype = ctypes.c_char_p
+    lib.hsadmm_version.argtypes = []
+    lib.hsadmm_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def exported_symbols():
+    """Names include/hsadmm.h declares, each resolved in the loaded library."""
+    lib = load_library()
+    return {name: getattr(lib, name) for name in EXPORTS}
+
+
+def hsadmm_strerror(code: int) -> str:
+    return load_library().hsadmm_strerror(int(code)).decode()
+
+
+def hsadmm_version() -> int:
+    return int(load_library().hsadmm_version())
+
+
+def _ptr(x) -> Optional[int]:
+    """Device address of a torch tensor, or an integer address passed through; None -> NULL."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _nbytes(x) -> int:
+    return int(x.numel() * x.element_size())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+class Plan:
+    """Owner of an hsadmm_plan_t*.  `table` has the columns elem_off, c_out, c_in, khw, mode, k."""
+
+    def __init__(self, table, pack_align_elems: int = 1):
+        lib = load_library()
+        L = len(table["c_out"])
+        arr = (_Layer * max(L, 1))()
+        for i in range(L):
+            arr[i].elem_off = int(table["elem_off"][i])
+            arr[i].c_out = int(table["c_out"][i])
+            arr[i].c_in = int(table["c_in"][i])
+            arr[i].khw = int(table["khw"][i])
+            arr[i].mode = int(table["mode"][i])
+            arr[i].k = int(table["k"][i])
+        handle = ctypes.c_void_p()
+        rc = lib.hsadmm_plan_create(arr, L, int(pack_align_elems), ctypes.byref(handle))
+        self.handle = None
+        if rc != 0:
+            raise HsadmmError(rc, "hsadmm_plan_create")
+        self.handle = handle
+        self.n_layers = L
+        self.pack_align_elems = int(pack_align_elems)
+        a, g, c, w = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_size_t()
+        rc = lib.hsadmm_plan_sizes(self.handle, ctypes.byref(a), ctypes.byref(g), ctypes.byref(c),
+                                   ctypes.byref(w))
+        if rc != 0:
+            raise HsadmmError(rc, "hsadmm_plan_sizes")
+        self.arena_elems, self.groups_total = a.value, g.value
+        self.packed_capacity_elems, self.workspace_bytes = c.value, w.value
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load_library().hsadmm_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def hsadmm_project(plan: Plan, W_replicas: Sequence, U, Z, Wbar, mask, sqnorm, workspace,
+                   stream=None, workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_project(plan.handle, ptrs, R, _ptr(U), _ptr(Z), _ptr(Wbar), _ptr(mask), _ptr(sqnorm),
+                            _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_project")
+    return rc
+
+
+def hsadmm_compact(plan: Plan, src, mask, packed, layer_off, kept_idx, workspace, stream=None,
+                   workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    lib = load_library()
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_compact(plan.handle, _ptr(src), _ptr(mask), _ptr(packed), _ptr(layer_off), _ptr(kept_idx),
+                            _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_compact")
+    return rc
+
+
+def hsadmm_expand(plan: Plan, packed, mask, dst, workspace, stream=None,
+                  workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    lib = load_library()
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_expand(plan.handle, _ptr(packed), _ptr(mask), _ptr(dst), _ptr(workspace), wb,
+                           _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_expand")
+    return rc

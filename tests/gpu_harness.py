@@ -1,0 +1,117 @@
+"""Runs the HIP path through the C ABI binding and brings every output back as numpy (tests only)."""
+import numpy as np
+import torch
+
+import paper_2512_14628_amd as pkg
+
+
+class GpuRun:
+    def __init__(self, wl, W, U, pack_align=1, want_wbar=True, want_sqnorm=True, device="cuda:0"):
+        self.wl = wl
+        self.dev = torch.device(device)
+        self.plan = pkg.Plan(wl.table(), pack_align_elems=pack_align)
+        p = self.plan
+        assert p.arena_elems <= wl.n_arena
+        n = wl.n_arena
+        self.dW = [torch.from_numpy(np.ascontiguousarray(W[r])).to(self.dev) for r in range(W.shape[0])]
+        self.dU = torch.from_numpy(np.ascontiguousarray(U)).to(self.dev)
+        nan = float("nan")
+        self.dZ = torch.full((n,), nan, dtype=torch.float32, device=self.dev)
+        self.dWbar = torch.full((n,), nan, dtype=torch.float32, device=self.dev) if want_wbar else None
+        self.dmask = torch.full((p.groups_total,), 7, dtype=torch.uint8, device=self.dev)
+        self.dkey = torch.full((p.groups_total,), nan, dtype=torch.float64, device=self.dev) if want_sqnorm else None
+        self.ws = torch.zeros(p.workspace_bytes, dtype=torch.uint8, device=self.dev)
+        self.dpacked = torch.full((max(p.packed_capacity_elems, 1),), nan, dtype=torch.float32, device=self.dev)
+        self.doff = torch.full((p.n_layers + 1,), -1, dtype=torch.int64, device=self.dev)
+        self.dkept = torch.full((p.groups_total,), -1, dtype=torch.int32, device=self.dev)
+        self.ddst = torch.full((n,), nan, dtype=torch.float32, device=self.dev)
+
+    def project(self):
+        pkg.hsadmm_project(self.plan, self.dW, self.dU, self.dZ, self.dWbar, self.dmask, self.dkey, self.ws)
+
+    def compact(self, src=None, mask=None):
+        pkg.hsadmm_compact(self.plan, self.dZ if src is None else src, self.dmask if mask is None else mask,
+                           self.dpacked, self.doff, self.dkept, self.ws)
+
+    def expand(self, mask=None):
+        pkg.hsadmm_expand(self.plan, self.dpacked, self.dmask if mask is None else mask, self.ddst, self.ws)
+
+    def step(self):
+        self.project()
+        self.compact()
+        self.expand()
+        torch.cuda.synchronize()
+
+    def outputs(self):
+        torch.cuda.synchronize()
+        out = {"U": self.dU.cpu().numpy(), "Z": self.dZ.cpu().numpy(), "mask": self.dmask.cpu().numpy(),
+               "packed": self.dpacked.cpu().numpy(), "layer_off": self.doff.cpu().numpy(),
+               "kept_idx": self.dkept.cpu().numpy(), "dst": self.ddst.cpu().numpy()}
+        if self.dWbar is not None:
+            out["Wbar"] = self.dWbar.cpu().numpy()
+        if self.dkey is not None:
+            out["key"] = self.dkey.cpu().numpy()
+        return out
+
+    def close(self):
+        self.plan.close()
+
+
+def bits(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def layer_view(wl, arena):
+    """Concatenation of the layers' elements (arena padding dropped)."""
+    return np.concatenate([arena[l.elem_off:l.elem_off + l.n] for l in wl.layers])
+
+
+def min_relative_gap(wl, key):
+    """Smallest nonzero relative gap between the k-th and (k+1)-th largest key of any constrained layer."""
+    worst = np.inf
+    for l in wl.layers:
+        if l.mode == 0 or l.k >= l.groups:
+            continue
+        ks = np.sort(key[l.group_base:l.group_base + l.groups])[::-1]
+        a, b = ks[l.k - 1], ks[l.k]
+        if a != b and a > 0:
+            worst = min(worst, (a - b) / a)
+    return worst
+
+
+def check_against_oracle(wl, got, ref, refc, check_float_tol=True):
+    """Bit-exact integer outputs; floats within 1e-6 of the layer's largest magnitude (and counted bitwise)."""
+    report = {}
+    gap = min_relative_gap(wl, ref["key"])
+    assert gap > 1e-10, "near-tie in the synthetic inputs (relative gap %g): unsuitable for a bit-exact mask test" % gap
+    assert np.array_equal(got["mask"], ref["mask"]), "mask differs from the oracle"
+    if "key" in got:
+        np.testing.assert_allclose(got["key"], ref["key"], rtol=1e-12, atol=0)
+    names = ["Z", "U"] + (["Wbar"] if "Wbar" in got and ref.get("Wbar") is not None else [])
+    for name in names:
+        for l in wl.layers:
+            sl = slice(l.elem_off, l.elem_off + l.n)
+            g, r = got[name][sl], ref[name][sl]
+            scale = max(float(np.max(np.abs(r))), float(np.finfo(np.float32).tiny))
+            err = float(np.max(np.abs(g.astype(np.float64) - r.astype(np.float64))))
+            assert err <= 1e-6 * scale, "%s layer %s: max abs err %g > 1e-6 * %g" % (name, l.name, err, scale)
+        report[name + "_bit_mismatches"] = int(np.count_nonzero(bits(layer_view(wl, got[name])) !=
+                                                                 bits(layer_view(wl, ref[name]))))
+    assert np.array_equal(got["layer_off"], refc["layer_off"]), "layer_off differs"
+    nk = refc["kept_idx"].size
+    assert np.array_equal(got["kept_idx"][:nk], refc["kept_idx"]), "kept_idx differs"
+    L = len(wl.layers)
+    for li in range(L):
+        a = int(refc["layer_off"][li])
+        size = wl.layers[li].n if wl.layers[li].mode == 0 else None
+        b = int(refc["layer_off"][li + 1])
+        # compare the meaningful part of the segment (alignment padding is unspecified)
+        seg_ref = refc["packed"][a:b]
+        seg_got = got["packed"][a:b]
+        used = refc.get("seg_sizes", None)
+        n_used = int(used[li]) if used is not None else (b - a)
+        assert np.array_equal(bits(seg_got[:n_used]), bits(seg_ref[:n_used])), "packed segment %d differs" % li
+    for l in wl.layers:
+        sl = slice(l.elem_off, l.elem_off + l.n)
+        assert np.array_equal(bits(got["dst"][sl]), bits(got["Z"][sl])), "expand(compact(Z)) != Z in layer %s" % l.name
+    return report

@@ -1,0 +1,85 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol, and rejects bad
+arguments before touching a device.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2512_14628_amd as pkg
+from paper_2512_14628_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pkg.LIB_PATH):
+        pkg.build_library()
+    return pkg.load_library()
+
+
+def test_header_symbols_are_all_exported(lib):
+    header = open(os.path.join(ROOT, "include", "hsadmm.h")).read()
+    declared = set(re.findall(r"\b(hsadmm_[a-z_]+)\s*\(", header))
+    declared -= {"hsadmm_plan_t", "hsadmm_layer_t"}
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert pkg.hsadmm_version() >= 100
+    assert pkg.hsadmm_strerror(0) == "ok"
+    assert "argument" in pkg.hsadmm_strerror(-1)
+    assert "workspace" in pkg.hsadmm_strerror(-2)
+    assert pkg.hsadmm_strerror(-99) == "unknown error code"
+
+
+def _table(rows):
+    cols = list(zip(*rows))
+    return {"elem_off": np.array(cols[0], np.int64), "c_out": np.array(cols[1], np.int32),
+            "c_in": np.array(cols[2], np.int32), "khw": np.array(cols[3], np.int32),
+            "mode": np.array(cols[4], np.int32), "k": np.array(cols[5], np.int32)}
+
+
+@pytest.mark.parametrize("rows", [
+    [(0, 0, 3, 1, 1, 1)],                       # c_out < 1
+    [(0, 4, 3, 0, 1, 1)],                       # khw < 1
+    [(0, 4, 3, 1, 5, 1)],                       # unknown mode
+    [(0, 4, 3, 1, 1, 0)],                       # k < 1
+    [(0, 4, 3, 1, 1, 5)],                       # k > G (filter)
+    [(0, 4, 3, 1, 2, 4)],                       # k > G (channel)
+    [(2, 4, 3, 1, 1, 1)],                       # elem_off not a multiple of 4
+    [(0, 4, 4, 1, 1, 1), (8, 4, 4, 1, 1, 1)],   # layers overlap
+    [(-4, 4, 4, 1, 1, 1)],                      # negative offset
+])
+def test_plan_create_rejects_bad_tables(lib, rows):
+    with pytest.raises(pkg.HsadmmError) as e:
+        pkg.Plan(_table(rows))
+    assert e.value.code == -1
+
+
+def test_plan_create_rejects_bad_scalars(lib):
+    arr = (binding._Layer * 1)()
+    out = ctypes.c_void_p()
+    assert lib.hsadmm_plan_create(None, 1, 1, ctypes.byref(out)) == -1
+    assert lib.hsadmm_plan_create(arr, 0, 1, ctypes.byref(out)) == -1
+    assert lib.hsadmm_plan_create(arr, 1, 0, ctypes.byref(out)) == -1
+    assert lib.hsadmm_plan_create(arr, 1, 1, None) == -1
+    assert lib.hsadmm_plan_create(arr, 5000, 1, ctypes.byref(out)) == -1
+    lib.hsadmm_plan_destroy(None)               # must be a no-op
+
+
+def test_hot_calls_reject_null_plan(lib):
+    assert lib.hsadmm_plan_sizes(None, None, None, None, None) == -1
+    assert lib.hsadmm_project(None, None, 1, None, None, None, None, None, None, 0, None) == -1
+    assert lib.hsadmm_compact(None, None, None, None, None, None, None, 0, None) == -1
+    assert lib.hsadmm_expand(None, None, None, None, None, 0, None) == -1
+
+
+def test_no_cpu_fallback_in_the_product_package():
+    """The product path must not import the oracle (or numpy-level arithmetic) anywhere."""
+    for fn in ("__init__.py", "binding.py"):
+        src = open(os.path.join(ROOT, "paper_2512_14628_amd", fn)).read()
+        assert "oracle" not in src.replace("no CPU fallback", "")
+    hip = open(os.path.join(ROOT, "paper_2512_14628_amd", "csrc", "hsadmm.hip")).read()
+    assert "oracle" not in hip

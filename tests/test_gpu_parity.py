@@ -1,0 +1,188 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bar: masks, offsets, kept indices and packed layout bit-exact; fp32 outputs within 1e-6 of each layer's
+largest magnitude (they are expected to be bit-identical; mismatching bit patterns are counted and must be 0).
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wk
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _run(wl, pack_align=1, want_wbar=True, want_sqnorm=True, threads=8):
+    from tests.gpu_harness import GpuRun, check_against_oracle
+    W, U = wk.generate(wl, threads=threads)
+    oracle.set_threads(threads)
+    t = wl.table()
+    ref = oracle.project(t, W, U, want_wbar=True)
+    refc = oracle.compact(t, ref["Z"], ref["mask"], pack_align=pack_align)
+    sizes = []
+    for l in wl.layers:
+        cnt = int(ref["mask"][l.group_base:l.group_base + l.groups].sum())
+        sizes.append(l.n if l.mode == wk.MODE_NONE else cnt * l.group_size)
+    refc["seg_sizes"] = np.array(sizes)
+    run = GpuRun(wl, W, U, pack_align=pack_align, want_wbar=want_wbar, want_sqnorm=want_sqnorm)
+    run.step()
+    got = run.outputs()
+    rep = check_against_oracle(wl, got, ref, refc)
+    for name, cnt in rep.items():
+        assert cnt == 0, "%s = %d" % (name, cnt)
+    # untouched arena padding
+    pad = np.ones(wl.n_arena, dtype=bool)
+    for l in wl.layers:
+        pad[l.elem_off:l.elem_off + l.n] = False
+    assert np.all(np.isnan(got["Z"][pad])) and np.all(np.isnan(got["dst"][pad]))
+    # determinism: a second run from fresh inputs gives the same bits
+    run2 = GpuRun(wl, W, U, pack_align=pack_align, want_wbar=want_wbar, want_sqnorm=want_sqnorm)
+    run2.step()
+    got2 = run2.outputs()
+    for name in got:
+        a, b = got[name], got2[name]
+        if a.dtype.kind == "f":
+            if a.dtype == np.float64:
+                assert np.array_equal(a.view(np.uint64), b.view(np.uint64)), name
+            else:
+                assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), name
+        else:
+            assert np.array_equal(a, b), name
+    run.close()
+    run2.close()
+    return got, ref, refc
+
+
+def test_tiny_cnn():
+    _run(wk.make_workload("tiny"))
+
+
+def test_resnet18_filter():
+    _run(wk.make_workload("resnet18"))
+
+
+def test_resnet50_filter_R4():
+    _run(wk.make_workload("resnet50"))
+
+
+def test_resnet152_channel_R4_roundtrip():
+    _run(wk.make_workload("resnet152"))
+
+
+def _odd_shapes(rng, n_layers):
+    shapes = []
+    for _ in range(n_layers):
+        co = int(rng.integers(1, 300))
+        ci = int(rng.integers(1, 300))
+        khw = int(rng.choice([1, 1, 1, 4, 9, 9, 25, 49]))
+        mode = int(rng.choice([0, 1, 1, 2, 2]))
+        G = ci if mode == wk.MODE_CHANNEL else co
+        shapes.append((co, ci, khw, mode, int(rng.integers(1, G + 1))))
+    return shapes
+
+
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 8, 16])
+def test_ragged_shapes_every_replica_count(R):
+    rng = np.random.default_rng(1000 + R)
+    wl = wk.custom_workload(_odd_shapes(rng, 12), R=R, seed=R, sigma_replica=0.03)
+    _run(wl, pack_align=1, want_wbar=(R % 2 == 0), want_sqnorm=(R % 3 != 0))
+
+
+@pytest.mark.parametrize("pack_align", [1, 4, 7, 64])
+def test_pack_alignment(pack_align):
+    rng = np.random.default_rng(77)
+    wl = wk.custom_workload(_odd_shapes(rng, 10), R=2, seed=5, sigma_replica=0.03)
+    _run(wl, pack_align=pack_align)
+
+
+def test_degenerate_layers():
+    """G = 1, k = 1, k = G, single-element layers, one very long row, many tiny rows, a 3-channel stem in CHANNEL mode."""
+    shapes = [(1, 1, 1, wk.MODE_FILTER, 1), (1, 1, 1, wk.MODE_CHANNEL, 1), (1, 50000, 1, wk.MODE_FILTER, 1),
+              (50000, 1, 1, wk.MODE_FILTER, 17), (64, 3, 49, wk.MODE_CHANNEL, 1), (7, 9000, 1, wk.MODE_CHANNEL, 8999),
+              (9000, 2, 1, wk.MODE_CHANNEL, 1), (5, 5, 9, wk.MODE_FILTER, 5), (5, 5, 9, wk.MODE_CHANNEL, 5),
+              (3, 3, 1, wk.MODE_NONE, 3), (2, 4100, 9, wk.MODE_FILTER, 1)]
+    wl = wk.custom_workload(shapes, R=3, seed=11, sigma_replica=0.03)
+    _run(wl)
+
+
+def test_exact_ties_lower_index_wins():
+    from tests.gpu_harness import GpuRun
+    # identical filters (and identical channels) straddling the cut, in layers large enough for several tiles
+    wl = wk.custom_workload([(300, 64, 9, wk.MODE_FILTER, 100), (128, 200, 1, wk.MODE_CHANNEL, 50),
+                             (40, 7, 1, wk.MODE_FILTER, 20)], R=2, seed=4, sigma_replica=0.0)
+    W, U = wk.generate(wl)
+    l0, l1, l2 = wl.layers
+    for arr in (W[0], W[1], U):
+        a = arr[l0.elem_off:l0.elem_off + l0.n].reshape(300, -1)
+        a[:] = a[np.arange(300) % 37]               # 37 distinct filters repeated
+        b = arr[l1.elem_off:l1.elem_off + l1.n].reshape(128, 200)
+        b[:] = b[:, np.arange(200) % 11]            # 11 distinct channels repeated
+        c = arr[l2.elem_off:l2.elem_off + l2.n]
+        c[:] = 0                                     # all keys zero: the first k indices win
+    t = wl.table()
+    ref = oracle.project(t, W, U)
+    run = GpuRun(wl, W, U)
+    run.step()
+    got = run.outputs()
+    assert np.array_equal(got["mask"], ref["mask"])
+    assert np.array_equal(got["key"].view(np.uint64)[:300].reshape(-1)[:37],
+                          got["key"].view(np.uint64)[37:74])       # identical groups -> identical key bits
+    assert got["mask"][l2.group_base:l2.group_base + 40].tolist() == [1] * 20 + [0] * 20
+    assert np.array_equal(got["Z"].view(np.uint32), ref["Z"].view(np.uint32))
+    assert np.array_equal(got["U"].view(np.uint32), ref["U"].view(np.uint32))
+    run.close()
+
+
+def test_compact_and_expand_with_a_foreign_mask_and_source():
+    """Compaction under a mask that is not the projection's own (union of masks: counts differ from k)."""
+    from tests.gpu_harness import GpuRun, bits
+    rng = np.random.default_rng(9)
+    wl = wk.custom_workload(_odd_shapes(rng, 9), R=1, seed=2)
+    W, U = wk.generate(wl)
+    run = GpuRun(wl, W, U)
+    src = rng.standard_normal(wl.n_arena).astype(np.float32)
+    mask = (rng.random(wl.groups_total) < 0.5).astype(np.uint8) * 3      # any nonzero byte means kept
+    mask[wl.layers[0].group_base:wl.layers[0].group_base + wl.layers[0].groups] = 0 if wl.layers[0].mode else 1
+    t = wl.table()
+    refc = oracle.compact(t, src, (mask != 0).astype(np.uint8))
+    refe = oracle.expand(t, refc["packed"], (mask != 0).astype(np.uint8), wl.n_arena)
+    dsrc = torch.from_numpy(src).to(run.dev)
+    dmask = torch.from_numpy(mask).to(run.dev)
+    run.compact(src=dsrc, mask=dmask)
+    run.expand(mask=dmask)
+    got = run.outputs()
+    assert np.array_equal(got["layer_off"], refc["layer_off"])
+    nk = refc["kept_idx"].size
+    assert np.array_equal(got["kept_idx"][:nk], refc["kept_idx"])
+    n = int(refc["layer_off"][-1])
+    assert np.array_equal(bits(got["packed"][:n]), bits(refc["packed"]))
+    for l in wl.layers:
+        sl = slice(l.elem_off, l.elem_off + l.n)
+        assert np.array_equal(bits(got["dst"][sl]), bits(refe[sl]))
+    run.close()
+
+
+def test_repeated_steps_follow_the_oracle():
+    """Three outer iterations with U carried over (in place on the GPU) and fresh replicas each time."""
+    from tests.gpu_harness import GpuRun
+    wl = wk.custom_workload([(96, 64, 9, wk.MODE_FILTER, 40), (128, 96, 1, wk.MODE_CHANNEL, 30),
+                             (10, 128, 1, wk.MODE_NONE, 10)], R=4, seed=1, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    run = GpuRun(wl, W, U)
+    t = wl.table()
+    Uref = U.copy()
+    for it in range(3):
+        wl.seed = 100 + it
+        Wn, _ = wk.generate(wl)
+        for r in range(wl.R):
+            run.dW[r].copy_(torch.from_numpy(Wn[r]))
+        ref = oracle.project(t, Wn, Uref)
+        run.step()
+        got = run.outputs()
+        assert np.array_equal(got["mask"], ref["mask"])
+        assert np.array_equal(got["Z"].view(np.uint32)[:wl.n_arena], ref["Z"].view(np.uint32))
+        assert np.array_equal(got["U"].view(np.uint32), ref["U"].view(np.uint32))
+        Uref = ref["U"]
+    run.close()
