@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the H-SADMM structured-sparsity step on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input:
+hsadmm_project (average R replicas, candidate, group norms, top-k projection, dual update),
+hsadmm_compact (pack the kept groups), hsadmm_expand (zero fill + scatter back), issued back to back on
+one stream with every buffer already resident in HBM.
+
+Prints ONE JSON line.  `value` is algorithmic bytes per second for the whole step (each unique input
+read once, each output written once: 4n(R+4) + 12 n_kept bytes); `roofline` prices the dominant kernel
+against the 8 TB/s HBM peak with its duration taken from per-launch HIP events; `cpu_baseline` is the
+plain CPU oracle timed on the host cores on the same workload.
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+METRIC = "H-SADMM project+compact GB/s (fraction of HBM peak) + params/s, ResNet-50 fp32"
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
+    ap.add_argument("--no-verify", action="store_true", help="skip the one-shot oracle check of the outputs")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path has no collectives); "
+              "run with --gpus 1. See DESIGN.md for how the step would shard.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as wk
+    import paper_2512_14628_amd as pkg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    pkg.load_library()            # fails loudly when the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = wk.make_workload(args.workload, seed=args.seed)
+    t_gen = time.perf_counter()
+    W, U = wk.generate(wl, threads=min(16, os.cpu_count() or 1))
+    t_gen = time.perf_counter() - t_gen
+    table = wl.table()
+    plan = pkg.Plan(table)
+    n = wl.n_arena
+    dW = [torch.from_numpy(W[r]).to(dev) for r in range(wl.R)]
+    dU0 = torch.from_numpy(U).to(dev)
+    dU = dU0.clone()
+    dZ = torch.zeros(n, dtype=torch.float32, device=dev)
+    dmask = torch.zeros(plan.groups_total, dtype=torch.uint8, device=dev)
+    ws = torch.zeros(plan.workspace_bytes, dtype=torch.uint8, device=dev)
+    dpacked = torch.zeros(plan.packed_capacity_elems, dtype=torch.float32, device=dev)
+    doff = torch.zeros(plan.n_layers + 1, dtype=torch.int64, device=dev)
+    dkept = torch.zeros(plan.groups_total, dtype=torch.int32, device=dev)
+    ddst = torch.zeros(n, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        pkg.hsadmm_project(plan, dW, dU, dZ, None, dmask, None, ws, stream=stream)
+        pkg.hsadmm_compact(plan, dZ, dmask, dpacked, doff, dkept, ws, stream=stream)
+        pkg.hsadmm_expand(plan, dpacked, dmask, ddst, ws, stream=stream)
+
+    # ---- one-shot correctness check against the oracle (outside every timed region)
+    verify = None
+    if not args.no_verify:
+        import oracle
+        oracle.set_threads(min(16, os.cpu_count() or 1))
+        ref = oracle.project(table, W, U)
+        refc = oracle.compact(table, ref["Z"], ref["mask"])
+        step()
+        torch.cuda.synchronize()
+        ok_mask = bool(np.array_equal(dmask.cpu().numpy(), ref["mask"]))
+        ok_z = bool(np.array_equal(dZ.cpu().numpy().view(np.uint32), ref["Z"].view(np.uint32)))
+        ok_u = bool(np.array_equal(dU.cpu().numpy().view(np.uint32), ref["U"].view(np.uint32)))
+        npk = int(refc["layer_off"][-1])
+        ok_p = bool(np.array_equal(dpacked.cpu().numpy()[:npk].view(np.uint32), refc["packed"].view(np.uint32)))
+        ok_o = bool(np.array_equal(doff.cpu().numpy(), refc["layer_off"]))
+        ok_d = bool(np.array_equal(ddst.cpu().numpy().view(np.uint32), ref["Z"].view(np.uint32)))
+        verify = {"mask": ok_mask, "Z": ok_z, "U": ok_u, "packed": ok_p, "layer_off": ok_o, "expand": ok_d}
+        if not all(verify.values()):
+            print("bench.py: outputs differ from the oracle: %s" % verify, file=sys.stderr)
+            sys.exit(4)
+        dU.copy_(dU0)
+
+    bytes_ = wl.algorithmic_bytes()
+
+    # ---- main timed region: W warm-up steps, then exactly K steps between two device synchronisations
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    gbps = bytes_["step"] / (elapsed / args.steps) / 1e9
+    params_per_s = wl.n_total / (elapsed / args.steps)
+
+    # ---- per-kernel durations: the same K steps again with every launch carrying its own HIP events
+    pkg.hsadmm_kernel_timing_enable(plan, True)
+    kernel_ms = {}
+    done = 0
+    while done < args.steps:
+        chunk = min(args.steps - done, 1000)     # 7 launches per step, 8192 recorded launches per read
+        for _ in range(chunk):
+            step()
+        torch.cuda.synchronize()
+        for name, (ms, cnt) in pkg.hsadmm_kernel_timing_read(plan).items():
+            a = kernel_ms.setdefault(name, [0.0, 0])
+            a[0] += ms
+            a[1] += cnt
+        done += chunk
+    pkg.hsadmm_kernel_timing_enable(plan, False)
+    per_launch_us = {k: (1e3 * v[0] / v[1] if v[1] else None) for k, v in kernel_ms.items()}
+    launches_per_step = {k: v[1] / args.steps for k, v in kernel_ms.items()}
+    kernel_us_per_step = {k: 1e3 * v[0] / args.steps for k, v in kernel_ms.items()}
+
+    # algorithmic bytes each kernel is charged with (per launch)
+    nk = wl.n_kept
+    kernel_bytes = {
+        "project_pass1": bytes_["project"],          # all of project's traffic: R replicas + U in, Z + U out
+        "compact_gather": bytes_["compact"],
+        "expand_scatter": bytes_["expand"],
+    }
+    dom = max(kernel_us_per_step, key=lambda k: kernel_us_per_step[k])
+    dom_us = per_launch_us[dom]
+    achieved = kernel_bytes.get(dom, 0) / (dom_us * 1e-6) / 1e9 if dom_us else 0.0
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": None,
+                "algorithmic_bytes_per_launch": kernel_bytes.get(dom, 0),
+                "avg_launch_us": round(dom_us, 2) if dom_us else None}
+    traffic_file = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
+    if os.path.exists(traffic_file):
+        try:
+            with open(traffic_file) as f:
+                roofline["traffic"] = json.load(f).get(dom)
+        except Exception:
+            pass
+
+    # ---- context: a plain device copy of the same size class (practical streaming ceiling)
+    a_src, a_dst = dW[0], dZ
+    for _ in range(5):
+        a_dst.copy_(a_src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(50):
+        a_dst.copy_(a_src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * 4 * n * 50 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    # ---- CPU baseline: the oracle as it stands, on the host cores, same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = min(16, os.cpu_count() or 1)
+        oracle.set_threads(cores)
+        reps, spent = 0, 0.0
+        while reps < 1 or (spent < args.cpu_seconds and reps < 50):
+            r = oracle.project(table, W, U)
+            s = oracle.last_call_seconds
+            c = oracle.compact(table, r["Z"], r["mask"])
+            s += oracle.last_call_seconds
+            oracle.expand(table, c["packed"], r["mask"], wl.n_arena)
+            s += oracle.last_call_seconds
+            spent += s
+            reps += 1
+        cpu = {"value": round(bytes_["step"] / (spent / reps) / 1e9, 3), "unit": "GB/s", "cores": cores,
+               "kind": "oracle", "sample": "%d full steps of workload %s (all %d layers, %d parameters), C calls only"
+               % (reps, wl.name, len(wl.layers), wl.n_total),
+               "ms_per_step": round(1e3 * spent / reps, 2),
+               "params_per_s": round(wl.n_total / (spent / reps), 1)}
+
+    out = {
+        "metric": METRIC,
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s" % (wl.name, wl.description), "layers": len(wl.layers),
+                   "params": wl.n_total, "replicas": wl.R, "kept_params": nk, "seed": wl.seed,
+                   "algorithmic_bytes_per_step": bytes_["step"]},
+        "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
+        "params_per_s": round(params_per_s, 1),
+        "kernel_us_per_launch": {k: (round(v, 2) if v else None) for k, v in per_launch_us.items()},
+        "kernel_launches_per_step": launches_per_step,
+        "kernel_us_per_step_sum": round(sum(kernel_us_per_step.values()), 2),
+        "copy_GBps": round(copy_gbps, 1),
+        "verified_against_oracle": verify,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    plan.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -71,7 +71,7 @@ typedef struct {
     int32_t k;          /* groups kept (the paper's alpha), 1 <= k <= G; ignored for MODE_NONE */
 } hsadmm_layer_t;
 
-typedef struct hsadmm_plan hsadmm_plan_t;   /* opaque, immutable after creation */
+typedef struct hsadmm_plan hsadmm_plan_t;   /* opaque; its tables never change after creation */
 
 /*
  * Build a plan for a table of L layers (1 <= L <= HSADMM_MAX_LAYERS).
@@ -172,6 +172,25 @@ const char* hsadmm_strerror(int code);
 
 /* Library version: major*10000 + minor*100 + patch. */
 int hsadmm_version(void);
+
+/*
+ * Diagnostics: per-kernel device time of the hot calls made on this plan.
+ *
+ * hsadmm_kernel_timing_enable(plan, 1) makes every kernel launch of the three
+ * hot calls carry a start/stop event pair that takes the kernel's own begin
+ * and end timestamps; nothing else is put on the stream.  At most 8192
+ * launches are recorded between two reads; later launches run untimed.
+ * hsadmm_kernel_timing_read waits for the recorded kernels, returns for every
+ * kernel id 0..HSADMM_KERNEL_COUNT-1 the summed duration in milliseconds and
+ * the number of launches, and clears the record.  While timing is enabled
+ * the plan must be used from one host thread only.  Off by default.
+ * Errors: INVALID_ARGUMENT, HIP.
+ */
+#define HSADMM_KERNEL_COUNT 6
+int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
+int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
+/* Name of a kernel id ("" when out of range). */
+const char* hsadmm_kernel_name(int kernel_id);
 
 #ifdef __cplusplus
 }

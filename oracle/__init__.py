@@ -11,6 +11,7 @@ from __future__ import annotations
 import ctypes
 import os
 import subprocess
+import time
 
 import numpy as np
 
@@ -18,6 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hsadmm_oracle.c")
 _LIB = os.path.join(_HERE, "libhsadmm_oracle.so")
 _lib = None
+last_call_seconds = 0.0     # wall time of the most recent C call (excludes numpy marshalling)
 
 CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra"]
 
@@ -114,12 +116,15 @@ def project(table, W, U, want_wbar: bool = False):
     key = np.zeros(gt, dtype=np.float64)
     f32p = ctypes.POINTER(ctypes.c_float)
     ptrs = (f32p * R)(*[_p(W[r], ctypes.c_float) for r in range(R)])
+    global last_call_seconds
+    _t0 = time.perf_counter()
     rc = lib.oracle_project(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
                             _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
                             _p(t["mode"], ctypes.c_int32), _p(t["k"], ctypes.c_int32),
                             ptrs, R, _p(U_new, ctypes.c_float), _p(Z, ctypes.c_float),
                             _p(Wbar, ctypes.c_float) if want_wbar else None,
                             _p(mask, ctypes.c_uint8), _p(key, ctypes.c_double))
+    last_call_seconds = time.perf_counter() - _t0
     if rc != 0:
         raise ValueError("oracle_project failed with code %d" % rc)
     return {"U": U_new, "Z": Z, "mask": mask, "key": key, "Wbar": Wbar}
@@ -144,12 +149,15 @@ def compact(table, src, mask, pack_align: int = 1):
     layer_off = np.zeros(L + 1, dtype=np.int64)
     kept_idx = np.zeros(gt, dtype=np.int32)
     nk = ctypes.c_int64(0)
+    global last_call_seconds
+    _t0 = time.perf_counter()
     rc = lib.oracle_compact(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
                             _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
                             _p(t["mode"], ctypes.c_int32), int(pack_align),
                             _p(src, ctypes.c_float), _p(mask, ctypes.c_uint8),
                             _p(packed, ctypes.c_float), _p(layer_off, ctypes.c_int64),
                             _p(kept_idx, ctypes.c_int32), ctypes.byref(nk))
+    last_call_seconds = time.perf_counter() - _t0
     if rc != 0:
         raise ValueError("oracle_compact failed with code %d" % rc)
     return {"packed": packed[:int(layer_off[L])], "layer_off": layer_off,
@@ -166,11 +174,14 @@ def expand(table, packed, mask, n_arena: int, pack_align: int = 1):
         packed = np.zeros(1, dtype=np.float32)
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     dst = _poisoned_arena(t, n_arena)
+    global last_call_seconds
+    _t0 = time.perf_counter()
     rc = lib.oracle_expand(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
                            _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
                            _p(t["mode"], ctypes.c_int32), int(pack_align),
                            _p(packed, ctypes.c_float), _p(mask, ctypes.c_uint8),
                            _p(dst, ctypes.c_float))
+    last_call_seconds = time.perf_counter() - _t0
     if rc != 0:
         raise ValueError("oracle_expand failed with code %d" % rc)
     return dst

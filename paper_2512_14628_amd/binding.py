@@ -27,7 +27,9 @@ HIPCC_FLAGS = [
 ]
 
 EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hsadmm_project",
-           "hsadmm_compact", "hsadmm_expand", "hsadmm_strerror", "hsadmm_version")
+           "hsadmm_compact", "hsadmm_expand", "hsadmm_strerror", "hsadmm_version",
+           "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name")
+KERNEL_COUNT = 6
 
 
 class HsadmmError(RuntimeError):
@@ -88,6 +90,12 @@ def load_library():
     lib.hsadmm_strerror.restype = ctypes.c_char_p
     lib.hsadmm_version.argtypes = []
     lib.hsadmm_version.restype = ctypes.c_int
+    lib.hsadmm_kernel_timing_enable.argtypes = [vp, ctypes.c_int]
+    lib.hsadmm_kernel_timing_enable.restype = ctypes.c_int
+    lib.hsadmm_kernel_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.hsadmm_kernel_timing_read.restype = ctypes.c_int
+    lib.hsadmm_kernel_name.argtypes = [ctypes.c_int]
+    lib.hsadmm_kernel_name.restype = ctypes.c_char_p
     _lib = lib
     return lib
 
@@ -168,6 +176,23 @@ class Plan:
             self.close()
         except Exception:
             pass
+
+
+def hsadmm_kernel_timing_enable(plan: Plan, enable: bool) -> None:
+    rc = load_library().hsadmm_kernel_timing_enable(plan.handle, 1 if enable else 0)
+    if rc != 0:
+        raise HsadmmError(rc, "hsadmm_kernel_timing_enable")
+
+
+def hsadmm_kernel_timing_read(plan: Plan):
+    """{kernel name: (total milliseconds, launches)} since the last read."""
+    lib = load_library()
+    ms = (ctypes.c_double * KERNEL_COUNT)()
+    cnt = (ctypes.c_int64 * KERNEL_COUNT)()
+    rc = lib.hsadmm_kernel_timing_read(plan.handle, ms, cnt)
+    if rc != 0:
+        raise HsadmmError(rc, "hsadmm_kernel_timing_read")
+    return {lib.hsadmm_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(KERNEL_COUNT)}
 
 
 def hsadmm_project(plan: Plan, W_replicas: Sequence, U, Z, Wbar, mask, sqnorm, workspace,

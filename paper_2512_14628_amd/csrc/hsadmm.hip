@@ -20,6 +20,7 @@
 // uses fma(v, v, acc), which equals mul+add because the square of an fp32 value is exact in fp64.
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdint>
 #include <cstdlib>
@@ -635,6 +636,11 @@ struct hsadmm_plan {
     DevLayer* d_layers = nullptr;
     WorkItem* d_items_proj = nullptr;
     WorkItem* d_items_rows = nullptr;
+    // Optional per-kernel timing (diagnostics; off by default).  Not thread-safe.
+    bool timing = false;
+    std::vector<hipEvent_t> ev;      // pairs: start, stop
+    std::vector<int> ev_kernel;      // kernel id of each recorded pair
+    size_t ev_used = 0;              // pairs recorded since the last read
 };
 
 namespace {
@@ -662,12 +668,31 @@ void add_row_items(std::vector<WorkItem>& out, int layer, const DevLayer& d)
 
 bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kKernelCount };
+constexpr size_t kTimingPairs = 8192;
+
+// Launches `kernel` on stream s.  With timing enabled the launch carries a start and a stop event
+// that take the kernel's own begin / end timestamps (no extra work is put on the stream).
+template <typename... KArgs, typename... Args>
+hipError_t launch(const hsadmm_plan* cp, int kid, void (*kernel)(KArgs...), unsigned grid, unsigned block,
+                  hipStream_t s, Args... args)
+{
+    hsadmm_plan* p = const_cast<hsadmm_plan*>(cp);
+    if (p->timing && p->ev_used < kTimingPairs) {
+        const size_t i = p->ev_used++;
+        p->ev_kernel[i] = kid;
+        hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, s, p->ev[2 * i], p->ev[2 * i + 1], 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, s, args...);
+    }
+    return hipGetLastError();
+}
+
 template <int R>
 hipError_t launch_pass1(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, hipStream_t s)
 {
-    hipLaunchKernelGGL(project_pass1<R>, dim3((unsigned)p->items_proj.size()), dim3(kBlock), 0, s,
-                       p->d_layers, p->d_items_proj, a, Rrt);
-    return hipGetLastError();
+    return launch(p, kPass1, project_pass1<R>, (unsigned)p->items_proj.size(), kBlock, s,
+                  (const DevLayer*)p->d_layers, (const WorkItem*)p->d_items_proj, a, Rrt);
 }
 
 int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, int64_t* layer_off, int32_t* kept_idx,
@@ -678,9 +703,9 @@ int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, int64_t* layer
     o.cnt = reinterpret_cast<int32_t*>(ws + p->ws.cnt);
     o.layer_off = layer_off;
     o.kept_idx = kept_idx;
-    hipLaunchKernelGGL(scan_mask, dim3((unsigned)p->layers.size()), dim3(kScanBlock), 0, s,
-                       p->d_layers, (int)p->layers.size(), (int)p->pack_align, mask, o);
-    return hipGetLastError() == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+    const hipError_t e = launch(p, kScan, scan_mask, (unsigned)p->layers.size(), kScanBlock, s,
+                                (const DevLayer*)p->d_layers, (int)p->layers.size(), (int)p->pack_align, mask, o);
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
 }  // namespace
@@ -782,6 +807,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
 void hsadmm_plan_destroy(hsadmm_plan_t* p)
 {
     if (!p) return;
+    for (hipEvent_t e : p->ev) (void)hipEventDestroy(e);
     if (p->d_layers) (void)hipFree(p->d_layers);
     if (p->d_items_proj) (void)hipFree(p->d_items_proj);
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
@@ -829,12 +855,12 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
         default: e = launch_pass1<0>(p, a, R, s); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
-    hipLaunchKernelGGL(select_topk, dim3((unsigned)p->layers.size()), dim3(kScanBlock), 0, s,
-                       p->d_layers, a.key, a.colpart, mask);
-    if (hipGetLastError() != hipSuccess) return HSADMM_ERR_HIP;
-    hipLaunchKernelGGL(project_fixup, dim3((unsigned)p->items_proj.size()), dim3(kBlock), 0, s,
-                       p->d_layers, p->d_items_proj, mask, U, Z);
-    if (hipGetLastError() != hipSuccess) return HSADMM_ERR_HIP;
+    e = launch(p, kTopk, select_topk, (unsigned)p->layers.size(), kScanBlock, s,
+               (const DevLayer*)p->d_layers, a.key, (const double*)a.colpart, mask);
+    if (e != hipSuccess) return HSADMM_ERR_HIP;
+    e = launch(p, kFixup, project_fixup, (unsigned)p->items_proj.size(), kBlock, s,
+               (const DevLayer*)p->d_layers, (const WorkItem*)p->d_items_proj, (const uint8_t*)mask, U, Z);
+    if (e != hipSuccess) return HSADMM_ERR_HIP;
     return HSADMM_OK;
 }
 
@@ -851,10 +877,11 @@ int hsadmm_compact(const hsadmm_plan_t* p, const float* src, const uint8_t* mask
     char* ws = static_cast<char*>(workspace);
     const int rc = run_scan(p, mask, ws, layer_off, kept_idx, s);
     if (rc != HSADMM_OK) return rc;
-    hipLaunchKernelGGL(compact_gather, dim3((unsigned)p->items_rows.size()), dim3(kBlock), 0, s,
-                       p->d_layers, p->d_items_rows, src, reinterpret_cast<const int32_t*>(ws + p->ws.pos),
-                       reinterpret_cast<const int32_t*>(ws + p->ws.cnt), layer_off, packed);
-    if (hipGetLastError() != hipSuccess) return HSADMM_ERR_HIP;
+    const hipError_t e = launch(p, kGather, compact_gather, (unsigned)p->items_rows.size(), kBlock, s,
+                                (const DevLayer*)p->d_layers, (const WorkItem*)p->d_items_rows, src,
+                                reinterpret_cast<const int32_t*>(ws + p->ws.pos),
+                                reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (const int64_t*)layer_off, packed);
+    if (e != hipSuccess) return HSADMM_ERR_HIP;
     return HSADMM_OK;
 }
 
@@ -870,10 +897,11 @@ int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* ma
     int64_t* lo = reinterpret_cast<int64_t*>(ws + p->ws.layer_off);
     const int rc = run_scan(p, mask, ws, lo, reinterpret_cast<int32_t*>(ws + p->ws.kept_idx), s);
     if (rc != HSADMM_OK) return rc;
-    hipLaunchKernelGGL(expand_scatter, dim3((unsigned)p->items_rows.size()), dim3(kBlock), 0, s,
-                       p->d_layers, p->d_items_rows, packed, reinterpret_cast<const int32_t*>(ws + p->ws.pos),
-                       reinterpret_cast<const int32_t*>(ws + p->ws.cnt), lo, dst);
-    if (hipGetLastError() != hipSuccess) return HSADMM_ERR_HIP;
+    const hipError_t e = launch(p, kScatter, expand_scatter, (unsigned)p->items_rows.size(), kBlock, s,
+                                (const DevLayer*)p->d_layers, (const WorkItem*)p->d_items_rows, packed,
+                                reinterpret_cast<const int32_t*>(ws + p->ws.pos),
+                                reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (const int64_t*)lo, dst);
+    if (e != hipSuccess) return HSADMM_ERR_HIP;
     return HSADMM_OK;
 }
 
@@ -890,5 +918,54 @@ const char* hsadmm_strerror(int code)
 }
 
 int hsadmm_version(void) { return kVersion; }
+
+int hsadmm_kernel_timing_enable(hsadmm_plan_t* p, int enable)
+{
+    if (!p) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (enable && p->ev.empty()) {
+        try {
+            p->ev_kernel.assign(kTimingPairs, 0);
+            p->ev.reserve(2 * kTimingPairs);
+        } catch (...) {
+            return HSADMM_ERR_HIP;
+        }
+        for (size_t i = 0; i < 2 * kTimingPairs; ++i) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return HSADMM_ERR_HIP;
+            p->ev.push_back(e);
+        }
+    }
+    p->timing = enable != 0 && p->ev.size() == 2 * kTimingPairs;
+    p->ev_used = 0;
+    return HSADMM_OK;
+}
+
+int hsadmm_kernel_timing_read(hsadmm_plan_t* p, double* total_ms, int64_t* launches)
+{
+    if (!p || !total_ms || !launches) return HSADMM_ERR_INVALID_ARGUMENT;
+    for (int k = 0; k < kKernelCount; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
+    for (size_t i = 0; i < p->ev_used; ++i) {
+        if (hipEventSynchronize(p->ev[2 * i + 1]) != hipSuccess) return HSADMM_ERR_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p->ev[2 * i], p->ev[2 * i + 1]) != hipSuccess) return HSADMM_ERR_HIP;
+        total_ms[p->ev_kernel[i]] += (double)ms;
+        launches[p->ev_kernel[i]] += 1;
+    }
+    p->ev_used = 0;
+    return HSADMM_OK;
+}
+
+const char* hsadmm_kernel_name(int kernel_id)
+{
+    switch (kernel_id) {
+        case kPass1: return "project_pass1";
+        case kTopk: return "select_topk";
+        case kFixup: return "project_fixup";
+        case kScan: return "scan_mask";
+        case kGather: return "compact_gather";
+        case kScatter: return "expand_scatter";
+        default: return "";
+    }
+}
 
 }  // extern "C"
