@@ -6,9 +6,10 @@
 //   project_pass1   streams the R replicas and U once.  Computes Wbar, V = Wbar + U, the fp64
 //                   partial sums of V^2, and writes the values that are final if the group is
 //                   kept: Z <- V, U <- U + (Wbar - V).                       [Eq. (9), (12)]
-//   select_topk     one workgroup per layer: 8-pass byte-wise radix select of the k-th largest
-//                   key on the uint64 view of the non-negative doubles, ties cut by an ordered
-//                   scan so that lower indices win.                          [Eq. (10)]
+//   select_topk     one workgroup per layer: byte-wise radix select of the k-th largest key on
+//                   the uint64 view of the non-negative doubles (bytes all keys share are skipped,
+//                   the search stops once one candidate is left), ties cut by an ordered scan so
+//                   that lower indices win.                                  [Eq. (10)]
 //   project_fixup   touches pruned groups only: U <- V (taken from Z), Z <- +0.  For a pruned
 //                   group U + (Wbar - 0) equals V bit for bit, so no replica is read again.
 //   scan_mask       per layer: kept count, exclusive positions, kept_idx, layer_off.
@@ -16,6 +17,7 @@
 //   expand_scatter  dst <- zero fill + scatter of packed                      [Section 4.4.3]
 //
 // Nothing here is a dense contraction, so no MFMA is used; every kernel is bound by HBM traffic.
+// Arena data is touched once per kernel, so it is moved with non-temporal 128-bit accesses.
 // fp32 arithmetic is compiled without contraction (-ffp-contract=off); the fp64 accumulation
 // uses fma(v, v, acc), which equals mul+add because the square of an fp32 value is exact in fp64.
 
@@ -37,27 +39,45 @@ constexpr int kBlock = 256;                 // streaming kernels: 4 waves
 constexpr int kWaves = kBlock / kWave;
 constexpr int kScanBlock = 1024;            // select_topk and scan_mask
 constexpr int kScanWaves = kScanBlock / kWave;
-constexpr int kTileElems = 8192;            // target elements per work item
-constexpr int kChanRows = 64;               // CHANNEL tiles: rows per row block
-constexpr int kVersion = 100;
+constexpr int kTileElems = 4096;            // target elements per work item
+constexpr int kWideRow = 2048;              // rows at least this long are shared by the whole workgroup
+constexpr int kChanRows = 32;               // CHANNEL tiles: rows per row block
+constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
+constexpr int kVersion = 103;
+
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 struct DevLayer {
     int64_t elem_off;
     int64_t colpart_off;    // CHANNEL: first double of this layer's per-row-block column sums
+    int64_t unit;           // packed elements one kept group contributes (NONE: the whole layer)
     int32_t c_out, c_in, khw, mode, k;
     int32_t G, group_base, row_len;
-    int32_t lpr;            // row-wise kernels: lanes that share one row (power of two <= 64)
-    int32_t vec;            // row_len % 4 == 0 -> 128-bit accesses
     int32_t n_rowblocks;    // CHANNEL: ceil(c_out / kChanRows)
     int32_t pad_;
 };
 
-// One unit of work for a 256-thread workgroup.
+// One unit of work for a 256-thread workgroup; it carries everything the streaming kernels need,
+// so a workgroup starts with a single 64-byte scalar load.
 //   row item  (FILTER / NONE in project kernels, every mode in compact / expand): rows [r0, r0+nr)
-//   tile item (CHANNEL in project kernels): rows [r0, r0+nr) x column strip `strip`
+//   tile item (CHANNEL in project kernels): rows [r0, r0+nr) x one column strip
 struct WorkItem {
-    int32_t layer, r0, nr, strip;
+    int64_t base;       // arena element offset of the item's first row (column 0)
+    int64_t aux;        // tile: offset (doubles) of this row block's column sums in the workspace
+    int32_t g0;         // row item: index in mask/key/pos of the first row; tile: group_base
+    int32_t nr;         // rows
+    int32_t row_len;    // c_in * khw
+    int32_t lpr;        // row item: lanes sharing a row, power of two <= 64, or 256 (whole workgroup)
+    int32_t flags;      // bits 0-1: mode; bit 2: 128-bit path (row_len % 4 == 0)
+    int32_t col0;       // tile: first column of the strip; CHANNEL row item: index of the first row
+    int32_t khw;
+    int32_t layer;
+    int32_t pad_[4];
 };
+static_assert(sizeof(WorkItem) == 64, "WorkItem layout");
+
+__device__ __forceinline__ int item_mode(const WorkItem& it) { return it.flags & 3; }
+__device__ __forceinline__ bool item_vec(const WorkItem& it) { return (it.flags & 4) != 0; }
 
 struct ProjectArgs {
     const float* W[HSADMM_MAX_REPLICAS];
@@ -69,11 +89,14 @@ struct ProjectArgs {
     float inv_R;
 };
 
-__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
-__device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+// Streaming (touch-once) accesses.
+__device__ __forceinline__ v4f ld4(const float* p) { return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p)); }
+__device__ __forceinline__ void st4(float* p, v4f v) { __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p)); }
+__device__ __forceinline__ float ld1(const float* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void st1(float* p, float v) { __builtin_nontemporal_store(v, p); }
 // 128-bit access to an address that is only 4-byte aligned (segments of the packed buffer).
-__device__ __forceinline__ float4 ld4u(const float* p) { float4 v; __builtin_memcpy(&v, p, 16); return v; }
-__device__ __forceinline__ void st4u(float* p, float4 v) { __builtin_memcpy(p, &v, 16); }
+__device__ __forceinline__ v4f ld4u(const float* p) { v4f v; __builtin_memcpy(&v, p, 16); return v; }
+__device__ __forceinline__ void st4u(float* p, v4f v) { __builtin_memcpy(p, &v, 16); }
 
 __device__ __forceinline__ double wave_xor_sum(double a, int width)
 {
@@ -88,42 +111,15 @@ __device__ __forceinline__ int wave_sum_i32(int a)
     return a;
 }
 
+__device__ __forceinline__ long long wave_sum_i64(long long a)
+{
+    for (int o = kWave >> 1; o > 0; o >>= 1) a += __shfl_xor(a, o, kWave);
+    return a;
+}
+
 // ------------------------------------------------------------------ project, pass 1
 
-// Wbar, V and the dual value that is final if the group is kept, for 4 (or 1) adjacent elements.
-// R > 0: replica count known at compile time (loop unrolled, pointers stay in scalar registers);
-// R == 0: any replica count, taken from Rrt.
-template <int R>
-struct Cand {
-    static __device__ __forceinline__ void v4(const ProjectArgs& a, int Rrt, int64_t e, float4& wbar, float4& v, float4& un)
-    {
-        const int RR = R > 0 ? R : Rrt;
-        float4 s = ld4(a.W[0] + e);
-#pragma unroll
-        for (int r = 1; r < RR; ++r) {
-            const float4 w = ld4(a.W[r] + e);
-            s.x = s.x + w.x; s.y = s.y + w.y; s.z = s.z + w.z; s.w = s.w + w.w;
-        }
-        const float4 u = ld4(a.U + e);
-        wbar.x = s.x * a.inv_R; wbar.y = s.y * a.inv_R; wbar.z = s.z * a.inv_R; wbar.w = s.w * a.inv_R;
-        v.x = wbar.x + u.x; v.y = wbar.y + u.y; v.z = wbar.z + u.z; v.w = wbar.w + u.w;
-        un.x = u.x + (wbar.x - v.x); un.y = u.y + (wbar.y - v.y);
-        un.z = u.z + (wbar.z - v.z); un.w = u.w + (wbar.w - v.w);
-    }
-    static __device__ __forceinline__ void v1(const ProjectArgs& a, int Rrt, int64_t e, float& wbar, float& v, float& un)
-    {
-        const int RR = R > 0 ? R : Rrt;
-        float s = a.W[0][e];
-#pragma unroll
-        for (int r = 1; r < RR; ++r) s = s + a.W[r][e];
-        const float u = a.U[e];
-        wbar = s * a.inv_R;
-        v = wbar + u;
-        un = u + (wbar - v);
-    }
-};
-
-__device__ __forceinline__ double sq4(double acc, const float4& v)
+__device__ __forceinline__ double sq4(double acc, const v4f& v)
 {
     acc = fma((double)v.x, (double)v.x, acc);
     acc = fma((double)v.y, (double)v.y, acc);
@@ -132,90 +128,157 @@ __device__ __forceinline__ double sq4(double acc, const float4& v)
     return acc;
 }
 
-// FILTER / NONE: a group is a row.  `lpr` lanes share a row, a wave covers 64/lpr adjacent rows,
-// the waves of the workgroup take consecutive row bundles.  Lane j of a row accumulates elements
-// 4j..4j+3 (+ 4*lpr*i) in order, then the lanes of the row are combined by a butterfly: the order
-// of additions depends only on (row_len, lpr), never on where the row sits.
+// Wbar, V and the dual value that is final if the group is kept, for 4 (or 1) adjacent elements.
+// R > 0: replica count known at compile time (loop unrolled, pointers stay in scalar registers);
+// R == 0: any replica count, taken from Rrt.
 template <int R>
-__device__ __forceinline__ void project_rows_impl(const DevLayer& L, const WorkItem& it, const ProjectArgs& a, int Rrt)
+struct Cand {
+    // two independent 4-element chunks at once (twice the loads in flight)
+    static __device__ __forceinline__ double two(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, double acc)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) {
+            const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
+            s0 = s0 + w0;
+            s1 = s1 + w1;
+        }
+        const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
+        const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
+        const v4f v0 = wb0 + u0, v1 = wb1 + u1;
+        const v4f d0 = wb0 - v0, d1 = wb1 - v1;
+        st4(a.Z + e0, v0);
+        st4(a.Z + e1, v1);
+        st4(a.U + e0, u0 + d0);
+        st4(a.U + e1, u1 + d1);
+        if (a.Wbar) { st4(a.Wbar + e0, wb0); st4(a.Wbar + e1, wb1); }
+        acc = sq4(acc, v0);
+        return sq4(acc, v1);
+    }
+    static __device__ __forceinline__ v4f one(const ProjectArgs& a, int Rrt, int64_t e)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        v4f s = ld4(a.W[0] + e);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+        const v4f u = ld4(a.U + e);
+        const v4f wb = s * a.inv_R;
+        const v4f v = wb + u;
+        const v4f d = wb - v;
+        st4(a.Z + e, v);
+        st4(a.U + e, u + d);
+        if (a.Wbar) st4(a.Wbar + e, wb);
+        return v;
+    }
+    static __device__ __forceinline__ float scalar(const ProjectArgs& a, int Rrt, int64_t e)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        float s = ld1(a.W[0] + e);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
+        const float u = ld1(a.U + e);
+        const float wb = s * a.inv_R;
+        const float v = wb + u;
+        const float d = wb - v;
+        st1(a.Z + e, v);
+        st1(a.U + e, u + d);
+        if (a.Wbar) st1(a.Wbar + e, wb);
+        return v;
+    }
+};
+
+// Sum of squares of the part of one row that lane j of `step` lanes owns (chunks j, j+step, ...),
+// accumulated in increasing chunk order.
+template <int R>
+__device__ __forceinline__ double pass1_row(const ProjectArgs& a, int Rrt, int64_t base, int row_len, bool vec,
+                                            int j, int step)
+{
+    double acc = 0.0;
+    if (vec) {
+        const int nchunk = row_len >> 2;
+        int c = j;
+        for (; c + step < nchunk; c += 2 * step)
+            acc = Cand<R>::two(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + step) << 2), acc);
+        if (c < nchunk) acc = sq4(acc, Cand<R>::one(a, Rrt, base + ((int64_t)c << 2)));
+    } else {
+        for (int c = j; c < row_len; c += step) {
+            const float v = Cand<R>::scalar(a, Rrt, base + c);
+            acc = fma((double)v, (double)v, acc);
+        }
+    }
+    return acc;
+}
+
+// FILTER / NONE: a group is a row.  Short rows: `lpr` <= 64 lanes share a row and a wave covers
+// 64/lpr adjacent rows.  Long rows: the whole workgroup shares a row.  Per-lane sums are combined
+// by a butterfly inside the wave and (long rows) in wave order through LDS, so the order of
+// additions depends only on (row_len, lpr), never on where the row sits: equal groups get equal keys.
+template <int R>
+__device__ __forceinline__ void project_rows(const WorkItem& it, const ProjectArgs& a, int Rrt)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int lpr = L.lpr;
-    const int rpw = kWave / lpr;
-    const int sub = lane / lpr;
-    const int j = lane - sub * lpr;
-    const int row_len = L.row_len;
-    for (int rb = wave * rpw; rb < it.nr; rb += kWaves * rpw) {
-        const int rr = rb + sub;
-        const bool active = rr < it.nr;
-        const int row = it.r0 + rr;
-        const int64_t base = L.elem_off + (int64_t)row * row_len;
-        double acc = 0.0;
-        if (active) {
-            if (L.vec) {
-                const int nchunk = row_len >> 2;
-                for (int c = j; c < nchunk; c += lpr) {
-                    const int64_t e = base + ((int64_t)c << 2);
-                    float4 wbar, v, un;
-                    Cand<R>::v4(a, Rrt, e, wbar, v, un);
-                    st4(a.Z + e, v);
-                    st4(a.U + e, un);
-                    if (a.Wbar) st4(a.Wbar + e, wbar);
-                    acc = sq4(acc, v);
-                }
-            } else {
-                for (int c = j; c < row_len; c += lpr) {
-                    const int64_t e = base + c;
-                    float wbar, v, un;
-                    Cand<R>::v1(a, Rrt, e, wbar, v, un);
-                    a.Z[e] = v;
-                    a.U[e] = un;
-                    if (a.Wbar) a.Wbar[e] = wbar;
-                    acc = fma((double)v, (double)v, acc);
-                }
-            }
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    if (it.lpr <= kWave) {
+        const int lpr = it.lpr;
+        const int rpw = kWave / lpr;
+        const int sub = lane / lpr;
+        const int j = lane - sub * lpr;
+        for (int rb = wave * rpw; rb < it.nr; rb += kWaves * rpw) {
+            const int rr = rb + sub;
+            const bool active = rr < it.nr;
+            double acc = 0.0;
+            if (active) acc = pass1_row<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr);
+            acc = wave_xor_sum(acc, lpr);
+            if (active && j == 0) a.key[it.g0 + rr] = acc;
         }
-        acc = wave_xor_sum(acc, lpr);
-        if (active && j == 0) a.key[L.group_base + row] = acc;
+    } else {
+        __shared__ double wsum[kWaves];
+        for (int rr = 0; rr < it.nr; ++rr) {
+            double acc = pass1_row<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, threadIdx.x, kBlock);
+            acc = wave_xor_sum(acc, kWave);
+            if (lane == 0) wsum[wave] = acc;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double s = wsum[0];
+                for (int w = 1; w < kWaves; ++w) s += wsum[w];
+                a.key[it.g0 + rr] = s;
+            }
+            __syncthreads();
+        }
     }
 }
 
 // CHANNEL: a group is a block of khw adjacent columns of the [c_out][row_len] view.  A tile is
-// (row block, column strip); each lane owns VW adjacent columns of the strip and walks down the
-// rows of its wave, so it accumulates per-column sums in registers.  The four waves' sums are
-// added in wave order through LDS and stored as this row block's partial column sums; select_topk
-// later adds row blocks and the khw columns of a channel in a fixed order.
+// (row block, column strip); each lane owns 4 (or 1) adjacent columns of the strip and walks down
+// the rows of its wave, accumulating per-column sums in registers.  The four waves' sums are added
+// in wave order through LDS and stored as this row block's partial column sums; the layer's selection later
+// adds row blocks and the khw columns of a channel in a fixed order.
 template <int R>
-__device__ __forceinline__ void project_tile_impl(const DevLayer& L, const WorkItem& it, const ProjectArgs& a, int Rrt)
+__device__ __forceinline__ void project_tile(const WorkItem& it, const ProjectArgs& a, int Rrt)
 {
     __shared__ double part[kWaves][kWave * 4];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int row_len = L.row_len;
-    const int vw = L.vec ? 4 : 1;
-    const int col = (it.strip * kWave + lane) * vw;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const int vw = vec ? 4 : 1;
+    const int col = it.col0 + lane * vw;
     const bool in = col < row_len;
     double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
     if (in) {
         for (int rr = wave; rr < it.nr; rr += kWaves) {
-            const int64_t e = L.elem_off + (int64_t)(it.r0 + rr) * row_len + col;
-            if (L.vec) {
-                float4 wbar, v, un;
-                Cand<R>::v4(a, Rrt, e, wbar, v, un);
-                st4(a.Z + e, v);
-                st4(a.U + e, un);
-                if (a.Wbar) st4(a.Wbar + e, wbar);
+            const int64_t e = it.base + (int64_t)rr * row_len + col;
+            if (vec) {
+                const v4f v = Cand<R>::one(a, Rrt, e);
                 acc0 = fma((double)v.x, (double)v.x, acc0);
                 acc1 = fma((double)v.y, (double)v.y, acc1);
                 acc2 = fma((double)v.z, (double)v.z, acc2);
                 acc3 = fma((double)v.w, (double)v.w, acc3);
             } else {
-                float wbar, v, un;
-                Cand<R>::v1(a, Rrt, e, wbar, v, un);
-                a.Z[e] = v;
-                a.U[e] = un;
-                if (a.Wbar) a.Wbar[e] = wbar;
+                const float v = Cand<R>::scalar(a, Rrt, e);
                 acc0 = fma((double)v, (double)v, acc0);
             }
         }
@@ -226,8 +289,7 @@ __device__ __forceinline__ void project_tile_impl(const DevLayer& L, const WorkI
     part[wave][lane * 4 + 3] = acc3;
     __syncthreads();
     if (wave == 0 && in) {
-        const int rbi = it.r0 / kChanRows;
-        double* out = a.colpart + L.colpart_off + (int64_t)rbi * row_len + col;
+        double* out = a.colpart + it.aux + col;
         for (int i = 0; i < vw; ++i) {
             double s = part[0][lane * 4 + i];
             for (int w = 1; w < kWaves; ++w) s += part[w][lane * 4 + i];
@@ -237,19 +299,18 @@ __device__ __forceinline__ void project_tile_impl(const DevLayer& L, const WorkI
 }
 
 template <int R>
-__global__ __launch_bounds__(kBlock) void project_pass1(const DevLayer* __restrict__ layers,
-                                                        const WorkItem* __restrict__ items,
-                                                        ProjectArgs a, int Rrt)
+__global__ __launch_bounds__(kBlock) void project_pass1(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt)
 {
     const WorkItem it = items[blockIdx.x];
-    const DevLayer L = layers[it.layer];
-    if (L.mode == HSADMM_MODE_CHANNEL) project_tile_impl<R>(L, it, a, Rrt);
-    else project_rows_impl<R>(L, it, a, Rrt);
+    if (item_mode(it) == HSADMM_MODE_CHANNEL) project_tile<R>(it, a, Rrt);
+    else project_rows<R>(it, a, Rrt);
 }
 
 // ------------------------------------------------------------------ top-k selection
 
-__device__ __forceinline__ int block_excl_scan_1024(bool flag, int* wtot, int& total)
+// Exclusive prefix count of `flag` over the NW*64 threads of the block, in thread order.
+template <int NW>
+__device__ __forceinline__ int block_excl_scan(bool flag, int* wtot, int& total)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
@@ -259,7 +320,8 @@ __device__ __forceinline__ int block_excl_scan_1024(bool flag, int* wtot, int& t
     if (lane == 0) wtot[wave] = __popcll(b);
     __syncthreads();
     int before = 0, tot = 0;
-    for (int w = 0; w < kScanWaves; ++w) {
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
         const int t = wtot[w];
         before += (w < wave) ? t : 0;
         tot += t;
@@ -268,25 +330,183 @@ __device__ __forceinline__ int block_excl_scan_1024(bool flag, int* wtot, int& t
     return before + in_wave;
 }
 
-// One workgroup per layer.  Keys are non-negative finite doubles, so their uint64 bit patterns
-// order like their values.  The k-th largest pattern tau is found byte by byte from the top
-// (256-bin histogram per pass).  Groups with key > tau are kept; of the groups with key == tau
-// the first `need` in index order are kept.
+struct TopkShared {
+    unsigned int hist[2][256];                 // double-buffered: one is cleared while the other fills
+    unsigned long long w_and[kScanWaves], w_or[kScanWaves];
+    int wtot[kScanWaves];
+    unsigned long long prefix;                 // bytes of tau found so far (lower bytes zero)
+    unsigned long long tau;                    // early exit: the one remaining candidate
+    unsigned int need;                         // how many groups to take among the current candidates
+    unsigned int cand;                         // number of current candidates
+};
+
+// Keys of a layer as seen by the selection: in registers (G <= 8 * 1024) or re-read from memory.
+template <bool INREG>
+struct LayerKeys {
+    unsigned long long kreg[kTopkRegs];
+    const unsigned long long* kb;
+    int G;
+    __device__ __forceinline__ void load(const unsigned long long* p, int g_count)
+    {
+        kb = p;
+        G = g_count;
+        if (INREG) {
+#pragma unroll
+            for (int i = 0; i < kTopkRegs; ++i) {
+                const int g = (int)threadIdx.x + i * kScanBlock;
+                kreg[i] = (g < G) ? kb[g] : 0ull;
+            }
+        }
+    }
+    // calls f(g, key) for every group this thread owns (g = tid, tid + 1024, ...)
+    template <typename F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        if (INREG) {
+#pragma unroll
+            for (int i = 0; i < kTopkRegs; ++i) {
+                const int g = (int)threadIdx.x + i * kScanBlock;
+                if (g < G) f(g, kreg[i]);
+            }
+        } else {
+            for (int g = threadIdx.x; g < G; g += kScanBlock) f(g, kb[g]);
+        }
+    }
+};
+
+// Keys are non-negative finite doubles, so their uint64 bit patterns order like their values.
+// tau, the k-th largest pattern, is found byte by byte from the most significant byte in which the
+// keys differ (one 256-bin histogram per pass).  `need` tracks how many groups must still be taken
+// from the candidates that share the prefix found so far.  Groups with key > tau are kept; of the
+// groups with key == tau the first `need` in index order are kept.
+template <bool INREG>
+__device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, uint8_t* ml, int kk, TopkShared& sh)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    LayerKeys<INREG> keys;
+    keys.load(kb, G);
+
+    // bits shared by all keys
+    unsigned long long a_and = ~0ull, a_or = 0ull;
+    keys.for_each([&](int, unsigned long long x) { a_and &= x; a_or |= x; });
+    for (int o = kWave >> 1; o > 0; o >>= 1) {
+        a_and &= __shfl_xor(a_and, o, kWave);
+        a_or |= __shfl_xor(a_or, o, kWave);
+    }
+    if (lane == 0) { sh.w_and[wave] = a_and; sh.w_or[wave] = a_or; }
+    if (tid < 256) { sh.hist[0][tid] = 0u; sh.hist[1][tid] = 0u; }
+    __syncthreads();
+    a_and = ~0ull; a_or = 0ull;
+#pragma unroll
+    for (int w = 0; w < kScanWaves; ++w) { a_and &= sh.w_and[w]; a_or |= sh.w_or[w]; }
+    const unsigned long long diff = a_and ^ a_or;
+
+    unsigned long long tau;
+    int need;
+    bool scan_ties;
+    if (diff == 0ull) {
+        // all keys equal: the first k groups win
+        tau = a_or;
+        need = kk;
+        scan_ties = true;
+    } else {
+        const int top = 63 - __clzll((long long)diff);        // most significant differing bit
+        int shift = (top >> 3) << 3;                          // its byte
+        const unsigned long long common = (shift + 8 >= 64) ? 0ull : ((a_or >> (shift + 8)) << (shift + 8));
+        if (tid == 0) { sh.prefix = common; sh.need = (unsigned int)kk; sh.cand = (unsigned int)G; }
+        __syncthreads();
+        int buf = 0;
+        bool unique = false;
+        for (; shift >= 0; shift -= 8) {
+            const unsigned long long prefix = sh.prefix;
+            const unsigned int need_now = sh.need;
+            unsigned int* h = sh.hist[buf];
+            keys.for_each([&](int, unsigned long long x) {
+                if (shift + 8 >= 64 || (x >> (shift + 8)) == (prefix >> (shift + 8)))
+                    atomicAdd(&h[(unsigned int)(x >> shift) & 255u], 1u);
+            });
+            if (tid < 256) sh.hist[buf ^ 1][tid] = 0u;         // ready for the next pass
+            __syncthreads();
+            if (tid < kWave) {
+                // lane i owns bins 4i..4i+3; `above` = number of candidates in higher bins
+                const unsigned int h0 = h[4 * tid], h1 = h[4 * tid + 1], h2 = h[4 * tid + 2], h3 = h[4 * tid + 3];
+                const unsigned int hh[4] = {h0, h1, h2, h3};
+                const unsigned int mine = h0 + h1 + h2 + h3;
+                unsigned int incl = mine;   // inclusive suffix sum over lanes tid..63
+                for (int o = 1; o < kWave; o <<= 1) {
+                    const unsigned int up = __shfl_down(incl, o, kWave);
+                    if (tid + o < kWave) incl += up;
+                }
+                unsigned int above = incl - mine;
+#pragma unroll
+                for (int b = 3; b >= 0; --b) {
+                    if (above < need_now && need_now <= above + hh[b]) {
+                        sh.prefix = prefix | ((unsigned long long)(4 * tid + b) << shift);
+                        sh.need = need_now - above;
+                        sh.cand = hh[b];
+                    }
+                    above += hh[b];
+                }
+            }
+            __syncthreads();
+            buf ^= 1;
+            if (sh.cand == 1u && shift > 0) { unique = true; break; }
+        }
+        if (unique) {
+            // one candidate left: it is tau; find it by its prefix
+            const unsigned long long prefix = sh.prefix;
+            keys.for_each([&](int, unsigned long long x) {
+                if ((x >> shift) == (prefix >> shift)) sh.tau = x;
+            });
+            __syncthreads();
+            tau = sh.tau;
+            need = 1;
+            scan_ties = false;
+        } else {
+            tau = sh.prefix;
+            need = (int)sh.need;
+            scan_ties = (unsigned int)need != sh.cand;        // fewer wanted than tied: index order decides
+        }
+    }
+    if (!scan_ties) {
+        keys.for_each([&](int g, unsigned long long x) { ml[g] = (x >= tau) ? 1 : 0; });
+        return;
+    }
+    int carry = 0;
+    for (int base = 0; base < G; base += kScanBlock) {
+        const int g = base + tid;
+        unsigned long long x = 0ull;
+        if (g < G) {
+            if (INREG) {
+#pragma unroll
+                for (int i = 0; i < kTopkRegs; ++i) if (i * kScanBlock == base) x = keys.kreg[i];
+            } else {
+                x = kb[g];
+            }
+        }
+        const bool eq = (g < G) && (x == tau);
+        const bool gt = (g < G) && (x > tau);
+        int total;
+        const int rank = carry + block_excl_scan<kScanWaves>(eq, sh.wtot, total);
+        if (g < G) ml[g] = (gt || (eq && rank < need)) ? 1 : 0;
+        carry += total;
+    }
+}
+
+// One workgroup per layer: finish the CHANNEL keys, then write the layer's mask.
 __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __restrict__ layers,
                                                           double* __restrict__ key,
                                                           const double* __restrict__ colpart,
                                                           uint8_t* __restrict__ mask)
 {
-    __shared__ unsigned int hist[256];
-    __shared__ int wtot[kScanWaves];
-    __shared__ unsigned long long s_prefix;
-    __shared__ unsigned int s_need;
+    __shared__ TopkShared sh;
     const DevLayer L = layers[blockIdx.x];
     const int G = L.G;
     const int tid = threadIdx.x;
     double* kl = key + L.group_base;
     uint8_t* ml = mask + L.group_base;
-
     if (L.mode == HSADMM_MODE_CHANNEL) {
         // key[c] = sum over row blocks (ascending), then over the channel's khw columns (ascending)
         const double* cp = colpart + L.colpart_off;
@@ -304,81 +524,34 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
         return;
     }
     const unsigned long long* kb = reinterpret_cast<const unsigned long long*>(kl);
-    if (tid == 0) { s_prefix = 0ull; s_need = (unsigned int)kk; }
-    for (int pass = 0; pass < 8; ++pass) {
-        const int shift = 56 - 8 * pass;
-        if (tid < 256) hist[tid] = 0u;
-        __syncthreads();
-        const unsigned long long prefix = s_prefix;
-        const unsigned int need = s_need;
-        for (int g = tid; g < G; g += kScanBlock) {
-            const unsigned long long x = kb[g];
-            const bool match = (pass == 0) || ((x >> (shift + 8)) == (prefix >> (shift + 8)));
-            if (match) atomicAdd(&hist[(unsigned int)(x >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (tid < kWave) {
-            // lane i owns bins 4i..4i+3; `above` = number of matching keys in bins of higher lanes
-            const unsigned int h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
-            const unsigned int mine = h0 + h1 + h2 + h3;
-            unsigned int incl = mine;   // inclusive suffix sum over lanes tid..63
-            for (int o = 1; o < kWave; o <<= 1) {
-                const unsigned int up = __shfl_down(incl, o, kWave);
-                if (tid + o < kWave) incl += up;
-            }
-            unsigned int above = incl - mine;
-            const unsigned int hh[4] = {h0, h1, h2, h3};
-            for (int b = 3; b >= 0; --b) {
-                if (above < need && need <= above + hh[b]) {
-                    s_prefix = prefix | ((unsigned long long)(4 * tid + b) << shift);
-                    s_need = need - above;
-                }
-                above += hh[b];
-            }
-        }
-        __syncthreads();
-    }
-    const unsigned long long tau = s_prefix;
-    const int need = (int)s_need;
-    int carry = 0;
-    for (int base = 0; base < G; base += kScanBlock) {
-        const int g = base + tid;
-        const unsigned long long x = (g < G) ? kb[g] : 0ull;
-        const bool eq = (g < G) && (x == tau);
-        const bool gt = (g < G) && (x > tau);
-        int total;
-        const int rank = carry + block_excl_scan_1024(eq, wtot, total);
-        if (g < G) ml[g] = (gt || (eq && rank < need)) ? 1 : 0;
-        carry += total;
-    }
+    if (G <= kTopkRegs * kScanBlock) topk_layer<true>(G, kb, ml, kk, sh);
+    else topk_layer<false>(G, kb, ml, kk, sh);
 }
 
 // ------------------------------------------------------------------ project, fix-up of pruned groups
 
-__global__ __launch_bounds__(kBlock) void project_fixup(const DevLayer* __restrict__ layers,
-                                                        const WorkItem* __restrict__ items,
+__global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restrict__ items,
                                                         const uint8_t* __restrict__ mask,
                                                         float* __restrict__ U, float* __restrict__ Z)
 {
     const WorkItem it = items[blockIdx.x];
-    const DevLayer L = layers[it.layer];
-    if (L.mode == HSADMM_MODE_NONE) return;
+    const int mode = item_mode(it);
+    if (mode == HSADMM_MODE_NONE) return;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int row_len = L.row_len;
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (L.mode == HSADMM_MODE_FILTER) {
-        const int lpr = L.lpr;
-        const int rpw = kWave / lpr;
-        const int sub = lane / lpr;
-        const int j = lane - sub * lpr;
-        for (int rb = wave * rpw; rb < it.nr; rb += kWaves * rpw) {
-            const int rr = rb + sub;
-            if (rr >= it.nr) continue;
-            const int row = it.r0 + rr;
-            if (mask[L.group_base + row]) continue;
-            const int64_t base = L.elem_off + (int64_t)row * row_len;
-            if (L.vec) {
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    if (mode == HSADMM_MODE_FILTER) {
+        // lanes-per-row mapping as in pass 1 (the mapping carries no arithmetic here)
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            if (mask[it.g0 + rr]) continue;
+            const int64_t base = it.base + (int64_t)rr * row_len;
+            if (vec) {
                 const int nchunk = row_len >> 2;
                 for (int c = j; c < nchunk; c += lpr) {
                     const int64_t e = base + ((int64_t)c << 2);
@@ -387,26 +560,26 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const DevLayer* __restri
                 }
             } else {
                 for (int c = j; c < row_len; c += lpr) {
-                    U[base + c] = Z[base + c];
-                    Z[base + c] = 0.f;
+                    st1(U + base + c, ld1(Z + base + c));
+                    st1(Z + base + c, 0.f);
                 }
             }
         }
     } else {
-        const int vw = L.vec ? 4 : 1;
-        const int col = (it.strip * kWave + lane) * vw;
+        const int vw = vec ? 4 : 1;
+        const int col = it.col0 + lane * vw;
         if (col >= row_len) return;
         bool pr[4] = {false, false, false, false};
         bool any = false;
         for (int i = 0; i < vw; ++i) {
-            pr[i] = mask[L.group_base + (col + i) / L.khw] == 0;
+            pr[i] = mask[it.g0 + (col + i) / it.khw] == 0;
             any = any || pr[i];
         }
         if (!any) return;
         for (int rr = wave; rr < it.nr; rr += kWaves) {
-            const int64_t e = L.elem_off + (int64_t)(it.r0 + rr) * row_len + col;
-            if (L.vec) {
-                const float4 z = ld4(Z + e);
+            const int64_t e = it.base + (int64_t)rr * row_len + col;
+            if (vec) {
+                const v4f z = ld4(Z + e);
                 if (pr[0] && pr[1] && pr[2] && pr[3]) {
                     st4(U + e, z);
                     st4(Z + e, zero4);
@@ -433,65 +606,118 @@ struct ScanOut {
     int32_t* kept_idx;   // groups_total
 };
 
-__device__ __forceinline__ int64_t packed_size(const DevLayer& L, int cnt)
+__device__ __forceinline__ int nonzero_bytes(unsigned int x)
 {
-    if (L.mode == HSADMM_MODE_CHANNEL) return (int64_t)L.c_out * cnt * L.khw;
-    return (int64_t)cnt * L.row_len;
+    // bit 7 of every byte becomes 1 iff the byte is nonzero
+    const unsigned int t = (((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) & 0x80808080u;
+    return __popc(t);
 }
 
-// One workgroup per layer.  Workgroup l first counts the kept groups of layers 0..l (waves share
-// the layers), derives its own segment offset, then scans its own layer's mask.
+// One workgroup per layer.  Every workgroup counts the kept groups of all layers in one flat pass
+// over the mask, 16 groups per thread and step: chunk_layer gives the layer of a 16-group chunk that
+// lies inside one constrained layer (one 128-bit load, a popcount, and one LDS add per wave when
+// the whole wave sits in one layer); chunks that straddle layers or touch an unconstrained layer
+// (0xffff) go group by group through group_layer (bit 15 marks an unconstrained layer, whose groups
+// are always kept).  The workgroup then sums the aligned segment sizes of layers 0..l-1 to get its
+// segment offset and scans its own layer's mask.  Segment starts are multiples of pack_align, so
+// the offset is the plain sum of the rounded-up sizes.
 __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restrict__ layers, int nL,
-                                                        int pack_align, const uint8_t* __restrict__ mask,
-                                                        ScanOut o)
+                                                        int n_groups, int pack_align,
+                                                        const uint8_t* __restrict__ mask,
+                                                        const uint16_t* __restrict__ group_layer,
+                                                        const uint16_t* __restrict__ chunk_layer, ScanOut o)
 {
     __shared__ int cnt[HSADMM_MAX_LAYERS];
     __shared__ int wtot[kScanWaves];
-    __shared__ int s_keptbase;
+    __shared__ long long wsum[kScanWaves];
+    __shared__ int wkept[kScanWaves];
     const int l = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
-    for (int j = wave; j <= l; j += kScanWaves) {
-        const int G = layers[j].G;
-        const int gb = layers[j].group_base;
-        int c = 0;
-        if (layers[j].mode == HSADMM_MODE_NONE) {
-            c = (lane == 0) ? G : 0;
-        } else {
-            for (int g = lane; g < G; g += kWave) c += mask[gb + g] != 0 ? 1 : 0;
+    const DevLayer L = layers[l];
+    // loads that depend on nothing but the thread index go first
+    long long unit_j = 0;
+    int none_j = 0;
+    if (tid < l) { unit_j = layers[tid].unit; none_j = layers[tid].mode == HSADMM_MODE_NONE; }
+    for (int j = tid; j < nL; j += kScanBlock) cnt[j] = 0;
+    __syncthreads();
+    const bool aligned16 = (reinterpret_cast<uintptr_t>(mask) & 15u) == 0;
+    const int nchunks = (n_groups + 15) >> 4;
+    for (int c0 = wave * kWave; c0 < nchunks; c0 += kScanBlock) {
+        const int c = c0 + lane;
+        unsigned int cl = 0xffffu;
+        int kept = 0;
+        bool slow = false;
+        if (c < nchunks) {
+            cl = chunk_layer[c];
+            if (cl != 0xffffu) {
+                if (aligned16) {
+                    const uint4 m = reinterpret_cast<const uint4*>(mask)[c];
+                    kept = nonzero_bytes(m.x) + nonzero_bytes(m.y) + nonzero_bytes(m.z) + nonzero_bytes(m.w);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) kept += mask[16 * c + i] != 0 ? 1 : 0;
+                }
+            } else {
+                slow = true;
+            }
         }
-        c = wave_sum_i32(c);
-        if (lane == 0) cnt[j] = c;
+        const unsigned int cl0 = __shfl(cl, 0, kWave);
+        if (cl0 != 0xffffu && __all((c >= nchunks) || cl == cl0)) {
+            const int tot = wave_sum_i32(kept);
+            if (lane == 0 && tot) atomicAdd(&cnt[cl0], tot);
+        } else {
+            if (cl != 0xffffu && kept) atomicAdd(&cnt[cl], kept);
+            if (slow) {
+                for (int i = 0; i < 16; ++i) {
+                    const int g = 16 * c + i;
+                    if (g >= n_groups) break;
+                    const unsigned int gl = group_layer[g];
+                    if ((gl & 0x8000u) != 0 || mask[g] != 0) atomicAdd(&cnt[gl & 0x7fffu], 1);
+                }
+            }
+        }
     }
     __syncthreads();
-    const DevLayer L = layers[l];
+    long long sz = 0;
+    int kept_before = 0;
+    if (tid < l) {
+        const int c = cnt[tid];
+        long long s = none_j ? unit_j : (long long)c * unit_j;
+        sz = (s + pack_align - 1) / pack_align * pack_align;
+        kept_before = c;
+    }
+    for (int j = tid + kScanBlock; j < l; j += kScanBlock) {    // more than 1024 layers
+        const int c = cnt[j];
+        long long s = (layers[j].mode == HSADMM_MODE_NONE) ? layers[j].unit : (long long)c * layers[j].unit;
+        sz += (s + pack_align - 1) / pack_align * pack_align;
+        kept_before += c;
+    }
+    sz = wave_sum_i64(sz);
+    kept_before = wave_sum_i32(kept_before);
+    if (lane == 0) { wsum[wave] = sz; wkept[wave] = kept_before; }
+    __syncthreads();
+    long long pos = 0;
+    int kb = 0;
+#pragma unroll
+    for (int w = 0; w < kScanWaves; ++w) { pos += wsum[w]; kb += wkept[w]; }
     if (tid == 0) {
-        int64_t pos = 0;
-        int kb = 0;
-        for (int j = 0; j < l; ++j) {
-            pos += packed_size(layers[j], cnt[j]);
-            pos = (pos + pack_align - 1) / pack_align * pack_align;
-            kb += cnt[j];
-        }
         o.layer_off[l] = pos;
         o.cnt[l] = cnt[l];
-        s_keptbase = kb;
         if (l == nL - 1) {
-            pos += packed_size(L, cnt[l]);
-            pos = (pos + pack_align - 1) / pack_align * pack_align;
-            o.layer_off[nL] = pos;
+            long long s = (L.mode == HSADMM_MODE_NONE) ? L.unit : (long long)cnt[l] * L.unit;
+            s = (s + pack_align - 1) / pack_align * pack_align;
+            o.layer_off[nL] = pos + s;
         }
     }
-    __syncthreads();
-    const int kb = s_keptbase;
     const int G = L.G;
     int carry = 0;
     for (int base = 0; base < G; base += kScanBlock) {
         const int g = base + tid;
         const bool m = (g < G) && (L.mode == HSADMM_MODE_NONE || mask[L.group_base + g] != 0);
         int total;
-        const int rank = carry + block_excl_scan_1024(m, wtot, total);
+        const int rank = carry + block_excl_scan<kScanWaves>(m, wtot, total);
         if (g < G) {
             o.pos[L.group_base + g] = m ? rank : -1;
             if (m) o.kept_idx[kb + rank] = g;
@@ -502,8 +728,7 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
 
 // ------------------------------------------------------------------ compaction (gather)
 
-__global__ __launch_bounds__(kBlock) void compact_gather(const DevLayer* __restrict__ layers,
-                                                         const WorkItem* __restrict__ items,
+__global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restrict__ items,
                                                          const float* __restrict__ src,
                                                          const int32_t* __restrict__ pos,
                                                          const int32_t* __restrict__ cnt,
@@ -511,25 +736,21 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const DevLayer* __restr
                                                          float* __restrict__ packed)
 {
     const WorkItem it = items[blockIdx.x];
-    const DevLayer L = layers[it.layer];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int row_len = L.row_len;
+    const int row_len = it.row_len;
     float* out = packed + layer_off[it.layer];
-    if (L.mode != HSADMM_MODE_CHANNEL) {
-        const int lpr = L.lpr;
-        const int rpw = kWave / lpr;
-        const int sub = lane / lpr;
-        const int j = lane - sub * lpr;
-        for (int rb = wave * rpw; rb < it.nr; rb += kWaves * rpw) {
-            const int rr = rb + sub;
-            if (rr >= it.nr) continue;
-            const int row = it.r0 + rr;
-            const int p = pos[L.group_base + row];
+    if (item_mode(it) != HSADMM_MODE_CHANNEL) {
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            const int p = pos[it.g0 + rr];
             if (p < 0) continue;
-            const float* s = src + L.elem_off + (int64_t)row * row_len;
+            const float* s = src + it.base + (int64_t)rr * row_len;
             float* d = out + (int64_t)p * row_len;
-            if (L.vec) {
+            if (item_vec(it)) {
                 const int nchunk = row_len >> 2;
                 for (int c = j; c < nchunk; c += lpr) st4u(d + 4 * c, ld4(s + 4 * c));
             } else {
@@ -537,19 +758,17 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const DevLayer* __restr
             }
         }
     } else {
-        // packed row o holds the kept channels' khw-blocks in ascending channel order
+        // packed row o holds the kept channels' khw-blocks in ascending channel order; it.g0 is the
+        // layer's group base and it.col0 the index of the item's first row inside the layer
         const int kc = cnt[it.layer];
-        const int khw = L.khw;
+        const int khw = it.khw;
         const int out_len = kc * khw;
-        // kept channel q of this layer -> channel index: invert pos by a search-free gather:
-        // walk source columns and write each kept one to its slot.
         for (int rr = wave; rr < it.nr; rr += kWaves) {
-            const int row = it.r0 + rr;
-            const float* s = src + L.elem_off + (int64_t)row * row_len;
-            float* d = out + (int64_t)row * out_len;
+            const float* s = src + it.base + (int64_t)rr * row_len;
+            float* d = out + (int64_t)(it.col0 + rr) * out_len;
             for (int c = lane; c < row_len; c += kWave) {
                 const int ch = c / khw;
-                const int p = pos[L.group_base + ch];
+                const int p = pos[it.g0 + ch];
                 if (p >= 0) d[p * khw + (c - ch * khw)] = s[c];
             }
         }
@@ -558,8 +777,7 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const DevLayer* __restr
 
 // ------------------------------------------------------------------ expansion (zero fill + scatter)
 
-__global__ __launch_bounds__(kBlock) void expand_scatter(const DevLayer* __restrict__ layers,
-                                                         const WorkItem* __restrict__ items,
+__global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restrict__ items,
                                                          const float* __restrict__ packed,
                                                          const int32_t* __restrict__ pos,
                                                          const int32_t* __restrict__ cnt,
@@ -567,25 +785,21 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const DevLayer* __restr
                                                          float* __restrict__ dst)
 {
     const WorkItem it = items[blockIdx.x];
-    const DevLayer L = layers[it.layer];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int row_len = L.row_len;
+    const int row_len = it.row_len;
     const float* in = packed + layer_off[it.layer];
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (L.mode != HSADMM_MODE_CHANNEL) {
-        const int lpr = L.lpr;
-        const int rpw = kWave / lpr;
-        const int sub = lane / lpr;
-        const int j = lane - sub * lpr;
-        for (int rb = wave * rpw; rb < it.nr; rb += kWaves * rpw) {
-            const int rr = rb + sub;
-            if (rr >= it.nr) continue;
-            const int row = it.r0 + rr;
-            const int p = pos[L.group_base + row];
-            float* d = dst + L.elem_off + (int64_t)row * row_len;
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    if (item_mode(it) != HSADMM_MODE_CHANNEL) {
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            const int p = pos[it.g0 + rr];
+            float* d = dst + it.base + (int64_t)rr * row_len;
             const float* s = in + (int64_t)(p < 0 ? 0 : p) * row_len;
-            if (L.vec) {
+            if (item_vec(it)) {
                 const int nchunk = row_len >> 2;
                 if (p >= 0) for (int c = j; c < nchunk; c += lpr) st4(d + 4 * c, ld4u(s + 4 * c));
                 else for (int c = j; c < nchunk; c += lpr) st4(d + 4 * c, zero4);
@@ -596,15 +810,14 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const DevLayer* __restr
         }
     } else {
         const int kc = cnt[it.layer];
-        const int khw = L.khw;
+        const int khw = it.khw;
         const int in_len = kc * khw;
         for (int rr = wave; rr < it.nr; rr += kWaves) {
-            const int row = it.r0 + rr;
-            float* d = dst + L.elem_off + (int64_t)row * row_len;
-            const float* s = in + (int64_t)row * in_len;
+            float* d = dst + it.base + (int64_t)rr * row_len;
+            const float* s = in + (int64_t)(it.col0 + rr) * in_len;
             for (int c = lane; c < row_len; c += kWave) {
                 const int ch = c / khw;
-                const int p = pos[L.group_base + ch];
+                const int p = pos[it.g0 + ch];
                 d[c] = (p >= 0) ? s[p * khw + (c - ch * khw)] : 0.f;
             }
         }
@@ -618,6 +831,9 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, total;
 };
+
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kKernelCount };
+constexpr size_t kTimingPairs = 8192;
 
 }  // namespace
 
@@ -636,6 +852,8 @@ struct hsadmm_plan {
     DevLayer* d_layers = nullptr;
     WorkItem* d_items_proj = nullptr;
     WorkItem* d_items_rows = nullptr;
+    uint16_t* d_group_layer = nullptr;   // groups_total: layer of every group (bit 15: unconstrained layer)
+    uint16_t* d_chunk_layer = nullptr;   // per 16 groups: their layer if all 16 lie in one constrained layer, else 0xffff
     // Optional per-kernel timing (diagnostics; off by default).  Not thread-safe.
     bool timing = false;
     std::vector<hipEvent_t> ev;      // pairs: start, stop
@@ -645,7 +863,6 @@ struct hsadmm_plan {
 
 namespace {
 
-
 int ceil_pow2(int x)
 {
     int p = 1;
@@ -653,23 +870,58 @@ int ceil_pow2(int x)
     return p;
 }
 
-void add_row_items(std::vector<WorkItem>& out, int layer, const DevLayer& d)
+// Row items of one layer.  `mode` is the mode the kernels should see (compact / expand walk a
+// CHANNEL layer row by row as well).
+void add_row_items(std::vector<WorkItem>& out, int layer, const DevLayer& d, int mode)
 {
-    const int rpw = kWave / d.lpr;
-    const int bundle = kWaves * rpw;   // rows one pass of the workgroup covers
+    const bool vec = (d.row_len % 4) == 0;
+    const int units = vec ? d.row_len / 4 : d.row_len;          // accesses per row
+    int lpr, bundle;
+    if (d.row_len >= kWideRow && vec) { lpr = kBlock; bundle = 1; }
+    else { lpr = units >= kWave ? kWave : ceil_pow2(units); bundle = kWaves * (kWave / lpr); }
     int64_t want = kTileElems / (int64_t)d.row_len;
     if (want < bundle) want = bundle;
     want = (want + bundle - 1) / bundle * bundle;
     for (int r0 = 0; r0 < d.c_out; r0 += (int)want) {
-        const int nr = (int)((d.c_out - r0) < want ? (d.c_out - r0) : want);
-        out.push_back(WorkItem{layer, r0, nr, 0});
+        WorkItem it{};
+        it.base = d.elem_off + (int64_t)r0 * d.row_len;
+        it.aux = 0;
+        it.g0 = (mode == HSADMM_MODE_CHANNEL) ? d.group_base : d.group_base + r0;
+        it.nr = (int)((d.c_out - r0) < want ? (d.c_out - r0) : want);
+        it.row_len = d.row_len;
+        it.lpr = lpr;
+        it.flags = mode | (vec ? 4 : 0);
+        it.col0 = (mode == HSADMM_MODE_CHANNEL) ? r0 : 0;
+        it.khw = d.khw;
+        it.layer = layer;
+        out.push_back(it);
+    }
+}
+
+void add_tile_items(std::vector<WorkItem>& out, int layer, const DevLayer& d)
+{
+    const bool vec = (d.row_len % 4) == 0;
+    const int strip_cols = kWave * (vec ? 4 : 1);
+    const int nstrips = (d.row_len + strip_cols - 1) / strip_cols;
+    for (int r0 = 0; r0 < d.c_out; r0 += kChanRows) {
+        for (int s = 0; s < nstrips; ++s) {
+            WorkItem it{};
+            it.base = d.elem_off + (int64_t)r0 * d.row_len;
+            it.aux = d.colpart_off + (int64_t)(r0 / kChanRows) * d.row_len;
+            it.g0 = d.group_base;
+            it.nr = (d.c_out - r0) < kChanRows ? (d.c_out - r0) : kChanRows;
+            it.row_len = d.row_len;
+            it.lpr = kWave;
+            it.flags = HSADMM_MODE_CHANNEL | (vec ? 4 : 0);
+            it.col0 = s * strip_cols;
+            it.khw = d.khw;
+            it.layer = layer;
+            out.push_back(it);
+        }
     }
 }
 
 bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
-
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kKernelCount };
-constexpr size_t kTimingPairs = 8192;
 
 // Launches `kernel` on stream s.  With timing enabled the launch carries a start and a stop event
 // that take the kernel's own begin / end timestamps (no extra work is put on the stream).
@@ -692,7 +944,7 @@ template <int R>
 hipError_t launch_pass1(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, hipStream_t s)
 {
     return launch(p, kPass1, project_pass1<R>, (unsigned)p->items_proj.size(), kBlock, s,
-                  (const DevLayer*)p->d_layers, (const WorkItem*)p->d_items_proj, a, Rrt);
+                  (const WorkItem*)p->d_items_proj, a, Rrt);
 }
 
 int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, int64_t* layer_off, int32_t* kept_idx,
@@ -704,7 +956,9 @@ int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, int64_t* layer
     o.layer_off = layer_off;
     o.kept_idx = kept_idx;
     const hipError_t e = launch(p, kScan, scan_mask, (unsigned)p->layers.size(), kScanBlock, s,
-                                (const DevLayer*)p->d_layers, (int)p->layers.size(), (int)p->pack_align, mask, o);
+                                (const DevLayer*)p->d_layers, (int)p->layers.size(), (int)p->groups_total,
+                                (int)p->pack_align, mask, (const uint16_t*)p->d_group_layer,
+                                (const uint16_t*)p->d_chunk_layer, o);
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
@@ -732,54 +986,50 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     }
     hsadmm_plan* p = new (std::nothrow) hsadmm_plan();
     if (!p) return HSADMM_ERR_HIP;
+    std::vector<uint16_t> group_layer;
     try {
-    p->pack_align = pack_align_elems;
-    p->layers.assign(layers, layers + L);
-    p->arena_elems = prev_end;
-    int64_t gb = 0, cp = 0, cap = 0;
-    for (int32_t l = 0; l < L; ++l) {
-        const hsadmm_layer_t& x = layers[l];
-        DevLayer d{};
-        d.elem_off = x.elem_off;
-        d.c_out = x.c_out; d.c_in = x.c_in; d.khw = x.khw; d.mode = x.mode;
-        d.G = x.mode == HSADMM_MODE_CHANNEL ? x.c_in : x.c_out;
-        d.k = x.mode == HSADMM_MODE_NONE ? d.G : x.k;
-        d.group_base = (int32_t)gb;
-        d.row_len = x.c_in * x.khw;
-        d.vec = (d.row_len % 4) == 0 ? 1 : 0;
-        const int units = d.vec ? d.row_len / 4 : d.row_len;   // accesses per row
-        d.lpr = units >= kWave ? kWave : ceil_pow2(units);
-        d.n_rowblocks = (x.c_out + kChanRows - 1) / kChanRows;
-        d.colpart_off = cp;
-        if (x.mode == HSADMM_MODE_CHANNEL) cp += (int64_t)d.n_rowblocks * d.row_len;
-        gb += d.G;
-        cap += (int64_t)x.c_out * d.row_len;
-        cap = (cap + pack_align_elems - 1) / pack_align_elems * pack_align_elems;
-        p->dev_layers.push_back(d);
-        add_row_items(p->items_rows, l, d);
-        if (x.mode == HSADMM_MODE_CHANNEL) {
-            const int strip_cols = kWave * (d.vec ? 4 : 1);
-            const int nstrips = (d.row_len + strip_cols - 1) / strip_cols;
-            for (int r0 = 0; r0 < x.c_out; r0 += kChanRows) {
-                const int nr = (x.c_out - r0) < kChanRows ? (x.c_out - r0) : kChanRows;
-                for (int s = 0; s < nstrips; ++s) p->items_proj.push_back(WorkItem{l, r0, nr, s});
-            }
-        } else {
-            add_row_items(p->items_proj, l, d);
+        p->pack_align = pack_align_elems;
+        p->layers.assign(layers, layers + L);
+        p->arena_elems = prev_end;
+        int64_t gb = 0, cp = 0, cap = 0;
+        group_layer.clear();
+        for (int32_t l = 0; l < L; ++l) {
+            const hsadmm_layer_t& x = layers[l];
+            DevLayer d{};
+            d.elem_off = x.elem_off;
+            d.c_out = x.c_out; d.c_in = x.c_in; d.khw = x.khw; d.mode = x.mode;
+            d.G = x.mode == HSADMM_MODE_CHANNEL ? x.c_in : x.c_out;
+            d.k = x.mode == HSADMM_MODE_NONE ? d.G : x.k;
+            d.group_base = (int32_t)gb;
+            d.row_len = x.c_in * x.khw;
+            d.n_rowblocks = (x.c_out + kChanRows - 1) / kChanRows;
+            d.colpart_off = cp;
+            if (x.mode == HSADMM_MODE_CHANNEL) d.unit = (int64_t)x.c_out * x.khw;
+            else if (x.mode == HSADMM_MODE_FILTER) d.unit = d.row_len;
+            else d.unit = (int64_t)x.c_out * d.row_len;
+            if (x.mode == HSADMM_MODE_CHANNEL) cp += (int64_t)d.n_rowblocks * d.row_len;
+            gb += d.G;
+            cap += (int64_t)x.c_out * d.row_len;
+            cap = (cap + pack_align_elems - 1) / pack_align_elems * pack_align_elems;
+            add_row_items(p->items_rows, l, d, x.mode);
+            if (x.mode == HSADMM_MODE_CHANNEL) add_tile_items(p->items_proj, l, d);
+            else add_row_items(p->items_proj, l, d, x.mode);
+            p->dev_layers.push_back(d);
+            for (int32_t g = 0; g < d.G; ++g)
+                group_layer.push_back((uint16_t)(l | (x.mode == HSADMM_MODE_NONE ? 0x8000 : 0)));
         }
-    }
-    if (gb > INT32_MAX) { delete p; return HSADMM_ERR_UNSUPPORTED; }
-    p->groups_total = gb;
-    p->colpart_total = cp;
-    p->packed_capacity = cap;
-    size_t off = 0;
-    p->ws.key = off;        off = align_up(off + sizeof(double) * (size_t)gb, 256);
-    p->ws.colpart = off;    off = align_up(off + sizeof(double) * (size_t)(cp ? cp : 1), 256);
-    p->ws.pos = off;        off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
-    p->ws.cnt = off;        off = align_up(off + sizeof(int32_t) * (size_t)L, 256);
-    p->ws.layer_off = off;  off = align_up(off + sizeof(int64_t) * (size_t)(L + 1), 256);
-    p->ws.kept_idx = off;   off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
-    p->ws.total = off;
+        if (gb > INT32_MAX) { delete p; return HSADMM_ERR_UNSUPPORTED; }
+        p->groups_total = gb;
+        p->colpart_total = cp;
+        p->packed_capacity = cap;
+        size_t off = 0;
+        p->ws.key = off;        off = align_up(off + sizeof(double) * (size_t)gb, 256);
+        p->ws.colpart = off;    off = align_up(off + sizeof(double) * (size_t)(cp ? cp : 1), 256);
+        p->ws.pos = off;        off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
+        p->ws.cnt = off;        off = align_up(off + sizeof(int32_t) * (size_t)L, 256);
+        p->ws.layer_off = off;  off = align_up(off + sizeof(int64_t) * (size_t)(L + 1), 256);
+        p->ws.kept_idx = off;   off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
+        p->ws.total = off;
     } catch (...) {   // host allocation failure while building the tables
         delete p;
         return HSADMM_ERR_HIP;
@@ -789,9 +1039,30 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     const size_t bl = sizeof(DevLayer) * p->dev_layers.size();
     const size_t bp = sizeof(WorkItem) * p->items_proj.size();
     const size_t br = sizeof(WorkItem) * p->items_rows.size();
+    std::vector<uint16_t> chunk_layer;
+    try {
+        const size_t ng = group_layer.size();
+        chunk_layer.assign((ng + 15) / 16, 0xffff);
+        for (size_t c = 0; c + 1 <= chunk_layer.size(); ++c) {
+            if (16 * c + 15 >= ng) break;
+            const uint16_t first = group_layer[16 * c];
+            bool pure = (first & 0x8000) == 0;
+            for (size_t i = 1; i < 16 && pure; ++i) pure = group_layer[16 * c + i] == first;
+            if (pure) chunk_layer[c] = first;
+        }
+    } catch (...) {
+        delete p;
+        return HSADMM_ERR_HIP;
+    }
+    const size_t bg = sizeof(uint16_t) * group_layer.size();
+    const size_t bc = sizeof(uint16_t) * chunk_layer.size();
     bool ok = hipMalloc(&p->d_layers, bl) == hipSuccess;
     ok = ok && hipMalloc(&p->d_items_proj, bp) == hipSuccess;
     ok = ok && hipMalloc(&p->d_items_rows, br) == hipSuccess;
+    ok = ok && hipMalloc(&p->d_group_layer, bg) == hipSuccess;
+    ok = ok && hipMalloc(&p->d_chunk_layer, bc) == hipSuccess;
+    ok = ok && hipMemcpy(p->d_group_layer, group_layer.data(), bg, hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(p->d_chunk_layer, chunk_layer.data(), bc, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_layers, p->dev_layers.data(), bl, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_items_proj, p->items_proj.data(), bp, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_items_rows, p->items_rows.data(), br, hipMemcpyHostToDevice) == hipSuccess;
@@ -811,6 +1082,8 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_layers) (void)hipFree(p->d_layers);
     if (p->d_items_proj) (void)hipFree(p->d_items_proj);
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
+    if (p->d_group_layer) (void)hipFree(p->d_group_layer);
+    if (p->d_chunk_layer) (void)hipFree(p->d_chunk_layer);
     delete p;
 }
 
@@ -859,7 +1132,7 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
                (const DevLayer*)p->d_layers, a.key, (const double*)a.colpart, mask);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     e = launch(p, kFixup, project_fixup, (unsigned)p->items_proj.size(), kBlock, s,
-               (const DevLayer*)p->d_layers, (const WorkItem*)p->d_items_proj, (const uint8_t*)mask, U, Z);
+               (const WorkItem*)p->d_items_proj, (const uint8_t*)mask, U, Z);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     return HSADMM_OK;
 }
@@ -878,7 +1151,7 @@ int hsadmm_compact(const hsadmm_plan_t* p, const float* src, const uint8_t* mask
     const int rc = run_scan(p, mask, ws, layer_off, kept_idx, s);
     if (rc != HSADMM_OK) return rc;
     const hipError_t e = launch(p, kGather, compact_gather, (unsigned)p->items_rows.size(), kBlock, s,
-                                (const DevLayer*)p->d_layers, (const WorkItem*)p->d_items_rows, src,
+                                (const WorkItem*)p->d_items_rows, src,
                                 reinterpret_cast<const int32_t*>(ws + p->ws.pos),
                                 reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (const int64_t*)layer_off, packed);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
@@ -898,7 +1171,7 @@ int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* ma
     const int rc = run_scan(p, mask, ws, lo, reinterpret_cast<int32_t*>(ws + p->ws.kept_idx), s);
     if (rc != HSADMM_OK) return rc;
     const hipError_t e = launch(p, kScatter, expand_scatter, (unsigned)p->items_rows.size(), kBlock, s,
-                                (const DevLayer*)p->d_layers, (const WorkItem*)p->d_items_rows, packed,
+                                (const WorkItem*)p->d_items_rows, packed,
                                 reinterpret_cast<const int32_t*>(ws + p->ws.pos),
                                 reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (const int64_t*)lo, dst);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
