@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-verify", action="store_true", help="skip the one-shot oracle check of the outputs")
+    ap.add_argument("--sets", type=int, default=3,
+                    help="independent copies of every buffer the steps rotate over, so that no step finds "
+                         "its own data from the previous step in the caches")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -63,22 +66,31 @@ def main():
     table = wl.table()
     plan = pkg.Plan(table)
     n = wl.n_arena
-    dW = [torch.from_numpy(W[r]).to(dev) for r in range(wl.R)]
+    nsets = max(1, args.sets)
+
+    class BufferSet:
+        def __init__(self):
+            self.W = [torch.from_numpy(W[r]).to(dev) for r in range(wl.R)]
+            self.U = torch.from_numpy(U).to(dev)
+            self.Z = torch.zeros(n, dtype=torch.float32, device=dev)
+            self.mask = torch.zeros(plan.groups_total, dtype=torch.uint8, device=dev)
+            self.ws = torch.zeros(plan.workspace_bytes, dtype=torch.uint8, device=dev)
+            self.packed = torch.zeros(plan.packed_capacity_elems, dtype=torch.float32, device=dev)
+            self.off = torch.zeros(plan.n_layers + 1, dtype=torch.int64, device=dev)
+            self.kept = torch.zeros(plan.groups_total, dtype=torch.int32, device=dev)
+            self.dst = torch.zeros(n, dtype=torch.float32, device=dev)
+
+    sets = [BufferSet() for _ in range(nsets)]
     dU0 = torch.from_numpy(U).to(dev)
-    dU = dU0.clone()
-    dZ = torch.zeros(n, dtype=torch.float32, device=dev)
-    dmask = torch.zeros(plan.groups_total, dtype=torch.uint8, device=dev)
-    ws = torch.zeros(plan.workspace_bytes, dtype=torch.uint8, device=dev)
-    dpacked = torch.zeros(plan.packed_capacity_elems, dtype=torch.float32, device=dev)
-    doff = torch.zeros(plan.n_layers + 1, dtype=torch.int64, device=dev)
-    dkept = torch.zeros(plan.groups_total, dtype=torch.int32, device=dev)
-    ddst = torch.zeros(n, dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
+    counter = [0]
 
     def step():
-        pkg.hsadmm_project(plan, dW, dU, dZ, None, dmask, None, ws, stream=stream)
-        pkg.hsadmm_compact(plan, dZ, dmask, dpacked, doff, dkept, ws, stream=stream)
-        pkg.hsadmm_expand(plan, dpacked, dmask, ddst, ws, stream=stream)
+        b = sets[counter[0] % nsets]
+        counter[0] += 1
+        pkg.hsadmm_project(plan, b.W, b.U, b.Z, None, b.mask, None, b.ws, stream=stream)
+        pkg.hsadmm_compact(plan, b.Z, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
+        pkg.hsadmm_expand(plan, b.packed, b.mask, b.dst, b.ws, stream=stream)
 
     # ---- one-shot correctness check against the oracle (outside every timed region)
     verify = None
@@ -89,18 +101,20 @@ def main():
         refc = oracle.compact(table, ref["Z"], ref["mask"])
         step()
         torch.cuda.synchronize()
-        ok_mask = bool(np.array_equal(dmask.cpu().numpy(), ref["mask"]))
-        ok_z = bool(np.array_equal(dZ.cpu().numpy().view(np.uint32), ref["Z"].view(np.uint32)))
-        ok_u = bool(np.array_equal(dU.cpu().numpy().view(np.uint32), ref["U"].view(np.uint32)))
+        b0 = sets[0]
+        ok_mask = bool(np.array_equal(b0.mask.cpu().numpy(), ref["mask"]))
+        ok_z = bool(np.array_equal(b0.Z.cpu().numpy().view(np.uint32), ref["Z"].view(np.uint32)))
+        ok_u = bool(np.array_equal(b0.U.cpu().numpy().view(np.uint32), ref["U"].view(np.uint32)))
         npk = int(refc["layer_off"][-1])
-        ok_p = bool(np.array_equal(dpacked.cpu().numpy()[:npk].view(np.uint32), refc["packed"].view(np.uint32)))
-        ok_o = bool(np.array_equal(doff.cpu().numpy(), refc["layer_off"]))
-        ok_d = bool(np.array_equal(ddst.cpu().numpy().view(np.uint32), ref["Z"].view(np.uint32)))
+        ok_p = bool(np.array_equal(b0.packed.cpu().numpy()[:npk].view(np.uint32), refc["packed"].view(np.uint32)))
+        ok_o = bool(np.array_equal(b0.off.cpu().numpy(), refc["layer_off"]))
+        ok_d = bool(np.array_equal(b0.dst.cpu().numpy().view(np.uint32), ref["Z"].view(np.uint32)))
         verify = {"mask": ok_mask, "Z": ok_z, "U": ok_u, "packed": ok_p, "layer_off": ok_o, "expand": ok_d}
         if not all(verify.values()):
             print("bench.py: outputs differ from the oracle: %s" % verify, file=sys.stderr)
             sys.exit(4)
-        dU.copy_(dU0)
+        b0.U.copy_(dU0)
+        counter[0] = 0
 
     bytes_ = wl.algorithmic_bytes()
 
@@ -160,7 +174,7 @@ def main():
             pass
 
     # ---- context: a plain device copy of the same size class (practical streaming ceiling)
-    a_src, a_dst = dW[0], dZ
+    a_src, a_dst = sets[0].W[0], sets[0].Z
     for _ in range(5):
         a_dst.copy_(a_src)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -208,6 +222,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (wl.name, wl.description), "layers": len(wl.layers),
                    "params": wl.n_total, "replicas": wl.R, "kept_params": nk, "seed": wl.seed,
+                   "buffer_sets_rotated": nsets,
                    "algorithmic_bytes_per_step": bytes_["step"]},
         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
         "params_per_s": round(params_per_s, 1),

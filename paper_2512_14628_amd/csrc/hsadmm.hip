@@ -39,8 +39,8 @@ constexpr int kBlock = 256;                 // streaming kernels: 4 waves
 constexpr int kWaves = kBlock / kWave;
 constexpr int kScanBlock = 1024;            // select_topk and scan_mask
 constexpr int kScanWaves = kScanBlock / kWave;
-constexpr int kTileElems = 4096;            // target elements per work item
-constexpr int kWideRow = 2048;              // rows at least this long are shared by the whole workgroup
+constexpr int kTileElems = 2048;                // target elements per work item
+constexpr int kWideRow = 2048;                  // rows at least this long are shared by the whole workgroup
 constexpr int kChanRows = 32;               // CHANNEL tiles: rows per row block
 constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
 constexpr int kVersion = 103;
