@@ -165,13 +165,14 @@ def main():
                 "traffic": None,
                 "algorithmic_bytes_per_launch": kernel_bytes.get(dom, 0),
                 "avg_launch_us": round(dom_us, 2) if dom_us else None}
-    traffic_file = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
+    # HBM-side bytes per launch of that kernel, from the committed rocprofv3 --pmc summary (two counter runs)
+    traffic_file = os.path.join(ROOT, "profiles", "%s_step_hbm_traffic.md" % args.workload)
     if os.path.exists(traffic_file):
-        try:
-            with open(traffic_file) as f:
-                roofline["traffic"] = json.load(f).get(dom)
-        except Exception:
-            pass
+        with open(traffic_file) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == dom:
+                    roofline["traffic"] = int(parts[2])
 
     # ---- context: a plain device copy of the same size class (practical streaming ceiling)
     a_src, a_dst = sets[0].W[0], sets[0].Z

@@ -98,6 +98,22 @@ __device__ __forceinline__ void st1(float* p, float v) { __builtin_nontemporal_s
 __device__ __forceinline__ v4f ld4u(const float* p) { v4f v; __builtin_memcpy(&v, p, 16); return v; }
 __device__ __forceinline__ void st4u(float* p, v4f v) { __builtin_memcpy(p, &v, 16); }
 
+// j / khw for 0 <= j < 2^22 without an integer division: a float estimate corrected by one step.
+struct DivKhw {
+    int khw;
+    float rcp;
+    __device__ __forceinline__ explicit DivKhw(int k) : khw(k), rcp(1.0f / (float)k) {}
+    __device__ __forceinline__ int operator()(int j) const
+    {
+        if (khw == 1) return j;
+        if (j >= (1 << 22)) return j / khw;
+        int q = (int)((float)j * rcp);
+        if (q * khw > j) --q;
+        else if ((q + 1) * khw <= j) ++q;
+        return q;
+    }
+};
+
 __device__ __forceinline__ double wave_xor_sum(double a, int width)
 {
     // butterfly over `width` adjacent lanes; every lane ends with the same bits
@@ -512,8 +528,26 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
         const double* cp = colpart + L.colpart_off;
         for (int g = tid; g < G; g += kScanBlock) {
             double acc = 0.0;
-            for (int rb = 0; rb < L.n_rowblocks; ++rb)
-                for (int t = 0; t < L.khw; ++t) acc += cp[(int64_t)rb * L.row_len + g * L.khw + t];
+            const double* cg = cp + (int64_t)g * L.khw;
+            int rb = 0;
+            if (L.khw <= 9) {
+                // same order of additions as the plain loop below, with four row blocks' loads in flight
+                for (; rb + 4 <= L.n_rowblocks; rb += 4) {
+                    double x[4][9];
+#pragma unroll
+                    for (int b4 = 0; b4 < 4; ++b4)
+#pragma unroll
+                        for (int t = 0; t < 9; ++t)
+                            x[b4][t] = (t < L.khw) ? cg[(int64_t)(rb + b4) * L.row_len + t] : 0.0;
+#pragma unroll
+                    for (int b4 = 0; b4 < 4; ++b4)
+#pragma unroll
+                        for (int t = 0; t < 9; ++t)
+                            if (t < L.khw) acc += x[b4][t];
+                }
+            }
+            for (; rb < L.n_rowblocks; ++rb)
+                for (int t = 0; t < L.khw; ++t) acc += cg[(int64_t)rb * L.row_len + t];
             kl[g] = acc;
         }
         __syncthreads();
@@ -576,18 +610,21 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
             any = any || pr[i];
         }
         if (!any) return;
+        const bool all = pr[0] && pr[1] && pr[2] && pr[3];
         for (int rr = wave; rr < it.nr; rr += kWaves) {
             const int64_t e = it.base + (int64_t)rr * row_len + col;
             if (vec) {
+                // a fully pruned quad moves as 128 bits; a partly pruned one stores its pruned
+                // elements one by one (merging through a read of U costs more traffic than it saves)
                 const v4f z = ld4(Z + e);
-                if (pr[0] && pr[1] && pr[2] && pr[3]) {
+                if (all) {
                     st4(U + e, z);
                     st4(Z + e, zero4);
                 } else {
-                    if (pr[0]) { U[e + 0] = z.x; Z[e + 0] = 0.f; }
-                    if (pr[1]) { U[e + 1] = z.y; Z[e + 1] = 0.f; }
-                    if (pr[2]) { U[e + 2] = z.z; Z[e + 2] = 0.f; }
-                    if (pr[3]) { U[e + 3] = z.w; Z[e + 3] = 0.f; }
+                    if (pr[0]) { st1(U + e + 0, z.x); st1(Z + e + 0, 0.f); }
+                    if (pr[1]) { st1(U + e + 1, z.y); st1(Z + e + 1, 0.f); }
+                    if (pr[2]) { st1(U + e + 2, z.z); st1(Z + e + 2, 0.f); }
+                    if (pr[3]) { st1(U + e + 3, z.w); st1(Z + e + 3, 0.f); }
                 }
             } else {
                 U[e] = Z[e];
@@ -601,7 +638,7 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
 
 struct ScanOut {
     int32_t* pos;        // groups_total: rank of a kept group inside its layer, -1 if pruned
-    int32_t* cnt;        // L: kept groups per layer
+    int32_t* cnt;        // 2L: kept groups per layer, then the start of every layer's run in kept_idx
     int64_t* layer_off;  // L+1
     int32_t* kept_idx;   // groups_total
 };
@@ -649,19 +686,23 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
         unsigned int cl = 0xffffu;
         int kept = 0;
         bool slow = false;
+        unsigned int mw[4] = {0u, 0u, 0u, 0u};     // the chunk's 16 mask bytes
         if (c < nchunks) {
             cl = chunk_layer[c];
-            if (cl != 0xffffu) {
-                if (aligned16) {
-                    const uint4 m = reinterpret_cast<const uint4*>(mask)[c];
-                    kept = nonzero_bytes(m.x) + nonzero_bytes(m.y) + nonzero_bytes(m.z) + nonzero_bytes(m.w);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) kept += mask[16 * c + i] != 0 ? 1 : 0;
-                }
+            const bool full = 16 * c + 15 < n_groups;
+            if (full && aligned16) {
+                const uint4 m = reinterpret_cast<const uint4*>(mask)[c];
+                mw[0] = m.x; mw[1] = m.y; mw[2] = m.z; mw[3] = m.w;
             } else {
-                slow = true;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int g = 16 * c + i;
+                    const unsigned int byte = (g < n_groups) ? mask[g] : 0u;
+                    mw[i >> 2] |= byte << (8 * (i & 3));
+                }
             }
+            if (cl != 0xffffu) kept = nonzero_bytes(mw[0]) + nonzero_bytes(mw[1]) + nonzero_bytes(mw[2]) + nonzero_bytes(mw[3]);
+            else slow = true;
         }
         const unsigned int cl0 = __shfl(cl, 0, kWave);
         if (cl0 != 0xffffu && __all((c >= nchunks) || cl == cl0)) {
@@ -670,12 +711,34 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
         } else {
             if (cl != 0xffffu && kept) atomicAdd(&cnt[cl], kept);
             if (slow) {
-                for (int i = 0; i < 16; ++i) {
-                    const int g = 16 * c + i;
-                    if (g >= n_groups) break;
-                    const unsigned int gl = group_layer[g];
-                    if ((gl & 0x8000u) != 0 || mask[g] != 0) atomicAdd(&cnt[gl & 0x7fffu], 1);
+                // mixed chunk: the 16 layer ids come with two 128-bit loads (a partial last chunk one by one);
+                // runs of one layer are counted in a register
+                unsigned int gl[16];
+                if (16 * c + 15 < n_groups) {
+                    const uint4 a0 = reinterpret_cast<const uint4*>(group_layer)[2 * c];
+                    const uint4 a1 = reinterpret_cast<const uint4*>(group_layer)[2 * c + 1];
+                    const unsigned int w8[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) gl[i] = (w8[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) gl[i] = (16 * c + i < n_groups) ? group_layer[16 * c + i] : 0xffffu;
                 }
+                int run_layer = -1, run = 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    if (gl[i] != 0xffffu) {
+                        const int lay = (int)(gl[i] & 0x7fffu);
+                        const unsigned int byte = (mw[i >> 2] >> (8 * (i & 3))) & 0xffu;
+                        if (lay != run_layer) {
+                            if (run) atomicAdd(&cnt[run_layer], run);
+                            run_layer = lay;
+                            run = 0;
+                        }
+                        run += ((gl[i] & 0x8000u) != 0 || byte != 0) ? 1 : 0;
+                    }
+                }
+                if (run) atomicAdd(&cnt[run_layer], run);
             }
         }
     }
@@ -705,6 +768,7 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
     if (tid == 0) {
         o.layer_off[l] = pos;
         o.cnt[l] = cnt[l];
+        o.cnt[nL + l] = kb;
         if (l == nL - 1) {
             long long s = (L.mode == HSADMM_MODE_NONE) ? L.unit : (long long)cnt[l] * L.unit;
             s = (s + pack_align - 1) / pack_align * pack_align;
@@ -732,6 +796,7 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
                                                          const float* __restrict__ src,
                                                          const int32_t* __restrict__ pos,
                                                          const int32_t* __restrict__ cnt,
+                                                         const int32_t* __restrict__ kept_idx, int n_layers,
                                                          const int64_t* __restrict__ layer_off,
                                                          float* __restrict__ packed)
 {
@@ -758,18 +823,40 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
             }
         }
     } else {
-        // packed row o holds the kept channels' khw-blocks in ascending channel order; it.g0 is the
-        // layer's group base and it.col0 the index of the item's first row inside the layer
+        // packed row o holds the kept channels' khw-blocks in ascending channel order: packed column
+        // j = q*khw + t comes from source column kept[q]*khw + t.  it.col0 is the index of the item's
+        // first row inside the layer.  A wave takes a row; a lane gathers 4 adjacent packed columns
+        // and stores them with one 128-bit access.
         const int kc = cnt[it.layer];
         const int khw = it.khw;
         const int out_len = kc * khw;
+        const int32_t* kl = kept_idx + cnt[n_layers + it.layer];
+        const DivKhw div(khw);
+        const int quads = out_len >> 2;
         for (int rr = wave; rr < it.nr; rr += kWaves) {
             const float* s = src + it.base + (int64_t)rr * row_len;
             float* d = out + (int64_t)(it.col0 + rr) * out_len;
-            for (int c = lane; c < row_len; c += kWave) {
-                const int ch = c / khw;
-                const int p = pos[it.g0 + ch];
-                if (p >= 0) d[p * khw + (c - ch * khw)] = s[c];
+            for (int j4 = lane; j4 < quads; j4 += kWave) {
+                const int j = j4 << 2;
+                v4f v;
+                if (khw == 1) {
+                    int4 c;
+                    __builtin_memcpy(&c, kl + j, 16);
+                    v.x = ld1(s + c.x); v.y = ld1(s + c.y); v.z = ld1(s + c.z); v.w = ld1(s + c.w);
+                } else {
+                    float t4[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int q = div(j + i);
+                        t4[i] = ld1(s + kl[q] * khw + (j + i - q * khw));
+                    }
+                    v.x = t4[0]; v.y = t4[1]; v.z = t4[2]; v.w = t4[3];
+                }
+                st4u(d + j, v);
+            }
+            for (int j = (quads << 2) + lane; j < out_len; j += kWave) {
+                const int q = div(j);
+                d[j] = s[kl[q] * khw + (j - q * khw)];
             }
         }
     }
@@ -809,15 +896,42 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
             }
         }
     } else {
+        // a wave takes a row of dst; a lane fills 4 adjacent columns (kept ones from the packed row,
+        // the others +0) and stores them with one 128-bit access
         const int kc = cnt[it.layer];
         const int khw = it.khw;
         const int in_len = kc * khw;
+        const DivKhw div(khw);
+        const int32_t* pl = pos + it.g0;
+        const int quads = item_vec(it) ? (row_len >> 2) : 0;
         for (int rr = wave; rr < it.nr; rr += kWaves) {
             float* d = dst + it.base + (int64_t)rr * row_len;
             const float* s = in + (int64_t)(it.col0 + rr) * in_len;
-            for (int c = lane; c < row_len; c += kWave) {
-                const int ch = c / khw;
-                const int p = pos[it.g0 + ch];
+            for (int c4 = lane; c4 < quads; c4 += kWave) {
+                const int c = c4 << 2;
+                float t4[4];
+                if (khw == 1) {
+                    int4 p;
+                    __builtin_memcpy(&p, pl + c, 16);
+                    t4[0] = p.x >= 0 ? s[p.x] : 0.f;
+                    t4[1] = p.y >= 0 ? s[p.y] : 0.f;
+                    t4[2] = p.z >= 0 ? s[p.z] : 0.f;
+                    t4[3] = p.w >= 0 ? s[p.w] : 0.f;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int ch = div(c + i);
+                        const int p = pl[ch];
+                        t4[i] = p >= 0 ? s[p * khw + (c + i - ch * khw)] : 0.f;
+                    }
+                }
+                v4f v;
+                v.x = t4[0]; v.y = t4[1]; v.z = t4[2]; v.w = t4[3];
+                st4(d + c, v);
+            }
+            for (int c = (quads << 2) + lane; c < row_len; c += kWave) {
+                const int ch = div(c);
+                const int p = pl[ch];
                 d[c] = (p >= 0) ? s[p * khw + (c - ch * khw)] : 0.f;
             }
         }
@@ -1026,7 +1140,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->ws.key = off;        off = align_up(off + sizeof(double) * (size_t)gb, 256);
         p->ws.colpart = off;    off = align_up(off + sizeof(double) * (size_t)(cp ? cp : 1), 256);
         p->ws.pos = off;        off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
-        p->ws.cnt = off;        off = align_up(off + sizeof(int32_t) * (size_t)L, 256);
+        p->ws.cnt = off;        off = align_up(off + sizeof(int32_t) * (size_t)L * 2, 256);
         p->ws.layer_off = off;  off = align_up(off + sizeof(int64_t) * (size_t)(L + 1), 256);
         p->ws.kept_idx = off;   off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
         p->ws.total = off;
@@ -1153,7 +1267,8 @@ int hsadmm_compact(const hsadmm_plan_t* p, const float* src, const uint8_t* mask
     const hipError_t e = launch(p, kGather, compact_gather, (unsigned)p->items_rows.size(), kBlock, s,
                                 (const WorkItem*)p->d_items_rows, src,
                                 reinterpret_cast<const int32_t*>(ws + p->ws.pos),
-                                reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (const int64_t*)layer_off, packed);
+                                reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (const int32_t*)kept_idx,
+                                (int)p->layers.size(), (const int64_t*)layer_off, packed);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     return HSADMM_OK;
 }
