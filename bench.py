@@ -37,6 +37,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-verify", action="store_true", help="skip the one-shot oracle check of the outputs")
+    ap.add_argument("--expand-rescan", action="store_true",
+                    help="hsadmm_expand recomputes positions from the mask instead of reusing hsadmm_compact's")
     ap.add_argument("--sets", type=int, default=3,
                     help="independent copies of every buffer the steps rotate over, so that no step finds "
                          "its own data from the previous step in the caches")
@@ -90,7 +92,9 @@ def main():
         counter[0] += 1
         pkg.hsadmm_project(plan, b.W, b.U, b.Z, None, b.mask, None, b.ws, stream=stream)
         pkg.hsadmm_compact(plan, b.Z, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
-        pkg.hsadmm_expand(plan, b.packed, b.mask, b.dst, b.ws, stream=stream)
+        # expansion reuses the index mappings the compaction just cached in the workspace (mask = NULL), as
+        # the paper's recovery step does (Section 4.4.3); --expand-rescan derives them from the mask again
+        pkg.hsadmm_expand(plan, b.packed, b.mask if args.expand_rescan else None, b.dst, b.ws, stream=stream)
 
     # ---- one-shot correctness check against the oracle (outside every timed region)
     verify = None
@@ -223,7 +227,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (wl.name, wl.description), "layers": len(wl.layers),
                    "params": wl.n_total, "replicas": wl.R, "kept_params": nk, "seed": wl.seed,
-                   "buffer_sets_rotated": nsets,
+                   "buffer_sets_rotated": nsets, "expand_reuses_cached_index_mappings": not args.expand_rescan,
                    "algorithmic_bytes_per_step": bytes_["step"]},
         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
         "params_per_s": round(params_per_s, 1),

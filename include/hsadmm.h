@@ -160,7 +160,11 @@ int hsadmm_compact(const hsadmm_plan_t* plan, const float* src, const uint8_t* m
  * `packed` are recomputed from the mask as in hsadmm_compact.
  *
  *   packed     device, read only, as produced by hsadmm_compact for this mask
- *   mask       device, groups_total bytes
+ *   mask       device, groups_total bytes; or NULL: reuse the index mappings
+ *              that the most recent hsadmm_compact call on this plan left in
+ *              this same workspace (the cached K_out / K_in of Section 4.4.3).
+ *              With NULL the caller guarantees that no other call has used
+ *              the workspace since that hsadmm_compact, on this stream.
  *   dst        device, out, full-layout arena, 16-byte aligned
  * Errors: INVALID_ARGUMENT, WORKSPACE, HIP.
  */

@@ -639,7 +639,8 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
 struct ScanOut {
     int32_t* pos;        // groups_total: rank of a kept group inside its layer, -1 if pruned
     int32_t* cnt;        // 2L: kept groups per layer, then the start of every layer's run in kept_idx
-    int64_t* layer_off;  // L+1
+    int64_t* layer_off;  // L+1, in the workspace (kept there for a later hsadmm_expand without a mask)
+    int64_t* layer_off_out;  // L+1, the caller's copy; may be null
     int32_t* kept_idx;   // groups_total
 };
 
@@ -767,12 +768,14 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
     for (int w = 0; w < kScanWaves; ++w) { pos += wsum[w]; kb += wkept[w]; }
     if (tid == 0) {
         o.layer_off[l] = pos;
+        if (o.layer_off_out) o.layer_off_out[l] = pos;
         o.cnt[l] = cnt[l];
         o.cnt[nL + l] = kb;
         if (l == nL - 1) {
             long long s = (L.mode == HSADMM_MODE_NONE) ? L.unit : (long long)cnt[l] * L.unit;
             s = (s + pack_align - 1) / pack_align * pack_align;
             o.layer_off[nL] = pos + s;
+            if (o.layer_off_out) o.layer_off_out[nL] = pos + s;
         }
     }
     const int G = L.G;
@@ -1061,13 +1064,14 @@ hipError_t launch_pass1(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, hip
                   (const WorkItem*)p->d_items_proj, a, Rrt);
 }
 
-int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, int64_t* layer_off, int32_t* kept_idx,
+int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, int64_t* layer_off_out, int32_t* kept_idx,
              hipStream_t s)
 {
     ScanOut o;
     o.pos = reinterpret_cast<int32_t*>(ws + p->ws.pos);
     o.cnt = reinterpret_cast<int32_t*>(ws + p->ws.cnt);
-    o.layer_off = layer_off;
+    o.layer_off = reinterpret_cast<int64_t*>(ws + p->ws.layer_off);
+    o.layer_off_out = layer_off_out;
     o.kept_idx = kept_idx;
     const hipError_t e = launch(p, kScan, scan_mask, (unsigned)p->layers.size(), kScanBlock, s,
                                 (const DevLayer*)p->d_layers, (int)p->layers.size(), (int)p->groups_total,
@@ -1268,7 +1272,7 @@ int hsadmm_compact(const hsadmm_plan_t* p, const float* src, const uint8_t* mask
                                 (const WorkItem*)p->d_items_rows, src,
                                 reinterpret_cast<const int32_t*>(ws + p->ws.pos),
                                 reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (const int32_t*)kept_idx,
-                                (int)p->layers.size(), (const int64_t*)layer_off, packed);
+                                (int)p->layers.size(), reinterpret_cast<const int64_t*>(ws + p->ws.layer_off), packed);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     return HSADMM_OK;
 }
@@ -1276,19 +1280,21 @@ int hsadmm_compact(const hsadmm_plan_t* p, const float* src, const uint8_t* mask
 int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* mask, float* dst,
                   void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    if (!p || !packed || !mask || !dst || !workspace) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!p || !packed || !dst || !workspace) return HSADMM_ERR_INVALID_ARGUMENT;
     if (!is_aligned(packed, 16) || !is_aligned(dst, 16) || !is_aligned(workspace, 256))
         return HSADMM_ERR_INVALID_ARGUMENT;
     if (workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
-    int64_t* lo = reinterpret_cast<int64_t*>(ws + p->ws.layer_off);
-    const int rc = run_scan(p, mask, ws, lo, reinterpret_cast<int32_t*>(ws + p->ws.kept_idx), s);
-    if (rc != HSADMM_OK) return rc;
+    const int64_t* lo = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
+    if (mask) {
+        const int rc = run_scan(p, mask, ws, nullptr, reinterpret_cast<int32_t*>(ws + p->ws.kept_idx), s);
+        if (rc != HSADMM_OK) return rc;
+    }   // else: the positions and offsets the last hsadmm_compact left in this workspace are used
     const hipError_t e = launch(p, kScatter, expand_scatter, (unsigned)p->items_rows.size(), kBlock, s,
                                 (const WorkItem*)p->d_items_rows, packed,
                                 reinterpret_cast<const int32_t*>(ws + p->ws.pos),
-                                reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (const int64_t*)lo, dst);
+                                reinterpret_cast<const int32_t*>(ws + p->ws.cnt), lo, dst);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     return HSADMM_OK;
 }

@@ -33,8 +33,10 @@ class GpuRun:
         pkg.hsadmm_compact(self.plan, self.dZ if src is None else src, self.dmask if mask is None else mask,
                            self.dpacked, self.doff, self.dkept, self.ws)
 
-    def expand(self, mask=None):
-        pkg.hsadmm_expand(self.plan, self.dpacked, self.dmask if mask is None else mask, self.ddst, self.ws)
+    def expand(self, mask=None, cached=False):
+        """cached=True passes a NULL mask: reuse the index mappings the last compact left in the workspace."""
+        m = None if cached else (self.dmask if mask is None else mask)
+        pkg.hsadmm_expand(self.plan, self.dpacked, m, self.ddst, self.ws)
 
     def step(self):
         self.project()

@@ -173,6 +173,28 @@ def test_compact_and_expand_with_a_foreign_mask_and_source():
     run.close()
 
 
+def test_expand_with_cached_index_mappings_equals_expand_with_mask():
+    """hsadmm_expand(mask=NULL) reuses what hsadmm_compact left in the workspace (Section 4.4.3's cached
+    K_out / K_in); an hsadmm_project in between does not disturb it."""
+    from tests.gpu_harness import GpuRun, bits
+    for name in ("resnet18", "resnet152"):
+        wl = wk.make_workload(name)
+        W, U = wk.generate(wl, threads=8)
+        run = GpuRun(wl, W, U)
+        run.project()
+        run.compact()
+        run.expand()
+        a = run.outputs()["dst"].copy()
+        run.ddst.fill_(float("nan"))
+        run.project()                     # U moves on, Z and mask are recomputed; the cached mappings stay
+        run.expand(cached=True)
+        b = run.outputs()["dst"]
+        for l in wl.layers:
+            sl = slice(l.elem_off, l.elem_off + l.n)
+            assert np.array_equal(bits(a[sl]), bits(b[sl])), l.name
+        run.close()
+
+
 def test_repeated_steps_follow_the_oracle():
     """Three outer iterations with U carried over (in place on the GPU) and fresh replicas each time."""
     from tests.gpu_harness import GpuRun
