@@ -270,3 +270,42 @@ def test_mask_pointer_need_not_be_aligned():
         assert np.array_equal(bits(a["packed"][:n]), bits(b["packed"][:n]))
         assert np.array_equal(bits(a["dst"]), bits(b["dst"]))
     run.close()
+
+
+@pytest.mark.parametrize("R", [1, 3, 4, 5])
+def test_outer_iterations_with_changing_supports(R):
+    """Several outer iterations with U carried over in place and replicas that change between iterations, so
+    that pruned groups (whose dual is by then their whole accumulated candidate) come back and kept groups
+    drop out.  Every iteration must match the oracle bit for bit."""
+    from tests.gpu_harness import GpuRun
+    shapes = [(96, 16, 1, wk.MODE_FILTER, 40), (80, 64, 9, wk.MODE_FILTER, 30), (40, 256, 9, wk.MODE_FILTER, 16),
+              (24, 512, 9, wk.MODE_FILTER, 9), (64, 3, 49, wk.MODE_FILTER, 20), (96, 128, 1, wk.MODE_CHANNEL, 50),
+              (10, 128, 1, wk.MODE_NONE, 10)]
+    wl = wk.custom_workload(shapes, R=R, seed=1, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    U[:] = 0                                    # Algorithm 1 starts from u = 0
+    run = GpuRun(wl, W, U)
+    t = wl.table()
+    Uref = U.copy()
+    n_repaired = 0
+    prev_mask = None
+    for it, seed in enumerate([1, 1, 2, 2, 2, 3, 1]):
+        wl.seed = seed
+        Wn, _ = wk.generate(wl)
+        for r in range(wl.R):
+            run.dW[r].copy_(torch.from_numpy(Wn[r]))
+        ref = oracle.project(t, Wn, Uref)
+        run.step()
+        got = run.outputs()
+        assert np.array_equal(got["mask"], ref["mask"]), "iteration %d" % it
+        assert np.array_equal(got["Z"].view(np.uint32), ref["Z"].view(np.uint32)), "iteration %d" % it
+        assert np.array_equal(got["U"].view(np.uint32), ref["U"].view(np.uint32)), "iteration %d" % it
+        for l in wl.layers:
+            sl = slice(l.elem_off, l.elem_off + l.n)
+            assert np.array_equal(got["dst"][sl].view(np.uint32), ref["Z"][sl].view(np.uint32))
+        if prev_mask is not None:
+            n_repaired += int(np.sum((prev_mask == 0) & (ref["mask"] == 1)))
+        prev_mask = ref["mask"]
+        Uref = ref["U"]
+    assert n_repaired > 0      # the inputs did make pruned groups come back
+    run.close()
