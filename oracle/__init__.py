@@ -58,6 +58,11 @@ def _load():
     lib.oracle_expand.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p, ctypes.c_int32,
                                   f32p, u8p, f32p]
     lib.oracle_expand.restype = ctypes.c_int
+    lib.oracle_project_frozen.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p,
+                                          ctypes.POINTER(f32p), ctypes.c_int32, f32p, f32p, f32p, u8p]
+    lib.oracle_project_frozen.restype = ctypes.c_int
+    lib.oracle_mask_or.argtypes = [ctypes.c_int64, ctypes.POINTER(u8p), ctypes.c_int32, u8p]
+    lib.oracle_mask_or.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -185,3 +190,45 @@ def expand(table, packed, mask, n_arena: int, pack_align: int = 1):
     if rc != 0:
         raise ValueError("oracle_expand failed with code %d" % rc)
     return dst
+
+
+def project_frozen(table, W, U, mask, want_wbar: bool = False):
+    """Frozen-mask branch: Z = (Wbar + U) under a given mask, dual update.  Returns dict(U, Z, Wbar or None)."""
+    global last_call_seconds
+    lib = _load()
+    t = _cols(table)
+    L = len(t["c_out"])
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    R, n_arena = W.shape
+    U_new = np.array(U, dtype=np.float32, copy=True, order="C")
+    Z = _poisoned_arena(t, n_arena)
+    Wbar = _poisoned_arena(t, n_arena) if want_wbar else None
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    assert mask.shape == (groups_total(t),)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    ptrs = (f32p * R)(*[_p(W[r], ctypes.c_float) for r in range(R)])
+    _t0 = time.perf_counter()
+    rc = lib.oracle_project_frozen(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                                   _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
+                                   _p(t["mode"], ctypes.c_int32), ptrs, R, _p(U_new, ctypes.c_float),
+                                   _p(Z, ctypes.c_float), _p(Wbar, ctypes.c_float) if want_wbar else None,
+                                   _p(mask, ctypes.c_uint8))
+    last_call_seconds = time.perf_counter() - _t0
+    if rc != 0:
+        raise ValueError("oracle_project_frozen failed with code %d" % rc)
+    return {"U": U_new, "Z": Z, "Wbar": Wbar}
+
+
+def mask_or(masks):
+    """Eq. (14): union of M masks (list of uint8 arrays of equal length)."""
+    lib = _load()
+    ms = [np.ascontiguousarray(m, dtype=np.uint8) for m in masks]
+    n = ms[0].size
+    assert all(m.shape == (n,) for m in ms)
+    out = np.full(n, 255, dtype=np.uint8)
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    ptrs = (u8p * len(ms))(*[_p(m, ctypes.c_uint8) for m in ms])
+    rc = lib.oracle_mask_or(n, ptrs, len(ms), _p(out, ctypes.c_uint8))
+    if rc != 0:
+        raise ValueError("oracle_mask_or failed with code %d" % rc)
+    return out

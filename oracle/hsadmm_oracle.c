@@ -267,3 +267,66 @@ int oracle_expand(int32_t L, const int64_t *elem_off, const int32_t *c_out, cons
     }
     return 0;
 }
+
+/*
+ * Retraining branch of Algorithm 1, Phase 3 (Section 4.5, "Mask Freezing and Retraining Phase"): once the
+ * masks are frozen the projection is replaced by the element-wise application of the cached mask,
+ *     z = z~ (.) m,
+ * with the same candidate z~ = Wbar + U (steps (a), (b)) and the same dual update (d) as oracle_project.
+ * mask: in, nonzero = kept, any number of kept groups per layer (a union of node masks keeps more than k);
+ * groups of an unconstrained layer are kept whatever their mask bytes say.  Entries of a masked-out
+ * group are exactly +0 (as the projection writes them), whatever the sign of the candidate.
+ * Returns 0, -1 on a bad argument, -2 on a non-finite candidate.
+ */
+int oracle_project_frozen(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                          const int32_t *khw, const int32_t *mode,
+                          const float *const *W, int32_t R, float *U, float *Z, float *Wbar,
+                          const uint8_t *mask)
+{
+    if (L < 1 || R < 1 || !W || !U || !Z || !mask) return -1;
+    const float inv_R = 1.0f / (float)R;
+    int64_t gbase = 0;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
+        if (co < 1 || ci < 1 || s < 1) return -1;
+        const int64_t n = co * ci * s;
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
+        const int64_t off = elem_off[l];
+        const uint8_t *ml = mask + gbase;
+        int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+        for (int64_t e = 0; e < n; ++e) {
+            float acc = W[0][off + e];
+            for (int32_t r = 1; r < R; ++r) acc = acc + W[r][off + e];
+            const float wbar = acc * inv_R;
+            const float v = wbar + U[off + e];
+            if (!isfinite(v)) bad = 1;
+            int64_t g;
+            if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;
+            else g = e / (ci * s);
+            const int keep = mode[l] == ORACLE_NONE || ml[g] != 0;
+            const float z = keep ? v : 0.0f;
+            Z[off + e] = z;
+            U[off + e] = U[off + e] + (wbar - z);
+            if (Wbar) Wbar[off + e] = wbar;
+        }
+        if (bad) return -2;
+        gbase += G;
+    }
+    return 0;
+}
+
+/*
+ * Bitwise mask synchronisation (Section 4.3, Eq. (14)): out = OR over the M masks, byte by byte
+ * (any nonzero byte counts as "kept"; the result holds 0 / 1).
+ */
+int oracle_mask_or(int64_t n_groups_total, const uint8_t *const *masks, int32_t M, uint8_t *out)
+{
+    if (n_groups_total < 0 || M < 1 || !masks || !out) return -1;
+    for (int64_t g = 0; g < n_groups_total; ++g) {
+        uint8_t any = 0;
+        for (int32_t i = 0; i < M; ++i) any |= masks[i][g] != 0 ? 1 : 0;
+        out[g] = any;
+    }
+    return 0;
+}

@@ -12,6 +12,7 @@ import pytest
 
 import oracle
 from tests import test_oracle_pins as pins
+from tests import test_oracle_frozen as fpins
 
 MUTATIONS = [
     ("tie_goes_to_higher_index", "(kl[h] == kl[g] && h < g)", "(kl[h] == kl[g] && h > g)"),
@@ -35,6 +36,17 @@ MUTATIONS = [
     ("expand_no_zero_fill", "for (int64_t e = 0; e < n; ++e) dl[e] = 0.0f;", "for (int64_t e = 0; e < 0; ++e) dl[e] = 0.0f;"),
     ("none_layer_is_pruned", "if (mode[l] == ORACLE_NONE) {\n            for (int64_t g = 0; g < G; ++g) ml[g] = 1;",
      "if (0) {\n            for (int64_t g = 0; g < G; ++g) ml[g] = 1;"),
+    ("frozen_mask_inverted", "const int keep = mode[l] == ORACLE_NONE || ml[g] != 0;", "const int keep = mode[l] == ORACLE_NONE || ml[g] == 0;"),
+    ("frozen_ignores_mode_none", "const int keep = mode[l] == ORACLE_NONE || ml[g] != 0;", "const int keep = ml[g] != 0;"),
+    ("frozen_channel_group_wrong", "if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;\n            else g = e / (ci * s);\n            const int keep",
+     "if (mode[l] == ORACLE_CHANNEL) g = e % ci;\n            else g = e / (ci * s);\n            const int keep"),
+    ("frozen_dual_regrouped", "U[off + e] = U[off + e] + (wbar - z);\n            if (Wbar) Wbar[off + e] = wbar;\n        }\n        if (bad)",
+     "U[off + e] = (U[off + e] + wbar) - z;\n            if (Wbar) Wbar[off + e] = wbar;\n        }\n        if (bad)"),
+    ("frozen_multiplies_by_mask", "const float z = keep ? v : 0.0f;\n            Z[off + e] = z;\n            U[off + e] = U[off + e] + (wbar - z);\n            if (Wbar) Wbar[off + e] = wbar;\n        }\n        if (bad)",
+     "const float z = v * (float)keep;\n            Z[off + e] = z;\n            U[off + e] = U[off + e] + (wbar - z);\n            if (Wbar) Wbar[off + e] = wbar;\n        }\n        if (bad)"),
+    ("mask_or_is_and", "uint8_t any = 0;\n        for (int32_t i = 0; i < M; ++i) any |= masks[i][g] != 0 ? 1 : 0;",
+     "uint8_t any = 1;\n        for (int32_t i = 0; i < M; ++i) any &= masks[i][g] != 0 ? 1 : 0;"),
+    ("mask_or_keeps_raw_bytes", "any |= masks[i][g] != 0 ? 1 : 0;", "any |= masks[i][g];"),
     ("filter_mask_prunes_channels_too", "if (mode != ORACLE_CHANNEL || ml[c]) k_in[b++]", "if (mode == ORACLE_NONE || ml[c % co]) k_in[b++]"),
 ]
 
@@ -50,6 +62,11 @@ PIN_FUNCS = [
     pins.test_eq_9_reduces_to_plain_mean_plus_mean_dual,
     pins.test_invariants_on_tiny_and_random_workloads,
     pins.test_identity_cases,
+    fpins.test_handworked_frozen_masks,
+    lambda: [fpins.test_frozen_with_the_projections_own_mask_is_the_projection(s) for s in range(2)],
+    lambda: [fpins.test_frozen_against_the_printed_formula_in_numpy(s) for s in range(2)],
+    fpins.test_all_ones_mask_and_unconstrained_layers,
+    fpins.test_mask_union_is_the_logical_or,
 ]
 
 
@@ -65,7 +82,8 @@ def test_a_planted_mistake_in_the_oracle_fails_a_pin(name, old, new, tmp_path, m
                            "-o", str(so_file), str(c_file), "-lm"])
     good = oracle._load()
     lib = ctypes.CDLL(str(so_file))
-    for fn in ("oracle_project", "oracle_compact", "oracle_expand", "oracle_set_threads", "oracle_get_threads"):
+    for fn in ("oracle_project", "oracle_compact", "oracle_expand", "oracle_set_threads", "oracle_get_threads",
+               "oracle_project_frozen", "oracle_mask_or"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(oracle, "_lib", lib)
