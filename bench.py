@@ -178,6 +178,38 @@ def main():
                 if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == dom:
                     roofline["traffic"] = int(parts[2])
 
+    # ---- frozen-mask step (Algorithm 1 Phase 3 once the masks are frozen, Section 4.5): the same three calls
+    #      with hsadmm_project_frozen in place of hsadmm_project, applying each buffer set's last mask
+    def frozen_step():
+        b = sets[counter[0] % nsets]
+        counter[0] += 1
+        pkg.hsadmm_project_frozen(plan, b.W, b.U, b.Z, None, b.mask, stream=stream)
+        pkg.hsadmm_compact(plan, b.Z, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
+        pkg.hsadmm_expand(plan, b.packed, None, b.dst, b.ws, stream=stream)
+
+    fsteps = max(1, args.steps // 2)
+    for _ in range(max(3, args.warmup // 2)):
+        frozen_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(fsteps):
+        frozen_step()
+    torch.cuda.synchronize()
+    f_elapsed = (time.perf_counter() - t0) / fsteps
+    pkg.hsadmm_kernel_timing_enable(plan, True)
+    for _ in range(fsteps):
+        frozen_step()
+    torch.cuda.synchronize()
+    ft = pkg.hsadmm_kernel_timing_read(plan)
+    pkg.hsadmm_kernel_timing_enable(plan, False)
+    f_us = 1e3 * ft["project_frozen"][0] / max(1, ft["project_frozen"][1])
+    frozen = {"ms_per_step": round(1e3 * f_elapsed, 4),
+              "value_GBps": round(bytes_["step"] / f_elapsed / 1e9, 1),
+              "hbm_frac": round(bytes_["step"] / f_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+              "project_frozen_us_per_launch": round(f_us, 2),
+              "project_frozen_GBps": round(bytes_["project"] / (f_us * 1e-6) / 1e9, 1),
+              "project_frozen_frac": round(bytes_["project"] / (f_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+
     # ---- context: a plain device copy of the same size class (practical streaming ceiling)
     a_src, a_dst = sets[0].W[0], sets[0].Z
     for _ in range(5):
@@ -235,6 +267,7 @@ def main():
         "kernel_launches_per_step": launches_per_step,
         "kernel_us_per_step_sum": round(sum(kernel_us_per_step.values()), 2),
         "copy_GBps": round(copy_gbps, 1),
+        "frozen_mask_step": frozen,
         "verified_against_oracle": verify,
         "roofline": roofline,
         "cpu_baseline": cpu,

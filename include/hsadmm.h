@@ -60,6 +60,7 @@ extern "C" {
 
 #define HSADMM_MAX_REPLICAS  16
 #define HSADMM_MAX_LAYERS    4096
+#define HSADMM_MAX_MASKS     64
 
 /* One table entry per layer.  Host memory, caller-owned, copied by hsadmm_plan_create. */
 typedef struct {
@@ -128,6 +129,33 @@ int hsadmm_project(const hsadmm_plan_t* plan, const float* const* W_replicas, in
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Retraining branch of Algorithm 1, Phase 3 (Section 4.5, mask freezing): the
+ * projection is replaced by the element-wise application of a cached mask,
+ *     Z = (Wbar + U) (.) mask,   U <- U + (Wbar - Z),
+ * with the candidate formed exactly as in hsadmm_project.  One pass: every
+ * replica and U are read once, Z and U written once; no norms, no selection.
+ *
+ *   mask   device, in, groups_total bytes, nonzero = kept; any number of kept
+ *          groups per layer (e.g. the union hsadmm_mask_or gives); the groups
+ *          of a MODE_NONE layer are kept whatever their bytes say.
+ * Masked-out entries of Z are exactly +0.  Other arguments, alignment and
+ * aliasing rules as for hsadmm_project; no workspace is needed.
+ * Errors: INVALID_ARGUMENT, UNSUPPORTED, HIP.
+ */
+int hsadmm_project_frozen(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                          float* U, float* Z, float* Wbar, const uint8_t* mask, void* hip_stream);
+
+/*
+ * Bitwise mask synchronisation on one device (Section 4.3, Eq. (14)):
+ * out[g] = 1 if any of the M masks has a nonzero byte at g, else 0.
+ *   masks  HOST array of M DEVICE pointers (1 <= M <= HSADMM_MAX_MASKS), each groups_total bytes
+ *   out    device, groups_total bytes; may be one of the inputs
+ * Errors: INVALID_ARGUMENT, UNSUPPORTED, HIP.
+ */
+int hsadmm_mask_or(const hsadmm_plan_t* plan, const uint8_t* const* masks, int32_t M, uint8_t* out,
+                   void* hip_stream);
+
+/*
  * Step (e1), tensor shrinkage: packs the kept slices of `src` into one
  * contiguous dense buffer, layer after layer,
  *     packed[layer_off[l] + (p*|K_in| + q)*khw + t] = src[l][K_out[p]][K_in[q]][t]
@@ -190,7 +218,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 6
+#define HSADMM_KERNEL_COUNT 8
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

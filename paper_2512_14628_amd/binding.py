@@ -28,8 +28,9 @@ HIPCC_FLAGS = [
 
 EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hsadmm_project",
            "hsadmm_compact", "hsadmm_expand", "hsadmm_strerror", "hsadmm_version",
-           "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name")
-KERNEL_COUNT = 6
+           "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name",
+           "hsadmm_project_frozen", "hsadmm_mask_or")
+KERNEL_COUNT = 8
 
 
 class HsadmmError(RuntimeError):
@@ -82,6 +83,10 @@ def load_library():
     lib.hsadmm_project.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp,
                                    ctypes.c_size_t, vp]
     lib.hsadmm_project.restype = ctypes.c_int
+    lib.hsadmm_project_frozen.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp]
+    lib.hsadmm_project_frozen.restype = ctypes.c_int
+    lib.hsadmm_mask_or.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp]
+    lib.hsadmm_mask_or.restype = ctypes.c_int
     lib.hsadmm_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hsadmm_compact.restype = ctypes.c_int
     lib.hsadmm_expand.argtypes = [vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -205,6 +210,26 @@ def hsadmm_project(plan: Plan, W_replicas: Sequence, U, Z, Wbar, mask, sqnorm, w
                             _ptr(workspace), wb, _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_project")
+    return rc
+
+
+def hsadmm_project_frozen(plan: Plan, W_replicas: Sequence, U, Z, Wbar, mask, stream=None, check: bool = True) -> int:
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    rc = lib.hsadmm_project_frozen(plan.handle, ptrs, R, _ptr(U), _ptr(Z), _ptr(Wbar), _ptr(mask), _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_project_frozen")
+    return rc
+
+
+def hsadmm_mask_or(plan: Plan, masks: Sequence, out, stream=None, check: bool = True) -> int:
+    lib = load_library()
+    M = len(masks)
+    ptrs = (ctypes.c_void_p * max(M, 1))(*[_ptr(m) for m in masks])
+    rc = lib.hsadmm_mask_or(plan.handle, ptrs, M, _ptr(out), _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_mask_or")
     return rc
 
 

@@ -43,7 +43,7 @@ constexpr int kTileElems = 2048;                // target elements per work item
 constexpr int kWideRow = 2048;                  // rows at least this long are shared by the whole workgroup
 constexpr int kChanRows = 32;               // CHANNEL tiles: rows per row block
 constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
-constexpr int kVersion = 103;
+constexpr int kVersion = 110;
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -320,6 +320,127 @@ __global__ __launch_bounds__(kBlock) void project_pass1(const WorkItem* __restri
     const WorkItem it = items[blockIdx.x];
     if (item_mode(it) == HSADMM_MODE_CHANNEL) project_tile<R>(it, a, Rrt);
     else project_rows<R>(it, a, Rrt);
+}
+
+// ------------------------------------------------------------------ project under a frozen mask
+
+// Final values of 4 adjacent elements under a known mask (Algorithm 1 Phase 3, retraining branch:
+// z = z~ (.) m): kept element Z = V, U += Wbar - V; masked-out element Z = +0, U = U + Wbar (= V).
+template <int R>
+__device__ __forceinline__ void frozen4(const ProjectArgs& a, int Rrt, int64_t e, bool k0, bool k1, bool k2, bool k3)
+{
+    const int RR = R > 0 ? R : Rrt;
+    v4f s = ld4(a.W[0] + e);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+    const v4f u = ld4(a.U + e);
+    const v4f wb = s * a.inv_R;
+    const v4f v = wb + u;
+    v4f z;
+    z.x = k0 ? v.x : 0.f; z.y = k1 ? v.y : 0.f; z.z = k2 ? v.z : 0.f; z.w = k3 ? v.w : 0.f;
+    st4(a.Z + e, z);
+    st4(a.U + e, u + (wb - z));
+    if (a.Wbar) st4(a.Wbar + e, wb);
+}
+
+// two chunks of one row (same keep flag) with all loads issued before any store
+template <int R>
+__device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, bool keep)
+{
+    const int RR = R > 0 ? R : Rrt;
+    v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) {
+        const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
+        s0 = s0 + w0;
+        s1 = s1 + w1;
+    }
+    const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
+    const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
+    const v4f v0 = wb0 + u0, v1 = wb1 + u1;
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    const v4f z0 = keep ? v0 : zero4, z1 = keep ? v1 : zero4;
+    st4(a.Z + e0, z0);
+    st4(a.Z + e1, z1);
+    st4(a.U + e0, u0 + (wb0 - z0));
+    st4(a.U + e1, u1 + (wb1 - z1));
+    if (a.Wbar) { st4(a.Wbar + e0, wb0); st4(a.Wbar + e1, wb1); }
+}
+
+template <int R>
+__device__ __forceinline__ void frozen1(const ProjectArgs& a, int Rrt, int64_t e, bool keep)
+{
+    const int RR = R > 0 ? R : Rrt;
+    float s = ld1(a.W[0] + e);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
+    const float u = ld1(a.U + e);
+    const float wb = s * a.inv_R;
+    const float v = wb + u;
+    const float z = keep ? v : 0.f;
+    st1(a.Z + e, z);
+    st1(a.U + e, u + (wb - z));
+    if (a.Wbar) st1(a.Wbar + e, wb);
+}
+
+// Same work items and lane mappings as project_pass1; no keys, no second pass: every byte of the
+// replicas and of U is read once and Z and U are written once.
+template <int R>
+__global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
+                                                         const uint8_t* __restrict__ mask)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int mode = item_mode(it);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    if (mode != HSADMM_MODE_CHANNEL) {
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            const bool keep = mode == HSADMM_MODE_NONE || mask[it.g0 + rr] != 0;
+            const int64_t base = it.base + (int64_t)rr * row_len;
+            if (vec) {
+                const int nchunk = row_len >> 2;
+                int c = j;
+                for (; c + lpr < nchunk; c += 2 * lpr)
+                    frozen4x2<R>(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + lpr) << 2), keep);
+                if (c < nchunk) frozen4<R>(a, Rrt, base + ((int64_t)c << 2), keep, keep, keep, keep);
+            } else {
+                for (int c = j; c < row_len; c += lpr) frozen1<R>(a, Rrt, base + c, keep);
+            }
+        }
+    } else {
+        const int vw = vec ? 4 : 1;
+        const int col = it.col0 + lane * vw;
+        if (col >= row_len) return;
+        const DivKhw div(it.khw);
+        bool k[4] = {true, true, true, true};
+        for (int i = 0; i < vw; ++i) k[i] = mask[it.g0 + div(col + i)] != 0;
+        for (int rr = wave; rr < it.nr; rr += kWaves) {
+            const int64_t e = it.base + (int64_t)rr * row_len + col;
+            if (vec) frozen4<R>(a, Rrt, e, k[0], k[1], k[2], k[3]);
+            else frozen1<R>(a, Rrt, e, k[0]);
+        }
+    }
+}
+
+// Eq. (14): out = OR of M masks, 0 / 1 bytes.
+struct MaskOrArgs {
+    const uint8_t* m[HSADMM_MAX_MASKS];
+};
+
+__global__ __launch_bounds__(kBlock) void mask_or_kernel(MaskOrArgs a, int M, int64_t n, uint8_t* __restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x; g < n; g += stride) {
+        unsigned int any = 0;
+        for (int i = 0; i < M; ++i) any |= a.m[i][g];
+        out[g] = any != 0 ? 1 : 0;
+    }
 }
 
 // ------------------------------------------------------------------ top-k selection
@@ -949,7 +1070,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kKernelCount };
 constexpr size_t kTimingPairs = 8192;
 
 }  // namespace
@@ -1064,6 +1185,12 @@ hipError_t launch_pass1(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, hip
                   (const WorkItem*)p->d_items_proj, a, Rrt);
 }
 
+template <int R>
+hipError_t launch_frozen(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, const uint8_t* mask, hipStream_t s)
+{
+    return launch(p, kFrozen, project_frozen<R>, (unsigned)p->items_proj.size(), kBlock, s,
+                  (const WorkItem*)p->d_items_proj, a, Rrt, mask);
+}
 int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, int64_t* layer_off_out, int32_t* kept_idx,
              hipStream_t s)
 {
@@ -1255,6 +1382,49 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
     return HSADMM_OK;
 }
 
+int hsadmm_project_frozen(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U, float* Z,
+                          float* Wbar, const uint8_t* mask, void* hip_stream)
+{
+    if (!p || !W_replicas || !U || !Z || !mask || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
+    if (!is_aligned(U, 16) || !is_aligned(Z, 16) || (Wbar && !is_aligned(Wbar, 16))) return HSADMM_ERR_INVALID_ARGUMENT;
+    for (int r = 0; r < R; ++r)
+        if (!W_replicas[r] || !is_aligned(W_replicas[r], 16)) return HSADMM_ERR_INVALID_ARGUMENT;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    ProjectArgs a{};
+    for (int r = 0; r < R; ++r) a.W[r] = W_replicas[r];
+    a.U = U; a.Z = Z; a.Wbar = Wbar;
+    a.inv_R = 1.0f / (float)R;
+    hipError_t e;
+    switch (R) {
+        case 1: e = launch_frozen<1>(p, a, R, mask, s); break;
+        case 2: e = launch_frozen<2>(p, a, R, mask, s); break;
+        case 3: e = launch_frozen<3>(p, a, R, mask, s); break;
+        case 4: e = launch_frozen<4>(p, a, R, mask, s); break;
+        case 8: e = launch_frozen<8>(p, a, R, mask, s); break;
+        default: e = launch_frozen<0>(p, a, R, mask, s); break;
+    }
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
+int hsadmm_mask_or(const hsadmm_plan_t* p, const uint8_t* const* masks, int32_t M, uint8_t* out, void* hip_stream)
+{
+    if (!p || !masks || !out || M < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (M > HSADMM_MAX_MASKS) return HSADMM_ERR_UNSUPPORTED;
+    MaskOrArgs a{};
+    for (int i = 0; i < M; ++i) {
+        if (!masks[i]) return HSADMM_ERR_INVALID_ARGUMENT;
+        a.m[i] = masks[i];
+    }
+    const int64_t n = p->groups_total;
+    unsigned grid = (unsigned)((n + kBlock - 1) / kBlock);
+    if (grid > 1024u) grid = 1024u;
+    if (grid < 1u) grid = 1u;
+    const hipError_t e = launch(p, kMaskOr, mask_or_kernel, grid, kBlock, static_cast<hipStream_t>(hip_stream),
+                                a, (int)M, n, out);
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
 int hsadmm_compact(const hsadmm_plan_t* p, const float* src, const uint8_t* mask, float* packed,
                    int64_t* layer_off, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
                    void* hip_stream)
@@ -1358,6 +1528,8 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kScan: return "scan_mask";
         case kGather: return "compact_gather";
         case kScatter: return "expand_scatter";
+        case kFrozen: return "project_frozen";
+        case kMaskOr: return "mask_or";
         default: return "";
     }
 }
