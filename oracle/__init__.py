@@ -61,6 +61,18 @@ def _load():
     lib.oracle_project_frozen.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p,
                                           ctypes.POINTER(f32p), ctypes.c_int32, f32p, f32p, f32p, u8p]
     lib.oracle_project_frozen.restype = ctypes.c_int
+    f64pp = ctypes.POINTER(ctypes.c_double)
+    lib.oracle_node_coefficients.argtypes = [ctypes.c_int32, f64pp, f64pp, ctypes.c_double, ctypes.c_int32,
+                                             ctypes.c_int32, f32p, f32p]
+    lib.oracle_node_coefficients.restype = ctypes.c_int
+    lib.oracle_project_weighted.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p, i32p,
+                                            ctypes.POINTER(f32p), ctypes.c_int32, f32p, f32p, f32p, f32p, f32p,
+                                            f32p, f32p, u8p, f64p]
+    lib.oracle_project_weighted.restype = ctypes.c_int
+    lib.oracle_dual_inter.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, f32p, f32p, f32p]
+    lib.oracle_dual_inter.restype = ctypes.c_int
+    lib.oracle_add_arenas.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, f32p, f32p, f32p]
+    lib.oracle_add_arenas.restype = ctypes.c_int
     lib.oracle_mask_or.argtypes = [ctypes.c_int64, ctypes.POINTER(u8p), ctypes.c_int32, u8p]
     lib.oracle_mask_or.restype = ctypes.c_int
     _lib = lib
@@ -232,3 +244,83 @@ def mask_or(masks):
     if rc != 0:
         raise ValueError("oracle_mask_or failed with code %d" % rc)
     return out
+
+
+def node_coefficients(rho1, rho2, lam: float, M: int, P: int):
+    """Eq. (9): a_l = P rho_1 / gamma_l, b_l = rho_2 / gamma_l with gamma_l = lambda/M + P rho_1 + rho_2 (fp32 arrays)."""
+    lib = _load()
+    r1 = np.ascontiguousarray(rho1, dtype=np.float64)
+    r2 = np.ascontiguousarray(rho2, dtype=np.float64)
+    L = r1.size
+    a = np.zeros(L, dtype=np.float32)
+    b = np.zeros(L, dtype=np.float32)
+    rc = lib.oracle_node_coefficients(L, _p(r1, ctypes.c_double), _p(r2, ctypes.c_double), float(lam), int(M), int(P),
+                                      _p(a, ctypes.c_float), _p(b, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("oracle_node_coefficients failed with code %d" % rc)
+    return a, b
+
+
+def project_weighted(table, W, U, Zg, Vd, a, b, want_wbar: bool = False):
+    """Steps (a)-(d) with the full candidate of Eq. (9).  Returns dict(U, Z, mask, key, Wbar or None)."""
+    global last_call_seconds
+    lib = _load()
+    t = _cols(table)
+    L = len(t["c_out"])
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    R, n_arena = W.shape
+    U_new = np.array(U, dtype=np.float32, copy=True, order="C")
+    Zg = np.ascontiguousarray(Zg, dtype=np.float32)
+    Vd = np.ascontiguousarray(Vd, dtype=np.float32)
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    b = np.ascontiguousarray(b, dtype=np.float32)
+    assert a.shape == (L,) and b.shape == (L,) and Zg.shape == (n_arena,) and Vd.shape == (n_arena,)
+    Z = _poisoned_arena(t, n_arena)
+    Wbar = _poisoned_arena(t, n_arena) if want_wbar else None
+    gt = groups_total(t)
+    mask = np.zeros(gt, dtype=np.uint8)
+    key = np.zeros(gt, dtype=np.float64)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    ptrs = (f32p * R)(*[_p(W[r], ctypes.c_float) for r in range(R)])
+    _t0 = time.perf_counter()
+    rc = lib.oracle_project_weighted(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                                     _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
+                                     _p(t["mode"], ctypes.c_int32), _p(t["k"], ctypes.c_int32), ptrs, R,
+                                     _p(U_new, ctypes.c_float), _p(Zg, ctypes.c_float), _p(Vd, ctypes.c_float),
+                                     _p(a, ctypes.c_float), _p(b, ctypes.c_float), _p(Z, ctypes.c_float),
+                                     _p(Wbar, ctypes.c_float) if want_wbar else None,
+                                     _p(mask, ctypes.c_uint8), _p(key, ctypes.c_double))
+    last_call_seconds = time.perf_counter() - _t0
+    if rc != 0:
+        raise ValueError("oracle_project_weighted failed with code %d" % rc)
+    return {"U": U_new, "Z": Z, "mask": mask, "key": key, "Wbar": Wbar}
+
+
+def dual_inter(table, Zi, Zg, Vd):
+    """Eq. (13): returns v + (z_i - z)."""
+    lib = _load()
+    t = _cols(table)
+    V_new = np.array(Vd, dtype=np.float32, copy=True, order="C")
+    Zi = np.ascontiguousarray(Zi, dtype=np.float32)
+    Zg = np.ascontiguousarray(Zg, dtype=np.float32)
+    rc = lib.oracle_dual_inter(len(t["c_out"]), _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                               _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
+                               _p(Zi, ctypes.c_float), _p(Zg, ctypes.c_float), _p(V_new, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("oracle_dual_inter failed with code %d" % rc)
+    return V_new
+
+
+def add_arenas(table, A, B):
+    """c = z_i + v_i of Section 4.4.1 (padding stays +0)."""
+    lib = _load()
+    t = _cols(table)
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    C = _poisoned_arena(t, A.size)
+    rc = lib.oracle_add_arenas(len(t["c_out"]), _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                               _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
+                               _p(A, ctypes.c_float), _p(B, ctypes.c_float), _p(C, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("oracle_add_arenas failed with code %d" % rc)
+    return C

@@ -330,3 +330,147 @@ int oracle_mask_or(int64_t n_groups_total, const uint8_t *const *masks, int32_t 
     }
     return 0;
 }
+
+/*
+ * Weights of the dense node candidate, Eq. (9): with P accelerators per node, M nodes, weight decay
+ * lambda and the layer's penalties rho_1, rho_2,
+ *     gamma = lambda / M + P rho_1 + rho_2,
+ *     z~ = (1/gamma) [ rho_1 sum_j (theta_j + u_j) + rho_2 (z - v) ] = a (Wbar + U) + b (z - v)
+ * where Wbar and U are the means over the node's P replicas, a = P rho_1 / gamma, b = rho_2 / gamma.
+ * Computed in fp64, rounded once to fp32.  Returns 0, or -1 on a bad argument (gamma <= 0 included).
+ */
+int oracle_node_coefficients(int32_t L, const double *rho1, const double *rho2, double lambda, int32_t M,
+                             int32_t P, float *a, float *b)
+{
+    if (L < 1 || !rho1 || !rho2 || !a || !b || M < 1 || P < 1) return -1;
+    for (int32_t l = 0; l < L; ++l) {
+        const double gamma = lambda / (double)M + (double)P * rho1[l] + rho2[l];
+        if (!(gamma > 0.0) || rho1[l] < 0.0 || rho2[l] < 0.0) return -1;
+        a[l] = (float)((double)P * rho1[l] / gamma);
+        b[l] = (float)(rho2[l] / gamma);
+    }
+    return 0;
+}
+
+/*
+ * Steps (a)-(d) with the full candidate of Eq. (9):
+ *     Wbar as in oracle_project;  t = Wbar + U;  q = Zg - Vd  (global consensus minus inter-node dual);
+ *     z~ = fl(fl(a_l t) + fl(b_l q))   in fp32, no fused multiply-add;
+ *     keys, selection and Z = Pi_S(z~) as in oracle_project (Eq. (10));
+ *     U <- U + (Wbar - Z)  (Eq. (12): the intra-node dual update involves theta and z_i only).
+ * Zg, Vd: in, full-layout arenas.  a, b: L fp32 weights.  Other arguments as for oracle_project.
+ */
+int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                            const int32_t *khw, const int32_t *mode, const int32_t *k,
+                            const float *const *W, int32_t R, float *U, const float *Zg, const float *Vd,
+                            const float *a, const float *b, float *Z, float *Wbar, uint8_t *mask, double *key)
+{
+    if (L < 1 || R < 1 || !W || !U || !Zg || !Vd || !a || !b || !Z || !mask || !key) return -1;
+    const float inv_R = 1.0f / (float)R;
+    int64_t gbase = 0;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
+        if (co < 1 || ci < 1 || s < 1) return -1;
+        const int64_t n = co * ci * s;
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
+        if (mode[l] != ORACLE_NONE && (k[l] < 1 || k[l] > G)) return -1;
+        const int64_t off = elem_off[l];
+        float *wbar = (float *)malloc(sizeof(float) * (size_t)n);
+        float *v = (float *)malloc(sizeof(float) * (size_t)n);
+        if (!wbar || !v) { free(wbar); free(v); return -1; }
+        int bad = 0;
+        const float al = a[l], bl = b[l];
+#pragma omp parallel for schedule(static) reduction(| : bad)
+        for (int64_t e = 0; e < n; ++e) {
+            float acc = W[0][off + e];
+            for (int32_t r = 1; r < R; ++r) acc = acc + W[r][off + e];
+            wbar[e] = acc * inv_R;
+            const float t = wbar[e] + U[off + e];
+            const float q = Zg[off + e] - Vd[off + e];
+            const float at = al * t;
+            const float bq = bl * q;
+            v[e] = at + bq;
+            if (!isfinite(v[e])) bad = 1;
+        }
+        if (bad) { free(wbar); free(v); return -2; }
+        double *kl = key + gbase;
+#pragma omp parallel for schedule(static)
+        for (int64_t g = 0; g < G; ++g) {
+            double acc = 0.0;
+            if (mode[l] == ORACLE_CHANNEL) {
+                for (int64_t o = 0; o < co; ++o)
+                    for (int64_t t = 0; t < s; ++t) {
+                        const double x = (double)v[(o * ci + g) * s + t];
+                        acc += x * x;
+                    }
+            } else {
+                for (int64_t t = 0; t < ci * s; ++t) {
+                    const double x = (double)v[g * ci * s + t];
+                    acc += x * x;
+                }
+            }
+            kl[g] = acc;
+        }
+        uint8_t *ml = mask + gbase;
+        if (mode[l] == ORACLE_NONE) {
+            for (int64_t g = 0; g < G; ++g) ml[g] = 1;
+        } else {
+            const int64_t kk = k[l];
+#pragma omp parallel for schedule(static)
+            for (int64_t g = 0; g < G; ++g) {
+                int64_t before = 0;
+                for (int64_t h = 0; h < G; ++h)
+                    if (kl[h] > kl[g] || (kl[h] == kl[g] && h < g)) ++before;
+                ml[g] = before < kk ? 1 : 0;
+            }
+        }
+#pragma omp parallel for schedule(static)
+        for (int64_t e = 0; e < n; ++e) {
+            int64_t g;
+            if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;
+            else g = e / (ci * s);
+            const float z = ml[g] ? v[e] : 0.0f;
+            Z[off + e] = z;
+            U[off + e] = U[off + e] + (wbar[e] - z);
+            if (Wbar) Wbar[off + e] = wbar[e];
+        }
+        free(wbar);
+        free(v);
+        gbase += G;
+    }
+    return 0;
+}
+
+/*
+ * Inter-node dual update, Eq. (13): v <- v + (z_i - z), element by element over every layer (arena
+ * padding is left alone).  Zi: the node's projected consensus; Zg: the new global consensus.
+ */
+int oracle_dual_inter(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                      const int32_t *khw, const float *Zi, const float *Zg, float *Vd)
+{
+    if (L < 1 || !Zi || !Zg || !Vd) return -1;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t n = (int64_t)c_out[l] * c_in[l] * khw[l];
+        const int64_t off = elem_off[l];
+#pragma omp parallel for schedule(static)
+        for (int64_t e = 0; e < n; ++e) Vd[off + e] = Vd[off + e] + (Zi[off + e] - Zg[off + e]);
+    }
+    return 0;
+}
+
+/*
+ * Pre-transmission buffer of Section 4.4.1: c = z_i + v_i (fp32), element by element over every layer,
+ * into a full-layout arena that oracle_compact then shrinks (Algorithm 1, Phase 4).
+ */
+int oracle_add_arenas(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                      const int32_t *khw, const float *A, const float *B, float *C)
+{
+    if (L < 1 || !A || !B || !C) return -1;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t n = (int64_t)c_out[l] * c_in[l] * khw[l];
+        const int64_t off = elem_off[l];
+#pragma omp parallel for schedule(static)
+        for (int64_t e = 0; e < n; ++e) C[off + e] = A[off + e] + B[off + e];
+    }
+    return 0;
+}

@@ -13,6 +13,7 @@ import pytest
 import oracle
 from tests import test_oracle_pins as pins
 from tests import test_oracle_frozen as fpins
+from tests import test_oracle_weighted as wpins
 
 MUTATIONS = [
     ("tie_goes_to_higher_index", "(kl[h] == kl[g] && h < g)", "(kl[h] == kl[g] && h > g)"),
@@ -47,6 +48,15 @@ MUTATIONS = [
     ("mask_or_is_and", "uint8_t any = 0;\n        for (int32_t i = 0; i < M; ++i) any |= masks[i][g] != 0 ? 1 : 0;",
      "uint8_t any = 1;\n        for (int32_t i = 0; i < M; ++i) any &= masks[i][g] != 0 ? 1 : 0;"),
     ("mask_or_keeps_raw_bytes", "any |= masks[i][g] != 0 ? 1 : 0;", "any |= masks[i][g];"),
+    ("weighted_gamma_drops_lambda", "const double gamma = lambda / (double)M + (double)P * rho1[l] + rho2[l];", "const double gamma = (double)P * rho1[l] + rho2[l];"),
+    ("weighted_gamma_forgets_P", "const double gamma = lambda / (double)M + (double)P * rho1[l] + rho2[l];", "const double gamma = lambda / (double)M + rho1[l] + rho2[l];"),
+    ("weighted_lambda_not_divided", "const double gamma = lambda / (double)M +", "const double gamma = lambda +"),
+    ("weighted_q_sign", "const float q = Zg[off + e] - Vd[off + e];", "const float q = Zg[off + e] + Vd[off + e];"),
+    ("weighted_drops_dual_in_t", "const float t = wbar[e] + U[off + e];\n            const float q", "const float t = wbar[e];\n            const float q"),
+    ("weighted_swaps_coefficients", "const float at = al * t;\n            const float bq = bl * q;", "const float at = bl * t;\n            const float bq = al * q;"),
+    ("weighted_dual_uses_candidate", "const float at = al * t;", "const float at = al * t; wbar[e] = t;"),
+    ("dual_inter_sign", "Vd[off + e] = Vd[off + e] + (Zi[off + e] - Zg[off + e]);", "Vd[off + e] = Vd[off + e] + (Zg[off + e] - Zi[off + e]);"),
+    ("add_arenas_subtracts", "C[off + e] = A[off + e] + B[off + e];", "C[off + e] = A[off + e] - B[off + e];"),
     ("filter_mask_prunes_channels_too", "if (mode != ORACLE_CHANNEL || ml[c]) k_in[b++]", "if (mode == ORACLE_NONE || ml[c % co]) k_in[b++]"),
 ]
 
@@ -67,6 +77,12 @@ PIN_FUNCS = [
     lambda: [fpins.test_frozen_against_the_printed_formula_in_numpy(s) for s in range(2)],
     fpins.test_all_ones_mask_and_unconstrained_layers,
     fpins.test_mask_union_is_the_logical_or,
+    wpins.test_coefficients_of_eq_9,
+    wpins.test_handworked_weighted_projection,
+    lambda: [wpins.test_weights_one_and_zero_give_the_base_projection(s) for s in range(2)],
+    wpins.test_eq_9_printed_formula_with_per_replica_duals,
+    lambda: [wpins.test_weighted_against_numpy(s) for s in range(2)],
+    wpins.test_inter_node_dual_update_and_transmission_sum,
 ]
 
 
@@ -83,7 +99,8 @@ def test_a_planted_mistake_in_the_oracle_fails_a_pin(name, old, new, tmp_path, m
     good = oracle._load()
     lib = ctypes.CDLL(str(so_file))
     for fn in ("oracle_project", "oracle_compact", "oracle_expand", "oracle_set_threads", "oracle_get_threads",
-               "oracle_project_frozen", "oracle_mask_or"):
+               "oracle_project_frozen", "oracle_mask_or", "oracle_node_coefficients", "oracle_project_weighted",
+               "oracle_dual_inter", "oracle_add_arenas"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(oracle, "_lib", lib)
