@@ -210,6 +210,45 @@ def main():
               "project_frozen_GBps": round(bytes_["project"] / (f_us * 1e-6) / 1e9, 1),
               "project_frozen_frac": round(bytes_["project"] / (f_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
 
+    # ---- full node update (Eq. (9) with the rho_2 (z - v) term) + Phase 4 on one node:
+    #      hsadmm_project_weighted, hsadmm_compact_sum (c = z_i + v_i), hsadmm_expand, hsadmm_dual_inter (Eq. (13))
+    L = len(wl.layers)
+    wa, wb_ = pkg.hsadmm_node_coefficients([1.5e-3] * L, [1.5e-4] * L, 1e-4, 16, wl.R)   # the paper's initial penalties
+    pkg.hsadmm_plan_set_node_weights(plan, wa, wb_)
+    for b in sets:
+        b.Zg = torch.randn(n, dtype=torch.float32, device=dev) * 0.05
+        b.Vd = torch.randn(n, dtype=torch.float32, device=dev) * 0.01
+
+    def weighted_step():
+        b = sets[counter[0] % nsets]
+        counter[0] += 1
+        pkg.hsadmm_project_weighted(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, None, b.ws, stream=stream)
+        pkg.hsadmm_compact_sum(plan, b.Z, b.Vd, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
+        pkg.hsadmm_expand(plan, b.packed, None, b.dst, b.ws, stream=stream)
+        pkg.hsadmm_dual_inter(plan, b.Z, b.dst, b.Vd, stream=stream)
+
+    wsteps = max(1, args.steps // 4)
+    for _ in range(3):
+        weighted_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(wsteps):
+        weighted_step()
+    torch.cuda.synchronize()
+    w_elapsed = (time.perf_counter() - t0) / wsteps
+    pkg.hsadmm_kernel_timing_enable(plan, True)
+    for _ in range(wsteps):
+        weighted_step()
+    torch.cuda.synchronize()
+    wt = pkg.hsadmm_kernel_timing_read(plan)
+    pkg.hsadmm_kernel_timing_enable(plan, False)
+    w_bytes = 4 * wl.n_total * (wl.R + 10) + 16 * nk
+    weighted = {"ms_per_step": round(1e3 * w_elapsed, 4),
+                "algorithmic_bytes_per_step": w_bytes,
+                "value_GBps": round(w_bytes / w_elapsed / 1e9, 1),
+                "hbm_frac": round(w_bytes / w_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in wt.items() if v[1]}}
+
     # ---- context: a plain device copy of the same size class (practical streaming ceiling)
     a_src, a_dst = sets[0].W[0], sets[0].Z
     for _ in range(5):
@@ -268,6 +307,7 @@ def main():
         "kernel_us_per_step_sum": round(sum(kernel_us_per_step.values()), 2),
         "copy_GBps": round(copy_gbps, 1),
         "frozen_mask_step": frozen,
+        "weighted_step": weighted,
         "verified_against_oracle": verify,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -182,6 +182,63 @@ int hsadmm_compact(const hsadmm_plan_t* plan, const float* src, const uint8_t* m
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Tensor shrinkage of the pre-transmission buffer c = z_i + v_i (Section
+ * 4.4.1; Algorithm 1, Phase 4): exactly hsadmm_compact applied to the
+ * element-wise fp32 sum src0 + src1, which is formed on the fly (no full-size
+ * temporary).  src0 and src1 are full-layout arenas, 16-byte aligned.
+ */
+int hsadmm_compact_sum(const hsadmm_plan_t* plan, const float* src0, const float* src1, const uint8_t* mask,
+                       float* packed, int64_t* layer_off, int32_t* kept_idx,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Weights of the dense node candidate, Eq. (9).  With P accelerators per
+ * node, M nodes, weight decay lambda and the layer's penalties rho_1, rho_2:
+ *     gamma = lambda / M + P rho_1 + rho_2
+ *     z~ = (1/gamma) [ rho_1 sum_j (theta_j + u_j) + rho_2 (z - v) ]
+ *        = a (Wbar + U) + b (z - v),   a = P rho_1 / gamma,  b = rho_2 / gamma
+ * (Wbar, U: means over the node's P replicas).  Host function, all pointers
+ * are HOST arrays of L entries; a, b are computed in fp64 and rounded once.
+ * Errors: INVALID_ARGUMENT (also when some gamma <= 0 or a penalty is negative).
+ */
+int hsadmm_node_coefficients(const double* rho1, const double* rho2, int32_t L, double lambda, int32_t M,
+                             int32_t P, float* a, float* b);
+
+/*
+ * Stores the per-layer weights a_l, b_l (HOST arrays of L floats) in the
+ * plan; hsadmm_project_weighted uses them.  A new plan holds a = 1, b = 0.
+ * Synchronous host-to-device copy: call it between steps (penalties adapt
+ * once per outer iteration), not while a hsadmm_project_weighted of this
+ * plan is in flight.  Errors: INVALID_ARGUMENT, HIP.
+ */
+int hsadmm_plan_set_node_weights(hsadmm_plan_t* plan, const float* a, const float* b);
+
+/*
+ * Steps (a)-(d) with the full candidate of Eq. (9):
+ *     t = Wbar + U;  q = Zg - Vd;  z~ = fl(fl(a_l t) + fl(b_l q))   (fp32, no fused multiply-add)
+ * then group norms, top-k and Z = Pi_S(z~) as in hsadmm_project, and the
+ * intra-node dual update U <- U + (Wbar - Z) of Eq. (12).
+ *   Zg   device, in: the global consensus z (full-layout arena)
+ *   Vd   device, in: the node's inter-node dual v_i (full-layout arena)
+ * All other arguments, alignment and aliasing rules as for hsadmm_project.
+ * Here neither output of a group follows from the other one, so the inputs
+ * are read twice (once for the norms, once for the final values).
+ * Errors: INVALID_ARGUMENT, WORKSPACE, UNSUPPORTED, HIP.
+ */
+int hsadmm_project_weighted(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                            float* U, const float* Zg, const float* Vd, float* Z, float* Wbar,
+                            uint8_t* mask, double* sqnorm,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Inter-node dual update, Eq. (13): Vd <- Vd + (Zi - Zg) on every layer
+ * (arena padding untouched).  Zi: the node's projected consensus; Zg: the new
+ * global consensus (e.g. the output of hsadmm_expand); Vd in/out.  All three
+ * are full-layout arenas, 16-byte aligned.  Errors: INVALID_ARGUMENT, HIP.
+ */
+int hsadmm_dual_inter(const hsadmm_plan_t* plan, const float* Zi, const float* Zg, float* Vd, void* hip_stream);
+
+/*
  * Step (e2), recovery: the inverse scatter.  Every element of every layer of
  * `dst` is written: kept positions receive their packed value, all others
  * exactly +0 (dst need not be cleared beforehand).  Segment offsets inside
@@ -218,7 +275,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 8
+#define HSADMM_KERNEL_COUNT 11
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

@@ -29,8 +29,9 @@ HIPCC_FLAGS = [
 EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hsadmm_project",
            "hsadmm_compact", "hsadmm_expand", "hsadmm_strerror", "hsadmm_version",
            "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name",
-           "hsadmm_project_frozen", "hsadmm_mask_or")
-KERNEL_COUNT = 8
+           "hsadmm_project_frozen", "hsadmm_mask_or", "hsadmm_compact_sum", "hsadmm_node_coefficients",
+           "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter")
+KERNEL_COUNT = 11
 
 
 class HsadmmError(RuntimeError):
@@ -87,6 +88,20 @@ def load_library():
     lib.hsadmm_project_frozen.restype = ctypes.c_int
     lib.hsadmm_mask_or.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp]
     lib.hsadmm_mask_or.restype = ctypes.c_int
+    lib.hsadmm_compact_sum.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_compact_sum.restype = ctypes.c_int
+    f64p = ctypes.POINTER(ctypes.c_double)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    lib.hsadmm_node_coefficients.argtypes = [f64p, f64p, ctypes.c_int32, ctypes.c_double, ctypes.c_int32,
+                                             ctypes.c_int32, f32p, f32p]
+    lib.hsadmm_node_coefficients.restype = ctypes.c_int
+    lib.hsadmm_plan_set_node_weights.argtypes = [vp, f32p, f32p]
+    lib.hsadmm_plan_set_node_weights.restype = ctypes.c_int
+    lib.hsadmm_project_weighted.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, vp,
+                                            ctypes.c_size_t, vp]
+    lib.hsadmm_project_weighted.restype = ctypes.c_int
+    lib.hsadmm_dual_inter.argtypes = [vp, vp, vp, vp, vp]
+    lib.hsadmm_dual_inter.restype = ctypes.c_int
     lib.hsadmm_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hsadmm_compact.restype = ctypes.c_int
     lib.hsadmm_expand.argtypes = [vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -230,6 +245,63 @@ def hsadmm_mask_or(plan: Plan, masks: Sequence, out, stream=None, check: bool = 
     rc = lib.hsadmm_mask_or(plan.handle, ptrs, M, _ptr(out), _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_mask_or")
+    return rc
+
+
+def hsadmm_node_coefficients(rho1, rho2, lam: float, M: int, P: int):
+    """Eq. (9) weights as two lists of L floats (host computation inside the library)."""
+    lib = load_library()
+    L = len(rho1)
+    r1 = (ctypes.c_double * L)(*[float(x) for x in rho1])
+    r2 = (ctypes.c_double * L)(*[float(x) for x in rho2])
+    a = (ctypes.c_float * L)()
+    b = (ctypes.c_float * L)()
+    rc = lib.hsadmm_node_coefficients(r1, r2, L, float(lam), int(M), int(P), a, b)
+    if rc != 0:
+        raise HsadmmError(rc, "hsadmm_node_coefficients")
+    return list(a), list(b)
+
+
+def hsadmm_plan_set_node_weights(plan: Plan, a, b) -> None:
+    lib = load_library()
+    L = plan.n_layers
+    if len(a) != L or len(b) != L:
+        raise ValueError("a and b need one entry per layer")
+    fa = (ctypes.c_float * L)(*[float(x) for x in a])
+    fb = (ctypes.c_float * L)(*[float(x) for x in b])
+    rc = lib.hsadmm_plan_set_node_weights(plan.handle, fa, fb)
+    if rc != 0:
+        raise HsadmmError(rc, "hsadmm_plan_set_node_weights")
+
+
+def hsadmm_project_weighted(plan: Plan, W_replicas: Sequence, U, Zg, Vd, Z, Wbar, mask, sqnorm, workspace,
+                            stream=None, workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_project_weighted(plan.handle, ptrs, R, _ptr(U), _ptr(Zg), _ptr(Vd), _ptr(Z), _ptr(Wbar),
+                                     _ptr(mask), _ptr(sqnorm), _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_project_weighted")
+    return rc
+
+
+def hsadmm_dual_inter(plan: Plan, Zi, Zg, Vd, stream=None, check: bool = True) -> int:
+    rc = load_library().hsadmm_dual_inter(plan.handle, _ptr(Zi), _ptr(Zg), _ptr(Vd), _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_dual_inter")
+    return rc
+
+
+def hsadmm_compact_sum(plan: Plan, src0, src1, mask, packed, layer_off, kept_idx, workspace, stream=None,
+                       workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    lib = load_library()
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_compact_sum(plan.handle, _ptr(src0), _ptr(src1), _ptr(mask), _ptr(packed), _ptr(layer_off),
+                                _ptr(kept_idx), _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_compact_sum")
     return rc
 
 

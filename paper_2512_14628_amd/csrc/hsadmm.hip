@@ -43,7 +43,7 @@ constexpr int kTileElems = 2048;                // target elements per work item
 constexpr int kWideRow = 2048;                  // rows at least this long are shared by the whole workgroup
 constexpr int kChanRows = 32;               // CHANNEL tiles: rows per row block
 constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
-constexpr int kVersion = 110;
+constexpr int kVersion = 120;
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -440,6 +440,226 @@ __global__ __launch_bounds__(kBlock) void mask_or_kernel(MaskOrArgs a, int M, in
         unsigned int any = 0;
         for (int i = 0; i < M; ++i) any |= a.m[i][g];
         out[g] = any != 0 ? 1 : 0;
+    }
+}
+
+// ------------------------------------------------------------------ full node update (Eq. (9)) and Eq. (13)
+
+struct WeightedArgs {
+    ProjectArgs p;
+    const float* Zg;      // global consensus z
+    const float* Vd;      // inter-node dual v_i
+    const float* coef;    // per layer: a_l, b_l
+};
+
+// z~ = fl(fl(a t) + fl(b q)) with t = Wbar + U, q = z - v, for 4 (or 1) adjacent elements; no stores.
+template <int R>
+__device__ __forceinline__ void wcand4(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
+                                       v4f& wb, v4f& u, v4f& zt)
+{
+    const int RR = R > 0 ? R : Rrt;
+    v4f s = ld4(w.p.W[0] + e);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) s = s + ld4(w.p.W[r] + e);
+    u = ld4(w.p.U + e);
+    const v4f q = ld4(w.Zg + e) - ld4(w.Vd + e);
+    wb = s * w.p.inv_R;
+    const v4f t = wb + u;
+    const v4f at = t * al;
+    const v4f bq = q * bl;
+    zt = at + bq;
+}
+
+template <int R>
+__device__ __forceinline__ void wcand1(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
+                                       float& wb, float& u, float& zt)
+{
+    const int RR = R > 0 ? R : Rrt;
+    float s = ld1(w.p.W[0] + e);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) s = s + ld1(w.p.W[r] + e);
+    u = ld1(w.p.U + e);
+    const float q = ld1(w.Zg + e) - ld1(w.Vd + e);
+    wb = s * w.p.inv_R;
+    const float t = wb + u;
+    const float at = t * al;
+    const float bq = q * bl;
+    zt = at + bq;
+}
+
+// Keys of the weighted candidate: the lane mappings and the order of additions of project_pass1,
+// but nothing is stored except keys / partial column sums (the selection must be known before
+// anything final can be written: neither output of a group follows from the other one here).
+template <int R>
+__global__ __launch_bounds__(kBlock) void weighted_keys(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt)
+{
+    __shared__ double wsum[kWaves];
+    __shared__ double part[kWaves][kWave * 4];
+    const WorkItem it = items[blockIdx.x];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const float al = w.coef[2 * it.layer], bl = w.coef[2 * it.layer + 1];
+    if (item_mode(it) != HSADMM_MODE_CHANNEL) {
+        const bool wide = it.lpr > kWave;
+        const int lpr = wide ? kBlock : it.lpr;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        const int rounds = (it.nr + rows_at_once - 1) / rows_at_once;
+        for (int rd = 0; rd < rounds; ++rd) {
+            const int rr = rd * rows_at_once + sub;
+            const bool active = rr < it.nr;
+            const int64_t base = it.base + (int64_t)rr * row_len;
+            double acc = 0.0;
+            if (active) {
+                if (vec) {
+                    const int nchunk = row_len >> 2;
+                    for (int c = j; c < nchunk; c += lpr) {
+                        v4f wb, u, zt;
+                        wcand4<R>(w, Rrt, base + ((int64_t)c << 2), al, bl, wb, u, zt);
+                        acc = sq4(acc, zt);
+                    }
+                } else {
+                    for (int c = j; c < row_len; c += lpr) {
+                        float wb, u, zt;
+                        wcand1<R>(w, Rrt, base + c, al, bl, wb, u, zt);
+                        acc = fma((double)zt, (double)zt, acc);
+                    }
+                }
+            }
+            if (!wide) {
+                acc = wave_xor_sum(acc, lpr);
+                if (active && j == 0) w.p.key[it.g0 + rr] = acc;
+            } else {
+                acc = wave_xor_sum(acc, kWave);
+                if (lane == 0) wsum[wave] = acc;
+                __syncthreads();
+                if (threadIdx.x == 0) {
+                    double s = wsum[0];
+                    for (int v = 1; v < kWaves; ++v) s += wsum[v];
+                    w.p.key[it.g0 + rr] = s;
+                }
+                __syncthreads();
+            }
+        }
+    } else {
+        const int vw = vec ? 4 : 1;
+        const int col = it.col0 + lane * vw;
+        const bool in = col < row_len;
+        double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+        if (in) {
+            for (int rr = wave; rr < it.nr; rr += kWaves) {
+                const int64_t e = it.base + (int64_t)rr * row_len + col;
+                if (vec) {
+                    v4f wb, u, zt;
+                    wcand4<R>(w, Rrt, e, al, bl, wb, u, zt);
+                    acc0 = fma((double)zt.x, (double)zt.x, acc0);
+                    acc1 = fma((double)zt.y, (double)zt.y, acc1);
+                    acc2 = fma((double)zt.z, (double)zt.z, acc2);
+                    acc3 = fma((double)zt.w, (double)zt.w, acc3);
+                } else {
+                    float wb, u, zt;
+                    wcand1<R>(w, Rrt, e, al, bl, wb, u, zt);
+                    acc0 = fma((double)zt, (double)zt, acc0);
+                }
+            }
+        }
+        part[wave][lane * 4 + 0] = acc0;
+        part[wave][lane * 4 + 1] = acc1;
+        part[wave][lane * 4 + 2] = acc2;
+        part[wave][lane * 4 + 3] = acc3;
+        __syncthreads();
+        if (wave == 0 && in) {
+            double* out = w.p.colpart + it.aux + col;
+            for (int i = 0; i < vw; ++i) {
+                double s = part[0][lane * 4 + i];
+                for (int v = 1; v < kWaves; ++v) s += part[v][lane * 4 + i];
+                out[i] = s;
+            }
+        }
+    }
+}
+
+// Final values once the mask is known: Z = z~ on kept groups, +0 elsewhere; U <- U + (Wbar - Z).
+template <int R>
+__global__ __launch_bounds__(kBlock) void weighted_final(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt,
+                                                         const uint8_t* __restrict__ mask)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int mode = item_mode(it);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const float al = w.coef[2 * it.layer], bl = w.coef[2 * it.layer + 1];
+    auto put4 = [&](int64_t e, bool k0, bool k1, bool k2, bool k3) {
+        v4f wb, u, zt;
+        wcand4<R>(w, Rrt, e, al, bl, wb, u, zt);
+        v4f z;
+        z.x = k0 ? zt.x : 0.f; z.y = k1 ? zt.y : 0.f; z.z = k2 ? zt.z : 0.f; z.w = k3 ? zt.w : 0.f;
+        st4(w.p.Z + e, z);
+        st4(w.p.U + e, u + (wb - z));
+        if (w.p.Wbar) st4(w.p.Wbar + e, wb);
+    };
+    auto put1 = [&](int64_t e, bool keep) {
+        float wb, u, zt;
+        wcand1<R>(w, Rrt, e, al, bl, wb, u, zt);
+        const float z = keep ? zt : 0.f;
+        st1(w.p.Z + e, z);
+        st1(w.p.U + e, u + (wb - z));
+        if (w.p.Wbar) st1(w.p.Wbar + e, wb);
+    };
+    if (mode != HSADMM_MODE_CHANNEL) {
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            const bool keep = mode == HSADMM_MODE_NONE || mask[it.g0 + rr] != 0;
+            const int64_t base = it.base + (int64_t)rr * row_len;
+            if (vec) {
+                const int nchunk = row_len >> 2;
+                for (int c = j; c < nchunk; c += lpr) put4(base + ((int64_t)c << 2), keep, keep, keep, keep);
+            } else {
+                for (int c = j; c < row_len; c += lpr) put1(base + c, keep);
+            }
+        }
+    } else {
+        const int vw = vec ? 4 : 1;
+        const int col = it.col0 + lane * vw;
+        if (col >= row_len) return;
+        const DivKhw div(it.khw);
+        bool k[4] = {true, true, true, true};
+        for (int i = 0; i < vw; ++i) k[i] = mask[it.g0 + div(col + i)] != 0;
+        for (int rr = wave; rr < it.nr; rr += kWaves) {
+            const int64_t e = it.base + (int64_t)rr * row_len + col;
+            if (vec) put4(e, k[0], k[1], k[2], k[3]);
+            else put1(e, k[0]);
+        }
+    }
+}
+
+// Eq. (13): v <- v + (z_i - z) over every layer.  A row item is one contiguous span of the arena.
+__global__ __launch_bounds__(kBlock) void dual_inter_kernel(const WorkItem* __restrict__ items,
+                                                            const float* __restrict__ Zi,
+                                                            const float* __restrict__ Zg, float* __restrict__ Vd)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int64_t len = (int64_t)it.nr * it.row_len;
+    if (item_vec(it)) {
+        for (int64_t c = threadIdx.x; c < (len >> 2); c += kBlock) {
+            const int64_t e = it.base + (c << 2);
+            const v4f d = ld4(Zi + e) - ld4(Zg + e);
+            st4(Vd + e, ld4(Vd + e) + d);
+        }
+    } else {
+        for (int64_t c = threadIdx.x; c < len; c += kBlock) {
+            const int64_t e = it.base + c;
+            const float d = Zi[e] - Zg[e];
+            Vd[e] = Vd[e] + d;
+        }
     }
 }
 
@@ -916,8 +1136,11 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
 
 // ------------------------------------------------------------------ compaction (gather)
 
+// SUM: the source is the element-wise sum of two arenas (c = z_i + v_i, Section 4.4.1), formed on the fly.
+template <bool SUM>
 __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restrict__ items,
                                                          const float* __restrict__ src,
+                                                         const float* __restrict__ src1,
                                                          const int32_t* __restrict__ pos,
                                                          const int32_t* __restrict__ cnt,
                                                          const int32_t* __restrict__ kept_idx, int n_layers,
@@ -938,12 +1161,17 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
             const int p = pos[it.g0 + rr];
             if (p < 0) continue;
             const float* s = src + it.base + (int64_t)rr * row_len;
+            const float* s1 = SUM ? src1 + it.base + (int64_t)rr * row_len : nullptr;
             float* d = out + (int64_t)p * row_len;
             if (item_vec(it)) {
                 const int nchunk = row_len >> 2;
-                for (int c = j; c < nchunk; c += lpr) st4u(d + 4 * c, ld4(s + 4 * c));
+                for (int c = j; c < nchunk; c += lpr) {
+                    v4f v = ld4(s + 4 * c);
+                    if (SUM) v = v + ld4(s1 + 4 * c);
+                    st4u(d + 4 * c, v);
+                }
             } else {
-                for (int c = j; c < row_len; c += lpr) d[c] = s[c];
+                for (int c = j; c < row_len; c += lpr) d[c] = SUM ? s[c] + s1[c] : s[c];
             }
         }
     } else {
@@ -959,6 +1187,8 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
         const int quads = out_len >> 2;
         for (int rr = wave; rr < it.nr; rr += kWaves) {
             const float* s = src + it.base + (int64_t)rr * row_len;
+            const float* s1 = SUM ? src1 + it.base + (int64_t)rr * row_len : nullptr;
+            auto at = [&](int idx) -> float { return SUM ? ld1(s + idx) + ld1(s1 + idx) : ld1(s + idx); };
             float* d = out + (int64_t)(it.col0 + rr) * out_len;
             for (int j4 = lane; j4 < quads; j4 += kWave) {
                 const int j = j4 << 2;
@@ -966,13 +1196,13 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
                 if (khw == 1) {
                     int4 c;
                     __builtin_memcpy(&c, kl + j, 16);
-                    v.x = ld1(s + c.x); v.y = ld1(s + c.y); v.z = ld1(s + c.z); v.w = ld1(s + c.w);
+                    v.x = at(c.x); v.y = at(c.y); v.z = at(c.z); v.w = at(c.w);
                 } else {
                     float t4[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int q = div(j + i);
-                        t4[i] = ld1(s + kl[q] * khw + (j + i - q * khw));
+                        t4[i] = at(kl[q] * khw + (j + i - q * khw));
                     }
                     v.x = t4[0]; v.y = t4[1]; v.z = t4[2]; v.w = t4[3];
                 }
@@ -980,7 +1210,7 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
             }
             for (int j = (quads << 2) + lane; j < out_len; j += kWave) {
                 const int q = div(j);
-                d[j] = s[kl[q] * khw + (j - q * khw)];
+                d[j] = at(kl[q] * khw + (j - q * khw));
             }
         }
     }
@@ -1070,7 +1300,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kKernelCount };
 constexpr size_t kTimingPairs = 8192;
 
 }  // namespace
@@ -1091,6 +1321,7 @@ struct hsadmm_plan {
     WorkItem* d_items_proj = nullptr;
     WorkItem* d_items_rows = nullptr;
     uint16_t* d_group_layer = nullptr;   // groups_total: layer of every group (bit 15: unconstrained layer)
+    float* d_coef = nullptr;             // 2L: a_l, b_l of Eq. (9), set by hsadmm_plan_set_node_weights (default 1, 0)
     uint16_t* d_chunk_layer = nullptr;   // per 16 groups: their layer if all 16 lie in one constrained layer, else 0xffff
     // Optional per-kernel timing (diagnostics; off by default).  Not thread-safe.
     bool timing = false;
@@ -1306,6 +1537,12 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     ok = ok && hipMalloc(&p->d_items_rows, br) == hipSuccess;
     ok = ok && hipMalloc(&p->d_group_layer, bg) == hipSuccess;
     ok = ok && hipMalloc(&p->d_chunk_layer, bc) == hipSuccess;
+    ok = ok && hipMalloc(&p->d_coef, sizeof(float) * 2 * p->layers.size()) == hipSuccess;
+    if (ok) {
+        std::vector<float> ones(2 * p->layers.size(), 0.f);
+        for (size_t l = 0; l < p->layers.size(); ++l) ones[2 * l] = 1.f;
+        ok = hipMemcpy(p->d_coef, ones.data(), sizeof(float) * ones.size(), hipMemcpyHostToDevice) == hipSuccess;
+    }
     ok = ok && hipMemcpy(p->d_group_layer, group_layer.data(), bg, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_chunk_layer, chunk_layer.data(), bc, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_layers, p->dev_layers.data(), bl, hipMemcpyHostToDevice) == hipSuccess;
@@ -1329,6 +1566,7 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
     if (p->d_group_layer) (void)hipFree(p->d_group_layer);
     if (p->d_chunk_layer) (void)hipFree(p->d_chunk_layer);
+    if (p->d_coef) (void)hipFree(p->d_coef);
     delete p;
 }
 
@@ -1425,26 +1663,133 @@ int hsadmm_mask_or(const hsadmm_plan_t* p, const uint8_t* const* masks, int32_t 
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
-int hsadmm_compact(const hsadmm_plan_t* p, const float* src, const uint8_t* mask, float* packed,
-                   int64_t* layer_off, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
-                   void* hip_stream)
+static int compact_impl(const hsadmm_plan_t* p, const float* src, const float* src1, bool sum, const uint8_t* mask,
+                        float* packed, int64_t* layer_off, int32_t* kept_idx, void* workspace,
+                        size_t workspace_bytes, void* hip_stream)
 {
-    if (!p || !src || !mask || !packed || !layer_off || !kept_idx || !workspace) return HSADMM_ERR_INVALID_ARGUMENT;
-    if (!is_aligned(src, 16) || !is_aligned(packed, 16) || !is_aligned(layer_off, 8) ||
-        !is_aligned(kept_idx, 4) || !is_aligned(workspace, 256))
+    if (!p || !src || (sum && !src1) || !mask || !packed || !layer_off || !kept_idx || !workspace)
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!is_aligned(src, 16) || (sum && !is_aligned(src1, 16)) || !is_aligned(packed, 16) ||
+        !is_aligned(layer_off, 8) || !is_aligned(kept_idx, 4) || !is_aligned(workspace, 256))
         return HSADMM_ERR_INVALID_ARGUMENT;
     if (workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
     const int rc = run_scan(p, mask, ws, layer_off, kept_idx, s);
     if (rc != HSADMM_OK) return rc;
-    const hipError_t e = launch(p, kGather, compact_gather, (unsigned)p->items_rows.size(), kBlock, s,
-                                (const WorkItem*)p->d_items_rows, src,
-                                reinterpret_cast<const int32_t*>(ws + p->ws.pos),
-                                reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (const int32_t*)kept_idx,
-                                (int)p->layers.size(), reinterpret_cast<const int64_t*>(ws + p->ws.layer_off), packed);
-    if (e != hipSuccess) return HSADMM_ERR_HIP;
+    const int32_t* pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
+    const int32_t* cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
+    const int64_t* lo = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
+    hipError_t e;
+    if (sum)
+        e = launch(p, kGather, compact_gather<true>, (unsigned)p->items_rows.size(), kBlock, s,
+                   (const WorkItem*)p->d_items_rows, src, src1, pos, cnt, (const int32_t*)kept_idx,
+                   (int)p->layers.size(), lo, packed);
+    else
+        e = launch(p, kGather, compact_gather<false>, (unsigned)p->items_rows.size(), kBlock, s,
+                   (const WorkItem*)p->d_items_rows, src, (const float*)nullptr, pos, cnt, (const int32_t*)kept_idx,
+                   (int)p->layers.size(), lo, packed);
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
+int hsadmm_compact(const hsadmm_plan_t* p, const float* src, const uint8_t* mask, float* packed,
+                   int64_t* layer_off, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
+                   void* hip_stream)
+{
+    return compact_impl(p, src, nullptr, false, mask, packed, layer_off, kept_idx, workspace, workspace_bytes,
+                        hip_stream);
+}
+
+int hsadmm_compact_sum(const hsadmm_plan_t* p, const float* src0, const float* src1, const uint8_t* mask,
+                       float* packed, int64_t* layer_off, int32_t* kept_idx, void* workspace,
+                       size_t workspace_bytes, void* hip_stream)
+{
+    return compact_impl(p, src0, src1, true, mask, packed, layer_off, kept_idx, workspace, workspace_bytes,
+                        hip_stream);
+}
+
+int hsadmm_node_coefficients(const double* rho1, const double* rho2, int32_t L, double lambda, int32_t M, int32_t P,
+                             float* a, float* b)
+{
+    if (!rho1 || !rho2 || !a || !b || L < 1 || M < 1 || P < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    for (int32_t l = 0; l < L; ++l) {
+        const double gamma = lambda / (double)M + (double)P * rho1[l] + rho2[l];
+        if (!(gamma > 0.0) || rho1[l] < 0.0 || rho2[l] < 0.0) return HSADMM_ERR_INVALID_ARGUMENT;
+        a[l] = (float)((double)P * rho1[l] / gamma);
+        b[l] = (float)(rho2[l] / gamma);
+    }
     return HSADMM_OK;
+}
+
+int hsadmm_plan_set_node_weights(hsadmm_plan_t* p, const float* a, const float* b)
+{
+    if (!p || !a || !b) return HSADMM_ERR_INVALID_ARGUMENT;
+    const size_t L = p->layers.size();
+    std::vector<float> ab;
+    try {
+        ab.resize(2 * L);
+    } catch (...) {
+        return HSADMM_ERR_HIP;
+    }
+    for (size_t l = 0; l < L; ++l) { ab[2 * l] = a[l]; ab[2 * l + 1] = b[l]; }
+    if (hipMemcpy(p->d_coef, ab.data(), sizeof(float) * ab.size(), hipMemcpyHostToDevice) != hipSuccess)
+        return HSADMM_ERR_HIP;
+    return HSADMM_OK;
+}
+
+int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
+                            const float* Zg, const float* Vd, float* Z, float* Wbar, uint8_t* mask, double* sqnorm,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!p || !W_replicas || !U || !Zg || !Vd || !Z || !mask || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
+    if (!is_aligned(U, 16) || !is_aligned(Z, 16) || !is_aligned(Zg, 16) || !is_aligned(Vd, 16) ||
+        (Wbar && !is_aligned(Wbar, 16)) || (sqnorm && !is_aligned(sqnorm, 8)) || !is_aligned(workspace, 256))
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    for (int r = 0; r < R; ++r)
+        if (!W_replicas[r] || !is_aligned(W_replicas[r], 16)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    WeightedArgs w{};
+    for (int r = 0; r < R; ++r) w.p.W[r] = W_replicas[r];
+    w.p.U = U; w.p.Z = Z; w.p.Wbar = Wbar;
+    w.p.key = sqnorm ? sqnorm : reinterpret_cast<double*>(ws + p->ws.key);
+    w.p.colpart = reinterpret_cast<double*>(ws + p->ws.colpart);
+    w.p.inv_R = 1.0f / (float)R;
+    w.Zg = Zg; w.Vd = Vd; w.coef = p->d_coef;
+    const unsigned grid = (unsigned)p->items_proj.size();
+    const WorkItem* items = p->d_items_proj;
+    hipError_t e;
+    switch (R) {
+        case 1: e = launch(p, kWKeys, weighted_keys<1>, grid, kBlock, s, items, w, (int)R); break;
+        case 2: e = launch(p, kWKeys, weighted_keys<2>, grid, kBlock, s, items, w, (int)R); break;
+        case 4: e = launch(p, kWKeys, weighted_keys<4>, grid, kBlock, s, items, w, (int)R); break;
+        case 8: e = launch(p, kWKeys, weighted_keys<8>, grid, kBlock, s, items, w, (int)R); break;
+        default: e = launch(p, kWKeys, weighted_keys<0>, grid, kBlock, s, items, w, (int)R); break;
+    }
+    if (e != hipSuccess) return HSADMM_ERR_HIP;
+    e = launch(p, kTopk, select_topk, (unsigned)p->layers.size(), kScanBlock, s,
+               (const DevLayer*)p->d_layers, w.p.key, (const double*)w.p.colpart, mask);
+    if (e != hipSuccess) return HSADMM_ERR_HIP;
+    const uint8_t* cm = mask;
+    switch (R) {
+        case 1: e = launch(p, kWFinal, weighted_final<1>, grid, kBlock, s, items, w, (int)R, cm); break;
+        case 2: e = launch(p, kWFinal, weighted_final<2>, grid, kBlock, s, items, w, (int)R, cm); break;
+        case 4: e = launch(p, kWFinal, weighted_final<4>, grid, kBlock, s, items, w, (int)R, cm); break;
+        case 8: e = launch(p, kWFinal, weighted_final<8>, grid, kBlock, s, items, w, (int)R, cm); break;
+        default: e = launch(p, kWFinal, weighted_final<0>, grid, kBlock, s, items, w, (int)R, cm); break;
+    }
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
+int hsadmm_dual_inter(const hsadmm_plan_t* p, const float* Zi, const float* Zg, float* Vd, void* hip_stream)
+{
+    if (!p || !Zi || !Zg || !Vd) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!is_aligned(Zi, 16) || !is_aligned(Zg, 16) || !is_aligned(Vd, 16)) return HSADMM_ERR_INVALID_ARGUMENT;
+    const hipError_t e = launch(p, kDualInter, dual_inter_kernel, (unsigned)p->items_rows.size(), kBlock,
+                                static_cast<hipStream_t>(hip_stream), (const WorkItem*)p->d_items_rows, Zi, Zg, Vd);
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
 int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* mask, float* dst,
@@ -1530,6 +1875,9 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kScatter: return "expand_scatter";
         case kFrozen: return "project_frozen";
         case kMaskOr: return "mask_or";
+        case kWKeys: return "weighted_keys";
+        case kWFinal: return "weighted_final";
+        case kDualInter: return "dual_inter";
         default: return "";
     }
 }

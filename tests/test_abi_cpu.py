@@ -83,3 +83,18 @@ def test_no_cpu_fallback_in_the_product_package():
         assert "oracle" not in src.replace("no CPU fallback", "")
     hip = open(os.path.join(ROOT, "paper_2512_14628_amd", "csrc", "hsadmm.hip")).read()
     assert "oracle" not in hip
+
+
+def test_node_coefficients_host_function_matches_the_oracle(lib):
+    """hsadmm_node_coefficients runs on the host (no device needed): same fp32 weights as the oracle's Eq. (9)."""
+    import oracle
+    rng = np.random.default_rng(1)
+    r1, r2 = rng.uniform(1e-4, 10, 40), rng.uniform(0, 10, 40)
+    for lam, M, P in ((1e-4, 16, 4), (0.0, 1, 1), (3e-2, 64, 8)):
+        a, b = pkg.hsadmm_node_coefficients(r1, r2, lam, M, P)
+        ao, bo = oracle.node_coefficients(r1, r2, lam, M, P)
+        assert np.array_equal(np.array(a, np.float32), ao) and np.array_equal(np.array(b, np.float32), bo)
+    with pytest.raises(pkg.HsadmmError):
+        pkg.hsadmm_node_coefficients([0.0], [0.0], 0.0, 1, 1)
+    with pytest.raises(pkg.HsadmmError):
+        pkg.hsadmm_node_coefficients([-1.0], [3.0], 0.0, 1, 1)
