@@ -73,6 +73,9 @@ def _load():
     lib.oracle_dual_inter.restype = ctypes.c_int
     lib.oracle_add_arenas.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, f32p, f32p, f32p]
     lib.oracle_add_arenas.restype = ctypes.c_int
+    lib.oracle_residuals.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, ctypes.POINTER(f32p), ctypes.c_int32,
+                                     f32p, f32p, f32p, f32p, f64p]
+    lib.oracle_residuals.restype = ctypes.c_int
     lib.oracle_mask_or.argtypes = [ctypes.c_int64, ctypes.POINTER(u8p), ctypes.c_int32, u8p]
     lib.oracle_mask_or.restype = ctypes.c_int
     _lib = lib
@@ -324,3 +327,24 @@ def add_arenas(table, A, B):
     if rc != 0:
         raise ValueError("oracle_add_arenas failed with code %d" % rc)
     return C
+
+
+def residuals(table, W, Zi, Zi_prev=None, Zg=None, Zg_prev=None):
+    """Squared residual norms per layer, float64 array [4, L]: intra primal (summed over replicas), intra dual,
+    inter primal, inter dual (the dual ones without their rho factors)."""
+    lib = _load()
+    t = _cols(table)
+    L = len(t["c_out"])
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    R = W.shape[0]
+    f32p = ctypes.POINTER(ctypes.c_float)
+    ptrs = (f32p * R)(*[_p(W[r], ctypes.c_float) for r in range(R)])
+    arrs = [None if a is None else np.ascontiguousarray(a, dtype=np.float32) for a in (Zi, Zi_prev, Zg, Zg_prev)]
+    out = np.full((4, L), np.nan, dtype=np.float64)
+    rc = lib.oracle_residuals(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                              _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32), ptrs, R,
+                              *[None if a is None else _p(a, ctypes.c_float) for a in arrs],
+                              _p(out, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("oracle_residuals failed with code %d" % rc)
+    return out

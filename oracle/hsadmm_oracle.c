@@ -474,3 +474,39 @@ int oracle_add_arenas(int32_t L, const int64_t *elem_off, const int32_t *c_out, 
     }
     return 0;
 }
+
+/*
+ * Layer-wise squared residual norms of Section 3.4 (last paragraph) / Algorithm 1 Phase 5, in fp64,
+ * accumulated sequentially in memory order (differences are formed in fp64 from the fp32 values):
+ *     out[0*L + l] = sum_j || theta_j - z_i ||_F^2      intra-node primal, summed over the node's R replicas
+ *     out[1*L + l] = || z_i - z_i_prev ||_F^2           intra-node dual, without its rho_1 factor
+ *     out[2*L + l] = || z_i - z ||_F^2                  inter-node primal
+ *     out[3*L + l] = || z - z_prev ||_F^2               inter-node dual, without its rho_2 factor
+ * Zi_prev, Zg, Zg_prev may be NULL; rows whose operands are missing are set to 0.
+ */
+int oracle_residuals(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                     const int32_t *khw, const float *const *W, int32_t R, const float *Zi,
+                     const float *Zi_prev, const float *Zg, const float *Zg_prev, double *out)
+{
+    if (L < 1 || R < 1 || !W || !Zi || !out) return -1;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t n = (int64_t)c_out[l] * c_in[l] * khw[l];
+        const int64_t off = elem_off[l];
+        double r_in = 0.0, s_in = 0.0, r_out = 0.0, s_out = 0.0;
+        for (int64_t e = 0; e < n; ++e) {
+            const double zi = (double)Zi[off + e];
+            for (int32_t r = 0; r < R; ++r) {
+                const double d = (double)W[r][off + e] - zi;
+                r_in += d * d;
+            }
+            if (Zi_prev) { const double d = zi - (double)Zi_prev[off + e]; s_in += d * d; }
+            if (Zg) { const double d = zi - (double)Zg[off + e]; r_out += d * d; }
+            if (Zg && Zg_prev) { const double d = (double)Zg[off + e] - (double)Zg_prev[off + e]; s_out += d * d; }
+        }
+        out[0 * (int64_t)L + l] = r_in;
+        out[1 * (int64_t)L + l] = s_in;
+        out[2 * (int64_t)L + l] = r_out;
+        out[3 * (int64_t)L + l] = s_out;
+    }
+    return 0;
+}

@@ -14,6 +14,7 @@ import oracle
 from tests import test_oracle_pins as pins
 from tests import test_oracle_frozen as fpins
 from tests import test_oracle_weighted as wpins
+from tests import test_oracle_residuals as rpins
 
 MUTATIONS = [
     ("tie_goes_to_higher_index", "(kl[h] == kl[g] && h < g)", "(kl[h] == kl[g] && h > g)"),
@@ -57,6 +58,11 @@ MUTATIONS = [
     ("weighted_dual_uses_candidate", "const float at = al * t;", "const float at = al * t; wbar[e] = t;"),
     ("dual_inter_sign", "Vd[off + e] = Vd[off + e] + (Zi[off + e] - Zg[off + e]);", "Vd[off + e] = Vd[off + e] + (Zg[off + e] - Zi[off + e]);"),
     ("add_arenas_subtracts", "C[off + e] = A[off + e] + B[off + e];", "C[off + e] = A[off + e] - B[off + e];"),
+    ("residual_in_fp32", "const double d = (double)W[r][off + e] - zi;", "const double d = (double)(W[r][off + e] - (float)zi);"),
+    ("residual_skips_a_replica", "for (int32_t r = 0; r < R; ++r) {\n                const double d = (double)W[r][off + e] - zi;", "for (int32_t r = 1; r < R; ++r) {\n                const double d = (double)W[r][off + e] - zi;"),
+    ("residual_abs_not_square", "const double d = zi - (double)Zi_prev[off + e]; s_in += d * d;", "const double d = zi - (double)Zi_prev[off + e]; s_in += fabs(d);"),
+    ("residual_rows_swapped", "out[1 * (int64_t)L + l] = s_in;\n        out[2 * (int64_t)L + l] = r_out;", "out[2 * (int64_t)L + l] = s_in;\n        out[1 * (int64_t)L + l] = r_out;"),
+    ("residual_inter_dual_uses_zi", "const double d = (double)Zg[off + e] - (double)Zg_prev[off + e]; s_out += d * d;", "const double d = zi - (double)Zg_prev[off + e]; s_out += d * d;"),
     ("filter_mask_prunes_channels_too", "if (mode != ORACLE_CHANNEL || ml[c]) k_in[b++]", "if (mode == ORACLE_NONE || ml[c % co]) k_in[b++]"),
 ]
 
@@ -83,6 +89,8 @@ PIN_FUNCS = [
     wpins.test_eq_9_printed_formula_with_per_replica_duals,
     lambda: [wpins.test_weighted_against_numpy(s) for s in range(2)],
     wpins.test_inter_node_dual_update_and_transmission_sum,
+    rpins.test_handworked_residuals,
+    rpins.test_residuals_against_numpy_and_their_zero_cases,
 ]
 
 
@@ -100,7 +108,7 @@ def test_a_planted_mistake_in_the_oracle_fails_a_pin(name, old, new, tmp_path, m
     lib = ctypes.CDLL(str(so_file))
     for fn in ("oracle_project", "oracle_compact", "oracle_expand", "oracle_set_threads", "oracle_get_threads",
                "oracle_project_frozen", "oracle_mask_or", "oracle_node_coefficients", "oracle_project_weighted",
-               "oracle_dual_inter", "oracle_add_arenas"):
+               "oracle_dual_inter", "oracle_add_arenas", "oracle_residuals"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(oracle, "_lib", lib)
