@@ -242,6 +242,27 @@ def main():
     torch.cuda.synchronize()
     wt = pkg.hsadmm_kernel_timing_read(plan)
     pkg.hsadmm_kernel_timing_enable(plan, False)
+    # layer-wise residual norms (Algorithm 1 Phase 5) with all four operands: (R + 4) arenas read
+    res_out = torch.zeros(4 * L, dtype=torch.float64, device=dev)
+
+    def residual_call():
+        b = sets[counter[0] % nsets]
+        counter[0] += 1
+        pkg.hsadmm_residuals(plan, b.W, b.Z, b.dst, b.Zg, b.Vd, res_out, b.ws, stream=stream)
+
+    for _ in range(3):
+        residual_call()
+    pkg.hsadmm_kernel_timing_enable(plan, True)
+    for _ in range(wsteps):
+        residual_call()
+    torch.cuda.synchronize()
+    rt = pkg.hsadmm_kernel_timing_read(plan)
+    pkg.hsadmm_kernel_timing_enable(plan, False)
+    r_us = 1e3 * (rt["residual_partials"][0] + rt["residual_finish"][0]) / max(1, rt["residual_partials"][1])
+    r_bytes = 4 * wl.n_total * (wl.R + 4)
+    residuals = {"us_per_call": round(r_us, 2), "algorithmic_bytes": r_bytes,
+                 "GBps": round(r_bytes / (r_us * 1e-6) / 1e9, 1),
+                 "hbm_frac": round(r_bytes / (r_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
     w_bytes = 4 * wl.n_total * (wl.R + 10) + 16 * nk
     weighted = {"ms_per_step": round(1e3 * w_elapsed, 4),
                 "algorithmic_bytes_per_step": w_bytes,
@@ -308,6 +329,7 @@ def main():
         "copy_GBps": round(copy_gbps, 1),
         "frozen_mask_step": frozen,
         "weighted_step": weighted,
+        "residuals": residuals,
         "verified_against_oracle": verify,
         "roofline": roofline,
         "cpu_baseline": cpu,

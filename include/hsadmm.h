@@ -239,6 +239,24 @@ int hsadmm_project_weighted(const hsadmm_plan_t* plan, const float* const* W_rep
 int hsadmm_dual_inter(const hsadmm_plan_t* plan, const float* Zi, const float* Zg, float* Vd, void* hip_stream);
 
 /*
+ * Layer-wise squared residual norms (Section 3.4, last paragraph; Algorithm
+ * 1, Phase 5), accumulated in fp64 from the fp32 values:
+ *     out[0*L + l] = sum over the R replicas of || W_r - Zi ||_F^2   (intra-node primal)
+ *     out[1*L + l] = || Zi - Zi_prev ||_F^2    (intra-node dual, without its rho_1 factor)
+ *     out[2*L + l] = || Zi - Zg ||_F^2         (inter-node primal)
+ *     out[3*L + l] = || Zg - Zg_prev ||_F^2    (inter-node dual, without its rho_2 factor)
+ * Zi_prev, Zg, Zg_prev may be NULL: rows whose operands are missing are 0.
+ *   out   device, 4*L doubles.  The order of additions is fixed (results are
+ *         reproducible run to run) but differs from a sequential sum.
+ * The thresholds and the penalty adaptation that consume these norms are
+ * host logic the paper leaves to its reference (Boyd et al.); not part of
+ * this library.  Errors: INVALID_ARGUMENT, WORKSPACE, UNSUPPORTED, HIP.
+ */
+int hsadmm_residuals(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                     const float* Zi, const float* Zi_prev, const float* Zg, const float* Zg_prev,
+                     double* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Step (e2), recovery: the inverse scatter.  Every element of every layer of
  * `dst` is written: kept positions receive their packed value, all others
  * exactly +0 (dst need not be cleared beforehand).  Segment offsets inside
@@ -275,7 +293,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 11
+#define HSADMM_KERNEL_COUNT 13
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

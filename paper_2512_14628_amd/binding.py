@@ -30,8 +30,8 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_compact", "hsadmm_expand", "hsadmm_strerror", "hsadmm_version",
            "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name",
            "hsadmm_project_frozen", "hsadmm_mask_or", "hsadmm_compact_sum", "hsadmm_node_coefficients",
-           "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter")
-KERNEL_COUNT = 11
+           "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals")
+KERNEL_COUNT = 13
 
 
 class HsadmmError(RuntimeError):
@@ -100,6 +100,8 @@ def load_library():
     lib.hsadmm_project_weighted.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, vp,
                                             ctypes.c_size_t, vp]
     lib.hsadmm_project_weighted.restype = ctypes.c_int
+    lib.hsadmm_residuals.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_residuals.restype = ctypes.c_int
     lib.hsadmm_dual_inter.argtypes = [vp, vp, vp, vp, vp]
     lib.hsadmm_dual_inter.restype = ctypes.c_int
     lib.hsadmm_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -284,6 +286,19 @@ def hsadmm_project_weighted(plan: Plan, W_replicas: Sequence, U, Zg, Vd, Z, Wbar
                                      _ptr(mask), _ptr(sqnorm), _ptr(workspace), wb, _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_project_weighted")
+    return rc
+
+
+def hsadmm_residuals(plan: Plan, W_replicas: Sequence, Zi, Zi_prev, Zg, Zg_prev, out, workspace, stream=None,
+                     workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_residuals(plan.handle, ptrs, R, _ptr(Zi), _ptr(Zi_prev), _ptr(Zg), _ptr(Zg_prev), _ptr(out),
+                              _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_residuals")
     return rc
 
 

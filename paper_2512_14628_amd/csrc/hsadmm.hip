@@ -43,7 +43,7 @@ constexpr int kTileElems = 2048;                // target elements per work item
 constexpr int kWideRow = 2048;                  // rows at least this long are shared by the whole workgroup
 constexpr int kChanRows = 32;               // CHANNEL tiles: rows per row block
 constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
-constexpr int kVersion = 120;
+constexpr int kVersion = 130;
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -54,6 +54,8 @@ struct DevLayer {
     int32_t c_out, c_in, khw, mode, k;
     int32_t G, group_base, row_len;
     int32_t n_rowblocks;    // CHANNEL: ceil(c_out / kChanRows)
+    int32_t rows_item0;     // first of this layer's row items (compact / expand / residual kernels)
+    int32_t rows_items;     // number of them
     int32_t pad_;
 };
 
@@ -660,6 +662,103 @@ __global__ __launch_bounds__(kBlock) void dual_inter_kernel(const WorkItem* __re
             const float d = Zi[e] - Zg[e];
             Vd[e] = Vd[e] + d;
         }
+    }
+}
+
+// ------------------------------------------------------------------ residual norms (Algorithm 1 Phase 5)
+
+struct ResidualArgs {
+    const float* W[HSADMM_MAX_REPLICAS];
+    const float* Zi;
+    const float* Zi_prev;   // may be null
+    const float* Zg;        // may be null
+    const float* Zg_prev;   // may be null
+    double* part;           // per row item: 4 partial sums
+};
+
+__device__ __forceinline__ double sqd(double acc, float a, float b)
+{
+    const double d = (double)a - (double)b;
+    return fma(d, d, acc);
+}
+
+// One workgroup per row item (a contiguous span of one layer): per-thread fp64 sums of the four
+// squared differences, combined by a butterfly per wave and in wave order through LDS.
+template <int R>
+__global__ __launch_bounds__(kBlock) void residual_partials(const WorkItem* __restrict__ items, ResidualArgs a, int Rrt)
+{
+    __shared__ double red[kWaves][4];
+    const int RR = R > 0 ? R : Rrt;
+    const WorkItem it = items[blockIdx.x];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t len = (int64_t)it.nr * it.row_len;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    if (item_vec(it)) {
+        for (int64_t c = threadIdx.x; c < (len >> 2); c += kBlock) {
+            const int64_t e = it.base + (c << 2);
+            const v4f zi = ld4(a.Zi + e);
+#pragma unroll
+            for (int r = 0; r < RR; ++r) {
+                const v4f w = ld4(a.W[r] + e);
+                s0 = sqd(s0, w.x, zi.x); s0 = sqd(s0, w.y, zi.y); s0 = sqd(s0, w.z, zi.z); s0 = sqd(s0, w.w, zi.w);
+            }
+            if (a.Zi_prev) {
+                const v4f p = ld4(a.Zi_prev + e);
+                s1 = sqd(s1, zi.x, p.x); s1 = sqd(s1, zi.y, p.y); s1 = sqd(s1, zi.z, p.z); s1 = sqd(s1, zi.w, p.w);
+            }
+            if (a.Zg) {
+                const v4f g = ld4(a.Zg + e);
+                s2 = sqd(s2, zi.x, g.x); s2 = sqd(s2, zi.y, g.y); s2 = sqd(s2, zi.z, g.z); s2 = sqd(s2, zi.w, g.w);
+                if (a.Zg_prev) {
+                    const v4f q = ld4(a.Zg_prev + e);
+                    s3 = sqd(s3, g.x, q.x); s3 = sqd(s3, g.y, q.y); s3 = sqd(s3, g.z, q.z); s3 = sqd(s3, g.w, q.w);
+                }
+            }
+        }
+    } else {
+        for (int64_t c = threadIdx.x; c < len; c += kBlock) {
+            const int64_t e = it.base + c;
+            const float zi = a.Zi[e];
+            for (int r = 0; r < RR; ++r) s0 = sqd(s0, a.W[r][e], zi);
+            if (a.Zi_prev) s1 = sqd(s1, zi, a.Zi_prev[e]);
+            if (a.Zg) {
+                s2 = sqd(s2, zi, a.Zg[e]);
+                if (a.Zg_prev) s3 = sqd(s3, a.Zg[e], a.Zg_prev[e]);
+            }
+        }
+    }
+    s0 = wave_xor_sum(s0, kWave); s1 = wave_xor_sum(s1, kWave);
+    s2 = wave_xor_sum(s2, kWave); s3 = wave_xor_sum(s3, kWave);
+    if (lane == 0) { red[wave][0] = s0; red[wave][1] = s1; red[wave][2] = s2; red[wave][3] = s3; }
+    __syncthreads();
+    if (threadIdx.x < 4) {
+        double t = red[0][threadIdx.x];
+        for (int w = 1; w < kWaves; ++w) t += red[w][threadIdx.x];
+        a.part[(int64_t)blockIdx.x * 4 + threadIdx.x] = t;
+    }
+}
+
+// One workgroup per layer: adds the layer's item partials (thread t takes items t, t+256, ... in
+// order; threads are combined by a butterfly per wave and in wave order), writes out[k*L + l].
+__global__ __launch_bounds__(kBlock) void residual_finish(const DevLayer* __restrict__ layers, int nL,
+                                                          const double* __restrict__ part, double* __restrict__ out)
+{
+    __shared__ double red[kWaves][4];
+    const int l = blockIdx.x;
+    const int first = layers[l].rows_item0, count = layers[l].rows_items;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int i = threadIdx.x; i < count; i += kBlock)
+        for (int k = 0; k < 4; ++k) s[k] += part[(int64_t)(first + i) * 4 + k];
+    for (int k = 0; k < 4; ++k) s[k] = wave_xor_sum(s[k], kWave);
+    if (lane == 0) for (int k = 0; k < 4; ++k) red[wave][k] = s[k];
+    __syncthreads();
+    if (threadIdx.x < 4) {
+        double t = red[0][threadIdx.x];
+        for (int w = 1; w < kWaves; ++w) t += red[w][threadIdx.x];
+        out[(int64_t)threadIdx.x * nL + l] = t;
     }
 }
 
@@ -1297,10 +1396,10 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct WsLayout {
-    size_t key, colpart, pos, cnt, layer_off, kept_idx, total;
+    size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kKernelCount };
 constexpr size_t kTimingPairs = 8192;
 
 }  // namespace
@@ -1487,7 +1586,9 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             gb += d.G;
             cap += (int64_t)x.c_out * d.row_len;
             cap = (cap + pack_align_elems - 1) / pack_align_elems * pack_align_elems;
+            d.rows_item0 = (int32_t)p->items_rows.size();
             add_row_items(p->items_rows, l, d, x.mode);
+            d.rows_items = (int32_t)p->items_rows.size() - d.rows_item0;
             if (x.mode == HSADMM_MODE_CHANNEL) add_tile_items(p->items_proj, l, d);
             else add_row_items(p->items_proj, l, d, x.mode);
             p->dev_layers.push_back(d);
@@ -1505,6 +1606,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->ws.cnt = off;        off = align_up(off + sizeof(int32_t) * (size_t)L * 2, 256);
         p->ws.layer_off = off;  off = align_up(off + sizeof(int64_t) * (size_t)(L + 1), 256);
         p->ws.kept_idx = off;   off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
+        p->ws.respart = off;    off = align_up(off + sizeof(double) * 4 * p->items_rows.size(), 256);
         p->ws.total = off;
     } catch (...) {   // host allocation failure while building the tables
         delete p;
@@ -1783,6 +1885,39 @@ int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replic
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
+int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, const float* Zi,
+                     const float* Zi_prev, const float* Zg, const float* Zg_prev, double* out, void* workspace,
+                     size_t workspace_bytes, void* hip_stream)
+{
+    if (!p || !W_replicas || !Zi || !out || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
+    if (!is_aligned(Zi, 16) || (Zi_prev && !is_aligned(Zi_prev, 16)) || (Zg && !is_aligned(Zg, 16)) ||
+        (Zg_prev && !is_aligned(Zg_prev, 16)) || !is_aligned(out, 8) || !is_aligned(workspace, 256))
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    for (int r = 0; r < R; ++r)
+        if (!W_replicas[r] || !is_aligned(W_replicas[r], 16)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    ResidualArgs a{};
+    for (int r = 0; r < R; ++r) a.W[r] = W_replicas[r];
+    a.Zi = Zi; a.Zi_prev = Zi_prev; a.Zg = Zg; a.Zg_prev = Zg_prev;
+    a.part = reinterpret_cast<double*>(static_cast<char*>(workspace) + p->ws.respart);
+    const unsigned grid = (unsigned)p->items_rows.size();
+    const WorkItem* items = p->d_items_rows;
+    hipError_t e;
+    switch (R) {
+        case 1: e = launch(p, kResPart, residual_partials<1>, grid, kBlock, s, items, a, (int)R); break;
+        case 2: e = launch(p, kResPart, residual_partials<2>, grid, kBlock, s, items, a, (int)R); break;
+        case 4: e = launch(p, kResPart, residual_partials<4>, grid, kBlock, s, items, a, (int)R); break;
+        case 8: e = launch(p, kResPart, residual_partials<8>, grid, kBlock, s, items, a, (int)R); break;
+        default: e = launch(p, kResPart, residual_partials<0>, grid, kBlock, s, items, a, (int)R); break;
+    }
+    if (e != hipSuccess) return HSADMM_ERR_HIP;
+    e = launch(p, kResFinish, residual_finish, (unsigned)p->layers.size(), kBlock, s,
+               (const DevLayer*)p->d_layers, (int)p->layers.size(), (const double*)a.part, out);
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
 int hsadmm_dual_inter(const hsadmm_plan_t* p, const float* Zi, const float* Zg, float* Vd, void* hip_stream)
 {
     if (!p || !Zi || !Zg || !Vd) return HSADMM_ERR_INVALID_ARGUMENT;
@@ -1878,6 +2013,8 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kWKeys: return "weighted_keys";
         case kWFinal: return "weighted_final";
         case kDualInter: return "dual_inter";
+        case kResPart: return "residual_partials";
+        case kResFinish: return "residual_finish";
         default: return "";
     }
 }
