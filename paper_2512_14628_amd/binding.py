@@ -52,7 +52,7 @@ def build_library(verbose: bool = False) -> str:
     """Compile csrc/hsadmm.hip for gfx950 with hipcc into libhsadmm.so (in-tree)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB_PATH + ".tmp.%d" % os.getpid()
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE_DIR, "-o", tmp, SRC_PATH]
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE_DIR, "-I", os.path.dirname(SRC_PATH), "-o", tmp, SRC_PATH]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if verbose or res.returncode != 0:
         print(res.stdout)

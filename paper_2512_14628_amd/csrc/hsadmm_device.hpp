@@ -1,0 +1,113 @@
+// Constants, work-item / argument structures and device helpers shared by every kernel.
+// Part of the single translation unit built from hsadmm.hip (included there, in order).
+#ifndef HSADMM_DEVICE_HPP
+#define HSADMM_DEVICE_HPP
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include "hsadmm.h"
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;                 // streaming kernels: 4 waves
+constexpr int kWaves = kBlock / kWave;
+constexpr int kScanBlock = 1024;            // select_topk and scan_mask
+constexpr int kScanWaves = kScanBlock / kWave;
+constexpr int kTileElems = 2048;                // target elements per work item
+constexpr int kWideRow = 2048;                  // rows at least this long are shared by the whole workgroup
+constexpr int kChanRows = 32;               // CHANNEL tiles: rows per row block
+constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
+constexpr int kVersion = 130;
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct DevLayer {
+    int64_t elem_off;
+    int64_t colpart_off;    // CHANNEL: first double of this layer's per-row-block column sums
+    int64_t unit;           // packed elements one kept group contributes (NONE: the whole layer)
+    int32_t c_out, c_in, khw, mode, k;
+    int32_t G, group_base, row_len;
+    int32_t n_rowblocks;    // CHANNEL: ceil(c_out / kChanRows)
+    int32_t rows_item0;     // first of this layer's row items (compact / expand / residual kernels)
+    int32_t rows_items;     // number of them
+    int32_t pad_;
+};
+
+// One unit of work for a 256-thread workgroup; it carries everything the streaming kernels need,
+// so a workgroup starts with a single 64-byte scalar load.
+//   row item  (FILTER / NONE in project kernels, every mode in compact / expand): rows [r0, r0+nr)
+//   tile item (CHANNEL in project kernels): rows [r0, r0+nr) x one column strip
+struct WorkItem {
+    int64_t base;       // arena element offset of the item's first row (column 0)
+    int64_t aux;        // tile: offset (doubles) of this row block's column sums in the workspace
+    int32_t g0;         // row item: index in mask/key/pos of the first row; tile: group_base
+    int32_t nr;         // rows
+    int32_t row_len;    // c_in * khw
+    int32_t lpr;        // row item: lanes sharing a row, power of two <= 64, or 256 (whole workgroup)
+    int32_t flags;      // bits 0-1: mode; bit 2: 128-bit path (row_len % 4 == 0)
+    int32_t col0;       // tile: first column of the strip; CHANNEL row item: index of the first row
+    int32_t khw;
+    int32_t layer;
+    int32_t pad_[4];
+};
+static_assert(sizeof(WorkItem) == 64, "WorkItem layout");
+
+__device__ __forceinline__ int item_mode(const WorkItem& it) { return it.flags & 3; }
+__device__ __forceinline__ bool item_vec(const WorkItem& it) { return (it.flags & 4) != 0; }
+
+struct ProjectArgs {
+    const float* W[HSADMM_MAX_REPLICAS];
+    float* U;
+    float* Z;
+    float* Wbar;      // may be null
+    double* key;      // groups_total
+    double* colpart;  // CHANNEL partial column sums
+    float inv_R;
+};
+
+// Streaming (touch-once) accesses.
+__device__ __forceinline__ v4f ld4(const float* p) { return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p)); }
+__device__ __forceinline__ void st4(float* p, v4f v) { __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p)); }
+__device__ __forceinline__ float ld1(const float* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void st1(float* p, float v) { __builtin_nontemporal_store(v, p); }
+// 128-bit access to an address that is only 4-byte aligned (segments of the packed buffer).
+__device__ __forceinline__ v4f ld4u(const float* p) { v4f v; __builtin_memcpy(&v, p, 16); return v; }
+__device__ __forceinline__ void st4u(float* p, v4f v) { __builtin_memcpy(p, &v, 16); }
+
+// j / khw for 0 <= j < 2^22 without an integer division: a float estimate corrected by one step.
+struct DivKhw {
+    int khw;
+    float rcp;
+    __device__ __forceinline__ explicit DivKhw(int k) : khw(k), rcp(1.0f / (float)k) {}
+    __device__ __forceinline__ int operator()(int j) const
+    {
+        if (khw == 1) return j;
+        if (j >= (1 << 22)) return j / khw;
+        int q = (int)((float)j * rcp);
+        if (q * khw > j) --q;
+        else if ((q + 1) * khw <= j) ++q;
+        return q;
+    }
+};
+
+__device__ __forceinline__ double wave_xor_sum(double a, int width)
+{
+    // butterfly over `width` adjacent lanes; every lane ends with the same bits
+    for (int o = width >> 1; o > 0; o >>= 1) a += __shfl_xor(a, o, kWave);
+    return a;
+}
+
+__device__ __forceinline__ int wave_sum_i32(int a)
+{
+    for (int o = kWave >> 1; o > 0; o >>= 1) a += __shfl_xor(a, o, kWave);
+    return a;
+}
+
+__device__ __forceinline__ long long wave_sum_i64(long long a)
+{
+    for (int o = kWave >> 1; o > 0; o >>= 1) a += __shfl_xor(a, o, kWave);
+    return a;
+}
+
+}  // namespace
+#endif

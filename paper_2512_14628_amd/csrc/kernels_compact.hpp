@@ -1,0 +1,328 @@
+// hsadmm_compact / hsadmm_expand: mask scan, gather into the packed buffer, zero fill + scatter back.
+// Part of the single translation unit built from hsadmm.hip (included there, in order).
+#ifndef KERNELS_COMPACT_HPP
+#define KERNELS_COMPACT_HPP
+#include "hsadmm_device.hpp"
+#include "kernels_select.hpp"
+
+namespace {
+
+// ------------------------------------------------------------------ mask scan (compact / expand)
+
+struct ScanOut {
+    int32_t* pos;        // groups_total: rank of a kept group inside its layer, -1 if pruned
+    int32_t* cnt;        // 2L: kept groups per layer, then the start of every layer's run in kept_idx
+    int64_t* layer_off;  // L+1, in the workspace (kept there for a later hsadmm_expand without a mask)
+    int64_t* layer_off_out;  // L+1, the caller's copy; may be null
+    int32_t* kept_idx;   // groups_total
+};
+
+__device__ __forceinline__ int nonzero_bytes(unsigned int x)
+{
+    // bit 7 of every byte becomes 1 iff the byte is nonzero
+    const unsigned int t = (((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) & 0x80808080u;
+    return __popc(t);
+}
+
+// One workgroup per layer.  Every workgroup counts the kept groups of all layers in one flat pass
+// over the mask, 16 groups per thread and step: chunk_layer gives the layer of a 16-group chunk that
+// lies inside one constrained layer (one 128-bit load, a popcount, and one LDS add per wave when
+// the whole wave sits in one layer); chunks that straddle layers or touch an unconstrained layer
+// (0xffff) go group by group through group_layer (bit 15 marks an unconstrained layer, whose groups
+// are always kept).  The workgroup then sums the aligned segment sizes of layers 0..l-1 to get its
+// segment offset and scans its own layer's mask.  Segment starts are multiples of pack_align, so
+// the offset is the plain sum of the rounded-up sizes.
+__global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restrict__ layers, int nL,
+                                                        int n_groups, int pack_align,
+                                                        const uint8_t* __restrict__ mask,
+                                                        const uint16_t* __restrict__ group_layer,
+                                                        const uint16_t* __restrict__ chunk_layer, ScanOut o)
+{
+    __shared__ int cnt[HSADMM_MAX_LAYERS];
+    __shared__ int wtot[kScanWaves];
+    __shared__ long long wsum[kScanWaves];
+    __shared__ int wkept[kScanWaves];
+    const int l = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const DevLayer L = layers[l];
+    // loads that depend on nothing but the thread index go first
+    long long unit_j = 0;
+    int none_j = 0;
+    if (tid < l) { unit_j = layers[tid].unit; none_j = layers[tid].mode == HSADMM_MODE_NONE; }
+    for (int j = tid; j < nL; j += kScanBlock) cnt[j] = 0;
+    __syncthreads();
+    const bool aligned16 = (reinterpret_cast<uintptr_t>(mask) & 15u) == 0;
+    const int nchunks = (n_groups + 15) >> 4;
+    for (int c0 = wave * kWave; c0 < nchunks; c0 += kScanBlock) {
+        const int c = c0 + lane;
+        unsigned int cl = 0xffffu;
+        int kept = 0;
+        bool slow = false;
+        unsigned int mw[4] = {0u, 0u, 0u, 0u};     // the chunk's 16 mask bytes
+        if (c < nchunks) {
+            cl = chunk_layer[c];
+            const bool full = 16 * c + 15 < n_groups;
+            if (full && aligned16) {
+                const uint4 m = reinterpret_cast<const uint4*>(mask)[c];
+                mw[0] = m.x; mw[1] = m.y; mw[2] = m.z; mw[3] = m.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int g = 16 * c + i;
+                    const unsigned int byte = (g < n_groups) ? mask[g] : 0u;
+                    mw[i >> 2] |= byte << (8 * (i & 3));
+                }
+            }
+            if (cl != 0xffffu) kept = nonzero_bytes(mw[0]) + nonzero_bytes(mw[1]) + nonzero_bytes(mw[2]) + nonzero_bytes(mw[3]);
+            else slow = true;
+        }
+        const unsigned int cl0 = __shfl(cl, 0, kWave);
+        if (cl0 != 0xffffu && __all((c >= nchunks) || cl == cl0)) {
+            const int tot = wave_sum_i32(kept);
+            if (lane == 0 && tot) atomicAdd(&cnt[cl0], tot);
+        } else {
+            if (cl != 0xffffu && kept) atomicAdd(&cnt[cl], kept);
+            if (slow) {
+                // mixed chunk: the 16 layer ids come with two 128-bit loads (a partial last chunk one by one);
+                // runs of one layer are counted in a register
+                unsigned int gl[16];
+                if (16 * c + 15 < n_groups) {
+                    const uint4 a0 = reinterpret_cast<const uint4*>(group_layer)[2 * c];
+                    const uint4 a1 = reinterpret_cast<const uint4*>(group_layer)[2 * c + 1];
+                    const unsigned int w8[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) gl[i] = (w8[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) gl[i] = (16 * c + i < n_groups) ? group_layer[16 * c + i] : 0xffffu;
+                }
+                int run_layer = -1, run = 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    if (gl[i] != 0xffffu) {
+                        const int lay = (int)(gl[i] & 0x7fffu);
+                        const unsigned int byte = (mw[i >> 2] >> (8 * (i & 3))) & 0xffu;
+                        if (lay != run_layer) {
+                            if (run) atomicAdd(&cnt[run_layer], run);
+                            run_layer = lay;
+                            run = 0;
+                        }
+                        run += ((gl[i] & 0x8000u) != 0 || byte != 0) ? 1 : 0;
+                    }
+                }
+                if (run) atomicAdd(&cnt[run_layer], run);
+            }
+        }
+    }
+    __syncthreads();
+    long long sz = 0;
+    int kept_before = 0;
+    if (tid < l) {
+        const int c = cnt[tid];
+        long long s = none_j ? unit_j : (long long)c * unit_j;
+        sz = (s + pack_align - 1) / pack_align * pack_align;
+        kept_before = c;
+    }
+    for (int j = tid + kScanBlock; j < l; j += kScanBlock) {    // more than 1024 layers
+        const int c = cnt[j];
+        long long s = (layers[j].mode == HSADMM_MODE_NONE) ? layers[j].unit : (long long)c * layers[j].unit;
+        sz += (s + pack_align - 1) / pack_align * pack_align;
+        kept_before += c;
+    }
+    sz = wave_sum_i64(sz);
+    kept_before = wave_sum_i32(kept_before);
+    if (lane == 0) { wsum[wave] = sz; wkept[wave] = kept_before; }
+    __syncthreads();
+    long long pos = 0;
+    int kb = 0;
+#pragma unroll
+    for (int w = 0; w < kScanWaves; ++w) { pos += wsum[w]; kb += wkept[w]; }
+    if (tid == 0) {
+        o.layer_off[l] = pos;
+        if (o.layer_off_out) o.layer_off_out[l] = pos;
+        o.cnt[l] = cnt[l];
+        o.cnt[nL + l] = kb;
+        if (l == nL - 1) {
+            long long s = (L.mode == HSADMM_MODE_NONE) ? L.unit : (long long)cnt[l] * L.unit;
+            s = (s + pack_align - 1) / pack_align * pack_align;
+            o.layer_off[nL] = pos + s;
+            if (o.layer_off_out) o.layer_off_out[nL] = pos + s;
+        }
+    }
+    const int G = L.G;
+    int carry = 0;
+    for (int base = 0; base < G; base += kScanBlock) {
+        const int g = base + tid;
+        const bool m = (g < G) && (L.mode == HSADMM_MODE_NONE || mask[L.group_base + g] != 0);
+        int total;
+        const int rank = carry + block_excl_scan<kScanWaves>(m, wtot, total);
+        if (g < G) {
+            o.pos[L.group_base + g] = m ? rank : -1;
+            if (m) o.kept_idx[kb + rank] = g;
+        }
+        carry += total;
+    }
+}
+
+// ------------------------------------------------------------------ compaction (gather)
+
+// SUM: the source is the element-wise sum of two arenas (c = z_i + v_i, Section 4.4.1), formed on the fly.
+template <bool SUM>
+__global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restrict__ items,
+                                                         const float* __restrict__ src,
+                                                         const float* __restrict__ src1,
+                                                         const int32_t* __restrict__ pos,
+                                                         const int32_t* __restrict__ cnt,
+                                                         const int32_t* __restrict__ kept_idx, int n_layers,
+                                                         const int64_t* __restrict__ layer_off,
+                                                         float* __restrict__ packed)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    float* out = packed + layer_off[it.layer];
+    if (item_mode(it) != HSADMM_MODE_CHANNEL) {
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            const int p = pos[it.g0 + rr];
+            if (p < 0) continue;
+            const float* s = src + it.base + (int64_t)rr * row_len;
+            const float* s1 = SUM ? src1 + it.base + (int64_t)rr * row_len : nullptr;
+            float* d = out + (int64_t)p * row_len;
+            if (item_vec(it)) {
+                const int nchunk = row_len >> 2;
+                for (int c = j; c < nchunk; c += lpr) {
+                    v4f v = ld4(s + 4 * c);
+                    if (SUM) v = v + ld4(s1 + 4 * c);
+                    st4u(d + 4 * c, v);
+                }
+            } else {
+                for (int c = j; c < row_len; c += lpr) d[c] = SUM ? s[c] + s1[c] : s[c];
+            }
+        }
+    } else {
+        // packed row o holds the kept channels' khw-blocks in ascending channel order: packed column
+        // j = q*khw + t comes from source column kept[q]*khw + t.  it.col0 is the index of the item's
+        // first row inside the layer.  A wave takes a row; a lane gathers 4 adjacent packed columns
+        // and stores them with one 128-bit access.
+        const int kc = cnt[it.layer];
+        const int khw = it.khw;
+        const int out_len = kc * khw;
+        const int32_t* kl = kept_idx + cnt[n_layers + it.layer];
+        const DivKhw div(khw);
+        const int quads = out_len >> 2;
+        for (int rr = wave; rr < it.nr; rr += kWaves) {
+            const float* s = src + it.base + (int64_t)rr * row_len;
+            const float* s1 = SUM ? src1 + it.base + (int64_t)rr * row_len : nullptr;
+            auto at = [&](int idx) -> float { return SUM ? ld1(s + idx) + ld1(s1 + idx) : ld1(s + idx); };
+            float* d = out + (int64_t)(it.col0 + rr) * out_len;
+            for (int j4 = lane; j4 < quads; j4 += kWave) {
+                const int j = j4 << 2;
+                v4f v;
+                if (khw == 1) {
+                    int4 c;
+                    __builtin_memcpy(&c, kl + j, 16);
+                    v.x = at(c.x); v.y = at(c.y); v.z = at(c.z); v.w = at(c.w);
+                } else {
+                    float t4[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int q = div(j + i);
+                        t4[i] = at(kl[q] * khw + (j + i - q * khw));
+                    }
+                    v.x = t4[0]; v.y = t4[1]; v.z = t4[2]; v.w = t4[3];
+                }
+                st4u(d + j, v);
+            }
+            for (int j = (quads << 2) + lane; j < out_len; j += kWave) {
+                const int q = div(j);
+                d[j] = at(kl[q] * khw + (j - q * khw));
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ expansion (zero fill + scatter)
+
+__global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restrict__ items,
+                                                         const float* __restrict__ packed,
+                                                         const int32_t* __restrict__ pos,
+                                                         const int32_t* __restrict__ cnt,
+                                                         const int64_t* __restrict__ layer_off,
+                                                         float* __restrict__ dst)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const float* in = packed + layer_off[it.layer];
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    if (item_mode(it) != HSADMM_MODE_CHANNEL) {
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            const int p = pos[it.g0 + rr];
+            float* d = dst + it.base + (int64_t)rr * row_len;
+            const float* s = in + (int64_t)(p < 0 ? 0 : p) * row_len;
+            if (item_vec(it)) {
+                const int nchunk = row_len >> 2;
+                if (p >= 0) for (int c = j; c < nchunk; c += lpr) st4(d + 4 * c, ld4u(s + 4 * c));
+                else for (int c = j; c < nchunk; c += lpr) st4(d + 4 * c, zero4);
+            } else {
+                if (p >= 0) for (int c = j; c < row_len; c += lpr) d[c] = s[c];
+                else for (int c = j; c < row_len; c += lpr) d[c] = 0.f;
+            }
+        }
+    } else {
+        // a wave takes a row of dst; a lane fills 4 adjacent columns (kept ones from the packed row,
+        // the others +0) and stores them with one 128-bit access
+        const int kc = cnt[it.layer];
+        const int khw = it.khw;
+        const int in_len = kc * khw;
+        const DivKhw div(khw);
+        const int32_t* pl = pos + it.g0;
+        const int quads = item_vec(it) ? (row_len >> 2) : 0;
+        for (int rr = wave; rr < it.nr; rr += kWaves) {
+            float* d = dst + it.base + (int64_t)rr * row_len;
+            const float* s = in + (int64_t)(it.col0 + rr) * in_len;
+            for (int c4 = lane; c4 < quads; c4 += kWave) {
+                const int c = c4 << 2;
+                float t4[4];
+                if (khw == 1) {
+                    int4 p;
+                    __builtin_memcpy(&p, pl + c, 16);
+                    t4[0] = p.x >= 0 ? s[p.x] : 0.f;
+                    t4[1] = p.y >= 0 ? s[p.y] : 0.f;
+                    t4[2] = p.z >= 0 ? s[p.z] : 0.f;
+                    t4[3] = p.w >= 0 ? s[p.w] : 0.f;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int ch = div(c + i);
+                        const int p = pl[ch];
+                        t4[i] = p >= 0 ? s[p * khw + (c + i - ch * khw)] : 0.f;
+                    }
+                }
+                v4f v;
+                v.x = t4[0]; v.y = t4[1]; v.z = t4[2]; v.w = t4[3];
+                st4(d + c, v);
+            }
+            for (int c = (quads << 2) + lane; c < row_len; c += kWave) {
+                const int ch = div(c);
+                const int p = pl[ch];
+                d[c] = (p >= 0) ? s[p * khw + (c - ch * khw)] : 0.f;
+            }
+        }
+    }
+}
+
+}  // namespace
+#endif

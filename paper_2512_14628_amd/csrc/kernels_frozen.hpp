@@ -1,0 +1,131 @@
+// hsadmm_project_frozen (cached mask applied in one pass) and hsadmm_mask_or.
+// Part of the single translation unit built from hsadmm.hip (included there, in order).
+#ifndef KERNELS_FROZEN_HPP
+#define KERNELS_FROZEN_HPP
+#include "hsadmm_device.hpp"
+
+namespace {
+
+// ------------------------------------------------------------------ project under a frozen mask
+
+// Final values of 4 adjacent elements under a known mask (Algorithm 1 Phase 3, retraining branch:
+// z = z~ (.) m): kept element Z = V, U += Wbar - V; masked-out element Z = +0, U = U + Wbar (= V).
+template <int R>
+__device__ __forceinline__ void frozen4(const ProjectArgs& a, int Rrt, int64_t e, bool k0, bool k1, bool k2, bool k3)
+{
+    const int RR = R > 0 ? R : Rrt;
+    v4f s = ld4(a.W[0] + e);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+    const v4f u = ld4(a.U + e);
+    const v4f wb = s * a.inv_R;
+    const v4f v = wb + u;
+    v4f z;
+    z.x = k0 ? v.x : 0.f; z.y = k1 ? v.y : 0.f; z.z = k2 ? v.z : 0.f; z.w = k3 ? v.w : 0.f;
+    st4(a.Z + e, z);
+    st4(a.U + e, u + (wb - z));
+    if (a.Wbar) st4(a.Wbar + e, wb);
+}
+
+// two chunks of one row (same keep flag) with all loads issued before any store
+template <int R>
+__device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, bool keep)
+{
+    const int RR = R > 0 ? R : Rrt;
+    v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) {
+        const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
+        s0 = s0 + w0;
+        s1 = s1 + w1;
+    }
+    const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
+    const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
+    const v4f v0 = wb0 + u0, v1 = wb1 + u1;
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    const v4f z0 = keep ? v0 : zero4, z1 = keep ? v1 : zero4;
+    st4(a.Z + e0, z0);
+    st4(a.Z + e1, z1);
+    st4(a.U + e0, u0 + (wb0 - z0));
+    st4(a.U + e1, u1 + (wb1 - z1));
+    if (a.Wbar) { st4(a.Wbar + e0, wb0); st4(a.Wbar + e1, wb1); }
+}
+
+template <int R>
+__device__ __forceinline__ void frozen1(const ProjectArgs& a, int Rrt, int64_t e, bool keep)
+{
+    const int RR = R > 0 ? R : Rrt;
+    float s = ld1(a.W[0] + e);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
+    const float u = ld1(a.U + e);
+    const float wb = s * a.inv_R;
+    const float v = wb + u;
+    const float z = keep ? v : 0.f;
+    st1(a.Z + e, z);
+    st1(a.U + e, u + (wb - z));
+    if (a.Wbar) st1(a.Wbar + e, wb);
+}
+
+// Same work items and lane mappings as project_pass1; no keys, no second pass: every byte of the
+// replicas and of U is read once and Z and U are written once.
+template <int R>
+__global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
+                                                         const uint8_t* __restrict__ mask)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int mode = item_mode(it);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    if (mode != HSADMM_MODE_CHANNEL) {
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            const bool keep = mode == HSADMM_MODE_NONE || mask[it.g0 + rr] != 0;
+            const int64_t base = it.base + (int64_t)rr * row_len;
+            if (vec) {
+                const int nchunk = row_len >> 2;
+                int c = j;
+                for (; c + lpr < nchunk; c += 2 * lpr)
+                    frozen4x2<R>(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + lpr) << 2), keep);
+                if (c < nchunk) frozen4<R>(a, Rrt, base + ((int64_t)c << 2), keep, keep, keep, keep);
+            } else {
+                for (int c = j; c < row_len; c += lpr) frozen1<R>(a, Rrt, base + c, keep);
+            }
+        }
+    } else {
+        const int vw = vec ? 4 : 1;
+        const int col = it.col0 + lane * vw;
+        if (col >= row_len) return;
+        const DivKhw div(it.khw);
+        bool k[4] = {true, true, true, true};
+        for (int i = 0; i < vw; ++i) k[i] = mask[it.g0 + div(col + i)] != 0;
+        for (int rr = wave; rr < it.nr; rr += kWaves) {
+            const int64_t e = it.base + (int64_t)rr * row_len + col;
+            if (vec) frozen4<R>(a, Rrt, e, k[0], k[1], k[2], k[3]);
+            else frozen1<R>(a, Rrt, e, k[0]);
+        }
+    }
+}
+
+// Eq. (14): out = OR of M masks, 0 / 1 bytes.
+struct MaskOrArgs {
+    const uint8_t* m[HSADMM_MAX_MASKS];
+};
+
+__global__ __launch_bounds__(kBlock) void mask_or_kernel(MaskOrArgs a, int M, int64_t n, uint8_t* __restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x; g < n; g += stride) {
+        unsigned int any = 0;
+        for (int i = 0; i < M; ++i) any |= a.m[i][g];
+        out[g] = any != 0 ? 1 : 0;
+    }
+}
+
+}  // namespace
+#endif

@@ -1,0 +1,272 @@
+// hsadmm_project: streaming pass 1 (mean, candidate, fp64 group sums, speculative outputs) and the fix-up of pruned groups.
+// Part of the single translation unit built from hsadmm.hip (included there, in order).
+#ifndef KERNELS_PROJECT_HPP
+#define KERNELS_PROJECT_HPP
+#include "hsadmm_device.hpp"
+
+namespace {
+
+// ------------------------------------------------------------------ project, pass 1
+
+__device__ __forceinline__ double sq4(double acc, const v4f& v)
+{
+    acc = fma((double)v.x, (double)v.x, acc);
+    acc = fma((double)v.y, (double)v.y, acc);
+    acc = fma((double)v.z, (double)v.z, acc);
+    acc = fma((double)v.w, (double)v.w, acc);
+    return acc;
+}
+
+// Wbar, V and the dual value that is final if the group is kept, for 4 (or 1) adjacent elements.
+// R > 0: replica count known at compile time (loop unrolled, pointers stay in scalar registers);
+// R == 0: any replica count, taken from Rrt.
+template <int R>
+struct Cand {
+    // two independent 4-element chunks at once (twice the loads in flight)
+    static __device__ __forceinline__ double two(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, double acc)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) {
+            const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
+            s0 = s0 + w0;
+            s1 = s1 + w1;
+        }
+        const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
+        const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
+        const v4f v0 = wb0 + u0, v1 = wb1 + u1;
+        const v4f d0 = wb0 - v0, d1 = wb1 - v1;
+        st4(a.Z + e0, v0);
+        st4(a.Z + e1, v1);
+        st4(a.U + e0, u0 + d0);
+        st4(a.U + e1, u1 + d1);
+        if (a.Wbar) { st4(a.Wbar + e0, wb0); st4(a.Wbar + e1, wb1); }
+        acc = sq4(acc, v0);
+        return sq4(acc, v1);
+    }
+    static __device__ __forceinline__ v4f one(const ProjectArgs& a, int Rrt, int64_t e)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        v4f s = ld4(a.W[0] + e);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+        const v4f u = ld4(a.U + e);
+        const v4f wb = s * a.inv_R;
+        const v4f v = wb + u;
+        const v4f d = wb - v;
+        st4(a.Z + e, v);
+        st4(a.U + e, u + d);
+        if (a.Wbar) st4(a.Wbar + e, wb);
+        return v;
+    }
+    static __device__ __forceinline__ float scalar(const ProjectArgs& a, int Rrt, int64_t e)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        float s = ld1(a.W[0] + e);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
+        const float u = ld1(a.U + e);
+        const float wb = s * a.inv_R;
+        const float v = wb + u;
+        const float d = wb - v;
+        st1(a.Z + e, v);
+        st1(a.U + e, u + d);
+        if (a.Wbar) st1(a.Wbar + e, wb);
+        return v;
+    }
+};
+
+// Sum of squares of the part of one row that lane j of `step` lanes owns (chunks j, j+step, ...),
+// accumulated in increasing chunk order.
+template <int R>
+__device__ __forceinline__ double pass1_row(const ProjectArgs& a, int Rrt, int64_t base, int row_len, bool vec,
+                                            int j, int step)
+{
+    double acc = 0.0;
+    if (vec) {
+        const int nchunk = row_len >> 2;
+        int c = j;
+        for (; c + step < nchunk; c += 2 * step)
+            acc = Cand<R>::two(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + step) << 2), acc);
+        if (c < nchunk) acc = sq4(acc, Cand<R>::one(a, Rrt, base + ((int64_t)c << 2)));
+    } else {
+        for (int c = j; c < row_len; c += step) {
+            const float v = Cand<R>::scalar(a, Rrt, base + c);
+            acc = fma((double)v, (double)v, acc);
+        }
+    }
+    return acc;
+}
+
+// FILTER / NONE: a group is a row.  Short rows: `lpr` <= 64 lanes share a row and a wave covers
+// 64/lpr adjacent rows.  Long rows: the whole workgroup shares a row.  Per-lane sums are combined
+// by a butterfly inside the wave and (long rows) in wave order through LDS, so the order of
+// additions depends only on (row_len, lpr), never on where the row sits: equal groups get equal keys.
+template <int R>
+__device__ __forceinline__ void project_rows(const WorkItem& it, const ProjectArgs& a, int Rrt)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    if (it.lpr <= kWave) {
+        const int lpr = it.lpr;
+        const int rpw = kWave / lpr;
+        const int sub = lane / lpr;
+        const int j = lane - sub * lpr;
+        for (int rb = wave * rpw; rb < it.nr; rb += kWaves * rpw) {
+            const int rr = rb + sub;
+            const bool active = rr < it.nr;
+            double acc = 0.0;
+            if (active) acc = pass1_row<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr);
+            acc = wave_xor_sum(acc, lpr);
+            if (active && j == 0) a.key[it.g0 + rr] = acc;
+        }
+    } else {
+        __shared__ double wsum[kWaves];
+        for (int rr = 0; rr < it.nr; ++rr) {
+            double acc = pass1_row<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, threadIdx.x, kBlock);
+            acc = wave_xor_sum(acc, kWave);
+            if (lane == 0) wsum[wave] = acc;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double s = wsum[0];
+                for (int w = 1; w < kWaves; ++w) s += wsum[w];
+                a.key[it.g0 + rr] = s;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// CHANNEL: a group is a block of khw adjacent columns of the [c_out][row_len] view.  A tile is
+// (row block, column strip); each lane owns 4 (or 1) adjacent columns of the strip and walks down
+// the rows of its wave, accumulating per-column sums in registers.  The four waves' sums are added
+// in wave order through LDS and stored as this row block's partial column sums; the layer's selection later
+// adds row blocks and the khw columns of a channel in a fixed order.
+template <int R>
+__device__ __forceinline__ void project_tile(const WorkItem& it, const ProjectArgs& a, int Rrt)
+{
+    __shared__ double part[kWaves][kWave * 4];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const int vw = vec ? 4 : 1;
+    const int col = it.col0 + lane * vw;
+    const bool in = col < row_len;
+    double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+    if (in) {
+        for (int rr = wave; rr < it.nr; rr += kWaves) {
+            const int64_t e = it.base + (int64_t)rr * row_len + col;
+            if (vec) {
+                const v4f v = Cand<R>::one(a, Rrt, e);
+                acc0 = fma((double)v.x, (double)v.x, acc0);
+                acc1 = fma((double)v.y, (double)v.y, acc1);
+                acc2 = fma((double)v.z, (double)v.z, acc2);
+                acc3 = fma((double)v.w, (double)v.w, acc3);
+            } else {
+                const float v = Cand<R>::scalar(a, Rrt, e);
+                acc0 = fma((double)v, (double)v, acc0);
+            }
+        }
+    }
+    part[wave][lane * 4 + 0] = acc0;
+    part[wave][lane * 4 + 1] = acc1;
+    part[wave][lane * 4 + 2] = acc2;
+    part[wave][lane * 4 + 3] = acc3;
+    __syncthreads();
+    if (wave == 0 && in) {
+        double* out = a.colpart + it.aux + col;
+        for (int i = 0; i < vw; ++i) {
+            double s = part[0][lane * 4 + i];
+            for (int w = 1; w < kWaves; ++w) s += part[w][lane * 4 + i];
+            out[i] = s;
+        }
+    }
+}
+
+template <int R>
+__global__ __launch_bounds__(kBlock) void project_pass1(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt)
+{
+    const WorkItem it = items[blockIdx.x];
+    if (item_mode(it) == HSADMM_MODE_CHANNEL) project_tile<R>(it, a, Rrt);
+    else project_rows<R>(it, a, Rrt);
+}
+
+
+// ------------------------------------------------------------------ project, fix-up of pruned groups
+
+__global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restrict__ items,
+                                                        const uint8_t* __restrict__ mask,
+                                                        float* __restrict__ U, float* __restrict__ Z)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int mode = item_mode(it);
+    if (mode == HSADMM_MODE_NONE) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    if (mode == HSADMM_MODE_FILTER) {
+        // lanes-per-row mapping as in pass 1 (the mapping carries no arithmetic here)
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            if (mask[it.g0 + rr]) continue;
+            const int64_t base = it.base + (int64_t)rr * row_len;
+            if (vec) {
+                const int nchunk = row_len >> 2;
+                for (int c = j; c < nchunk; c += lpr) {
+                    const int64_t e = base + ((int64_t)c << 2);
+                    st4(U + e, ld4(Z + e));
+                    st4(Z + e, zero4);
+                }
+            } else {
+                for (int c = j; c < row_len; c += lpr) {
+                    st1(U + base + c, ld1(Z + base + c));
+                    st1(Z + base + c, 0.f);
+                }
+            }
+        }
+    } else {
+        const int vw = vec ? 4 : 1;
+        const int col = it.col0 + lane * vw;
+        if (col >= row_len) return;
+        bool pr[4] = {false, false, false, false};
+        bool any = false;
+        for (int i = 0; i < vw; ++i) {
+            pr[i] = mask[it.g0 + (col + i) / it.khw] == 0;
+            any = any || pr[i];
+        }
+        if (!any) return;
+        const bool all = pr[0] && pr[1] && pr[2] && pr[3];
+        for (int rr = wave; rr < it.nr; rr += kWaves) {
+            const int64_t e = it.base + (int64_t)rr * row_len + col;
+            if (vec) {
+                // a fully pruned quad moves as 128 bits; a partly pruned one stores its pruned
+                // elements one by one (merging through a read of U costs more traffic than it saves)
+                const v4f z = ld4(Z + e);
+                if (all) {
+                    st4(U + e, z);
+                    st4(Z + e, zero4);
+                } else {
+                    if (pr[0]) { st1(U + e + 0, z.x); st1(Z + e + 0, 0.f); }
+                    if (pr[1]) { st1(U + e + 1, z.y); st1(Z + e + 1, 0.f); }
+                    if (pr[2]) { st1(U + e + 2, z.z); st1(Z + e + 2, 0.f); }
+                    if (pr[3]) { st1(U + e + 3, z.w); st1(Z + e + 3, 0.f); }
+                }
+            } else {
+                U[e] = Z[e];
+                Z[e] = 0.f;
+            }
+        }
+    }
+}
+
+}  // namespace
+#endif

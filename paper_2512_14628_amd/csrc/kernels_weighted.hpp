@@ -1,0 +1,230 @@
+// hsadmm_project_weighted (full candidate of Eq. (9), two passes) and hsadmm_dual_inter (Eq. (13)).
+// Part of the single translation unit built from hsadmm.hip (included there, in order).
+#ifndef KERNELS_WEIGHTED_HPP
+#define KERNELS_WEIGHTED_HPP
+#include "hsadmm_device.hpp"
+
+namespace {
+
+// ------------------------------------------------------------------ full node update (Eq. (9)) and Eq. (13)
+
+struct WeightedArgs {
+    ProjectArgs p;
+    const float* Zg;      // global consensus z
+    const float* Vd;      // inter-node dual v_i
+    const float* coef;    // per layer: a_l, b_l
+};
+
+// z~ = fl(fl(a t) + fl(b q)) with t = Wbar + U, q = z - v, for 4 (or 1) adjacent elements; no stores.
+template <int R>
+__device__ __forceinline__ void wcand4(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
+                                       v4f& wb, v4f& u, v4f& zt)
+{
+    const int RR = R > 0 ? R : Rrt;
+    v4f s = ld4(w.p.W[0] + e);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) s = s + ld4(w.p.W[r] + e);
+    u = ld4(w.p.U + e);
+    const v4f q = ld4(w.Zg + e) - ld4(w.Vd + e);
+    wb = s * w.p.inv_R;
+    const v4f t = wb + u;
+    const v4f at = t * al;
+    const v4f bq = q * bl;
+    zt = at + bq;
+}
+
+template <int R>
+__device__ __forceinline__ void wcand1(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
+                                       float& wb, float& u, float& zt)
+{
+    const int RR = R > 0 ? R : Rrt;
+    float s = ld1(w.p.W[0] + e);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) s = s + ld1(w.p.W[r] + e);
+    u = ld1(w.p.U + e);
+    const float q = ld1(w.Zg + e) - ld1(w.Vd + e);
+    wb = s * w.p.inv_R;
+    const float t = wb + u;
+    const float at = t * al;
+    const float bq = q * bl;
+    zt = at + bq;
+}
+
+// Keys of the weighted candidate: the lane mappings and the order of additions of project_pass1,
+// but nothing is stored except keys / partial column sums (the selection must be known before
+// anything final can be written: neither output of a group follows from the other one here).
+template <int R>
+__global__ __launch_bounds__(kBlock) void weighted_keys(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt)
+{
+    __shared__ double wsum[kWaves];
+    __shared__ double part[kWaves][kWave * 4];
+    const WorkItem it = items[blockIdx.x];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const float al = w.coef[2 * it.layer], bl = w.coef[2 * it.layer + 1];
+    if (item_mode(it) != HSADMM_MODE_CHANNEL) {
+        const bool wide = it.lpr > kWave;
+        const int lpr = wide ? kBlock : it.lpr;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        const int rounds = (it.nr + rows_at_once - 1) / rows_at_once;
+        for (int rd = 0; rd < rounds; ++rd) {
+            const int rr = rd * rows_at_once + sub;
+            const bool active = rr < it.nr;
+            const int64_t base = it.base + (int64_t)rr * row_len;
+            double acc = 0.0;
+            if (active) {
+                if (vec) {
+                    const int nchunk = row_len >> 2;
+                    for (int c = j; c < nchunk; c += lpr) {
+                        v4f wb, u, zt;
+                        wcand4<R>(w, Rrt, base + ((int64_t)c << 2), al, bl, wb, u, zt);
+                        acc = sq4(acc, zt);
+                    }
+                } else {
+                    for (int c = j; c < row_len; c += lpr) {
+                        float wb, u, zt;
+                        wcand1<R>(w, Rrt, base + c, al, bl, wb, u, zt);
+                        acc = fma((double)zt, (double)zt, acc);
+                    }
+                }
+            }
+            if (!wide) {
+                acc = wave_xor_sum(acc, lpr);
+                if (active && j == 0) w.p.key[it.g0 + rr] = acc;
+            } else {
+                acc = wave_xor_sum(acc, kWave);
+                if (lane == 0) wsum[wave] = acc;
+                __syncthreads();
+                if (threadIdx.x == 0) {
+                    double s = wsum[0];
+                    for (int v = 1; v < kWaves; ++v) s += wsum[v];
+                    w.p.key[it.g0 + rr] = s;
+                }
+                __syncthreads();
+            }
+        }
+    } else {
+        const int vw = vec ? 4 : 1;
+        const int col = it.col0 + lane * vw;
+        const bool in = col < row_len;
+        double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+        if (in) {
+            for (int rr = wave; rr < it.nr; rr += kWaves) {
+                const int64_t e = it.base + (int64_t)rr * row_len + col;
+                if (vec) {
+                    v4f wb, u, zt;
+                    wcand4<R>(w, Rrt, e, al, bl, wb, u, zt);
+                    acc0 = fma((double)zt.x, (double)zt.x, acc0);
+                    acc1 = fma((double)zt.y, (double)zt.y, acc1);
+                    acc2 = fma((double)zt.z, (double)zt.z, acc2);
+                    acc3 = fma((double)zt.w, (double)zt.w, acc3);
+                } else {
+                    float wb, u, zt;
+                    wcand1<R>(w, Rrt, e, al, bl, wb, u, zt);
+                    acc0 = fma((double)zt, (double)zt, acc0);
+                }
+            }
+        }
+        part[wave][lane * 4 + 0] = acc0;
+        part[wave][lane * 4 + 1] = acc1;
+        part[wave][lane * 4 + 2] = acc2;
+        part[wave][lane * 4 + 3] = acc3;
+        __syncthreads();
+        if (wave == 0 && in) {
+            double* out = w.p.colpart + it.aux + col;
+            for (int i = 0; i < vw; ++i) {
+                double s = part[0][lane * 4 + i];
+                for (int v = 1; v < kWaves; ++v) s += part[v][lane * 4 + i];
+                out[i] = s;
+            }
+        }
+    }
+}
+
+// Final values once the mask is known: Z = z~ on kept groups, +0 elsewhere; U <- U + (Wbar - Z).
+template <int R>
+__global__ __launch_bounds__(kBlock) void weighted_final(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt,
+                                                         const uint8_t* __restrict__ mask)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int mode = item_mode(it);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const float al = w.coef[2 * it.layer], bl = w.coef[2 * it.layer + 1];
+    auto put4 = [&](int64_t e, bool k0, bool k1, bool k2, bool k3) {
+        v4f wb, u, zt;
+        wcand4<R>(w, Rrt, e, al, bl, wb, u, zt);
+        v4f z;
+        z.x = k0 ? zt.x : 0.f; z.y = k1 ? zt.y : 0.f; z.z = k2 ? zt.z : 0.f; z.w = k3 ? zt.w : 0.f;
+        st4(w.p.Z + e, z);
+        st4(w.p.U + e, u + (wb - z));
+        if (w.p.Wbar) st4(w.p.Wbar + e, wb);
+    };
+    auto put1 = [&](int64_t e, bool keep) {
+        float wb, u, zt;
+        wcand1<R>(w, Rrt, e, al, bl, wb, u, zt);
+        const float z = keep ? zt : 0.f;
+        st1(w.p.Z + e, z);
+        st1(w.p.U + e, u + (wb - z));
+        if (w.p.Wbar) st1(w.p.Wbar + e, wb);
+    };
+    if (mode != HSADMM_MODE_CHANNEL) {
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            const bool keep = mode == HSADMM_MODE_NONE || mask[it.g0 + rr] != 0;
+            const int64_t base = it.base + (int64_t)rr * row_len;
+            if (vec) {
+                const int nchunk = row_len >> 2;
+                for (int c = j; c < nchunk; c += lpr) put4(base + ((int64_t)c << 2), keep, keep, keep, keep);
+            } else {
+                for (int c = j; c < row_len; c += lpr) put1(base + c, keep);
+            }
+        }
+    } else {
+        const int vw = vec ? 4 : 1;
+        const int col = it.col0 + lane * vw;
+        if (col >= row_len) return;
+        const DivKhw div(it.khw);
+        bool k[4] = {true, true, true, true};
+        for (int i = 0; i < vw; ++i) k[i] = mask[it.g0 + div(col + i)] != 0;
+        for (int rr = wave; rr < it.nr; rr += kWaves) {
+            const int64_t e = it.base + (int64_t)rr * row_len + col;
+            if (vec) put4(e, k[0], k[1], k[2], k[3]);
+            else put1(e, k[0]);
+        }
+    }
+}
+
+// Eq. (13): v <- v + (z_i - z) over every layer.  A row item is one contiguous span of the arena.
+__global__ __launch_bounds__(kBlock) void dual_inter_kernel(const WorkItem* __restrict__ items,
+                                                            const float* __restrict__ Zi,
+                                                            const float* __restrict__ Zg, float* __restrict__ Vd)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int64_t len = (int64_t)it.nr * it.row_len;
+    if (item_vec(it)) {
+        for (int64_t c = threadIdx.x; c < (len >> 2); c += kBlock) {
+            const int64_t e = it.base + (c << 2);
+            const v4f d = ld4(Zi + e) - ld4(Zg + e);
+            st4(Vd + e, ld4(Vd + e) + d);
+        }
+    } else {
+        for (int64_t c = threadIdx.x; c < len; c += kBlock) {
+            const int64_t e = it.base + c;
+            const float d = Zi[e] - Zg[e];
+            Vd[e] = Vd[e] + d;
+        }
+    }
+}
+
+}  // namespace
+#endif
