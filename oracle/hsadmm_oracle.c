@@ -16,6 +16,9 @@
  *     mode 2, channel g:  W[:, g, :]   (G = c_in)
  *     mode 0, none:       unconstrained layer (Section 2.1, last sentence);
  *                         its c_out filters are all kept.
+ *     mode 3, both:       the intersection S_f ^ S_c of Section 2.1: c_out filter
+ *                         groups followed by c_in channel groups (G = c_out + c_in);
+ *                         k filters and k_in channels are kept.
  * Mask and key arrays hold the groups of all layers, concatenated in table
  * order.
  *
@@ -36,7 +39,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_NONE = 0, ORACLE_FILTER = 1, ORACLE_CHANNEL = 2 };
+enum { ORACLE_NONE = 0, ORACLE_FILTER = 1, ORACLE_CHANNEL = 2, ORACLE_BOTH = 3 };
 
 static int g_threads = 1;
 
@@ -52,11 +55,71 @@ int oracle_get_threads(void) { return g_threads; }
 
 static int64_t n_groups(int mode, int c_out, int c_in)
 {
+    if (mode == ORACLE_BOTH) return (int64_t)c_out + c_in;
     return mode == ORACLE_CHANNEL ? c_in : c_out;
 }
 
 /*
- * Steps (a)-(d) for every layer.
+ * One projection onto "at most kk nonzero groups" (Eq. (10) and the paragraph after it), applied in
+ * place to the layer x[co][ci][s]: squared Frobenius norm of every group of x as it stands
+ * (sequential fp64 sum in memory order), rank count (larger key first, lower index first among
+ * equals), +0 written over the groups not kept.  channel = 0: groups are filters x[g,:,:];
+ * channel = 1: groups are input channels x[:,g,:].  key, m: the G entries of this constraint.
+ */
+static void project_in_place(float *x, int64_t co, int64_t ci, int64_t s, int channel, int64_t kk,
+                             double *key, uint8_t *m)
+{
+    const int64_t G = channel ? ci : co;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < G; ++g) {
+        double acc = 0.0;
+        if (channel) {
+            for (int64_t o = 0; o < co; ++o)
+                for (int64_t t = 0; t < s; ++t) {
+                    const double y = (double)x[(o * ci + g) * s + t];
+                    acc += y * y;
+                }
+        } else {
+            for (int64_t t = 0; t < ci * s; ++t) {
+                const double y = (double)x[g * ci * s + t];
+                acc += y * y;
+            }
+        }
+        key[g] = acc;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < G; ++g) {
+        int64_t before = 0;
+        for (int64_t h = 0; h < G; ++h)
+            if (key[h] > key[g] || (key[h] == key[g] && h < g)) ++before;
+        m[g] = before < kk ? 1 : 0;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < co * ci * s; ++e) {
+        const int64_t g = channel ? (e / s) % ci : e / (ci * s);
+        if (!m[g]) x[e] = 0.0f;
+    }
+}
+
+/*
+ * Composite projection for S = S_f ^ S_c (Section 2.1; Section 3, paragraph after Eq. (10)): the
+ * individual projections applied one after the other, the filter projection first, the channel
+ * projection on its output.  The channel norms are therefore those of the tensor whose pruned
+ * filters are already zero.  (The channels selected can differ from those the opposite order
+ * selects: the paper's remark that the order does not matter holds for which kind of group each
+ * projection removes, rows or columns of the GEMM view, not for the selection itself.)
+ * key, m: c_out filter entries followed by c_in channel entries.
+ */
+static void project_composite(float *x, int64_t co, int64_t ci, int64_t s, int64_t k_out, int64_t k_in,
+                              double *key, uint8_t *m)
+{
+    project_in_place(x, co, ci, s, 0, k_out, key, m);
+    project_in_place(x, co, ci, s, 1, k_in, key + co, m + co);
+}
+
+/*
+ * Steps (a)-(d) for every layer.  (A layer under both constraints takes (b) and (c) from
+ * project_composite above; k_in is read for such layers only.)
  *
  *  (a) consensus average: Eq. (9) with lambda = 0 and rho_2 = 0 is the plain
  *      mean over the node's replicas; summed left to right in fp32, then
@@ -75,11 +138,11 @@ static int64_t n_groups(int mode, int c_out, int c_in)
  * non-finite input.
  */
 int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
-                   const int32_t *khw, const int32_t *mode, const int32_t *k,
+                   const int32_t *khw, const int32_t *mode, const int32_t *k, const int32_t *k_in,
                    const float *const *W, int32_t R, float *U, float *Z, float *Wbar,
                    uint8_t *mask, double *key)
 {
-    if (L < 1 || R < 1 || !W || !U || !Z || !mask || !key) return -1;
+    if (L < 1 || R < 1 || !W || !U || !Z || !mask || !key || !k_in) return -1;
     const float inv_R = 1.0f / (float)R;
     int64_t gbase = 0;
     for (int32_t l = 0; l < L; ++l) {
@@ -87,7 +150,9 @@ int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
         const int64_t n = co * ci * s;
         const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
         if (co < 1 || ci < 1 || s < 1) return -1;
-        if (mode[l] != ORACLE_NONE && (k[l] < 1 || k[l] > G)) return -1;
+        if (mode[l] == ORACLE_BOTH) {
+            if (k[l] < 1 || k[l] > co || k_in[l] < 1 || k_in[l] > ci) return -1;
+        } else if (mode[l] != ORACLE_NONE && (k[l] < 1 || k[l] > G)) return -1;
         const int64_t off = elem_off[l];
         float *wbar = (float *)malloc(sizeof(float) * (size_t)n);
         float *v = (float *)malloc(sizeof(float) * (size_t)n);
@@ -104,6 +169,21 @@ int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
             if (!isfinite(v[e])) bad = 1;
         }
         if (bad) { free(wbar); free(v); return -2; }
+
+        if (mode[l] == ORACLE_BOTH) {
+            /* (b), (c) under both constraints: v becomes Pi_S(v); then (d) */
+            project_composite(v, co, ci, s, k[l], k_in[l], key + gbase, mask + gbase);
+#pragma omp parallel for schedule(static)
+            for (int64_t e = 0; e < n; ++e) {
+                Z[off + e] = v[e];
+                U[off + e] = U[off + e] + (wbar[e] - v[e]);
+                if (Wbar) Wbar[off + e] = wbar[e];
+            }
+            free(wbar);
+            free(v);
+            gbase += G;
+            continue;
+        }
 
         /* (b): one fp64 key per group */
         double *kl = key + gbase;
@@ -167,15 +247,18 @@ int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
 
 /* Index sets of Section 4.4.1 ("Tensor Shrinkage"): the kept filters and kept channels of layer l,
  * ascending (the order nonzero-extraction gives).  A filter mask keeps all
- * channels, a channel mask keeps all filters, mode none keeps both whole. */
+ * channels, a channel mask keeps all filters, mode none keeps both whole; with
+ * both constraints the filter bytes ml[0..co) and the channel bytes
+ * ml[co..co+ci) each give their own set. */
 static void index_sets(int mode, int64_t co, int64_t ci, const uint8_t *ml,
                        int32_t *k_out, int64_t *n_out, int32_t *k_in, int64_t *n_in)
 {
     int64_t a = 0, b = 0;
+    const uint8_t *mc = mode == ORACLE_BOTH ? ml + co : ml;      /* channel bytes */
     for (int64_t o = 0; o < co; ++o)
-        if (mode != ORACLE_FILTER || ml[o]) k_out[a++] = (int32_t)o;
+        if ((mode != ORACLE_FILTER && mode != ORACLE_BOTH) || ml[o]) k_out[a++] = (int32_t)o;
     for (int64_t c = 0; c < ci; ++c)
-        if (mode != ORACLE_CHANNEL || ml[c]) k_in[b++] = (int32_t)c;
+        if ((mode != ORACLE_CHANNEL && mode != ORACLE_BOTH) || mc[c]) k_in[b++] = (int32_t)c;
     *n_out = a;
     *n_in = b;
 }
@@ -186,7 +269,7 @@ static void index_sets(int mode, int64_t co, int64_t ci, const uint8_t *ml,
  * with layer_off[0] = 0 and layer_off[l+1] = roundup(layer_off[l] + size_l,
  * pack_align).  Offsets are in elements.  kept_idx receives, layer after
  * layer, the ascending layer-local indices of the kept groups (for mode none:
- * 0..c_out-1).  Padding elements of `packed` are not written.  The number of
+ * 0..c_out-1; for both constraints: the kept filters, then the kept channels).  Padding elements of `packed` are not written.  The number of
  * kept groups comes from the mask, not from a k.
  * Returns 0 or -1.  *n_kept_idx (may be NULL) receives the entries written
  * to kept_idx.
@@ -214,10 +297,10 @@ int oracle_compact(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
             for (int64_t q = 0; q < n_in; ++q)
                 for (int64_t t = 0; t < s; ++t)
                     pl[(p * n_in + q) * s + t] = sl[((int64_t)k_out[p] * ci + k_in[q]) * s + t];
-        if (mode[l] == ORACLE_CHANNEL)
-            for (int64_t q = 0; q < n_in; ++q) kept_idx[nk++] = k_in[q];
-        else
+        if (mode[l] != ORACLE_CHANNEL)
             for (int64_t p = 0; p < n_out; ++p) kept_idx[nk++] = k_out[p];
+        if (mode[l] == ORACLE_CHANNEL || mode[l] == ORACLE_BOTH)
+            for (int64_t q = 0; q < n_in; ++q) kept_idx[nk++] = k_in[q];
         pos += n_out * n_in * s;
         pos = (pos + pack_align - 1) / pack_align * pack_align;
         layer_off[l + 1] = pos;
@@ -274,7 +357,8 @@ int oracle_expand(int32_t L, const int64_t *elem_off, const int32_t *c_out, cons
  *     z = z~ (.) m,
  * with the same candidate z~ = Wbar + U (steps (a), (b)) and the same dual update (d) as oracle_project.
  * mask: in, nonzero = kept, any number of kept groups per layer (a union of node masks keeps more than k);
- * groups of an unconstrained layer are kept whatever their mask bytes say.  Entries of a masked-out
+ * groups of an unconstrained layer are kept whatever their mask bytes say; under both constraints an
+ * entry is kept iff its filter byte and its channel byte are both nonzero.  Entries of a masked-out
  * group are exactly +0 (as the projection writes them), whatever the sign of the candidate.
  * Returns 0, -1 on a bad argument, -2 on a non-finite candidate.
  */
@@ -304,7 +388,8 @@ int oracle_project_frozen(int32_t L, const int64_t *elem_off, const int32_t *c_o
             int64_t g;
             if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;
             else g = e / (ci * s);
-            const int keep = mode[l] == ORACLE_NONE || ml[g] != 0;
+            int keep = mode[l] == ORACLE_NONE || ml[g] != 0;          /* both: g is the filter */
+            if (mode[l] == ORACLE_BOTH) keep = keep && ml[co + (e / s) % ci] != 0;
             const float z = keep ? v : 0.0f;
             Z[off + e] = z;
             U[off + e] = U[off + e] + (wbar - z);
@@ -361,11 +446,11 @@ int oracle_node_coefficients(int32_t L, const double *rho1, const double *rho2, 
  * Zg, Vd: in, full-layout arenas.  a, b: L fp32 weights.  Other arguments as for oracle_project.
  */
 int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
-                            const int32_t *khw, const int32_t *mode, const int32_t *k,
+                            const int32_t *khw, const int32_t *mode, const int32_t *k, const int32_t *k_in,
                             const float *const *W, int32_t R, float *U, const float *Zg, const float *Vd,
                             const float *a, const float *b, float *Z, float *Wbar, uint8_t *mask, double *key)
 {
-    if (L < 1 || R < 1 || !W || !U || !Zg || !Vd || !a || !b || !Z || !mask || !key) return -1;
+    if (L < 1 || R < 1 || !W || !U || !Zg || !Vd || !a || !b || !Z || !mask || !key || !k_in) return -1;
     const float inv_R = 1.0f / (float)R;
     int64_t gbase = 0;
     for (int32_t l = 0; l < L; ++l) {
@@ -373,7 +458,9 @@ int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c
         if (co < 1 || ci < 1 || s < 1) return -1;
         const int64_t n = co * ci * s;
         const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
-        if (mode[l] != ORACLE_NONE && (k[l] < 1 || k[l] > G)) return -1;
+        if (mode[l] == ORACLE_BOTH) {
+            if (k[l] < 1 || k[l] > co || k_in[l] < 1 || k_in[l] > ci) return -1;
+        } else if (mode[l] != ORACLE_NONE && (k[l] < 1 || k[l] > G)) return -1;
         const int64_t off = elem_off[l];
         float *wbar = (float *)malloc(sizeof(float) * (size_t)n);
         float *v = (float *)malloc(sizeof(float) * (size_t)n);
@@ -393,6 +480,19 @@ int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c
             if (!isfinite(v[e])) bad = 1;
         }
         if (bad) { free(wbar); free(v); return -2; }
+        if (mode[l] == ORACLE_BOTH) {
+            project_composite(v, co, ci, s, k[l], k_in[l], key + gbase, mask + gbase);
+#pragma omp parallel for schedule(static)
+            for (int64_t e = 0; e < n; ++e) {
+                Z[off + e] = v[e];
+                U[off + e] = U[off + e] + (wbar[e] - v[e]);
+                if (Wbar) Wbar[off + e] = wbar[e];
+            }
+            free(wbar);
+            free(v);
+            gbase += G;
+            continue;
+        }
         double *kl = key + gbase;
 #pragma omp parallel for schedule(static)
         for (int64_t g = 0; g < G; ++g) {

@@ -8,7 +8,7 @@ implementation).  Used by tests only.
 """
 import numpy as np
 
-NONE, FILTER, CHANNEL = 0, 1, 2
+NONE, FILTER, CHANNEL, BOTH = 0, 1, 2, 3
 
 
 def _layers(table):
@@ -17,7 +17,7 @@ def _layers(table):
     for l in range(L):
         co, ci, s = int(table["c_out"][l]), int(table["c_in"][l]), int(table["khw"][l])
         mode, k = int(table["mode"][l]), int(table["k"][l])
-        G = ci if mode == CHANNEL else co
+        G = ci if mode == CHANNEL else (co + ci if mode == BOTH else co)
         yield l, int(table["elem_off"][l]), co, ci, s, mode, k, G, gb
         gb += G
 
@@ -36,6 +36,24 @@ def project(table, W, U):
         wbar = (acc * (np.float32(1.0) / np.float32(R))).astype(np.float32)
         v = (wbar + U[off:off + n]).astype(np.float32)
         v3 = v.reshape(co, ci, s).astype(np.float64)
+        if mode == BOTH:
+            # the two projections one after the other: filters of v, then channels of what is left
+            x = v.reshape(co, ci, s).copy()
+            kf = np.sum(x.astype(np.float64) ** 2, axis=(1, 2))
+            mf = np.zeros(co, dtype=np.uint8)
+            mf[np.argsort(-kf, kind="stable")[:k]] = 1
+            x[mf == 0] = np.float32(0)
+            kc = np.sum(x.astype(np.float64) ** 2, axis=(0, 2))
+            mc = np.zeros(ci, dtype=np.uint8)
+            mc[np.argsort(-kc, kind="stable")[:int(table["k_in"][l])]] = 1
+            x[:, mc == 0] = np.float32(0)
+            z = x.reshape(-1)
+            Z[off:off + n] = z
+            U_new[off:off + n] = (U[off:off + n] + (wbar - z).astype(np.float32)).astype(np.float32)
+            Wbar[off:off + n] = wbar
+            masks.append(np.concatenate([mf, mc]))
+            keys.append(np.concatenate([kf, kc]))
+            continue
         if mode == CHANNEL:
             key = np.sum(v3 * v3, axis=(0, 2))
         else:
@@ -58,6 +76,8 @@ def project(table, W, U):
 
 
 def index_sets(mode, co, ci, m):
+    if mode == BOTH:
+        return np.nonzero(m[:co])[0], np.nonzero(m[co:])[0]
     k_out = np.nonzero(m)[0] if mode == FILTER else np.arange(co)
     k_in = np.nonzero(m)[0] if mode == CHANNEL else np.arange(ci)
     return k_out, k_in
@@ -75,7 +95,7 @@ def compact(table, src, mask, pack_align=1):
         pos += packed.size
         pos = -(-pos // pack_align) * pack_align
         offs.append(pos)
-        kept.append(k_in if mode == CHANNEL else k_out)
+        kept.append(np.concatenate([k_out, k_in]) if mode == BOTH else (k_in if mode == CHANNEL else k_out))
     out = np.zeros(pos, dtype=np.float32)
     for p, c in chunks:
         out[p:p + c.size] = c

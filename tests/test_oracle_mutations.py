@@ -15,6 +15,7 @@ from tests import test_oracle_pins as pins
 from tests import test_oracle_frozen as fpins
 from tests import test_oracle_weighted as wpins
 from tests import test_oracle_residuals as rpins
+from tests import test_oracle_composite as cpins
 
 MUTATIONS = [
     ("tie_goes_to_higher_index", "(kl[h] == kl[g] && h < g)", "(kl[h] == kl[g] && h > g)"),
@@ -38,10 +39,10 @@ MUTATIONS = [
     ("expand_no_zero_fill", "for (int64_t e = 0; e < n; ++e) dl[e] = 0.0f;", "for (int64_t e = 0; e < 0; ++e) dl[e] = 0.0f;"),
     ("none_layer_is_pruned", "if (mode[l] == ORACLE_NONE) {\n            for (int64_t g = 0; g < G; ++g) ml[g] = 1;",
      "if (0) {\n            for (int64_t g = 0; g < G; ++g) ml[g] = 1;"),
-    ("frozen_mask_inverted", "const int keep = mode[l] == ORACLE_NONE || ml[g] != 0;", "const int keep = mode[l] == ORACLE_NONE || ml[g] == 0;"),
-    ("frozen_ignores_mode_none", "const int keep = mode[l] == ORACLE_NONE || ml[g] != 0;", "const int keep = ml[g] != 0;"),
-    ("frozen_channel_group_wrong", "if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;\n            else g = e / (ci * s);\n            const int keep",
-     "if (mode[l] == ORACLE_CHANNEL) g = e % ci;\n            else g = e / (ci * s);\n            const int keep"),
+    ("frozen_mask_inverted", "int keep = mode[l] == ORACLE_NONE || ml[g] != 0;", "int keep = mode[l] == ORACLE_NONE || ml[g] == 0;"),
+    ("frozen_ignores_mode_none", "int keep = mode[l] == ORACLE_NONE || ml[g] != 0;", "int keep = ml[g] != 0;"),
+    ("frozen_channel_group_wrong", "if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;\n            else g = e / (ci * s);\n            int keep",
+     "if (mode[l] == ORACLE_CHANNEL) g = e % ci;\n            else g = e / (ci * s);\n            int keep"),
     ("frozen_dual_regrouped", "U[off + e] = U[off + e] + (wbar - z);\n            if (Wbar) Wbar[off + e] = wbar;\n        }\n        if (bad)",
      "U[off + e] = (U[off + e] + wbar) - z;\n            if (Wbar) Wbar[off + e] = wbar;\n        }\n        if (bad)"),
     ("frozen_multiplies_by_mask", "const float z = keep ? v : 0.0f;\n            Z[off + e] = z;\n            U[off + e] = U[off + e] + (wbar - z);\n            if (Wbar) Wbar[off + e] = wbar;\n        }\n        if (bad)",
@@ -63,7 +64,22 @@ MUTATIONS = [
     ("residual_abs_not_square", "const double d = zi - (double)Zi_prev[off + e]; s_in += d * d;", "const double d = zi - (double)Zi_prev[off + e]; s_in += fabs(d);"),
     ("residual_rows_swapped", "out[1 * (int64_t)L + l] = s_in;\n        out[2 * (int64_t)L + l] = r_out;", "out[2 * (int64_t)L + l] = s_in;\n        out[1 * (int64_t)L + l] = r_out;"),
     ("residual_inter_dual_uses_zi", "const double d = (double)Zg[off + e] - (double)Zg_prev[off + e]; s_out += d * d;", "const double d = zi - (double)Zg_prev[off + e]; s_out += d * d;"),
-    ("filter_mask_prunes_channels_too", "if (mode != ORACLE_CHANNEL || ml[c]) k_in[b++]", "if (mode == ORACLE_NONE || ml[c % co]) k_in[b++]"),
+    ("filter_mask_prunes_channels_too", "if ((mode != ORACLE_CHANNEL && mode != ORACLE_BOTH) || mc[c]) k_in[b++]", "if (mode == ORACLE_NONE || mc[c % co]) k_in[b++]"),
+    ("composite_channels_first", "project_in_place(x, co, ci, s, 0, k_out, key, m);\n    project_in_place(x, co, ci, s, 1, k_in, key + co, m + co);",
+     "project_in_place(x, co, ci, s, 1, k_in, key + co, m + co);\n    project_in_place(x, co, ci, s, 0, k_out, key, m);"),
+    ("composite_counts_swapped", "project_in_place(x, co, ci, s, 0, k_out, key, m);\n    project_in_place(x, co, ci, s, 1, k_in, key + co, m + co);",
+     "project_in_place(x, co, ci, s, 0, k_in, key, m);\n    project_in_place(x, co, ci, s, 1, k_out, key + co, m + co);"),
+    ("composite_stage_tie_rule", "(key[h] == key[g] && h < g)", "(key[h] == key[g] && h > g)"),
+    ("composite_stage_channel_transposed", "x[(o * ci + g) * s + t]", "x[(g * co + o) * s + t]"),
+    ("composite_stage_zeroes_wrong_group", "const int64_t g = channel ? (e / s) % ci : e / (ci * s);", "const int64_t g = channel ? e % ci : e / (ci * s);"),
+    ("composite_dual_regrouped", "U[off + e] = U[off + e] + (wbar[e] - v[e]);", "U[off + e] = (U[off + e] + wbar[e]) - v[e];"),
+    ("composite_channel_bytes_misplaced", "const uint8_t *mc = mode == ORACLE_BOTH ? ml + co : ml;", "const uint8_t *mc = mode == ORACLE_BOTH ? ml + ci : ml;"),
+    ("composite_kept_idx_channels_first", "if (mode[l] != ORACLE_CHANNEL)\n            for (int64_t p = 0; p < n_out; ++p) kept_idx[nk++] = k_out[p];\n        if (mode[l] == ORACLE_CHANNEL || mode[l] == ORACLE_BOTH)\n            for (int64_t q = 0; q < n_in; ++q) kept_idx[nk++] = k_in[q];",
+     "if (mode[l] == ORACLE_CHANNEL || mode[l] == ORACLE_BOTH)\n            for (int64_t q = 0; q < n_in; ++q) kept_idx[nk++] = k_in[q];\n        if (mode[l] != ORACLE_CHANNEL)\n            for (int64_t p = 0; p < n_out; ++p) kept_idx[nk++] = k_out[p];"),
+    ("composite_frozen_or_instead_of_and", "keep = keep && ml[co + (e / s) % ci] != 0;", "keep = keep || ml[co + (e / s) % ci] != 0;"),
+    ("composite_frozen_channel_byte_offset", "keep = keep && ml[co + (e / s) % ci] != 0;", "keep = keep && ml[(e / s) % ci] != 0;"),
+    ("composite_weighted_projects_filters_only", "project_composite(v, co, ci, s, k[l], k_in[l], key + gbase, mask + gbase);\n#pragma omp parallel for schedule(static)\n            for (int64_t e = 0; e < n; ++e) {\n                Z[off + e] = v[e];\n                U[off + e] = U[off + e] + (wbar[e] - v[e]);\n                if (Wbar) Wbar[off + e] = wbar[e];\n            }\n            free(wbar);\n            free(v);\n            gbase += G;\n            continue;\n        }\n        double *kl = key + gbase;\n#pragma omp",
+     "project_composite(v, co, ci, s, k[l], ci, key + gbase, mask + gbase);\n#pragma omp parallel for schedule(static)\n            for (int64_t e = 0; e < n; ++e) {\n                Z[off + e] = v[e];\n                U[off + e] = U[off + e] + (wbar[e] - v[e]);\n                if (Wbar) Wbar[off + e] = wbar[e];\n            }\n            free(wbar);\n            free(v);\n            gbase += G;\n            continue;\n        }\n        double *kl = key + gbase;\n#pragma omp"),
 ]
 
 PIN_FUNCS = [
@@ -91,6 +107,15 @@ PIN_FUNCS = [
     wpins.test_inter_node_dual_update_and_transmission_sum,
     rpins.test_handworked_residuals,
     rpins.test_residuals_against_numpy_and_their_zero_cases,
+    lambda: [cpins.test_handworked_composite_layer(c) for c in cpins.CASES],
+    cpins.test_the_selection_depends_on_the_order_and_the_oracle_takes_filters_first,
+    lambda: [cpins.test_composite_is_the_two_single_projections_applied_in_sequence(s) for s in range(2)],
+    lambda: [cpins.test_composite_against_numpy_library_routines(s) for s in range(2)],
+    cpins.test_separable_magnitudes_have_a_closed_form_answer,
+    cpins.test_invariants_feasibility_conservation_idempotence,
+    cpins.test_frozen_mask_under_both_constraints,
+    cpins.test_weighted_candidate_under_both_constraints,
+    cpins.test_union_of_composite_masks_packs_the_union_of_both_index_sets,
 ]
 
 

@@ -25,6 +25,7 @@ import numpy as np
 MODE_NONE = 0      # no constraint on this layer: every filter is kept
 MODE_FILTER = 1    # groups are output filters  W[g, :, :, :]
 MODE_CHANNEL = 2   # groups are input channels  W[:, g, :, :]
+MODE_BOTH = 3      # both constraints: c_out filter groups followed by c_in channel groups
 
 _TENSOR_W = 0
 _TENSOR_U = 1
@@ -41,6 +42,7 @@ class Layer:
     khw: int
     mode: int = MODE_NONE
     k: int = 0
+    k_in: int = 0              # MODE_BOTH only: channels kept (k is then the number of filters kept)
     elem_off: int = 0          # offset, in elements, inside every full-layout arena
     group_base: int = 0        # offset of this layer's groups in mask / sqnorm
 
@@ -50,10 +52,13 @@ class Layer:
 
     @property
     def groups(self) -> int:
+        if self.mode == MODE_BOTH:
+            return self.c_out + self.c_in
         return self.c_in if self.mode == MODE_CHANNEL else self.c_out
 
     @property
     def group_size(self) -> int:
+        """Elements per group (MODE_BOTH: of a filter group)."""
         return (self.c_out if self.mode == MODE_CHANNEL else self.c_in) * self.khw
 
     @property
@@ -64,6 +69,8 @@ class Layer:
     def kept_elems(self) -> int:
         if self.mode == MODE_NONE:
             return self.n
+        if self.mode == MODE_BOTH:
+            return self.k * self.k_in * self.khw
         return self.k * self.group_size
 
 
@@ -97,6 +104,7 @@ class Workload:
             "khw": np.array([l.khw for l in self.layers], dtype=np.int32),
             "mode": np.array([l.mode for l in self.layers], dtype=np.int32),
             "k": np.array([l.k for l in self.layers], dtype=np.int32),
+            "k_in": np.array([l.k_in for l in self.layers], dtype=np.int32),
         }
         return cols
 
@@ -169,12 +177,17 @@ def _resnet_bottleneck_shapes(blocks, mult=1, n_classes=1000):
     return s
 
 
-def _apply_policy(shapes, mode, keep, prune_fc):
+def _apply_policy(shapes, mode, keep, prune_fc, keep_in=None):
+    """keep_in: MODE_BOTH only, keep ratio of the input channels (keep is then that of the filters)."""
     layers = []
     for (name, co, ci, khw) in shapes:
         l = Layer(name, co, ci, khw)
         if name == "fc" and not prune_fc:
             l.mode, l.k = MODE_NONE, co
+        elif mode == MODE_BOTH:
+            l.mode = mode
+            l.k = keep_count(keep, co)
+            l.k_in = keep_count(keep_in, ci)
         else:
             l.mode = mode
             l.k = keep_count(keep, l.groups)
@@ -186,7 +199,7 @@ def _philox(seed: int, layer: int, tensor: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[int(seed), (int(layer) << 16) | int(tensor)]))
 
 
-WORKLOAD_NAMES = ("tiny", "resnet18", "resnet50", "resnet152", "wide")
+WORKLOAD_NAMES = ("tiny", "resnet18", "resnet50", "resnet152", "wide", "resnet50_both")
 
 
 def make_workload(name: str, seed: int = 0, prune_fc: Optional[bool] = None) -> Workload:
@@ -221,6 +234,12 @@ def make_workload(name: str, seed: int = 0, prune_fc: Optional[bool] = None) -> 
                       filter_scale_log10=(-3.0, 1.0),
                       description="ResNet-50 shapes with every width x4, output-filter groups, "
                                   "keep ~ U(0.2,0.8) per layer, per-filter scales 1e-3..1e1, R=8")
+    elif name == "resnet50_both":
+        layers = _apply_policy(_resnet_bottleneck_shapes((3, 4, 6, 3)), MODE_BOTH, 0.6, bool(prune_fc),
+                               keep_in=0.6)
+        wl = Workload(name, layers, R=4, seed=seed, sigma_replica=float(np.sqrt(1e-3)),
+                      description="ResNet-50 conv/fc weights, filter and channel constraints together "
+                                  "(keep 0.6 of the filters, then 0.6 of the channels), R=4")
     else:
         raise ValueError("unknown workload %r (have %s)" % (name, ", ".join(WORKLOAD_NAMES)))
     wl.n_arena, wl.groups_total = finalize(wl.layers)
@@ -228,8 +247,9 @@ def make_workload(name: str, seed: int = 0, prune_fc: Optional[bool] = None) -> 
 
 
 def custom_workload(shapes, R=1, seed=0, sigma_replica=0.0, name="custom") -> Workload:
-    """shapes: list of (c_out, c_in, khw, mode, k). For tests of odd shapes and edge cases."""
-    layers = [Layer("l%d" % i, co, ci, khw, mode, k) for i, (co, ci, khw, mode, k) in enumerate(shapes)]
+    """shapes: list of (c_out, c_in, khw, mode, k) or, for MODE_BOTH, (c_out, c_in, khw, mode, k, k_in).
+    For tests of odd shapes and edge cases."""
+    layers = [Layer("l%d" % i, *sh) for i, sh in enumerate(shapes)]
     for l in layers:
         if l.mode == MODE_NONE:
             l.k = l.c_out
