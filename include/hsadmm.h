@@ -18,8 +18,11 @@
  * (each replica, U, Z, Wbar, src, dst) share that table.  Groups (Section
  * 2.1): FILTER group g = W[g,:,:] (G = c_out), CHANNEL group g = W[:,g,:]
  * (G = c_in); a NONE layer is unconstrained and contributes G = c_out groups
- * that are always kept.  `mask` and `sqnorm` hold the groups of all layers
- * concatenated in table order.
+ * that are always kept.  A BOTH layer carries the intersection S_f ^ S_c of
+ * Section 2.1: its c_out filter groups are followed by its c_in channel
+ * groups (G = c_out + c_in), k filters and k_in channels are kept, and an
+ * element survives iff its filter and its channel both do.  `mask` and
+ * `sqnorm` hold the groups of all layers concatenated in table order.
  *
  * Ownership.  The caller owns every device buffer and the stream.  The
  * library owns only the plan (host tables plus a device copy, allocated in
@@ -57,6 +60,7 @@ extern "C" {
 #define HSADMM_MODE_NONE     0
 #define HSADMM_MODE_FILTER   1
 #define HSADMM_MODE_CHANNEL  2
+#define HSADMM_MODE_BOTH     3   /* FILTER | CHANNEL: both constraints on one layer */
 
 #define HSADMM_MAX_REPLICAS  16
 #define HSADMM_MAX_LAYERS    4096
@@ -69,7 +73,9 @@ typedef struct {
     int32_t c_in;       /* >= 1 */
     int32_t khw;        /* >= 1; K_H*K_W, 1 for linear layers */
     int32_t mode;       /* HSADMM_MODE_* */
-    int32_t k;          /* groups kept (the paper's alpha), 1 <= k <= G; ignored for MODE_NONE */
+    int32_t k;          /* groups kept (the paper's alpha), 1 <= k <= G; ignored for MODE_NONE;
+                           MODE_BOTH: filters kept (alpha_out), 1 <= k <= c_out */
+    int32_t k_in;       /* MODE_BOTH only: channels kept (alpha_in), 1 <= k_in <= c_in; ignored otherwise */
 } hsadmm_layer_t;
 
 typedef struct hsadmm_plan hsadmm_plan_t;   /* opaque; its tables never change after creation */
@@ -118,6 +124,11 @@ int hsadmm_plan_sizes(const hsadmm_plan_t* plan, int64_t* arena_elems, int64_t* 
  *   a group is kept iff fewer than k groups of its layer have a larger
  *   sqnorm, or an equal sqnorm and a lower index;
  *   Z = V on kept groups, +0 elsewhere;  U <- U + (Wbar - Z).
+ * MODE_BOTH layers (Section 3, paragraph after Eq. (10): the individual
+ * projections applied one after the other): the k filters are selected from
+ * the filter norms of V; the channel norms are then taken over the kept
+ * filters only (the pruned ones are already zero) and the k_in channels
+ * selected from them; sqnorm holds the filter norms, then these channel norms.
  *
  * All arena pointers must be 16-byte aligned.  Z, Wbar, mask, sqnorm and the
  * workspace must not alias each other or any input.  Padding elements of the
@@ -137,7 +148,9 @@ int hsadmm_project(const hsadmm_plan_t* plan, const float* const* W_replicas, in
  *
  *   mask   device, in, groups_total bytes, nonzero = kept; any number of kept
  *          groups per layer (e.g. the union hsadmm_mask_or gives); the groups
- *          of a MODE_NONE layer are kept whatever their bytes say.
+ *          of a MODE_NONE layer are kept whatever their bytes say; an element
+ *          of a MODE_BOTH layer is kept iff its filter byte and its channel
+ *          byte are both nonzero.
  * Masked-out entries of Z are exactly +0.  Other arguments, alignment and
  * aliasing rules as for hsadmm_project; no workspace is needed.
  * Errors: INVALID_ARGUMENT, UNSUPPORTED, HIP.
@@ -161,7 +174,7 @@ int hsadmm_mask_or(const hsadmm_plan_t* plan, const uint8_t* const* masks, int32
  *     packed[layer_off[l] + (p*|K_in| + q)*khw + t] = src[l][K_out[p]][K_in[q]][t]
  * where K_out / K_in are the ascending kept filter / channel indices the mask
  * gives (FILTER: K_in is every channel; CHANNEL: K_out is every filter; NONE:
- * both are everything).  The number of kept groups is read from the mask (any
+ * both are everything; BOTH: each set from its own part of the mask).  The number of kept groups is read from the mask (any
  * count 0..G), not from the plan's k, so a union of several masks is valid.
  *
  *   src        device, full-layout arena (read only), 16-byte aligned
@@ -173,8 +186,9 @@ int hsadmm_mask_or(const hsadmm_plan_t* plan, const uint8_t* const* masks, int32
  *              elements; layer_off[0] = 0, layer_off[l+1] =
  *              roundup(layer_off[l] + size_l, pack_align_elems)
  *   kept_idx   device, out, groups_total int32 capacity: per layer, the
- *              ascending layer-local indices of its kept groups, concatenated
- *              without gaps (entries past the total kept count are not written)
+ *              ascending layer-local indices of its kept groups (BOTH: the kept
+ *              filters, then the kept channels), concatenated without gaps
+ *              (entries past the total kept count are not written)
  * Errors: INVALID_ARGUMENT, WORKSPACE, HIP.
  */
 int hsadmm_compact(const hsadmm_plan_t* plan, const float* src, const uint8_t* mask,
@@ -293,7 +307,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 13
+#define HSADMM_KERNEL_COUNT 14
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

@@ -31,7 +31,7 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name",
            "hsadmm_project_frozen", "hsadmm_mask_or", "hsadmm_compact_sum", "hsadmm_node_coefficients",
            "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals")
-KERNEL_COUNT = 13
+KERNEL_COUNT = 14
 
 
 class HsadmmError(RuntimeError):
@@ -42,7 +42,8 @@ class HsadmmError(RuntimeError):
 
 class _Layer(ctypes.Structure):
     _fields_ = [("elem_off", ctypes.c_int64), ("c_out", ctypes.c_int32), ("c_in", ctypes.c_int32),
-                ("khw", ctypes.c_int32), ("mode", ctypes.c_int32), ("k", ctypes.c_int32)]
+                ("khw", ctypes.c_int32), ("mode", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("k_in", ctypes.c_int32)]
 
 
 _lib = None
@@ -159,7 +160,8 @@ def _stream(stream) -> Optional[int]:
 
 
 class Plan:
-    """Owner of an hsadmm_plan_t*.  `table` has the columns elem_off, c_out, c_in, khw, mode, k."""
+    """Owner of an hsadmm_plan_t*.  `table` has the columns elem_off, c_out, c_in, khw, mode, k and, when it
+    holds layers under both constraints (mode 3), k_in."""
 
     def __init__(self, table, pack_align_elems: int = 1):
         lib = load_library()
@@ -172,6 +174,7 @@ class Plan:
             arr[i].khw = int(table["khw"][i])
             arr[i].mode = int(table["mode"][i])
             arr[i].k = int(table["k"][i])
+            arr[i].k_in = int(table["k_in"][i]) if "k_in" in table else 0
         handle = ctypes.c_void_p()
         rc = lib.hsadmm_plan_create(arr, L, int(pack_align_elems), ctypes.byref(handle))
         self.handle = None

@@ -12,6 +12,8 @@
 //                   that lower indices win.                                  [Eq. (10)]
 //   project_fixup   touches pruned groups only: U <- V (taken from Z), Z <- +0.  For a pruned
 //                   group U + (Wbar - 0) equals V bit for bit, so no replica is read again.
+//   composite_colsums   layers under both constraints: channel norms over the kept filters, then a
+//                   second select_topk for the channels.   [Section 3, paragraph after Eq. (10)]
 //   scan_mask       per layer: kept count, exclusive positions, kept_idx, layer_off.
 //   compact_gather  packed <- src[K_out, K_in, :]                             [Eq. (15)]
 //   expand_scatter  dst <- zero fill + scatter of packed                      [Section 4.4.3]
@@ -53,7 +55,8 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kKernelCount };
+static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
 }  // namespace
@@ -63,6 +66,9 @@ struct hsadmm_plan {
     std::vector<DevLayer> dev_layers;
     std::vector<WorkItem> items_proj;   // project kernels
     std::vector<WorkItem> items_rows;   // compact / expand kernels
+    std::vector<WorkItem> items_both;   // composite_colsums: tiles of the layers under both constraints
+    std::vector<int32_t> both_layers;   // their indices
+    int32_t n_segments = 0;             // scan segments (one per layer, two per BOTH layer)
     int32_t pack_align = 1;
     int64_t arena_elems = 0;
     int64_t groups_total = 0;
@@ -73,9 +79,11 @@ struct hsadmm_plan {
     DevLayer* d_layers = nullptr;
     WorkItem* d_items_proj = nullptr;
     WorkItem* d_items_rows = nullptr;
-    uint16_t* d_group_layer = nullptr;   // groups_total: layer of every group (bit 15: unconstrained layer)
+    WorkItem* d_items_both = nullptr;
+    int32_t* d_both_layers = nullptr;
+    uint16_t* d_group_layer = nullptr;   // groups_total: scan segment of every group (bit 15: unconstrained layer)
     float* d_coef = nullptr;             // 2L: a_l, b_l of Eq. (9), set by hsadmm_plan_set_node_weights (default 1, 0)
-    uint16_t* d_chunk_layer = nullptr;   // per 16 groups: their layer if all 16 lie in one constrained layer, else 0xffff
+    uint16_t* d_chunk_layer = nullptr;   // per 16 groups: their segment if all 16 lie in one constrained segment, else 0xffff
     // Optional per-kernel timing (diagnostics; off by default).  Not thread-safe.
     bool timing = false;
     std::vector<hipEvent_t> ev;      // pairs: start, stop
@@ -107,15 +115,16 @@ void add_row_items(std::vector<WorkItem>& out, int layer, const DevLayer& d, int
     for (int r0 = 0; r0 < d.c_out; r0 += (int)want) {
         WorkItem it{};
         it.base = d.elem_off + (int64_t)r0 * d.row_len;
-        it.aux = 0;
+        it.aux = (mode == HSADMM_MODE_BOTH) ? (int64_t)d.group_base + d.c_out : 0;
         it.g0 = (mode == HSADMM_MODE_CHANNEL) ? d.group_base : d.group_base + r0;
         it.nr = (int)((d.c_out - r0) < want ? (d.c_out - r0) : want);
         it.row_len = d.row_len;
         it.lpr = lpr;
         it.flags = mode | (vec ? 4 : 0);
-        it.col0 = (mode == HSADMM_MODE_CHANNEL) ? r0 : 0;
+        it.col0 = 0;
         it.khw = d.khw;
         it.layer = layer;
+        it.row0 = r0;
         out.push_back(it);
     }
 }
@@ -138,6 +147,7 @@ void add_tile_items(std::vector<WorkItem>& out, int layer, const DevLayer& d)
             it.col0 = s * strip_cols;
             it.khw = d.khw;
             it.layer = layer;
+            it.row0 = r0;
             out.push_back(it);
         }
     }
@@ -175,6 +185,24 @@ hipError_t launch_frozen(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, co
     return launch(p, kFrozen, project_frozen<R>, (unsigned)p->items_proj.size(), kBlock, s,
                   (const WorkItem*)p->d_items_proj, a, Rrt, mask);
 }
+// Per-layer selection once the keys (FILTER, and the filters of BOTH) or the partial column sums
+// (CHANNEL) are in place.  Layers under both constraints then take their second projection: channel
+// norms over the kept filters from the candidate held in Z, and the selection of the channels.
+hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, const float* Z, uint8_t* mask,
+                         hipStream_t s)
+{
+    hipError_t e = launch(p, kTopk, select_topk, (unsigned)p->layers.size(), kScanBlock, s,
+                          (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
+                          (const int32_t*)nullptr, 0);
+    if (e != hipSuccess || p->both_layers.empty()) return e;
+    e = launch(p, kColsums, composite_colsums, (unsigned)p->items_both.size(), kBlock, s,
+               (const WorkItem*)p->d_items_both, Z, (const uint8_t*)mask, colpart);
+    if (e != hipSuccess) return e;
+    return launch(p, kTopk, select_topk, (unsigned)p->both_layers.size(), kScanBlock, s,
+                  (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
+                  (const int32_t*)p->d_both_layers, 1);
+}
+
 int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, int64_t* layer_off_out, int32_t* kept_idx,
              hipStream_t s)
 {
@@ -185,7 +213,8 @@ int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, int64_t* layer
     o.layer_off_out = layer_off_out;
     o.kept_idx = kept_idx;
     const hipError_t e = launch(p, kScan, scan_mask, (unsigned)p->layers.size(), kScanBlock, s,
-                                (const DevLayer*)p->d_layers, (int)p->layers.size(), (int)p->groups_total,
+                                (const DevLayer*)p->d_layers, (int)p->layers.size(), (int)p->n_segments,
+                                (int)p->groups_total,
                                 (int)p->pack_align, mask, (const uint16_t*)p->d_group_layer,
                                 (const uint16_t*)p->d_chunk_layer, o);
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
@@ -203,14 +232,16 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     for (int32_t l = 0; l < L; ++l) {
         const hsadmm_layer_t& x = layers[l];
         if (x.c_out < 1 || x.c_in < 1 || x.khw < 1) return HSADMM_ERR_INVALID_ARGUMENT;
-        if (x.mode != HSADMM_MODE_NONE && x.mode != HSADMM_MODE_FILTER && x.mode != HSADMM_MODE_CHANNEL)
+        if (x.mode != HSADMM_MODE_NONE && x.mode != HSADMM_MODE_FILTER && x.mode != HSADMM_MODE_CHANNEL &&
+            x.mode != HSADMM_MODE_BOTH)
             return HSADMM_ERR_INVALID_ARGUMENT;
         const int64_t row_len = (int64_t)x.c_in * x.khw;
         const int64_t n = row_len * x.c_out;
         if (row_len > INT32_MAX || n > INT32_MAX) return HSADMM_ERR_INVALID_ARGUMENT;
         if (x.elem_off < 0 || (x.elem_off % 4) != 0 || x.elem_off < prev_end) return HSADMM_ERR_INVALID_ARGUMENT;
-        const int32_t G = x.mode == HSADMM_MODE_CHANNEL ? x.c_in : x.c_out;
+        const int32_t G = x.mode == HSADMM_MODE_CHANNEL ? x.c_in : x.c_out;     // BOTH: k counts filters
         if (x.mode != HSADMM_MODE_NONE && (x.k < 1 || x.k > G)) return HSADMM_ERR_INVALID_ARGUMENT;
+        if (x.mode == HSADMM_MODE_BOTH && (x.k_in < 1 || x.k_in > x.c_in)) return HSADMM_ERR_INVALID_ARGUMENT;
         prev_end = x.elem_off + n;
     }
     hsadmm_plan* p = new (std::nothrow) hsadmm_plan();
@@ -221,22 +252,28 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->layers.assign(layers, layers + L);
         p->arena_elems = prev_end;
         int64_t gb = 0, cp = 0, cap = 0;
+        int32_t seg = 0;
         group_layer.clear();
         for (int32_t l = 0; l < L; ++l) {
             const hsadmm_layer_t& x = layers[l];
             DevLayer d{};
             d.elem_off = x.elem_off;
             d.c_out = x.c_out; d.c_in = x.c_in; d.khw = x.khw; d.mode = x.mode;
-            d.G = x.mode == HSADMM_MODE_CHANNEL ? x.c_in : x.c_out;
+            const bool both = x.mode == HSADMM_MODE_BOTH;
+            const bool has_colsums = x.mode == HSADMM_MODE_CHANNEL || both;
+            d.G = x.mode == HSADMM_MODE_CHANNEL ? x.c_in : (both ? x.c_out + x.c_in : x.c_out);
             d.k = x.mode == HSADMM_MODE_NONE ? d.G : x.k;
+            d.k_in = both ? x.k_in : 0;
+            d.seg0 = seg;
             d.group_base = (int32_t)gb;
             d.row_len = x.c_in * x.khw;
             d.n_rowblocks = (x.c_out + kChanRows - 1) / kChanRows;
             d.colpart_off = cp;
             if (x.mode == HSADMM_MODE_CHANNEL) d.unit = (int64_t)x.c_out * x.khw;
             else if (x.mode == HSADMM_MODE_FILTER) d.unit = d.row_len;
+            else if (both) d.unit = x.khw;
             else d.unit = (int64_t)x.c_out * d.row_len;
-            if (x.mode == HSADMM_MODE_CHANNEL) cp += (int64_t)d.n_rowblocks * d.row_len;
+            if (has_colsums) cp += (int64_t)d.n_rowblocks * d.row_len;
             gb += d.G;
             cap += (int64_t)x.c_out * d.row_len;
             cap = (cap + pack_align_elems - 1) / pack_align_elems * pack_align_elems;
@@ -245,10 +282,19 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             d.rows_items = (int32_t)p->items_rows.size() - d.rows_item0;
             if (x.mode == HSADMM_MODE_CHANNEL) add_tile_items(p->items_proj, l, d);
             else add_row_items(p->items_proj, l, d, x.mode);
+            if (both) {
+                add_tile_items(p->items_both, l, d);
+                p->both_layers.push_back(l);
+            }
             p->dev_layers.push_back(d);
-            for (int32_t g = 0; g < d.G; ++g)
-                group_layer.push_back((uint16_t)(l | (x.mode == HSADMM_MODE_NONE ? 0x8000 : 0)));
+            // scan segments: at most 2 * HSADMM_MAX_LAYERS = 8192, so an id fits below bit 15
+            for (int32_t g = 0; g < d.G; ++g) {
+                const int32_t sg = seg + ((both && g >= x.c_out) ? 1 : 0);
+                group_layer.push_back((uint16_t)(sg | (x.mode == HSADMM_MODE_NONE ? 0x8000 : 0)));
+            }
+            seg += both ? 2 : 1;
         }
+        p->n_segments = seg;
         if (gb > INT32_MAX) { delete p; return HSADMM_ERR_UNSUPPORTED; }
         p->groups_total = gb;
         p->colpart_total = cp;
@@ -257,7 +303,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->ws.key = off;        off = align_up(off + sizeof(double) * (size_t)gb, 256);
         p->ws.colpart = off;    off = align_up(off + sizeof(double) * (size_t)(cp ? cp : 1), 256);
         p->ws.pos = off;        off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
-        p->ws.cnt = off;        off = align_up(off + sizeof(int32_t) * (size_t)L * 2, 256);
+        p->ws.cnt = off;        off = align_up(off + sizeof(int32_t) * (size_t)L * 3, 256);
         p->ws.layer_off = off;  off = align_up(off + sizeof(int64_t) * (size_t)(L + 1), 256);
         p->ws.kept_idx = off;   off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
         p->ws.respart = off;    off = align_up(off + sizeof(double) * 4 * p->items_rows.size(), 256);
@@ -271,6 +317,8 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     const size_t bl = sizeof(DevLayer) * p->dev_layers.size();
     const size_t bp = sizeof(WorkItem) * p->items_proj.size();
     const size_t br = sizeof(WorkItem) * p->items_rows.size();
+    const size_t bb = sizeof(WorkItem) * p->items_both.size();
+    const size_t bbl = sizeof(int32_t) * p->both_layers.size();
     std::vector<uint16_t> chunk_layer;
     try {
         const size_t ng = group_layer.size();
@@ -291,6 +339,12 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     bool ok = hipMalloc(&p->d_layers, bl) == hipSuccess;
     ok = ok && hipMalloc(&p->d_items_proj, bp) == hipSuccess;
     ok = ok && hipMalloc(&p->d_items_rows, br) == hipSuccess;
+    if (bb) {
+        ok = ok && hipMalloc(&p->d_items_both, bb) == hipSuccess;
+        ok = ok && hipMalloc(&p->d_both_layers, bbl) == hipSuccess;
+        ok = ok && hipMemcpy(p->d_items_both, p->items_both.data(), bb, hipMemcpyHostToDevice) == hipSuccess;
+        ok = ok && hipMemcpy(p->d_both_layers, p->both_layers.data(), bbl, hipMemcpyHostToDevice) == hipSuccess;
+    }
     ok = ok && hipMalloc(&p->d_group_layer, bg) == hipSuccess;
     ok = ok && hipMalloc(&p->d_chunk_layer, bc) == hipSuccess;
     ok = ok && hipMalloc(&p->d_coef, sizeof(float) * 2 * p->layers.size()) == hipSuccess;
@@ -320,6 +374,8 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_layers) (void)hipFree(p->d_layers);
     if (p->d_items_proj) (void)hipFree(p->d_items_proj);
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
+    if (p->d_items_both) (void)hipFree(p->d_items_both);
+    if (p->d_both_layers) (void)hipFree(p->d_both_layers);
     if (p->d_group_layer) (void)hipFree(p->d_group_layer);
     if (p->d_chunk_layer) (void)hipFree(p->d_chunk_layer);
     if (p->d_coef) (void)hipFree(p->d_coef);
@@ -367,9 +423,7 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
         default: e = launch_pass1<0>(p, a, R, s); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
-    e = launch(p, kTopk, select_topk, (unsigned)p->layers.size(), kScanBlock, s,
-               (const DevLayer*)p->d_layers, a.key, (const double*)a.colpart, mask);
-    if (e != hipSuccess) return HSADMM_ERR_HIP;
+    if (run_selection(p, a.key, a.colpart, Z, mask, s) != hipSuccess) return HSADMM_ERR_HIP;
     e = launch(p, kFixup, project_fixup, (unsigned)p->items_proj.size(), kBlock, s,
                (const WorkItem*)p->d_items_proj, (const uint8_t*)mask, U, Z);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
@@ -525,9 +579,7 @@ int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replic
         default: e = launch(p, kWKeys, weighted_keys<0>, grid, kBlock, s, items, w, (int)R); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
-    e = launch(p, kTopk, select_topk, (unsigned)p->layers.size(), kScanBlock, s,
-               (const DevLayer*)p->d_layers, w.p.key, (const double*)w.p.colpart, mask);
-    if (e != hipSuccess) return HSADMM_ERR_HIP;
+    if (run_selection(p, w.p.key, w.p.colpart, Z, mask, s) != hipSuccess) return HSADMM_ERR_HIP;
     const uint8_t* cm = mask;
     switch (R) {
         case 1: e = launch(p, kWFinal, weighted_final<1>, grid, kBlock, s, items, w, (int)R, cm); break;
@@ -598,7 +650,7 @@ int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* ma
     const hipError_t e = launch(p, kScatter, expand_scatter, (unsigned)p->items_rows.size(), kBlock, s,
                                 (const WorkItem*)p->d_items_rows, packed,
                                 reinterpret_cast<const int32_t*>(ws + p->ws.pos),
-                                reinterpret_cast<const int32_t*>(ws + p->ws.cnt), lo, dst);
+                                reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (int)p->layers.size(), lo, dst);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     return HSADMM_OK;
 }
@@ -669,6 +721,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kDualInter: return "dual_inter";
         case kResPart: return "residual_partials";
         case kResFinish: return "residual_finish";
+        case kColsums: return "composite_colsums";
         default: return "";
     }
 }

@@ -17,42 +17,50 @@ constexpr int kTileElems = 2048;                // target elements per work item
 constexpr int kWideRow = 2048;                  // rows at least this long are shared by the whole workgroup
 constexpr int kChanRows = 32;               // CHANNEL tiles: rows per row block
 constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
-constexpr int kVersion = 130;
+constexpr int kVersion = 140;
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 struct DevLayer {
     int64_t elem_off;
     int64_t colpart_off;    // CHANNEL: first double of this layer's per-row-block column sums
-    int64_t unit;           // packed elements one kept group contributes (NONE: the whole layer)
+    int64_t unit;           // packed elements one kept group contributes (NONE: the whole layer;
+                            // BOTH: khw, the layer packs K_out * K_in * khw elements)
     int32_t c_out, c_in, khw, mode, k;
-    int32_t G, group_base, row_len;
-    int32_t n_rowblocks;    // CHANNEL: ceil(c_out / kChanRows)
+    int32_t G, group_base, row_len;   // G: groups in mask / key (BOTH: c_out filters, then c_in channels)
+    int32_t n_rowblocks;    // CHANNEL, BOTH: ceil(c_out / kChanRows)
     int32_t rows_item0;     // first of this layer's row items (compact / expand / residual kernels)
     int32_t rows_items;     // number of them
+    int32_t k_in;           // BOTH: channels kept
+    int32_t seg0;           // first scan segment of the layer (a BOTH layer has two: filters, channels)
     int32_t pad_;
 };
+static_assert(sizeof(DevLayer) == 80, "DevLayer layout");
 
 // One unit of work for a 256-thread workgroup; it carries everything the streaming kernels need,
 // so a workgroup starts with a single 64-byte scalar load.
-//   row item  (FILTER / NONE in project kernels, every mode in compact / expand): rows [r0, r0+nr)
-//   tile item (CHANNEL in project kernels): rows [r0, r0+nr) x one column strip
+//   row item  (FILTER / NONE / BOTH in project kernels, every mode in compact / expand): rows [r0, r0+nr)
+//   tile item (CHANNEL in project kernels, BOTH in composite_colsums): rows [r0, r0+nr) x one column strip
 struct WorkItem {
     int64_t base;       // arena element offset of the item's first row (column 0)
-    int64_t aux;        // tile: offset (doubles) of this row block's column sums in the workspace
+    int64_t aux;        // tile: offset (doubles) of this row block's column sums in the workspace;
+                        // BOTH row item: index in mask/pos of the layer's first channel group
     int32_t g0;         // row item: index in mask/key/pos of the first row; tile: group_base
     int32_t nr;         // rows
     int32_t row_len;    // c_in * khw
     int32_t lpr;        // row item: lanes sharing a row, power of two <= 64, or 256 (whole workgroup)
     int32_t flags;      // bits 0-1: mode; bit 2: 128-bit path (row_len % 4 == 0)
-    int32_t col0;       // tile: first column of the strip; CHANNEL row item: index of the first row
+    int32_t col0;       // tile: first column of the strip; row item: 0
     int32_t khw;
     int32_t layer;
-    int32_t pad_[4];
+    int32_t row0;       // index of the item's first row inside the layer
+    int32_t pad_[3];
 };
 static_assert(sizeof(WorkItem) == 64, "WorkItem layout");
 
 __device__ __forceinline__ int item_mode(const WorkItem& it) { return it.flags & 3; }
+// modes whose packed rows hold a subset of the columns (CHANNEL, BOTH)
+__device__ __forceinline__ bool mode_has_channels(int mode) { return (mode & HSADMM_MODE_CHANNEL) != 0; }
 __device__ __forceinline__ bool item_vec(const WorkItem& it) { return (it.flags & 4) != 0; }
 
 struct ProjectArgs {

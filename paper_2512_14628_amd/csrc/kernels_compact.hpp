@@ -10,8 +10,9 @@ namespace {
 // ------------------------------------------------------------------ mask scan (compact / expand)
 
 struct ScanOut {
-    int32_t* pos;        // groups_total: rank of a kept group inside its layer, -1 if pruned
-    int32_t* cnt;        // 2L: kept groups per layer, then the start of every layer's run in kept_idx
+    int32_t* pos;        // groups_total: rank of a kept group inside its segment, -1 if pruned
+    int32_t* cnt;        // 3L: kept groups of every layer's first segment, the start of every layer's
+                         // run in kept_idx, kept groups of the second segment (BOTH: channels; else 0)
     int64_t* layer_off;  // L+1, in the workspace (kept there for a later hsadmm_expand without a mask)
     int64_t* layer_off_out;  // L+1, the caller's copy; may be null
     int32_t* kept_idx;   // groups_total
@@ -24,21 +25,29 @@ __device__ __forceinline__ int nonzero_bytes(unsigned int x)
     return __popc(t);
 }
 
-// One workgroup per layer.  Every workgroup counts the kept groups of all layers in one flat pass
-// over the mask, 16 groups per thread and step: chunk_layer gives the layer of a 16-group chunk that
-// lies inside one constrained layer (one 128-bit load, a popcount, and one LDS add per wave when
-// the whole wave sits in one layer); chunks that straddle layers or touch an unconstrained layer
-// (0xffff) go group by group through group_layer (bit 15 marks an unconstrained layer, whose groups
-// are always kept).  The workgroup then sums the aligned segment sizes of layers 0..l-1 to get its
-// segment offset and scans its own layer's mask.  Segment starts are multiples of pack_align, so
-// the offset is the plain sum of the rounded-up sizes.
-__global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restrict__ layers, int nL,
+// One workgroup per layer.  The groups of a layer form one scan segment (a BOTH layer two: its
+// filters, then its channels).  Every workgroup counts the kept groups of all segments in one flat
+// pass over the mask, 16 groups per thread and step: chunk_layer gives the segment of a 16-group
+// chunk that lies inside one constrained segment (one 128-bit load, a popcount, and one LDS add per
+// wave when the whole wave sits in one segment); chunks that straddle segments or touch an
+// unconstrained layer (0xffff) go group by group through group_layer (bit 15 marks an unconstrained
+// layer, whose groups are always kept).  The workgroup then sums the aligned packed sizes of layers
+// 0..l-1 to get its own offset in the packed buffer and scans its own layer's mask.  Packed starts
+// are multiples of pack_align, so the offset is the plain sum of the rounded-up sizes.
+__device__ __forceinline__ long long packed_size(int mode, long long unit, int c0, int c1, int pack_align)
+{
+    long long s = (mode == HSADMM_MODE_NONE) ? unit : (long long)c0 * unit;
+    if (mode == HSADMM_MODE_BOTH) s *= c1;          // K_out * K_in * khw
+    return (s + pack_align - 1) / pack_align * pack_align;
+}
+
+__global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restrict__ layers, int nL, int nSeg,
                                                         int n_groups, int pack_align,
                                                         const uint8_t* __restrict__ mask,
                                                         const uint16_t* __restrict__ group_layer,
                                                         const uint16_t* __restrict__ chunk_layer, ScanOut o)
 {
-    __shared__ int cnt[HSADMM_MAX_LAYERS];
+    __shared__ int cnt[2 * HSADMM_MAX_LAYERS];      // per segment
     __shared__ int wtot[kScanWaves];
     __shared__ long long wsum[kScanWaves];
     __shared__ int wkept[kScanWaves];
@@ -49,9 +58,9 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
     const DevLayer L = layers[l];
     // loads that depend on nothing but the thread index go first
     long long unit_j = 0;
-    int none_j = 0;
-    if (tid < l) { unit_j = layers[tid].unit; none_j = layers[tid].mode == HSADMM_MODE_NONE; }
-    for (int j = tid; j < nL; j += kScanBlock) cnt[j] = 0;
+    int mode_j = 0, seg_j = 0;
+    if (tid < l) { unit_j = layers[tid].unit; mode_j = layers[tid].mode; seg_j = layers[tid].seg0; }
+    for (int j = tid; j < nSeg; j += kScanBlock) cnt[j] = 0;
     __syncthreads();
     const bool aligned16 = (reinterpret_cast<uintptr_t>(mask) & 15u) == 0;
     const int nchunks = (n_groups + 15) >> 4;
@@ -120,16 +129,17 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
     long long sz = 0;
     int kept_before = 0;
     if (tid < l) {
-        const int c = cnt[tid];
-        long long s = none_j ? unit_j : (long long)c * unit_j;
-        sz = (s + pack_align - 1) / pack_align * pack_align;
-        kept_before = c;
+        const int c0 = cnt[seg_j];
+        const int c1 = (mode_j == HSADMM_MODE_BOTH) ? cnt[seg_j + 1] : 0;
+        sz = packed_size(mode_j, unit_j, c0, c1, pack_align);
+        kept_before = c0 + c1;
     }
     for (int j = tid + kScanBlock; j < l; j += kScanBlock) {    // more than 1024 layers
-        const int c = cnt[j];
-        long long s = (layers[j].mode == HSADMM_MODE_NONE) ? layers[j].unit : (long long)c * layers[j].unit;
-        sz += (s + pack_align - 1) / pack_align * pack_align;
-        kept_before += c;
+        const int mj = layers[j].mode, sj = layers[j].seg0;
+        const int c0 = cnt[sj];
+        const int c1 = (mj == HSADMM_MODE_BOTH) ? cnt[sj + 1] : 0;
+        sz += packed_size(mj, layers[j].unit, c0, c1, pack_align);
+        kept_before += c0 + c1;
     }
     sz = wave_sum_i64(sz);
     kept_before = wave_sum_i32(kept_before);
@@ -139,30 +149,38 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
     int kb = 0;
 #pragma unroll
     for (int w = 0; w < kScanWaves; ++w) { pos += wsum[w]; kb += wkept[w]; }
+    const bool both = L.mode == HSADMM_MODE_BOTH;
+    const int own0 = cnt[L.seg0];
+    const int own1 = both ? cnt[L.seg0 + 1] : 0;
     if (tid == 0) {
         o.layer_off[l] = pos;
         if (o.layer_off_out) o.layer_off_out[l] = pos;
-        o.cnt[l] = cnt[l];
+        o.cnt[l] = own0;
         o.cnt[nL + l] = kb;
+        o.cnt[2 * nL + l] = own1;
         if (l == nL - 1) {
-            long long s = (L.mode == HSADMM_MODE_NONE) ? L.unit : (long long)cnt[l] * L.unit;
-            s = (s + pack_align - 1) / pack_align * pack_align;
+            const long long s = packed_size(L.mode, L.unit, own0, own1, pack_align);
             o.layer_off[nL] = pos + s;
             if (o.layer_off_out) o.layer_off_out[nL] = pos + s;
         }
     }
-    const int G = L.G;
-    int carry = 0;
-    for (int base = 0; base < G; base += kScanBlock) {
-        const int g = base + tid;
-        const bool m = (g < G) && (L.mode == HSADMM_MODE_NONE || mask[L.group_base + g] != 0);
-        int total;
-        const int rank = carry + block_excl_scan<kScanWaves>(m, wtot, total);
-        if (g < G) {
-            o.pos[L.group_base + g] = m ? rank : -1;
-            if (m) o.kept_idx[kb + rank] = g;
+    // ranks inside each of the layer's segments; kept_idx lists the first segment, then the second
+    for (int seg = 0; seg < (both ? 2 : 1); ++seg) {
+        const int G = both ? (seg == 0 ? L.c_out : L.c_in) : L.G;
+        const int g_first = L.group_base + (seg == 1 ? L.c_out : 0);
+        const int k_first = kb + (seg == 1 ? own0 : 0);
+        int carry = 0;
+        for (int base = 0; base < G; base += kScanBlock) {
+            const int g = base + tid;
+            const bool m = (g < G) && (L.mode == HSADMM_MODE_NONE || mask[g_first + g] != 0);
+            int total;
+            const int rank = carry + block_excl_scan<kScanWaves>(m, wtot, total);
+            if (g < G) {
+                o.pos[g_first + g] = m ? rank : -1;
+                if (m) o.kept_idx[k_first + rank] = g;
+            }
+            carry += total;
         }
-        carry += total;
     }
 }
 
@@ -184,7 +202,7 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
     const int wave = threadIdx.x / kWave;
     const int row_len = it.row_len;
     float* out = packed + layer_off[it.layer];
-    if (item_mode(it) != HSADMM_MODE_CHANNEL) {
+    if (!mode_has_channels(item_mode(it))) {
         const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
         const int rows_at_once = kBlock / lpr;
         const int sub = threadIdx.x / lpr;
@@ -208,20 +226,27 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
         }
     } else {
         // packed row o holds the kept channels' khw-blocks in ascending channel order: packed column
-        // j = q*khw + t comes from source column kept[q]*khw + t.  it.col0 is the index of the item's
+        // j = q*khw + t comes from source column kept[q]*khw + t.  it.row0 is the index of the item's
         // first row inside the layer.  A wave takes a row; a lane gathers 4 adjacent packed columns
-        // and stores them with one 128-bit access.
-        const int kc = cnt[it.layer];
+        // and stores them with one 128-bit access.  BOTH: only the kept filters' rows are packed, at
+        // their rank among the kept filters; the kept channels follow the kept filters in kept_idx.
+        const bool both = item_mode(it) == HSADMM_MODE_BOTH;
+        const int kc = both ? cnt[2 * n_layers + it.layer] : cnt[it.layer];
         const int khw = it.khw;
         const int out_len = kc * khw;
-        const int32_t* kl = kept_idx + cnt[n_layers + it.layer];
+        const int32_t* kl = kept_idx + cnt[n_layers + it.layer] + (both ? cnt[it.layer] : 0);
         const DivKhw div(khw);
         const int quads = out_len >> 2;
         for (int rr = wave; rr < it.nr; rr += kWaves) {
+            int prow = it.row0 + rr;
+            if (both) {
+                prow = pos[it.g0 + rr];
+                if (prow < 0) continue;
+            }
             const float* s = src + it.base + (int64_t)rr * row_len;
             const float* s1 = SUM ? src1 + it.base + (int64_t)rr * row_len : nullptr;
             auto at = [&](int idx) -> float { return SUM ? ld1(s + idx) + ld1(s1 + idx) : ld1(s + idx); };
-            float* d = out + (int64_t)(it.col0 + rr) * out_len;
+            float* d = out + (int64_t)prow * out_len;
             for (int j4 = lane; j4 < quads; j4 += kWave) {
                 const int j = j4 << 2;
                 v4f v;
@@ -253,7 +278,7 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
 __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restrict__ items,
                                                          const float* __restrict__ packed,
                                                          const int32_t* __restrict__ pos,
-                                                         const int32_t* __restrict__ cnt,
+                                                         const int32_t* __restrict__ cnt, int n_layers,
                                                          const int64_t* __restrict__ layer_off,
                                                          float* __restrict__ dst)
 {
@@ -263,7 +288,7 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
     const int row_len = it.row_len;
     const float* in = packed + layer_off[it.layer];
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-    if (item_mode(it) != HSADMM_MODE_CHANNEL) {
+    if (!mode_has_channels(item_mode(it))) {
         const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
         const int rows_at_once = kBlock / lpr;
         const int sub = threadIdx.x / lpr;
@@ -283,16 +308,27 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
         }
     } else {
         // a wave takes a row of dst; a lane fills 4 adjacent columns (kept ones from the packed row,
-        // the others +0) and stores them with one 128-bit access
-        const int kc = cnt[it.layer];
+        // the others +0) and stores them with one 128-bit access.  BOTH: the row of a pruned filter
+        // is all +0, the row of a kept one is read at its rank among the kept filters.
+        const bool both = item_mode(it) == HSADMM_MODE_BOTH;
+        const int kc = both ? cnt[2 * n_layers + it.layer] : cnt[it.layer];
         const int khw = it.khw;
         const int in_len = kc * khw;
         const DivKhw div(khw);
-        const int32_t* pl = pos + it.g0;
+        const int32_t* pl = pos + (both ? it.aux : (int64_t)it.g0);
         const int quads = item_vec(it) ? (row_len >> 2) : 0;
         for (int rr = wave; rr < it.nr; rr += kWaves) {
             float* d = dst + it.base + (int64_t)rr * row_len;
-            const float* s = in + (int64_t)(it.col0 + rr) * in_len;
+            int prow = it.row0 + rr;
+            if (both) {
+                prow = pos[it.g0 + rr];
+                if (prow < 0) {
+                    for (int c4 = lane; c4 < quads; c4 += kWave) st4(d + (c4 << 2), zero4);
+                    for (int c = (quads << 2) + lane; c < row_len; c += kWave) d[c] = 0.f;
+                    continue;
+                }
+            }
+            const float* s = in + (int64_t)prow * in_len;
             for (int c4 = lane; c4 < quads; c4 += kWave) {
                 const int c = c4 << 2;
                 float t4[4];

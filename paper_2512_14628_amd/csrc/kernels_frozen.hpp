@@ -84,9 +84,27 @@ __global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restr
         const int rows_at_once = kBlock / lpr;
         const int sub = threadIdx.x / lpr;
         const int j = threadIdx.x - sub * lpr;
+        const bool both = mode == HSADMM_MODE_BOTH;
+        const uint8_t* mc = mask + it.aux;            // BOTH: channel bytes of the layer
+        const DivKhw div(it.khw);
         for (int rr = sub; rr < it.nr; rr += rows_at_once) {
             const bool keep = mode == HSADMM_MODE_NONE || mask[it.g0 + rr] != 0;
             const int64_t base = it.base + (int64_t)rr * row_len;
+            if (both && keep) {
+                // kept filter of a BOTH layer: an element survives iff its channel does too
+                if (vec) {
+                    const int nchunk = row_len >> 2;
+                    for (int c = j; c < nchunk; c += lpr) {
+                        const int col = c << 2;
+                        bool k[4];
+                        for (int i = 0; i < 4; ++i) k[i] = mc[div(col + i)] != 0;
+                        frozen4<R>(a, Rrt, base + col, k[0], k[1], k[2], k[3]);
+                    }
+                } else {
+                    for (int c = j; c < row_len; c += lpr) frozen1<R>(a, Rrt, base + c, mc[div(c)] != 0);
+                }
+                continue;
+            }
             if (vec) {
                 const int nchunk = row_len >> 2;
                 int c = j;

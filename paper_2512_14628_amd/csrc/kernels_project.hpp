@@ -192,7 +192,60 @@ __global__ __launch_bounds__(kBlock) void project_pass1(const WorkItem* __restri
 {
     const WorkItem it = items[blockIdx.x];
     if (item_mode(it) == HSADMM_MODE_CHANNEL) project_tile<R>(it, a, Rrt);
-    else project_rows<R>(it, a, Rrt);
+    else project_rows<R>(it, a, Rrt);       // BOTH: the filter norms come first
+}
+
+// ------------------------------------------------------------------ BOTH: channel norms after the filter projection
+
+// Second projection of a layer under both constraints (Section 3, paragraph after Eq. (10)): the
+// channel norms of the tensor whose pruned filters are already zero, i.e. column sums of V^2 over
+// the kept rows only.  Z holds V after pass 1.  Tiles and the order of additions are those of
+// project_tile (rows of a pruned filter add nothing and are not read).
+__global__ __launch_bounds__(kBlock) void composite_colsums(const WorkItem* __restrict__ items,
+                                                            const float* __restrict__ Z,
+                                                            const uint8_t* __restrict__ mask,
+                                                            double* __restrict__ colpart)
+{
+    __shared__ double part[kWaves][kWave * 4];
+    const WorkItem it = items[blockIdx.x];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const int vw = vec ? 4 : 1;
+    const int col = it.col0 + lane * vw;
+    const bool in = col < row_len;
+    const uint8_t* mf = mask + it.g0 + it.row0;      // filter bytes of the tile's rows
+    double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+    if (in) {
+        for (int rr = wave; rr < it.nr; rr += kWaves) {
+            if (mf[rr] == 0) continue;
+            const int64_t e = it.base + (int64_t)rr * row_len + col;
+            if (vec) {
+                const v4f v = ld4(Z + e);
+                acc0 = fma((double)v.x, (double)v.x, acc0);
+                acc1 = fma((double)v.y, (double)v.y, acc1);
+                acc2 = fma((double)v.z, (double)v.z, acc2);
+                acc3 = fma((double)v.w, (double)v.w, acc3);
+            } else {
+                const float v = ld1(Z + e);
+                acc0 = fma((double)v, (double)v, acc0);
+            }
+        }
+    }
+    part[wave][lane * 4 + 0] = acc0;
+    part[wave][lane * 4 + 1] = acc1;
+    part[wave][lane * 4 + 2] = acc2;
+    part[wave][lane * 4 + 3] = acc3;
+    __syncthreads();
+    if (wave == 0 && in) {
+        double* out = colpart + it.aux + col;
+        for (int i = 0; i < vw; ++i) {
+            double s = part[0][lane * 4 + i];
+            for (int w = 1; w < kWaves; ++w) s += part[w][lane * 4 + i];
+            out[i] = s;
+        }
+    }
 }
 
 
@@ -210,15 +263,54 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-    if (mode == HSADMM_MODE_FILTER) {
+    if (mode != HSADMM_MODE_CHANNEL) {
         // lanes-per-row mapping as in pass 1 (the mapping carries no arithmetic here)
         const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
         const int rows_at_once = kBlock / lpr;
         const int sub = threadIdx.x / lpr;
         const int j = threadIdx.x - sub * lpr;
+        const bool both = mode == HSADMM_MODE_BOTH;
+        const uint8_t* mc = mask + it.aux;            // BOTH: channel bytes of the layer
+        const DivKhw div(it.khw);
         for (int rr = sub; rr < it.nr; rr += rows_at_once) {
-            if (mask[it.g0 + rr]) continue;
             const int64_t base = it.base + (int64_t)rr * row_len;
+            if (mask[it.g0 + rr]) {
+                if (!both) continue;
+                // kept filter of a BOTH layer: only the columns of pruned channels change
+                if (vec) {
+                    const int nchunk = row_len >> 2;
+                    for (int c = j; c < nchunk; c += lpr) {
+                        const int col = c << 2;
+                        bool pr[4];
+                        if (it.khw == 1) {
+                            unsigned int m4;
+                            __builtin_memcpy(&m4, mc + col, 4);
+                            for (int i = 0; i < 4; ++i) pr[i] = ((m4 >> (8 * i)) & 0xffu) == 0u;
+                        } else {
+                            for (int i = 0; i < 4; ++i) pr[i] = mc[div(col + i)] == 0;
+                        }
+                        if (!(pr[0] || pr[1] || pr[2] || pr[3])) continue;
+                        const int64_t e = base + col;
+                        const v4f z = ld4(Z + e);
+                        if (pr[0] && pr[1] && pr[2] && pr[3]) {
+                            st4(U + e, z);
+                            st4(Z + e, zero4);
+                        } else {
+                            if (pr[0]) { st1(U + e + 0, z.x); st1(Z + e + 0, 0.f); }
+                            if (pr[1]) { st1(U + e + 1, z.y); st1(Z + e + 1, 0.f); }
+                            if (pr[2]) { st1(U + e + 2, z.z); st1(Z + e + 2, 0.f); }
+                            if (pr[3]) { st1(U + e + 3, z.w); st1(Z + e + 3, 0.f); }
+                        }
+                    }
+                } else {
+                    for (int c = j; c < row_len; c += lpr) {
+                        if (mc[div(c)] != 0) continue;
+                        st1(U + base + c, ld1(Z + base + c));
+                        st1(Z + base + c, 0.f);
+                    }
+                }
+                continue;
+            }
             if (vec) {
                 const int nchunk = row_len >> 2;
                 for (int c = j; c < nchunk; c += lpr) {

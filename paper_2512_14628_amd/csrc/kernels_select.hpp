@@ -196,18 +196,25 @@ __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, 
 }
 
 // One workgroup per layer: finish the CHANNEL keys, then write the layer's mask.
+// stage 0: workgroup b takes layer b; of a BOTH layer it selects the filters (its first c_out groups).
+// stage 1: workgroup b takes layer layer_list[b], a BOTH layer, and selects its channels (the c_in
+//          groups after the filters) from the column sums composite_colsums left in colpart.
 __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __restrict__ layers,
                                                           double* __restrict__ key,
                                                           const double* __restrict__ colpart,
-                                                          uint8_t* __restrict__ mask)
+                                                          uint8_t* __restrict__ mask,
+                                                          const int32_t* __restrict__ layer_list, int stage)
 {
     __shared__ TopkShared sh;
-    const DevLayer L = layers[blockIdx.x];
-    const int G = L.G;
+    const DevLayer L = layers[stage == 0 ? (int)blockIdx.x : layer_list[blockIdx.x]];
+    const bool both = L.mode == HSADMM_MODE_BOTH;
+    const bool channels = L.mode == HSADMM_MODE_CHANNEL || (both && stage == 1);
+    const int G = both ? (stage == 0 ? L.c_out : L.c_in) : L.G;
+    const int first = L.group_base + ((both && stage == 1) ? L.c_out : 0);
     const int tid = threadIdx.x;
-    double* kl = key + L.group_base;
-    uint8_t* ml = mask + L.group_base;
-    if (L.mode == HSADMM_MODE_CHANNEL) {
+    double* kl = key + first;
+    uint8_t* ml = mask + first;
+    if (channels) {
         // key[c] = sum over row blocks (ascending), then over the channel's khw columns (ascending)
         const double* cp = colpart + L.colpart_off;
         for (int g = tid; g < G; g += kScanBlock) {
@@ -236,7 +243,7 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
         }
         __syncthreads();
     }
-    const int kk = (L.mode == HSADMM_MODE_NONE) ? G : L.k;
+    const int kk = (L.mode == HSADMM_MODE_NONE) ? G : ((both && stage == 1) ? L.k_in : L.k);
     if (kk >= G) {
         for (int g = tid; g < G; g += kScanBlock) ml[g] = 1;
         return;

@@ -65,6 +65,9 @@ __global__ __launch_bounds__(kBlock) void weighted_keys(const WorkItem* __restri
     const bool vec = item_vec(it);
     const float al = w.coef[2 * it.layer], bl = w.coef[2 * it.layer + 1];
     if (item_mode(it) != HSADMM_MODE_CHANNEL) {
+        // BOTH: these are the filter norms; the candidate is also parked in Z, where composite_colsums
+        // reads it for the channel norms over the kept filters
+        const bool park = item_mode(it) == HSADMM_MODE_BOTH;
         const bool wide = it.lpr > kWave;
         const int lpr = wide ? kBlock : it.lpr;
         const int rows_at_once = kBlock / lpr;
@@ -82,12 +85,14 @@ __global__ __launch_bounds__(kBlock) void weighted_keys(const WorkItem* __restri
                     for (int c = j; c < nchunk; c += lpr) {
                         v4f wb, u, zt;
                         wcand4<R>(w, Rrt, base + ((int64_t)c << 2), al, bl, wb, u, zt);
+                        if (park) st4(w.p.Z + base + ((int64_t)c << 2), zt);
                         acc = sq4(acc, zt);
                     }
                 } else {
                     for (int c = j; c < row_len; c += lpr) {
                         float wb, u, zt;
                         wcand1<R>(w, Rrt, base + c, al, bl, wb, u, zt);
+                        if (park) st1(w.p.Z + base + c, zt);
                         acc = fma((double)zt, (double)zt, acc);
                     }
                 }
@@ -179,9 +184,26 @@ __global__ __launch_bounds__(kBlock) void weighted_final(const WorkItem* __restr
         const int rows_at_once = kBlock / lpr;
         const int sub = threadIdx.x / lpr;
         const int j = threadIdx.x - sub * lpr;
+        const bool both = mode == HSADMM_MODE_BOTH;
+        const uint8_t* mc = mask + it.aux;            // BOTH: channel bytes of the layer
+        const DivKhw div(it.khw);
         for (int rr = sub; rr < it.nr; rr += rows_at_once) {
             const bool keep = mode == HSADMM_MODE_NONE || mask[it.g0 + rr] != 0;
             const int64_t base = it.base + (int64_t)rr * row_len;
+            if (both && keep) {
+                if (vec) {
+                    const int nchunk = row_len >> 2;
+                    for (int c = j; c < nchunk; c += lpr) {
+                        const int col = c << 2;
+                        bool k[4];
+                        for (int i = 0; i < 4; ++i) k[i] = mc[div(col + i)] != 0;
+                        put4(base + col, k[0], k[1], k[2], k[3]);
+                    }
+                } else {
+                    for (int c = j; c < row_len; c += lpr) put1(base + c, mc[div(c)] != 0);
+                }
+                continue;
+            }
             if (vec) {
                 const int nchunk = row_len >> 2;
                 for (int c = j; c < nchunk; c += lpr) put4(base + ((int64_t)c << 2), keep, keep, keep, keep);

@@ -69,15 +69,23 @@ def layer_view(wl, arena):
 
 
 def min_relative_gap(wl, key):
-    """Smallest nonzero relative gap between the k-th and (k+1)-th largest key of any constrained layer."""
+    """Smallest nonzero relative gap between the k-th and (k+1)-th largest key of any constrained layer
+    (of either selection of a layer under both constraints)."""
     worst = np.inf
     for l in wl.layers:
-        if l.mode == 0 or l.k >= l.groups:
+        if l.mode == 0:
             continue
-        ks = np.sort(key[l.group_base:l.group_base + l.groups])[::-1]
-        a, b = ks[l.k - 1], ks[l.k]
-        if a != b and a > 0:
-            worst = min(worst, (a - b) / a)
+        if l.mode == 3:
+            parts = [(l.group_base, l.c_out, l.k), (l.group_base + l.c_out, l.c_in, l.k_in)]
+        else:
+            parts = [(l.group_base, l.groups, l.k)]
+        for first, G, k in parts:
+            if k >= G:
+                continue
+            ks = np.sort(key[first:first + G])[::-1]
+            a, b = ks[k - 1], ks[k]
+            if a != b and a > 0:
+                worst = min(worst, (a - b) / a)
     return worst
 
 

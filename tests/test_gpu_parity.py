@@ -23,8 +23,11 @@ def _run(wl, pack_align=1, want_wbar=True, want_sqnorm=True, threads=8, determin
     refc = oracle.compact(t, ref["Z"], ref["mask"], pack_align=pack_align)
     sizes = []
     for l in wl.layers:
-        cnt = int(ref["mask"][l.group_base:l.group_base + l.groups].sum())
-        sizes.append(l.n if l.mode == wk.MODE_NONE else cnt * l.group_size)
+        m = ref["mask"][l.group_base:l.group_base + l.groups]
+        if l.mode == wk.MODE_BOTH:
+            sizes.append(int(m[:l.c_out].sum()) * int(m[l.c_out:].sum()) * l.khw)
+        else:
+            sizes.append(l.n if l.mode == wk.MODE_NONE else int(m.sum()) * l.group_size)
     refc["seg_sizes"] = np.array(sizes)
     run = GpuRun(wl, W, U, pack_align=pack_align, want_wbar=want_wbar, want_sqnorm=want_sqnorm)
     run.step()
