@@ -270,6 +270,66 @@ def main():
                 "hbm_frac": round(w_bytes / w_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
                 "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in wt.items() if v[1]}}
 
+    # ---- both constraints on every conv layer (filter + channel; Section 2.1's intersection, projected by the two
+    #      projections in sequence): the same shapes, replicas and duals under another layer table
+    composite = None
+    if args.workload == "resnet50":
+        wl2 = wk.make_workload("resnet50_both", seed=args.seed)
+        assert wl2.n_arena == wl.n_arena
+        plan2 = pkg.Plan(wl2.table())
+        for b in sets:
+            b.mask2 = torch.zeros(plan2.groups_total, dtype=torch.uint8, device=dev)
+            b.kept2 = torch.zeros(plan2.groups_total, dtype=torch.int32, device=dev)
+            b.ws2 = torch.zeros(plan2.workspace_bytes, dtype=torch.uint8, device=dev)
+            b.U.copy_(dU0)
+
+        def composite_step():
+            b = sets[counter[0] % nsets]
+            counter[0] += 1
+            pkg.hsadmm_project(plan2, b.W, b.U, b.Z, None, b.mask2, None, b.ws2, stream=stream)
+            pkg.hsadmm_compact(plan2, b.Z, b.mask2, b.packed, b.off, b.kept2, b.ws2, stream=stream)
+            pkg.hsadmm_expand(plan2, b.packed, None, b.dst, b.ws2, stream=stream)
+
+        if not args.no_verify:
+            import oracle
+            counter[0] = 0
+            composite_step()
+            torch.cuda.synchronize()
+            r2 = oracle.project(wl2.table(), W, U)
+            c2 = oracle.compact(wl2.table(), r2["Z"], r2["mask"])
+            b0 = sets[0]
+            ok2 = (np.array_equal(b0.mask2.cpu().numpy(), r2["mask"])
+                   and np.array_equal(b0.Z.cpu().numpy().view(np.uint32), r2["Z"].view(np.uint32))
+                   and np.array_equal(b0.U.cpu().numpy().view(np.uint32), r2["U"].view(np.uint32))
+                   and np.array_equal(b0.packed.cpu().numpy()[:int(c2["layer_off"][-1])].view(np.uint32),
+                                      c2["packed"].view(np.uint32))
+                   and np.array_equal(b0.dst.cpu().numpy().view(np.uint32), r2["Z"].view(np.uint32)))
+            if not ok2:
+                print("bench.py: composite outputs differ from the oracle", file=sys.stderr)
+                sys.exit(4)
+        csteps = max(1, args.steps // 2)
+        for _ in range(max(3, args.warmup // 2)):
+            composite_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(csteps):
+            composite_step()
+        torch.cuda.synchronize()
+        c_elapsed = (time.perf_counter() - t0) / csteps
+        pkg.hsadmm_kernel_timing_enable(plan2, True)
+        for _ in range(csteps):
+            composite_step()
+        torch.cuda.synchronize()
+        ct = pkg.hsadmm_kernel_timing_read(plan2)
+        pkg.hsadmm_kernel_timing_enable(plan2, False)
+        c_bytes = wl2.algorithmic_bytes()["step"]
+        composite = {"workload": wl2.description, "kept_params": wl2.n_kept,
+                     "ms_per_step": round(1e3 * c_elapsed, 4), "algorithmic_bytes_per_step": c_bytes,
+                     "value_GBps": round(c_bytes / c_elapsed / 1e9, 1),
+                     "hbm_frac": round(c_bytes / c_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                     "kernel_us_per_step": {k: round(1e3 * v[0] / csteps, 2) for k, v in ct.items() if v[1]}}
+        plan2.close()
+
     # ---- context: a plain device copy of the same size class (practical streaming ceiling)
     a_src, a_dst = sets[0].W[0], sets[0].Z
     for _ in range(5):
@@ -330,6 +390,7 @@ def main():
         "frozen_mask_step": frozen,
         "weighted_step": weighted,
         "residuals": residuals,
+        "composite_step": composite,
         "verified_against_oracle": verify,
         "roofline": roofline,
         "cpu_baseline": cpu,

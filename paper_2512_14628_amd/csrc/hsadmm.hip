@@ -424,8 +424,8 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     if (run_selection(p, a.key, a.colpart, Z, mask, s) != hipSuccess) return HSADMM_ERR_HIP;
-    e = launch(p, kFixup, project_fixup, (unsigned)p->items_proj.size(), kBlock, s,
-               (const WorkItem*)p->d_items_proj, (const uint8_t*)mask, U, Z);
+    e = launch(p, kFixup, project_fixup, (unsigned)p->items_rows.size(), kBlock, s,
+               (const WorkItem*)p->d_items_rows, (const uint8_t*)mask, U, Z);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     return HSADMM_OK;
 }

@@ -237,37 +237,48 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
         const int32_t* kl = kept_idx + cnt[n_layers + it.layer] + (both ? cnt[it.layer] : 0);
         const DivKhw div(khw);
         const int quads = out_len >> 2;
-        for (int rr = wave; rr < it.nr; rr += kWaves) {
-            int prow = it.row0 + rr;
-            if (both) {
-                prow = pos[it.g0 + rr];
-                if (prow < 0) continue;
+        constexpr int kRows = 4;      // rows a wave keeps in flight: their loads are issued together
+        for (int rr0 = wave; rr0 < it.nr; rr0 += kRows * kWaves) {
+            int prow[kRows];
+            int64_t ro[kRows];
+#pragma unroll
+            for (int u = 0; u < kRows; ++u) {
+                const int rr = rr0 + u * kWaves;
+                prow[u] = -1;
+                if (rr < it.nr) prow[u] = both ? pos[it.g0 + rr] : it.row0 + rr;
+                ro[u] = it.base + (int64_t)rr * row_len;
             }
-            const float* s = src + it.base + (int64_t)rr * row_len;
-            const float* s1 = SUM ? src1 + it.base + (int64_t)rr * row_len : nullptr;
-            auto at = [&](int idx) -> float { return SUM ? ld1(s + idx) + ld1(s1 + idx) : ld1(s + idx); };
-            float* d = out + (int64_t)prow * out_len;
+            auto at = [&](int u, int idx) -> float {
+                return SUM ? ld1(src + ro[u] + idx) + ld1(src1 + ro[u] + idx) : ld1(src + ro[u] + idx);
+            };
             for (int j4 = lane; j4 < quads; j4 += kWave) {
                 const int j = j4 << 2;
-                v4f v;
+                int4 c;
                 if (khw == 1) {
-                    int4 c;
                     __builtin_memcpy(&c, kl + j, 16);
-                    v.x = at(c.x); v.y = at(c.y); v.z = at(c.z); v.w = at(c.w);
                 } else {
-                    float t4[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int q = div(j + i);
-                        t4[i] = at(kl[q] * khw + (j + i - q * khw));
-                    }
-                    v.x = t4[0]; v.y = t4[1]; v.z = t4[2]; v.w = t4[3];
+                    const int q0 = div(j), q1 = div(j + 1), q2 = div(j + 2), q3 = div(j + 3);
+                    c.x = kl[q0] * khw + (j - q0 * khw);
+                    c.y = kl[q1] * khw + (j + 1 - q1 * khw);
+                    c.z = kl[q2] * khw + (j + 2 - q2 * khw);
+                    c.w = kl[q3] * khw + (j + 3 - q3 * khw);
                 }
-                st4u(d + j, v);
+                v4f v[kRows];
+#pragma unroll
+                for (int u = 0; u < kRows; ++u) {
+                    if (prow[u] < 0) continue;
+                    v[u].x = at(u, c.x); v[u].y = at(u, c.y); v[u].z = at(u, c.z); v[u].w = at(u, c.w);
+                }
+#pragma unroll
+                for (int u = 0; u < kRows; ++u)
+                    if (prow[u] >= 0) st4u(out + (int64_t)prow[u] * out_len + j, v[u]);
             }
             for (int j = (quads << 2) + lane; j < out_len; j += kWave) {
                 const int q = div(j);
-                d[j] = at(kl[q] * khw + (j - q * khw));
+                const int cs = kl[q] * khw + (j - q * khw);
+#pragma unroll
+                for (int u = 0; u < kRows; ++u)
+                    if (prow[u] >= 0) out[(int64_t)prow[u] * out_len + j] = at(u, cs);
             }
         }
     }
@@ -317,44 +328,53 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
         const DivKhw div(khw);
         const int32_t* pl = pos + (both ? it.aux : (int64_t)it.g0);
         const int quads = item_vec(it) ? (row_len >> 2) : 0;
-        for (int rr = wave; rr < it.nr; rr += kWaves) {
-            float* d = dst + it.base + (int64_t)rr * row_len;
-            int prow = it.row0 + rr;
-            if (both) {
-                prow = pos[it.g0 + rr];
-                if (prow < 0) {
-                    for (int c4 = lane; c4 < quads; c4 += kWave) st4(d + (c4 << 2), zero4);
-                    for (int c = (quads << 2) + lane; c < row_len; c += kWave) d[c] = 0.f;
-                    continue;
-                }
+        constexpr int kRows = 4;      // rows a wave keeps in flight
+        for (int rr0 = wave; rr0 < it.nr; rr0 += kRows * kWaves) {
+            int prow[kRows];
+            bool live[kRows];
+            const float* srow[kRows];
+#pragma unroll
+            for (int u = 0; u < kRows; ++u) {
+                const int rr = rr0 + u * kWaves;
+                live[u] = rr < it.nr;
+                prow[u] = -1;
+                if (live[u]) prow[u] = both ? pos[it.g0 + rr] : it.row0 + rr;
+                srow[u] = in + (int64_t)(prow[u] < 0 ? 0 : prow[u]) * in_len;
             }
-            const float* s = in + (int64_t)prow * in_len;
             for (int c4 = lane; c4 < quads; c4 += kWave) {
                 const int c = c4 << 2;
-                float t4[4];
+                int4 p;                       // packed column of each dst column, -1: pruned channel
                 if (khw == 1) {
-                    int4 p;
                     __builtin_memcpy(&p, pl + c, 16);
-                    t4[0] = p.x >= 0 ? s[p.x] : 0.f;
-                    t4[1] = p.y >= 0 ? s[p.y] : 0.f;
-                    t4[2] = p.z >= 0 ? s[p.z] : 0.f;
-                    t4[3] = p.w >= 0 ? s[p.w] : 0.f;
                 } else {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int ch = div(c + i);
-                        const int p = pl[ch];
-                        t4[i] = p >= 0 ? s[p * khw + (c + i - ch * khw)] : 0.f;
-                    }
+                    const int h0 = div(c), h1 = div(c + 1), h2 = div(c + 2), h3 = div(c + 3);
+                    const int p0 = pl[h0], p1 = pl[h1], p2 = pl[h2], p3 = pl[h3];
+                    p.x = p0 >= 0 ? p0 * khw + (c - h0 * khw) : -1;
+                    p.y = p1 >= 0 ? p1 * khw + (c + 1 - h1 * khw) : -1;
+                    p.z = p2 >= 0 ? p2 * khw + (c + 2 - h2 * khw) : -1;
+                    p.w = p3 >= 0 ? p3 * khw + (c + 3 - h3 * khw) : -1;
                 }
-                v4f v;
-                v.x = t4[0]; v.y = t4[1]; v.z = t4[2]; v.w = t4[3];
-                st4(d + c, v);
+                v4f v[kRows];
+#pragma unroll
+                for (int u = 0; u < kRows; ++u) {
+                    const bool k = prow[u] >= 0;
+                    v[u].x = (k && p.x >= 0) ? srow[u][p.x] : 0.f;
+                    v[u].y = (k && p.y >= 0) ? srow[u][p.y] : 0.f;
+                    v[u].z = (k && p.z >= 0) ? srow[u][p.z] : 0.f;
+                    v[u].w = (k && p.w >= 0) ? srow[u][p.w] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < kRows; ++u)
+                    if (live[u]) st4(dst + it.base + (int64_t)(rr0 + u * kWaves) * row_len + c, v[u]);
             }
             for (int c = (quads << 2) + lane; c < row_len; c += kWave) {
                 const int ch = div(c);
-                const int p = pl[ch];
-                d[c] = (p >= 0) ? s[p * khw + (c - ch * khw)] : 0.f;
+                const int p0 = pl[ch];
+                const int pc = p0 >= 0 ? p0 * khw + (c - ch * khw) : -1;
+#pragma unroll
+                for (int u = 0; u < kRows; ++u)
+                    if (live[u])
+                        dst[it.base + (int64_t)(rr0 + u * kWaves) * row_len + c] = (prow[u] >= 0 && pc >= 0) ? srow[u][pc] : 0.f;
             }
         }
     }

@@ -251,6 +251,32 @@ __global__ __launch_bounds__(kBlock) void composite_colsums(const WorkItem* __re
 
 // ------------------------------------------------------------------ project, fix-up of pruned groups
 
+// pr[i] = the channel of column col + i is pruned (mc: the layer's channel bytes), for 4 adjacent columns.
+__device__ __forceinline__ void quad_pruned(const uint8_t* __restrict__ mc, const DivKhw& div, int col, bool pr[4])
+{
+    if (div.khw == 1) {
+        unsigned int m4;
+        __builtin_memcpy(&m4, mc + col, 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pr[i] = ((m4 >> (8 * i)) & 0xffu) == 0u;
+    } else if (div.khw >= 4) {
+        // at most two channels meet in a quad
+        const int ch = div(col);
+        const int left = (ch + 1) * div.khw - col;          // columns of the quad that belong to ch
+        const bool p0 = mc[ch] == 0;
+        const bool p1 = left < 4 ? mc[ch + 1] == 0 : p0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pr[i] = i < left ? p0 : p1;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pr[i] = mc[div(col + i)] == 0;
+    }
+}
+
+// Row items of every mode (the compact / expand item table).  A pruned filter's row moves whole:
+// U <- V (held in Z), Z <- +0.  In a row that stays (every row of a CHANNEL layer, the kept filters of a
+// BOTH layer) only the columns of pruned channels change; a partly pruned quad is rewritten whole, the kept
+// elements of U passing through (they are final already), so that every access is a full 128 bits.
 __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restrict__ items,
                                                         const uint8_t* __restrict__ mask,
                                                         float* __restrict__ U, float* __restrict__ Z)
@@ -258,103 +284,64 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
     const WorkItem it = items[blockIdx.x];
     const int mode = item_mode(it);
     if (mode == HSADMM_MODE_NONE) return;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-    if (mode != HSADMM_MODE_CHANNEL) {
-        // lanes-per-row mapping as in pass 1 (the mapping carries no arithmetic here)
-        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
-        const int rows_at_once = kBlock / lpr;
-        const int sub = threadIdx.x / lpr;
-        const int j = threadIdx.x - sub * lpr;
-        const bool both = mode == HSADMM_MODE_BOTH;
-        const uint8_t* mc = mask + it.aux;            // BOTH: channel bytes of the layer
-        const DivKhw div(it.khw);
-        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
-            const int64_t base = it.base + (int64_t)rr * row_len;
-            if (mask[it.g0 + rr]) {
-                if (!both) continue;
-                // kept filter of a BOTH layer: only the columns of pruned channels change
-                if (vec) {
-                    const int nchunk = row_len >> 2;
-                    for (int c = j; c < nchunk; c += lpr) {
-                        const int col = c << 2;
-                        bool pr[4];
-                        if (it.khw == 1) {
-                            unsigned int m4;
-                            __builtin_memcpy(&m4, mc + col, 4);
-                            for (int i = 0; i < 4; ++i) pr[i] = ((m4 >> (8 * i)) & 0xffu) == 0u;
-                        } else {
-                            for (int i = 0; i < 4; ++i) pr[i] = mc[div(col + i)] == 0;
-                        }
-                        if (!(pr[0] || pr[1] || pr[2] || pr[3])) continue;
-                        const int64_t e = base + col;
-                        const v4f z = ld4(Z + e);
-                        if (pr[0] && pr[1] && pr[2] && pr[3]) {
-                            st4(U + e, z);
-                            st4(Z + e, zero4);
-                        } else {
-                            if (pr[0]) { st1(U + e + 0, z.x); st1(Z + e + 0, 0.f); }
-                            if (pr[1]) { st1(U + e + 1, z.y); st1(Z + e + 1, 0.f); }
-                            if (pr[2]) { st1(U + e + 2, z.z); st1(Z + e + 2, 0.f); }
-                            if (pr[3]) { st1(U + e + 3, z.w); st1(Z + e + 3, 0.f); }
-                        }
-                    }
-                } else {
-                    for (int c = j; c < row_len; c += lpr) {
-                        if (mc[div(c)] != 0) continue;
-                        st1(U + base + c, ld1(Z + base + c));
-                        st1(Z + base + c, 0.f);
-                    }
-                }
-                continue;
-            }
+    // lanes-per-row mapping as in pass 1 (the mapping carries no arithmetic here)
+    const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+    const int rows_at_once = kBlock / lpr;
+    const int sub = threadIdx.x / lpr;
+    const int j = threadIdx.x - sub * lpr;
+    const bool columns = mode_has_channels(mode);
+    // channel bytes of the layer (CHANNEL row item: g0 is the layer's first group)
+    const uint8_t* mc = mask + (mode == HSADMM_MODE_BOTH ? it.aux : (int64_t)it.g0);
+    const DivKhw div(it.khw);
+    for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+        const int64_t base = it.base + (int64_t)rr * row_len;
+        const bool row_stays = mode == HSADMM_MODE_CHANNEL || mask[it.g0 + rr] != 0;
+        if (row_stays) {
+            if (!columns) continue;
             if (vec) {
                 const int nchunk = row_len >> 2;
                 for (int c = j; c < nchunk; c += lpr) {
-                    const int64_t e = base + ((int64_t)c << 2);
-                    st4(U + e, ld4(Z + e));
-                    st4(Z + e, zero4);
+                    const int col = c << 2;
+                    bool pr[4];
+                    quad_pruned(mc, div, col, pr);
+                    if (!(pr[0] || pr[1] || pr[2] || pr[3])) continue;
+                    const int64_t e = base + col;
+                    const v4f z = ld4(Z + e);
+                    if (pr[0] && pr[1] && pr[2] && pr[3]) {
+                        st4(U + e, z);
+                        st4(Z + e, zero4);
+                    } else {
+                        v4f u = ld4(U + e);
+                        v4f zn = z;
+                        if (pr[0]) { u.x = z.x; zn.x = 0.f; }
+                        if (pr[1]) { u.y = z.y; zn.y = 0.f; }
+                        if (pr[2]) { u.z = z.z; zn.z = 0.f; }
+                        if (pr[3]) { u.w = z.w; zn.w = 0.f; }
+                        st4(U + e, u);
+                        st4(Z + e, zn);
+                    }
                 }
             } else {
                 for (int c = j; c < row_len; c += lpr) {
+                    if (mc[div(c)] != 0) continue;
                     st1(U + base + c, ld1(Z + base + c));
                     st1(Z + base + c, 0.f);
                 }
             }
-        }
-    } else {
-        const int vw = vec ? 4 : 1;
-        const int col = it.col0 + lane * vw;
-        if (col >= row_len) return;
-        bool pr[4] = {false, false, false, false};
-        bool any = false;
-        for (int i = 0; i < vw; ++i) {
-            pr[i] = mask[it.g0 + (col + i) / it.khw] == 0;
-            any = any || pr[i];
-        }
-        if (!any) return;
-        const bool all = pr[0] && pr[1] && pr[2] && pr[3];
-        for (int rr = wave; rr < it.nr; rr += kWaves) {
-            const int64_t e = it.base + (int64_t)rr * row_len + col;
-            if (vec) {
-                // a fully pruned quad moves as 128 bits; a partly pruned one stores its pruned
-                // elements one by one (merging through a read of U costs more traffic than it saves)
-                const v4f z = ld4(Z + e);
-                if (all) {
-                    st4(U + e, z);
-                    st4(Z + e, zero4);
-                } else {
-                    if (pr[0]) { st1(U + e + 0, z.x); st1(Z + e + 0, 0.f); }
-                    if (pr[1]) { st1(U + e + 1, z.y); st1(Z + e + 1, 0.f); }
-                    if (pr[2]) { st1(U + e + 2, z.z); st1(Z + e + 2, 0.f); }
-                    if (pr[3]) { st1(U + e + 3, z.w); st1(Z + e + 3, 0.f); }
-                }
-            } else {
-                U[e] = Z[e];
-                Z[e] = 0.f;
+        } else if (vec) {
+            const int nchunk = row_len >> 2;
+            for (int c = j; c < nchunk; c += lpr) {
+                const int64_t e = base + ((int64_t)c << 2);
+                st4(U + e, ld4(Z + e));
+                st4(Z + e, zero4);
+            }
+        } else {
+            for (int c = j; c < row_len; c += lpr) {
+                st1(U + base + c, ld1(Z + base + c));
+                st1(Z + base + c, 0.f);
             }
         }
     }

@@ -221,8 +221,17 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
             double acc = 0.0;
             const double* cg = cp + (int64_t)g * L.khw;
             int rb = 0;
+            // same order of additions as the plain loop below, with many loads in flight
+            if (L.khw == 1) {
+                for (; rb + 16 <= L.n_rowblocks; rb += 16) {
+                    double x[16];
+#pragma unroll
+                    for (int b = 0; b < 16; ++b) x[b] = cg[(int64_t)(rb + b) * L.row_len];
+#pragma unroll
+                    for (int b = 0; b < 16; ++b) acc += x[b];
+                }
+            }
             if (L.khw <= 9) {
-                // same order of additions as the plain loop below, with four row blocks' loads in flight
                 for (; rb + 4 <= L.n_rowblocks; rb += 4) {
                     double x[4][9];
 #pragma unroll
