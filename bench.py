@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--no-verify", action="store_true", help="skip the one-shot oracle check of the outputs")
     ap.add_argument("--expand-rescan", action="store_true",
                     help="hsadmm_expand recomputes positions from the mask instead of reusing hsadmm_compact's")
+    ap.add_argument("--skip-extras", action="store_true",
+                    help="time the base step only (no frozen-mask, weighted, residual and composite sections): "
+                         "the form the rocprofv3 summaries under profiles/ are taken with")
     ap.add_argument("--sets", type=int, default=3,
                     help="independent copies of every buffer the steps rotate over, so that no step finds "
                          "its own data from the previous step in the caches")
@@ -178,157 +181,158 @@ def main():
                 if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == dom:
                     roofline["traffic"] = int(parts[2])
 
-    # ---- frozen-mask step (Algorithm 1 Phase 3 once the masks are frozen, Section 4.5): the same three calls
-    #      with hsadmm_project_frozen in place of hsadmm_project, applying each buffer set's last mask
-    def frozen_step():
-        b = sets[counter[0] % nsets]
-        counter[0] += 1
-        pkg.hsadmm_project_frozen(plan, b.W, b.U, b.Z, None, b.mask, stream=stream)
-        pkg.hsadmm_compact(plan, b.Z, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
-        pkg.hsadmm_expand(plan, b.packed, None, b.dst, b.ws, stream=stream)
-
-    fsteps = max(1, args.steps // 2)
-    for _ in range(max(3, args.warmup // 2)):
-        frozen_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(fsteps):
-        frozen_step()
-    torch.cuda.synchronize()
-    f_elapsed = (time.perf_counter() - t0) / fsteps
-    pkg.hsadmm_kernel_timing_enable(plan, True)
-    for _ in range(fsteps):
-        frozen_step()
-    torch.cuda.synchronize()
-    ft = pkg.hsadmm_kernel_timing_read(plan)
-    pkg.hsadmm_kernel_timing_enable(plan, False)
-    f_us = 1e3 * ft["project_frozen"][0] / max(1, ft["project_frozen"][1])
-    frozen = {"ms_per_step": round(1e3 * f_elapsed, 4),
-              "value_GBps": round(bytes_["step"] / f_elapsed / 1e9, 1),
-              "hbm_frac": round(bytes_["step"] / f_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
-              "project_frozen_us_per_launch": round(f_us, 2),
-              "project_frozen_GBps": round(bytes_["project"] / (f_us * 1e-6) / 1e9, 1),
-              "project_frozen_frac": round(bytes_["project"] / (f_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
-
-    # ---- full node update (Eq. (9) with the rho_2 (z - v) term) + Phase 4 on one node:
-    #      hsadmm_project_weighted, hsadmm_compact_sum (c = z_i + v_i), hsadmm_expand, hsadmm_dual_inter (Eq. (13))
-    L = len(wl.layers)
-    wa, wb_ = pkg.hsadmm_node_coefficients([1.5e-3] * L, [1.5e-4] * L, 1e-4, 16, wl.R)   # the paper's initial penalties
-    pkg.hsadmm_plan_set_node_weights(plan, wa, wb_)
-    for b in sets:
-        b.Zg = torch.randn(n, dtype=torch.float32, device=dev) * 0.05
-        b.Vd = torch.randn(n, dtype=torch.float32, device=dev) * 0.01
-
-    def weighted_step():
-        b = sets[counter[0] % nsets]
-        counter[0] += 1
-        pkg.hsadmm_project_weighted(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, None, b.ws, stream=stream)
-        pkg.hsadmm_compact_sum(plan, b.Z, b.Vd, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
-        pkg.hsadmm_expand(plan, b.packed, None, b.dst, b.ws, stream=stream)
-        pkg.hsadmm_dual_inter(plan, b.Z, b.dst, b.Vd, stream=stream)
-
-    wsteps = max(1, args.steps // 4)
-    for _ in range(3):
-        weighted_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(wsteps):
-        weighted_step()
-    torch.cuda.synchronize()
-    w_elapsed = (time.perf_counter() - t0) / wsteps
-    pkg.hsadmm_kernel_timing_enable(plan, True)
-    for _ in range(wsteps):
-        weighted_step()
-    torch.cuda.synchronize()
-    wt = pkg.hsadmm_kernel_timing_read(plan)
-    pkg.hsadmm_kernel_timing_enable(plan, False)
-    # layer-wise residual norms (Algorithm 1 Phase 5) with all four operands: (R + 4) arenas read
-    res_out = torch.zeros(4 * L, dtype=torch.float64, device=dev)
-
-    def residual_call():
-        b = sets[counter[0] % nsets]
-        counter[0] += 1
-        pkg.hsadmm_residuals(plan, b.W, b.Z, b.dst, b.Zg, b.Vd, res_out, b.ws, stream=stream)
-
-    for _ in range(3):
-        residual_call()
-    pkg.hsadmm_kernel_timing_enable(plan, True)
-    for _ in range(wsteps):
-        residual_call()
-    torch.cuda.synchronize()
-    rt = pkg.hsadmm_kernel_timing_read(plan)
-    pkg.hsadmm_kernel_timing_enable(plan, False)
-    r_us = 1e3 * (rt["residual_partials"][0] + rt["residual_finish"][0]) / max(1, rt["residual_partials"][1])
-    r_bytes = 4 * wl.n_total * (wl.R + 4)
-    residuals = {"us_per_call": round(r_us, 2), "algorithmic_bytes": r_bytes,
-                 "GBps": round(r_bytes / (r_us * 1e-6) / 1e9, 1),
-                 "hbm_frac": round(r_bytes / (r_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
-    w_bytes = 4 * wl.n_total * (wl.R + 10) + 16 * nk
-    weighted = {"ms_per_step": round(1e3 * w_elapsed, 4),
-                "algorithmic_bytes_per_step": w_bytes,
-                "value_GBps": round(w_bytes / w_elapsed / 1e9, 1),
-                "hbm_frac": round(w_bytes / w_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
-                "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in wt.items() if v[1]}}
-
-    # ---- both constraints on every conv layer (filter + channel; Section 2.1's intersection, projected by the two
-    #      projections in sequence): the same shapes, replicas and duals under another layer table
-    composite = None
-    if args.workload == "resnet50":
-        wl2 = wk.make_workload("resnet50_both", seed=args.seed)
-        assert wl2.n_arena == wl.n_arena
-        plan2 = pkg.Plan(wl2.table())
-        for b in sets:
-            b.mask2 = torch.zeros(plan2.groups_total, dtype=torch.uint8, device=dev)
-            b.kept2 = torch.zeros(plan2.groups_total, dtype=torch.int32, device=dev)
-            b.ws2 = torch.zeros(plan2.workspace_bytes, dtype=torch.uint8, device=dev)
-            b.U.copy_(dU0)
-
-        def composite_step():
+    frozen = weighted = residuals = composite = None
+    if not args.skip_extras:
+        # ---- frozen-mask step (Algorithm 1 Phase 3 once the masks are frozen, Section 4.5): the same three calls
+        #      with hsadmm_project_frozen in place of hsadmm_project, applying each buffer set's last mask
+        def frozen_step():
             b = sets[counter[0] % nsets]
             counter[0] += 1
-            pkg.hsadmm_project(plan2, b.W, b.U, b.Z, None, b.mask2, None, b.ws2, stream=stream)
-            pkg.hsadmm_compact(plan2, b.Z, b.mask2, b.packed, b.off, b.kept2, b.ws2, stream=stream)
-            pkg.hsadmm_expand(plan2, b.packed, None, b.dst, b.ws2, stream=stream)
+            pkg.hsadmm_project_frozen(plan, b.W, b.U, b.Z, None, b.mask, stream=stream)
+            pkg.hsadmm_compact(plan, b.Z, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
+            pkg.hsadmm_expand(plan, b.packed, None, b.dst, b.ws, stream=stream)
 
-        if not args.no_verify:
-            import oracle
-            counter[0] = 0
-            composite_step()
-            torch.cuda.synchronize()
-            r2 = oracle.project(wl2.table(), W, U)
-            c2 = oracle.compact(wl2.table(), r2["Z"], r2["mask"])
-            b0 = sets[0]
-            ok2 = (np.array_equal(b0.mask2.cpu().numpy(), r2["mask"])
-                   and np.array_equal(b0.Z.cpu().numpy().view(np.uint32), r2["Z"].view(np.uint32))
-                   and np.array_equal(b0.U.cpu().numpy().view(np.uint32), r2["U"].view(np.uint32))
-                   and np.array_equal(b0.packed.cpu().numpy()[:int(c2["layer_off"][-1])].view(np.uint32),
-                                      c2["packed"].view(np.uint32))
-                   and np.array_equal(b0.dst.cpu().numpy().view(np.uint32), r2["Z"].view(np.uint32)))
-            if not ok2:
-                print("bench.py: composite outputs differ from the oracle", file=sys.stderr)
-                sys.exit(4)
-        csteps = max(1, args.steps // 2)
+        fsteps = max(1, args.steps // 2)
         for _ in range(max(3, args.warmup // 2)):
-            composite_step()
+            frozen_step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(csteps):
-            composite_step()
+        for _ in range(fsteps):
+            frozen_step()
         torch.cuda.synchronize()
-        c_elapsed = (time.perf_counter() - t0) / csteps
-        pkg.hsadmm_kernel_timing_enable(plan2, True)
-        for _ in range(csteps):
-            composite_step()
+        f_elapsed = (time.perf_counter() - t0) / fsteps
+        pkg.hsadmm_kernel_timing_enable(plan, True)
+        for _ in range(fsteps):
+            frozen_step()
         torch.cuda.synchronize()
-        ct = pkg.hsadmm_kernel_timing_read(plan2)
-        pkg.hsadmm_kernel_timing_enable(plan2, False)
-        c_bytes = wl2.algorithmic_bytes()["step"]
-        composite = {"workload": wl2.description, "kept_params": wl2.n_kept,
-                     "ms_per_step": round(1e3 * c_elapsed, 4), "algorithmic_bytes_per_step": c_bytes,
-                     "value_GBps": round(c_bytes / c_elapsed / 1e9, 1),
-                     "hbm_frac": round(c_bytes / c_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
-                     "kernel_us_per_step": {k: round(1e3 * v[0] / csteps, 2) for k, v in ct.items() if v[1]}}
-        plan2.close()
+        ft = pkg.hsadmm_kernel_timing_read(plan)
+        pkg.hsadmm_kernel_timing_enable(plan, False)
+        f_us = 1e3 * ft["project_frozen"][0] / max(1, ft["project_frozen"][1])
+        frozen = {"ms_per_step": round(1e3 * f_elapsed, 4),
+                  "value_GBps": round(bytes_["step"] / f_elapsed / 1e9, 1),
+                  "hbm_frac": round(bytes_["step"] / f_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                  "project_frozen_us_per_launch": round(f_us, 2),
+                  "project_frozen_GBps": round(bytes_["project"] / (f_us * 1e-6) / 1e9, 1),
+                  "project_frozen_frac": round(bytes_["project"] / (f_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+
+        # ---- full node update (Eq. (9) with the rho_2 (z - v) term) + Phase 4 on one node:
+        #      hsadmm_project_weighted, hsadmm_compact_sum (c = z_i + v_i), hsadmm_expand, hsadmm_dual_inter (Eq. (13))
+        L = len(wl.layers)
+        wa, wb_ = pkg.hsadmm_node_coefficients([1.5e-3] * L, [1.5e-4] * L, 1e-4, 16, wl.R)   # the paper's initial penalties
+        pkg.hsadmm_plan_set_node_weights(plan, wa, wb_)
+        for b in sets:
+            b.Zg = torch.randn(n, dtype=torch.float32, device=dev) * 0.05
+            b.Vd = torch.randn(n, dtype=torch.float32, device=dev) * 0.01
+
+        def weighted_step():
+            b = sets[counter[0] % nsets]
+            counter[0] += 1
+            pkg.hsadmm_project_weighted(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, None, b.ws, stream=stream)
+            pkg.hsadmm_compact_sum(plan, b.Z, b.Vd, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
+            pkg.hsadmm_expand(plan, b.packed, None, b.dst, b.ws, stream=stream)
+            pkg.hsadmm_dual_inter(plan, b.Z, b.dst, b.Vd, stream=stream)
+
+        wsteps = max(1, args.steps // 4)
+        for _ in range(3):
+            weighted_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(wsteps):
+            weighted_step()
+        torch.cuda.synchronize()
+        w_elapsed = (time.perf_counter() - t0) / wsteps
+        pkg.hsadmm_kernel_timing_enable(plan, True)
+        for _ in range(wsteps):
+            weighted_step()
+        torch.cuda.synchronize()
+        wt = pkg.hsadmm_kernel_timing_read(plan)
+        pkg.hsadmm_kernel_timing_enable(plan, False)
+        # layer-wise residual norms (Algorithm 1 Phase 5) with all four operands: (R + 4) arenas read
+        res_out = torch.zeros(4 * L, dtype=torch.float64, device=dev)
+
+        def residual_call():
+            b = sets[counter[0] % nsets]
+            counter[0] += 1
+            pkg.hsadmm_residuals(plan, b.W, b.Z, b.dst, b.Zg, b.Vd, res_out, b.ws, stream=stream)
+
+        for _ in range(3):
+            residual_call()
+        pkg.hsadmm_kernel_timing_enable(plan, True)
+        for _ in range(wsteps):
+            residual_call()
+        torch.cuda.synchronize()
+        rt = pkg.hsadmm_kernel_timing_read(plan)
+        pkg.hsadmm_kernel_timing_enable(plan, False)
+        r_us = 1e3 * (rt["residual_partials"][0] + rt["residual_finish"][0]) / max(1, rt["residual_partials"][1])
+        r_bytes = 4 * wl.n_total * (wl.R + 4)
+        residuals = {"us_per_call": round(r_us, 2), "algorithmic_bytes": r_bytes,
+                     "GBps": round(r_bytes / (r_us * 1e-6) / 1e9, 1),
+                     "hbm_frac": round(r_bytes / (r_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+        w_bytes = 4 * wl.n_total * (wl.R + 10) + 16 * nk
+        weighted = {"ms_per_step": round(1e3 * w_elapsed, 4),
+                    "algorithmic_bytes_per_step": w_bytes,
+                    "value_GBps": round(w_bytes / w_elapsed / 1e9, 1),
+                    "hbm_frac": round(w_bytes / w_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                    "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in wt.items() if v[1]}}
+
+        # ---- both constraints on every conv layer (filter + channel; Section 2.1's intersection, projected by the two
+        #      projections in sequence): the same shapes, replicas and duals under another layer table
+        if args.workload == "resnet50":
+            wl2 = wk.make_workload("resnet50_both", seed=args.seed)
+            assert wl2.n_arena == wl.n_arena
+            plan2 = pkg.Plan(wl2.table())
+            for b in sets:
+                b.mask2 = torch.zeros(plan2.groups_total, dtype=torch.uint8, device=dev)
+                b.kept2 = torch.zeros(plan2.groups_total, dtype=torch.int32, device=dev)
+                b.ws2 = torch.zeros(plan2.workspace_bytes, dtype=torch.uint8, device=dev)
+                b.U.copy_(dU0)
+
+            def composite_step():
+                b = sets[counter[0] % nsets]
+                counter[0] += 1
+                pkg.hsadmm_project(plan2, b.W, b.U, b.Z, None, b.mask2, None, b.ws2, stream=stream)
+                pkg.hsadmm_compact(plan2, b.Z, b.mask2, b.packed, b.off, b.kept2, b.ws2, stream=stream)
+                pkg.hsadmm_expand(plan2, b.packed, None, b.dst, b.ws2, stream=stream)
+
+            if not args.no_verify:
+                import oracle
+                counter[0] = 0
+                composite_step()
+                torch.cuda.synchronize()
+                r2 = oracle.project(wl2.table(), W, U)
+                c2 = oracle.compact(wl2.table(), r2["Z"], r2["mask"])
+                b0 = sets[0]
+                ok2 = (np.array_equal(b0.mask2.cpu().numpy(), r2["mask"])
+                       and np.array_equal(b0.Z.cpu().numpy().view(np.uint32), r2["Z"].view(np.uint32))
+                       and np.array_equal(b0.U.cpu().numpy().view(np.uint32), r2["U"].view(np.uint32))
+                       and np.array_equal(b0.packed.cpu().numpy()[:int(c2["layer_off"][-1])].view(np.uint32),
+                                          c2["packed"].view(np.uint32))
+                       and np.array_equal(b0.dst.cpu().numpy().view(np.uint32), r2["Z"].view(np.uint32)))
+                if not ok2:
+                    print("bench.py: composite outputs differ from the oracle", file=sys.stderr)
+                    sys.exit(4)
+            csteps = max(1, args.steps // 2)
+            for _ in range(max(3, args.warmup // 2)):
+                composite_step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(csteps):
+                composite_step()
+            torch.cuda.synchronize()
+            c_elapsed = (time.perf_counter() - t0) / csteps
+            pkg.hsadmm_kernel_timing_enable(plan2, True)
+            for _ in range(csteps):
+                composite_step()
+            torch.cuda.synchronize()
+            ct = pkg.hsadmm_kernel_timing_read(plan2)
+            pkg.hsadmm_kernel_timing_enable(plan2, False)
+            c_bytes = wl2.algorithmic_bytes()["step"]
+            composite = {"workload": wl2.description, "kept_params": wl2.n_kept,
+                         "ms_per_step": round(1e3 * c_elapsed, 4), "algorithmic_bytes_per_step": c_bytes,
+                         "value_GBps": round(c_bytes / c_elapsed / 1e9, 1),
+                         "hbm_frac": round(c_bytes / c_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                         "kernel_us_per_step": {k: round(1e3 * v[0] / csteps, 2) for k, v in ct.items() if v[1]}}
+            plan2.close()
 
     # ---- context: a plain device copy of the same size class (practical streaming ceiling)
     a_src, a_dst = sets[0].W[0], sets[0].Z

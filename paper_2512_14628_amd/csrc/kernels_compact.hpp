@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
         const int32_t* kl = kept_idx + cnt[n_layers + it.layer] + (both ? cnt[it.layer] : 0);
         const DivKhw div(khw);
         const int quads = out_len >> 2;
-        constexpr int kRows = 4;      // rows a wave keeps in flight: their loads are issued together
+        constexpr int kRows = 2;      // rows a wave keeps in flight: their loads are issued together
         for (int rr0 = wave; rr0 < it.nr; rr0 += kRows * kWaves) {
             int prow[kRows];
             int64_t ro[kRows];
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
         const DivKhw div(khw);
         const int32_t* pl = pos + (both ? it.aux : (int64_t)it.g0);
         const int quads = item_vec(it) ? (row_len >> 2) : 0;
-        constexpr int kRows = 4;      // rows a wave keeps in flight
+        constexpr int kRows = 2;      // rows a wave keeps in flight
         for (int rr0 = wave; rr0 < it.nr; rr0 += kRows * kWaves) {
             int prow[kRows];
             bool live[kRows];
