@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-verify", action="store_true", help="skip the one-shot oracle check of the outputs")
+    ap.add_argument("--compact-rescan", action="store_true",
+                    help="hsadmm_compact derives the index mappings from the mask (scan_mask) instead of reusing those "
+                         "the selection inside hsadmm_project left in the workspace")
     ap.add_argument("--expand-rescan", action="store_true",
                     help="hsadmm_expand recomputes positions from the mask instead of reusing hsadmm_compact's")
     ap.add_argument("--skip-extras", action="store_true",
@@ -94,9 +97,11 @@ def main():
         b = sets[counter[0] % nsets]
         counter[0] += 1
         pkg.hsadmm_project(plan, b.W, b.U, b.Z, None, b.mask, None, b.ws, stream=stream)
-        pkg.hsadmm_compact(plan, b.Z, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
-        # expansion reuses the index mappings the compaction just cached in the workspace (mask = NULL), as
-        # the paper's recovery step does (Section 4.4.3); --expand-rescan derives them from the mask again
+        # compaction and expansion reuse the index mappings (kept positions, counts, offsets) that the selection
+        # inside hsadmm_project left in the workspace (mask = NULL), as the paper's recovery step reuses its cached
+        # index sets (Section 4.4.3); --compact-rescan / --expand-rescan derive them from the mask again
+        pkg.hsadmm_compact(plan, b.Z, b.mask if args.compact_rescan else None, b.packed, b.off, b.kept, b.ws,
+                           stream=stream)
         pkg.hsadmm_expand(plan, b.packed, b.mask if args.expand_rescan else None, b.dst, b.ws, stream=stream)
 
     # ---- one-shot correctness check against the oracle (outside every timed region)
@@ -228,7 +233,8 @@ def main():
             b = sets[counter[0] % nsets]
             counter[0] += 1
             pkg.hsadmm_project_weighted(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, None, b.ws, stream=stream)
-            pkg.hsadmm_compact_sum(plan, b.Z, b.Vd, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
+            pkg.hsadmm_compact_sum(plan, b.Z, b.Vd, b.mask if args.compact_rescan else None, b.packed, b.off, b.kept,
+                                   b.ws, stream=stream)
             pkg.hsadmm_expand(plan, b.packed, None, b.dst, b.ws, stream=stream)
             pkg.hsadmm_dual_inter(plan, b.Z, b.dst, b.Vd, stream=stream)
 
@@ -291,7 +297,8 @@ def main():
                 b = sets[counter[0] % nsets]
                 counter[0] += 1
                 pkg.hsadmm_project(plan2, b.W, b.U, b.Z, None, b.mask2, None, b.ws2, stream=stream)
-                pkg.hsadmm_compact(plan2, b.Z, b.mask2, b.packed, b.off, b.kept2, b.ws2, stream=stream)
+                pkg.hsadmm_compact(plan2, b.Z, b.mask2 if args.compact_rescan else None, b.packed, b.off, b.kept2, b.ws2,
+                               stream=stream)
                 pkg.hsadmm_expand(plan2, b.packed, None, b.dst, b.ws2, stream=stream)
 
             if not args.no_verify:
@@ -384,6 +391,7 @@ def main():
         "config": {"workload": "%s: %s" % (wl.name, wl.description), "layers": len(wl.layers),
                    "params": wl.n_total, "replicas": wl.R, "kept_params": nk, "seed": wl.seed,
                    "buffer_sets_rotated": nsets, "expand_reuses_cached_index_mappings": not args.expand_rescan,
+                   "compact_reuses_the_selections_index_mappings": not args.compact_rescan,
                    "algorithmic_bytes_per_step": bytes_["step"]},
         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
         "params_per_s": round(params_per_s, 1),

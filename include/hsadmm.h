@@ -30,7 +30,10 @@
  * hsadmm_plan_destroy).  The three hot calls allocate nothing, never
  * synchronise the device, and enqueue all their work on `hip_stream`
  * (a hipStream_t passed as void*; NULL is the default stream).  Outputs are
- * valid once the caller has synchronised that stream.
+ * valid once the caller has synchronised that stream.  The workspace also
+ * carries the index mappings of the compaction (kept positions, counts,
+ * offsets) from the call that derives them to the calls that reuse them, so
+ * calls that share a workspace must be ordered on one stream.
  *
  * Errors.  Every call returns HSADMM_OK (0) or a negative code.  Arguments
  * are validated before anything is enqueued, so a call that returns an
@@ -178,7 +181,14 @@ int hsadmm_mask_or(const hsadmm_plan_t* plan, const uint8_t* const* masks, int32
  * count 0..G), not from the plan's k, so a union of several masks is valid.
  *
  *   src        device, full-layout arena (read only), 16-byte aligned
- *   mask       device, groups_total bytes, nonzero = kept
+ *   mask       device, groups_total bytes, nonzero = kept; or NULL: pack under
+ *              the index mappings already held in this workspace -- those of
+ *              the selection the most recent hsadmm_project /
+ *              hsadmm_project_weighted made (its mask, without scanning it
+ *              again), or of the most recent hsadmm_compact / hsadmm_expand
+ *              that was given a mask, whichever used the workspace last.
+ *              With NULL the caller guarantees that one of them has run on
+ *              this plan, workspace and stream.
  *   packed     device, out, at least packed_capacity_elems elements; only
  *              layer_off[L] elements are meaningful; alignment padding between
  *              segments is not written
@@ -278,10 +288,8 @@ int hsadmm_residuals(const hsadmm_plan_t* plan, const float* const* W_replicas, 
  *
  *   packed     device, read only, as produced by hsadmm_compact for this mask
  *   mask       device, groups_total bytes; or NULL: reuse the index mappings
- *              that the most recent hsadmm_compact call on this plan left in
- *              this same workspace (the cached K_out / K_in of Section 4.4.3).
- *              With NULL the caller guarantees that no other call has used
- *              the workspace since that hsadmm_compact, on this stream.
+ *              held in this workspace (the cached K_out / K_in of Section
+ *              4.4.3), as described for hsadmm_compact.
  *   dst        device, out, full-layout arena, 16-byte aligned
  * Errors: INVALID_ARGUMENT, WORKSPACE, HIP.
  */

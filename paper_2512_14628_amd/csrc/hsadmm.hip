@@ -189,29 +189,34 @@ hipError_t launch_frozen(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, co
 // (CHANNEL) are in place.  Layers under both constraints then take their second projection: channel
 // norms over the kept filters from the candidate held in Z, and the selection of the channels.
 hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, const float* Z, uint8_t* mask,
-                         hipStream_t s)
+                         char* ws, hipStream_t s)
 {
+    // the selection also leaves its index mappings in the workspace, for a compaction without a mask
+    IndexMaps im;
+    im.pos = reinterpret_cast<int32_t*>(ws + p->ws.pos);
+    im.cnt = reinterpret_cast<int32_t*>(ws + p->ws.cnt);
+    im.layer_off = reinterpret_cast<int64_t*>(ws + p->ws.layer_off);
+    im.kept_idx = reinterpret_cast<int32_t*>(ws + p->ws.kept_idx);
+    const int nL = (int)p->layers.size();
     hipError_t e = launch(p, kTopk, select_topk, (unsigned)p->layers.size(), kScanBlock, s,
                           (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
-                          (const int32_t*)nullptr, 0);
+                          (const int32_t*)nullptr, 0, im, nL, (int)p->pack_align);
     if (e != hipSuccess || p->both_layers.empty()) return e;
     e = launch(p, kColsums, composite_colsums, (unsigned)p->items_both.size(), kBlock, s,
                (const WorkItem*)p->d_items_both, Z, (const uint8_t*)mask, colpart);
     if (e != hipSuccess) return e;
     return launch(p, kTopk, select_topk, (unsigned)p->both_layers.size(), kScanBlock, s,
                   (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
-                  (const int32_t*)p->d_both_layers, 1);
+                  (const int32_t*)p->d_both_layers, 1, im, nL, (int)p->pack_align);
 }
 
-int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, int64_t* layer_off_out, int32_t* kept_idx,
-             hipStream_t s)
+int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, hipStream_t s)
 {
-    ScanOut o;
+    IndexMaps o;
     o.pos = reinterpret_cast<int32_t*>(ws + p->ws.pos);
     o.cnt = reinterpret_cast<int32_t*>(ws + p->ws.cnt);
     o.layer_off = reinterpret_cast<int64_t*>(ws + p->ws.layer_off);
-    o.layer_off_out = layer_off_out;
-    o.kept_idx = kept_idx;
+    o.kept_idx = reinterpret_cast<int32_t*>(ws + p->ws.kept_idx);
     const hipError_t e = launch(p, kScan, scan_mask, (unsigned)p->layers.size(), kScanBlock, s,
                                 (const DevLayer*)p->d_layers, (int)p->layers.size(), (int)p->n_segments,
                                 (int)p->groups_total,
@@ -251,8 +256,8 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->pack_align = pack_align_elems;
         p->layers.assign(layers, layers + L);
         p->arena_elems = prev_end;
-        int64_t gb = 0, cp = 0, cap = 0;
-        int32_t seg = 0;
+        int64_t gb = 0, cp = 0, cap = 0, poff = 0;
+        int32_t seg = 0, kstart = 0;
         group_layer.clear();
         for (int32_t l = 0; l < L; ++l) {
             const hsadmm_layer_t& x = layers[l];
@@ -274,6 +279,12 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             else if (both) d.unit = x.khw;
             else d.unit = (int64_t)x.c_out * d.row_len;
             if (has_colsums) cp += (int64_t)d.n_rowblocks * d.row_len;
+            // where the layer starts in the packed buffer / in kept_idx when the mask is the plan's own selection
+            d.packed_off = poff;
+            d.kept_start = kstart;
+            const int32_t c0 = x.mode == HSADMM_MODE_NONE ? d.G : x.k;
+            poff += packed_size(x.mode, d.unit, c0, d.k_in, pack_align_elems);
+            kstart += c0 + d.k_in;
             gb += d.G;
             cap += (int64_t)x.c_out * d.row_len;
             cap = (cap + pack_align_elems - 1) / pack_align_elems * pack_align_elems;
@@ -423,7 +434,7 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
         default: e = launch_pass1<0>(p, a, R, s); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
-    if (run_selection(p, a.key, a.colpart, Z, mask, s) != hipSuccess) return HSADMM_ERR_HIP;
+    if (run_selection(p, a.key, a.colpart, Z, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
     e = launch(p, kFixup, project_fixup, (unsigned)p->items_rows.size(), kBlock, s,
                (const WorkItem*)p->d_items_rows, (const uint8_t*)mask, U, Z);
     if (e != hipSuccess) return HSADMM_ERR_HIP;
@@ -477,7 +488,7 @@ static int compact_impl(const hsadmm_plan_t* p, const float* src, const float* s
                         float* packed, int64_t* layer_off, int32_t* kept_idx, void* workspace,
                         size_t workspace_bytes, void* hip_stream)
 {
-    if (!p || !src || (sum && !src1) || !mask || !packed || !layer_off || !kept_idx || !workspace)
+    if (!p || !src || (sum && !src1) || !packed || !layer_off || !kept_idx || !workspace)
         return HSADMM_ERR_INVALID_ARGUMENT;
     if (!is_aligned(src, 16) || (sum && !is_aligned(src1, 16)) || !is_aligned(packed, 16) ||
         !is_aligned(layer_off, 8) || !is_aligned(kept_idx, 4) || !is_aligned(workspace, 256))
@@ -485,20 +496,26 @@ static int compact_impl(const hsadmm_plan_t* p, const float* src, const float* s
     if (workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
-    const int rc = run_scan(p, mask, ws, layer_off, kept_idx, s);
-    if (rc != HSADMM_OK) return rc;
+    // The index mappings live in the workspace: derived from the mask here, or (mask == NULL) those the last
+    // projection, compaction or expansion left there.  The gather hands the caller its copies.
+    const int32_t* kidx = reinterpret_cast<const int32_t*>(ws + p->ws.kept_idx);
+    CopyOut co{layer_off, kept_idx};
+    if (mask) {
+        const int rc = run_scan(p, mask, ws, s);
+        if (rc != HSADMM_OK) return rc;
+    }
     const int32_t* pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
     const int32_t* cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
     const int64_t* lo = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
     hipError_t e;
     if (sum)
         e = launch(p, kGather, compact_gather<true>, (unsigned)p->items_rows.size(), kBlock, s,
-                   (const WorkItem*)p->d_items_rows, src, src1, pos, cnt, (const int32_t*)kept_idx,
-                   (int)p->layers.size(), lo, packed);
+                   (const WorkItem*)p->d_items_rows, src, src1, pos, cnt, kidx,
+                   (int)p->layers.size(), lo, packed, co);
     else
         e = launch(p, kGather, compact_gather<false>, (unsigned)p->items_rows.size(), kBlock, s,
-                   (const WorkItem*)p->d_items_rows, src, (const float*)nullptr, pos, cnt, (const int32_t*)kept_idx,
-                   (int)p->layers.size(), lo, packed);
+                   (const WorkItem*)p->d_items_rows, src, (const float*)nullptr, pos, cnt, kidx,
+                   (int)p->layers.size(), lo, packed, co);
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
@@ -579,7 +596,7 @@ int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replic
         default: e = launch(p, kWKeys, weighted_keys<0>, grid, kBlock, s, items, w, (int)R); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
-    if (run_selection(p, w.p.key, w.p.colpart, Z, mask, s) != hipSuccess) return HSADMM_ERR_HIP;
+    if (run_selection(p, w.p.key, w.p.colpart, Z, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
     const uint8_t* cm = mask;
     switch (R) {
         case 1: e = launch(p, kWFinal, weighted_final<1>, grid, kBlock, s, items, w, (int)R, cm); break;
@@ -644,7 +661,7 @@ int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* ma
     char* ws = static_cast<char*>(workspace);
     const int64_t* lo = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
     if (mask) {
-        const int rc = run_scan(p, mask, ws, nullptr, reinterpret_cast<int32_t*>(ws + p->ws.kept_idx), s);
+        const int rc = run_scan(p, mask, ws, s);
         if (rc != HSADMM_OK) return rc;
     }   // else: the positions and offsets the last hsadmm_compact left in this workspace are used
     const hipError_t e = launch(p, kScatter, expand_scatter, (unsigned)p->items_rows.size(), kBlock, s,

@@ -24,6 +24,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 struct DevLayer {
     int64_t elem_off;
     int64_t colpart_off;    // CHANNEL: first double of this layer's per-row-block column sums
+    int64_t packed_off;     // start of the layer in the packed buffer when exactly k (and k_in) groups are kept
     int64_t unit;           // packed elements one kept group contributes (NONE: the whole layer;
                             // BOTH: khw, the layer packs K_out * K_in * khw elements)
     int32_t c_out, c_in, khw, mode, k;
@@ -33,9 +34,27 @@ struct DevLayer {
     int32_t rows_items;     // number of them
     int32_t k_in;           // BOTH: channels kept
     int32_t seg0;           // first scan segment of the layer (a BOTH layer has two: filters, channels)
-    int32_t pad_;
+    int32_t kept_start;     // start of the layer's run in kept_idx when exactly k (and k_in) groups are kept
 };
-static_assert(sizeof(DevLayer) == 80, "DevLayer layout");
+static_assert(sizeof(DevLayer) == 88, "DevLayer layout");
+
+// Packed elements of a layer that keeps c0 groups (BOTH: c0 filters and c1 channels), rounded up to pack_align.
+__host__ __device__ __forceinline__ long long packed_size(int mode, long long unit, int c0, int c1, int pack_align)
+{
+    long long s = (mode == HSADMM_MODE_NONE) ? unit : (long long)c0 * unit;
+    if (mode == HSADMM_MODE_BOTH) s *= c1;          // K_out * K_in * khw
+    return (s + pack_align - 1) / pack_align * pack_align;
+}
+
+// Index mappings of the compaction, kept in the workspace: written by scan_mask from a mask, or by
+// select_topk for the selection it has just made (then the counts are the plan's k / k_in).
+struct IndexMaps {
+    int32_t* pos;        // groups_total: rank of a kept group inside its segment, -1 if pruned
+    int32_t* cnt;        // 3L: kept groups of every layer's first segment, the start of every layer's
+                         // run in kept_idx, kept groups of the second segment (BOTH: channels; else 0)
+    int64_t* layer_off;  // L+1
+    int32_t* kept_idx;   // groups_total
+};
 
 // One unit of work for a 256-thread workgroup; it carries everything the streaming kernels need,
 // so a workgroup starts with a single 64-byte scalar load.

@@ -9,15 +9,6 @@ namespace {
 
 // ------------------------------------------------------------------ mask scan (compact / expand)
 
-struct ScanOut {
-    int32_t* pos;        // groups_total: rank of a kept group inside its segment, -1 if pruned
-    int32_t* cnt;        // 3L: kept groups of every layer's first segment, the start of every layer's
-                         // run in kept_idx, kept groups of the second segment (BOTH: channels; else 0)
-    int64_t* layer_off;  // L+1, in the workspace (kept there for a later hsadmm_expand without a mask)
-    int64_t* layer_off_out;  // L+1, the caller's copy; may be null
-    int32_t* kept_idx;   // groups_total
-};
-
 __device__ __forceinline__ int nonzero_bytes(unsigned int x)
 {
     // bit 7 of every byte becomes 1 iff the byte is nonzero
@@ -34,18 +25,11 @@ __device__ __forceinline__ int nonzero_bytes(unsigned int x)
 // layer, whose groups are always kept).  The workgroup then sums the aligned packed sizes of layers
 // 0..l-1 to get its own offset in the packed buffer and scans its own layer's mask.  Packed starts
 // are multiples of pack_align, so the offset is the plain sum of the rounded-up sizes.
-__device__ __forceinline__ long long packed_size(int mode, long long unit, int c0, int c1, int pack_align)
-{
-    long long s = (mode == HSADMM_MODE_NONE) ? unit : (long long)c0 * unit;
-    if (mode == HSADMM_MODE_BOTH) s *= c1;          // K_out * K_in * khw
-    return (s + pack_align - 1) / pack_align * pack_align;
-}
-
 __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restrict__ layers, int nL, int nSeg,
                                                         int n_groups, int pack_align,
                                                         const uint8_t* __restrict__ mask,
                                                         const uint16_t* __restrict__ group_layer,
-                                                        const uint16_t* __restrict__ chunk_layer, ScanOut o)
+                                                        const uint16_t* __restrict__ chunk_layer, IndexMaps o)
 {
     __shared__ int cnt[2 * HSADMM_MAX_LAYERS];      // per segment
     __shared__ int wtot[kScanWaves];
@@ -154,14 +138,12 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
     const int own1 = both ? cnt[L.seg0 + 1] : 0;
     if (tid == 0) {
         o.layer_off[l] = pos;
-        if (o.layer_off_out) o.layer_off_out[l] = pos;
         o.cnt[l] = own0;
         o.cnt[nL + l] = kb;
         o.cnt[2 * nL + l] = own1;
         if (l == nL - 1) {
             const long long s = packed_size(L.mode, L.unit, own0, own1, pack_align);
             o.layer_off[nL] = pos + s;
-            if (o.layer_off_out) o.layer_off_out[nL] = pos + s;
         }
     }
     // ranks inside each of the layer's segments; kept_idx lists the first segment, then the second
@@ -186,6 +168,13 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
 
 // ------------------------------------------------------------------ compaction (gather)
 
+// Where the first work item of every layer copies the layer's part of the index mappings held in the workspace
+// (the caller's layer_off / kept_idx).
+struct CopyOut {
+    int64_t* layer_off;
+    int32_t* kept_idx;
+};
+
 // SUM: the source is the element-wise sum of two arenas (c = z_i + v_i, Section 4.4.1), formed on the fly.
 template <bool SUM>
 __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restrict__ items,
@@ -195,12 +184,22 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
                                                          const int32_t* __restrict__ cnt,
                                                          const int32_t* __restrict__ kept_idx, int n_layers,
                                                          const int64_t* __restrict__ layer_off,
-                                                         float* __restrict__ packed)
+                                                         float* __restrict__ packed, CopyOut co)
 {
     const WorkItem it = items[blockIdx.x];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int row_len = it.row_len;
+    if (it.row0 == 0) {
+        const int l = it.layer;
+        const int start = cnt[n_layers + l];
+        const int nk = cnt[l] + cnt[2 * n_layers + l];
+        for (int i = threadIdx.x; i < nk; i += kBlock) co.kept_idx[start + i] = kept_idx[start + i];
+        if (threadIdx.x == 0) {
+            co.layer_off[l] = layer_off[l];
+            if (l == n_layers - 1) co.layer_off[n_layers] = layer_off[n_layers];
+        }
+    }
     float* out = packed + layer_off[it.layer];
     if (!mode_has_channels(item_mode(it))) {
         const int lpr = it.lpr <= kWave ? it.lpr : kBlock;

@@ -79,8 +79,11 @@ struct LayerKeys {
 // keys differ (one 256-bin histogram per pass).  `need` tracks how many groups must still be taken
 // from the candidates that share the prefix found so far.  Groups with key > tau are kept; of the
 // groups with key == tau the first `need` in index order are kept.
+// pos_l / kidx_l receive the layer's index mappings: the rank of every kept group (-1: pruned) and the
+// ascending list of the kept groups.
 template <bool INREG>
-__device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, uint8_t* ml, int kk, TopkShared& sh)
+__device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, uint8_t* ml, int kk, TopkShared& sh,
+                                           int32_t* pos_l, int32_t* kidx_l)
 {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -170,11 +173,9 @@ __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, 
             scan_ties = (unsigned int)need != sh.cand;        // fewer wanted than tied: index order decides
         }
     }
-    if (!scan_ties) {
-        keys.for_each([&](int g, unsigned long long x) { ml[g] = (x >= tau) ? 1 : 0; });
-        return;
-    }
-    int carry = 0;
+    // final pass in index order: the kept flag (ties: the first `need` groups equal to tau), then the rank
+    // of every kept group among the kept ones
+    int carry_eq = 0, carry_kept = 0;
     for (int base = 0; base < G; base += kScanBlock) {
         const int g = base + tid;
         unsigned long long x = 0ull;
@@ -186,12 +187,23 @@ __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, 
                 x = kb[g];
             }
         }
-        const bool eq = (g < G) && (x == tau);
-        const bool gt = (g < G) && (x > tau);
-        int total;
-        const int rank = carry + block_excl_scan<kScanWaves>(eq, sh.wtot, total);
-        if (g < G) ml[g] = (gt || (eq && rank < need)) ? 1 : 0;
-        carry += total;
+        bool kept = (g < G) && (x >= tau);
+        if (scan_ties) {
+            const bool eq = (g < G) && (x == tau);
+            const bool gt = (g < G) && (x > tau);
+            int total;
+            const int rank = carry_eq + block_excl_scan<kScanWaves>(eq, sh.wtot, total);
+            kept = gt || (eq && rank < need);
+            carry_eq += total;
+        }
+        int total_kept;
+        const int r = carry_kept + block_excl_scan<kScanWaves>(kept, sh.wtot, total_kept);
+        if (g < G) {
+            ml[g] = kept ? 1 : 0;
+            pos_l[g] = kept ? r : -1;
+            if (kept) kidx_l[r] = g;
+        }
+        carry_kept += total_kept;
     }
 }
 
@@ -203,7 +215,8 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
                                                           double* __restrict__ key,
                                                           const double* __restrict__ colpart,
                                                           uint8_t* __restrict__ mask,
-                                                          const int32_t* __restrict__ layer_list, int stage)
+                                                          const int32_t* __restrict__ layer_list, int stage,
+                                                          IndexMaps im, int n_layers, int pack_align)
 {
     __shared__ TopkShared sh;
     const DevLayer L = layers[stage == 0 ? (int)blockIdx.x : layer_list[blockIdx.x]];
@@ -214,6 +227,18 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
     const int tid = threadIdx.x;
     double* kl = key + first;
     uint8_t* ml = mask + first;
+    // the index mappings of this selection (what scan_mask would derive from the mask)
+    int32_t* pos_l = im.pos + first;
+    int32_t* kidx_l = im.kept_idx + L.kept_start + ((both && stage == 1) ? L.k : 0);
+    if (tid == 0 && stage == 0) {
+        const int l = blockIdx.x;
+        const int c0 = (L.mode == HSADMM_MODE_NONE) ? L.G : L.k;
+        im.cnt[l] = c0;
+        im.cnt[n_layers + l] = L.kept_start;
+        im.cnt[2 * n_layers + l] = both ? L.k_in : 0;
+        im.layer_off[l] = L.packed_off;
+        if (l == n_layers - 1) im.layer_off[n_layers] = L.packed_off + packed_size(L.mode, L.unit, c0, L.k_in, pack_align);
+    }
     if (channels) {
         // key[c] = sum over row blocks (ascending), then over the channel's khw columns (ascending)
         const double* cp = colpart + L.colpart_off;
@@ -254,12 +279,12 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
     }
     const int kk = (L.mode == HSADMM_MODE_NONE) ? G : ((both && stage == 1) ? L.k_in : L.k);
     if (kk >= G) {
-        for (int g = tid; g < G; g += kScanBlock) ml[g] = 1;
+        for (int g = tid; g < G; g += kScanBlock) { ml[g] = 1; pos_l[g] = g; kidx_l[g] = g; }
         return;
     }
     const unsigned long long* kb = reinterpret_cast<const unsigned long long*>(kl);
-    if (G <= kTopkRegs * kScanBlock) topk_layer<true>(G, kb, ml, kk, sh);
-    else topk_layer<false>(G, kb, ml, kk, sh);
+    if (G <= kTopkRegs * kScanBlock) topk_layer<true>(G, kb, ml, kk, sh, pos_l, kidx_l);
+    else topk_layer<false>(G, kb, ml, kk, sh, pos_l, kidx_l);
 }
 
 }  // namespace

@@ -29,8 +29,10 @@ class GpuRun:
     def project(self):
         pkg.hsadmm_project(self.plan, self.dW, self.dU, self.dZ, self.dWbar, self.dmask, self.dkey, self.ws)
 
-    def compact(self, src=None, mask=None):
-        pkg.hsadmm_compact(self.plan, self.dZ if src is None else src, self.dmask if mask is None else mask,
+    def compact(self, src=None, mask=None, cached=False):
+        """cached=True passes a NULL mask: pack under the index mappings the last projection left in the workspace."""
+        m = None if cached else (self.dmask if mask is None else mask)
+        pkg.hsadmm_compact(self.plan, self.dZ if src is None else src, m,
                            self.dpacked, self.doff, self.dkept, self.ws)
 
     def expand(self, mask=None, cached=False):
@@ -38,10 +40,11 @@ class GpuRun:
         m = None if cached else (self.dmask if mask is None else mask)
         pkg.hsadmm_expand(self.plan, self.dpacked, m, self.ddst, self.ws)
 
-    def step(self):
+    def step(self, cached=False):
+        """cached=True: compaction and expansion reuse the index mappings of the projection (no mask scan)."""
         self.project()
-        self.compact()
-        self.expand()
+        self.compact(cached=cached)
+        self.expand(cached=cached)
         torch.cuda.synchronize()
 
     def outputs(self):

@@ -43,10 +43,14 @@ def _run(wl, pack_align=1, want_wbar=True, want_sqnorm=True, threads=8, determin
     if not determinism:
         run.close()
         return got, ref, refc
-    # determinism: a second run from fresh inputs gives the same bits
+    # determinism: a second run from fresh inputs gives the same bits; this one packs and expands under the index
+    # mappings the projection left in the workspace (NULL masks), which must give the same packed buffer, offsets and
+    # kept indices as scanning the mask
     run2 = GpuRun(wl, W, U, pack_align=pack_align, want_wbar=want_wbar, want_sqnorm=want_sqnorm)
-    run2.step()
+    run2.step(cached=True)
     got2 = run2.outputs()
+    assert np.array_equal(got2["layer_off"], refc["layer_off"])
+    assert np.array_equal(got2["kept_idx"][:refc["kept_idx"].size], refc["kept_idx"])
     for name in got:
         a, b = got[name], got2[name]
         if a.dtype.kind == "f":
@@ -177,8 +181,8 @@ def test_compact_and_expand_with_a_foreign_mask_and_source():
 
 
 def test_expand_with_cached_index_mappings_equals_expand_with_mask():
-    """hsadmm_expand(mask=NULL) reuses what hsadmm_compact left in the workspace (Section 4.4.3's cached
-    K_out / K_in); an hsadmm_project in between does not disturb it."""
+    """hsadmm_expand(mask=NULL) reuses the index mappings held in the workspace (Section 4.4.3's cached K_out / K_in).
+    A later hsadmm_project replaces them with those of its own selection."""
     from tests.gpu_harness import GpuRun, bits
     for name in ("resnet18", "resnet152"):
         wl = wk.make_workload(name)
@@ -189,12 +193,21 @@ def test_expand_with_cached_index_mappings_equals_expand_with_mask():
         run.expand()
         a = run.outputs()["dst"].copy()
         run.ddst.fill_(float("nan"))
-        run.project()                     # U moves on, Z and mask are recomputed; the cached mappings stay
         run.expand(cached=True)
-        b = run.outputs()["dst"]
+        b = run.outputs()["dst"].copy()
         for l in wl.layers:
             sl = slice(l.elem_off, l.elem_off + l.n)
             assert np.array_equal(bits(a[sl]), bits(b[sl])), l.name
+        # second iteration: U has moved on, the selection changes; NULL masks now mean the new selection
+        run.project()
+        run.compact(cached=True)
+        run.ddst.fill_(float("nan"))
+        run.expand(cached=True)
+        out = run.outputs()
+        assert not np.array_equal(out["Z"], a)          # the step did change the support or the values
+        for l in wl.layers:
+            sl = slice(l.elem_off, l.elem_off + l.n)
+            assert np.array_equal(bits(out["dst"][sl]), bits(out["Z"][sl])), l.name
         run.close()
 
 
@@ -239,7 +252,8 @@ def test_error_codes_on_device_arguments():
     assert pkg.hsadmm_project(p, run.dW, None, run.dZ, None, run.dmask, None, run.ws, check=False) == -1
     assert pkg.hsadmm_project(p, run.dW, run.dU[1:], run.dZ, None, run.dmask, None, run.ws, check=False) == -1   # misaligned
     assert pkg.hsadmm_project(p, [run.dW[0][1:]], run.dU, run.dZ, None, run.dmask, None, run.ws, check=False) == -1
-    assert pkg.hsadmm_compact(p, run.dZ, None, run.dpacked, run.doff, run.dkept, run.ws, check=False) == -1
+    assert pkg.hsadmm_compact(p, None, run.dmask, run.dpacked, run.doff, run.dkept, run.ws, check=False) == -1
+    assert pkg.hsadmm_compact(p, run.dZ, run.dmask, run.dpacked, None, run.dkept, run.ws, check=False) == -1
     assert pkg.hsadmm_expand(p, None, run.dmask, run.ddst, run.ws, check=False) == -1
     # nothing above may have touched the outputs
     torch.cuda.synchronize()
@@ -311,4 +325,52 @@ def test_outer_iterations_with_changing_supports(R):
         prev_mask = ref["mask"]
         Uref = ref["U"]
     assert n_repaired > 0      # the inputs did make pruned groups come back
+    run.close()
+
+
+def test_null_mask_means_the_index_mappings_last_left_in_the_workspace():
+    """hsadmm_compact / hsadmm_expand with mask = NULL: after a projection they pack under its selection; after a
+    compaction under another mask they use that mask's mappings."""
+    from tests.gpu_harness import GpuRun, bits
+    rng = np.random.default_rng(17)
+    wl = wk.custom_workload(_odd_shapes(rng, 10), R=2, seed=3, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    t = wl.table()
+    ref = oracle.project(t, W, U)
+    run = GpuRun(wl, W, U, pack_align=4)
+    run.project()
+    run.compact(cached=True)
+    run.expand(cached=True)
+    got = run.outputs()
+    refc = oracle.compact(t, ref["Z"], ref["mask"], pack_align=4)
+    assert np.array_equal(got["layer_off"], refc["layer_off"])
+    assert np.array_equal(got["kept_idx"][:refc["kept_idx"].size], refc["kept_idx"])
+    for l in wl.layers:
+        sl = slice(l.elem_off, l.elem_off + l.n)
+        assert np.array_equal(bits(got["dst"][sl]), bits(ref["Z"][sl]))
+    for li, l in enumerate(wl.layers):
+        a0 = int(refc["layer_off"][li])
+        used = l.n if l.mode == wk.MODE_NONE else l.k * l.group_size
+        assert np.array_equal(bits(got["packed"][a0:a0 + used]), bits(refc["packed"][a0:a0 + used]))
+    # now another mask through the scan, then NULL again: the scan's mappings are the ones in the workspace
+    other = (rng.random(wl.groups_total) < 0.5).astype(np.uint8)
+    src = rng.standard_normal(wl.n_arena).astype(np.float32)
+    dsrc, dm = torch.from_numpy(src).to(run.dev), torch.from_numpy(other).to(run.dev)
+    run.compact(src=dsrc, mask=dm)
+    a = run.outputs()
+    run.dpacked.fill_(float("nan"))
+    run.doff.fill_(-1)
+    run.dkept.fill_(-1)
+    run.compact(src=dsrc, cached=True)
+    b = run.outputs()
+    refo = oracle.compact(t, src, other, pack_align=4)
+    for got_o in (a, b):
+        assert np.array_equal(got_o["layer_off"], refo["layer_off"])
+        assert np.array_equal(got_o["kept_idx"][:refo["kept_idx"].size], refo["kept_idx"])
+    for li, l in enumerate(wl.layers):
+        m = other[l.group_base:l.group_base + l.groups]
+        used = l.n if l.mode == wk.MODE_NONE else int(m.sum()) * l.group_size
+        a0 = int(refo["layer_off"][li])
+        for got_o in (a, b):          # alignment padding and the tail of the buffer are unspecified
+            assert np.array_equal(bits(got_o["packed"][a0:a0 + used]), bits(refo["packed"][a0:a0 + used]))
     run.close()
