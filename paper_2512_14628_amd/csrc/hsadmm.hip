@@ -12,6 +12,8 @@
 //                   that lower indices win.                                  [Eq. (10)]
 //   project_fixup   touches pruned groups only: U <- V (taken from Z), Z <- +0.  For a pruned
 //                   group U + (Wbar - 0) equals V bit for bit, so no replica is read again.
+//   channel_final   CHANNEL layers: pass 1 only sums; their Z and U are written here, in one streaming
+//                   pass under the mask just selected (the kernel of the frozen-mask path).
 //   composite_colsums   layers under both constraints: channel norms over the kept filters, then a
 //                   second select_topk for the channels.   [Section 3, paragraph after Eq. (10)]
 //   scan_mask       per layer: kept count, exclusive positions, kept_idx, layer_off.
@@ -55,7 +57,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -66,6 +68,8 @@ struct hsadmm_plan {
     std::vector<DevLayer> dev_layers;
     std::vector<WorkItem> items_proj;   // project kernels
     std::vector<WorkItem> items_rows;   // compact / expand kernels
+    std::vector<WorkItem> items_fix;    // project_fixup: the row items of the FILTER and BOTH layers
+    std::vector<WorkItem> items_chan;   // channel_final: the row items of the CHANNEL layers (a subset of items_rows)
     std::vector<WorkItem> items_both;   // composite_colsums: tiles of the layers under both constraints
     std::vector<int32_t> both_layers;   // their indices
     int32_t n_segments = 0;             // scan segments (one per layer, two per BOTH layer)
@@ -79,6 +83,8 @@ struct hsadmm_plan {
     DevLayer* d_layers = nullptr;
     WorkItem* d_items_proj = nullptr;
     WorkItem* d_items_rows = nullptr;
+    WorkItem* d_items_fix = nullptr;
+    WorkItem* d_items_chan = nullptr;
     WorkItem* d_items_both = nullptr;
     int32_t* d_both_layers = nullptr;
     uint16_t* d_group_layer = nullptr;   // groups_total: scan segment of every group (bit 15: unconstrained layer)
@@ -182,8 +188,16 @@ hipError_t launch_pass1(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, hip
 template <int R>
 hipError_t launch_frozen(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, const uint8_t* mask, hipStream_t s)
 {
-    return launch(p, kFrozen, project_frozen<R>, (unsigned)p->items_proj.size(), kBlock, s,
-                  (const WorkItem*)p->d_items_proj, a, Rrt, mask);
+    return launch(p, kFrozen, project_frozen<R>, (unsigned)p->items_rows.size(), kBlock, s,
+                  (const WorkItem*)p->d_items_rows, a, Rrt, mask);
+}
+
+// Final Z / U of the CHANNEL layers under the mask just selected (same kernel, their row items only).
+template <int R>
+hipError_t launch_channel_final(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, const uint8_t* mask, hipStream_t s)
+{
+    return launch(p, kChanFinal, project_frozen<R>, (unsigned)p->items_chan.size(), kBlock, s,
+                  (const WorkItem*)p->d_items_chan, a, Rrt, mask);
 }
 // Per-layer selection once the keys (FILTER, and the filters of BOTH) or the partial column sums
 // (CHANNEL) are in place.  Layers under both constraints then take their second projection: channel
@@ -291,8 +305,13 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             d.rows_item0 = (int32_t)p->items_rows.size();
             add_row_items(p->items_rows, l, d, x.mode);
             d.rows_items = (int32_t)p->items_rows.size() - d.rows_item0;
-            if (x.mode == HSADMM_MODE_CHANNEL) add_tile_items(p->items_proj, l, d);
-            else add_row_items(p->items_proj, l, d, x.mode);
+            if (x.mode == HSADMM_MODE_CHANNEL) {
+                add_tile_items(p->items_proj, l, d);
+                add_row_items(p->items_chan, l, d, x.mode);
+            } else {
+                add_row_items(p->items_proj, l, d, x.mode);
+                if (x.mode != HSADMM_MODE_NONE) add_row_items(p->items_fix, l, d, x.mode);
+            }
             if (both) {
                 add_tile_items(p->items_both, l, d);
                 p->both_layers.push_back(l);
@@ -329,6 +348,8 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     const size_t bp = sizeof(WorkItem) * p->items_proj.size();
     const size_t br = sizeof(WorkItem) * p->items_rows.size();
     const size_t bb = sizeof(WorkItem) * p->items_both.size();
+    const size_t bch = sizeof(WorkItem) * p->items_chan.size();
+    const size_t bfx = sizeof(WorkItem) * p->items_fix.size();
     const size_t bbl = sizeof(int32_t) * p->both_layers.size();
     std::vector<uint16_t> chunk_layer;
     try {
@@ -350,6 +371,14 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     bool ok = hipMalloc(&p->d_layers, bl) == hipSuccess;
     ok = ok && hipMalloc(&p->d_items_proj, bp) == hipSuccess;
     ok = ok && hipMalloc(&p->d_items_rows, br) == hipSuccess;
+    if (bfx) {
+        ok = ok && hipMalloc(&p->d_items_fix, bfx) == hipSuccess;
+        ok = ok && hipMemcpy(p->d_items_fix, p->items_fix.data(), bfx, hipMemcpyHostToDevice) == hipSuccess;
+    }
+    if (bch) {
+        ok = ok && hipMalloc(&p->d_items_chan, bch) == hipSuccess;
+        ok = ok && hipMemcpy(p->d_items_chan, p->items_chan.data(), bch, hipMemcpyHostToDevice) == hipSuccess;
+    }
     if (bb) {
         ok = ok && hipMalloc(&p->d_items_both, bb) == hipSuccess;
         ok = ok && hipMalloc(&p->d_both_layers, bbl) == hipSuccess;
@@ -385,6 +414,8 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_layers) (void)hipFree(p->d_layers);
     if (p->d_items_proj) (void)hipFree(p->d_items_proj);
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
+    if (p->d_items_fix) (void)hipFree(p->d_items_fix);
+    if (p->d_items_chan) (void)hipFree(p->d_items_chan);
     if (p->d_items_both) (void)hipFree(p->d_items_both);
     if (p->d_both_layers) (void)hipFree(p->d_both_layers);
     if (p->d_group_layer) (void)hipFree(p->d_group_layer);
@@ -435,9 +466,23 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     if (run_selection(p, a.key, a.colpart, Z, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
-    e = launch(p, kFixup, project_fixup, (unsigned)p->items_rows.size(), kBlock, s,
-               (const WorkItem*)p->d_items_rows, (const uint8_t*)mask, U, Z);
-    if (e != hipSuccess) return HSADMM_ERR_HIP;
+    if (!p->items_fix.empty()) {
+        e = launch(p, kFixup, project_fixup, (unsigned)p->items_fix.size(), kBlock, s,
+                   (const WorkItem*)p->d_items_fix, (const uint8_t*)mask, U, Z);
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
+    if (!p->items_chan.empty()) {
+        const uint8_t* cm = mask;
+        switch (R) {
+            case 1: e = launch_channel_final<1>(p, a, R, cm, s); break;
+            case 2: e = launch_channel_final<2>(p, a, R, cm, s); break;
+            case 3: e = launch_channel_final<3>(p, a, R, cm, s); break;
+            case 4: e = launch_channel_final<4>(p, a, R, cm, s); break;
+            case 8: e = launch_channel_final<8>(p, a, R, cm, s); break;
+            default: e = launch_channel_final<0>(p, a, R, cm, s); break;
+        }
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
     return HSADMM_OK;
 }
 
@@ -739,6 +784,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kResPart: return "residual_partials";
         case kResFinish: return "residual_finish";
         case kColsums: return "composite_colsums";
+        case kChanFinal: return "channel_final";
         default: return "";
     }
 }

@@ -67,65 +67,51 @@ __device__ __forceinline__ void frozen1(const ProjectArgs& a, int Rrt, int64_t e
     if (a.Wbar) st1(a.Wbar + e, wb);
 }
 
-// Same work items and lane mappings as project_pass1; no keys, no second pass: every byte of the
-// replicas and of U is read once and Z and U are written once.
+// Row items of every mode (the compact / expand item table): no keys, no second pass, every byte of the
+// replicas and of U is read once and Z and U are written once, streaming along the rows.  FILTER / NONE rows
+// share one keep flag; in CHANNEL rows and in the kept filters' rows of a BOTH layer every column takes the
+// flag of its channel.
 template <int R>
 __global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
                                                          const uint8_t* __restrict__ mask)
 {
     const WorkItem it = items[blockIdx.x];
     const int mode = item_mode(it);
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
-    if (mode != HSADMM_MODE_CHANNEL) {
-        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
-        const int rows_at_once = kBlock / lpr;
-        const int sub = threadIdx.x / lpr;
-        const int j = threadIdx.x - sub * lpr;
-        const bool both = mode == HSADMM_MODE_BOTH;
-        const uint8_t* mc = mask + it.aux;            // BOTH: channel bytes of the layer
-        const DivKhw div(it.khw);
-        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
-            const bool keep = mode == HSADMM_MODE_NONE || mask[it.g0 + rr] != 0;
-            const int64_t base = it.base + (int64_t)rr * row_len;
-            if (both && keep) {
-                // kept filter of a BOTH layer: an element survives iff its channel does too
-                if (vec) {
-                    const int nchunk = row_len >> 2;
-                    for (int c = j; c < nchunk; c += lpr) {
-                        const int col = c << 2;
-                        bool k[4];
-                        for (int i = 0; i < 4; ++i) k[i] = mc[div(col + i)] != 0;
-                        frozen4<R>(a, Rrt, base + col, k[0], k[1], k[2], k[3]);
-                    }
-                } else {
-                    for (int c = j; c < row_len; c += lpr) frozen1<R>(a, Rrt, base + c, mc[div(c)] != 0);
-                }
-                continue;
-            }
+    const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+    const int rows_at_once = kBlock / lpr;
+    const int sub = threadIdx.x / lpr;
+    const int j = threadIdx.x - sub * lpr;
+    const bool columns = mode_has_channels(mode);
+    // channel bytes of the layer (CHANNEL row item: g0 is the layer's first group)
+    const uint8_t* mc = mask + (mode == HSADMM_MODE_BOTH ? it.aux : (int64_t)it.g0);
+    const DivKhw div(it.khw);
+    for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+        const bool keep = mode == HSADMM_MODE_NONE || mode == HSADMM_MODE_CHANNEL || mask[it.g0 + rr] != 0;
+        const int64_t base = it.base + (int64_t)rr * row_len;
+        if (columns && keep) {
             if (vec) {
                 const int nchunk = row_len >> 2;
-                int c = j;
-                for (; c + lpr < nchunk; c += 2 * lpr)
-                    frozen4x2<R>(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + lpr) << 2), keep);
-                if (c < nchunk) frozen4<R>(a, Rrt, base + ((int64_t)c << 2), keep, keep, keep, keep);
+                for (int c = j; c < nchunk; c += lpr) {
+                    const int col = c << 2;
+                    bool pr[4];
+                    quad_pruned(mc, div, col, pr);
+                    frozen4<R>(a, Rrt, base + col, !pr[0], !pr[1], !pr[2], !pr[3]);
+                }
             } else {
-                for (int c = j; c < row_len; c += lpr) frozen1<R>(a, Rrt, base + c, keep);
+                for (int c = j; c < row_len; c += lpr) frozen1<R>(a, Rrt, base + c, mc[div(c)] != 0);
             }
+            continue;
         }
-    } else {
-        const int vw = vec ? 4 : 1;
-        const int col = it.col0 + lane * vw;
-        if (col >= row_len) return;
-        const DivKhw div(it.khw);
-        bool k[4] = {true, true, true, true};
-        for (int i = 0; i < vw; ++i) k[i] = mask[it.g0 + div(col + i)] != 0;
-        for (int rr = wave; rr < it.nr; rr += kWaves) {
-            const int64_t e = it.base + (int64_t)rr * row_len + col;
-            if (vec) frozen4<R>(a, Rrt, e, k[0], k[1], k[2], k[3]);
-            else frozen1<R>(a, Rrt, e, k[0]);
+        if (vec) {
+            const int nchunk = row_len >> 2;
+            int c = j;
+            for (; c + lpr < nchunk; c += 2 * lpr)
+                frozen4x2<R>(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + lpr) << 2), keep);
+            if (c < nchunk) frozen4<R>(a, Rrt, base + ((int64_t)c << 2), keep, keep, keep, keep);
+        } else {
+            for (int c = j; c < row_len; c += lpr) frozen1<R>(a, Rrt, base + c, keep);
         }
     }
 }

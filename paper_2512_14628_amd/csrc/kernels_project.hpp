@@ -60,6 +60,23 @@ struct Cand {
         if (a.Wbar) st4(a.Wbar + e, wb);
         return v;
     }
+    // the candidate alone, nothing stored (CHANNEL layers: their outputs are written once the mask is known)
+    static __device__ __forceinline__ v4f value4(const ProjectArgs& a, int Rrt, int64_t e)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        v4f s = ld4(a.W[0] + e);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+        return s * a.inv_R + ld4(a.U + e);
+    }
+    static __device__ __forceinline__ float value1(const ProjectArgs& a, int Rrt, int64_t e)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        float s = ld1(a.W[0] + e);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
+        return s * a.inv_R + ld1(a.U + e);
+    }
     static __device__ __forceinline__ float scalar(const ProjectArgs& a, int Rrt, int64_t e)
     {
         const int RR = R > 0 ? R : Rrt;
@@ -145,6 +162,9 @@ __device__ __forceinline__ void project_rows(const WorkItem& it, const ProjectAr
 // the rows of its wave, accumulating per-column sums in registers.  The four waves' sums are added
 // in wave order through LDS and stored as this row block's partial column sums; the layer's selection later
 // adds row blocks and the khw columns of a channel in a fixed order.
+// Nothing but the sums is written: a pruned channel is a set of 4-byte (khw = 1) or 4*khw-byte runs
+// scattered over every row, so repairing speculative outputs would rewrite most 128-bit quads of the
+// layer; the outputs are instead written in one streaming pass once the mask is known (channel_final).
 template <int R>
 __device__ __forceinline__ void project_tile(const WorkItem& it, const ProjectArgs& a, int Rrt)
 {
@@ -161,13 +181,13 @@ __device__ __forceinline__ void project_tile(const WorkItem& it, const ProjectAr
         for (int rr = wave; rr < it.nr; rr += kWaves) {
             const int64_t e = it.base + (int64_t)rr * row_len + col;
             if (vec) {
-                const v4f v = Cand<R>::one(a, Rrt, e);
+                const v4f v = Cand<R>::value4(a, Rrt, e);
                 acc0 = fma((double)v.x, (double)v.x, acc0);
                 acc1 = fma((double)v.y, (double)v.y, acc1);
                 acc2 = fma((double)v.z, (double)v.z, acc2);
                 acc3 = fma((double)v.w, (double)v.w, acc3);
             } else {
-                const float v = Cand<R>::scalar(a, Rrt, e);
+                const float v = Cand<R>::value1(a, Rrt, e);
                 acc0 = fma((double)v, (double)v, acc0);
             }
         }
@@ -273,17 +293,17 @@ __device__ __forceinline__ void quad_pruned(const uint8_t* __restrict__ mc, cons
     }
 }
 
-// Row items of every mode (the compact / expand item table).  A pruned filter's row moves whole:
-// U <- V (held in Z), Z <- +0.  In a row that stays (every row of a CHANNEL layer, the kept filters of a
-// BOTH layer) only the columns of pruned channels change; a partly pruned quad is rewritten whole, the kept
-// elements of U passing through (they are final already), so that every access is a full 128 bits.
+// Row items of the FILTER and BOTH layers (CHANNEL layers have no speculative outputs, NONE layers nothing to repair).
+// A pruned filter's row moves whole: U <- V (held in Z), Z <- +0.  In a kept filter's row of a BOTH layer only
+// the columns of pruned channels change; a partly pruned quad is rewritten whole, the kept elements of U
+// passing through (they are final already), so that every access is a full 128 bits.
 __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restrict__ items,
                                                         const uint8_t* __restrict__ mask,
                                                         float* __restrict__ U, float* __restrict__ Z)
 {
     const WorkItem it = items[blockIdx.x];
     const int mode = item_mode(it);
-    if (mode == HSADMM_MODE_NONE) return;
+    if (mode == HSADMM_MODE_NONE || mode == HSADMM_MODE_CHANNEL) return;
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
@@ -292,13 +312,12 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
     const int rows_at_once = kBlock / lpr;
     const int sub = threadIdx.x / lpr;
     const int j = threadIdx.x - sub * lpr;
-    const bool columns = mode_has_channels(mode);
-    // channel bytes of the layer (CHANNEL row item: g0 is the layer's first group)
-    const uint8_t* mc = mask + (mode == HSADMM_MODE_BOTH ? it.aux : (int64_t)it.g0);
+    const bool columns = mode == HSADMM_MODE_BOTH;
+    const uint8_t* mc = mask + it.aux;            // BOTH: channel bytes of the layer
     const DivKhw div(it.khw);
     for (int rr = sub; rr < it.nr; rr += rows_at_once) {
         const int64_t base = it.base + (int64_t)rr * row_len;
-        const bool row_stays = mode == HSADMM_MODE_CHANNEL || mask[it.g0 + rr] != 0;
+        const bool row_stays = mask[it.g0 + rr] != 0;
         if (row_stays) {
             if (!columns) continue;
             if (vec) {

@@ -81,6 +81,16 @@ def test_resnet152_channel_R4_roundtrip():
     _run(wk.make_workload("resnet152"))
 
 
+def test_wide_resnet50_2_filter_R4():
+    """The paper's WideResNet-50-2 shapes (Section 5.1, table of evaluated models), every element against the oracle."""
+    _run(wk.make_workload("wrn50_2"), threads=16, determinism=False)
+
+
+def test_resnet152_filter_R4():
+    """The paper's primary model under filter groups (the named ResNet-152 configuration uses channel groups)."""
+    _run(wk.make_workload("resnet152_filter"), threads=16, determinism=False)
+
+
 def test_wide_stress_full_size_R8():
     """Largest configuration (383 M parameters, 8 replicas, G up to 8192, per-filter scales over 4 decades),
     compared with the oracle on every element."""

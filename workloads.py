@@ -160,16 +160,19 @@ def _resnet_basic_shapes(blocks=(2, 2, 2, 2), mult=1, n_classes=1000):
     return s
 
 
-def _resnet_bottleneck_shapes(blocks, mult=1, n_classes=1000):
+def _resnet_bottleneck_shapes(blocks, mult=1, n_classes=1000, inner_mult=1):
+    """inner_mult widens only the two inner convs of every bottleneck (the wide-ResNet construction: the block's
+    output width stays 4 * w)."""
     s = [("conv1", 64 * mult, 3, 49)]
     inp = 64 * mult
     for si, nb in enumerate(blocks):
         w = 64 * mult * (2 ** si)
+        wi = w * inner_mult
         for b in range(nb):
             pre = "layer%d.%d." % (si + 1, b)
-            s.append((pre + "conv1", w, inp, 1))
-            s.append((pre + "conv2", w, w, 9))
-            s.append((pre + "conv3", 4 * w, w, 1))
+            s.append((pre + "conv1", wi, inp, 1))
+            s.append((pre + "conv2", wi, wi, 9))
+            s.append((pre + "conv3", 4 * w, wi, 1))
             if b == 0:
                 s.append((pre + "downsample", 4 * w, inp, 1))
             inp = 4 * w
@@ -199,7 +202,7 @@ def _philox(seed: int, layer: int, tensor: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[int(seed), (int(layer) << 16) | int(tensor)]))
 
 
-WORKLOAD_NAMES = ("tiny", "resnet18", "resnet50", "resnet152", "wide", "resnet50_both")
+WORKLOAD_NAMES = ("tiny", "resnet18", "resnet50", "resnet152", "wide", "resnet50_both", "wrn50_2", "resnet152_filter")
 
 
 def make_workload(name: str, seed: int = 0, prune_fc: Optional[bool] = None) -> Workload:
@@ -234,6 +237,16 @@ def make_workload(name: str, seed: int = 0, prune_fc: Optional[bool] = None) -> 
                       filter_scale_log10=(-3.0, 1.0),
                       description="ResNet-50 shapes with every width x4, output-filter groups, "
                                   "keep ~ U(0.2,0.8) per layer, per-filter scales 1e-3..1e1, R=8")
+    elif name == "wrn50_2":
+        shapes = _resnet_bottleneck_shapes((3, 4, 6, 3), inner_mult=2)
+        layers = _apply_policy(shapes, MODE_FILTER, 0.4, bool(prune_fc))
+        wl = Workload(name, layers, R=4, seed=seed, sigma_replica=float(np.sqrt(1e-3)),
+                      description="WideResNet-50-2 conv/fc weights (inner bottleneck widths x2, ~69 M parameters), "
+                                  "output-filter groups, keep 0.4, R=4")
+    elif name == "resnet152_filter":
+        layers = _apply_policy(_resnet_bottleneck_shapes((3, 8, 36, 3)), MODE_FILTER, 0.4, bool(prune_fc))
+        wl = Workload(name, layers, R=4, seed=seed, sigma_replica=float(np.sqrt(1e-3)),
+                      description="ResNet-152 conv/fc weights, output-filter groups, keep 0.4, R=4")
     elif name == "resnet50_both":
         layers = _apply_policy(_resnet_bottleneck_shapes((3, 4, 6, 3)), MODE_BOTH, 0.6, bool(prune_fc),
                                keep_in=0.6)
