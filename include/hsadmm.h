@@ -245,8 +245,9 @@ int hsadmm_plan_set_node_weights(hsadmm_plan_t* plan, const float* a, const floa
  *   Zg   device, in: the global consensus z (full-layout arena)
  *   Vd   device, in: the node's inter-node dual v_i (full-layout arena)
  * All other arguments, alignment and aliasing rules as for hsadmm_project.
- * Here neither output of a group follows from the other one, so the inputs
- * are read twice (once for the norms, once for the final values).
+ * FILTER layers take one pass over the replicas (Z first holds Wbar + U, from
+ * which either outcome of a filter is finished once the mask is known);
+ * CHANNEL and BOTH layers read their inputs twice (norms, then final values).
  * Errors: INVALID_ARGUMENT, WORKSPACE, UNSUPPORTED, HIP.
  */
 int hsadmm_project_weighted(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
@@ -315,7 +316,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 15
+#define HSADMM_KERNEL_COUNT 16
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

@@ -57,7 +57,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -69,6 +69,8 @@ struct hsadmm_plan {
     std::vector<WorkItem> items_proj;   // project kernels
     std::vector<WorkItem> items_rows;   // compact / expand kernels
     std::vector<WorkItem> items_fix;    // project_fixup: the row items of the FILTER and BOTH layers
+    std::vector<WorkItem> items_wfix;   // weighted_fixup: the row items of the FILTER layers
+    std::vector<WorkItem> items_wfinal; // weighted_final: CHANNEL tiles and BOTH rows (a subset of items_proj)
     std::vector<WorkItem> items_chan;   // channel_final: the row items of the CHANNEL layers (a subset of items_rows)
     std::vector<WorkItem> items_both;   // composite_colsums: tiles of the layers under both constraints
     std::vector<int32_t> both_layers;   // their indices
@@ -84,6 +86,8 @@ struct hsadmm_plan {
     WorkItem* d_items_proj = nullptr;
     WorkItem* d_items_rows = nullptr;
     WorkItem* d_items_fix = nullptr;
+    WorkItem* d_items_wfix = nullptr;
+    WorkItem* d_items_wfinal = nullptr;
     WorkItem* d_items_chan = nullptr;
     WorkItem* d_items_both = nullptr;
     int32_t* d_both_layers = nullptr;
@@ -307,10 +311,13 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             d.rows_items = (int32_t)p->items_rows.size() - d.rows_item0;
             if (x.mode == HSADMM_MODE_CHANNEL) {
                 add_tile_items(p->items_proj, l, d);
+                add_tile_items(p->items_wfinal, l, d);
                 add_row_items(p->items_chan, l, d, x.mode);
             } else {
                 add_row_items(p->items_proj, l, d, x.mode);
                 if (x.mode != HSADMM_MODE_NONE) add_row_items(p->items_fix, l, d, x.mode);
+                if (x.mode == HSADMM_MODE_FILTER) add_row_items(p->items_wfix, l, d, x.mode);
+                if (x.mode == HSADMM_MODE_BOTH) add_row_items(p->items_wfinal, l, d, x.mode);
             }
             if (both) {
                 add_tile_items(p->items_both, l, d);
@@ -371,6 +378,14 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     bool ok = hipMalloc(&p->d_layers, bl) == hipSuccess;
     ok = ok && hipMalloc(&p->d_items_proj, bp) == hipSuccess;
     ok = ok && hipMalloc(&p->d_items_rows, br) == hipSuccess;
+    auto upload = [&](const std::vector<WorkItem>& v, WorkItem** d) {
+        if (v.empty()) return;
+        const size_t b = sizeof(WorkItem) * v.size();
+        ok = ok && hipMalloc(d, b) == hipSuccess;
+        ok = ok && hipMemcpy(*d, v.data(), b, hipMemcpyHostToDevice) == hipSuccess;
+    };
+    upload(p->items_wfix, &p->d_items_wfix);
+    upload(p->items_wfinal, &p->d_items_wfinal);
     if (bfx) {
         ok = ok && hipMalloc(&p->d_items_fix, bfx) == hipSuccess;
         ok = ok && hipMemcpy(p->d_items_fix, p->items_fix.data(), bfx, hipMemcpyHostToDevice) == hipSuccess;
@@ -415,6 +430,8 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_items_proj) (void)hipFree(p->d_items_proj);
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
     if (p->d_items_fix) (void)hipFree(p->d_items_fix);
+    if (p->d_items_wfix) (void)hipFree(p->d_items_wfix);
+    if (p->d_items_wfinal) (void)hipFree(p->d_items_wfinal);
     if (p->d_items_chan) (void)hipFree(p->d_items_chan);
     if (p->d_items_both) (void)hipFree(p->d_items_both);
     if (p->d_both_layers) (void)hipFree(p->d_both_layers);
@@ -634,23 +651,33 @@ int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replic
     const WorkItem* items = p->d_items_proj;
     hipError_t e;
     switch (R) {
-        case 1: e = launch(p, kWKeys, weighted_keys<1>, grid, kBlock, s, items, w, (int)R); break;
-        case 2: e = launch(p, kWKeys, weighted_keys<2>, grid, kBlock, s, items, w, (int)R); break;
-        case 4: e = launch(p, kWKeys, weighted_keys<4>, grid, kBlock, s, items, w, (int)R); break;
-        case 8: e = launch(p, kWKeys, weighted_keys<8>, grid, kBlock, s, items, w, (int)R); break;
-        default: e = launch(p, kWKeys, weighted_keys<0>, grid, kBlock, s, items, w, (int)R); break;
+        case 1: e = launch(p, kWKeys, weighted_pass1<1>, grid, kBlock, s, items, w, (int)R); break;
+        case 2: e = launch(p, kWKeys, weighted_pass1<2>, grid, kBlock, s, items, w, (int)R); break;
+        case 4: e = launch(p, kWKeys, weighted_pass1<4>, grid, kBlock, s, items, w, (int)R); break;
+        case 8: e = launch(p, kWKeys, weighted_pass1<8>, grid, kBlock, s, items, w, (int)R); break;
+        default: e = launch(p, kWKeys, weighted_pass1<0>, grid, kBlock, s, items, w, (int)R); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     if (run_selection(p, w.p.key, w.p.colpart, Z, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
     const uint8_t* cm = mask;
-    switch (R) {
-        case 1: e = launch(p, kWFinal, weighted_final<1>, grid, kBlock, s, items, w, (int)R, cm); break;
-        case 2: e = launch(p, kWFinal, weighted_final<2>, grid, kBlock, s, items, w, (int)R, cm); break;
-        case 4: e = launch(p, kWFinal, weighted_final<4>, grid, kBlock, s, items, w, (int)R, cm); break;
-        case 8: e = launch(p, kWFinal, weighted_final<8>, grid, kBlock, s, items, w, (int)R, cm); break;
-        default: e = launch(p, kWFinal, weighted_final<0>, grid, kBlock, s, items, w, (int)R, cm); break;
+    if (!p->items_wfix.empty()) {
+        e = launch(p, kWFixup, weighted_fixup, (unsigned)p->items_wfix.size(), kBlock, s,
+                   (const WorkItem*)p->d_items_wfix, cm, U, Z, Zg, Vd, (const float*)p->d_coef);
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
-    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+    if (!p->items_wfinal.empty()) {
+        const unsigned gf = (unsigned)p->items_wfinal.size();
+        const WorkItem* fi = p->d_items_wfinal;
+        switch (R) {
+            case 1: e = launch(p, kWFinal, weighted_final<1>, gf, kBlock, s, fi, w, (int)R, cm); break;
+            case 2: e = launch(p, kWFinal, weighted_final<2>, gf, kBlock, s, fi, w, (int)R, cm); break;
+            case 4: e = launch(p, kWFinal, weighted_final<4>, gf, kBlock, s, fi, w, (int)R, cm); break;
+            case 8: e = launch(p, kWFinal, weighted_final<8>, gf, kBlock, s, fi, w, (int)R, cm); break;
+            default: e = launch(p, kWFinal, weighted_final<0>, gf, kBlock, s, fi, w, (int)R, cm); break;
+        }
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
+    return HSADMM_OK;
 }
 
 int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, const float* Zi,
@@ -778,13 +805,14 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kScatter: return "expand_scatter";
         case kFrozen: return "project_frozen";
         case kMaskOr: return "mask_or";
-        case kWKeys: return "weighted_keys";
+        case kWKeys: return "weighted_pass1";
         case kWFinal: return "weighted_final";
         case kDualInter: return "dual_inter";
         case kResPart: return "residual_partials";
         case kResFinish: return "residual_finish";
         case kColsums: return "composite_colsums";
         case kChanFinal: return "channel_final";
+        case kWFixup: return "weighted_fixup";
         default: return "";
     }
 }

@@ -1,4 +1,4 @@
-// hsadmm_project_weighted (full candidate of Eq. (9), two passes) and hsadmm_dual_inter (Eq. (13)).
+// hsadmm_project_weighted (full candidate of Eq. (9)) and hsadmm_dual_inter (Eq. (13)).
 // Part of the single translation unit built from hsadmm.hip (included there, in order).
 #ifndef KERNELS_WEIGHTED_HPP
 #define KERNELS_WEIGHTED_HPP
@@ -50,11 +50,16 @@ __device__ __forceinline__ void wcand1(const WeightedArgs& w, int Rrt, int64_t e
     zt = at + bq;
 }
 
-// Keys of the weighted candidate: the lane mappings and the order of additions of project_pass1,
-// but nothing is stored except keys / partial column sums (the selection must be known before
-// anything final can be written: neither output of a group follows from the other one here).
+// Pass 1 of the weighted projection: keys of the candidate z~ with the lane mappings and the order of
+// additions of project_pass1.  With the rho_2 term a pruned group needs t = Wbar + U (its dual becomes t) and
+// a kept group z~ and U + (Wbar - z~); z~ follows from t, Zg and Vd, so per mode:
+//   FILTER   Z <- t (a stash), U <- U + (Wbar - z~) (final if kept); weighted_fixup finishes either case
+//            without reading the replicas again;
+//   NONE     everything is kept: Z <- z~ and U are final;
+//   BOTH     Z <- z~, parked where composite_colsums reads the channel norms; weighted_final writes the outputs;
+//   CHANNEL  partial column sums only; weighted_final writes the outputs.
 template <int R>
-__global__ __launch_bounds__(kBlock) void weighted_keys(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt)
+__global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt)
 {
     __shared__ double wsum[kWaves];
     __shared__ double part[kWaves][kWave * 4];
@@ -65,9 +70,9 @@ __global__ __launch_bounds__(kBlock) void weighted_keys(const WorkItem* __restri
     const bool vec = item_vec(it);
     const float al = w.coef[2 * it.layer], bl = w.coef[2 * it.layer + 1];
     if (item_mode(it) != HSADMM_MODE_CHANNEL) {
-        // BOTH: these are the filter norms; the candidate is also parked in Z, where composite_colsums
-        // reads it for the channel norms over the kept filters
-        const bool park = item_mode(it) == HSADMM_MODE_BOTH;
+        const int mode = item_mode(it);
+        const bool park = mode == HSADMM_MODE_BOTH;
+        const bool all_kept = mode == HSADMM_MODE_NONE;
         const bool wide = it.lpr > kWave;
         const int lpr = wide ? kBlock : it.lpr;
         const int rows_at_once = kBlock / lpr;
@@ -85,14 +90,27 @@ __global__ __launch_bounds__(kBlock) void weighted_keys(const WorkItem* __restri
                     for (int c = j; c < nchunk; c += lpr) {
                         v4f wb, u, zt;
                         wcand4<R>(w, Rrt, base + ((int64_t)c << 2), al, bl, wb, u, zt);
-                        if (park) st4(w.p.Z + base + ((int64_t)c << 2), zt);
+                        const int64_t e = base + ((int64_t)c << 2);
+                        if (park) {
+                            st4(w.p.Z + e, zt);
+                        } else {
+                            st4(w.p.Z + e, all_kept ? zt : wb + u);
+                            st4(w.p.U + e, u + (wb - zt));
+                            if (w.p.Wbar) st4(w.p.Wbar + e, wb);
+                        }
                         acc = sq4(acc, zt);
                     }
                 } else {
                     for (int c = j; c < row_len; c += lpr) {
                         float wb, u, zt;
                         wcand1<R>(w, Rrt, base + c, al, bl, wb, u, zt);
-                        if (park) st1(w.p.Z + base + c, zt);
+                        if (park) {
+                            st1(w.p.Z + base + c, zt);
+                        } else {
+                            st1(w.p.Z + base + c, all_kept ? zt : wb + u);
+                            st1(w.p.U + base + c, u + (wb - zt));
+                            if (w.p.Wbar) st1(w.p.Wbar + base + c, wb);
+                        }
                         acc = fma((double)zt, (double)zt, acc);
                     }
                 }
@@ -150,7 +168,62 @@ __global__ __launch_bounds__(kBlock) void weighted_keys(const WorkItem* __restri
     }
 }
 
-// Final values once the mask is known: Z = z~ on kept groups, +0 elsewhere; U <- U + (Wbar - Z).
+// FILTER layers once the mask is known (row items): Z holds t = Wbar + U and U the kept form.
+//   kept filter:   Z <- z~ = fl(fl(a t) + fl(b (Zg - Vd)))   (the arithmetic of wcand4, from the stashed t)
+//   pruned filter: U <- t (= U + (Wbar - 0) bit for bit), Z <- +0
+__global__ __launch_bounds__(kBlock) void weighted_fixup(const WorkItem* __restrict__ items,
+                                                         const uint8_t* __restrict__ mask,
+                                                         float* __restrict__ U, float* __restrict__ Z,
+                                                         const float* __restrict__ Zg, const float* __restrict__ Vd,
+                                                         const float* __restrict__ coef)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const float al = coef[2 * it.layer], bl = coef[2 * it.layer + 1];
+    const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+    const int rows_at_once = kBlock / lpr;
+    const int sub = threadIdx.x / lpr;
+    const int j = threadIdx.x - sub * lpr;
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+        const bool keep = mask[it.g0 + rr] != 0;
+        const int64_t base = it.base + (int64_t)rr * row_len;
+        if (vec) {
+            const int nchunk = row_len >> 2;
+            for (int c = j; c < nchunk; c += lpr) {
+                const int64_t e = base + ((int64_t)c << 2);
+                const v4f t = ld4(Z + e);
+                if (keep) {
+                    const v4f q = ld4(Zg + e) - ld4(Vd + e);
+                    const v4f at = t * al;
+                    const v4f bq = q * bl;
+                    st4(Z + e, at + bq);
+                } else {
+                    st4(U + e, t);
+                    st4(Z + e, zero4);
+                }
+            }
+        } else {
+            for (int c = j; c < row_len; c += lpr) {
+                const int64_t e = base + c;
+                const float t = ld1(Z + e);
+                if (keep) {
+                    const float q = ld1(Zg + e) - ld1(Vd + e);
+                    const float at = t * al;
+                    const float bq = q * bl;
+                    st1(Z + e, at + bq);
+                } else {
+                    st1(U + e, t);
+                    st1(Z + e, 0.f);
+                }
+            }
+        }
+    }
+}
+
+// CHANNEL and BOTH layers once the mask is known: everything is formed again from the inputs;
+// Z = z~ on kept groups, +0 elsewhere; U <- U + (Wbar - Z).
 template <int R>
 __global__ __launch_bounds__(kBlock) void weighted_final(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt,
                                                          const uint8_t* __restrict__ mask)
