@@ -23,6 +23,10 @@
  * groups (G = c_out + c_in), k filters and k_in channels are kept, and an
  * element survives iff its filter and its channel both do.  `mask` and
  * `sqnorm` hold the groups of all layers concatenated in table order.
+ * Shape sparsity (groups W[:, b, u, v], one per input channel and spatial
+ * position) needs no mode of its own: such a group is a column of the
+ * [c_out][c_in*khw] view, so declare the layer as CHANNEL with c_in*khw
+ * channels and khw = 1 (BOTH, the same way, for filters together with shapes).
  *
  * Ownership.  The caller owns every device buffer and the stream.  The
  * library owns only the plan (host tables plus a device copy, allocated in

@@ -117,6 +117,7 @@ def _poisoned_arena(t, n_arena):
 def groups_total(table) -> int:
     t = _cols(table)
     g = np.where(t["mode"] == 2, t["c_in"], t["c_out"]) + np.where(t["mode"] == 3, t["c_in"], 0)
+    g = np.where(t["mode"] == 4, t["c_in"] * t["khw"], g)
     return int(g.sum())
 
 

@@ -16,6 +16,9 @@
  *     mode 2, channel g:  W[:, g, :]   (G = c_in)
  *     mode 0, none:       unconstrained layer (Section 2.1, last sentence);
  *                         its c_out filters are all kept.
+ *     mode 4, shape   g:  W[:, b, u, v] with g = b*khw + (u,v)   (G = c_in*khw): shape
+ *                         sparsity of Section 2.1, one group per spatial position of an input
+ *                         channel, i.e. per column of the [c_out][c_in*khw] GEMM view
  *     mode 3, both:       the intersection S_f ^ S_c of Section 2.1: c_out filter
  *                         groups followed by c_in channel groups (G = c_out + c_in);
  *                         k filters and k_in channels are kept.
@@ -39,7 +42,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_NONE = 0, ORACLE_FILTER = 1, ORACLE_CHANNEL = 2, ORACLE_BOTH = 3 };
+enum { ORACLE_NONE = 0, ORACLE_FILTER = 1, ORACLE_CHANNEL = 2, ORACLE_BOTH = 3, ORACLE_SHAPE = 4 };
 
 static int g_threads = 1;
 
@@ -59,21 +62,34 @@ static int64_t n_groups(int mode, int c_out, int c_in)
     return mode == ORACLE_CHANNEL ? c_in : c_out;
 }
 
+/* Groups of a layer in mask / key: as above, and c_in*khw for shape sparsity. */
+static int64_t n_groups_s(int mode, int c_out, int c_in, int khw)
+{
+    if (mode == ORACLE_SHAPE) return (int64_t)c_in * khw;
+    return n_groups(mode, c_out, c_in);
+}
+
 /*
  * One projection onto "at most kk nonzero groups" (Eq. (10) and the paragraph after it), applied in
  * place to the layer x[co][ci][s]: squared Frobenius norm of every group of x as it stands
  * (sequential fp64 sum in memory order), rank count (larger key first, lower index first among
  * equals), +0 written over the groups not kept.  channel = 0: groups are filters x[g,:,:];
- * channel = 1: groups are input channels x[:,g,:].  key, m: the G entries of this constraint.
+ * channel = 1: groups are input channels x[:,g,:]; channel = 2: groups are the shape positions
+ * x[:,b,t] with g = b*s + t.  key, m: the G entries of this constraint.
  */
 static void project_in_place(float *x, int64_t co, int64_t ci, int64_t s, int channel, int64_t kk,
                              double *key, uint8_t *m)
 {
-    const int64_t G = channel ? ci : co;
+    const int64_t G = channel == 2 ? ci * s : (channel ? ci : co);
 #pragma omp parallel for schedule(static)
     for (int64_t g = 0; g < G; ++g) {
         double acc = 0.0;
-        if (channel) {
+        if (channel == 2) {
+            for (int64_t o = 0; o < co; ++o) {
+                const double y = (double)x[o * ci * s + g];
+                acc += y * y;
+            }
+        } else if (channel) {
             for (int64_t o = 0; o < co; ++o)
                 for (int64_t t = 0; t < s; ++t) {
                     const double y = (double)x[(o * ci + g) * s + t];
@@ -96,7 +112,7 @@ static void project_in_place(float *x, int64_t co, int64_t ci, int64_t s, int ch
     }
 #pragma omp parallel for schedule(static)
     for (int64_t e = 0; e < co * ci * s; ++e) {
-        const int64_t g = channel ? (e / s) % ci : e / (ci * s);
+        const int64_t g = channel == 2 ? e % (ci * s) : (channel ? (e / s) % ci : e / (ci * s));
         if (!m[g]) x[e] = 0.0f;
     }
 }
@@ -148,7 +164,7 @@ int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
     for (int32_t l = 0; l < L; ++l) {
         const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
         const int64_t n = co * ci * s;
-        const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
+        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
         if (co < 1 || ci < 1 || s < 1) return -1;
         if (mode[l] == ORACLE_BOTH) {
             if (k[l] < 1 || k[l] > co || k_in[l] < 1 || k_in[l] > ci) return -1;
@@ -170,9 +186,10 @@ int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
         }
         if (bad) { free(wbar); free(v); return -2; }
 
-        if (mode[l] == ORACLE_BOTH) {
-            /* (b), (c) under both constraints: v becomes Pi_S(v); then (d) */
-            project_composite(v, co, ci, s, k[l], k_in[l], key + gbase, mask + gbase);
+        if (mode[l] == ORACLE_BOTH || mode[l] == ORACLE_SHAPE) {
+            /* (b), (c) under both constraints, or under shape sparsity: v becomes Pi_S(v); then (d) */
+            if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], k_in[l], key + gbase, mask + gbase);
+            else project_in_place(v, co, ci, s, 2, k[l], key + gbase, mask + gbase);
 #pragma omp parallel for schedule(static)
             for (int64_t e = 0; e < n; ++e) {
                 Z[off + e] = v[e];
@@ -283,13 +300,21 @@ int oracle_compact(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
     int64_t gbase = 0, pos = 0, nk = 0;
     layer_off[0] = 0;
     for (int32_t l = 0; l < L; ++l) {
-        const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
-        const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
+        const int64_t co = c_out[l];
+        int64_t ci = c_in[l], s = khw[l];
+        int lm = mode[l];
+        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
+        if (lm == ORACLE_SHAPE) {
+            /* shape groups are the columns of the [c_out][c_in*khw] view: packed like channels of width 1 */
+            ci *= s;
+            s = 1;
+            lm = ORACLE_CHANNEL;
+        }
         int32_t *k_out = (int32_t *)malloc(sizeof(int32_t) * (size_t)co);
         int32_t *k_in = (int32_t *)malloc(sizeof(int32_t) * (size_t)ci);
         if (!k_out || !k_in) { free(k_out); free(k_in); return -1; }
         int64_t n_out, n_in;
-        index_sets(mode[l], co, ci, mask + gbase, k_out, &n_out, k_in, &n_in);
+        index_sets(lm, co, ci, mask + gbase, k_out, &n_out, k_in, &n_in);
         const float *sl = src + elem_off[l];
         float *pl = packed + pos;
 #pragma omp parallel for schedule(static)
@@ -297,9 +322,9 @@ int oracle_compact(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
             for (int64_t q = 0; q < n_in; ++q)
                 for (int64_t t = 0; t < s; ++t)
                     pl[(p * n_in + q) * s + t] = sl[((int64_t)k_out[p] * ci + k_in[q]) * s + t];
-        if (mode[l] != ORACLE_CHANNEL)
+        if (lm != ORACLE_CHANNEL)
             for (int64_t p = 0; p < n_out; ++p) kept_idx[nk++] = k_out[p];
-        if (mode[l] == ORACLE_CHANNEL || mode[l] == ORACLE_BOTH)
+        if (lm == ORACLE_CHANNEL || lm == ORACLE_BOTH)
             for (int64_t q = 0; q < n_in; ++q) kept_idx[nk++] = k_in[q];
         pos += n_out * n_in * s;
         pos = (pos + pack_align - 1) / pack_align * pack_align;
@@ -325,13 +350,16 @@ int oracle_expand(int32_t L, const int64_t *elem_off, const int32_t *c_out, cons
     if (L < 1 || pack_align < 1 || !packed || !mask || !dst) return -1;
     int64_t gbase = 0, pos = 0;
     for (int32_t l = 0; l < L; ++l) {
-        const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
-        const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
+        const int64_t co = c_out[l];
+        int64_t ci = c_in[l], s = khw[l];
+        int lm = mode[l];
+        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
+        if (lm == ORACLE_SHAPE) { ci *= s; s = 1; lm = ORACLE_CHANNEL; }     /* as in oracle_compact */
         int32_t *k_out = (int32_t *)malloc(sizeof(int32_t) * (size_t)co);
         int32_t *k_in = (int32_t *)malloc(sizeof(int32_t) * (size_t)ci);
         if (!k_out || !k_in) { free(k_out); free(k_in); return -1; }
         int64_t n_out, n_in;
-        index_sets(mode[l], co, ci, mask + gbase, k_out, &n_out, k_in, &n_in);
+        index_sets(lm, co, ci, mask + gbase, k_out, &n_out, k_in, &n_in);
         float *dl = dst + elem_off[l];
         const float *pl = packed + pos;
         const int64_t n = co * ci * s;
@@ -357,7 +385,8 @@ int oracle_expand(int32_t L, const int64_t *elem_off, const int32_t *c_out, cons
  *     z = z~ (.) m,
  * with the same candidate z~ = Wbar + U (steps (a), (b)) and the same dual update (d) as oracle_project.
  * mask: in, nonzero = kept, any number of kept groups per layer (a union of node masks keeps more than k);
- * groups of an unconstrained layer are kept whatever their mask bytes say; under both constraints an
+ * groups of an unconstrained layer are kept whatever their mask bytes say; under shape sparsity an entry
+ * takes the byte of its (channel, position) column; under both constraints an
  * entry is kept iff its filter byte and its channel byte are both nonzero.  Entries of a masked-out
  * group are exactly +0 (as the projection writes them), whatever the sign of the candidate.
  * Returns 0, -1 on a bad argument, -2 on a non-finite candidate.
@@ -374,7 +403,7 @@ int oracle_project_frozen(int32_t L, const int64_t *elem_off, const int32_t *c_o
         const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
         if (co < 1 || ci < 1 || s < 1) return -1;
         const int64_t n = co * ci * s;
-        const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
+        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
         const int64_t off = elem_off[l];
         const uint8_t *ml = mask + gbase;
         int bad = 0;
@@ -386,7 +415,8 @@ int oracle_project_frozen(int32_t L, const int64_t *elem_off, const int32_t *c_o
             const float v = wbar + U[off + e];
             if (!isfinite(v)) bad = 1;
             int64_t g;
-            if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;
+            if (mode[l] == ORACLE_SHAPE) g = e % (ci * s);
+            else if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;
             else g = e / (ci * s);
             int keep = mode[l] == ORACLE_NONE || ml[g] != 0;          /* both: g is the filter */
             if (mode[l] == ORACLE_BOTH) keep = keep && ml[co + (e / s) % ci] != 0;
@@ -457,7 +487,7 @@ int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c
         const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
         if (co < 1 || ci < 1 || s < 1) return -1;
         const int64_t n = co * ci * s;
-        const int64_t G = n_groups(mode[l], c_out[l], c_in[l]);
+        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
         if (mode[l] == ORACLE_BOTH) {
             if (k[l] < 1 || k[l] > co || k_in[l] < 1 || k_in[l] > ci) return -1;
         } else if (mode[l] != ORACLE_NONE && (k[l] < 1 || k[l] > G)) return -1;
@@ -480,8 +510,9 @@ int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c
             if (!isfinite(v[e])) bad = 1;
         }
         if (bad) { free(wbar); free(v); return -2; }
-        if (mode[l] == ORACLE_BOTH) {
-            project_composite(v, co, ci, s, k[l], k_in[l], key + gbase, mask + gbase);
+        if (mode[l] == ORACLE_BOTH || mode[l] == ORACLE_SHAPE) {
+            if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], k_in[l], key + gbase, mask + gbase);
+            else project_in_place(v, co, ci, s, 2, k[l], key + gbase, mask + gbase);
 #pragma omp parallel for schedule(static)
             for (int64_t e = 0; e < n; ++e) {
                 Z[off + e] = v[e];

@@ -6,10 +6,12 @@ import paper_2512_14628_amd as pkg
 
 
 class GpuRun:
-    def __init__(self, wl, W, U, pack_align=1, want_wbar=True, want_sqnorm=True, device="cuda:0"):
+    def __init__(self, wl, W, U, pack_align=1, want_wbar=True, want_sqnorm=True, device="cuda:0", table=None):
+        """table: the layer table handed to the library when it differs from wl.table() (e.g. shape-sparsity
+        layers declared through their GEMM view)."""
         self.wl = wl
         self.dev = torch.device(device)
-        self.plan = pkg.Plan(wl.table(), pack_align_elems=pack_align)
+        self.plan = pkg.Plan(wl.table() if table is None else table, pack_align_elems=pack_align)
         p = self.plan
         assert p.arena_elems <= wl.n_arena
         n = wl.n_arena

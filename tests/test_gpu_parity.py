@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-def _run(wl, pack_align=1, want_wbar=True, want_sqnorm=True, threads=8, determinism=True):
+def _run(wl, pack_align=1, want_wbar=True, want_sqnorm=True, threads=8, determinism=True, gpu_table=None):
     from tests.gpu_harness import GpuRun, check_against_oracle
     W, U = wk.generate(wl, threads=threads)
     oracle.set_threads(threads)
@@ -29,7 +29,7 @@ def _run(wl, pack_align=1, want_wbar=True, want_sqnorm=True, threads=8, determin
         else:
             sizes.append(l.n if l.mode == wk.MODE_NONE else int(m.sum()) * l.group_size)
     refc["seg_sizes"] = np.array(sizes)
-    run = GpuRun(wl, W, U, pack_align=pack_align, want_wbar=want_wbar, want_sqnorm=want_sqnorm)
+    run = GpuRun(wl, W, U, pack_align=pack_align, want_wbar=want_wbar, want_sqnorm=want_sqnorm, table=gpu_table)
     run.step()
     got = run.outputs()
     rep = check_against_oracle(wl, got, ref, refc)
@@ -46,7 +46,7 @@ def _run(wl, pack_align=1, want_wbar=True, want_sqnorm=True, threads=8, determin
     # determinism: a second run from fresh inputs gives the same bits; this one packs and expands under the index
     # mappings the projection left in the workspace (NULL masks), which must give the same packed buffer, offsets and
     # kept indices as scanning the mask
-    run2 = GpuRun(wl, W, U, pack_align=pack_align, want_wbar=want_wbar, want_sqnorm=want_sqnorm)
+    run2 = GpuRun(wl, W, U, pack_align=pack_align, want_wbar=want_wbar, want_sqnorm=want_sqnorm, table=gpu_table)
     run2.step(cached=True)
     got2 = run2.outputs()
     assert np.array_equal(got2["layer_off"], refc["layer_off"])

@@ -16,6 +16,7 @@ from tests import test_oracle_frozen as fpins
 from tests import test_oracle_weighted as wpins
 from tests import test_oracle_residuals as rpins
 from tests import test_oracle_composite as cpins
+from tests import test_oracle_shape as spins
 
 MUTATIONS = [
     ("tie_goes_to_higher_index", "(kl[h] == kl[g] && h < g)", "(kl[h] == kl[g] && h > g)"),
@@ -41,8 +42,8 @@ MUTATIONS = [
      "if (0) {\n            for (int64_t g = 0; g < G; ++g) ml[g] = 1;"),
     ("frozen_mask_inverted", "int keep = mode[l] == ORACLE_NONE || ml[g] != 0;", "int keep = mode[l] == ORACLE_NONE || ml[g] == 0;"),
     ("frozen_ignores_mode_none", "int keep = mode[l] == ORACLE_NONE || ml[g] != 0;", "int keep = ml[g] != 0;"),
-    ("frozen_channel_group_wrong", "if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;\n            else g = e / (ci * s);\n            int keep",
-     "if (mode[l] == ORACLE_CHANNEL) g = e % ci;\n            else g = e / (ci * s);\n            int keep"),
+    ("frozen_channel_group_wrong", "else if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;\n            else g = e / (ci * s);\n            int keep",
+     "else if (mode[l] == ORACLE_CHANNEL) g = e % ci;\n            else g = e / (ci * s);\n            int keep"),
     ("frozen_dual_regrouped", "U[off + e] = U[off + e] + (wbar - z);\n            if (Wbar) Wbar[off + e] = wbar;\n        }\n        if (bad)",
      "U[off + e] = (U[off + e] + wbar) - z;\n            if (Wbar) Wbar[off + e] = wbar;\n        }\n        if (bad)"),
     ("frozen_multiplies_by_mask", "const float z = keep ? v : 0.0f;\n            Z[off + e] = z;\n            U[off + e] = U[off + e] + (wbar - z);\n            if (Wbar) Wbar[off + e] = wbar;\n        }\n        if (bad)",
@@ -71,15 +72,21 @@ MUTATIONS = [
      "project_in_place(x, co, ci, s, 0, k_in, key, m);\n    project_in_place(x, co, ci, s, 1, k_out, key + co, m + co);"),
     ("composite_stage_tie_rule", "(key[h] == key[g] && h < g)", "(key[h] == key[g] && h > g)"),
     ("composite_stage_channel_transposed", "x[(o * ci + g) * s + t]", "x[(g * co + o) * s + t]"),
-    ("composite_stage_zeroes_wrong_group", "const int64_t g = channel ? (e / s) % ci : e / (ci * s);", "const int64_t g = channel ? e % ci : e / (ci * s);"),
+    ("composite_stage_zeroes_wrong_group", "(channel ? (e / s) % ci : e / (ci * s));", "(channel ? e % ci : e / (ci * s));"),
+    ("shape_key_stride_wrong", "const double y = (double)x[o * ci * s + g];", "const double y = (double)x[o * ci + g];"),
+    ("shape_zeroes_wrong_group", "const int64_t g = channel == 2 ? e % (ci * s) :", "const int64_t g = channel == 2 ? e % ci :"),
+    ("shape_group_count_is_channels", "const int64_t G = channel == 2 ? ci * s : (channel ? ci : co);", "const int64_t G = channel == 2 ? ci : (channel ? ci : co);"),
+    ("shape_packed_as_whole_channels", "if (lm == ORACLE_SHAPE) {\n            /* shape groups", "if (0) {\n            /* shape groups"),
+    ("shape_frozen_group_wrong", "if (mode[l] == ORACLE_SHAPE) g = e % (ci * s);", "if (mode[l] == ORACLE_SHAPE) g = (e / s) % (ci * s);"),
     ("composite_dual_regrouped", "U[off + e] = U[off + e] + (wbar[e] - v[e]);", "U[off + e] = (U[off + e] + wbar[e]) - v[e];"),
     ("composite_channel_bytes_misplaced", "const uint8_t *mc = mode == ORACLE_BOTH ? ml + co : ml;", "const uint8_t *mc = mode == ORACLE_BOTH ? ml + ci : ml;"),
-    ("composite_kept_idx_channels_first", "if (mode[l] != ORACLE_CHANNEL)\n            for (int64_t p = 0; p < n_out; ++p) kept_idx[nk++] = k_out[p];\n        if (mode[l] == ORACLE_CHANNEL || mode[l] == ORACLE_BOTH)\n            for (int64_t q = 0; q < n_in; ++q) kept_idx[nk++] = k_in[q];",
-     "if (mode[l] == ORACLE_CHANNEL || mode[l] == ORACLE_BOTH)\n            for (int64_t q = 0; q < n_in; ++q) kept_idx[nk++] = k_in[q];\n        if (mode[l] != ORACLE_CHANNEL)\n            for (int64_t p = 0; p < n_out; ++p) kept_idx[nk++] = k_out[p];"),
+    ("composite_kept_idx_channels_first", "if (lm != ORACLE_CHANNEL)\n            for (int64_t p = 0; p < n_out; ++p) kept_idx[nk++] = k_out[p];\n        if (lm == ORACLE_CHANNEL || lm == ORACLE_BOTH)\n            for (int64_t q = 0; q < n_in; ++q) kept_idx[nk++] = k_in[q];",
+     "if (lm == ORACLE_CHANNEL || lm == ORACLE_BOTH)\n            for (int64_t q = 0; q < n_in; ++q) kept_idx[nk++] = k_in[q];\n        if (lm != ORACLE_CHANNEL)\n            for (int64_t p = 0; p < n_out; ++p) kept_idx[nk++] = k_out[p];"),
     ("composite_frozen_or_instead_of_and", "keep = keep && ml[co + (e / s) % ci] != 0;", "keep = keep || ml[co + (e / s) % ci] != 0;"),
     ("composite_frozen_channel_byte_offset", "keep = keep && ml[co + (e / s) % ci] != 0;", "keep = keep && ml[(e / s) % ci] != 0;"),
-    ("composite_weighted_projects_filters_only", "project_composite(v, co, ci, s, k[l], k_in[l], key + gbase, mask + gbase);\n#pragma omp parallel for schedule(static)\n            for (int64_t e = 0; e < n; ++e) {\n                Z[off + e] = v[e];\n                U[off + e] = U[off + e] + (wbar[e] - v[e]);\n                if (Wbar) Wbar[off + e] = wbar[e];\n            }\n            free(wbar);\n            free(v);\n            gbase += G;\n            continue;\n        }\n        double *kl = key + gbase;\n#pragma omp",
-     "project_composite(v, co, ci, s, k[l], ci, key + gbase, mask + gbase);\n#pragma omp parallel for schedule(static)\n            for (int64_t e = 0; e < n; ++e) {\n                Z[off + e] = v[e];\n                U[off + e] = U[off + e] + (wbar[e] - v[e]);\n                if (Wbar) Wbar[off + e] = wbar[e];\n            }\n            free(wbar);\n            free(v);\n            gbase += G;\n            continue;\n        }\n        double *kl = key + gbase;\n#pragma omp"),
+    ("composite_weighted_projects_filters_only",
+     "return -2; }\n        if (mode[l] == ORACLE_BOTH || mode[l] == ORACLE_SHAPE) {\n            if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], k_in[l],",
+     "return -2; }\n        if (mode[l] == ORACLE_BOTH || mode[l] == ORACLE_SHAPE) {\n            if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], ci,"),
 ]
 
 PIN_FUNCS = [
@@ -116,6 +123,9 @@ PIN_FUNCS = [
     cpins.test_frozen_mask_under_both_constraints,
     cpins.test_weighted_candidate_under_both_constraints,
     cpins.test_union_of_composite_masks_packs_the_union_of_both_index_sets,
+    spins.test_handworked_shape_layer,
+    lambda: [spins.test_shape_groups_are_the_columns_of_the_gemm_view(s) for s in range(2)],
+    lambda: [spins.test_shape_against_numpy(s) for s in range(2)],
 ]
 
 

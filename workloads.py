@@ -26,6 +26,7 @@ MODE_NONE = 0      # no constraint on this layer: every filter is kept
 MODE_FILTER = 1    # groups are output filters  W[g, :, :, :]
 MODE_CHANNEL = 2   # groups are input channels  W[:, g, :, :]
 MODE_BOTH = 3      # both constraints: c_out filter groups followed by c_in channel groups
+MODE_SHAPE = 4     # groups are the spatial positions of the input channels  W[:, b, u, v]  (c_in * khw groups)
 
 _TENSOR_W = 0
 _TENSOR_U = 1
@@ -54,11 +55,15 @@ class Layer:
     def groups(self) -> int:
         if self.mode == MODE_BOTH:
             return self.c_out + self.c_in
+        if self.mode == MODE_SHAPE:
+            return self.c_in * self.khw
         return self.c_in if self.mode == MODE_CHANNEL else self.c_out
 
     @property
     def group_size(self) -> int:
         """Elements per group (MODE_BOTH: of a filter group)."""
+        if self.mode == MODE_SHAPE:
+            return self.c_out
         return (self.c_out if self.mode == MODE_CHANNEL else self.c_in) * self.khw
 
     @property
@@ -106,6 +111,17 @@ class Workload:
             "k": np.array([l.k for l in self.layers], dtype=np.int32),
             "k_in": np.array([l.k_in for l in self.layers], dtype=np.int32),
         }
+        return cols
+
+    def gemm_view_table(self):
+        """The same layers with every MODE_SHAPE layer declared as what it is in the [c_out][c_in*khw] GEMM view:
+        a MODE_CHANNEL layer of c_in*khw channels with khw = 1 (its groups are that view's columns).  Element
+        offsets, group order and k do not change."""
+        cols = self.table()
+        shape = cols["mode"] == MODE_SHAPE
+        cols["c_in"] = np.where(shape, cols["c_in"] * cols["khw"], cols["c_in"]).astype(np.int32)
+        cols["khw"] = np.where(shape, 1, cols["khw"]).astype(np.int32)
+        cols["mode"] = np.where(shape, MODE_CHANNEL, cols["mode"]).astype(np.int32)
         return cols
 
     def algorithmic_bytes(self):
