@@ -143,6 +143,37 @@ def main():
     gbps = bytes_["step"] / (elapsed / args.steps) / 1e9
     params_per_s = wl.n_total / (elapsed / args.steps)
 
+    # ---- distribution over steps (median, min) and every call timed alone: HIP events on the stream the calls use
+    def timed_us(fn, reps):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for e0, e1 in evs:
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        return sorted(1e3 * e0.elapsed_time(e1) for e0, e1 in evs)
+
+    per_step = timed_us(step, args.steps)
+    step_stats = {"median_us": round(per_step[len(per_step) // 2], 2), "min_us": round(per_step[0], 2)}
+
+    def call_alone(which):
+        def fn():
+            b = sets[counter[0] % nsets]
+            counter[0] += 1
+            if which == "project":
+                pkg.hsadmm_project(plan, b.W, b.U, b.Z, None, b.mask, None, b.ws, stream=stream)
+            elif which == "compact":
+                pkg.hsadmm_compact(plan, b.Z, b.mask if args.compact_rescan else None, b.packed, b.off, b.kept, b.ws,
+                                   stream=stream)
+            else:
+                pkg.hsadmm_expand(plan, b.packed, b.mask if args.expand_rescan else None, b.dst, b.ws, stream=stream)
+        return fn
+
+    per_call_us = {}
+    for which in ("project", "compact", "expand"):      # in this order: every set then holds a valid selection
+        ts = timed_us(call_alone(which), max(nsets, args.steps // 2))
+        per_call_us[which] = {"median_us": round(ts[len(ts) // 2], 2), "min_us": round(ts[0], 2)}
+
     # ---- per-kernel durations: the same K steps again with every launch carrying its own HIP events
     pkg.hsadmm_kernel_timing_enable(plan, True)
     kernel_ms = {}
@@ -369,10 +400,22 @@ def main():
             s += oracle.last_call_seconds
             spent += s
             reps += 1
+        # the same three calls on one thread (two steps), for the per-core figure
+        oracle.set_threads(1)
+        t1 = 0.0
+        for _ in range(2):
+            r = oracle.project(table, W, U)
+            t1 += oracle.last_call_seconds
+            c = oracle.compact(table, r["Z"], r["mask"])
+            t1 += oracle.last_call_seconds
+            oracle.expand(table, c["packed"], r["mask"], wl.n_arena)
+            t1 += oracle.last_call_seconds
+        oracle.set_threads(cores)
+        single = {"ms_per_step": round(1e3 * t1 / 2, 2), "GBps": round(bytes_["step"] / (t1 / 2) / 1e9, 3)}
         cpu = {"value": round(bytes_["step"] / (spent / reps) / 1e9, 3), "unit": "GB/s", "cores": cores,
                "kind": "oracle", "sample": "%d full steps of workload %s (all %d layers, %d parameters), C calls only"
                % (reps, wl.name, len(wl.layers), wl.n_total),
-               "ms_per_step": round(1e3 * spent / reps, 2),
+               "ms_per_step": round(1e3 * spent / reps, 2), "one_thread": single,
                "params_per_s": round(wl.n_total / (spent / reps), 1)}
 
     out = {
@@ -395,6 +438,8 @@ def main():
                    "algorithmic_bytes_per_step": bytes_["step"]},
         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
         "params_per_s": round(params_per_s, 1),
+        "step_us": step_stats,
+        "call_alone_us": per_call_us,
         "kernel_us_per_launch": {k: (round(v, 2) if v else None) for k, v in per_launch_us.items()},
         "kernel_launches_per_step": launches_per_step,
         "kernel_us_per_step_sum": round(sum(kernel_us_per_step.values()), 2),
