@@ -3,22 +3,26 @@
 //
 // Kernel overview (every launch covers all layers of the plan through a work-item table):
 //
-//   project_pass1   streams the R replicas and U once.  Computes Wbar, V = Wbar + U, the fp64
-//                   partial sums of V^2, and writes the values that are final if the group is
-//                   kept: Z <- V, U <- U + (Wbar - V).                       [Eq. (9), (12)]
+//   project_pass1   streams the R replicas and U once.  Computes Wbar, V = Wbar + U and the fp64
+//                   partial sums of V^2; for FILTER / BOTH / NONE layers it writes the values that are
+//                   final if the group is kept: Z <- V, U <- U + (Wbar - V).   [Eq. (9), (12)]
 //   select_topk     one workgroup per layer: byte-wise radix select of the k-th largest key on
 //                   the uint64 view of the non-negative doubles (bytes all keys share are skipped,
 //                   the search stops once one candidate is left), ties cut by an ordered scan so
-//                   that lower indices win.                                  [Eq. (10)]
+//                   that lower indices win; leaves the selection's index mappings in the workspace
+//                   for a compaction / expansion without a mask.            [Eq. (10)]
 //   project_fixup   touches pruned groups only: U <- V (taken from Z), Z <- +0.  For a pruned
 //                   group U + (Wbar - 0) equals V bit for bit, so no replica is read again.
 //   channel_final   CHANNEL layers: pass 1 only sums; their Z and U are written here, in one streaming
 //                   pass under the mask just selected (the kernel of the frozen-mask path).
 //   composite_colsums   layers under both constraints: channel norms over the kept filters, then a
 //                   second select_topk for the channels.   [Section 3, paragraph after Eq. (10)]
-//   scan_mask       per layer: kept count, exclusive positions, kept_idx, layer_off.
+//   scan_mask       index mappings from a given mask: kept counts, positions, kept_idx, layer_off.
 //   compact_gather  packed <- src[K_out, K_in, :]                             [Eq. (15)]
 //   expand_scatter  dst <- zero fill + scatter of packed                      [Section 4.4.3]
+//   project_frozen  one pass under a given mask                               [Section 4.5]
+//   weighted_pass1 / weighted_fixup / weighted_final   the candidate of Eq. (9) with its rho_2 term
+//   dual_inter_kernel  Eq. (13);  residual_partials / residual_finish  Section 3.4;  mask_or_kernel  Eq. (14)
 //
 // Nothing here is a dense contraction, so no MFMA is used; every kernel is bound by HBM traffic.
 // Arena data is touched once per kernel, so it is moved with non-temporal 128-bit accesses.
@@ -351,14 +355,8 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     }
 
     if (hipGetDevice(&p->device) != hipSuccess) { delete p; return HSADMM_ERR_HIP; }
-    const size_t bl = sizeof(DevLayer) * p->dev_layers.size();
-    const size_t bp = sizeof(WorkItem) * p->items_proj.size();
-    const size_t br = sizeof(WorkItem) * p->items_rows.size();
-    const size_t bb = sizeof(WorkItem) * p->items_both.size();
-    const size_t bch = sizeof(WorkItem) * p->items_chan.size();
-    const size_t bfx = sizeof(WorkItem) * p->items_fix.size();
-    const size_t bbl = sizeof(int32_t) * p->both_layers.size();
     std::vector<uint16_t> chunk_layer;
+    std::vector<float> coef;
     try {
         const size_t ng = group_layer.size();
         chunk_layer.assign((ng + 15) / 16, 0xffff);
@@ -369,50 +367,32 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             for (size_t i = 1; i < 16 && pure; ++i) pure = group_layer[16 * c + i] == first;
             if (pure) chunk_layer[c] = first;
         }
+        coef.assign(2 * p->layers.size(), 0.f);                  // a_l = 1, b_l = 0
+        for (size_t l = 0; l < p->layers.size(); ++l) coef[2 * l] = 1.f;
     } catch (...) {
         delete p;
         return HSADMM_ERR_HIP;
     }
-    const size_t bg = sizeof(uint16_t) * group_layer.size();
-    const size_t bc = sizeof(uint16_t) * chunk_layer.size();
-    bool ok = hipMalloc(&p->d_layers, bl) == hipSuccess;
-    ok = ok && hipMalloc(&p->d_items_proj, bp) == hipSuccess;
-    ok = ok && hipMalloc(&p->d_items_rows, br) == hipSuccess;
-    auto upload = [&](const std::vector<WorkItem>& v, WorkItem** d) {
-        if (v.empty()) return;
-        const size_t b = sizeof(WorkItem) * v.size();
-        ok = ok && hipMalloc(d, b) == hipSuccess;
-        ok = ok && hipMemcpy(*d, v.data(), b, hipMemcpyHostToDevice) == hipSuccess;
+    // device copies of the tables (an empty table stays a null pointer and is never launched over)
+    bool ok = true;
+    auto upload = [&ok](const auto& v, auto** d) {
+        if (v.empty() || !ok) return;
+        const size_t bytes = sizeof(v[0]) * v.size();
+        ok = hipMalloc(reinterpret_cast<void**>(d), bytes) == hipSuccess &&
+             hipMemcpy(*d, v.data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
     };
+    upload(p->dev_layers, &p->d_layers);
+    upload(p->items_proj, &p->d_items_proj);
+    upload(p->items_rows, &p->d_items_rows);
+    upload(p->items_fix, &p->d_items_fix);
     upload(p->items_wfix, &p->d_items_wfix);
     upload(p->items_wfinal, &p->d_items_wfinal);
-    if (bfx) {
-        ok = ok && hipMalloc(&p->d_items_fix, bfx) == hipSuccess;
-        ok = ok && hipMemcpy(p->d_items_fix, p->items_fix.data(), bfx, hipMemcpyHostToDevice) == hipSuccess;
-    }
-    if (bch) {
-        ok = ok && hipMalloc(&p->d_items_chan, bch) == hipSuccess;
-        ok = ok && hipMemcpy(p->d_items_chan, p->items_chan.data(), bch, hipMemcpyHostToDevice) == hipSuccess;
-    }
-    if (bb) {
-        ok = ok && hipMalloc(&p->d_items_both, bb) == hipSuccess;
-        ok = ok && hipMalloc(&p->d_both_layers, bbl) == hipSuccess;
-        ok = ok && hipMemcpy(p->d_items_both, p->items_both.data(), bb, hipMemcpyHostToDevice) == hipSuccess;
-        ok = ok && hipMemcpy(p->d_both_layers, p->both_layers.data(), bbl, hipMemcpyHostToDevice) == hipSuccess;
-    }
-    ok = ok && hipMalloc(&p->d_group_layer, bg) == hipSuccess;
-    ok = ok && hipMalloc(&p->d_chunk_layer, bc) == hipSuccess;
-    ok = ok && hipMalloc(&p->d_coef, sizeof(float) * 2 * p->layers.size()) == hipSuccess;
-    if (ok) {
-        std::vector<float> ones(2 * p->layers.size(), 0.f);
-        for (size_t l = 0; l < p->layers.size(); ++l) ones[2 * l] = 1.f;
-        ok = hipMemcpy(p->d_coef, ones.data(), sizeof(float) * ones.size(), hipMemcpyHostToDevice) == hipSuccess;
-    }
-    ok = ok && hipMemcpy(p->d_group_layer, group_layer.data(), bg, hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(p->d_chunk_layer, chunk_layer.data(), bc, hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(p->d_layers, p->dev_layers.data(), bl, hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(p->d_items_proj, p->items_proj.data(), bp, hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(p->d_items_rows, p->items_rows.data(), br, hipMemcpyHostToDevice) == hipSuccess;
+    upload(p->items_chan, &p->d_items_chan);
+    upload(p->items_both, &p->d_items_both);
+    upload(p->both_layers, &p->d_both_layers);
+    upload(group_layer, &p->d_group_layer);
+    upload(chunk_layer, &p->d_chunk_layer);
+    upload(coef, &p->d_coef);
     if (!ok) {
         (void)hipGetLastError();
         hsadmm_plan_destroy(p);
