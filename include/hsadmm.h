@@ -320,7 +320,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 16
+#define HSADMM_KERNEL_COUNT 17
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

@@ -31,7 +31,7 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name",
            "hsadmm_project_frozen", "hsadmm_mask_or", "hsadmm_compact_sum", "hsadmm_node_coefficients",
            "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals")
-KERNEL_COUNT = 16
+KERNEL_COUNT = 17
 
 
 class HsadmmError(RuntimeError):

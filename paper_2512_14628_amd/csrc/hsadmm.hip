@@ -61,7 +61,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFixup, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -72,8 +72,8 @@ struct hsadmm_plan {
     std::vector<DevLayer> dev_layers;
     std::vector<WorkItem> items_proj;   // project kernels
     std::vector<WorkItem> items_rows;   // compact / expand kernels
-    std::vector<WorkItem> items_fix;    // project_fixup: the row items of the FILTER and BOTH layers
-    std::vector<WorkItem> items_wfix;   // weighted_fixup: the row items of the FILTER layers
+    std::vector<WorkItem> items_fix;    // project_fixup, weighted_fixup: the row items of the FILTER layers
+    std::vector<WorkItem> items_bfix;   // composite_fixup: the row items of the BOTH layers
     std::vector<WorkItem> items_wfinal; // weighted_final: CHANNEL tiles and BOTH rows (a subset of items_proj)
     std::vector<WorkItem> items_chan;   // channel_final: the row items of the CHANNEL layers (a subset of items_rows)
     std::vector<WorkItem> items_both;   // composite_colsums: tiles of the layers under both constraints
@@ -90,7 +90,7 @@ struct hsadmm_plan {
     WorkItem* d_items_proj = nullptr;
     WorkItem* d_items_rows = nullptr;
     WorkItem* d_items_fix = nullptr;
-    WorkItem* d_items_wfix = nullptr;
+    WorkItem* d_items_bfix = nullptr;
     WorkItem* d_items_wfinal = nullptr;
     WorkItem* d_items_chan = nullptr;
     WorkItem* d_items_both = nullptr;
@@ -319,9 +319,11 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
                 add_row_items(p->items_chan, l, d, x.mode);
             } else {
                 add_row_items(p->items_proj, l, d, x.mode);
-                if (x.mode != HSADMM_MODE_NONE) add_row_items(p->items_fix, l, d, x.mode);
-                if (x.mode == HSADMM_MODE_FILTER) add_row_items(p->items_wfix, l, d, x.mode);
-                if (x.mode == HSADMM_MODE_BOTH) add_row_items(p->items_wfinal, l, d, x.mode);
+                if (x.mode == HSADMM_MODE_FILTER) add_row_items(p->items_fix, l, d, x.mode);
+                if (x.mode == HSADMM_MODE_BOTH) {
+                    add_row_items(p->items_bfix, l, d, x.mode);
+                    add_row_items(p->items_wfinal, l, d, x.mode);
+                }
             }
             if (both) {
                 add_tile_items(p->items_both, l, d);
@@ -385,7 +387,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     upload(p->items_proj, &p->d_items_proj);
     upload(p->items_rows, &p->d_items_rows);
     upload(p->items_fix, &p->d_items_fix);
-    upload(p->items_wfix, &p->d_items_wfix);
+    upload(p->items_bfix, &p->d_items_bfix);
     upload(p->items_wfinal, &p->d_items_wfinal);
     upload(p->items_chan, &p->d_items_chan);
     upload(p->items_both, &p->d_items_both);
@@ -410,7 +412,7 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_items_proj) (void)hipFree(p->d_items_proj);
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
     if (p->d_items_fix) (void)hipFree(p->d_items_fix);
-    if (p->d_items_wfix) (void)hipFree(p->d_items_wfix);
+    if (p->d_items_bfix) (void)hipFree(p->d_items_bfix);
     if (p->d_items_wfinal) (void)hipFree(p->d_items_wfinal);
     if (p->d_items_chan) (void)hipFree(p->d_items_chan);
     if (p->d_items_both) (void)hipFree(p->d_items_both);
@@ -466,6 +468,11 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
     if (!p->items_fix.empty()) {
         e = launch(p, kFixup, project_fixup, (unsigned)p->items_fix.size(), kBlock, s,
                    (const WorkItem*)p->d_items_fix, (const uint8_t*)mask, U, Z);
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
+    if (!p->items_bfix.empty()) {
+        e = launch(p, kBothFixup, composite_fixup, (unsigned)p->items_bfix.size(), kBlock, s,
+                   (const WorkItem*)p->d_items_bfix, (const uint8_t*)mask, U, Z);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
     if (!p->items_chan.empty()) {
@@ -640,9 +647,9 @@ int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replic
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     if (run_selection(p, w.p.key, w.p.colpart, Z, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
     const uint8_t* cm = mask;
-    if (!p->items_wfix.empty()) {
-        e = launch(p, kWFixup, weighted_fixup, (unsigned)p->items_wfix.size(), kBlock, s,
-                   (const WorkItem*)p->d_items_wfix, cm, U, Z, Zg, Vd, (const float*)p->d_coef);
+    if (!p->items_fix.empty()) {
+        e = launch(p, kWFixup, weighted_fixup, (unsigned)p->items_fix.size(), kBlock, s,
+                   (const WorkItem*)p->d_items_fix, cm, U, Z, Zg, Vd, (const float*)p->d_coef);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
     if (!p->items_wfinal.empty()) {
@@ -793,6 +800,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kColsums: return "composite_colsums";
         case kChanFinal: return "channel_final";
         case kWFixup: return "weighted_fixup";
+        case kBothFixup: return "composite_fixup";
         default: return "";
     }
 }

@@ -293,17 +293,13 @@ __device__ __forceinline__ void quad_pruned(const uint8_t* __restrict__ mc, cons
     }
 }
 
-// Row items of the FILTER and BOTH layers (CHANNEL layers have no speculative outputs, NONE layers nothing to repair).
-// A pruned filter's row moves whole: U <- V (held in Z), Z <- +0.  In a kept filter's row of a BOTH layer only
-// the columns of pruned channels change; a partly pruned quad is rewritten whole, the kept elements of U
-// passing through (they are final already), so that every access is a full 128 bits.
+// Row items of the FILTER layers.  A pruned filter's row moves whole: U <- V (held in Z), Z <- +0; kept rows are
+// final already.
 __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restrict__ items,
                                                         const uint8_t* __restrict__ mask,
                                                         float* __restrict__ U, float* __restrict__ Z)
 {
     const WorkItem it = items[blockIdx.x];
-    const int mode = item_mode(it);
-    if (mode == HSADMM_MODE_NONE || mode == HSADMM_MODE_CHANNEL) return;
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
@@ -312,45 +308,10 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
     const int rows_at_once = kBlock / lpr;
     const int sub = threadIdx.x / lpr;
     const int j = threadIdx.x - sub * lpr;
-    const bool columns = mode == HSADMM_MODE_BOTH;
-    const uint8_t* mc = mask + it.aux;            // BOTH: channel bytes of the layer
-    const DivKhw div(it.khw);
     for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+        if (mask[it.g0 + rr] != 0) continue;
         const int64_t base = it.base + (int64_t)rr * row_len;
-        const bool row_stays = mask[it.g0 + rr] != 0;
-        if (row_stays) {
-            if (!columns) continue;
-            if (vec) {
-                const int nchunk = row_len >> 2;
-                for (int c = j; c < nchunk; c += lpr) {
-                    const int col = c << 2;
-                    bool pr[4];
-                    quad_pruned(mc, div, col, pr);
-                    if (!(pr[0] || pr[1] || pr[2] || pr[3])) continue;
-                    const int64_t e = base + col;
-                    const v4f z = ld4(Z + e);
-                    if (pr[0] && pr[1] && pr[2] && pr[3]) {
-                        st4(U + e, z);
-                        st4(Z + e, zero4);
-                    } else {
-                        v4f u = ld4(U + e);
-                        v4f zn = z;
-                        if (pr[0]) { u.x = z.x; zn.x = 0.f; }
-                        if (pr[1]) { u.y = z.y; zn.y = 0.f; }
-                        if (pr[2]) { u.z = z.z; zn.z = 0.f; }
-                        if (pr[3]) { u.w = z.w; zn.w = 0.f; }
-                        st4(U + e, u);
-                        st4(Z + e, zn);
-                    }
-                }
-            } else {
-                for (int c = j; c < row_len; c += lpr) {
-                    if (mc[div(c)] != 0) continue;
-                    st1(U + base + c, ld1(Z + base + c));
-                    st1(Z + base + c, 0.f);
-                }
-            }
-        } else if (vec) {
+        if (vec) {
             const int nchunk = row_len >> 2;
             for (int c = j; c < nchunk; c += lpr) {
                 const int64_t e = base + ((int64_t)c << 2);
@@ -361,6 +322,86 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
             for (int c = j; c < row_len; c += lpr) {
                 st1(U + base + c, ld1(Z + base + c));
                 st1(Z + base + c, 0.f);
+            }
+        }
+    }
+}
+
+// Row items of the BOTH layers.  A pruned filter's row moves whole, as above.  In a kept filter's row only the
+// columns of pruned channels change: a fully pruned quad moves, a partly pruned quad is rewritten whole, the kept
+// elements of U passing through (they are final already), so that every access is a full 128 bits.  A lane
+// owns the same quads in every row, so their channel flags are fetched once and two rows are in flight.
+__global__ __launch_bounds__(kBlock) void composite_fixup(const WorkItem* __restrict__ items,
+                                                          const uint8_t* __restrict__ mask,
+                                                          float* __restrict__ U, float* __restrict__ Z)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int row_len = it.row_len;
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+    const int rows_at_once = kBlock / lpr;
+    const int sub = threadIdx.x / lpr;
+    const int j = threadIdx.x - sub * lpr;
+    const uint8_t* mc = mask + it.aux;            // channel bytes of the layer
+    const uint8_t* mf = mask + it.g0;             // filter bytes of the item's rows
+    const DivKhw div(it.khw);
+    if (!item_vec(it)) {
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            const bool stays = mf[rr] != 0;
+            const int64_t base = it.base + (int64_t)rr * row_len;
+            for (int c = j; c < row_len; c += lpr) {
+                if (stays && mc[div(c)] != 0) continue;
+                st1(U + base + c, ld1(Z + base + c));
+                st1(Z + base + c, 0.f);
+            }
+        }
+        return;
+    }
+    const int nchunk = row_len >> 2;
+    for (int c = j; c < nchunk; c += lpr) {
+        const int col = c << 2;
+        bool pr[4];
+        quad_pruned(mc, div, col, pr);
+        const bool any = pr[0] || pr[1] || pr[2] || pr[3];
+        const bool all = pr[0] && pr[1] && pr[2] && pr[3];
+        for (int rr0 = sub; rr0 < it.nr; rr0 += 2 * rows_at_once) {
+            const int rr1 = rr0 + rows_at_once;
+            const bool live1 = rr1 < it.nr;
+            const bool stays0 = mf[rr0] != 0;
+            const bool stays1 = live1 && mf[rr1] != 0;
+            // what each row's quad needs: nothing / a move (U <- Z, Z <- 0) / a merge (also reads U)
+            const bool move0 = !stays0 || all, move1 = live1 && (!stays1 || all);
+            const bool merge0 = stays0 && any && !all, merge1 = stays1 && any && !all;
+            const int64_t e0 = it.base + (int64_t)rr0 * row_len + col;
+            const int64_t e1 = it.base + (int64_t)rr1 * row_len + col;
+            v4f z0 = zero4, z1 = zero4, u0 = zero4, u1 = zero4;
+            if (move0 || merge0) z0 = ld4(Z + e0);
+            if (move1 || merge1) z1 = ld4(Z + e1);
+            if (merge0) u0 = ld4(U + e0);
+            if (merge1) u1 = ld4(U + e1);
+            if (move0) {
+                st4(U + e0, z0);
+                st4(Z + e0, zero4);
+            } else if (merge0) {
+                v4f zn = z0;
+                if (pr[0]) { u0.x = z0.x; zn.x = 0.f; }
+                if (pr[1]) { u0.y = z0.y; zn.y = 0.f; }
+                if (pr[2]) { u0.z = z0.z; zn.z = 0.f; }
+                if (pr[3]) { u0.w = z0.w; zn.w = 0.f; }
+                st4(U + e0, u0);
+                st4(Z + e0, zn);
+            }
+            if (move1) {
+                st4(U + e1, z1);
+                st4(Z + e1, zero4);
+            } else if (merge1) {
+                v4f zn = z1;
+                if (pr[0]) { u1.x = z1.x; zn.x = 0.f; }
+                if (pr[1]) { u1.y = z1.y; zn.y = 0.f; }
+                if (pr[2]) { u1.z = z1.z; zn.z = 0.f; }
+                if (pr[3]) { u1.w = z1.w; zn.w = 0.f; }
+                st4(U + e1, u1);
+                st4(Z + e1, zn);
             }
         }
     }
