@@ -76,6 +76,8 @@ def _load():
     lib.oracle_residuals.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, ctypes.POINTER(f32p), ctypes.c_int32,
                                      f32p, f32p, f32p, f32p, f64p]
     lib.oracle_residuals.restype = ctypes.c_int
+    lib.oracle_average.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.POINTER(f32p), f32p]
+    lib.oracle_average.restype = ctypes.c_int
     lib.oracle_mask_or.argtypes = [ctypes.c_int64, ctypes.POINTER(u8p), ctypes.c_int32, u8p]
     lib.oracle_mask_or.restype = ctypes.c_int
     _lib = lib
@@ -253,6 +255,21 @@ def mask_or(masks):
     if rc != 0:
         raise ValueError("oracle_mask_or failed with code %d" % rc)
     return out
+
+
+def average(bufs):
+    """Eq. (11): mean of M equally long float32 buffers (left-to-right sum in node order, times fl32(1/M))."""
+    lib = _load()
+    bs = [np.ascontiguousarray(b, dtype=np.float32) for b in bufs]
+    n = bs[0].size
+    assert all(b.shape == (n,) for b in bs)
+    out = np.full(max(n, 1), np.nan, dtype=np.float32)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    ptrs = (f32p * len(bs))(*[_p(b, ctypes.c_float) for b in bs])
+    rc = lib.oracle_average(len(bs), n, ptrs, _p(out, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("oracle_average failed with code %d" % rc)
+    return out[:n]
 
 
 def node_coefficients(rho1, rho2, lam: float, M: int, P: int):

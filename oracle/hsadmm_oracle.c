@@ -573,6 +573,24 @@ int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c
 }
 
 /*
+ * Global consensus, Eq. (11): z = (1/M) sum_i (z_i + v_i).  The terms c_i = z_i + v_i arrive as M buffers of
+ * equal length (the compacted pre-transmission buffers of Section 4.4.2, all under the same mask); the sum runs
+ * left to right in fp32 in node order and is multiplied by fl32(1/M), the convention of the replica mean.
+ */
+int oracle_average(int32_t M, int64_t n, const float *const *bufs, float *out)
+{
+    if (M < 1 || n < 0 || !bufs || !out) return -1;
+    const float inv_M = 1.0f / (float)M;
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < n; ++e) {
+        float acc = bufs[0][e];
+        for (int32_t i = 1; i < M; ++i) acc = acc + bufs[i][e];
+        out[e] = acc * inv_M;
+    }
+    return 0;
+}
+
+/*
  * Inter-node dual update, Eq. (13): v <- v + (z_i - z), element by element over every layer (arena
  * padding is left alone).  Zi: the node's projected consensus; Zg: the new global consensus.
  */

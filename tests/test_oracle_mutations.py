@@ -17,6 +17,7 @@ from tests import test_oracle_weighted as wpins
 from tests import test_oracle_residuals as rpins
 from tests import test_oracle_composite as cpins
 from tests import test_oracle_shape as spins
+from tests import test_oracle_global as gpins
 
 MUTATIONS = [
     ("tie_goes_to_higher_index", "(kl[h] == kl[g] && h < g)", "(kl[h] == kl[g] && h > g)"),
@@ -73,6 +74,9 @@ MUTATIONS = [
     ("composite_stage_tie_rule", "(key[h] == key[g] && h < g)", "(key[h] == key[g] && h > g)"),
     ("composite_stage_channel_transposed", "x[(o * ci + g) * s + t]", "x[(g * co + o) * s + t]"),
     ("composite_stage_zeroes_wrong_group", "(channel ? (e / s) % ci : e / (ci * s));", "(channel ? e % ci : e / (ci * s));"),
+    ("average_by_division", "out[e] = acc * inv_M;", "out[e] = acc / (float)M;"),
+    ("average_drops_last_node", "for (int32_t i = 1; i < M; ++i) acc = acc + bufs[i][e];", "for (int32_t i = 1; i < M - 1; ++i) acc = acc + bufs[i][e];"),
+    ("average_sums_in_double", "float acc = bufs[0][e];\n        for (int32_t i = 1; i < M; ++i) acc = acc + bufs[i][e];", "double acc = bufs[0][e];\n        for (int32_t i = 1; i < M; ++i) acc = acc + bufs[i][e];"),
     ("shape_key_stride_wrong", "const double y = (double)x[o * ci * s + g];", "const double y = (double)x[o * ci + g];"),
     ("shape_zeroes_wrong_group", "const int64_t g = channel == 2 ? e % (ci * s) :", "const int64_t g = channel == 2 ? e % ci :"),
     ("shape_group_count_is_channels", "const int64_t G = channel == 2 ? ci * s : (channel ? ci : co);", "const int64_t G = channel == 2 ? ci : (channel ? ci : co);"),
@@ -123,6 +127,8 @@ PIN_FUNCS = [
     cpins.test_frozen_mask_under_both_constraints,
     cpins.test_weighted_candidate_under_both_constraints,
     cpins.test_union_of_composite_masks_packs_the_union_of_both_index_sets,
+    gpins.test_handworked_mean_of_node_buffers,
+    lambda: [gpins.test_mean_equals_the_pinned_replica_mean_and_numpy(s) for s in range(2)],
     spins.test_handworked_shape_layer,
     lambda: [spins.test_shape_groups_are_the_columns_of_the_gemm_view(s) for s in range(2)],
     lambda: [spins.test_shape_against_numpy(s) for s in range(2)],
@@ -143,7 +149,7 @@ def test_a_planted_mistake_in_the_oracle_fails_a_pin(name, old, new, tmp_path, m
     lib = ctypes.CDLL(str(so_file))
     for fn in ("oracle_project", "oracle_compact", "oracle_expand", "oracle_set_threads", "oracle_get_threads",
                "oracle_project_frozen", "oracle_mask_or", "oracle_node_coefficients", "oracle_project_weighted",
-               "oracle_dual_inter", "oracle_add_arenas", "oracle_residuals"):
+               "oracle_dual_inter", "oracle_add_arenas", "oracle_residuals", "oracle_average"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(oracle, "_lib", lib)
