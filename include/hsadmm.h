@@ -268,6 +268,21 @@ int hsadmm_project_weighted(const hsadmm_plan_t* plan, const float* const* W_rep
 int hsadmm_dual_inter(const hsadmm_plan_t* plan, const float* Zi, const float* Zg, float* Vd, void* hip_stream);
 
 /*
+ * Global consensus on one device, Eq. (11): z = (1/M) sum_i (z_i + v_i).  The
+ * terms c_i = z_i + v_i are M buffers of n_elems floats each -- in the paper's
+ * pipeline the nodes' compact pre-transmission buffers, which all have the
+ * layout of the synchronised mask, reduced by an inter-node AllReduce and
+ * divided by M (Section 4.4.2); here they are resident in one HBM:
+ *     out = ((b_0 + b_1) + ... + b_{M-1}) * fl32(1/M)     (fp32, node order)
+ *   bufs   HOST array of M DEVICE pointers (1 <= M <= HSADMM_MAX_MASKS), 16-byte aligned
+ *   out    device, n_elems floats, 16-byte aligned; may be one of the inputs
+ * The plan only carries the diagnostics; no table of it is used.
+ * Errors: INVALID_ARGUMENT, UNSUPPORTED, HIP.
+ */
+int hsadmm_average(const hsadmm_plan_t* plan, const float* const* bufs, int32_t M, int64_t n_elems, float* out,
+                   void* hip_stream);
+
+/*
  * Layer-wise squared residual norms (Section 3.4, last paragraph; Algorithm
  * 1, Phase 5), accumulated in fp64 from the fp32 values:
  *     out[0*L + l] = sum over the R replicas of || W_r - Zi ||_F^2   (intra-node primal)
@@ -320,7 +335,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 17
+#define HSADMM_KERNEL_COUNT 18
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

@@ -30,8 +30,9 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_compact", "hsadmm_expand", "hsadmm_strerror", "hsadmm_version",
            "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name",
            "hsadmm_project_frozen", "hsadmm_mask_or", "hsadmm_compact_sum", "hsadmm_node_coefficients",
-           "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals")
-KERNEL_COUNT = 17
+           "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals",
+           "hsadmm_average")
+KERNEL_COUNT = 18
 
 
 class HsadmmError(RuntimeError):
@@ -89,6 +90,8 @@ def load_library():
     lib.hsadmm_project_frozen.restype = ctypes.c_int
     lib.hsadmm_mask_or.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp]
     lib.hsadmm_mask_or.restype = ctypes.c_int
+    lib.hsadmm_average.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, ctypes.c_int64, vp, vp]
+    lib.hsadmm_average.restype = ctypes.c_int
     lib.hsadmm_compact_sum.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hsadmm_compact_sum.restype = ctypes.c_int
     f64p = ctypes.POINTER(ctypes.c_double)
@@ -250,6 +253,17 @@ def hsadmm_mask_or(plan: Plan, masks: Sequence, out, stream=None, check: bool = 
     rc = lib.hsadmm_mask_or(plan.handle, ptrs, M, _ptr(out), _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_mask_or")
+    return rc
+
+
+def hsadmm_average(plan: Plan, bufs: Sequence, n_elems: int, out, stream=None, check: bool = True) -> int:
+    """Eq. (11): out = mean of the M buffers (each n_elems floats)."""
+    lib = load_library()
+    M = len(bufs)
+    ptrs = (ctypes.c_void_p * max(M, 1))(*[_ptr(b) for b in bufs])
+    rc = lib.hsadmm_average(plan.handle, ptrs, M, int(n_elems), _ptr(out), _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_average")
     return rc
 
 

@@ -61,7 +61,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFixup, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFixup, kAverage, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -709,6 +709,26 @@ int hsadmm_dual_inter(const hsadmm_plan_t* p, const float* Zi, const float* Zg, 
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
+int hsadmm_average(const hsadmm_plan_t* p, const float* const* bufs, int32_t M, int64_t n_elems, float* out,
+                   void* hip_stream)
+{
+    if (!p || !bufs || !out || M < 1 || n_elems < 0) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (M > HSADMM_MAX_MASKS) return HSADMM_ERR_UNSUPPORTED;
+    if (!is_aligned(out, 16)) return HSADMM_ERR_INVALID_ARGUMENT;
+    AverageArgs a{};
+    for (int i = 0; i < M; ++i) {
+        if (!bufs[i] || !is_aligned(bufs[i], 16)) return HSADMM_ERR_INVALID_ARGUMENT;
+        a.b[i] = bufs[i];
+    }
+    if (n_elems == 0) return HSADMM_OK;
+    int64_t want = ((n_elems >> 2) + kBlock - 1) / kBlock;      // one quad per thread ...
+    if (want > 16384) want = 16384;                              // ... up to a grid that fills the device many times
+    if (want < 1) want = 1;
+    const hipError_t e = launch(p, kAverage, average_kernel, (unsigned)want, kBlock, static_cast<hipStream_t>(hip_stream),
+                                a, (int)M, 1.0f / (float)M, n_elems, out);
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
 int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* mask, float* dst,
                   void* workspace, size_t workspace_bytes, void* hip_stream)
 {
@@ -801,6 +821,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kChanFinal: return "channel_final";
         case kWFixup: return "weighted_fixup";
         case kBothFixup: return "composite_fixup";
+        case kAverage: return "average";
         default: return "";
     }
 }

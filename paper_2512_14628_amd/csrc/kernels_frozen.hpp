@@ -121,7 +121,8 @@ struct MaskOrArgs {
     const uint8_t* m[HSADMM_MAX_MASKS];
 };
 
-__global__ __launch_bounds__(kBlock) void mask_or_kernel(MaskOrArgs a, int M, int64_t n, uint8_t* __restrict__ out)
+__global__ __launch_bounds__(kBlock) void mask_or_kernel(MaskOrArgs a, int M, int64_t n,
+                                                         uint8_t* out /* may be one of the inputs */)
 {
     const int64_t stride = (int64_t)gridDim.x * kBlock;
     for (int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x; g < n; g += stride) {

@@ -1,4 +1,4 @@
-// hsadmm_project_weighted (full candidate of Eq. (9)) and hsadmm_dual_inter (Eq. (13)).
+// hsadmm_project_weighted (full candidate of Eq. (9)), hsadmm_dual_inter (Eq. (13)) and hsadmm_average (Eq. (11)).
 // Part of the single translation unit built from hsadmm.hip (included there, in order).
 #ifndef KERNELS_WEIGHTED_HPP
 #define KERNELS_WEIGHTED_HPP
@@ -318,6 +318,32 @@ __global__ __launch_bounds__(kBlock) void dual_inter_kernel(const WorkItem* __re
             const float d = Zi[e] - Zg[e];
             Vd[e] = Vd[e] + d;
         }
+    }
+}
+
+// Eq. (11): global consensus z = (1/M) sum_i (z_i + v_i) over M equally long buffers (the nodes' compact
+// pre-transmission buffers): fp32 sum in node order, times fl32(1/M).  Flat grid-stride stream.
+struct AverageArgs {
+    const float* b[HSADMM_MAX_MASKS];
+};
+
+__global__ __launch_bounds__(kBlock) void average_kernel(AverageArgs a, int M, float inv_M, int64_t n,
+                                                         float* out /* may be one of the inputs */)
+{
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    const int64_t quads = n >> 2;
+    for (int64_t q = (int64_t)blockIdx.x * kBlock + threadIdx.x; q < quads; q += stride) {
+        const int64_t e = q << 2;
+        v4f s = ld4(a.b[0] + e);
+        for (int i = 1; i < M; ++i) s = s + ld4(a.b[i] + e);
+        st4(out + e, s * inv_M);
+    }
+    // the last n % 4 elements
+    const int64_t e = (quads << 2) + (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e < n) {
+        float s = a.b[0][e];
+        for (int i = 1; i < M; ++i) s = s + a.b[i][e];
+        out[e] = s * inv_M;
     }
 }
 
