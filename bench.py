@@ -221,11 +221,18 @@ def main():
     if not args.skip_extras:
         # ---- frozen-mask step (Algorithm 1 Phase 3 once the masks are frozen, Section 4.5): the same three calls
         #      with hsadmm_project_frozen in place of hsadmm_project, applying each buffer set's last mask
+        #      A frozen mask does not change between iterations, so its index mappings are derived once per buffer set
+        #      (one hsadmm_compact with the mask) and reused by every later step (NULL masks), as the paper's
+        #      retraining phase reuses its cached index sets and buffer sizes (Section 4.5).
+        for b in sets:
+            pkg.hsadmm_compact(plan, b.Z, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
+
         def frozen_step():
             b = sets[counter[0] % nsets]
             counter[0] += 1
             pkg.hsadmm_project_frozen(plan, b.W, b.U, b.Z, None, b.mask, stream=stream)
-            pkg.hsadmm_compact(plan, b.Z, b.mask, b.packed, b.off, b.kept, b.ws, stream=stream)
+            pkg.hsadmm_compact(plan, b.Z, b.mask if args.compact_rescan else None, b.packed, b.off, b.kept, b.ws,
+                               stream=stream)
             pkg.hsadmm_expand(plan, b.packed, None, b.dst, b.ws, stream=stream)
 
         fsteps = max(1, args.steps // 2)
