@@ -35,10 +35,12 @@ def test_header_symbols_are_all_exported(lib):
 
 
 def _table(rows):
+    rows = [tuple(r) + (0,) * (7 - len(r)) for r in rows]       # k_in defaults to 0
     cols = list(zip(*rows))
     return {"elem_off": np.array(cols[0], np.int64), "c_out": np.array(cols[1], np.int32),
             "c_in": np.array(cols[2], np.int32), "khw": np.array(cols[3], np.int32),
-            "mode": np.array(cols[4], np.int32), "k": np.array(cols[5], np.int32)}
+            "mode": np.array(cols[4], np.int32), "k": np.array(cols[5], np.int32),
+            "k_in": np.array(cols[6], np.int32)}
 
 
 @pytest.mark.parametrize("rows", [
@@ -51,6 +53,10 @@ def _table(rows):
     [(2, 4, 3, 1, 1, 1)],                       # elem_off not a multiple of 4
     [(0, 4, 4, 1, 1, 1), (8, 4, 4, 1, 1, 1)],   # layers overlap
     [(-4, 4, 4, 1, 1, 1)],                      # negative offset
+    [(0, 4, 3, 1, 3, 2, 0)],                    # both constraints: k_in < 1
+    [(0, 4, 3, 1, 3, 2, 4)],                    # both constraints: k_in > c_in
+    [(0, 4, 3, 1, 3, 5, 2)],                    # both constraints: k > c_out
+    [(0, 4, 3, 1, 4, 2)],                       # mode 4 is not a mode of the library (shape groups go through CHANNEL)
 ])
 def test_plan_create_rejects_bad_tables(lib, rows):
     with pytest.raises(pkg.HsadmmError) as e:
@@ -74,6 +80,16 @@ def test_hot_calls_reject_null_plan(lib):
     assert lib.hsadmm_project(None, None, 1, None, None, None, None, None, None, 0, None) == -1
     assert lib.hsadmm_compact(None, None, None, None, None, None, None, 0, None) == -1
     assert lib.hsadmm_expand(None, None, None, None, None, 0, None) == -1
+    assert lib.hsadmm_project_frozen(None, None, 1, None, None, None, None, None) == -1
+    assert lib.hsadmm_mask_or(None, None, 1, None, None) == -1
+    assert lib.hsadmm_average(None, None, 1, 0, None, None) == -1
+    assert lib.hsadmm_dual_inter(None, None, None, None, None) == -1
+    assert lib.hsadmm_compact_sum(None, None, None, None, None, None, None, None, 0, None) == -1
+    assert lib.hsadmm_kernel_timing_enable(None, 1) == -1
+    names = [lib.hsadmm_kernel_name(i).decode() for i in range(binding.KERNEL_COUNT)]
+    assert all(names) and len(set(names)) == len(names) and lib.hsadmm_kernel_name(binding.KERNEL_COUNT) == b""
+    header = open(os.path.join(ROOT, "include", "hsadmm.h")).read()
+    assert int(re.search(r"#define HSADMM_KERNEL_COUNT (\d+)", header).group(1)) == binding.KERNEL_COUNT
 
 
 def test_no_cpu_fallback_in_the_product_package():
