@@ -176,6 +176,17 @@ int hsadmm_mask_or(const hsadmm_plan_t* plan, const uint8_t* const* masks, int32
                    void* hip_stream);
 
 /*
+ * Mask drift (Section 4.5: the masks are frozen once the sparsity pattern has
+ * stopped changing): drift[l] = number of groups of layer l whose kept flag
+ * (byte != 0) differs between the two masks; 0 for a MODE_NONE layer.
+ *   mask_a, mask_b  device, groups_total bytes each
+ *   drift           device, out, L int32
+ * Errors: INVALID_ARGUMENT, HIP.
+ */
+int hsadmm_mask_drift(const hsadmm_plan_t* plan, const uint8_t* mask_a, const uint8_t* mask_b, int32_t* drift,
+                      void* hip_stream);
+
+/*
  * Step (e1), tensor shrinkage: packs the kept slices of `src` into one
  * contiguous dense buffer, layer after layer,
  *     packed[layer_off[l] + (p*|K_in| + q)*khw + t] = src[l][K_out[p]][K_in[q]][t]
@@ -335,7 +346,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 18
+#define HSADMM_KERNEL_COUNT 19
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

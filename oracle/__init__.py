@@ -78,6 +78,8 @@ def _load():
     lib.oracle_residuals.restype = ctypes.c_int
     lib.oracle_average.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.POINTER(f32p), f32p]
     lib.oracle_average.restype = ctypes.c_int
+    lib.oracle_mask_drift.argtypes = [ctypes.c_int32, i32p, i32p, i32p, i32p, u8p, u8p, i32p]
+    lib.oracle_mask_drift.restype = ctypes.c_int
     lib.oracle_mask_or.argtypes = [ctypes.c_int64, ctypes.POINTER(u8p), ctypes.c_int32, u8p]
     lib.oracle_mask_or.restype = ctypes.c_int
     _lib = lib
@@ -254,6 +256,23 @@ def mask_or(masks):
     rc = lib.oracle_mask_or(n, ptrs, len(ms), _p(out, ctypes.c_uint8))
     if rc != 0:
         raise ValueError("oracle_mask_or failed with code %d" % rc)
+    return out
+
+
+def mask_drift(table, mask_a, mask_b):
+    """Section 4.5: per layer, the number of groups whose kept flag differs between the two masks (int32[L])."""
+    lib = _load()
+    t = _cols(table)
+    L = len(t["c_out"])
+    a = np.ascontiguousarray(mask_a, dtype=np.uint8)
+    b = np.ascontiguousarray(mask_b, dtype=np.uint8)
+    assert a.shape == b.shape == (groups_total(t),)
+    out = np.full(L, -1, dtype=np.int32)
+    rc = lib.oracle_mask_drift(L, _p(t["c_out"], ctypes.c_int32), _p(t["c_in"], ctypes.c_int32),
+                               _p(t["khw"], ctypes.c_int32), _p(t["mode"], ctypes.c_int32),
+                               _p(a, ctypes.c_uint8), _p(b, ctypes.c_uint8), _p(out, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError("oracle_mask_drift failed with code %d" % rc)
     return out
 
 

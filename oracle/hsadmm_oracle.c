@@ -447,6 +447,27 @@ int oracle_mask_or(int64_t n_groups_total, const uint8_t *const *masks, int32_t 
 }
 
 /*
+ * Mask drift (Section 4.5, "Mask Freezing and Retraining Phase": the masks are frozen once the sparsity pattern has
+ * stopped changing): per layer, the number of groups whose kept flag differs between two masks (any nonzero byte
+ * counts as kept).  An unconstrained layer keeps all its groups whatever its bytes say, so its drift is 0.
+ */
+int oracle_mask_drift(int32_t L, const int32_t *c_out, const int32_t *c_in, const int32_t *khw, const int32_t *mode,
+                      const uint8_t *a, const uint8_t *b, int32_t *drift)
+{
+    if (L < 1 || !a || !b || !drift) return -1;
+    int64_t gbase = 0;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
+        int32_t d = 0;
+        if (mode[l] != ORACLE_NONE)
+            for (int64_t g = 0; g < G; ++g) d += ((a[gbase + g] != 0) != (b[gbase + g] != 0)) ? 1 : 0;
+        drift[l] = d;
+        gbase += G;
+    }
+    return 0;
+}
+
+/*
  * Weights of the dense node candidate, Eq. (9): with P accelerators per node, M nodes, weight decay
  * lambda and the layer's penalties rho_1, rho_2,
  *     gamma = lambda / M + P rho_1 + rho_2,

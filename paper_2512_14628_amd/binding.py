@@ -31,8 +31,8 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name",
            "hsadmm_project_frozen", "hsadmm_mask_or", "hsadmm_compact_sum", "hsadmm_node_coefficients",
            "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals",
-           "hsadmm_average")
-KERNEL_COUNT = 18
+           "hsadmm_average", "hsadmm_mask_drift")
+KERNEL_COUNT = 19
 
 
 class HsadmmError(RuntimeError):
@@ -90,6 +90,8 @@ def load_library():
     lib.hsadmm_project_frozen.restype = ctypes.c_int
     lib.hsadmm_mask_or.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp]
     lib.hsadmm_mask_or.restype = ctypes.c_int
+    lib.hsadmm_mask_drift.argtypes = [vp, vp, vp, vp, vp]
+    lib.hsadmm_mask_drift.restype = ctypes.c_int
     lib.hsadmm_average.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, ctypes.c_int64, vp, vp]
     lib.hsadmm_average.restype = ctypes.c_int
     lib.hsadmm_compact_sum.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -253,6 +255,14 @@ def hsadmm_mask_or(plan: Plan, masks: Sequence, out, stream=None, check: bool = 
     rc = lib.hsadmm_mask_or(plan.handle, ptrs, M, _ptr(out), _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_mask_or")
+    return rc
+
+
+def hsadmm_mask_drift(plan: Plan, mask_a, mask_b, drift, stream=None, check: bool = True) -> int:
+    """Section 4.5: drift[l] = groups of layer l whose kept flag differs between the two masks."""
+    rc = load_library().hsadmm_mask_drift(plan.handle, _ptr(mask_a), _ptr(mask_b), _ptr(drift), _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_mask_drift")
     return rc
 
 

@@ -61,7 +61,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFixup, kAverage, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFixup, kAverage, kMaskDrift, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -533,6 +533,16 @@ int hsadmm_mask_or(const hsadmm_plan_t* p, const uint8_t* const* masks, int32_t 
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
+int hsadmm_mask_drift(const hsadmm_plan_t* p, const uint8_t* mask_a, const uint8_t* mask_b, int32_t* drift,
+                      void* hip_stream)
+{
+    if (!p || !mask_a || !mask_b || !drift || !is_aligned(drift, 4)) return HSADMM_ERR_INVALID_ARGUMENT;
+    const hipError_t e = launch(p, kMaskDrift, mask_drift_kernel, (unsigned)p->layers.size(), kBlock,
+                                static_cast<hipStream_t>(hip_stream), (const DevLayer*)p->d_layers, mask_a, mask_b,
+                                drift);
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
 static int compact_impl(const hsadmm_plan_t* p, const float* src, const float* src1, bool sum, const uint8_t* mask,
                         float* packed, int64_t* layer_off, int32_t* kept_idx, void* workspace,
                         size_t workspace_bytes, void* hip_stream)
@@ -822,6 +832,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kWFixup: return "weighted_fixup";
         case kBothFixup: return "composite_fixup";
         case kAverage: return "average";
+        case kMaskDrift: return "mask_drift";
         default: return "";
     }
 }

@@ -1,4 +1,4 @@
-// hsadmm_project_frozen (cached mask applied in one pass) and hsadmm_mask_or.
+// hsadmm_project_frozen (cached mask applied in one pass), hsadmm_mask_or and hsadmm_mask_drift.
 // Part of the single translation unit built from hsadmm.hip (included there, in order).
 #ifndef KERNELS_FROZEN_HPP
 #define KERNELS_FROZEN_HPP
@@ -129,6 +129,29 @@ __global__ __launch_bounds__(kBlock) void mask_or_kernel(MaskOrArgs a, int M, in
         unsigned int any = 0;
         for (int i = 0; i < M; ++i) any |= a.m[i][g];
         out[g] = any != 0 ? 1 : 0;
+    }
+}
+
+// Section 4.5 (mask freezing once the pattern is stable): per layer, the number of groups whose kept flag differs
+// between two masks.  One workgroup per layer; an unconstrained layer reports 0.
+__global__ __launch_bounds__(kBlock) void mask_drift_kernel(const DevLayer* __restrict__ layers,
+                                                            const uint8_t* __restrict__ a,
+                                                            const uint8_t* __restrict__ b,
+                                                            int32_t* __restrict__ drift)
+{
+    __shared__ int wsum[kWaves];
+    const DevLayer L = layers[blockIdx.x];
+    int d = 0;
+    if (L.mode != HSADMM_MODE_NONE)
+        for (int g = threadIdx.x; g < L.G; g += kBlock)
+            d += ((a[L.group_base + g] != 0) != (b[L.group_base + g] != 0)) ? 1 : 0;
+    d = wave_sum_i32(d);
+    if ((threadIdx.x & (kWave - 1)) == 0) wsum[threadIdx.x / kWave] = d;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+        for (int w = 0; w < kWaves; ++w) t += wsum[w];
+        drift[blockIdx.x] = t;
     }
 }
 

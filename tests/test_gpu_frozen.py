@@ -102,3 +102,32 @@ def test_frozen_error_codes():
     assert pkg.hsadmm_mask_or(run.plan, [run.dmask] * 65, run.dmask, check=False) == -4
     assert pkg.hsadmm_mask_or(run.plan, [run.dmask, None], run.dmask, check=False) == -1
     run.close()
+
+
+def test_mask_drift_between_two_iterations():
+    """Section 4.5: per-layer count of groups whose kept flag changed; zero drift is the freezing signal."""
+    import paper_2512_14628_amd as pkg
+    from tests.gpu_harness import GpuRun
+    from tests.test_gpu_composite import _shapes_with_both
+    rng = np.random.default_rng(8)
+    wl = wk.custom_workload(_shapes_with_both(rng, 14), R=2, seed=3, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    run = GpuRun(wl, W, U)
+    run.project()
+    m1 = run.dmask.clone()
+    run.project()                                   # second iteration: U has moved on
+    drift = torch.full((len(wl.layers),), -7, dtype=torch.int32, device=run.dev)
+    pkg.hsadmm_mask_drift(run.plan, m1, run.dmask, drift)
+    torch.cuda.synchronize()
+    ref = oracle.mask_drift(wl.table(), m1.cpu().numpy(), run.dmask.cpu().numpy())
+    assert np.array_equal(drift.cpu().numpy(), ref)
+    pkg.hsadmm_mask_drift(run.plan, m1, m1 * 5, drift)
+    torch.cuda.synchronize()
+    assert not drift.cpu().numpy().any()
+    x = torch.from_numpy((rng.random(wl.groups_total) < 0.5).astype(np.uint8)).to(run.dev)
+    y = torch.from_numpy(((rng.random(wl.groups_total) < 0.5) * 255).astype(np.uint8)).to(run.dev)
+    pkg.hsadmm_mask_drift(run.plan, x, y, drift)
+    torch.cuda.synchronize()
+    assert np.array_equal(drift.cpu().numpy(), oracle.mask_drift(wl.table(), x.cpu().numpy(), y.cpu().numpy()))
+    assert pkg.hsadmm_mask_drift(run.plan, x, None, drift, check=False) == -1
+    run.close()

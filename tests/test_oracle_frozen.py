@@ -98,3 +98,25 @@ def test_mask_union_is_the_logical_or():
     for l in wl.layers:
         c = int(u[l.group_base:l.group_base + l.groups].sum())
         assert l.k <= c <= min(2 * l.k, l.groups)
+
+
+def test_mask_drift_counts_changed_groups_per_layer():
+    """Section 4.5: stability of the sparsity pattern = no group changes its kept flag between iterations."""
+    wl = wk.custom_workload([(6, 2, 1, wk.MODE_FILTER, 3), (2, 5, 4, wk.MODE_CHANNEL, 2), (3, 3, 1, wk.MODE_NONE, 3),
+                             (4, 3, 1, wk.MODE_BOTH, 2, 2)], R=1)
+    a = np.array([1, 1, 1, 0, 0, 0] + [1, 0, 1, 0, 0] + [0, 0, 0] + [1, 1, 0, 0, 1, 1, 0], np.uint8)
+    b = np.array([1, 0, 1, 9, 0, 0] + [0, 1, 1, 0, 0] + [1, 1, 1] + [1, 1, 0, 0, 0, 1, 7], np.uint8)
+    assert oracle.mask_drift(wl.table(), a, b).tolist() == [2, 2, 0, 2]
+    assert oracle.mask_drift(wl.table(), a, a * 200).tolist() == [0, 0, 0, 0]     # any nonzero byte is "kept"
+    rng = np.random.default_rng(2)
+    wl2 = wk.custom_workload(random_table(rng, 9), R=1)
+    x = (rng.random(wl2.groups_total) < 0.5).astype(np.uint8)
+    y = (rng.random(wl2.groups_total) < 0.5).astype(np.uint8) * 3
+    d = oracle.mask_drift(wl2.table(), x, y)
+    for l, dl in zip(wl2.layers, d):
+        sl = slice(l.group_base, l.group_base + l.groups)
+        assert dl == (0 if l.mode == wk.MODE_NONE else int(np.count_nonzero((x[sl] != 0) ^ (y[sl] != 0))))
+    # two successive projections of the same inputs select the same groups: no drift
+    W, U = wk.generate(wl2)
+    m = oracle.project(wl2.table(), W, U)["mask"]
+    assert not oracle.mask_drift(wl2.table(), m, m).any()

@@ -74,6 +74,8 @@ MUTATIONS = [
     ("composite_stage_tie_rule", "(key[h] == key[g] && h < g)", "(key[h] == key[g] && h > g)"),
     ("composite_stage_channel_transposed", "x[(o * ci + g) * s + t]", "x[(g * co + o) * s + t]"),
     ("composite_stage_zeroes_wrong_group", "(channel ? (e / s) % ci : e / (ci * s));", "(channel ? e % ci : e / (ci * s));"),
+    ("drift_counts_raw_bytes", "d += ((a[gbase + g] != 0) != (b[gbase + g] != 0)) ? 1 : 0;", "d += (a[gbase + g] != b[gbase + g]) ? 1 : 0;"),
+    ("drift_counts_unconstrained_layers", "if (mode[l] != ORACLE_NONE)\n            for (int64_t g = 0; g < G; ++g) d +=", "if (1)\n            for (int64_t g = 0; g < G; ++g) d +="),
     ("average_by_division", "out[e] = acc * inv_M;", "out[e] = acc / (float)M;"),
     ("average_drops_last_node", "for (int32_t i = 1; i < M; ++i) acc = acc + bufs[i][e];", "for (int32_t i = 1; i < M - 1; ++i) acc = acc + bufs[i][e];"),
     ("average_sums_in_double", "float acc = bufs[0][e];\n        for (int32_t i = 1; i < M; ++i) acc = acc + bufs[i][e];", "double acc = bufs[0][e];\n        for (int32_t i = 1; i < M; ++i) acc = acc + bufs[i][e];"),
@@ -110,6 +112,7 @@ PIN_FUNCS = [
     lambda: [fpins.test_frozen_against_the_printed_formula_in_numpy(s) for s in range(2)],
     fpins.test_all_ones_mask_and_unconstrained_layers,
     fpins.test_mask_union_is_the_logical_or,
+    fpins.test_mask_drift_counts_changed_groups_per_layer,
     wpins.test_coefficients_of_eq_9,
     wpins.test_handworked_weighted_projection,
     lambda: [wpins.test_weights_one_and_zero_give_the_base_projection(s) for s in range(2)],
@@ -149,7 +152,7 @@ def test_a_planted_mistake_in_the_oracle_fails_a_pin(name, old, new, tmp_path, m
     lib = ctypes.CDLL(str(so_file))
     for fn in ("oracle_project", "oracle_compact", "oracle_expand", "oracle_set_threads", "oracle_get_threads",
                "oracle_project_frozen", "oracle_mask_or", "oracle_node_coefficients", "oracle_project_weighted",
-               "oracle_dual_inter", "oracle_add_arenas", "oracle_residuals", "oracle_average"):
+               "oracle_dual_inter", "oracle_add_arenas", "oracle_residuals", "oracle_average", "oracle_mask_drift"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(oracle, "_lib", lib)
