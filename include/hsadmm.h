@@ -39,6 +39,10 @@
  * offsets) from the call that derives them to the calls that reuse them, so
  * calls that share a workspace must be ordered on one stream.
  *
+ * Device.  A plan belongs to the HIP device that was current in
+ * hsadmm_plan_create; every later call on it must be made with that device
+ * current (INVALID_ARGUMENT otherwise) and with buffers of that device.
+ *
  * Errors.  Every call returns HSADMM_OK (0) or a negative code.  Arguments
  * are validated before anything is enqueued, so a call that returns an
  * argument error has had no effect on device memory.  No exceptions cross

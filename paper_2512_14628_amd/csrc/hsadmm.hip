@@ -169,6 +169,13 @@ void add_tile_items(std::vector<WorkItem>& out, int layer, const DevLayer& d)
 
 bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// The plan's tables live on the device that was current when it was created; launches go to the current device.
+bool on_plan_device(const hsadmm_plan* p)
+{
+    int d = -1;
+    return hipGetDevice(&d) == hipSuccess && d == p->device;
+}
+
 // Launches `kernel` on stream s.  With timing enabled the launch carries a start and a stop event
 // that take the kernel's own begin / end timestamps (no extra work is put on the stream).
 template <typename... KArgs, typename... Args>
@@ -439,6 +446,7 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
                    void* hip_stream)
 {
     if (!p || !W_replicas || !U || !Z || !mask || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
     if (!is_aligned(U, 16) || !is_aligned(Z, 16) || (Wbar && !is_aligned(Wbar, 16)) ||
         (sqnorm && !is_aligned(sqnorm, 8)) || !is_aligned(workspace, 256))
@@ -494,6 +502,7 @@ int hsadmm_project_frozen(const hsadmm_plan_t* p, const float* const* W_replicas
                           float* Wbar, const uint8_t* mask, void* hip_stream)
 {
     if (!p || !W_replicas || !U || !Z || !mask || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
     if (!is_aligned(U, 16) || !is_aligned(Z, 16) || (Wbar && !is_aligned(Wbar, 16))) return HSADMM_ERR_INVALID_ARGUMENT;
     for (int r = 0; r < R; ++r)
@@ -518,6 +527,7 @@ int hsadmm_project_frozen(const hsadmm_plan_t* p, const float* const* W_replicas
 int hsadmm_mask_or(const hsadmm_plan_t* p, const uint8_t* const* masks, int32_t M, uint8_t* out, void* hip_stream)
 {
     if (!p || !masks || !out || M < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (M > HSADMM_MAX_MASKS) return HSADMM_ERR_UNSUPPORTED;
     MaskOrArgs a{};
     for (int i = 0; i < M; ++i) {
@@ -537,6 +547,7 @@ int hsadmm_mask_drift(const hsadmm_plan_t* p, const uint8_t* mask_a, const uint8
                       void* hip_stream)
 {
     if (!p || !mask_a || !mask_b || !drift || !is_aligned(drift, 4)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     const hipError_t e = launch(p, kMaskDrift, mask_drift_kernel, (unsigned)p->layers.size(), kBlock,
                                 static_cast<hipStream_t>(hip_stream), (const DevLayer*)p->d_layers, mask_a, mask_b,
                                 drift);
@@ -549,6 +560,7 @@ static int compact_impl(const hsadmm_plan_t* p, const float* src, const float* s
 {
     if (!p || !src || (sum && !src1) || !packed || !layer_off || !kept_idx || !workspace)
         return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (!is_aligned(src, 16) || (sum && !is_aligned(src1, 16)) || !is_aligned(packed, 16) ||
         !is_aligned(layer_off, 8) || !is_aligned(kept_idx, 4) || !is_aligned(workspace, 256))
         return HSADMM_ERR_INVALID_ARGUMENT;
@@ -610,6 +622,7 @@ int hsadmm_node_coefficients(const double* rho1, const double* rho2, int32_t L, 
 int hsadmm_plan_set_node_weights(hsadmm_plan_t* p, const float* a, const float* b)
 {
     if (!p || !a || !b) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     const size_t L = p->layers.size();
     std::vector<float> ab;
     try {
@@ -628,6 +641,7 @@ int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replic
                             void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!p || !W_replicas || !U || !Zg || !Vd || !Z || !mask || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
     if (!is_aligned(U, 16) || !is_aligned(Z, 16) || !is_aligned(Zg, 16) || !is_aligned(Vd, 16) ||
         (Wbar && !is_aligned(Wbar, 16)) || (sqnorm && !is_aligned(sqnorm, 8)) || !is_aligned(workspace, 256))
@@ -682,6 +696,7 @@ int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int
                      size_t workspace_bytes, void* hip_stream)
 {
     if (!p || !W_replicas || !Zi || !out || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
     if (!is_aligned(Zi, 16) || (Zi_prev && !is_aligned(Zi_prev, 16)) || (Zg && !is_aligned(Zg, 16)) ||
         (Zg_prev && !is_aligned(Zg_prev, 16)) || !is_aligned(out, 8) || !is_aligned(workspace, 256))
@@ -713,6 +728,7 @@ int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int
 int hsadmm_dual_inter(const hsadmm_plan_t* p, const float* Zi, const float* Zg, float* Vd, void* hip_stream)
 {
     if (!p || !Zi || !Zg || !Vd) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (!is_aligned(Zi, 16) || !is_aligned(Zg, 16) || !is_aligned(Vd, 16)) return HSADMM_ERR_INVALID_ARGUMENT;
     const hipError_t e = launch(p, kDualInter, dual_inter_kernel, (unsigned)p->items_rows.size(), kBlock,
                                 static_cast<hipStream_t>(hip_stream), (const WorkItem*)p->d_items_rows, Zi, Zg, Vd);
@@ -723,6 +739,7 @@ int hsadmm_average(const hsadmm_plan_t* p, const float* const* bufs, int32_t M, 
                    void* hip_stream)
 {
     if (!p || !bufs || !out || M < 1 || n_elems < 0) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (M > HSADMM_MAX_MASKS) return HSADMM_ERR_UNSUPPORTED;
     if (!is_aligned(out, 16)) return HSADMM_ERR_INVALID_ARGUMENT;
     AverageArgs a{};
@@ -743,6 +760,7 @@ int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* ma
                   void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!p || !packed || !dst || !workspace) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (!is_aligned(packed, 16) || !is_aligned(dst, 16) || !is_aligned(workspace, 256))
         return HSADMM_ERR_INVALID_ARGUMENT;
     if (workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;

@@ -118,7 +118,6 @@ def check_against_oracle(wl, got, ref, refc, check_float_tol=True):
     L = len(wl.layers)
     for li in range(L):
         a = int(refc["layer_off"][li])
-        size = wl.layers[li].n if wl.layers[li].mode == 0 else None
         b = int(refc["layer_off"][li + 1])
         # compare the meaningful part of the segment (alignment padding is unspecified)
         seg_ref = refc["packed"][a:b]
