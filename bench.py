@@ -259,7 +259,7 @@ def main():
                   "project_frozen_frac": round(bytes_["project"] / (f_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
 
         # ---- full node update (Eq. (9) with the rho_2 (z - v) term) + Phase 4 on one node:
-        #      hsadmm_project_weighted, hsadmm_compact_sum (c = z_i + v_i), hsadmm_expand, hsadmm_dual_inter (Eq. (13))
+        #      hsadmm_project_weighted, hsadmm_compact_sum (c = z_i + v_i), hsadmm_expand_dual (z and Eq. (13))
         L = len(wl.layers)
         wa, wb_ = pkg.hsadmm_node_coefficients([1.5e-3] * L, [1.5e-4] * L, 1e-4, 16, wl.R)   # the paper's initial penalties
         pkg.hsadmm_plan_set_node_weights(plan, wa, wb_)
@@ -273,8 +273,8 @@ def main():
             pkg.hsadmm_project_weighted(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, None, b.ws, stream=stream)
             pkg.hsadmm_compact_sum(plan, b.Z, b.Vd, b.mask if args.compact_rescan else None, b.packed, b.off, b.kept,
                                    b.ws, stream=stream)
-            pkg.hsadmm_expand(plan, b.packed, None, b.dst, b.ws, stream=stream)
-            pkg.hsadmm_dual_inter(plan, b.Z, b.dst, b.Vd, stream=stream)
+            # decompression and the inter-node dual update of Eq. (13) in one pass
+            pkg.hsadmm_expand_dual(plan, b.packed, None, b.dst, b.Z, b.Vd, b.ws, stream=stream)
 
         wsteps = max(1, args.steps // 4)
         for _ in range(3):
@@ -312,7 +312,11 @@ def main():
         residuals = {"us_per_call": round(r_us, 2), "algorithmic_bytes": r_bytes,
                      "GBps": round(r_bytes / (r_us * 1e-6) / 1e9, 1),
                      "hbm_frac": round(r_bytes / (r_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
-        w_bytes = 4 * wl.n_total * (wl.R + 10) + 16 * nk
+        # what the method must move: project_weighted reads R replicas, U, z, v and writes Z, U (R + 5 arenas);
+        # compact_sum reads the kept parts of Z and v and writes packed (12 n_kept); expand + Eq. (13) read packed
+        # (4 n_kept) and z_i, v and write z, v (4 arenas); z is produced and consumed in the same pass, so it is
+        # not counted as read again
+        w_bytes = 4 * wl.n_total * (wl.R + 9) + 16 * nk
         weighted = {"ms_per_step": round(1e3 * w_elapsed, 4),
                     "algorithmic_bytes_per_step": w_bytes,
                     "value_GBps": round(w_bytes / w_elapsed / 1e9, 1),

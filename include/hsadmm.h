@@ -331,6 +331,20 @@ int hsadmm_residuals(const hsadmm_plan_t* plan, const float* const* W_replicas, 
 int hsadmm_expand(const hsadmm_plan_t* plan, const float* packed, const uint8_t* mask,
                   float* dst, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * hsadmm_expand with the inter-node dual update of Eq. (13) applied in the
+ * same pass (Algorithm 1, Phase 4: decompress, then v_i <- v_i + z_i - z):
+ * dst receives the expanded tensor, the new global consensus z, exactly as
+ * hsadmm_expand writes it, and Vd <- Vd + (Zi - z) on every layer, exactly
+ * as hsadmm_dual_inter computes it; z is not read back from memory.
+ *   Zi   device, in: the node's projected consensus (full-layout arena)
+ *   Vd   device, in/out: the node's inter-node dual (full-layout arena)
+ * dst, Zi and Vd must not alias each other; 16-byte aligned.  Other arguments
+ * and errors as for hsadmm_expand.
+ */
+int hsadmm_expand_dual(const hsadmm_plan_t* plan, const float* packed, const uint8_t* mask, float* dst,
+                       const float* Zi, float* Vd, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static string for an error code (never NULL). */
 const char* hsadmm_strerror(int code);
 

@@ -31,7 +31,7 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name",
            "hsadmm_project_frozen", "hsadmm_mask_or", "hsadmm_compact_sum", "hsadmm_node_coefficients",
            "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals",
-           "hsadmm_average", "hsadmm_mask_drift")
+           "hsadmm_average", "hsadmm_mask_drift", "hsadmm_expand_dual")
 KERNEL_COUNT = 19
 
 
@@ -90,6 +90,8 @@ def load_library():
     lib.hsadmm_project_frozen.restype = ctypes.c_int
     lib.hsadmm_mask_or.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp]
     lib.hsadmm_mask_or.restype = ctypes.c_int
+    lib.hsadmm_expand_dual.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_expand_dual.restype = ctypes.c_int
     lib.hsadmm_mask_drift.argtypes = [vp, vp, vp, vp, vp]
     lib.hsadmm_mask_drift.restype = ctypes.c_int
     lib.hsadmm_average.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, ctypes.c_int64, vp, vp]
@@ -366,4 +368,16 @@ def hsadmm_expand(plan: Plan, packed, mask, dst, workspace, stream=None,
                            _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_expand")
+    return rc
+
+
+def hsadmm_expand_dual(plan: Plan, packed, mask, dst, Zi, Vd, workspace, stream=None,
+                       workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    """hsadmm_expand with Vd <- Vd + (Zi - dst) (Eq. (13)) applied in the same pass."""
+    lib = load_library()
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_expand_dual(plan.handle, _ptr(packed), _ptr(mask), _ptr(dst), _ptr(Zi), _ptr(Vd), _ptr(workspace),
+                                wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_expand_dual")
     return rc

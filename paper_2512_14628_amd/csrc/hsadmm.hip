@@ -756,12 +756,13 @@ int hsadmm_average(const hsadmm_plan_t* p, const float* const* bufs, int32_t M, 
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
-int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* mask, float* dst,
-                  void* workspace, size_t workspace_bytes, void* hip_stream)
+static int expand_impl(const hsadmm_plan_t* p, const float* packed, const uint8_t* mask, float* dst, const float* Zi,
+                       float* Vd, bool dual, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    if (!p || !packed || !dst || !workspace) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!p || !packed || !dst || !workspace || (dual && (!Zi || !Vd))) return HSADMM_ERR_INVALID_ARGUMENT;
     if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
-    if (!is_aligned(packed, 16) || !is_aligned(dst, 16) || !is_aligned(workspace, 256))
+    if (!is_aligned(packed, 16) || !is_aligned(dst, 16) || !is_aligned(workspace, 256) ||
+        (dual && (!is_aligned(Zi, 16) || !is_aligned(Vd, 16))))
         return HSADMM_ERR_INVALID_ARGUMENT;
     if (workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -770,13 +771,28 @@ int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* ma
     if (mask) {
         const int rc = run_scan(p, mask, ws, s);
         if (rc != HSADMM_OK) return rc;
-    }   // else: the positions and offsets the last hsadmm_compact left in this workspace are used
-    const hipError_t e = launch(p, kScatter, expand_scatter, (unsigned)p->items_rows.size(), kBlock, s,
-                                (const WorkItem*)p->d_items_rows, packed,
-                                reinterpret_cast<const int32_t*>(ws + p->ws.pos),
-                                reinterpret_cast<const int32_t*>(ws + p->ws.cnt), (int)p->layers.size(), lo, dst);
-    if (e != hipSuccess) return HSADMM_ERR_HIP;
-    return HSADMM_OK;
+    }   // else: the index mappings already held in this workspace are used
+    const int32_t* pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
+    const int32_t* cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
+    const hipError_t e = dual
+        ? launch(p, kScatter, expand_scatter<true>, (unsigned)p->items_rows.size(), kBlock, s,
+                 (const WorkItem*)p->d_items_rows, packed, pos, cnt, (int)p->layers.size(), lo, dst, Zi, Vd)
+        : launch(p, kScatter, expand_scatter<false>, (unsigned)p->items_rows.size(), kBlock, s,
+                 (const WorkItem*)p->d_items_rows, packed, pos, cnt, (int)p->layers.size(), lo, dst,
+                 (const float*)nullptr, (float*)nullptr);
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
+int hsadmm_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* mask, float* dst,
+                  void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return expand_impl(p, packed, mask, dst, nullptr, nullptr, false, workspace, workspace_bytes, hip_stream);
+}
+
+int hsadmm_expand_dual(const hsadmm_plan_t* p, const float* packed, const uint8_t* mask, float* dst, const float* Zi,
+                       float* Vd, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return expand_impl(p, packed, mask, dst, Zi, Vd, true, workspace, workspace_bytes, hip_stream);
 }
 
 const char* hsadmm_strerror(int code)

@@ -285,13 +285,32 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
 
 // ------------------------------------------------------------------ expansion (zero fill + scatter)
 
+// DUAL: the expanded tensor is the new global consensus z, and the inter-node dual update of Eq. (13),
+// Vd <- Vd + (Zi - z), is applied in the same pass (z is not read back from memory).
+template <bool DUAL>
 __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restrict__ items,
                                                          const float* __restrict__ packed,
                                                          const int32_t* __restrict__ pos,
                                                          const int32_t* __restrict__ cnt, int n_layers,
                                                          const int64_t* __restrict__ layer_off,
-                                                         float* __restrict__ dst)
+                                                         float* __restrict__ dst,
+                                                         const float* __restrict__ Zi, float* __restrict__ Vd)
 {
+    // stores 4 (or 1) elements of z at arena element e and, with DUAL, updates Vd there
+    auto put4 = [&](int64_t e, const v4f& z) {
+        st4(dst + e, z);
+        if (DUAL) {
+            const v4f d = ld4(Zi + e) - z;
+            st4(Vd + e, ld4(Vd + e) + d);
+        }
+    };
+    auto put1 = [&](int64_t e, float z) {
+        dst[e] = z;
+        if (DUAL) {
+            const float d = Zi[e] - z;
+            Vd[e] = Vd[e] + d;
+        }
+    };
     const WorkItem it = items[blockIdx.x];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
@@ -305,15 +324,15 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
         const int j = threadIdx.x - sub * lpr;
         for (int rr = sub; rr < it.nr; rr += rows_at_once) {
             const int p = pos[it.g0 + rr];
-            float* d = dst + it.base + (int64_t)rr * row_len;
+            const int64_t d = it.base + (int64_t)rr * row_len;
             const float* s = in + (int64_t)(p < 0 ? 0 : p) * row_len;
             if (item_vec(it)) {
                 const int nchunk = row_len >> 2;
-                if (p >= 0) for (int c = j; c < nchunk; c += lpr) st4(d + 4 * c, ld4u(s + 4 * c));
-                else for (int c = j; c < nchunk; c += lpr) st4(d + 4 * c, zero4);
+                if (p >= 0) for (int c = j; c < nchunk; c += lpr) put4(d + 4 * c, ld4u(s + 4 * c));
+                else for (int c = j; c < nchunk; c += lpr) put4(d + 4 * c, zero4);
             } else {
-                if (p >= 0) for (int c = j; c < row_len; c += lpr) d[c] = s[c];
-                else for (int c = j; c < row_len; c += lpr) d[c] = 0.f;
+                if (p >= 0) for (int c = j; c < row_len; c += lpr) put1(d + c, s[c]);
+                else for (int c = j; c < row_len; c += lpr) put1(d + c, 0.f);
             }
         }
     } else {
@@ -364,7 +383,7 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
                 }
 #pragma unroll
                 for (int u = 0; u < kRows; ++u)
-                    if (live[u]) st4(dst + it.base + (int64_t)(rr0 + u * kWaves) * row_len + c, v[u]);
+                    if (live[u]) put4(it.base + (int64_t)(rr0 + u * kWaves) * row_len + c, v[u]);
             }
             for (int c = (quads << 2) + lane; c < row_len; c += kWave) {
                 const int ch = div(c);
@@ -373,7 +392,7 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
 #pragma unroll
                 for (int u = 0; u < kRows; ++u)
                     if (live[u])
-                        dst[it.base + (int64_t)(rr0 + u * kWaves) * row_len + c] = (prow[u] >= 0 && pc >= 0) ? srow[u][pc] : 0.f;
+                        put1(it.base + (int64_t)(rr0 + u * kWaves) * row_len + c, (prow[u] >= 0 && pc >= 0) ? srow[u][pc] : 0.f);
             }
         }
     }

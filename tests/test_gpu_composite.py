@@ -132,7 +132,7 @@ def test_composite_weighted_step(R):
     L = len(wl.layers)
     a = rng.uniform(0.3, 1.0, L).astype(np.float32)
     b = rng.uniform(0.0, 0.7, L).astype(np.float32)
-    _phase4_chain(wl, W, U, a, b, rng, want_wbar=(R % 2 == 0), want_sqnorm=(R != 4))
+    _phase4_chain(wl, W, U, a, b, rng, want_wbar=(R % 2 == 0), want_sqnorm=(R != 4), fused_dual=(R in (2, 7)))
 
 
 def test_composite_arbitrary_source_and_mask_and_cached_expand():

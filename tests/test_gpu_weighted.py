@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-def _phase4_chain(wl, W, U, a, b, rng, want_wbar=True, want_sqnorm=True):
+def _phase4_chain(wl, W, U, a, b, rng, want_wbar=True, want_sqnorm=True, fused_dual=False):
     import paper_2512_14628_amd as pkg
     from tests.gpu_harness import GpuRun, bits, min_relative_gap
     t = wl.table()
@@ -29,8 +29,11 @@ def _phase4_chain(wl, W, U, a, b, rng, want_wbar=True, want_sqnorm=True):
     pkg.hsadmm_plan_set_node_weights(run.plan, a, b)
     pkg.hsadmm_project_weighted(run.plan, run.dW, run.dU, dZg, dVd, run.dZ, run.dWbar, run.dmask, run.dkey, run.ws)
     pkg.hsadmm_compact_sum(run.plan, run.dZ, dVd, run.dmask, run.dpacked, run.doff, run.dkept, run.ws)
-    pkg.hsadmm_expand(run.plan, run.dpacked, None, run.ddst, run.ws)
-    pkg.hsadmm_dual_inter(run.plan, run.dZ, run.ddst, dVd)
+    if fused_dual:
+        pkg.hsadmm_expand_dual(run.plan, run.dpacked, None, run.ddst, run.dZ, dVd, run.ws)
+    else:
+        pkg.hsadmm_expand(run.plan, run.dpacked, None, run.ddst, run.ws)
+        pkg.hsadmm_dual_inter(run.plan, run.dZ, run.ddst, dVd)
     got = run.outputs()
     gv = dVd.cpu().numpy()
     assert np.array_equal(got["mask"], ref["mask"])
@@ -62,6 +65,7 @@ def test_weighted_step_on_named_workloads(name):
     # the paper's initial penalties (Section 5.1): rho_1 = 1.5e-3, rho_2 = 1.5e-4, weight decay 1e-4, 16 nodes
     a, b = oracle.node_coefficients([1.5e-3] * L, [1.5e-4] * L, 1e-4, 16, wl.R)
     _phase4_chain(wl, W, U, a, b, np.random.default_rng(1))
+    _phase4_chain(wl, W, U, a, b, np.random.default_rng(1), fused_dual=True)
 
 
 @pytest.mark.parametrize("R", [1, 2, 3, 4, 7, 8])
@@ -73,7 +77,7 @@ def test_weighted_ragged_shapes_layerwise_weights(R):
     L = len(wl.layers)
     a = rng.uniform(0.3, 1.0, L).astype(np.float32)
     b = rng.uniform(0.0, 0.7, L).astype(np.float32)
-    _phase4_chain(wl, W, U, a, b, rng, want_wbar=(R % 2 == 0), want_sqnorm=(R % 3 != 0))
+    _phase4_chain(wl, W, U, a, b, rng, want_wbar=(R % 2 == 0), want_sqnorm=(R % 3 != 0), fused_dual=(R % 2 == 1))
 
 
 def test_default_weights_reproduce_the_base_projection():
@@ -108,6 +112,9 @@ def test_weighted_error_codes():
     assert pkg.hsadmm_compact_sum(r.plan, r.dZ, None, r.dmask, r.dpacked, r.doff, r.dkept, r.ws, check=False) == -1
     assert pkg.hsadmm_dual_inter(r.plan, r.dZ, None, z, check=False) == -1
     assert pkg.hsadmm_dual_inter(r.plan, r.dZ, z[1:], z, check=False) == -1
+    assert pkg.hsadmm_expand_dual(r.plan, r.dpacked, r.dmask, r.ddst, None, z, r.ws, check=False) == -1
+    assert pkg.hsadmm_expand_dual(r.plan, r.dpacked, r.dmask, r.ddst, r.dZ, z[1:], r.ws, check=False) == -1
+    assert pkg.hsadmm_expand_dual(r.plan, r.dpacked, r.dmask, r.ddst, r.dZ, z, r.ws[:256], check=False) == -2
     with pytest.raises(ValueError):
         pkg.hsadmm_plan_set_node_weights(r.plan, [1.0], [0.0])
     r.close()
