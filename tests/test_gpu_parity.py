@@ -478,3 +478,11 @@ def test_a_captured_graph_replays_the_step():
             assert float(scratch.sum().item()) == float((it + 1) * (1 << 20))
         run.close()
         eager.close()
+
+
+def test_plans_with_a_single_kind_of_layer():
+    """Plans whose optional kernels have nothing to do: only unconstrained layers, only one CHANNEL layer, only one
+    layer under both constraints."""
+    for shapes in ([(6, 5, 4, wk.MODE_NONE, 6), (3, 3, 1, wk.MODE_NONE, 3)], [(40, 30, 9, wk.MODE_CHANNEL, 7)],
+                   [(40, 30, 9, wk.MODE_BOTH, 11, 7)], [(40, 30, 9, wk.MODE_FILTER, 11)]):
+        _run(wk.custom_workload(shapes, R=2, seed=5, sigma_replica=0.03), determinism=True)
