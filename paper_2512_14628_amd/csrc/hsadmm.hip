@@ -143,18 +143,19 @@ void add_row_items(std::vector<WorkItem>& out, int layer, const DevLayer& d, int
     }
 }
 
-void add_tile_items(std::vector<WorkItem>& out, int layer, const DevLayer& d)
+// Tiles of (rows_per_block rows) x (one column strip); d.n_rowblocks must have been set for the same block height.
+void add_tile_items(std::vector<WorkItem>& out, int layer, const DevLayer& d, int rows_per_block)
 {
     const bool vec = (d.row_len % 4) == 0;
     const int strip_cols = kWave * (vec ? 4 : 1);
     const int nstrips = (d.row_len + strip_cols - 1) / strip_cols;
-    for (int r0 = 0; r0 < d.c_out; r0 += kChanRows) {
+    for (int r0 = 0; r0 < d.c_out; r0 += rows_per_block) {
         for (int s = 0; s < nstrips; ++s) {
             WorkItem it{};
             it.base = d.elem_off + (int64_t)r0 * d.row_len;
-            it.aux = d.colpart_off + (int64_t)(r0 / kChanRows) * d.row_len;
+            it.aux = d.colpart_off + (int64_t)(r0 / rows_per_block) * d.row_len;
             it.g0 = d.group_base;
-            it.nr = (d.c_out - r0) < kChanRows ? (d.c_out - r0) : kChanRows;
+            it.nr = (d.c_out - r0) < rows_per_block ? (d.c_out - r0) : rows_per_block;
             it.row_len = d.row_len;
             it.lpr = kWave;
             it.flags = HSADMM_MODE_CHANNEL | (vec ? 4 : 0);
@@ -301,7 +302,8 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             d.seg0 = seg;
             d.group_base = (int32_t)gb;
             d.row_len = x.c_in * x.khw;
-            d.n_rowblocks = (x.c_out + kChanRows - 1) / kChanRows;
+            const int tile_rows = both ? kBothRows : kChanRows;
+            d.n_rowblocks = (x.c_out + tile_rows - 1) / tile_rows;
             d.colpart_off = cp;
             if (x.mode == HSADMM_MODE_CHANNEL) d.unit = (int64_t)x.c_out * x.khw;
             else if (x.mode == HSADMM_MODE_FILTER) d.unit = d.row_len;
@@ -321,8 +323,8 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             add_row_items(p->items_rows, l, d, x.mode);
             d.rows_items = (int32_t)p->items_rows.size() - d.rows_item0;
             if (x.mode == HSADMM_MODE_CHANNEL) {
-                add_tile_items(p->items_proj, l, d);
-                add_tile_items(p->items_wfinal, l, d);
+                add_tile_items(p->items_proj, l, d, kChanRows);
+                add_tile_items(p->items_wfinal, l, d, kChanRows);
                 add_row_items(p->items_chan, l, d, x.mode);
             } else {
                 add_row_items(p->items_proj, l, d, x.mode);
@@ -333,7 +335,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
                 }
             }
             if (both) {
-                add_tile_items(p->items_both, l, d);
+                add_tile_items(p->items_both, l, d, kBothRows);
                 p->both_layers.push_back(l);
             }
             p->dev_layers.push_back(d);

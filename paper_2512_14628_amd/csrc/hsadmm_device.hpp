@@ -15,7 +15,8 @@ constexpr int kScanBlock = 1024;            // select_topk and scan_mask
 constexpr int kScanWaves = kScanBlock / kWave;
 constexpr int kTileElems = 2048;                // target elements per work item
 constexpr int kWideRow = 2048;                  // rows at least this long are shared by the whole workgroup
-constexpr int kChanRows = 32;               // CHANNEL tiles: rows per row block
+constexpr int kChanRows = 64;               // CHANNEL tiles: rows per row block
+constexpr int kBothRows = 64;               // composite_colsums tiles: rows per row block
 constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
 constexpr int kVersion = 140;
 
@@ -29,7 +30,7 @@ struct DevLayer {
                             // BOTH: khw, the layer packs K_out * K_in * khw elements)
     int32_t c_out, c_in, khw, mode, k;
     int32_t G, group_base, row_len;   // G: groups in mask / key (BOTH: c_out filters, then c_in channels)
-    int32_t n_rowblocks;    // CHANNEL, BOTH: ceil(c_out / kChanRows)
+    int32_t n_rowblocks;    // CHANNEL: ceil(c_out / kChanRows); BOTH: ceil(c_out / kBothRows)
     int32_t rows_item0;     // first of this layer's row items (compact / expand / residual kernels)
     int32_t rows_items;     // number of them
     int32_t k_in;           // BOTH: channels kept
