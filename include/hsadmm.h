@@ -11,6 +11,10 @@
  *   (d) dual update U <- U + (Wbar - Z)                    Eq. (12)
  *   (e) tensor shrinkage / recovery of the kept groups     Section 4.4.1 Eq. (15); Section 4.4.3
  *
+ * and, around it: the frozen-mask branch and the mask union (Section 4.5, Eq. (14)), the full node
+ * candidate with its rho_2 term, the inter-node dual update and the mean of the nodes' compact
+ * buffers (Eq. (9), (13), (11)), the residual norms (Section 3.4) and the mask drift (Section 4.5).
+ *
  * Data layout.  A layer is the row-major fp32 array W[c_out][c_in][khw]
  * (Section 2, first paragraph; khw = K_H*K_W, 1 for linear layers).  A
  * "full-layout arena" is one device buffer that holds every layer at the
@@ -31,9 +35,11 @@
  * Ownership.  The caller owns every device buffer and the stream.  The
  * library owns only the plan (host tables plus a device copy, allocated in
  * hsadmm_plan_create on the current device and released in
- * hsadmm_plan_destroy).  The three hot calls allocate nothing, never
- * synchronise the device, and enqueue all their work on `hip_stream`
- * (a hipStream_t passed as void*; NULL is the default stream).  Outputs are
+ * hsadmm_plan_destroy).  Apart from plan creation / destruction and
+ * hsadmm_plan_set_node_weights, no call allocates or frees memory or
+ * synchronises the device; each enqueues all its work on `hip_stream`
+ * (a hipStream_t passed as void*; NULL is the default stream), so a sequence
+ * of calls can be captured into a HIP graph.  Outputs are
  * valid once the caller has synchronised that stream.  The workspace also
  * carries the index mappings of the compaction (kept positions, counts,
  * offsets) from the call that derives them to the calls that reuse them, so
