@@ -28,7 +28,9 @@ def _phase4_chain(wl, W, U, a, b, rng, want_wbar=True, want_sqnorm=True, fused_d
     dVd = torch.from_numpy(Vd).to(run.dev)
     pkg.hsadmm_plan_set_node_weights(run.plan, a, b)
     pkg.hsadmm_project_weighted(run.plan, run.dW, run.dU, dZg, dVd, run.dZ, run.dWbar, run.dmask, run.dkey, run.ws)
-    pkg.hsadmm_compact_sum(run.plan, run.dZ, dVd, run.dmask, run.dpacked, run.doff, run.dkept, run.ws)
+    # with fused_dual the compaction also runs without a mask, under the index mappings of the selection just made
+    pkg.hsadmm_compact_sum(run.plan, run.dZ, dVd, None if fused_dual else run.dmask, run.dpacked, run.doff, run.dkept,
+                           run.ws)
     if fused_dual:
         pkg.hsadmm_expand_dual(run.plan, run.dpacked, None, run.ddst, run.dZ, dVd, run.ws)
     else:
