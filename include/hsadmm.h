@@ -117,7 +117,7 @@ void hsadmm_plan_destroy(hsadmm_plan_t* plan);
  *   arena_elems            minimum length of a full-layout arena, in elements
  *   groups_total           length of mask / sqnorm / kept_idx
  *   packed_capacity_elems  length of `packed` that fits any mask
- *   workspace_bytes        size of the scratch buffer the three hot calls take
+ *   workspace_bytes        size of the scratch buffer the calls with a workspace argument take
  */
 int hsadmm_plan_sizes(const hsadmm_plan_t* plan, int64_t* arena_elems, int64_t* groups_total,
                       int64_t* packed_capacity_elems, size_t* workspace_bytes);
@@ -358,11 +358,12 @@ const char* hsadmm_strerror(int code);
 int hsadmm_version(void);
 
 /*
- * Diagnostics: per-kernel device time of the hot calls made on this plan.
+ * Diagnostics: per-kernel device time of the calls made on this plan.
  *
- * hsadmm_kernel_timing_enable(plan, 1) makes every kernel launch of the three
- * hot calls carry a start/stop event pair that takes the kernel's own begin
- * and end timestamps; nothing else is put on the stream.  At most 8192
+ * hsadmm_kernel_timing_enable(plan, 1) makes every kernel launch of this plan
+ * carry a start/stop event pair that takes the kernel's own begin and end
+ * timestamps; nothing else is put on the stream (such launches cannot be
+ * captured into a graph).  At most 8192
  * launches are recorded between two reads; later launches run untimed.
  * hsadmm_kernel_timing_read waits for the recorded kernels, returns for every
  * kernel id 0..HSADMM_KERNEL_COUNT-1 the summed duration in milliseconds and
