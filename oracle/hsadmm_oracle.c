@@ -56,17 +56,12 @@ void oracle_set_threads(int t)
 
 int oracle_get_threads(void) { return g_threads; }
 
-static int64_t n_groups(int mode, int c_out, int c_in)
-{
-    if (mode == ORACLE_BOTH) return (int64_t)c_out + c_in;
-    return mode == ORACLE_CHANNEL ? c_in : c_out;
-}
-
-/* Groups of a layer in mask / key: as above, and c_in*khw for shape sparsity. */
-static int64_t n_groups_s(int mode, int c_out, int c_in, int khw)
+/* Groups of a layer in mask / key (see the list of modes above). */
+static int64_t n_groups(int mode, int c_out, int c_in, int khw)
 {
     if (mode == ORACLE_SHAPE) return (int64_t)c_in * khw;
-    return n_groups(mode, c_out, c_in);
+    if (mode == ORACLE_BOTH) return (int64_t)c_out + c_in;
+    return mode == ORACLE_CHANNEL ? c_in : c_out;
 }
 
 /*
@@ -164,7 +159,7 @@ int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
     for (int32_t l = 0; l < L; ++l) {
         const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
         const int64_t n = co * ci * s;
-        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
         if (co < 1 || ci < 1 || s < 1) return -1;
         if (mode[l] == ORACLE_BOTH) {
             if (k[l] < 1 || k[l] > co || k_in[l] < 1 || k_in[l] > ci) return -1;
@@ -303,7 +298,7 @@ int oracle_compact(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
         const int64_t co = c_out[l];
         int64_t ci = c_in[l], s = khw[l];
         int lm = mode[l];
-        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
         if (lm == ORACLE_SHAPE) {
             /* shape groups are the columns of the [c_out][c_in*khw] view: packed like channels of width 1 */
             ci *= s;
@@ -353,7 +348,7 @@ int oracle_expand(int32_t L, const int64_t *elem_off, const int32_t *c_out, cons
         const int64_t co = c_out[l];
         int64_t ci = c_in[l], s = khw[l];
         int lm = mode[l];
-        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
         if (lm == ORACLE_SHAPE) { ci *= s; s = 1; lm = ORACLE_CHANNEL; }     /* as in oracle_compact */
         int32_t *k_out = (int32_t *)malloc(sizeof(int32_t) * (size_t)co);
         int32_t *k_in = (int32_t *)malloc(sizeof(int32_t) * (size_t)ci);
@@ -403,7 +398,7 @@ int oracle_project_frozen(int32_t L, const int64_t *elem_off, const int32_t *c_o
         const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
         if (co < 1 || ci < 1 || s < 1) return -1;
         const int64_t n = co * ci * s;
-        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
         const int64_t off = elem_off[l];
         const uint8_t *ml = mask + gbase;
         int bad = 0;
@@ -457,7 +452,7 @@ int oracle_mask_drift(int32_t L, const int32_t *c_out, const int32_t *c_in, cons
     if (L < 1 || !a || !b || !drift) return -1;
     int64_t gbase = 0;
     for (int32_t l = 0; l < L; ++l) {
-        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
         int32_t d = 0;
         if (mode[l] != ORACLE_NONE)
             for (int64_t g = 0; g < G; ++g) d += ((a[gbase + g] != 0) != (b[gbase + g] != 0)) ? 1 : 0;
@@ -508,7 +503,7 @@ int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c
         const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
         if (co < 1 || ci < 1 || s < 1) return -1;
         const int64_t n = co * ci * s;
-        const int64_t G = n_groups_s(mode[l], c_out[l], c_in[l], khw[l]);
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
         if (mode[l] == ORACLE_BOTH) {
             if (k[l] < 1 || k[l] > co || k_in[l] < 1 || k_in[l] > ci) return -1;
         } else if (mode[l] != ORACLE_NONE && (k[l] < 1 || k[l] > G)) return -1;
