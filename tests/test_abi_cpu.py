@@ -115,3 +115,15 @@ def test_node_coefficients_host_function_matches_the_oracle(lib):
         pkg.hsadmm_node_coefficients([0.0], [0.0], 0.0, 1, 1)
     with pytest.raises(pkg.HsadmmError):
         pkg.hsadmm_node_coefficients([-1.0], [3.0], 0.0, 1, 1)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build has no collectives: bench.py --gpus N with N > 1 exits with a message instead of running."""
+    import subprocess
+    import sys
+    for extra_env, argv in (({}, ["--gpus", "2"]), ({"WORLD_SIZE": "4"}, [])):
+        env = dict(os.environ, **extra_env)
+        r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *argv], env=env, capture_output=True,
+                           text=True, timeout=120)
+        assert r.returncode == 2
+        assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
