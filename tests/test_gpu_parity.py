@@ -486,3 +486,25 @@ def test_plans_with_a_single_kind_of_layer():
     for shapes in ([(6, 5, 4, wk.MODE_NONE, 6), (3, 3, 1, wk.MODE_NONE, 3)], [(40, 30, 9, wk.MODE_CHANNEL, 7)],
                    [(40, 30, 9, wk.MODE_BOTH, 11, 7)], [(40, 30, 9, wk.MODE_FILTER, 11)]):
         _run(wk.custom_workload(shapes, R=2, seed=5, sigma_replica=0.03), determinism=True)
+
+
+def test_maximum_number_of_layers():
+    """HSADMM_MAX_LAYERS = 4096 layers, every one under both constraints (8192 scan segments, the most a plan can
+    hold), plus a mixed table of the same length; one layer more is refused."""
+    import paper_2512_14628_amd as pkg
+    rng = np.random.default_rng(123)
+    both = [(int(rng.integers(2, 7)), int(rng.integers(2, 7)), int(rng.choice([1, 4])), wk.MODE_BOTH) for _ in range(4096)]
+    both = [(co, ci, khw, m, int(rng.integers(1, co + 1)), int(rng.integers(1, ci + 1))) for co, ci, khw, m in both]
+    _run(wk.custom_workload(both, R=2, seed=8, sigma_replica=0.05), determinism=True)
+    mixed = []
+    for i in range(4096):
+        co, ci, khw = int(rng.integers(1, 9)), int(rng.integers(1, 9)), int(rng.choice([1, 1, 9]))
+        mode = int(rng.choice([0, 1, 2, 3]))
+        if mode == wk.MODE_BOTH:
+            mixed.append((co, ci, khw, mode, int(rng.integers(1, co + 1)), int(rng.integers(1, ci + 1))))
+        else:
+            G = ci if mode == wk.MODE_CHANNEL else co
+            mixed.append((co, ci, khw, mode, int(rng.integers(1, G + 1))))
+    _run(wk.custom_workload(mixed, R=1, seed=9), pack_align=4, determinism=False)
+    with pytest.raises(pkg.HsadmmError):
+        pkg.Plan(wk.custom_workload(mixed + [(2, 2, 1, wk.MODE_FILTER, 1)], R=1).table())
