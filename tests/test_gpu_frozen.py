@@ -131,3 +131,15 @@ def test_mask_drift_between_two_iterations():
     assert np.array_equal(drift.cpu().numpy(), oracle.mask_drift(wl.table(), x.cpu().numpy(), y.cpu().numpy()))
     assert pkg.hsadmm_mask_drift(run.plan, x, None, drift, check=False) == -1
     run.close()
+
+
+def test_rows_longer_than_four_million_columns():
+    """A CHANNEL layer whose rows hold more than 2^22 columns (c_in * khw = 5.4 M): the column -> channel division
+    leaves its fast path.  Frozen-mask projection, compaction and expansion (no selection: the oracle's rank count is
+    quadratic in the number of groups)."""
+    wl = wk.custom_workload([(2, 600_000, 9, wk.MODE_CHANNEL, 1000), (3, 5, 1, wk.MODE_FILTER, 2)], R=2, seed=1,
+                            sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    rng = np.random.default_rng(4)
+    mask = (rng.random(wl.groups_total) < 0.4).astype(np.uint8)
+    _check_frozen(wl, W, U, mask, want_wbar=False)
