@@ -30,14 +30,56 @@ __device__ __forceinline__ int block_excl_scan(bool flag, int* wtot, int& total)
     return before + in_wave;
 }
 
+// Exchanges inside rows of 16 lanes, as data-parallel primitives (no LDS traffic); every lane must be active.
+// After the four steps lane ^ 1, lane ^ 2, mirror inside 8 lanes, mirror inside 16 lanes, in this order, a
+// lane has met every other lane of its row.
+template <int CTRL>
+__device__ __forceinline__ unsigned int row_exchange(unsigned int v)
+{
+    return (unsigned int)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+}
+constexpr int kDppXor1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // lane i of 8 reads lane 7 - i
+constexpr int kDppMirror = 0x140;       // lane i of 16 reads lane 15 - i
+
+__device__ __forceinline__ unsigned int lane_value(unsigned int v, int lane)   // lane: the same in every lane
+{
+    return (unsigned int)__builtin_amdgcn_readlane((int)v, lane);
+}
+
+// min / max over the 16 lanes of a row, in every lane of the row
+__device__ __forceinline__ void row_min_max(unsigned int& mn, unsigned int& mx)
+{
+    unsigned int a, b;
+    a = row_exchange<kDppXor1>(mn); b = row_exchange<kDppXor1>(mx); mn = a < mn ? a : mn; mx = b > mx ? b : mx;
+    a = row_exchange<kDppXor2>(mn); b = row_exchange<kDppXor2>(mx); mn = a < mn ? a : mn; mx = b > mx ? b : mx;
+    a = row_exchange<kDppHalfMirror>(mn); b = row_exchange<kDppHalfMirror>(mx); mn = a < mn ? a : mn; mx = b > mx ? b : mx;
+    a = row_exchange<kDppMirror>(mn); b = row_exchange<kDppMirror>(mx); mn = a < mn ? a : mn; mx = b > mx ? b : mx;
+}
+
+// For lane i with value v: the sum of v over the lanes above i of the wave (`above`) and over all 64 lanes.
+__device__ __forceinline__ void wave_sum_above(unsigned int v, int lane, unsigned int& above, unsigned int& total)
+{
+    // butterfly inside the row: at each step the two halves of a block exchange their block sums
+    unsigned int tot = v, ab = 0u, p;
+    p = row_exchange<kDppXor1>(tot); ab += (lane & 1) ? 0u : p; tot += p;
+    p = row_exchange<kDppXor2>(tot); ab += (lane & 2) ? 0u : p; tot += p;
+    p = row_exchange<kDppHalfMirror>(tot); ab += (lane & 4) ? 0u : p; tot += p;
+    p = row_exchange<kDppMirror>(tot); ab += (lane & 8) ? 0u : p; tot += p;
+    const unsigned int t0 = lane_value(tot, 0), t1 = lane_value(tot, 16), t2 = lane_value(tot, 32),
+                       t3 = lane_value(tot, 48);
+    const int row = lane >> 4;
+    above = ab + (row == 0 ? t1 + t2 + t3 : row == 1 ? t2 + t3 : row == 2 ? t3 : 0u);
+    total = t0 + t1 + t2 + t3;
+}
+
 struct TopkShared {
-    unsigned int hist[2][256];                 // double-buffered: one is cleared while the other fills
-    unsigned long long w_and[kScanWaves], w_or[kScanWaves];
+    alignas(16) unsigned int hist[3][256];     // used in turn: one fills while the next is cleared
+    alignas(16) unsigned int w_lo[kScanWaves]; // per wave: smallest / largest upper key word
+    alignas(16) unsigned int w_hi[kScanWaves];
     int wtot[kScanWaves];
-    unsigned long long prefix;                 // bytes of tau found so far (lower bytes zero)
     unsigned long long tau;                    // early exit: the one remaining candidate
-    unsigned int need;                         // how many groups to take among the current candidates
-    unsigned int cand;                         // number of current candidates
 };
 
 // Keys of a layer as seen by the selection: in registers (G <= 8 * 1024) or re-read from memory.
@@ -75,12 +117,18 @@ struct LayerKeys {
 };
 
 // Keys are non-negative finite doubles, so their uint64 bit patterns order like their values.
-// tau, the k-th largest pattern, is found byte by byte from the most significant byte in which the
-// keys differ (one 256-bin histogram per pass).  `need` tracks how many groups must still be taken
-// from the candidates that share the prefix found so far.  Groups with key > tau are kept; of the
-// groups with key == tau the first `need` in index order are kept.
+// tau, the k-th largest pattern, is found eight bits at a time on y = key - c, c = the smallest upper key
+// word (lower word zero), from the most significant bit that can be set in a y downwards: one 256-bin
+// histogram per pass, which every wave then reads for itself (one barrier per pass).  `need` tracks how
+// many groups must still be taken from the candidates that share the prefix found so far.  Groups with
+// key > tau are kept; of the groups with key == tau the first `need` in index order are kept.
 // pos_l / kidx_l receive the layer's index mappings: the rank of every kept group (-1: pruned) and the
 // ascending list of the kept groups.
+__device__ __forceinline__ bool same_prefix(unsigned long long y, unsigned long long prefix, int known)
+{
+    return known >= 64 || (y >> known) == (prefix >> known);
+}
+
 template <bool INREG>
 __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, uint8_t* ml, int kk, TopkShared& sh,
                                            int32_t* pos_l, int32_t* kidx_l)
@@ -91,87 +139,89 @@ __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, 
     LayerKeys<INREG> keys;
     keys.load(kb, G);
 
-    // bits shared by all keys
-    unsigned long long a_and = ~0ull, a_or = 0ull;
-    keys.for_each([&](int, unsigned long long x) { a_and &= x; a_or |= x; });
-    for (int o = kWave >> 1; o > 0; o >>= 1) {
-        a_and &= __shfl_xor(a_and, o, kWave);
-        a_or |= __shfl_xor(a_or, o, kWave);
+    // range of the upper key words
+    unsigned int lo = ~0u, hi = 0u;
+    keys.for_each([&](int, unsigned long long x) {
+        const unsigned int w = (unsigned int)(x >> 32);
+        lo = w < lo ? w : lo;
+        hi = w > hi ? w : hi;
+    });
+    row_min_max(lo, hi);
+    {
+        const unsigned int l1 = lane_value(lo, 16), l2 = lane_value(lo, 32), l3 = lane_value(lo, 48);
+        const unsigned int h1 = lane_value(hi, 16), h2 = lane_value(hi, 32), h3 = lane_value(hi, 48);
+        lo = lo < l1 ? lo : l1; lo = lo < l2 ? lo : l2; lo = lo < l3 ? lo : l3;   // complete in row 0
+        hi = hi > h1 ? hi : h1; hi = hi > h2 ? hi : h2; hi = hi > h3 ? hi : h3;
     }
-    if (lane == 0) { sh.w_and[wave] = a_and; sh.w_or[wave] = a_or; }
-    if (tid < 256) { sh.hist[0][tid] = 0u; sh.hist[1][tid] = 0u; }
+    if (lane == 0) { sh.w_lo[wave] = lo; sh.w_hi[wave] = hi; }
+    if (tid < 768) (&sh.hist[0][0])[tid] = 0u;
     __syncthreads();
-    a_and = ~0ull; a_or = 0ull;
-#pragma unroll
-    for (int w = 0; w < kScanWaves; ++w) { a_and &= sh.w_and[w]; a_or |= sh.w_or[w]; }
-    const unsigned long long diff = a_and ^ a_or;
+    lo = sh.w_lo[lane & (kScanWaves - 1)];
+    hi = sh.w_hi[lane & (kScanWaves - 1)];
+    static_assert(kScanWaves == 16, "one row of lanes holds one value per wave");
+    row_min_max(lo, hi);
+    const unsigned long long c = (unsigned long long)lo << 32;
+    const unsigned int span = hi - lo;                        // every y is below (span + 1) << 32
 
+    const int top = span ? 63 - __clz((int)span) : 31;        // no y has a bit above this one
+    int shift = top - 7;                                      // the first digit ends at that bit
+    int known = top + 1;                                      // bits >= known of y agree with the prefix so far
+    unsigned long long prefix = 0ull;
+    unsigned int need_now = (unsigned int)kk, cand = (unsigned int)G;
+    int pass = 0;
+    for (;;) {
+        unsigned int* h = sh.hist[pass % 3];
+        keys.for_each([&](int, unsigned long long x) {
+            const unsigned long long y = x - c;
+            if (same_prefix(y, prefix, known)) atomicAdd(&h[(unsigned int)(y >> shift) & 255u], 1u);
+        });
+        if (tid < 256) sh.hist[(pass + 1) % 3][tid] = 0u;      // last read two barriers ago
+        __syncthreads();
+        // every wave for itself: lane i owns bins 4i..4i+3; `above` = number of candidates in higher bins
+        const uint4 hv = *reinterpret_cast<const uint4*>(&h[4 * lane]);
+        const unsigned int hh[4] = {hv.x, hv.y, hv.z, hv.w};
+        unsigned int above, all;
+        wave_sum_above(hv.x + hv.y + hv.z + hv.w, lane, above, all);
+        unsigned int bin = 0u, need_next = 0u, cand_next = 0u;
+        bool mine = false;
+#pragma unroll
+        for (int b = 3; b >= 0; --b) {
+            if (above < need_now && need_now <= above + hh[b]) {
+                mine = true;
+                bin = (unsigned int)(4 * lane + b);
+                need_next = need_now - above;
+                cand_next = hh[b];
+            }
+            above += hh[b];
+        }
+        const unsigned long long owners = __ballot(mine);      // one lane, as 1 <= need <= number of candidates
+        const int owner = owners ? __builtin_ctzll(owners) : 0;
+        bin = lane_value(bin, owner);
+        need_now = lane_value(need_next, owner);
+        cand = lane_value(cand_next, owner);
+        // a digit that reaches below bit 0 of the previous one repeats bits the prefix already has
+        prefix |= (unsigned long long)bin << shift;
+        ++pass;
+        known = shift;
+        if (shift == 0 || cand == 1u) break;
+        shift = shift > 8 ? shift - 8 : 0;
+    }
     unsigned long long tau;
     int need;
     bool scan_ties;
-    if (diff == 0ull) {
-        // all keys equal: the first k groups win
-        tau = a_or;
-        need = kk;
-        scan_ties = true;
-    } else {
-        const int top = 63 - __clzll((long long)diff);        // most significant differing bit
-        int shift = (top >> 3) << 3;                          // its byte
-        const unsigned long long common = (shift + 8 >= 64) ? 0ull : ((a_or >> (shift + 8)) << (shift + 8));
-        if (tid == 0) { sh.prefix = common; sh.need = (unsigned int)kk; sh.cand = (unsigned int)G; }
+    if (known > 0) {
+        // one candidate left before the last bit: it is tau; find it by its prefix
+        keys.for_each([&](int, unsigned long long x) {
+            if (same_prefix(x - c, prefix, known)) sh.tau = x;
+        });
         __syncthreads();
-        int buf = 0;
-        bool unique = false;
-        for (; shift >= 0; shift -= 8) {
-            const unsigned long long prefix = sh.prefix;
-            const unsigned int need_now = sh.need;
-            unsigned int* h = sh.hist[buf];
-            keys.for_each([&](int, unsigned long long x) {
-                if (shift + 8 >= 64 || (x >> (shift + 8)) == (prefix >> (shift + 8)))
-                    atomicAdd(&h[(unsigned int)(x >> shift) & 255u], 1u);
-            });
-            if (tid < 256) sh.hist[buf ^ 1][tid] = 0u;         // ready for the next pass
-            __syncthreads();
-            if (tid < kWave) {
-                // lane i owns bins 4i..4i+3; `above` = number of candidates in higher bins
-                const unsigned int h0 = h[4 * tid], h1 = h[4 * tid + 1], h2 = h[4 * tid + 2], h3 = h[4 * tid + 3];
-                const unsigned int hh[4] = {h0, h1, h2, h3};
-                const unsigned int mine = h0 + h1 + h2 + h3;
-                unsigned int incl = mine;   // inclusive suffix sum over lanes tid..63
-                for (int o = 1; o < kWave; o <<= 1) {
-                    const unsigned int up = __shfl_down(incl, o, kWave);
-                    if (tid + o < kWave) incl += up;
-                }
-                unsigned int above = incl - mine;
-#pragma unroll
-                for (int b = 3; b >= 0; --b) {
-                    if (above < need_now && need_now <= above + hh[b]) {
-                        sh.prefix = prefix | ((unsigned long long)(4 * tid + b) << shift);
-                        sh.need = need_now - above;
-                        sh.cand = hh[b];
-                    }
-                    above += hh[b];
-                }
-            }
-            __syncthreads();
-            buf ^= 1;
-            if (sh.cand == 1u && shift > 0) { unique = true; break; }
-        }
-        if (unique) {
-            // one candidate left: it is tau; find it by its prefix
-            const unsigned long long prefix = sh.prefix;
-            keys.for_each([&](int, unsigned long long x) {
-                if ((x >> shift) == (prefix >> shift)) sh.tau = x;
-            });
-            __syncthreads();
-            tau = sh.tau;
-            need = 1;
-            scan_ties = false;
-        } else {
-            tau = sh.prefix;
-            need = (int)sh.need;
-            scan_ties = (unsigned int)need != sh.cand;        // fewer wanted than tied: index order decides
-        }
+        tau = sh.tau;
+        need = 1;
+        scan_ties = false;
+    } else {
+        tau = prefix + c;
+        need = (int)need_now;
+        scan_ties = need_now != cand;                          // fewer wanted than tied: index order decides
     }
     // final pass in index order: the kept flag (ties: the first `need` groups equal to tau), then the rank
     // of every kept group among the kept ones
