@@ -74,12 +74,14 @@ __device__ __forceinline__ void wave_sum_above(unsigned int v, int lane, unsigne
     total = t0 + t1 + t2 + t3;
 }
 
+constexpr int kTopkList = 32;               // candidates ranked directly instead of by further passes
 struct TopkShared {
     alignas(16) unsigned int hist[3][256];     // used in turn: one fills while the next is cleared
     alignas(16) unsigned int w_lo[kScanWaves]; // per wave: smallest / largest upper key word
     alignas(16) unsigned int w_hi[kScanWaves];
     int wtot[kScanWaves];
-    unsigned long long tau;                    // early exit: the one remaining candidate
+    unsigned long long list[kTopkList];        // early exit: the few remaining candidates, in any order
+    unsigned int n_list;
 };
 
 // Keys of a layer as seen by the selection: in registers (G <= 8 * 1024) or re-read from memory.
@@ -155,6 +157,7 @@ __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, 
     }
     if (lane == 0) { sh.w_lo[wave] = lo; sh.w_hi[wave] = hi; }
     if (tid < 768) (&sh.hist[0][0])[tid] = 0u;
+    if (tid == 768) sh.n_list = 0u;
     __syncthreads();
     lo = sh.w_lo[lane & (kScanWaves - 1)];
     hi = sh.w_hi[lane & (kScanWaves - 1)];
@@ -203,21 +206,36 @@ __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, 
         prefix |= (unsigned long long)bin << shift;
         ++pass;
         known = shift;
-        if (shift == 0 || cand == 1u) break;
+        if (shift == 0 || cand <= (unsigned int)kTopkList) break;
         shift = shift > 8 ? shift - 8 : 0;
     }
     unsigned long long tau;
     int need;
     bool scan_ties;
     if (known > 0) {
-        // one candidate left before the last bit: it is tau; find it by its prefix
+        // few candidates left before the last bit: list them, then every wave ranks them directly
         keys.for_each([&](int, unsigned long long x) {
-            if (same_prefix(x - c, prefix, known)) sh.tau = x;
+            if (same_prefix(x - c, prefix, known)) {
+                const unsigned int j = atomicAdd(&sh.n_list, 1u);
+                if (j < (unsigned int)kTopkList) sh.list[j] = x;
+            }
         });
         __syncthreads();
-        tau = sh.tau;
-        need = 1;
-        scan_ties = false;
+        const int n = (int)cand;
+        const unsigned long long mine = lane < n ? sh.list[lane] : 0ull;
+        unsigned int gt = 0u, eq = 0u;          // candidates above / equal to this lane's
+        for (int j = 0; j < n; ++j) {
+            const unsigned long long v = sh.list[j];
+            gt += v > mine ? 1u : 0u;
+            eq += v == mine ? 1u : 0u;
+        }
+        // tau is the need_now-th largest candidate
+        const unsigned long long owners = __ballot(lane < n && gt < need_now && need_now <= gt + eq);
+        const int owner = owners ? __builtin_ctzll(owners) : 0;
+        tau = ((unsigned long long)lane_value((unsigned int)(mine >> 32), owner) << 32) |
+              (unsigned long long)lane_value((unsigned int)mine, owner);
+        need = (int)(need_now - lane_value(gt, owner));
+        scan_ties = (unsigned int)need != lane_value(eq, owner);   // fewer wanted than tied: index order decides
     } else {
         tau = prefix + c;
         need = (int)need_now;
