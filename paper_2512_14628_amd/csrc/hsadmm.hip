@@ -6,11 +6,12 @@
 //   project_pass1   streams the R replicas and U once.  Computes Wbar, V = Wbar + U and the fp64
 //                   partial sums of V^2; for FILTER / BOTH / NONE layers it writes the values that are
 //                   final if the group is kept: Z <- V, U <- U + (Wbar - V).   [Eq. (9), (12)]
-//   select_topk     one workgroup per layer: byte-wise radix select of the k-th largest key on
-//                   the uint64 view of the non-negative doubles (bytes all keys share are skipped,
-//                   the search stops once one candidate is left), ties cut by an ordered scan so
-//                   that lower indices win; leaves the selection's index mappings in the workspace
-//                   for a compaction / expansion without a mask.            [Eq. (10)]
+//   select_topk     one workgroup per layer: radix select, eight bits a pass, of the k-th largest key on
+//                   the uint64 view of the non-negative doubles (taken relative to the smallest upper
+//                   word, so the first digit already spreads the keys; the last few candidates are
+//                   ranked directly), ties cut by an ordered scan so that lower indices win; leaves
+//                   the selection's index mappings in the workspace for a compaction / expansion
+//                   without a mask.                                          [Eq. (10)]
 //   project_fixup   touches pruned groups only: U <- V (taken from Z), Z <- +0.  For a pruned
 //                   group U + (Wbar - 0) equals V bit for bit, so no replica is read again.
 //   channel_final   CHANNEL layers: pass 1 only sums; their Z and U are written here, in one streaming
