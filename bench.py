@@ -1,10 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the H-SADMM structured-sparsity step on one MI355X.
 
-One "step" is one pass of the whole hot path over one batch of synthetic input:
-hsadmm_project (average R replicas, candidate, group norms, top-k projection, dual update),
-hsadmm_compact (pack the kept groups), hsadmm_expand (zero fill + scatter back), issued back to back on
-one stream with every buffer already resident in HBM.
+One "step" is one pass of the whole hot path over one batch of synthetic input: the projection (average R
+replicas, candidate, group norms, top-k projection, dual update), the compaction (pack the kept groups) and the
+expansion (zero fill + scatter back), issued back to back on one stream with every buffer already resident in
+HBM.  Projection and compaction go through hsadmm_project_compact, which does the work of hsadmm_project followed
+by hsadmm_compact with the repair of pruned groups and the gather of kept groups in one launch
+(--separate-calls: the two calls); then hsadmm_expand.
 
 Prints ONE JSON line.  `value` is algorithmic bytes per second for the whole step (each unique input
 read once, each output written once: 4n(R+4) + 12 n_kept bytes); `roofline` prices the dominant kernel
@@ -42,6 +44,9 @@ def main():
                          "the selection inside hsadmm_project left in the workspace")
     ap.add_argument("--expand-rescan", action="store_true",
                     help="hsadmm_expand recomputes positions from the mask instead of reusing hsadmm_compact's")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="hsadmm_project and hsadmm_compact as two calls instead of hsadmm_project_compact, which "
+                         "does the same work with the fix-up and the gather sharing a launch")
     ap.add_argument("--skip-extras", action="store_true",
                     help="time the base step only (no frozen-mask, weighted, residual and composite sections): "
                          "the form the rocprofv3 summaries under profiles/ are taken with")
@@ -93,15 +98,21 @@ def main():
     stream = torch.cuda.current_stream()
     counter = [0]
 
+    one_call = not (args.separate_calls or args.compact_rescan)
+
     def step():
         b = sets[counter[0] % nsets]
         counter[0] += 1
-        pkg.hsadmm_project(plan, b.W, b.U, b.Z, None, b.mask, None, b.ws, stream=stream)
         # compaction and expansion reuse the index mappings (kept positions, counts, offsets) that the selection
-        # inside hsadmm_project left in the workspace (mask = NULL), as the paper's recovery step reuses its cached
+        # inside the projection left in the workspace (mask = NULL), as the paper's recovery step reuses its cached
         # index sets (Section 4.4.3); --compact-rescan / --expand-rescan derive them from the mask again
-        pkg.hsadmm_compact(plan, b.Z, b.mask if args.compact_rescan else None, b.packed, b.off, b.kept, b.ws,
-                           stream=stream)
+        if one_call:
+            pkg.hsadmm_project_compact(plan, b.W, b.U, b.Z, None, b.mask, None, b.packed, b.off, b.kept, b.ws,
+                                       stream=stream)
+        else:
+            pkg.hsadmm_project(plan, b.W, b.U, b.Z, None, b.mask, None, b.ws, stream=stream)
+            pkg.hsadmm_compact(plan, b.Z, b.mask if args.compact_rescan else None, b.packed, b.off, b.kept, b.ws,
+                               stream=stream)
         pkg.hsadmm_expand(plan, b.packed, b.mask if args.expand_rescan else None, b.dst, b.ws, stream=stream)
 
     # ---- one-shot correctness check against the oracle (outside every timed region)
@@ -162,6 +173,9 @@ def main():
             counter[0] += 1
             if which == "project":
                 pkg.hsadmm_project(plan, b.W, b.U, b.Z, None, b.mask, None, b.ws, stream=stream)
+            elif which == "project_compact":
+                pkg.hsadmm_project_compact(plan, b.W, b.U, b.Z, None, b.mask, None, b.packed, b.off, b.kept, b.ws,
+                                           stream=stream)
             elif which == "compact":
                 pkg.hsadmm_compact(plan, b.Z, b.mask if args.compact_rescan else None, b.packed, b.off, b.kept, b.ws,
                                    stream=stream)
@@ -170,7 +184,7 @@ def main():
         return fn
 
     per_call_us = {}
-    for which in ("project", "compact", "expand"):      # in this order: every set then holds a valid selection
+    for which in ("project", "compact", "expand", "project_compact"):   # every set holds a valid selection throughout
         ts = timed_us(call_alone(which), max(nsets, args.steps // 2))
         per_call_us[which] = {"median_us": round(ts[len(ts) // 2], 2), "min_us": round(ts[0], 2)}
 
@@ -446,6 +460,7 @@ def main():
                    "params": wl.n_total, "replicas": wl.R, "kept_params": nk, "seed": wl.seed,
                    "buffer_sets_rotated": nsets, "expand_reuses_cached_index_mappings": not args.expand_rescan,
                    "compact_reuses_the_selections_index_mappings": not args.compact_rescan,
+                   "project_and_compact_in_one_call": one_call,
                    "algorithmic_bytes_per_step": bytes_["step"]},
         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
         "params_per_s": round(params_per_s, 1),

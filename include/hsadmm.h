@@ -231,6 +231,25 @@ int hsadmm_compact(const hsadmm_plan_t* plan, const float* src, const uint8_t* m
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The projection step and the tensor shrinkage of its result in one call
+ * (Eq. (10), Eq. (12); Section 4.4.1, Eq. (15)): the same outputs, bit for
+ * bit, as hsadmm_project(...) followed by hsadmm_compact(plan, Z, NULL, packed,
+ * layer_off, kept_idx, ...), i.e. Z compacted under the selection just made.
+ * The compaction reads kept groups only and the repair of the speculative
+ * outputs rewrites pruned groups only, so for plans without CHANNEL layers
+ * the two share one kernel launch; plans with CHANNEL layers run the same
+ * kernels as the two separate calls.  Arguments, alignment, ownership and
+ * errors as for hsadmm_project (W_replicas .. sqnorm, workspace) and
+ * hsadmm_compact (packed, layer_off, kept_idx); all three compaction outputs
+ * are required.  Afterwards the workspace holds the selection's index
+ * mappings, as after hsadmm_project.
+ */
+int hsadmm_project_compact(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                           float* U, float* Z, float* Wbar, uint8_t* mask, double* sqnorm,
+                           float* packed, int64_t* layer_off, int32_t* kept_idx,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Tensor shrinkage of the pre-transmission buffer c = z_i + v_i (Section
  * 4.4.1; Algorithm 1, Phase 4): exactly hsadmm_compact applied to the
  * element-wise fp32 sum src0 + src1, which is formed on the fly (no full-size
@@ -371,7 +390,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 19
+#define HSADMM_KERNEL_COUNT 20
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

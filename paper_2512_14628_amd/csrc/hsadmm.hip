@@ -62,7 +62,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFixup, kAverage, kMaskDrift, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFixup, kAverage, kMaskDrift, kFixupGather, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -444,11 +444,21 @@ int hsadmm_plan_sizes(const hsadmm_plan_t* p, int64_t* arena_elems, int64_t* gro
     return HSADMM_OK;
 }
 
-int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U, float* Z,
-                   float* Wbar, uint8_t* mask, double* sqnorm, void* workspace, size_t workspace_bytes,
-                   void* hip_stream)
+// Where hsadmm_project_compact sends the compaction of Z (all NULL: no compaction).
+struct CompactOut {
+    float* packed;
+    int64_t* layer_off;
+    int32_t* kept_idx;
+};
+
+static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U, float* Z,
+                        float* Wbar, uint8_t* mask, double* sqnorm, const CompactOut* out, void* workspace,
+                        size_t workspace_bytes, void* hip_stream)
 {
     if (!p || !W_replicas || !U || !Z || !mask || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (out && (!out->packed || !out->layer_off || !out->kept_idx || !is_aligned(out->packed, 16) ||
+                !is_aligned(out->layer_off, 8) || !is_aligned(out->kept_idx, 4)))
+        return HSADMM_ERR_INVALID_ARGUMENT;
     if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
     if (!is_aligned(U, 16) || !is_aligned(Z, 16) || (Wbar && !is_aligned(Wbar, 16)) ||
@@ -476,7 +486,11 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     if (run_selection(p, a.key, a.colpart, Z, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
-    if (!p->items_fix.empty()) {
+    // The compaction of Z under the selection just made reads kept groups only, which FILTER and BOTH layers
+    // hold in final form since pass 1; it shares a launch with the FILTER fix-up unless a CHANNEL layer's Z
+    // is still to be written.
+    const bool fuse = out && !p->items_fix.empty() && p->items_chan.empty();
+    if (!p->items_fix.empty() && !fuse) {
         e = launch(p, kFixup, project_fixup, (unsigned)p->items_fix.size(), kBlock, s,
                    (const WorkItem*)p->d_items_fix, (const uint8_t*)mask, U, Z);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
@@ -498,7 +512,38 @@ int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32
         }
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
+    if (out) {
+        const CopyOut co{out->layer_off, out->kept_idx};
+        const int32_t* pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
+        const int32_t* cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
+        const int32_t* kidx = reinterpret_cast<const int32_t*>(ws + p->ws.kept_idx);
+        const int64_t* lo = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
+        if (fuse)
+            e = launch(p, kFixupGather, fixup_gather, (unsigned)(p->items_fix.size() + p->items_rows.size()), kBlock,
+                       s, (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), (const uint8_t*)mask, U, Z,
+                       (const WorkItem*)p->d_items_rows, pos, cnt, kidx, (int)p->layers.size(), lo, out->packed, co);
+        else
+            e = launch(p, kGather, compact_gather<false>, (unsigned)p->items_rows.size(), kBlock, s,
+                       (const WorkItem*)p->d_items_rows, (const float*)Z, (const float*)nullptr, pos, cnt, kidx,
+                       (int)p->layers.size(), lo, out->packed, co);
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
     return HSADMM_OK;
+}
+
+int hsadmm_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U, float* Z,
+                   float* Wbar, uint8_t* mask, double* sqnorm, void* workspace, size_t workspace_bytes,
+                   void* hip_stream)
+{
+    return project_impl(p, W_replicas, R, U, Z, Wbar, mask, sqnorm, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+int hsadmm_project_compact(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U, float* Z,
+                           float* Wbar, uint8_t* mask, double* sqnorm, float* packed, int64_t* layer_off,
+                           int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    const CompactOut out{packed, layer_off, kept_idx};
+    return project_impl(p, W_replicas, R, U, Z, Wbar, mask, sqnorm, &out, workspace, workspace_bytes, hip_stream);
 }
 
 int hsadmm_project_frozen(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U, float* Z,
@@ -870,6 +915,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kBothFixup: return "composite_fixup";
         case kAverage: return "average";
         case kMaskDrift: return "mask_drift";
+        case kFixupGather: return "fixup_gather";
         default: return "";
     }
 }

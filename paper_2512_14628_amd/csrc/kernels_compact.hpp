@@ -177,16 +177,11 @@ struct CopyOut {
 
 // SUM: the source is the element-wise sum of two arenas (c = z_i + v_i, Section 4.4.1), formed on the fly.
 template <bool SUM>
-__global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restrict__ items,
-                                                         const float* __restrict__ src,
-                                                         const float* __restrict__ src1,
-                                                         const int32_t* __restrict__ pos,
-                                                         const int32_t* __restrict__ cnt,
-                                                         const int32_t* __restrict__ kept_idx, int n_layers,
-                                                         const int64_t* __restrict__ layer_off,
-                                                         float* __restrict__ packed, CopyOut co)
+__device__ __forceinline__ void gather_item(const WorkItem& it, const float* src, const float* src1,
+                                            const int32_t* __restrict__ pos, const int32_t* __restrict__ cnt,
+                                            const int32_t* __restrict__ kept_idx, int n_layers,
+                                            const int64_t* __restrict__ layer_off, float* packed, CopyOut co)
 {
-    const WorkItem it = items[blockIdx.x];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int row_len = it.row_len;
@@ -281,6 +276,38 @@ __global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restr
             }
         }
     }
+}
+
+template <bool SUM>
+__global__ __launch_bounds__(kBlock) void compact_gather(const WorkItem* __restrict__ items,
+                                                         const float* __restrict__ src,
+                                                         const float* __restrict__ src1,
+                                                         const int32_t* __restrict__ pos,
+                                                         const int32_t* __restrict__ cnt,
+                                                         const int32_t* __restrict__ kept_idx, int n_layers,
+                                                         const int64_t* __restrict__ layer_off,
+                                                         float* __restrict__ packed, CopyOut co)
+{
+    gather_item<SUM>(items[blockIdx.x], src, src1, pos, cnt, kept_idx, n_layers, layer_off, packed, co);
+}
+
+// The FILTER fix-up and the compaction of Z in one launch: the fix-up rewrites pruned rows only, the gather
+// reads kept rows only (final since pass 1), so the two kinds of workgroup touch disjoint memory and need no
+// order between them.  Workgroups [0, n_fix) take the fix-up items, the rest the row items.
+__global__ __launch_bounds__(kBlock) void fixup_gather(const WorkItem* __restrict__ fix_items, int n_fix,
+                                                       const uint8_t* __restrict__ mask, float* U, float* Z,
+                                                       const WorkItem* __restrict__ row_items,
+                                                       const int32_t* __restrict__ pos,
+                                                       const int32_t* __restrict__ cnt,
+                                                       const int32_t* __restrict__ kept_idx, int n_layers,
+                                                       const int64_t* __restrict__ layer_off, float* packed,
+                                                       CopyOut co)
+{
+    if ((int)blockIdx.x < n_fix)
+        fixup_rows(fix_items[blockIdx.x], mask, U, Z);
+    else
+        gather_item<false>(row_items[(int)blockIdx.x - n_fix], Z, nullptr, pos, cnt, kept_idx, n_layers, layer_off,
+                           packed, co);
 }
 
 // ------------------------------------------------------------------ expansion (zero fill + scatter)

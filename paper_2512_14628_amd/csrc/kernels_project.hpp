@@ -295,11 +295,8 @@ __device__ __forceinline__ void quad_pruned(const uint8_t* __restrict__ mc, cons
 
 // Row items of the FILTER layers.  A pruned filter's row moves whole: U <- V (held in Z), Z <- +0; kept rows are
 // final already.
-__global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restrict__ items,
-                                                        const uint8_t* __restrict__ mask,
-                                                        float* __restrict__ U, float* __restrict__ Z)
+__device__ __forceinline__ void fixup_rows(const WorkItem& it, const uint8_t* mask, float* U, float* Z)
 {
-    const WorkItem it = items[blockIdx.x];
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
@@ -325,6 +322,13 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
             }
         }
     }
+}
+
+__global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restrict__ items,
+                                                        const uint8_t* __restrict__ mask,
+                                                        float* __restrict__ U, float* __restrict__ Z)
+{
+    fixup_rows(items[blockIdx.x], mask, U, Z);
 }
 
 // Row items of the BOTH layers.  A pruned filter's row moves whole, as above.  In a kept filter's row only the

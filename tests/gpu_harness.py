@@ -42,11 +42,20 @@ class GpuRun:
         m = None if cached else (self.dmask if mask is None else mask)
         pkg.hsadmm_expand(self.plan, self.dpacked, m, self.ddst, self.ws)
 
-    def step(self, cached=False):
-        """cached=True: compaction and expansion reuse the index mappings of the projection (no mask scan)."""
-        self.project()
-        self.compact(cached=cached)
-        self.expand(cached=cached)
+    def project_compact(self):
+        pkg.hsadmm_project_compact(self.plan, self.dW, self.dU, self.dZ, self.dWbar, self.dmask, self.dkey,
+                                   self.dpacked, self.doff, self.dkept, self.ws)
+
+    def step(self, cached=False, fused=False):
+        """cached=True: compaction and expansion reuse the index mappings of the projection (no mask scan).
+        fused=True: projection and compaction through the one call that does both."""
+        if fused:
+            self.project_compact()
+            self.expand(cached=True)
+        else:
+            self.project()
+            self.compact(cached=cached)
+            self.expand(cached=cached)
         torch.cuda.synchronize()
 
     def outputs(self):

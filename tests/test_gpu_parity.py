@@ -60,8 +60,16 @@ def _run(wl, pack_align=1, want_wbar=True, want_sqnorm=True, threads=8, determin
                 assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), name
         else:
             assert np.array_equal(a, b), name
+    # the call that projects and compacts in one go gives the same bits as the two calls
+    run3 = GpuRun(wl, W, U, pack_align=pack_align, want_wbar=want_wbar, want_sqnorm=want_sqnorm, table=gpu_table)
+    run3.step(fused=True)
+    got3 = run3.outputs()
+    for name in got:
+        assert got[name].dtype == got3[name].dtype and got[name].shape == got3[name].shape, name
+        assert np.array_equal(got[name].view(np.uint8), got3[name].view(np.uint8)), "fused call: %s" % name
     run.close()
     run2.close()
+    run3.close()
     return got, ref, refc
 
 
@@ -265,6 +273,16 @@ def test_error_codes_on_device_arguments():
     assert pkg.hsadmm_compact(p, None, run.dmask, run.dpacked, run.doff, run.dkept, run.ws, check=False) == -1
     assert pkg.hsadmm_compact(p, run.dZ, run.dmask, run.dpacked, None, run.dkept, run.ws, check=False) == -1
     assert pkg.hsadmm_expand(p, None, run.dmask, run.ddst, run.ws, check=False) == -1
+    pc = pkg.hsadmm_project_compact
+    assert pc(p, run.dW, run.dU, run.dZ, None, run.dmask, None, run.dpacked, run.doff, run.dkept, ws_small,
+              check=False) == -2
+    assert pc(p, run.dW, run.dU, run.dZ, None, run.dmask, None, None, run.doff, run.dkept, run.ws, check=False) == -1
+    assert pc(p, run.dW, run.dU, run.dZ, None, run.dmask, None, run.dpacked, None, run.dkept, run.ws, check=False) == -1
+    assert pc(p, run.dW, run.dU, run.dZ, None, run.dmask, None, run.dpacked, run.doff, None, run.ws, check=False) == -1
+    assert pc(p, run.dW, run.dU, run.dZ, None, run.dmask, None, run.dpacked[1:], run.doff, run.dkept, run.ws,
+              check=False) == -1                                                                      # misaligned
+    assert pc(p, run.dW * 17, run.dU, run.dZ, None, run.dmask, None, run.dpacked, run.doff, run.dkept, run.ws,
+              check=False) == -4
     # nothing above may have touched the outputs
     torch.cuda.synchronize()
     assert bool(torch.isnan(run.dZ).all()) and bool((run.dmask == 7).all())
