@@ -20,6 +20,8 @@
 //                   second select_topk for the channels.   [Section 3, paragraph after Eq. (10)]
 //   scan_mask       index mappings from a given mask: kept counts, positions, kept_idx, layer_off.
 //   compact_gather  packed <- src[K_out, K_in, :]                             [Eq. (15)]
+//   fixup_gather    project_fixup and compact_gather of Z in one launch (hsadmm_project_compact): the
+//                   first rewrites pruned rows only, the second reads kept rows only.
 //   expand_scatter  dst <- zero fill + scatter of packed                      [Section 4.4.3]
 //   project_frozen  one pass under a given mask                               [Section 4.5]
 //   weighted_pass1 / weighted_fixup / weighted_final   the candidate of Eq. (9) with its rho_2 term
