@@ -273,7 +273,8 @@ def main():
                   "project_frozen_frac": round(bytes_["project"] / (f_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
 
         # ---- full node update (Eq. (9) with the rho_2 (z - v) term) + Phase 4 on one node:
-        #      hsadmm_project_weighted, hsadmm_compact_sum (c = z_i + v_i), hsadmm_expand_dual (z and Eq. (13))
+        #      hsadmm_project_weighted + hsadmm_compact_sum (c = z_i + v_i) through hsadmm_project_weighted_compact
+        #      (--separate-calls: the two calls), then hsadmm_expand_dual (z and Eq. (13))
         L = len(wl.layers)
         wa, wb_ = pkg.hsadmm_node_coefficients([1.5e-3] * L, [1.5e-4] * L, 1e-4, 16, wl.R)   # the paper's initial penalties
         pkg.hsadmm_plan_set_node_weights(plan, wa, wb_)
@@ -284,9 +285,13 @@ def main():
         def weighted_step():
             b = sets[counter[0] % nsets]
             counter[0] += 1
-            pkg.hsadmm_project_weighted(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, None, b.ws, stream=stream)
-            pkg.hsadmm_compact_sum(plan, b.Z, b.Vd, b.mask if args.compact_rescan else None, b.packed, b.off, b.kept,
-                                   b.ws, stream=stream)
+            if one_call:
+                pkg.hsadmm_project_weighted_compact(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, None, b.packed,
+                                                    b.off, b.kept, b.ws, stream=stream)
+            else:
+                pkg.hsadmm_project_weighted(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, None, b.ws, stream=stream)
+                pkg.hsadmm_compact_sum(plan, b.Z, b.Vd, b.mask if args.compact_rescan else None, b.packed, b.off,
+                                       b.kept, b.ws, stream=stream)
             # decompression and the inter-node dual update of Eq. (13) in one pass
             pkg.hsadmm_expand_dual(plan, b.packed, None, b.dst, b.Z, b.Vd, b.ws, stream=stream)
 
@@ -327,10 +332,11 @@ def main():
                      "GBps": round(r_bytes / (r_us * 1e-6) / 1e9, 1),
                      "hbm_frac": round(r_bytes / (r_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
         # what the method must move: project_weighted reads R replicas, U, z, v and writes Z, U (R + 5 arenas);
-        # compact_sum reads the kept parts of Z and v and writes packed (12 n_kept); expand + Eq. (13) read packed
-        # (4 n_kept) and z_i, v and write z, v (4 arenas); z is produced and consumed in the same pass, so it is
-        # not counted as read again
-        w_bytes = 4 * wl.n_total * (wl.R + 9) + 16 * nk
+        # the shrinkage writes packed (4 n_kept) and, as a call of its own, first reads the kept parts of Z and v
+        # again (8 n_kept; in the one-call form they are packed as they are formed and not charged); expand +
+        # Eq. (13) read packed (4 n_kept) and z_i, v and write z, v (4 arenas); z is produced and consumed in the
+        # same pass, so it is not counted as read again
+        w_bytes = 4 * wl.n_total * (wl.R + 9) + (8 if one_call else 16) * nk
         weighted = {"ms_per_step": round(1e3 * w_elapsed, 4),
                     "algorithmic_bytes_per_step": w_bytes,
                     "value_GBps": round(w_bytes / w_elapsed / 1e9, 1),

@@ -300,6 +300,24 @@ int hsadmm_project_weighted(const hsadmm_plan_t* plan, const float* const* W_rep
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The weighted projection and the shrinkage of the pre-transmission buffer
+ * c = z_i + v_i in one call (Eq. (9), (10), (12); Section 4.4.1; Algorithm 1,
+ * Phase 4): the same outputs, bit for bit, as hsadmm_project_weighted(...)
+ * followed by hsadmm_compact_sum(plan, Z, Vd, NULL, packed, layer_off,
+ * kept_idx, ...).  The pass that finishes a kept filter's z~ already holds
+ * its Vd, so it writes the packed row as well and the FILTER layers are not
+ * read again; the rows of the other layers are packed by workgroups of the
+ * same launch.  Arguments, alignment, ownership and errors as for
+ * hsadmm_project_weighted and hsadmm_compact_sum; all three compaction
+ * outputs are required.
+ */
+int hsadmm_project_weighted_compact(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                                    float* U, const float* Zg, const float* Vd, float* Z, float* Wbar,
+                                    uint8_t* mask, double* sqnorm,
+                                    float* packed, int64_t* layer_off, int32_t* kept_idx,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Inter-node dual update, Eq. (13): Vd <- Vd + (Zi - Zg) on every layer
  * (arena padding untouched).  Zi: the node's projected consensus; Zg: the new
  * global consensus (e.g. the output of hsadmm_expand); Vd in/out.  All three
@@ -390,7 +408,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 20
+#define HSADMM_KERNEL_COUNT 21
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

@@ -31,8 +31,9 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_kernel_timing_enable", "hsadmm_kernel_timing_read", "hsadmm_kernel_name",
            "hsadmm_project_frozen", "hsadmm_mask_or", "hsadmm_compact_sum", "hsadmm_node_coefficients",
            "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals",
-           "hsadmm_average", "hsadmm_mask_drift", "hsadmm_expand_dual", "hsadmm_project_compact")
-KERNEL_COUNT = 20
+           "hsadmm_average", "hsadmm_mask_drift", "hsadmm_expand_dual", "hsadmm_project_compact",
+           "hsadmm_project_weighted_compact")
+KERNEL_COUNT = 21
 
 
 class HsadmmError(RuntimeError):
@@ -111,6 +112,9 @@ def load_library():
     lib.hsadmm_project_weighted.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, vp,
                                             ctypes.c_size_t, vp]
     lib.hsadmm_project_weighted.restype = ctypes.c_int
+    lib.hsadmm_project_weighted_compact.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp,
+                                                    vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_project_weighted_compact.restype = ctypes.c_int
     lib.hsadmm_residuals.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hsadmm_residuals.restype = ctypes.c_int
     lib.hsadmm_dual_inter.argtypes = [vp, vp, vp, vp, vp]
@@ -332,6 +336,21 @@ def hsadmm_project_weighted(plan: Plan, W_replicas: Sequence, U, Zg, Vd, Z, Wbar
                                      _ptr(mask), _ptr(sqnorm), _ptr(workspace), wb, _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_project_weighted")
+    return rc
+
+
+def hsadmm_project_weighted_compact(plan: Plan, W_replicas: Sequence, U, Zg, Vd, Z, Wbar, mask, sqnorm, packed,
+                                    layer_off, kept_idx, workspace, stream=None,
+                                    workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_project_weighted_compact(plan.handle, ptrs, R, _ptr(U), _ptr(Zg), _ptr(Vd), _ptr(Z), _ptr(Wbar),
+                                             _ptr(mask), _ptr(sqnorm), _ptr(packed), _ptr(layer_off),
+                                             _ptr(kept_idx), _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_project_weighted_compact")
     return rc
 
 

@@ -64,7 +64,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFixup, kAverage, kMaskDrift, kFixupGather, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFixup, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -76,6 +76,7 @@ struct hsadmm_plan {
     std::vector<WorkItem> items_proj;   // project kernels
     std::vector<WorkItem> items_rows;   // compact / expand kernels
     std::vector<WorkItem> items_fix;    // project_fixup, weighted_fixup: the row items of the FILTER layers
+    std::vector<WorkItem> items_rest;   // weighted_fixup_pack: the row items of all other layers
     std::vector<WorkItem> items_bfix;   // composite_fixup: the row items of the BOTH layers
     std::vector<WorkItem> items_wfinal; // weighted_final: CHANNEL tiles and BOTH rows (a subset of items_proj)
     std::vector<WorkItem> items_chan;   // channel_final: the row items of the CHANNEL layers (a subset of items_rows)
@@ -93,6 +94,7 @@ struct hsadmm_plan {
     WorkItem* d_items_proj = nullptr;
     WorkItem* d_items_rows = nullptr;
     WorkItem* d_items_fix = nullptr;
+    WorkItem* d_items_rest = nullptr;
     WorkItem* d_items_bfix = nullptr;
     WorkItem* d_items_wfinal = nullptr;
     WorkItem* d_items_chan = nullptr;
@@ -324,6 +326,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             cap = (cap + pack_align_elems - 1) / pack_align_elems * pack_align_elems;
             d.rows_item0 = (int32_t)p->items_rows.size();
             add_row_items(p->items_rows, l, d, x.mode);
+            if (x.mode != HSADMM_MODE_FILTER) add_row_items(p->items_rest, l, d, x.mode);
             d.rows_items = (int32_t)p->items_rows.size() - d.rows_item0;
             if (x.mode == HSADMM_MODE_CHANNEL) {
                 add_tile_items(p->items_proj, l, d, kChanRows);
@@ -399,6 +402,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     upload(p->items_proj, &p->d_items_proj);
     upload(p->items_rows, &p->d_items_rows);
     upload(p->items_fix, &p->d_items_fix);
+    upload(p->items_rest, &p->d_items_rest);
     upload(p->items_bfix, &p->d_items_bfix);
     upload(p->items_wfinal, &p->d_items_wfinal);
     upload(p->items_chan, &p->d_items_chan);
@@ -424,6 +428,7 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_items_proj) (void)hipFree(p->d_items_proj);
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
     if (p->d_items_fix) (void)hipFree(p->d_items_fix);
+    if (p->d_items_rest) (void)hipFree(p->d_items_rest);
     if (p->d_items_bfix) (void)hipFree(p->d_items_bfix);
     if (p->d_items_wfinal) (void)hipFree(p->d_items_wfinal);
     if (p->d_items_chan) (void)hipFree(p->d_items_chan);
@@ -686,11 +691,15 @@ int hsadmm_plan_set_node_weights(hsadmm_plan_t* p, const float* a, const float* 
     return HSADMM_OK;
 }
 
-int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
-                            const float* Zg, const float* Vd, float* Z, float* Wbar, uint8_t* mask, double* sqnorm,
-                            void* workspace, size_t workspace_bytes, void* hip_stream)
+static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
+                                 const float* Zg, const float* Vd, float* Z, float* Wbar, uint8_t* mask,
+                                 double* sqnorm, const CompactOut* out, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream)
 {
     if (!p || !W_replicas || !U || !Zg || !Vd || !Z || !mask || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (out && (!out->packed || !out->layer_off || !out->kept_idx || !is_aligned(out->packed, 16) ||
+                !is_aligned(out->layer_off, 8) || !is_aligned(out->kept_idx, 4)))
+        return HSADMM_ERR_INVALID_ARGUMENT;
     if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
     if (!is_aligned(U, 16) || !is_aligned(Z, 16) || !is_aligned(Zg, 16) || !is_aligned(Vd, 16) ||
@@ -721,7 +730,10 @@ int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replic
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     if (run_selection(p, w.p.key, w.p.colpart, Z, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
     const uint8_t* cm = mask;
-    if (!p->items_fix.empty()) {
+    // With a compaction to follow, the FILTER fix-up packs its kept rows as it forms them and shares its launch with
+    // the gather of the other layers' rows, which are final once weighted_final has run.
+    const bool fuse = out && !p->items_fix.empty();
+    if (!p->items_fix.empty() && !fuse) {
         e = launch(p, kWFixup, weighted_fixup, (unsigned)p->items_fix.size(), kBlock, s,
                    (const WorkItem*)p->d_items_fix, cm, U, Z, Zg, Vd, (const float*)p->d_coef);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
@@ -738,7 +750,44 @@ int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replic
         }
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
+    if (out) {
+        PackOut po{};
+        po.pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
+        po.cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
+        po.kept_idx = reinterpret_cast<const int32_t*>(ws + p->ws.kept_idx);
+        po.layer_off = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
+        po.packed = out->packed;
+        po.co = CopyOut{out->layer_off, out->kept_idx};
+        po.n_layers = (int)p->layers.size();
+        if (fuse)
+            e = launch(p, kWFixupPack, weighted_fixup_pack, (unsigned)(p->items_fix.size() + p->items_rest.size()),
+                       kBlock, s, (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), cm, U, Z, Zg, Vd,
+                       (const float*)p->d_coef, (const WorkItem*)p->d_items_rest, po);
+        else
+            e = launch(p, kGather, compact_gather<true>, (unsigned)p->items_rows.size(), kBlock, s,
+                       (const WorkItem*)p->d_items_rows, (const float*)Z, Vd, po.pos, po.cnt, po.kept_idx,
+                       po.n_layers, po.layer_off, po.packed, po.co);
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
     return HSADMM_OK;
+}
+
+int hsadmm_project_weighted(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
+                            const float* Zg, const float* Vd, float* Z, float* Wbar, uint8_t* mask, double* sqnorm,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return project_weighted_impl(p, W_replicas, R, U, Zg, Vd, Z, Wbar, mask, sqnorm, nullptr, workspace,
+                                 workspace_bytes, hip_stream);
+}
+
+int hsadmm_project_weighted_compact(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
+                                    const float* Zg, const float* Vd, float* Z, float* Wbar, uint8_t* mask,
+                                    double* sqnorm, float* packed, int64_t* layer_off, int32_t* kept_idx,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    const CompactOut out{packed, layer_off, kept_idx};
+    return project_weighted_impl(p, W_replicas, R, U, Zg, Vd, Z, Wbar, mask, sqnorm, &out, workspace,
+                                 workspace_bytes, hip_stream);
 }
 
 int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, const float* Zi,
@@ -918,6 +967,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kAverage: return "average";
         case kMaskDrift: return "mask_drift";
         case kFixupGather: return "fixup_gather";
+        case kWFixupPack: return "weighted_fixup_pack";
         default: return "";
     }
 }

@@ -18,7 +18,7 @@ constexpr int kWideRow = 2048;                  // rows at least this long are s
 constexpr int kChanRows = 64;               // CHANNEL tiles: rows per row block
 constexpr int kBothRows = 64;               // composite_colsums tiles: rows per row block
 constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
-constexpr int kVersion = 150;
+constexpr int kVersion = 160;
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -56,6 +56,26 @@ struct IndexMaps {
     int64_t* layer_off;  // L+1
     int32_t* kept_idx;   // groups_total
 };
+
+// Where the first work item of every layer copies the layer's part of the index mappings held in the workspace
+// (the caller's layer_off / kept_idx).
+struct CopyOut {
+    int64_t* layer_off;
+    int32_t* kept_idx;
+};
+
+// The whole 256-thread workgroup copies layer l's kept list and packed offset to the caller's buffers.
+__device__ __forceinline__ void copy_out_layer(int l, const int32_t* cnt, const int32_t* kept_idx, int n_layers,
+                                               const int64_t* layer_off, CopyOut co)
+{
+    const int start = cnt[n_layers + l];
+    const int nk = cnt[l] + cnt[2 * n_layers + l];
+    for (int i = threadIdx.x; i < nk; i += kBlock) co.kept_idx[start + i] = kept_idx[start + i];
+    if (threadIdx.x == 0) {
+        co.layer_off[l] = layer_off[l];
+        if (l == n_layers - 1) co.layer_off[n_layers] = layer_off[n_layers];
+    }
+}
 
 // One unit of work for a 256-thread workgroup; it carries everything the streaming kernels need,
 // so a workgroup starts with a single 64-byte scalar load.

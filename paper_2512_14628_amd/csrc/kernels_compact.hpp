@@ -168,13 +168,6 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
 
 // ------------------------------------------------------------------ compaction (gather)
 
-// Where the first work item of every layer copies the layer's part of the index mappings held in the workspace
-// (the caller's layer_off / kept_idx).
-struct CopyOut {
-    int64_t* layer_off;
-    int32_t* kept_idx;
-};
-
 // SUM: the source is the element-wise sum of two arenas (c = z_i + v_i, Section 4.4.1), formed on the fly.
 template <bool SUM>
 __device__ __forceinline__ void gather_item(const WorkItem& it, const float* src, const float* src1,
@@ -185,16 +178,7 @@ __device__ __forceinline__ void gather_item(const WorkItem& it, const float* src
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int row_len = it.row_len;
-    if (it.row0 == 0) {
-        const int l = it.layer;
-        const int start = cnt[n_layers + l];
-        const int nk = cnt[l] + cnt[2 * n_layers + l];
-        for (int i = threadIdx.x; i < nk; i += kBlock) co.kept_idx[start + i] = kept_idx[start + i];
-        if (threadIdx.x == 0) {
-            co.layer_off[l] = layer_off[l];
-            if (l == n_layers - 1) co.layer_off[n_layers] = layer_off[n_layers];
-        }
-    }
+    if (it.row0 == 0) copy_out_layer(it.layer, cnt, kept_idx, n_layers, layer_off, co);
     float* out = packed + layer_off[it.layer];
     if (!mode_has_channels(item_mode(it))) {
         const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
@@ -308,6 +292,22 @@ __global__ __launch_bounds__(kBlock) void fixup_gather(const WorkItem* __restric
     else
         gather_item<false>(row_items[(int)blockIdx.x - n_fix], Z, nullptr, pos, cnt, kept_idx, n_layers, layer_off,
                            packed, co);
+}
+
+// The weighted FILTER fix-up with its kept rows packed as they are formed, and the compaction c = Z + Vd of the
+// other layers' rows (final before this launch), in one launch: workgroups [0, n_fix) take the fix-up items, the
+// rest the row items of the layers that are not FILTER layers.
+__global__ __launch_bounds__(kBlock) void weighted_fixup_pack(const WorkItem* __restrict__ fix_items, int n_fix,
+                                                              const uint8_t* __restrict__ mask, float* U, float* Z,
+                                                              const float* __restrict__ Zg, const float* Vd,
+                                                              const float* __restrict__ coef,
+                                                              const WorkItem* __restrict__ rest_items, PackOut po)
+{
+    if ((int)blockIdx.x < n_fix)
+        weighted_fixup_rows<true>(fix_items[blockIdx.x], mask, U, Z, Zg, Vd, coef, po);
+    else
+        gather_item<true>(rest_items[(int)blockIdx.x - n_fix], Z, Vd, po.pos, po.cnt, po.kept_idx, po.n_layers,
+                          po.layer_off, po.packed, po.co);
 }
 
 // ------------------------------------------------------------------ expansion (zero fill + scatter)

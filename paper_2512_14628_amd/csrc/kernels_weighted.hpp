@@ -171,13 +171,23 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
 // FILTER layers once the mask is known (row items): Z holds t = Wbar + U and U the kept form.
 //   kept filter:   Z <- z~ = fl(fl(a t) + fl(b (Zg - Vd)))   (the arithmetic of wcand4, from the stashed t)
 //   pruned filter: U <- t (= U + (Wbar - 0) bit for bit), Z <- +0
-__global__ __launch_bounds__(kBlock) void weighted_fixup(const WorkItem* __restrict__ items,
-                                                         const uint8_t* __restrict__ mask,
-                                                         float* __restrict__ U, float* __restrict__ Z,
-                                                         const float* __restrict__ Zg, const float* __restrict__ Vd,
-                                                         const float* __restrict__ coef)
+// PACK: a kept row also goes to the packed buffer as c = z~ + Vd (the pre-transmission buffer z_i + v_i of Section
+// 4.4.1, which hsadmm_compact_sum would form from Z and Vd), at the row's rank under the selection's index mappings.
+struct PackOut {
+    const int32_t* pos;
+    const int32_t* cnt;
+    const int32_t* kept_idx;
+    const int64_t* layer_off;
+    float* packed;
+    CopyOut co;
+    int n_layers;
+};
+
+template <bool PACK>
+__device__ __forceinline__ void weighted_fixup_rows(const WorkItem& it, const uint8_t* mask, float* U, float* Z,
+                                                    const float* Zg, const float* Vd, const float* coef,
+                                                    const PackOut& po)
 {
-    const WorkItem it = items[blockIdx.x];
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
     const float al = coef[2 * it.layer], bl = coef[2 * it.layer + 1];
@@ -186,19 +196,29 @@ __global__ __launch_bounds__(kBlock) void weighted_fixup(const WorkItem* __restr
     const int sub = threadIdx.x / lpr;
     const int j = threadIdx.x - sub * lpr;
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    float* out = nullptr;
+    if (PACK) {
+        if (it.row0 == 0) copy_out_layer(it.layer, po.cnt, po.kept_idx, po.n_layers, po.layer_off, po.co);
+        out = po.packed + po.layer_off[it.layer];
+    }
     for (int rr = sub; rr < it.nr; rr += rows_at_once) {
         const bool keep = mask[it.g0 + rr] != 0;
         const int64_t base = it.base + (int64_t)rr * row_len;
+        float* d = nullptr;
+        if (PACK && keep) d = out + (int64_t)po.pos[it.g0 + rr] * row_len;
         if (vec) {
             const int nchunk = row_len >> 2;
             for (int c = j; c < nchunk; c += lpr) {
                 const int64_t e = base + ((int64_t)c << 2);
                 const v4f t = ld4(Z + e);
                 if (keep) {
-                    const v4f q = ld4(Zg + e) - ld4(Vd + e);
+                    const v4f vd = ld4(Vd + e);
+                    const v4f q = ld4(Zg + e) - vd;
                     const v4f at = t * al;
                     const v4f bq = q * bl;
-                    st4(Z + e, at + bq);
+                    const v4f z = at + bq;
+                    st4(Z + e, z);
+                    if (PACK) st4u(d + 4 * c, z + vd);
                 } else {
                     st4(U + e, t);
                     st4(Z + e, zero4);
@@ -209,10 +229,13 @@ __global__ __launch_bounds__(kBlock) void weighted_fixup(const WorkItem* __restr
                 const int64_t e = base + c;
                 const float t = ld1(Z + e);
                 if (keep) {
-                    const float q = ld1(Zg + e) - ld1(Vd + e);
+                    const float vd = ld1(Vd + e);
+                    const float q = ld1(Zg + e) - vd;
                     const float at = t * al;
                     const float bq = q * bl;
-                    st1(Z + e, at + bq);
+                    const float z = at + bq;
+                    st1(Z + e, z);
+                    if (PACK) d[c] = z + vd;
                 } else {
                     st1(U + e, t);
                     st1(Z + e, 0.f);
@@ -220,6 +243,15 @@ __global__ __launch_bounds__(kBlock) void weighted_fixup(const WorkItem* __restr
             }
         }
     }
+}
+
+__global__ __launch_bounds__(kBlock) void weighted_fixup(const WorkItem* __restrict__ items,
+                                                         const uint8_t* __restrict__ mask,
+                                                         float* __restrict__ U, float* __restrict__ Z,
+                                                         const float* __restrict__ Zg, const float* __restrict__ Vd,
+                                                         const float* __restrict__ coef)
+{
+    weighted_fixup_rows<false>(items[blockIdx.x], mask, U, Z, Zg, Vd, coef, PackOut{});
 }
 
 // CHANNEL and BOTH layers once the mask is known: everything is formed again from the inputs;

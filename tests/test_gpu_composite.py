@@ -133,6 +133,7 @@ def test_composite_weighted_step(R):
     a = rng.uniform(0.3, 1.0, L).astype(np.float32)
     b = rng.uniform(0.0, 0.7, L).astype(np.float32)
     _phase4_chain(wl, W, U, a, b, rng, want_wbar=(R % 2 == 0), want_sqnorm=(R != 4), fused_dual=(R in (2, 7)))
+    _phase4_chain(wl, W, U, a, b, rng, want_wbar=(R % 2 == 1), want_sqnorm=(R != 4), fused_dual=True, one_call=True)
 
 
 def test_composite_arbitrary_source_and_mask_and_cached_expand():

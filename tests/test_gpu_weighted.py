@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-def _phase4_chain(wl, W, U, a, b, rng, want_wbar=True, want_sqnorm=True, fused_dual=False):
+def _phase4_chain(wl, W, U, a, b, rng, want_wbar=True, want_sqnorm=True, fused_dual=False, one_call=False):
     import paper_2512_14628_amd as pkg
     from tests.gpu_harness import GpuRun, bits, min_relative_gap
     t = wl.table()
@@ -27,10 +27,15 @@ def _phase4_chain(wl, W, U, a, b, rng, want_wbar=True, want_sqnorm=True, fused_d
     dZg = torch.from_numpy(Zg).to(run.dev)
     dVd = torch.from_numpy(Vd).to(run.dev)
     pkg.hsadmm_plan_set_node_weights(run.plan, a, b)
-    pkg.hsadmm_project_weighted(run.plan, run.dW, run.dU, dZg, dVd, run.dZ, run.dWbar, run.dmask, run.dkey, run.ws)
-    # with fused_dual the compaction also runs without a mask, under the index mappings of the selection just made
-    pkg.hsadmm_compact_sum(run.plan, run.dZ, dVd, None if fused_dual else run.dmask, run.dpacked, run.doff, run.dkept,
-                           run.ws)
+    if one_call:
+        # projection and shrinkage of c = z_i + v_i through the call that does both
+        pkg.hsadmm_project_weighted_compact(run.plan, run.dW, run.dU, dZg, dVd, run.dZ, run.dWbar, run.dmask, run.dkey,
+                                            run.dpacked, run.doff, run.dkept, run.ws)
+    else:
+        pkg.hsadmm_project_weighted(run.plan, run.dW, run.dU, dZg, dVd, run.dZ, run.dWbar, run.dmask, run.dkey, run.ws)
+        # with fused_dual the compaction also runs without a mask, under the index mappings of the selection just made
+        pkg.hsadmm_compact_sum(run.plan, run.dZ, dVd, None if fused_dual else run.dmask, run.dpacked, run.doff,
+                               run.dkept, run.ws)
     if fused_dual:
         pkg.hsadmm_expand_dual(run.plan, run.dpacked, None, run.ddst, run.dZ, dVd, run.ws)
     else:
@@ -53,6 +58,7 @@ def _phase4_chain(wl, W, U, a, b, rng, want_wbar=True, want_sqnorm=True, fused_d
         assert np.array_equal(bits(gv[sl]), bits(v_new[sl])), "v " + l.name
     assert np.array_equal(gv[pad], Vd[pad])                               # padding untouched
     assert np.array_equal(got["layer_off"], refc["layer_off"])
+    assert np.array_equal(got["kept_idx"][:refc["kept_idx"].size], refc["kept_idx"])
     n = int(refc["layer_off"][-1])
     assert np.array_equal(bits(got["packed"][:n]), bits(refc["packed"]))
     run.close()
@@ -68,6 +74,7 @@ def test_weighted_step_on_named_workloads(name):
     a, b = oracle.node_coefficients([1.5e-3] * L, [1.5e-4] * L, 1e-4, 16, wl.R)
     _phase4_chain(wl, W, U, a, b, np.random.default_rng(1))
     _phase4_chain(wl, W, U, a, b, np.random.default_rng(1), fused_dual=True)
+    _phase4_chain(wl, W, U, a, b, np.random.default_rng(1), fused_dual=True, one_call=True)
 
 
 @pytest.mark.parametrize("R", [1, 2, 3, 4, 7, 8])
@@ -80,6 +87,8 @@ def test_weighted_ragged_shapes_layerwise_weights(R):
     a = rng.uniform(0.3, 1.0, L).astype(np.float32)
     b = rng.uniform(0.0, 0.7, L).astype(np.float32)
     _phase4_chain(wl, W, U, a, b, rng, want_wbar=(R % 2 == 0), want_sqnorm=(R % 3 != 0), fused_dual=(R % 2 == 1))
+    _phase4_chain(wl, W, U, a, b, rng, want_wbar=(R % 2 == 1), want_sqnorm=(R % 3 != 0), fused_dual=(R % 2 == 0),
+                  one_call=True)
 
 
 def test_default_weights_reproduce_the_base_projection():
@@ -101,6 +110,41 @@ def test_default_weights_reproduce_the_base_projection():
     b.close()
 
 
+@pytest.mark.parametrize("pack_align", [1, 7, 64])
+def test_weighted_one_call_equals_the_two_calls(pack_align):
+    """hsadmm_project_weighted_compact against hsadmm_project_weighted + hsadmm_compact_sum: every output, every bit
+    (also the alignment padding of the packed buffer, which neither touches), on layers of every mode."""
+    import paper_2512_14628_amd as pkg
+    from tests.gpu_harness import GpuRun
+    rng = np.random.default_rng(77 + pack_align)
+    shapes = [(70, 33, 9, wk.MODE_FILTER, 21), (10, 5, 1, wk.MODE_NONE, 10), (64, 48, 1, wk.MODE_CHANNEL, 17),
+              (300, 7, 1, wk.MODE_FILTER, 299), (40, 30, 4, wk.MODE_BOTH, 13, 11), (3, 5000, 1, wk.MODE_FILTER, 1),
+              (129, 130, 1, wk.MODE_FILTER, 64), (17, 3, 25, wk.MODE_FILTER, 17)]
+    wl = wk.custom_workload(shapes, R=3, seed=9, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    L = len(wl.layers)
+    a = rng.uniform(0.3, 1.0, L).astype(np.float32)
+    b = rng.uniform(0.0, 0.7, L).astype(np.float32)
+    Zg = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.05
+    Vd = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.01
+    outs = []
+    for one_call in (False, True):
+        r = GpuRun(wl, W, U, pack_align=pack_align)
+        dZg, dVd = torch.from_numpy(Zg).to(r.dev), torch.from_numpy(Vd).to(r.dev)
+        pkg.hsadmm_plan_set_node_weights(r.plan, a, b)
+        if one_call:
+            pkg.hsadmm_project_weighted_compact(r.plan, r.dW, r.dU, dZg, dVd, r.dZ, r.dWbar, r.dmask, r.dkey,
+                                                r.dpacked, r.doff, r.dkept, r.ws)
+        else:
+            pkg.hsadmm_project_weighted(r.plan, r.dW, r.dU, dZg, dVd, r.dZ, r.dWbar, r.dmask, r.dkey, r.ws)
+            pkg.hsadmm_compact_sum(r.plan, r.dZ, dVd, None, r.dpacked, r.doff, r.dkept, r.ws)
+        outs.append(r.outputs())
+        r.close()
+    for name in outs[0]:
+        assert np.array_equal(outs[0][name].view(np.uint8), outs[1][name].view(np.uint8)), name
+    assert int(outs[0]["layer_off"][-1]) > 0 and int(np.count_nonzero(outs[0]["mask"])) > 0
+
+
 def test_weighted_error_codes():
     import paper_2512_14628_amd as pkg
     from tests.gpu_harness import GpuRun
@@ -112,6 +156,13 @@ def test_weighted_error_codes():
     assert pkg.hsadmm_project_weighted(r.plan, r.dW, r.dU, z, z, r.dZ, None, r.dmask, None, r.ws[:256], check=False) == -2
     assert pkg.hsadmm_project_weighted(r.plan, r.dW * 17, r.dU, z, z, r.dZ, None, r.dmask, None, r.ws, check=False) == -4
     assert pkg.hsadmm_compact_sum(r.plan, r.dZ, None, r.dmask, r.dpacked, r.doff, r.dkept, r.ws, check=False) == -1
+    pwc = pkg.hsadmm_project_weighted_compact
+    assert pwc(r.plan, r.dW, r.dU, z, z, r.dZ, None, r.dmask, None, None, r.doff, r.dkept, r.ws, check=False) == -1
+    assert pwc(r.plan, r.dW, r.dU, z, z, r.dZ, None, r.dmask, None, r.dpacked, r.doff, None, r.ws, check=False) == -1
+    assert pwc(r.plan, r.dW, r.dU, z, None, r.dZ, None, r.dmask, None, r.dpacked, r.doff, r.dkept, r.ws,
+               check=False) == -1
+    assert pwc(r.plan, r.dW, r.dU, z, z, r.dZ, None, r.dmask, None, r.dpacked, r.doff, r.dkept, r.ws[:256],
+               check=False) == -2
     assert pkg.hsadmm_dual_inter(r.plan, r.dZ, None, z, check=False) == -1
     assert pkg.hsadmm_dual_inter(r.plan, r.dZ, z[1:], z, check=False) == -1
     assert pkg.hsadmm_expand_dual(r.plan, r.dpacked, r.dmask, r.ddst, None, z, r.ws, check=False) == -1
