@@ -25,6 +25,8 @@
 //   expand_scatter  dst <- zero fill + scatter of packed                      [Section 4.4.3]
 //   project_frozen  one pass under a given mask                               [Section 4.5]
 //   weighted_pass1 / weighted_fixup / weighted_final   the candidate of Eq. (9) with its rho_2 term
+//   weighted_fixup_pack   weighted_fixup that also packs c = z~ + v of its kept rows, and the gather of the
+//                   other layers' rows, in one launch (hsadmm_project_weighted_compact)   [Section 4.4.1]
 //   dual_inter_kernel  Eq. (13);  residual_partials / residual_finish  Section 3.4;  mask_or_kernel  Eq. (14)
 //
 // Nothing here is a dense contraction, so no MFMA is used; every kernel is bound by HBM traffic.
