@@ -176,6 +176,31 @@ int hsadmm_project_frozen(const hsadmm_plan_t* plan, const float* const* W_repli
                           float* U, float* Z, float* Wbar, const uint8_t* mask, void* hip_stream);
 
 /*
+ * The projection under a frozen mask and the tensor shrinkage of its result
+ * in one call (Section 4.5; Section 4.4.1, Eq. (15)): the same outputs, bit
+ * for bit, as hsadmm_project_frozen(...) followed by hsadmm_compact(plan, Z,
+ * mask, packed, layer_off, kept_idx, ...).  The kept rows of FILTER layers and
+ * the rows of MODE_NONE layers are written to the packed buffer by the pass
+ * that forms them (Z is not read again for them); the rows of CHANNEL and
+ * BOTH layers are gathered from Z by a second launch.
+ *   mappings_cached  0: the index mappings are derived from the mask first
+ *                    (as hsadmm_compact does when given a mask);
+ *                    nonzero: the workspace already holds the index mappings
+ *                    of THIS mask (left there by an earlier hsadmm_compact,
+ *                    hsadmm_expand or hsadmm_project_frozen_compact that was
+ *                    given it) and they are reused, as a frozen mask's cached
+ *                    index sets are from iteration to iteration (Section 4.5).
+ *                    With the mappings of another mask the packed buffer is
+ *                    unspecified (no access leaves it).
+ * Other arguments, alignment, ownership and errors as for
+ * hsadmm_project_frozen and hsadmm_compact.
+ */
+int hsadmm_project_frozen_compact(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                                  float* U, float* Z, float* Wbar, const uint8_t* mask, int32_t mappings_cached,
+                                  float* packed, int64_t* layer_off, int32_t* kept_idx,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Bitwise mask synchronisation on one device (Section 4.3, Eq. (14)):
  * out[g] = 1 if any of the M masks has a nonzero byte at g, else 0.
  *   masks  HOST array of M DEVICE pointers (1 <= M <= HSADMM_MAX_MASKS), each groups_total bytes

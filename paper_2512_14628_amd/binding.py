@@ -32,7 +32,7 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_project_frozen", "hsadmm_mask_or", "hsadmm_compact_sum", "hsadmm_node_coefficients",
            "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals",
            "hsadmm_average", "hsadmm_mask_drift", "hsadmm_expand_dual", "hsadmm_project_compact",
-           "hsadmm_project_weighted_compact")
+           "hsadmm_project_weighted_compact", "hsadmm_project_frozen_compact")
 KERNEL_COUNT = 21
 
 
@@ -92,6 +92,9 @@ def load_library():
     lib.hsadmm_project_compact.restype = ctypes.c_int
     lib.hsadmm_project_frozen.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp]
     lib.hsadmm_project_frozen.restype = ctypes.c_int
+    lib.hsadmm_project_frozen_compact.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp,
+                                                  ctypes.c_int32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_project_frozen_compact.restype = ctypes.c_int
     lib.hsadmm_mask_or.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp]
     lib.hsadmm_mask_or.restype = ctypes.c_int
     lib.hsadmm_expand_dual.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -268,6 +271,21 @@ def hsadmm_project_frozen(plan: Plan, W_replicas: Sequence, U, Z, Wbar, mask, st
     rc = lib.hsadmm_project_frozen(plan.handle, ptrs, R, _ptr(U), _ptr(Z), _ptr(Wbar), _ptr(mask), _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_project_frozen")
+    return rc
+
+
+def hsadmm_project_frozen_compact(plan: Plan, W_replicas: Sequence, U, Z, Wbar, mask, mappings_cached: bool, packed,
+                                  layer_off, kept_idx, workspace, stream=None, workspace_bytes: Optional[int] = None,
+                                  check: bool = True) -> int:
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_project_frozen_compact(plan.handle, ptrs, R, _ptr(U), _ptr(Z), _ptr(Wbar), _ptr(mask),
+                                           1 if mappings_cached else 0, _ptr(packed), _ptr(layer_off),
+                                           _ptr(kept_idx), _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_project_frozen_compact")
     return rc
 
 

@@ -79,6 +79,7 @@ struct hsadmm_plan {
     std::vector<WorkItem> items_rows;   // compact / expand kernels
     std::vector<WorkItem> items_fix;    // project_fixup, weighted_fixup: the row items of the FILTER layers
     std::vector<WorkItem> items_rest;   // weighted_fixup_pack: the row items of all other layers
+    std::vector<WorkItem> items_cols;   // hsadmm_project_frozen_compact: the row items of the CHANNEL and BOTH layers
     std::vector<WorkItem> items_bfix;   // composite_fixup: the row items of the BOTH layers
     std::vector<WorkItem> items_wfinal; // weighted_final: CHANNEL tiles and BOTH rows (a subset of items_proj)
     std::vector<WorkItem> items_chan;   // channel_final: the row items of the CHANNEL layers (a subset of items_rows)
@@ -97,6 +98,7 @@ struct hsadmm_plan {
     WorkItem* d_items_rows = nullptr;
     WorkItem* d_items_fix = nullptr;
     WorkItem* d_items_rest = nullptr;
+    WorkItem* d_items_cols = nullptr;
     WorkItem* d_items_bfix = nullptr;
     WorkItem* d_items_wfinal = nullptr;
     WorkItem* d_items_chan = nullptr;
@@ -212,7 +214,16 @@ template <int R>
 hipError_t launch_frozen(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, const uint8_t* mask, hipStream_t s)
 {
     return launch(p, kFrozen, project_frozen<R>, (unsigned)p->items_rows.size(), kBlock, s,
-                  (const WorkItem*)p->d_items_rows, a, Rrt, mask);
+                  (const WorkItem*)p->d_items_rows, a, Rrt, mask, PackOut{});
+}
+
+// The same pass with the kept rows of FILTER layers and the rows of NONE layers packed as they are formed.
+template <int R>
+hipError_t launch_frozen_pack(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, const uint8_t* mask,
+                              const PackOut& po, hipStream_t s)
+{
+    return launch(p, kFrozen, project_frozen<R, true>, (unsigned)p->items_rows.size(), kBlock, s,
+                  (const WorkItem*)p->d_items_rows, a, Rrt, mask, po);
 }
 
 // Final Z / U of the CHANNEL layers under the mask just selected (same kernel, their row items only).
@@ -220,7 +231,7 @@ template <int R>
 hipError_t launch_channel_final(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, const uint8_t* mask, hipStream_t s)
 {
     return launch(p, kChanFinal, project_frozen<R>, (unsigned)p->items_chan.size(), kBlock, s,
-                  (const WorkItem*)p->d_items_chan, a, Rrt, mask);
+                  (const WorkItem*)p->d_items_chan, a, Rrt, mask, PackOut{});
 }
 // Per-layer selection once the keys (FILTER, and the filters of BOTH) or the partial column sums
 // (CHANNEL) are in place.  Layers under both constraints then take their second projection: channel
@@ -329,6 +340,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             d.rows_item0 = (int32_t)p->items_rows.size();
             add_row_items(p->items_rows, l, d, x.mode);
             if (x.mode != HSADMM_MODE_FILTER) add_row_items(p->items_rest, l, d, x.mode);
+            if (has_colsums) add_row_items(p->items_cols, l, d, x.mode);
             d.rows_items = (int32_t)p->items_rows.size() - d.rows_item0;
             if (x.mode == HSADMM_MODE_CHANNEL) {
                 add_tile_items(p->items_proj, l, d, kChanRows);
@@ -405,6 +417,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     upload(p->items_rows, &p->d_items_rows);
     upload(p->items_fix, &p->d_items_fix);
     upload(p->items_rest, &p->d_items_rest);
+    upload(p->items_cols, &p->d_items_cols);
     upload(p->items_bfix, &p->d_items_bfix);
     upload(p->items_wfinal, &p->d_items_wfinal);
     upload(p->items_chan, &p->d_items_chan);
@@ -431,6 +444,7 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
     if (p->d_items_fix) (void)hipFree(p->d_items_fix);
     if (p->d_items_rest) (void)hipFree(p->d_items_rest);
+    if (p->d_items_cols) (void)hipFree(p->d_items_cols);
     if (p->d_items_bfix) (void)hipFree(p->d_items_bfix);
     if (p->d_items_wfinal) (void)hipFree(p->d_items_wfinal);
     if (p->d_items_chan) (void)hipFree(p->d_items_chan);
@@ -579,6 +593,59 @@ int hsadmm_project_frozen(const hsadmm_plan_t* p, const float* const* W_replicas
         default: e = launch_frozen<0>(p, a, R, mask, s); break;
     }
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
+int hsadmm_project_frozen_compact(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
+                                  float* Z, float* Wbar, const uint8_t* mask, int32_t mappings_cached, float* packed,
+                                  int64_t* layer_off, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream)
+{
+    if (!p || !W_replicas || !U || !Z || !mask || !packed || !layer_off || !kept_idx || !workspace || R < 1)
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
+    if (!is_aligned(U, 16) || !is_aligned(Z, 16) || (Wbar && !is_aligned(Wbar, 16)) || !is_aligned(packed, 16) ||
+        !is_aligned(layer_off, 8) || !is_aligned(kept_idx, 4) || !is_aligned(workspace, 256))
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    for (int r = 0; r < R; ++r)
+        if (!W_replicas[r] || !is_aligned(W_replicas[r], 16)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    if (!mappings_cached) {
+        const int rc = run_scan(p, mask, ws, s);
+        if (rc != HSADMM_OK) return rc;
+    }
+    ProjectArgs a{};
+    for (int r = 0; r < R; ++r) a.W[r] = W_replicas[r];
+    a.U = U; a.Z = Z; a.Wbar = Wbar;
+    a.inv_R = 1.0f / (float)R;
+    PackOut po{};
+    po.pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
+    po.cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
+    po.kept_idx = reinterpret_cast<const int32_t*>(ws + p->ws.kept_idx);
+    po.layer_off = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
+    po.packed = packed;
+    po.co = CopyOut{layer_off, kept_idx};
+    po.n_layers = (int)p->layers.size();
+    hipError_t e;
+    switch (R) {
+        case 1: e = launch_frozen_pack<1>(p, a, R, mask, po, s); break;
+        case 2: e = launch_frozen_pack<2>(p, a, R, mask, po, s); break;
+        case 3: e = launch_frozen_pack<3>(p, a, R, mask, po, s); break;
+        case 4: e = launch_frozen_pack<4>(p, a, R, mask, po, s); break;
+        case 8: e = launch_frozen_pack<8>(p, a, R, mask, po, s); break;
+        default: e = launch_frozen_pack<0>(p, a, R, mask, po, s); break;
+    }
+    if (e != hipSuccess) return HSADMM_ERR_HIP;
+    if (!p->items_cols.empty()) {
+        // rows that keep a subset of their columns: gathered from the Z just written
+        e = launch(p, kGather, compact_gather<false>, (unsigned)p->items_cols.size(), kBlock, s,
+                   (const WorkItem*)p->d_items_cols, (const float*)Z, (const float*)nullptr, po.pos, po.cnt,
+                   po.kept_idx, po.n_layers, po.layer_off, packed, po.co);
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
+    return HSADMM_OK;
 }
 
 int hsadmm_mask_or(const hsadmm_plan_t* p, const uint8_t* const* masks, int32_t M, uint8_t* out, void* hip_stream)

@@ -64,6 +64,18 @@ struct CopyOut {
     int32_t* kept_idx;
 };
 
+// What a kernel needs to pack rows as it forms them: the index mappings (in the workspace), the packed buffer
+// and where the caller wants its copies of layer_off / kept_idx.
+struct PackOut {
+    const int32_t* pos;
+    const int32_t* cnt;
+    const int32_t* kept_idx;
+    const int64_t* layer_off;
+    float* packed;
+    CopyOut co;
+    int n_layers;
+};
+
 // The whole 256-thread workgroup copies layer l's kept list and packed offset to the caller's buffers.
 __device__ __forceinline__ void copy_out_layer(int l, const int32_t* cnt, const int32_t* kept_idx, int n_layers,
                                                const int64_t* layer_off, CopyOut co)

@@ -10,8 +10,10 @@ namespace {
 
 // Final values of 4 adjacent elements under a known mask (Algorithm 1 Phase 3, retraining branch:
 // z = z~ (.) m): kept element Z = V, U += Wbar - V; masked-out element Z = +0, U = U + Wbar (= V).
-template <int R>
-__device__ __forceinline__ void frozen4(const ProjectArgs& a, int Rrt, int64_t e, bool k0, bool k1, bool k2, bool k3)
+// PACK: d, when not null, is where the 4 elements go in the packed buffer (rows packed whole).
+template <int R, bool PACK = false>
+__device__ __forceinline__ void frozen4(const ProjectArgs& a, int Rrt, int64_t e, bool k0, bool k1, bool k2, bool k3,
+                                        float* d = nullptr)
 {
     const int RR = R > 0 ? R : Rrt;
     v4f s = ld4(a.W[0] + e);
@@ -25,11 +27,13 @@ __device__ __forceinline__ void frozen4(const ProjectArgs& a, int Rrt, int64_t e
     st4(a.Z + e, z);
     st4(a.U + e, u + (wb - z));
     if (a.Wbar) st4(a.Wbar + e, wb);
+    if (PACK && d) st4u(d, z);
 }
 
 // two chunks of one row (same keep flag) with all loads issued before any store
-template <int R>
-__device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, bool keep)
+template <int R, bool PACK = false>
+__device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, bool keep,
+                                          float* d0 = nullptr, float* d1 = nullptr)
 {
     const int RR = R > 0 ? R : Rrt;
     v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
@@ -49,10 +53,11 @@ __device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t
     st4(a.U + e0, u0 + (wb0 - z0));
     st4(a.U + e1, u1 + (wb1 - z1));
     if (a.Wbar) { st4(a.Wbar + e0, wb0); st4(a.Wbar + e1, wb1); }
+    if (PACK && d0) { st4u(d0, z0); st4u(d1, z1); }
 }
 
-template <int R>
-__device__ __forceinline__ void frozen1(const ProjectArgs& a, int Rrt, int64_t e, bool keep)
+template <int R, bool PACK = false>
+__device__ __forceinline__ void frozen1(const ProjectArgs& a, int Rrt, int64_t e, bool keep, float* d = nullptr)
 {
     const int RR = R > 0 ? R : Rrt;
     float s = ld1(a.W[0] + e);
@@ -65,15 +70,18 @@ __device__ __forceinline__ void frozen1(const ProjectArgs& a, int Rrt, int64_t e
     st1(a.Z + e, z);
     st1(a.U + e, u + (wb - z));
     if (a.Wbar) st1(a.Wbar + e, wb);
+    if (PACK && d) *d = z;
 }
 
 // Row items of every mode (the compact / expand item table): no keys, no second pass, every byte of the
 // replicas and of U is read once and Z and U are written once, streaming along the rows.  FILTER / NONE rows
 // share one keep flag; in CHANNEL rows and in the kept filters' rows of a BOTH layer every column takes the
 // flag of its channel.
-template <int R>
+// PACK: kept FILTER rows and the rows of NONE layers also go to the packed buffer as they are formed, at their
+// rank under the index mappings of this mask (po); the rows of CHANNEL and BOTH layers are left to a gather.
+template <int R, bool PACK = false>
 __global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
-                                                         const uint8_t* __restrict__ mask)
+                                                         const uint8_t* __restrict__ mask, PackOut po)
 {
     const WorkItem it = items[blockIdx.x];
     const int mode = item_mode(it);
@@ -87,6 +95,11 @@ __global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restr
     // channel bytes of the layer (CHANNEL row item: g0 is the layer's first group)
     const uint8_t* mc = mask + (mode == HSADMM_MODE_BOTH ? it.aux : (int64_t)it.g0);
     const DivKhw div(it.khw);
+    float* out = nullptr;
+    if (PACK && !columns) {
+        if (it.row0 == 0) copy_out_layer(it.layer, po.cnt, po.kept_idx, po.n_layers, po.layer_off, po.co);
+        out = po.packed + po.layer_off[it.layer];
+    }
     for (int rr = sub; rr < it.nr; rr += rows_at_once) {
         const bool keep = mode == HSADMM_MODE_NONE || mode == HSADMM_MODE_CHANNEL || mask[it.g0 + rr] != 0;
         const int64_t base = it.base + (int64_t)rr * row_len;
@@ -104,14 +117,21 @@ __global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restr
             }
             continue;
         }
+        // a kept row of a FILTER or NONE layer is packed whole, at its rank (NONE: its own index)
+        float* d = nullptr;
+        if (PACK && !columns && keep) {
+            const int p = mode == HSADMM_MODE_NONE ? it.row0 + rr : po.pos[it.g0 + rr];
+            if (p >= 0) d = out + (int64_t)p * row_len;     // (mappings of another mask: the row is left out)
+        }
         if (vec) {
             const int nchunk = row_len >> 2;
             int c = j;
             for (; c + lpr < nchunk; c += 2 * lpr)
-                frozen4x2<R>(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + lpr) << 2), keep);
-            if (c < nchunk) frozen4<R>(a, Rrt, base + ((int64_t)c << 2), keep, keep, keep, keep);
+                frozen4x2<R, PACK>(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + lpr) << 2), keep,
+                                   d ? d + 4 * c : nullptr, d ? d + 4 * (c + lpr) : nullptr);
+            if (c < nchunk) frozen4<R, PACK>(a, Rrt, base + ((int64_t)c << 2), keep, keep, keep, keep, d ? d + 4 * c : nullptr);
         } else {
-            for (int c = j; c < row_len; c += lpr) frozen1<R>(a, Rrt, base + c, keep);
+            for (int c = j; c < row_len; c += lpr) frozen1<R, PACK>(a, Rrt, base + c, keep, d ? d + c : nullptr);
         }
     }
 }

@@ -173,16 +173,6 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
 //   pruned filter: U <- t (= U + (Wbar - 0) bit for bit), Z <- +0
 // PACK: a kept row also goes to the packed buffer as c = z~ + Vd (the pre-transmission buffer z_i + v_i of Section
 // 4.4.1, which hsadmm_compact_sum would form from Z and Vd), at the row's rank under the selection's index mappings.
-struct PackOut {
-    const int32_t* pos;
-    const int32_t* cnt;
-    const int32_t* kept_idx;
-    const int64_t* layer_off;
-    float* packed;
-    CopyOut co;
-    int n_layers;
-};
-
 template <bool PACK>
 __device__ __forceinline__ void weighted_fixup_rows(const WorkItem& it, const uint8_t* mask, float* U, float* Z,
                                                     const float* Zg, const float* Vd, const float* coef,

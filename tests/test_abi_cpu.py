@@ -85,6 +85,8 @@ def test_hot_calls_reject_null_plan(lib):
     assert lib.hsadmm_compact(None, None, None, None, None, None, None, 0, None) == -1
     assert lib.hsadmm_expand(None, None, None, None, None, 0, None) == -1
     assert lib.hsadmm_project_frozen(None, None, 1, None, None, None, None, None) == -1
+    assert lib.hsadmm_project_frozen_compact(None, None, 1, None, None, None, None, 0, None, None, None, None, 0,
+                                             None) == -1
     assert lib.hsadmm_mask_or(None, None, 1, None, None) == -1
     assert lib.hsadmm_average(None, None, 1, 0, None, None) == -1
     assert lib.hsadmm_dual_inter(None, None, None, None, None) == -1

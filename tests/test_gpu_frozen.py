@@ -32,6 +32,24 @@ def _check_frozen(wl, W, U, mask_np, want_wbar=True):
     n = int(refc["layer_off"][-1])
     assert np.array_equal(bits(got["packed"][:n]), bits(refc["packed"]))
     run.close()
+    # the call that projects and compacts in one go: every output, every bit, as the two calls; first deriving the
+    # index mappings from the mask, then reusing the ones an earlier call left in the workspace
+    for cached in (False, True):
+        r2 = GpuRun(wl, W, U, want_wbar=want_wbar)
+        dm2 = torch.from_numpy(mask_np).to(r2.dev)
+        if cached:
+            pkg.hsadmm_expand(r2.plan, r2.dpacked, dm2, r2.ddst, r2.ws)         # leaves this mask's mappings
+            r2.ddst.fill_(float("nan"))
+        pkg.hsadmm_project_frozen_compact(r2.plan, r2.dW, r2.dU, r2.dZ, r2.dWbar, dm2, cached, r2.dpacked, r2.doff,
+                                          r2.dkept, r2.ws)
+        pkg.hsadmm_expand(r2.plan, r2.dpacked, None, r2.ddst, r2.ws)
+        got2 = r2.outputs()
+        for name in got:
+            if name == "mask":
+                continue                                                         # the harness's own mask buffer: unused
+            assert np.array_equal(got[name].view(np.uint8), got2[name].view(np.uint8)), \
+                "one call (cached=%s): %s" % (cached, name)
+        r2.close()
 
 
 @pytest.mark.parametrize("name", ["tiny", "resnet18", "resnet50", "resnet152"])
@@ -98,6 +116,17 @@ def test_frozen_error_codes():
     assert pkg.hsadmm_project_frozen(run.plan, run.dW, run.dU, run.dZ, None, None, check=False) == -1
     assert pkg.hsadmm_project_frozen(run.plan, [], run.dU, run.dZ, None, run.dmask, check=False) == -1
     assert pkg.hsadmm_project_frozen(run.plan, run.dW * 17, run.dU, run.dZ, None, run.dmask, check=False) == -4
+    pfc = pkg.hsadmm_project_frozen_compact
+    assert pfc(run.plan, run.dW, run.dU, run.dZ, None, None, False, run.dpacked, run.doff, run.dkept, run.ws,
+               check=False) == -1
+    assert pfc(run.plan, run.dW, run.dU, run.dZ, None, run.dmask, False, None, run.doff, run.dkept, run.ws,
+               check=False) == -1
+    assert pfc(run.plan, run.dW, run.dU, run.dZ, None, run.dmask, False, run.dpacked, run.doff, run.dkept, None,
+               workspace_bytes=1 << 30, check=False) == -1
+    assert pfc(run.plan, run.dW, run.dU, run.dZ, None, run.dmask, False, run.dpacked, run.doff, run.dkept,
+               run.ws[:256], check=False) == -2
+    assert pfc(run.plan, run.dW * 17, run.dU, run.dZ, None, run.dmask, False, run.dpacked, run.doff, run.dkept,
+               run.ws, check=False) == -4
     assert pkg.hsadmm_mask_or(run.plan, [], run.dmask, check=False) == -1
     assert pkg.hsadmm_mask_or(run.plan, [run.dmask] * 65, run.dmask, check=False) == -4
     assert pkg.hsadmm_mask_or(run.plan, [run.dmask, None], run.dmask, check=False) == -1
