@@ -23,7 +23,8 @@
 //   fixup_gather    project_fixup and compact_gather of Z in one launch (hsadmm_project_compact): the
 //                   first rewrites pruned rows only, the second reads kept rows only.
 //   expand_scatter  dst <- zero fill + scatter of packed                      [Section 4.4.3]
-//   project_frozen  one pass under a given mask                               [Section 4.5]
+//   project_frozen  one pass under a given mask; as project_frozen<R, true> it also packs the kept rows of
+//                   FILTER layers and the rows of unconstrained layers (hsadmm_project_frozen_compact)  [Section 4.5]
 //   weighted_pass1 / weighted_fixup / weighted_final   the candidate of Eq. (9) with its rho_2 term
 //   weighted_fixup_pack   weighted_fixup that also packs c = z~ + v of its kept rows, and the gather of the
 //                   other layers' rows, in one launch (hsadmm_project_weighted_compact)   [Section 4.4.1]
