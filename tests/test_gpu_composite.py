@@ -38,6 +38,18 @@ def test_composite_ragged_shapes(R):
     _run(wl, pack_align=(1, 4, 7)[R % 3], want_wbar=(R % 2 == 0), want_sqnorm=(R % 3 != 0))
 
 
+@pytest.mark.parametrize("pack_align", [1, 5])
+def test_composite_and_filter_layers_without_channel_layers(pack_align):
+    """No CHANNEL layer: hsadmm_project_compact then runs the FILTER fix-up and the gather (also of the BOTH layers'
+    rows, repaired by the launch before) in one launch; _run compares it with the two calls and with the oracle."""
+    from tests.test_gpu_parity import _run
+    shapes = [(70, 33, 9, wk.MODE_FILTER, 21), (40, 30, 4, BOTH, 13, 11), (10, 5, 1, wk.MODE_NONE, 10),
+              (300, 7, 1, wk.MODE_FILTER, 299), (129, 130, 1, BOTH, 64, 100), (3, 5000, 1, wk.MODE_FILTER, 1),
+              (64, 64, 9, BOTH, 1, 64), (17, 3, 25, wk.MODE_FILTER, 17), (256, 96, 1, BOTH, 200, 1)]
+    wl = wk.custom_workload(shapes, R=3, seed=21, sigma_replica=0.03)
+    _run(wl, pack_align=pack_align)
+
+
 def test_composite_degenerate_layers():
     """1 x 1 layers, everything kept, one filter / one channel kept, a single column, a single row, rows longer than
     a workgroup's span, more groups than one scan block, a 3-channel stem."""
