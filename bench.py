@@ -6,7 +6,8 @@ replicas, candidate, group norms, top-k projection, dual update), the compaction
 expansion (zero fill + scatter back), issued back to back on one stream with every buffer already resident in
 HBM.  Projection and compaction go through hsadmm_project_compact, which does the work of hsadmm_project followed
 by hsadmm_compact with the repair of pruned groups and the gather of kept groups in one launch
-(--separate-calls: the two calls); then hsadmm_expand.
+(--separate-calls: the two calls); then hsadmm_expand.  The same step issued as the three calls hsadmm_project,
+hsadmm_compact, hsadmm_expand is timed as well (`three_calls_step`).
 
 Prints ONE JSON line.  `value` is algorithmic bytes per second for the whole step (each unique input
 read once, each output written once: 4n(R+4) + 12 n_kept bytes); `roofline` prices the dominant kernel
@@ -153,6 +154,27 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     gbps = bytes_["step"] / (elapsed / args.steps) / 1e9
     params_per_s = wl.n_total / (elapsed / args.steps)
+
+    # ---- the same step as the three calls hsadmm_project, hsadmm_compact, hsadmm_expand (identical outputs; the
+    #      fix-up and the gather are then launches of their own), timed the same way
+    three_calls = None
+    if one_call:
+        def step3():
+            b = sets[counter[0] % nsets]
+            counter[0] += 1
+            pkg.hsadmm_project(plan, b.W, b.U, b.Z, None, b.mask, None, b.ws, stream=stream)
+            pkg.hsadmm_compact(plan, b.Z, None, b.packed, b.off, b.kept, b.ws, stream=stream)
+            pkg.hsadmm_expand(plan, b.packed, b.mask if args.expand_rescan else None, b.dst, b.ws, stream=stream)
+        for _ in range(max(3, args.warmup // 2)):
+            step3()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(args.steps):
+            step3()
+        torch.cuda.synchronize()
+        e3 = (time.perf_counter() - t3) / args.steps
+        three_calls = {"ms_per_step": round(1e3 * e3, 4), "value_GBps": round(bytes_["step"] / e3 / 1e9, 1),
+                       "hbm_frac": round(bytes_["step"] / e3 / 1e9 / HBM_PEAK_GBPS, 4)}
 
     # ---- distribution over steps (median, min) and every call timed alone: HIP events on the stream the calls use
     def timed_us(fn, reps):
@@ -484,6 +506,7 @@ def main():
         "kernel_launches_per_step": launches_per_step,
         "kernel_us_per_step_sum": round(sum(kernel_us_per_step.values()), 2),
         "copy_GBps": round(copy_gbps, 1),
+        "three_calls_step": three_calls,
         "frozen_mask_step": frozen,
         "weighted_step": weighted,
         "residuals": residuals,
