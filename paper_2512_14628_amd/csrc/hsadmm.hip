@@ -14,8 +14,9 @@
 //                   without a mask.                                          [Eq. (10)]
 //   project_fixup   touches pruned groups only: U <- V (taken from Z), Z <- +0.  For a pruned
 //                   group U + (Wbar - 0) equals V bit for bit, so no replica is read again.
-//   channel_final   CHANNEL layers: pass 1 only sums; their Z and U are written here, in one streaming
-//                   pass under the mask just selected (the kernel of the frozen-mask path).
+//   channel_final   CHANNEL layers: pass 1 only sums (and, with 3 or more replicas, parks their mean in Z);
+//                   their Z and U are written here, in one streaming pass under the mask just selected
+//                   (the kernel of the frozen-mask path, reading the parked mean instead of the replicas).
 //   composite_colsums   layers under both constraints: channel norms over the kept filters, then a
 //                   second select_topk for the channels.   [Section 3, paragraph after Eq. (10)]
 //   scan_mask       index mappings from a given mask: kept counts, positions, kept_idx, layer_off.
@@ -227,7 +228,8 @@ hipError_t launch_frozen_pack(const hsadmm_plan* p, const ProjectArgs& a, int Rr
                   (const WorkItem*)p->d_items_rows, a, Rrt, mask, po);
 }
 
-// Final Z / U of the CHANNEL layers under the mask just selected (same kernel, their row items only).
+// Final Z / U of the CHANNEL layers under the mask just selected: the frozen-mask kernel over their row items.
+// With 3 or more replicas pass 1 has parked their mean in Z and it is read from there (R = kMeanInZ).
 template <int R>
 hipError_t launch_channel_final(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, const uint8_t* mask, hipStream_t s)
 {
@@ -499,6 +501,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     a.key = sqnorm ? sqnorm : reinterpret_cast<double*>(ws + p->ws.key);
     a.colpart = reinterpret_cast<double*>(ws + p->ws.colpart);
     a.inv_R = 1.0f / (float)R;
+    a.park_mean = R >= 3 ? 1 : 0;
     hipError_t e;
     switch (R) {
         case 1: e = launch_pass1<1>(p, a, R, s); break;
@@ -526,13 +529,10 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     }
     if (!p->items_chan.empty()) {
         const uint8_t* cm = mask;
-        switch (R) {
+        switch (a.park_mean ? 0 : R) {
+            case 0: e = launch_channel_final<kMeanInZ>(p, a, R, cm, s); break;
             case 1: e = launch_channel_final<1>(p, a, R, cm, s); break;
-            case 2: e = launch_channel_final<2>(p, a, R, cm, s); break;
-            case 3: e = launch_channel_final<3>(p, a, R, cm, s); break;
-            case 4: e = launch_channel_final<4>(p, a, R, cm, s); break;
-            case 8: e = launch_channel_final<8>(p, a, R, cm, s); break;
-            default: e = launch_channel_final<0>(p, a, R, cm, s); break;
+            default: e = launch_channel_final<2>(p, a, R, cm, s); break;
         }
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }

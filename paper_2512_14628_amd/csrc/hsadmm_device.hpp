@@ -123,6 +123,7 @@ struct ProjectArgs {
     double* key;      // groups_total
     double* colpart;  // CHANNEL partial column sums
     float inv_R;
+    int park_mean;    // pass 1 parks the mean of a CHANNEL layer's replicas in Z (read back by channel_final)
 };
 
 // Streaming (touch-once) accesses.

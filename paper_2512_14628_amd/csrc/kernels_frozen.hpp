@@ -8,6 +8,9 @@ namespace {
 
 // ------------------------------------------------------------------ project under a frozen mask
 
+// R = kMeanInZ: the mean of the replicas is not formed here but read from Z, where pass 1 parked it.
+constexpr int kMeanInZ = -1;
+
 // Final values of 4 adjacent elements under a known mask (Algorithm 1 Phase 3, retraining branch:
 // z = z~ (.) m): kept element Z = V, U += Wbar - V; masked-out element Z = +0, U = U + Wbar (= V).
 // PACK: d, when not null, is where the 4 elements go in the packed buffer (rows packed whole).
@@ -15,12 +18,17 @@ template <int R, bool PACK = false>
 __device__ __forceinline__ void frozen4(const ProjectArgs& a, int Rrt, int64_t e, bool k0, bool k1, bool k2, bool k3,
                                         float* d = nullptr)
 {
-    const int RR = R > 0 ? R : Rrt;
-    v4f s = ld4(a.W[0] + e);
+    v4f wb;
+    if (R == kMeanInZ) {
+        wb = ld4(a.Z + e);
+    } else {
+        const int RR = R > 0 ? R : Rrt;
+        v4f s = ld4(a.W[0] + e);
 #pragma unroll
-    for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+        for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+        wb = s * a.inv_R;
+    }
     const v4f u = ld4(a.U + e);
-    const v4f wb = s * a.inv_R;
     const v4f v = wb + u;
     v4f z;
     z.x = k0 ? v.x : 0.f; z.y = k1 ? v.y : 0.f; z.z = k2 ? v.z : 0.f; z.w = k3 ? v.w : 0.f;
@@ -35,16 +43,23 @@ template <int R, bool PACK = false>
 __device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, bool keep,
                                           float* d0 = nullptr, float* d1 = nullptr)
 {
-    const int RR = R > 0 ? R : Rrt;
-    v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
+    v4f wb0, wb1;
+    if (R == kMeanInZ) {
+        wb0 = ld4(a.Z + e0);
+        wb1 = ld4(a.Z + e1);
+    } else {
+        const int RR = R > 0 ? R : Rrt;
+        v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
 #pragma unroll
-    for (int r = 1; r < RR; ++r) {
-        const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
-        s0 = s0 + w0;
-        s1 = s1 + w1;
+        for (int r = 1; r < RR; ++r) {
+            const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
+            s0 = s0 + w0;
+            s1 = s1 + w1;
+        }
+        wb0 = s0 * a.inv_R;
+        wb1 = s1 * a.inv_R;
     }
     const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
-    const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
     const v4f v0 = wb0 + u0, v1 = wb1 + u1;
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
     const v4f z0 = keep ? v0 : zero4, z1 = keep ? v1 : zero4;
@@ -59,12 +74,17 @@ __device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t
 template <int R, bool PACK = false>
 __device__ __forceinline__ void frozen1(const ProjectArgs& a, int Rrt, int64_t e, bool keep, float* d = nullptr)
 {
-    const int RR = R > 0 ? R : Rrt;
-    float s = ld1(a.W[0] + e);
+    float wb;
+    if (R == kMeanInZ) {
+        wb = ld1(a.Z + e);
+    } else {
+        const int RR = R > 0 ? R : Rrt;
+        float s = ld1(a.W[0] + e);
 #pragma unroll
-    for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
+        for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
+        wb = s * a.inv_R;
+    }
     const float u = ld1(a.U + e);
-    const float wb = s * a.inv_R;
     const float v = wb + u;
     const float z = keep ? v : 0.f;
     st1(a.Z + e, z);

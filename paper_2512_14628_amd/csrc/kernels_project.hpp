@@ -60,14 +60,17 @@ struct Cand {
         if (a.Wbar) st4(a.Wbar + e, wb);
         return v;
     }
-    // the candidate alone, nothing stored (CHANNEL layers: their outputs are written once the mask is known)
+    // the candidate alone; with park_mean the mean is parked in Z (CHANNEL layers: their outputs are written once
+    // the mask is known, from the parked mean and U, so that the replicas are read once)
     static __device__ __forceinline__ v4f value4(const ProjectArgs& a, int Rrt, int64_t e)
     {
         const int RR = R > 0 ? R : Rrt;
         v4f s = ld4(a.W[0] + e);
 #pragma unroll
         for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
-        return s * a.inv_R + ld4(a.U + e);
+        const v4f wb = s * a.inv_R;
+        if (a.park_mean) st4(a.Z + e, wb);
+        return wb + ld4(a.U + e);
     }
     static __device__ __forceinline__ float value1(const ProjectArgs& a, int Rrt, int64_t e)
     {
@@ -75,7 +78,9 @@ struct Cand {
         float s = ld1(a.W[0] + e);
 #pragma unroll
         for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
-        return s * a.inv_R + ld1(a.U + e);
+        const float wb = s * a.inv_R;
+        if (a.park_mean) st1(a.Z + e, wb);
+        return wb + ld1(a.U + e);
     }
     static __device__ __forceinline__ float scalar(const ProjectArgs& a, int Rrt, int64_t e)
     {
@@ -162,9 +167,11 @@ __device__ __forceinline__ void project_rows(const WorkItem& it, const ProjectAr
 // the rows of its wave, accumulating per-column sums in registers.  The four waves' sums are added
 // in wave order through LDS and stored as this row block's partial column sums; the layer's selection later
 // adds row blocks and the khw columns of a channel in a fixed order.
-// Nothing but the sums is written: a pruned channel is a set of 4-byte (khw = 1) or 4*khw-byte runs
+// No output is written speculatively: a pruned channel is a set of 4-byte (khw = 1) or 4*khw-byte runs
 // scattered over every row, so repairing speculative outputs would rewrite most 128-bit quads of the
-// layer; the outputs are instead written in one streaming pass once the mask is known (channel_final).
+// layer.  Once the mask is known one streaming pass (channel_final) forms V = Wbar + U again, bit for bit, and
+// writes the final Z and U: from the mean Wbar parked in Z here when there are 3 or more replicas (R + 6 arenas
+// moved in all instead of 2R + 4), else from the replicas.
 template <int R>
 __device__ __forceinline__ void project_tile(const WorkItem& it, const ProjectArgs& a, int Rrt)
 {
