@@ -181,10 +181,10 @@ int hsadmm_project_frozen(const hsadmm_plan_t* plan, const float* const* W_repli
  * The projection under a frozen mask and the tensor shrinkage of its result
  * in one call (Section 4.5; Section 4.4.1, Eq. (15)): the same outputs, bit
  * for bit, as hsadmm_project_frozen(...) followed by hsadmm_compact(plan, Z,
- * mask, packed, layer_off, kept_idx, ...).  The kept rows of FILTER layers and
- * the rows of MODE_NONE layers are written to the packed buffer by the pass
- * that forms them (Z is not read again for them); the rows of CHANNEL and
- * BOTH layers are gathered from Z by a second launch.
+ * mask, packed, layer_off, kept_idx, ...).  Everything the mask keeps is
+ * written to the packed buffer by the pass that forms it (whole rows of
+ * FILTER and MODE_NONE layers, the kept channels' columns of CHANNEL and BOTH
+ * layers); Z is not read again.
  *   mappings_cached  0: the index mappings are derived from the mask first
  *                    (as hsadmm_compact does when given a mask);
  *                    nonzero: the workspace already holds the index mappings
@@ -263,9 +263,9 @@ int hsadmm_compact(const hsadmm_plan_t* plan, const float* src, const uint8_t* m
  * bit, as hsadmm_project(...) followed by hsadmm_compact(plan, Z, NULL, packed,
  * layer_off, kept_idx, ...), i.e. Z compacted under the selection just made.
  * The compaction reads kept groups only and the repair of the speculative
- * outputs rewrites pruned groups only, so for plans without CHANNEL layers
- * the two share one kernel launch; plans with CHANNEL layers run the same
- * kernels as the two separate calls.  Arguments, alignment, ownership and
+ * outputs rewrites pruned groups only, so the two share one kernel launch;
+ * CHANNEL layers are packed by the pass that writes their Z, and are not
+ * read again.  Arguments, alignment, ownership and
  * errors as for hsadmm_project (W_replicas .. sqnorm, workspace) and
  * hsadmm_compact (packed, layer_off, kept_idx); all three compaction outputs
  * are required.  Afterwards the workspace holds the selection's index

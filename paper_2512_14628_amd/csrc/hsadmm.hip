@@ -81,7 +81,7 @@ struct hsadmm_plan {
     std::vector<WorkItem> items_rows;   // compact / expand kernels
     std::vector<WorkItem> items_fix;    // project_fixup, weighted_fixup: the row items of the FILTER layers
     std::vector<WorkItem> items_rest;   // weighted_fixup_pack: the row items of all other layers
-    std::vector<WorkItem> items_cols;   // hsadmm_project_frozen_compact: the row items of the CHANNEL and BOTH layers
+    std::vector<WorkItem> items_nochan; // hsadmm_project_compact: the row items of all layers but the CHANNEL layers
     std::vector<WorkItem> items_bfix;   // composite_fixup: the row items of the BOTH layers
     std::vector<WorkItem> items_wfinal; // weighted_final: CHANNEL tiles and BOTH rows (a subset of items_proj)
     std::vector<WorkItem> items_chan;   // channel_final: the row items of the CHANNEL layers (a subset of items_rows)
@@ -100,7 +100,7 @@ struct hsadmm_plan {
     WorkItem* d_items_rows = nullptr;
     WorkItem* d_items_fix = nullptr;
     WorkItem* d_items_rest = nullptr;
-    WorkItem* d_items_cols = nullptr;
+    WorkItem* d_items_nochan = nullptr;
     WorkItem* d_items_bfix = nullptr;
     WorkItem* d_items_wfinal = nullptr;
     WorkItem* d_items_chan = nullptr;
@@ -219,7 +219,7 @@ hipError_t launch_frozen(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, co
                   (const WorkItem*)p->d_items_rows, a, Rrt, mask, PackOut{});
 }
 
-// The same pass with the kept rows of FILTER layers and the rows of NONE layers packed as they are formed.
+// The same pass with everything the mask keeps packed as it is formed.
 template <int R>
 hipError_t launch_frozen_pack(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, const uint8_t* mask,
                               const PackOut& po, hipStream_t s)
@@ -231,8 +231,12 @@ hipError_t launch_frozen_pack(const hsadmm_plan* p, const ProjectArgs& a, int Rr
 // Final Z / U of the CHANNEL layers under the mask just selected: the frozen-mask kernel over their row items.
 // With 3 or more replicas pass 1 has parked their mean in Z and it is read from there (R = kMeanInZ).
 template <int R>
-hipError_t launch_channel_final(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, const uint8_t* mask, hipStream_t s)
+hipError_t launch_channel_final(const hsadmm_plan* p, const ProjectArgs& a, int Rrt, const uint8_t* mask,
+                                const PackOut* po, hipStream_t s)
 {
+    if (po)     // hsadmm_project_compact: the kept columns are packed as they are formed
+        return launch(p, kChanFinal, project_frozen<R, true>, (unsigned)p->items_chan.size(), kBlock, s,
+                      (const WorkItem*)p->d_items_chan, a, Rrt, mask, *po);
     return launch(p, kChanFinal, project_frozen<R>, (unsigned)p->items_chan.size(), kBlock, s,
                   (const WorkItem*)p->d_items_chan, a, Rrt, mask, PackOut{});
 }
@@ -343,7 +347,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             d.rows_item0 = (int32_t)p->items_rows.size();
             add_row_items(p->items_rows, l, d, x.mode);
             if (x.mode != HSADMM_MODE_FILTER) add_row_items(p->items_rest, l, d, x.mode);
-            if (has_colsums) add_row_items(p->items_cols, l, d, x.mode);
+            if (x.mode != HSADMM_MODE_CHANNEL) add_row_items(p->items_nochan, l, d, x.mode);
             d.rows_items = (int32_t)p->items_rows.size() - d.rows_item0;
             if (x.mode == HSADMM_MODE_CHANNEL) {
                 add_tile_items(p->items_proj, l, d, kChanRows);
@@ -420,7 +424,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     upload(p->items_rows, &p->d_items_rows);
     upload(p->items_fix, &p->d_items_fix);
     upload(p->items_rest, &p->d_items_rest);
-    upload(p->items_cols, &p->d_items_cols);
+    upload(p->items_nochan, &p->d_items_nochan);
     upload(p->items_bfix, &p->d_items_bfix);
     upload(p->items_wfinal, &p->d_items_wfinal);
     upload(p->items_chan, &p->d_items_chan);
@@ -447,7 +451,7 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
     if (p->d_items_fix) (void)hipFree(p->d_items_fix);
     if (p->d_items_rest) (void)hipFree(p->d_items_rest);
-    if (p->d_items_cols) (void)hipFree(p->d_items_cols);
+    if (p->d_items_nochan) (void)hipFree(p->d_items_nochan);
     if (p->d_items_bfix) (void)hipFree(p->d_items_bfix);
     if (p->d_items_wfinal) (void)hipFree(p->d_items_wfinal);
     if (p->d_items_chan) (void)hipFree(p->d_items_chan);
@@ -514,9 +518,19 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     if (run_selection(p, a.key, a.colpart, Z, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
     // The compaction of Z under the selection just made reads kept groups only, which FILTER and BOTH layers
-    // hold in final form since pass 1; it shares a launch with the FILTER fix-up unless a CHANNEL layer's Z
-    // is still to be written.
-    const bool fuse = out && !p->items_fix.empty() && p->items_chan.empty();
+    // hold in final form since pass 1, so it shares a launch with the FILTER fix-up; the CHANNEL layers are
+    // packed by the pass that writes their Z (channel_final).
+    const bool fuse = out && !p->items_fix.empty();
+    PackOut po{};
+    if (out) {
+        po.pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
+        po.cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
+        po.kept_idx = reinterpret_cast<const int32_t*>(ws + p->ws.kept_idx);
+        po.layer_off = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
+        po.packed = out->packed;
+        po.co = CopyOut{out->layer_off, out->kept_idx};
+        po.n_layers = (int)p->layers.size();
+    }
     if (!p->items_fix.empty() && !fuse) {
         e = launch(p, kFixup, project_fixup, (unsigned)p->items_fix.size(), kBlock, s,
                    (const WorkItem*)p->d_items_fix, (const uint8_t*)mask, U, Z);
@@ -529,27 +543,25 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     }
     if (!p->items_chan.empty()) {
         const uint8_t* cm = mask;
+        const PackOut* pk = out ? &po : nullptr;
         switch (a.park_mean ? 0 : R) {
-            case 0: e = launch_channel_final<kMeanInZ>(p, a, R, cm, s); break;
-            case 1: e = launch_channel_final<1>(p, a, R, cm, s); break;
-            default: e = launch_channel_final<2>(p, a, R, cm, s); break;
+            case 0: e = launch_channel_final<kMeanInZ>(p, a, R, cm, pk, s); break;
+            case 1: e = launch_channel_final<1>(p, a, R, cm, pk, s); break;
+            default: e = launch_channel_final<2>(p, a, R, cm, pk, s); break;
         }
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
-    if (out) {
-        const CopyOut co{out->layer_off, out->kept_idx};
-        const int32_t* pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
-        const int32_t* cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
-        const int32_t* kidx = reinterpret_cast<const int32_t*>(ws + p->ws.kept_idx);
-        const int64_t* lo = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
+    if (out && !p->items_nochan.empty()) {
+        const unsigned n_rows = (unsigned)p->items_nochan.size();
         if (fuse)
-            e = launch(p, kFixupGather, fixup_gather, (unsigned)(p->items_fix.size() + p->items_rows.size()), kBlock,
-                       s, (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), (const uint8_t*)mask, U, Z,
-                       (const WorkItem*)p->d_items_rows, pos, cnt, kidx, (int)p->layers.size(), lo, out->packed, co);
+            e = launch(p, kFixupGather, fixup_gather, (unsigned)p->items_fix.size() + n_rows, kBlock, s,
+                       (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), (const uint8_t*)mask, U, Z,
+                       (const WorkItem*)p->d_items_nochan, po.pos, po.cnt, po.kept_idx, po.n_layers, po.layer_off,
+                       po.packed, po.co);
         else
-            e = launch(p, kGather, compact_gather<false>, (unsigned)p->items_rows.size(), kBlock, s,
-                       (const WorkItem*)p->d_items_rows, (const float*)Z, (const float*)nullptr, pos, cnt, kidx,
-                       (int)p->layers.size(), lo, out->packed, co);
+            e = launch(p, kGather, compact_gather<false>, n_rows, kBlock, s, (const WorkItem*)p->d_items_nochan,
+                       (const float*)Z, (const float*)nullptr, po.pos, po.cnt, po.kept_idx, po.n_layers,
+                       po.layer_off, po.packed, po.co);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
     return HSADMM_OK;
@@ -639,13 +651,6 @@ int hsadmm_project_frozen_compact(const hsadmm_plan_t* p, const float* const* W_
         default: e = launch_frozen_pack<0>(p, a, R, mask, po, s); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
-    if (!p->items_cols.empty()) {
-        // rows that keep a subset of their columns: gathered from the Z just written
-        e = launch(p, kGather, compact_gather<false>, (unsigned)p->items_cols.size(), kBlock, s,
-                   (const WorkItem*)p->d_items_cols, (const float*)Z, (const float*)nullptr, po.pos, po.cnt,
-                   po.kept_idx, po.n_layers, po.layer_off, packed, po.co);
-        if (e != hipSuccess) return HSADMM_ERR_HIP;
-    }
     return HSADMM_OK;
 }
 

@@ -15,8 +15,8 @@ constexpr int kMeanInZ = -1;
 // z = z~ (.) m): kept element Z = V, U += Wbar - V; masked-out element Z = +0, U = U + Wbar (= V).
 // PACK: d, when not null, is where the 4 elements go in the packed buffer (rows packed whole).
 template <int R, bool PACK = false>
-__device__ __forceinline__ void frozen4(const ProjectArgs& a, int Rrt, int64_t e, bool k0, bool k1, bool k2, bool k3,
-                                        float* d = nullptr)
+__device__ __forceinline__ v4f frozen4(const ProjectArgs& a, int Rrt, int64_t e, bool k0, bool k1, bool k2, bool k3,
+                                       float* d = nullptr)
 {
     v4f wb;
     if (R == kMeanInZ) {
@@ -36,6 +36,7 @@ __device__ __forceinline__ void frozen4(const ProjectArgs& a, int Rrt, int64_t e
     st4(a.U + e, u + (wb - z));
     if (a.Wbar) st4(a.Wbar + e, wb);
     if (PACK && d) st4u(d, z);
+    return z;
 }
 
 // two chunks of one row (same keep flag) with all loads issued before any store
@@ -72,7 +73,7 @@ __device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t
 }
 
 template <int R, bool PACK = false>
-__device__ __forceinline__ void frozen1(const ProjectArgs& a, int Rrt, int64_t e, bool keep, float* d = nullptr)
+__device__ __forceinline__ float frozen1(const ProjectArgs& a, int Rrt, int64_t e, bool keep, float* d = nullptr)
 {
     float wb;
     if (R == kMeanInZ) {
@@ -91,14 +92,35 @@ __device__ __forceinline__ void frozen1(const ProjectArgs& a, int Rrt, int64_t e
     st1(a.U + e, u + (wb - z));
     if (a.Wbar) st1(a.Wbar + e, wb);
     if (PACK && d) *d = z;
+    return z;
+}
+
+// pc[i] = the packed column of column col + i, or -1 if its channel is not kept (rank: the ranks of the layer's
+// channels among the kept ones, -1 for a pruned channel), for 4 adjacent columns.
+__device__ __forceinline__ void quad_packed_cols(const int32_t* __restrict__ rank, const DivKhw& div, int col,
+                                                 int pc[4])
+{
+    if (div.khw == 1) {
+        int4 r;
+        __builtin_memcpy(&r, rank + col, 16);
+        pc[0] = r.x; pc[1] = r.y; pc[2] = r.z; pc[3] = r.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ch = div(col + i);
+            const int r = rank[ch];
+            pc[i] = r < 0 ? -1 : r * div.khw + (col + i - ch * div.khw);
+        }
+    }
 }
 
 // Row items of every mode (the compact / expand item table): no keys, no second pass, every byte of the
 // replicas and of U is read once and Z and U are written once, streaming along the rows.  FILTER / NONE rows
 // share one keep flag; in CHANNEL rows and in the kept filters' rows of a BOTH layer every column takes the
 // flag of its channel.
-// PACK: kept FILTER rows and the rows of NONE layers also go to the packed buffer as they are formed, at their
-// rank under the index mappings of this mask (po); the rows of CHANNEL and BOTH layers are left to a gather.
+// PACK: what the mask keeps also goes to the packed buffer as it is formed, under the index mappings of this
+// mask (po): a kept FILTER row or a row of a NONE layer whole, at its rank; of a CHANNEL row, or a kept filter's
+// row of a BOTH layer, the columns of kept channels, each at its packed column.
 template <int R, bool PACK = false>
 __global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
                                                          const uint8_t* __restrict__ mask, PackOut po)
@@ -116,24 +138,51 @@ __global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restr
     const uint8_t* mc = mask + (mode == HSADMM_MODE_BOTH ? it.aux : (int64_t)it.g0);
     const DivKhw div(it.khw);
     float* out = nullptr;
-    if (PACK && !columns) {
+    int packed_row_len = 0;                 // rows that keep a subset of their columns: kept channels * khw
+    const int32_t* rank = nullptr;          // ... and the ranks of the layer's channels
+    if (PACK) {
         if (it.row0 == 0) copy_out_layer(it.layer, po.cnt, po.kept_idx, po.n_layers, po.layer_off, po.co);
         out = po.packed + po.layer_off[it.layer];
+        if (columns) {
+            const int kc = mode == HSADMM_MODE_BOTH ? po.cnt[2 * po.n_layers + it.layer] : po.cnt[it.layer];
+            packed_row_len = kc * it.khw;
+            rank = po.pos + (mode == HSADMM_MODE_BOTH ? it.aux : (int64_t)it.g0);
+        }
     }
     for (int rr = sub; rr < it.nr; rr += rows_at_once) {
         const bool keep = mode == HSADMM_MODE_NONE || mode == HSADMM_MODE_CHANNEL || mask[it.g0 + rr] != 0;
         const int64_t base = it.base + (int64_t)rr * row_len;
         if (columns && keep) {
+            float* drow = nullptr;          // this row in the packed buffer
+            if (PACK) {
+                const int p = mode == HSADMM_MODE_CHANNEL ? it.row0 + rr : po.pos[it.g0 + rr];
+                if (p >= 0) drow = out + (int64_t)p * packed_row_len;
+            }
             if (vec) {
                 const int nchunk = row_len >> 2;
                 for (int c = j; c < nchunk; c += lpr) {
                     const int col = c << 2;
                     bool pr[4];
                     quad_pruned(mc, div, col, pr);
-                    frozen4<R>(a, Rrt, base + col, !pr[0], !pr[1], !pr[2], !pr[3]);
+                    const v4f z = frozen4<R>(a, Rrt, base + col, !pr[0], !pr[1], !pr[2], !pr[3]);
+                    if (PACK && drow) {
+                        int pc[4];
+                        quad_packed_cols(rank, div, col, pc);
+                        if (pc[0] >= 0) drow[pc[0]] = z.x;
+                        if (pc[1] >= 0) drow[pc[1]] = z.y;
+                        if (pc[2] >= 0) drow[pc[2]] = z.z;
+                        if (pc[3] >= 0) drow[pc[3]] = z.w;
+                    }
                 }
             } else {
-                for (int c = j; c < row_len; c += lpr) frozen1<R>(a, Rrt, base + c, mc[div(c)] != 0);
+                for (int c = j; c < row_len; c += lpr) {
+                    const int ch = div(c);
+                    const float z = frozen1<R>(a, Rrt, base + c, mc[ch] != 0);
+                    if (PACK && drow) {
+                        const int r = rank[ch];
+                        if (r >= 0) drow[r * it.khw + (c - ch * it.khw)] = z;
+                    }
+                }
             }
             continue;
         }
