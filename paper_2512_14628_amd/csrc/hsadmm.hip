@@ -81,8 +81,8 @@ struct hsadmm_plan {
     std::vector<WorkItem> items_rows;   // compact / expand kernels
     std::vector<WorkItem> items_fix;    // project_fixup, weighted_fixup: the row items of the FILTER layers
     std::vector<WorkItem> items_rest;   // weighted_fixup_pack: the row items of all other layers
-    std::vector<WorkItem> items_nochan; // hsadmm_project_compact: the row items of all layers but the CHANNEL layers
-    std::vector<WorkItem> items_bfix;   // composite_fixup: the row items of the BOTH layers
+    std::vector<WorkItem> items_plain;  // hsadmm_project_compact: the row items of the FILTER and NONE layers
+    std::vector<WorkItem> items_bfix;   // composite_final: the row items of the BOTH layers
     std::vector<WorkItem> items_wfinal; // weighted_final: CHANNEL tiles and BOTH rows (a subset of items_proj)
     std::vector<WorkItem> items_chan;   // channel_final: the row items of the CHANNEL layers (a subset of items_rows)
     std::vector<WorkItem> items_both;   // composite_colsums: tiles of the layers under both constraints
@@ -100,7 +100,7 @@ struct hsadmm_plan {
     WorkItem* d_items_rows = nullptr;
     WorkItem* d_items_fix = nullptr;
     WorkItem* d_items_rest = nullptr;
-    WorkItem* d_items_nochan = nullptr;
+    WorkItem* d_items_plain = nullptr;
     WorkItem* d_items_bfix = nullptr;
     WorkItem* d_items_wfinal = nullptr;
     WorkItem* d_items_chan = nullptr;
@@ -243,8 +243,8 @@ hipError_t launch_channel_final(const hsadmm_plan* p, const ProjectArgs& a, int 
 // Per-layer selection once the keys (FILTER, and the filters of BOTH) or the partial column sums
 // (CHANNEL) are in place.  Layers under both constraints then take their second projection: channel
 // norms over the kept filters from the candidate held in Z, and the selection of the channels.
-hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, const float* Z, uint8_t* mask,
-                         char* ws, hipStream_t s)
+hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, const float* Z, const float* U,
+                         uint8_t* mask, char* ws, hipStream_t s)
 {
     // the selection also leaves its index mappings in the workspace, for a compaction without a mask
     IndexMaps im;
@@ -258,7 +258,7 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
                           (const int32_t*)nullptr, 0, im, nL, (int)p->pack_align);
     if (e != hipSuccess || p->both_layers.empty()) return e;
     e = launch(p, kColsums, composite_colsums, (unsigned)p->items_both.size(), kBlock, s,
-               (const WorkItem*)p->d_items_both, Z, (const uint8_t*)mask, colpart);
+               (const WorkItem*)p->d_items_both, Z, U, (const uint8_t*)mask, colpart);
     if (e != hipSuccess) return e;
     return launch(p, kTopk, select_topk, (unsigned)p->both_layers.size(), kScanBlock, s,
                   (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
@@ -347,7 +347,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             d.rows_item0 = (int32_t)p->items_rows.size();
             add_row_items(p->items_rows, l, d, x.mode);
             if (x.mode != HSADMM_MODE_FILTER) add_row_items(p->items_rest, l, d, x.mode);
-            if (x.mode != HSADMM_MODE_CHANNEL) add_row_items(p->items_nochan, l, d, x.mode);
+            if (!has_colsums) add_row_items(p->items_plain, l, d, x.mode);
             d.rows_items = (int32_t)p->items_rows.size() - d.rows_item0;
             if (x.mode == HSADMM_MODE_CHANNEL) {
                 add_tile_items(p->items_proj, l, d, kChanRows);
@@ -424,7 +424,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     upload(p->items_rows, &p->d_items_rows);
     upload(p->items_fix, &p->d_items_fix);
     upload(p->items_rest, &p->d_items_rest);
-    upload(p->items_nochan, &p->d_items_nochan);
+    upload(p->items_plain, &p->d_items_plain);
     upload(p->items_bfix, &p->d_items_bfix);
     upload(p->items_wfinal, &p->d_items_wfinal);
     upload(p->items_chan, &p->d_items_chan);
@@ -451,7 +451,7 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
     if (p->d_items_fix) (void)hipFree(p->d_items_fix);
     if (p->d_items_rest) (void)hipFree(p->d_items_rest);
-    if (p->d_items_nochan) (void)hipFree(p->d_items_nochan);
+    if (p->d_items_plain) (void)hipFree(p->d_items_plain);
     if (p->d_items_bfix) (void)hipFree(p->d_items_bfix);
     if (p->d_items_wfinal) (void)hipFree(p->d_items_wfinal);
     if (p->d_items_chan) (void)hipFree(p->d_items_chan);
@@ -516,10 +516,11 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         default: e = launch_pass1<0>(p, a, R, s); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
-    if (run_selection(p, a.key, a.colpart, Z, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
-    // The compaction of Z under the selection just made reads kept groups only, which FILTER and BOTH layers
-    // hold in final form since pass 1, so it shares a launch with the FILTER fix-up; the CHANNEL layers are
-    // packed by the pass that writes their Z (channel_final).
+    // (the candidate of a BOTH layer is its parked mean + U)
+    if (run_selection(p, a.key, a.colpart, Z, U, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
+    // The compaction of Z under the selection just made reads kept groups only, which FILTER layers hold in
+    // final form since pass 1, so it shares a launch with the FILTER fix-up; the CHANNEL and BOTH layers are
+    // packed by the pass that writes their Z.
     const bool fuse = out && !p->items_fix.empty();
     PackOut po{};
     if (out) {
@@ -537,8 +538,14 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
     if (!p->items_bfix.empty()) {
-        e = launch(p, kBothFixup, composite_fixup, (unsigned)p->items_bfix.size(), kBlock, s,
-                   (const WorkItem*)p->d_items_bfix, (const uint8_t*)mask, U, Z);
+        // layers under both constraints: final Z and U from the parked mean and U, under both selections
+        const unsigned gb = (unsigned)p->items_bfix.size();
+        if (out)
+            e = launch(p, kBothFixup, project_frozen<kMeanInZ, true>, gb, kBlock, s, (const WorkItem*)p->d_items_bfix,
+                       a, 0, (const uint8_t*)mask, po);
+        else
+            e = launch(p, kBothFixup, project_frozen<kMeanInZ>, gb, kBlock, s, (const WorkItem*)p->d_items_bfix,
+                       a, 0, (const uint8_t*)mask, PackOut{});
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
     if (!p->items_chan.empty()) {
@@ -551,15 +558,15 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         }
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
-    if (out && !p->items_nochan.empty()) {
-        const unsigned n_rows = (unsigned)p->items_nochan.size();
+    if (out && !p->items_plain.empty()) {
+        const unsigned n_rows = (unsigned)p->items_plain.size();
         if (fuse)
             e = launch(p, kFixupGather, fixup_gather, (unsigned)p->items_fix.size() + n_rows, kBlock, s,
                        (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), (const uint8_t*)mask, U, Z,
-                       (const WorkItem*)p->d_items_nochan, po.pos, po.cnt, po.kept_idx, po.n_layers, po.layer_off,
+                       (const WorkItem*)p->d_items_plain, po.pos, po.cnt, po.kept_idx, po.n_layers, po.layer_off,
                        po.packed, po.co);
         else
-            e = launch(p, kGather, compact_gather<false>, n_rows, kBlock, s, (const WorkItem*)p->d_items_nochan,
+            e = launch(p, kGather, compact_gather<false>, n_rows, kBlock, s, (const WorkItem*)p->d_items_plain,
                        (const float*)Z, (const float*)nullptr, po.pos, po.cnt, po.kept_idx, po.n_layers,
                        po.layer_off, po.packed, po.co);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
@@ -803,7 +810,8 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
         default: e = launch(p, kWKeys, weighted_pass1<0>, grid, kBlock, s, items, w, (int)R); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
-    if (run_selection(p, w.p.key, w.p.colpart, Z, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
+    // (the weighted candidate of a BOTH layer is parked in Z as it is)
+    if (run_selection(p, w.p.key, w.p.colpart, Z, nullptr, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
     const uint8_t* cm = mask;
     // With a compaction to follow, the FILTER fix-up packs its kept rows as it forms them and shares its launch with
     // the gather of the other layers' rows, which are final once weighted_final has run.
@@ -1038,7 +1046,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kColsums: return "composite_colsums";
         case kChanFinal: return "channel_final";
         case kWFixup: return "weighted_fixup";
-        case kBothFixup: return "composite_fixup";
+        case kBothFixup: return "composite_final";
         case kAverage: return "average";
         case kMaskDrift: return "mask_drift";
         case kFixupGather: return "fixup_gather";

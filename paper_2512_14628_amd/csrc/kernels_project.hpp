@@ -60,6 +60,45 @@ struct Cand {
         if (a.Wbar) st4(a.Wbar + e, wb);
         return v;
     }
+    // PARK forms (layers under both constraints): the candidate for the norms, the mean parked in Z, U untouched;
+    // the outputs are written once both selections are known, from the parked mean and U
+    static __device__ __forceinline__ double park_two(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, double acc)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) {
+            const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
+            s0 = s0 + w0;
+            s1 = s1 + w1;
+        }
+        const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
+        const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
+        st4(a.Z + e0, wb0);
+        st4(a.Z + e1, wb1);
+        acc = sq4(acc, wb0 + u0);
+        return sq4(acc, wb1 + u1);
+    }
+    static __device__ __forceinline__ v4f park_one(const ProjectArgs& a, int Rrt, int64_t e)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        v4f s = ld4(a.W[0] + e);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+        const v4f wb = s * a.inv_R;
+        st4(a.Z + e, wb);
+        return wb + ld4(a.U + e);
+    }
+    static __device__ __forceinline__ float park_scalar(const ProjectArgs& a, int Rrt, int64_t e)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        float s = ld1(a.W[0] + e);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
+        const float wb = s * a.inv_R;
+        st1(a.Z + e, wb);
+        return wb + ld1(a.U + e);
+    }
     // the candidate alone; with park_mean the mean is parked in Z (CHANNEL layers: their outputs are written once
     // the mask is known, from the parked mean and U, so that the replicas are read once)
     static __device__ __forceinline__ v4f value4(const ProjectArgs& a, int Rrt, int64_t e)
@@ -101,7 +140,7 @@ struct Cand {
 
 // Sum of squares of the part of one row that lane j of `step` lanes owns (chunks j, j+step, ...),
 // accumulated in increasing chunk order.
-template <int R>
+template <int R, bool PARK>
 __device__ __forceinline__ double pass1_row(const ProjectArgs& a, int Rrt, int64_t base, int row_len, bool vec,
                                             int j, int step)
 {
@@ -109,12 +148,17 @@ __device__ __forceinline__ double pass1_row(const ProjectArgs& a, int Rrt, int64
     if (vec) {
         const int nchunk = row_len >> 2;
         int c = j;
-        for (; c + step < nchunk; c += 2 * step)
-            acc = Cand<R>::two(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + step) << 2), acc);
-        if (c < nchunk) acc = sq4(acc, Cand<R>::one(a, Rrt, base + ((int64_t)c << 2)));
+        for (; c + step < nchunk; c += 2 * step) {
+            const int64_t e0 = base + ((int64_t)c << 2), e1 = base + ((int64_t)(c + step) << 2);
+            acc = PARK ? Cand<R>::park_two(a, Rrt, e0, e1, acc) : Cand<R>::two(a, Rrt, e0, e1, acc);
+        }
+        if (c < nchunk) {
+            const int64_t e = base + ((int64_t)c << 2);
+            acc = sq4(acc, PARK ? Cand<R>::park_one(a, Rrt, e) : Cand<R>::one(a, Rrt, e));
+        }
     } else {
         for (int c = j; c < row_len; c += step) {
-            const float v = Cand<R>::scalar(a, Rrt, base + c);
+            const float v = PARK ? Cand<R>::park_scalar(a, Rrt, base + c) : Cand<R>::scalar(a, Rrt, base + c);
             acc = fma((double)v, (double)v, acc);
         }
     }
@@ -125,7 +169,8 @@ __device__ __forceinline__ double pass1_row(const ProjectArgs& a, int Rrt, int64
 // 64/lpr adjacent rows.  Long rows: the whole workgroup shares a row.  Per-lane sums are combined
 // by a butterfly inside the wave and (long rows) in wave order through LDS, so the order of
 // additions depends only on (row_len, lpr), never on where the row sits: equal groups get equal keys.
-template <int R>
+// PARK (layers under both constraints): the norms of the rows only; the mean goes to Z, U stays.
+template <int R, bool PARK>
 __device__ __forceinline__ void project_rows(const WorkItem& it, const ProjectArgs& a, int Rrt)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -141,14 +186,14 @@ __device__ __forceinline__ void project_rows(const WorkItem& it, const ProjectAr
             const int rr = rb + sub;
             const bool active = rr < it.nr;
             double acc = 0.0;
-            if (active) acc = pass1_row<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr);
+            if (active) acc = pass1_row<R, PARK>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr);
             acc = wave_xor_sum(acc, lpr);
             if (active && j == 0) a.key[it.g0 + rr] = acc;
         }
     } else {
         __shared__ double wsum[kWaves];
         for (int rr = 0; rr < it.nr; ++rr) {
-            double acc = pass1_row<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, threadIdx.x, kBlock);
+            double acc = pass1_row<R, PARK>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, threadIdx.x, kBlock);
             acc = wave_xor_sum(acc, kWave);
             if (lane == 0) wsum[wave] = acc;
             __syncthreads();
@@ -218,18 +263,22 @@ template <int R>
 __global__ __launch_bounds__(kBlock) void project_pass1(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt)
 {
     const WorkItem it = items[blockIdx.x];
-    if (item_mode(it) == HSADMM_MODE_CHANNEL) project_tile<R>(it, a, Rrt);
-    else project_rows<R>(it, a, Rrt);       // BOTH: the filter norms come first
+    const int mode = item_mode(it);
+    if (mode == HSADMM_MODE_CHANNEL) project_tile<R>(it, a, Rrt);
+    else if (mode == HSADMM_MODE_BOTH) project_rows<R, true>(it, a, Rrt);       // the filter norms come first
+    else project_rows<R, false>(it, a, Rrt);
 }
 
 // ------------------------------------------------------------------ BOTH: channel norms after the filter projection
 
 // Second projection of a layer under both constraints (Section 3, paragraph after Eq. (10)): the
 // channel norms of the tensor whose pruned filters are already zero, i.e. column sums of V^2 over
-// the kept rows only.  Z holds V after pass 1.  Tiles and the order of additions are those of
+// the kept rows only.  After pass 1 Z holds the mean and V = Z + U is formed again, bit for bit (U given); the
+// weighted projection parks its candidate itself in Z (U null).  Tiles and the order of additions are those of
 // project_tile (rows of a pruned filter add nothing and are not read).
 __global__ __launch_bounds__(kBlock) void composite_colsums(const WorkItem* __restrict__ items,
                                                             const float* __restrict__ Z,
+                                                            const float* __restrict__ U,
                                                             const uint8_t* __restrict__ mask,
                                                             double* __restrict__ colpart)
 {
@@ -249,13 +298,15 @@ __global__ __launch_bounds__(kBlock) void composite_colsums(const WorkItem* __re
             if (mf[rr] == 0) continue;
             const int64_t e = it.base + (int64_t)rr * row_len + col;
             if (vec) {
-                const v4f v = ld4(Z + e);
+                v4f v = ld4(Z + e);
+                if (U) v = v + ld4(U + e);
                 acc0 = fma((double)v.x, (double)v.x, acc0);
                 acc1 = fma((double)v.y, (double)v.y, acc1);
                 acc2 = fma((double)v.z, (double)v.z, acc2);
                 acc3 = fma((double)v.w, (double)v.w, acc3);
             } else {
-                const float v = ld1(Z + e);
+                float v = ld1(Z + e);
+                if (U) v = v + ld1(U + e);
                 acc0 = fma((double)v, (double)v, acc0);
             }
         }
@@ -338,85 +389,6 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
     fixup_rows(items[blockIdx.x], mask, U, Z);
 }
 
-// Row items of the BOTH layers.  A pruned filter's row moves whole, as above.  In a kept filter's row only the
-// columns of pruned channels change: a fully pruned quad moves, a partly pruned quad is rewritten whole, the kept
-// elements of U passing through (they are final already), so that every access is a full 128 bits.  A lane
-// owns the same quads in every row, so their channel flags are fetched once and two rows are in flight.
-__global__ __launch_bounds__(kBlock) void composite_fixup(const WorkItem* __restrict__ items,
-                                                          const uint8_t* __restrict__ mask,
-                                                          float* __restrict__ U, float* __restrict__ Z)
-{
-    const WorkItem it = items[blockIdx.x];
-    const int row_len = it.row_len;
-    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-    const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
-    const int rows_at_once = kBlock / lpr;
-    const int sub = threadIdx.x / lpr;
-    const int j = threadIdx.x - sub * lpr;
-    const uint8_t* mc = mask + it.aux;            // channel bytes of the layer
-    const uint8_t* mf = mask + it.g0;             // filter bytes of the item's rows
-    const DivKhw div(it.khw);
-    if (!item_vec(it)) {
-        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
-            const bool stays = mf[rr] != 0;
-            const int64_t base = it.base + (int64_t)rr * row_len;
-            for (int c = j; c < row_len; c += lpr) {
-                if (stays && mc[div(c)] != 0) continue;
-                st1(U + base + c, ld1(Z + base + c));
-                st1(Z + base + c, 0.f);
-            }
-        }
-        return;
-    }
-    const int nchunk = row_len >> 2;
-    for (int c = j; c < nchunk; c += lpr) {
-        const int col = c << 2;
-        bool pr[4];
-        quad_pruned(mc, div, col, pr);
-        const bool any = pr[0] || pr[1] || pr[2] || pr[3];
-        const bool all = pr[0] && pr[1] && pr[2] && pr[3];
-        for (int rr0 = sub; rr0 < it.nr; rr0 += 2 * rows_at_once) {
-            const int rr1 = rr0 + rows_at_once;
-            const bool live1 = rr1 < it.nr;
-            const bool stays0 = mf[rr0] != 0;
-            const bool stays1 = live1 && mf[rr1] != 0;
-            // what each row's quad needs: nothing / a move (U <- Z, Z <- 0) / a merge (also reads U)
-            const bool move0 = !stays0 || all, move1 = live1 && (!stays1 || all);
-            const bool merge0 = stays0 && any && !all, merge1 = stays1 && any && !all;
-            const int64_t e0 = it.base + (int64_t)rr0 * row_len + col;
-            const int64_t e1 = it.base + (int64_t)rr1 * row_len + col;
-            v4f z0 = zero4, z1 = zero4, u0 = zero4, u1 = zero4;
-            if (move0 || merge0) z0 = ld4(Z + e0);
-            if (move1 || merge1) z1 = ld4(Z + e1);
-            if (merge0) u0 = ld4(U + e0);
-            if (merge1) u1 = ld4(U + e1);
-            if (move0) {
-                st4(U + e0, z0);
-                st4(Z + e0, zero4);
-            } else if (merge0) {
-                v4f zn = z0;
-                if (pr[0]) { u0.x = z0.x; zn.x = 0.f; }
-                if (pr[1]) { u0.y = z0.y; zn.y = 0.f; }
-                if (pr[2]) { u0.z = z0.z; zn.z = 0.f; }
-                if (pr[3]) { u0.w = z0.w; zn.w = 0.f; }
-                st4(U + e0, u0);
-                st4(Z + e0, zn);
-            }
-            if (move1) {
-                st4(U + e1, z1);
-                st4(Z + e1, zero4);
-            } else if (merge1) {
-                v4f zn = z1;
-                if (pr[0]) { u1.x = z1.x; zn.x = 0.f; }
-                if (pr[1]) { u1.y = z1.y; zn.y = 0.f; }
-                if (pr[2]) { u1.z = z1.z; zn.z = 0.f; }
-                if (pr[3]) { u1.w = z1.w; zn.w = 0.f; }
-                st4(U + e1, u1);
-                st4(Z + e1, zn);
-            }
-        }
-    }
-}
 
 }  // namespace
 #endif
