@@ -231,8 +231,17 @@ def main():
 
     # algorithmic bytes each kernel is charged with (per launch)
     nk = wl.n_kept
+    # pass 1 is charged with what it must move itself: on FILTER and unconstrained layers all of the projection's
+    # traffic (R replicas + U in, Z + U out); on layers whose outputs a later pass writes (CHANNEL, BOTH) only its
+    # reads and the mean it parks for that pass (CHANNEL: from 3 replicas on)
+    def pass1_bytes(l):
+        if l.mode == wk.MODE_CHANNEL:
+            return 4 * l.n * (wl.R + 1 + (1 if wl.R >= 3 else 0))
+        if l.mode == wk.MODE_BOTH:
+            return 4 * l.n * (wl.R + 2)
+        return 4 * l.n * (wl.R + 3)
     kernel_bytes = {
-        "project_pass1": bytes_["project"],          # all of project's traffic: R replicas + U in, Z + U out
+        "project_pass1": sum(pass1_bytes(l) for l in wl.layers),
         "compact_gather": bytes_["compact"],
         "expand_scatter": bytes_["expand"],
     }
@@ -388,9 +397,13 @@ def main():
             def composite_step():
                 b = sets[counter[0] % nsets]
                 counter[0] += 1
-                pkg.hsadmm_project(plan2, b.W, b.U, b.Z, None, b.mask2, None, b.ws2, stream=stream)
-                pkg.hsadmm_compact(plan2, b.Z, b.mask2 if args.compact_rescan else None, b.packed, b.off, b.kept2, b.ws2,
-                               stream=stream)
+                if one_call:
+                    pkg.hsadmm_project_compact(plan2, b.W, b.U, b.Z, None, b.mask2, None, b.packed, b.off, b.kept2,
+                                               b.ws2, stream=stream)
+                else:
+                    pkg.hsadmm_project(plan2, b.W, b.U, b.Z, None, b.mask2, None, b.ws2, stream=stream)
+                    pkg.hsadmm_compact(plan2, b.Z, b.mask2 if args.compact_rescan else None, b.packed, b.off, b.kept2,
+                                       b.ws2, stream=stream)
                 pkg.hsadmm_expand(plan2, b.packed, None, b.dst, b.ws2, stream=stream)
 
             if not args.no_verify:

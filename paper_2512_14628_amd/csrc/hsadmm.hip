@@ -4,7 +4,7 @@
 // Kernel overview (every launch covers all layers of the plan through a work-item table):
 //
 //   project_pass1   streams the R replicas and U once.  Computes Wbar, V = Wbar + U and the fp64
-//                   partial sums of V^2; for FILTER / BOTH / NONE layers it writes the values that are
+//                   partial sums of V^2; for FILTER / NONE layers it writes the values that are
 //                   final if the group is kept: Z <- V, U <- U + (Wbar - V).   [Eq. (9), (12)]
 //   select_topk     one workgroup per layer: radix select, eight bits a pass, of the k-th largest key on
 //                   the uint64 view of the non-negative doubles (taken relative to the smallest upper
@@ -17,8 +17,10 @@
 //   channel_final   CHANNEL layers: pass 1 only sums (and, with 3 or more replicas, parks their mean in Z);
 //                   their Z and U are written here, in one streaming pass under the mask just selected
 //                   (the kernel of the frozen-mask path, reading the parked mean instead of the replicas).
-//   composite_colsums   layers under both constraints: channel norms over the kept filters, then a
-//                   second select_topk for the channels.   [Section 3, paragraph after Eq. (10)]
+//   composite_colsums   layers under both constraints (pass 1 gives them their filter norms and parks the
+//                   mean in Z): channel norms of V = Z + U over the kept filters, then a second select_topk
+//                   for the channels, then the frozen-mask kernel on the parked mean writes Z and U
+//                   (composite_final).                     [Section 3, paragraph after Eq. (10)]
 //   scan_mask       index mappings from a given mask: kept counts, positions, kept_idx, layer_off.
 //   compact_gather  packed <- src[K_out, K_in, :]                             [Eq. (15)]
 //   fixup_gather    project_fixup and compact_gather of Z in one launch (hsadmm_project_compact): the
