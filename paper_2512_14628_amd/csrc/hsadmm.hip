@@ -70,7 +70,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFixup, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -84,7 +84,7 @@ struct hsadmm_plan {
     std::vector<WorkItem> items_fix;    // project_fixup, weighted_fixup: the row items of the FILTER layers
     std::vector<WorkItem> items_rest;   // weighted_fixup_pack: the row items of all other layers
     std::vector<WorkItem> items_plain;  // hsadmm_project_compact: the row items of the FILTER and NONE layers
-    std::vector<WorkItem> items_bfix;   // composite_final: the row items of the BOTH layers
+    std::vector<WorkItem> items_bfinal; // composite_final: the row items of the BOTH layers
     std::vector<WorkItem> items_wfinal; // weighted_final: CHANNEL tiles and BOTH rows (a subset of items_proj)
     std::vector<WorkItem> items_chan;   // channel_final: the row items of the CHANNEL layers (a subset of items_rows)
     std::vector<WorkItem> items_both;   // composite_colsums: tiles of the layers under both constraints
@@ -103,7 +103,7 @@ struct hsadmm_plan {
     WorkItem* d_items_fix = nullptr;
     WorkItem* d_items_rest = nullptr;
     WorkItem* d_items_plain = nullptr;
-    WorkItem* d_items_bfix = nullptr;
+    WorkItem* d_items_bfinal = nullptr;
     WorkItem* d_items_wfinal = nullptr;
     WorkItem* d_items_chan = nullptr;
     WorkItem* d_items_both = nullptr;
@@ -359,7 +359,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
                 add_row_items(p->items_proj, l, d, x.mode);
                 if (x.mode == HSADMM_MODE_FILTER) add_row_items(p->items_fix, l, d, x.mode);
                 if (x.mode == HSADMM_MODE_BOTH) {
-                    add_row_items(p->items_bfix, l, d, x.mode);
+                    add_row_items(p->items_bfinal, l, d, x.mode);
                     add_row_items(p->items_wfinal, l, d, x.mode);
                 }
             }
@@ -427,7 +427,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     upload(p->items_fix, &p->d_items_fix);
     upload(p->items_rest, &p->d_items_rest);
     upload(p->items_plain, &p->d_items_plain);
-    upload(p->items_bfix, &p->d_items_bfix);
+    upload(p->items_bfinal, &p->d_items_bfinal);
     upload(p->items_wfinal, &p->d_items_wfinal);
     upload(p->items_chan, &p->d_items_chan);
     upload(p->items_both, &p->d_items_both);
@@ -454,7 +454,7 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_items_fix) (void)hipFree(p->d_items_fix);
     if (p->d_items_rest) (void)hipFree(p->d_items_rest);
     if (p->d_items_plain) (void)hipFree(p->d_items_plain);
-    if (p->d_items_bfix) (void)hipFree(p->d_items_bfix);
+    if (p->d_items_bfinal) (void)hipFree(p->d_items_bfinal);
     if (p->d_items_wfinal) (void)hipFree(p->d_items_wfinal);
     if (p->d_items_chan) (void)hipFree(p->d_items_chan);
     if (p->d_items_both) (void)hipFree(p->d_items_both);
@@ -539,14 +539,14 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
                    (const WorkItem*)p->d_items_fix, (const uint8_t*)mask, U, Z);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
-    if (!p->items_bfix.empty()) {
+    if (!p->items_bfinal.empty()) {
         // layers under both constraints: final Z and U from the parked mean and U, under both selections
-        const unsigned gb = (unsigned)p->items_bfix.size();
+        const unsigned gb = (unsigned)p->items_bfinal.size();
         if (out)
-            e = launch(p, kBothFixup, project_frozen<kMeanInZ, true>, gb, kBlock, s, (const WorkItem*)p->d_items_bfix,
+            e = launch(p, kBothFinal, project_frozen<kMeanInZ, true>, gb, kBlock, s, (const WorkItem*)p->d_items_bfinal,
                        a, 0, (const uint8_t*)mask, po);
         else
-            e = launch(p, kBothFixup, project_frozen<kMeanInZ>, gb, kBlock, s, (const WorkItem*)p->d_items_bfix,
+            e = launch(p, kBothFinal, project_frozen<kMeanInZ>, gb, kBlock, s, (const WorkItem*)p->d_items_bfinal,
                        a, 0, (const uint8_t*)mask, PackOut{});
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
@@ -1048,7 +1048,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kColsums: return "composite_colsums";
         case kChanFinal: return "channel_final";
         case kWFixup: return "weighted_fixup";
-        case kBothFixup: return "composite_final";
+        case kBothFinal: return "composite_final";
         case kAverage: return "average";
         case kMaskDrift: return "mask_drift";
         case kFixupGather: return "fixup_gather";
