@@ -192,8 +192,10 @@ int hsadmm_project_frozen(const hsadmm_plan_t* plan, const float* const* W_repli
  *                    hsadmm_expand or hsadmm_project_frozen_compact that was
  *                    given it) and they are reused, as a frozen mask's cached
  *                    index sets are from iteration to iteration (Section 4.5).
- *                    With the mappings of another mask the packed buffer is
- *                    unspecified (no access leaves it).
+ *                    The caller guarantees that such a call has run on this
+ *                    plan, workspace and stream; with the mappings of another
+ *                    mask of this plan the packed buffer is unspecified (no
+ *                    access leaves it).
  * Other arguments, alignment, ownership and errors as for
  * hsadmm_project_frozen and hsadmm_compact.
  */
