@@ -1,6 +1,6 @@
 """Randomised parity sweep: layer tables drawn at random over every mode, odd sizes, replica counts and packing
-alignments, each run through project + compact + expand (with and without masks) and compared with the oracle on every
-element (tests/test_gpu_parity._run).  All sizes are within the documented limits of the library."""
+alignments, each run through project + compact + expand (with and without masks, as separate calls and through the *_compact
+calls) and compared with the oracle on every element (tests/test_gpu_parity._run).  All sizes are within the documented limits of the library."""
 import numpy as np
 import pytest
 
@@ -54,6 +54,8 @@ def test_random_tables_weighted_and_frozen(seed):
     a = rng.uniform(0.3, 1.0, L).astype(np.float32)
     b = rng.uniform(0.0, 0.7, L).astype(np.float32)
     _phase4_chain(wl, W, U, a, b, rng, want_wbar=bool(seed % 2), want_sqnorm=bool(seed % 3), fused_dual=bool(seed % 2))
+    _phase4_chain(wl, W, U, a, b, rng, want_wbar=not bool(seed % 2), want_sqnorm=bool(seed % 3), fused_dual=True,
+                  one_call=True)
     mask = (rng.random(wl.groups_total) < rng.uniform(0.1, 0.9)).astype(np.uint8) * 255
     _check_frozen(wl, W, U, mask, want_wbar=bool(seed % 2))
     _check_frozen(wl, W, U, oracle.project(wl.table(), W, U)["mask"], want_wbar=False)
