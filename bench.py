@@ -58,7 +58,7 @@ def main():
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path has no collectives); "
-              "run with --gpus 1. See DESIGN.md for how the step would shard.", file=sys.stderr)
+              "run with --gpus 1 (sharded, every GPU would run the same step on its own slice of the layer table).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
