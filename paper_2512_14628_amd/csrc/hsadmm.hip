@@ -25,6 +25,8 @@
 //   compact_gather  packed <- src[K_out, K_in, :]                             [Eq. (15)]
 //   fixup_gather    project_fixup and compact_gather of Z in one launch (hsadmm_project_compact): the
 //                   first rewrites pruned rows only, the second reads kept rows only.
+//   final_gather    without FILTER layers: the last final pass (with its packing) and the gather of the
+//                   unconstrained layers' rows in one launch.
 //   expand_scatter  dst <- zero fill + scatter of packed                      [Section 4.4.3]
 //   project_frozen  one pass under a given mask; as project_frozen<R, true> it also packs the kept rows of
 //                   FILTER layers and the rows of unconstrained layers (hsadmm_project_frozen_compact)  [Section 4.5]
@@ -539,10 +541,19 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
                    (const WorkItem*)p->d_items_fix, (const uint8_t*)mask, U, Z);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
+    // Without FILTER layers the gather of the plain rows (unconstrained layers) has no fix-up to share a launch
+    // with; it then rides on the last final pass.
+    bool plain_pending = out && !fuse && !p->items_plain.empty();
+    const unsigned n_plain = (unsigned)p->items_plain.size();
     if (!p->items_bfinal.empty()) {
         // layers under both constraints: final Z and U from the parked mean and U, under both selections
         const unsigned gb = (unsigned)p->items_bfinal.size();
-        if (out)
+        if (out && plain_pending && p->items_chan.empty()) {
+            e = launch(p, kBothFinal, final_gather<kMeanInZ>, gb + n_plain, kBlock, s,
+                       (const WorkItem*)p->d_items_bfinal, (int)gb, a, 0, (const uint8_t*)mask, po,
+                       (const WorkItem*)p->d_items_plain);
+            plain_pending = false;
+        } else if (out)
             e = launch(p, kBothFinal, project_frozen<kMeanInZ, true>, gb, kBlock, s, (const WorkItem*)p->d_items_bfinal,
                        a, 0, (const uint8_t*)mask, po);
         else
@@ -553,14 +564,26 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     if (!p->items_chan.empty()) {
         const uint8_t* cm = mask;
         const PackOut* pk = out ? &po : nullptr;
-        switch (a.park_mean ? 0 : R) {
-            case 0: e = launch_channel_final<kMeanInZ>(p, a, R, cm, pk, s); break;
-            case 1: e = launch_channel_final<1>(p, a, R, cm, pk, s); break;
-            default: e = launch_channel_final<2>(p, a, R, cm, pk, s); break;
+        const unsigned gc = (unsigned)p->items_chan.size();
+        const WorkItem* ci = p->d_items_chan;
+        const WorkItem* pi = p->d_items_plain;
+        if (plain_pending) {
+            switch (a.park_mean ? 0 : R) {
+                case 0: e = launch(p, kChanFinal, final_gather<kMeanInZ>, gc + n_plain, kBlock, s, ci, (int)gc, a, (int)R, cm, po, pi); break;
+                case 1: e = launch(p, kChanFinal, final_gather<1>, gc + n_plain, kBlock, s, ci, (int)gc, a, (int)R, cm, po, pi); break;
+                default: e = launch(p, kChanFinal, final_gather<2>, gc + n_plain, kBlock, s, ci, (int)gc, a, (int)R, cm, po, pi); break;
+            }
+            plain_pending = false;
+        } else {
+            switch (a.park_mean ? 0 : R) {
+                case 0: e = launch_channel_final<kMeanInZ>(p, a, R, cm, pk, s); break;
+                case 1: e = launch_channel_final<1>(p, a, R, cm, pk, s); break;
+                default: e = launch_channel_final<2>(p, a, R, cm, pk, s); break;
+            }
         }
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
-    if (out && !p->items_plain.empty()) {
+    if (out && !p->items_plain.empty() && (fuse || plain_pending)) {
         const unsigned n_rows = (unsigned)p->items_plain.size();
         if (fuse)
             e = launch(p, kFixupGather, fixup_gather, (unsigned)p->items_fix.size() + n_rows, kBlock, s,

@@ -294,6 +294,21 @@ __global__ __launch_bounds__(kBlock) void fixup_gather(const WorkItem* __restric
                            packed, co);
 }
 
+// The final pass of CHANNEL or BOTH layers with its packing (project_frozen<R, true>) and the gather of the plain
+// layers' rows (FILTER / NONE, final before this launch) in one launch: workgroups [0, n_final) take the final-pass
+// items, the rest the plain row items.  The two kinds of workgroup touch different layers.
+template <int R>
+__global__ __launch_bounds__(kBlock) void final_gather(const WorkItem* __restrict__ final_items, int n_final,
+                                                       ProjectArgs a, int Rrt, const uint8_t* __restrict__ mask,
+                                                       PackOut po, const WorkItem* __restrict__ plain_items)
+{
+    if ((int)blockIdx.x < n_final)
+        frozen_item<R, true>(final_items[blockIdx.x], a, Rrt, mask, po);
+    else
+        gather_item<false>(plain_items[(int)blockIdx.x - n_final], a.Z, nullptr, po.pos, po.cnt, po.kept_idx,
+                           po.n_layers, po.layer_off, po.packed, po.co);
+}
+
 // The weighted FILTER fix-up with its kept rows packed as they are formed, and the compaction c = Z + Vd of the
 // other layers' rows (final before this launch), in one launch: workgroups [0, n_fix) take the fix-up items, the
 // rest the row items of the layers that are not FILTER layers.

@@ -121,11 +121,10 @@ __device__ __forceinline__ void quad_packed_cols(const int32_t* __restrict__ ran
 // PACK: what the mask keeps also goes to the packed buffer as it is formed, under the index mappings of this
 // mask (po): a kept FILTER row or a row of a NONE layer whole, at its rank; of a CHANNEL row, or a kept filter's
 // row of a BOTH layer, the columns of kept channels, each at its packed column.
-template <int R, bool PACK = false>
-__global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
-                                                         const uint8_t* __restrict__ mask, PackOut po)
+template <int R, bool PACK>
+__device__ __forceinline__ void frozen_item(const WorkItem& it, const ProjectArgs& a, int Rrt,
+                                            const uint8_t* __restrict__ mask, const PackOut& po)
 {
-    const WorkItem it = items[blockIdx.x];
     const int mode = item_mode(it);
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
@@ -203,6 +202,13 @@ __global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restr
             for (int c = j; c < row_len; c += lpr) frozen1<R, PACK>(a, Rrt, base + c, keep, d ? d + c : nullptr);
         }
     }
+}
+
+template <int R, bool PACK = false>
+__global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
+                                                         const uint8_t* __restrict__ mask, PackOut po)
+{
+    frozen_item<R, PACK>(items[blockIdx.x], a, Rrt, mask, po);
 }
 
 // Eq. (14): out = OR of M masks, 0 / 1 bytes.
