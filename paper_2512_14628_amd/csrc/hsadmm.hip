@@ -30,7 +30,8 @@
 //   expand_scatter  dst <- zero fill + scatter of packed                      [Section 4.4.3]
 //   project_frozen  one pass under a given mask; as project_frozen<R, true> it also packs the kept rows of
 //                   FILTER layers and the rows of unconstrained layers (hsadmm_project_frozen_compact)  [Section 4.5]
-//   weighted_pass1 / weighted_fixup / weighted_final   the candidate of Eq. (9) with its rho_2 term
+//   weighted_pass1 / weighted_fixup   the candidate of Eq. (9) with its rho_2 term (CHANNEL and BOTH layers: the
+//                   final pass is project_frozen in its weighted form, "weighted_final" in the timing table)
 //   weighted_fixup_pack   weighted_fixup that also packs c = z~ + v of its kept rows, and the gather of the
 //                   other layers' rows, in one launch (hsadmm_project_weighted_compact)   [Section 4.4.1]
 //   dual_inter_kernel  Eq. (13);  residual_partials / residual_finish  Section 3.4;  mask_or_kernel  Eq. (14)
@@ -84,10 +85,9 @@ struct hsadmm_plan {
     std::vector<WorkItem> items_proj;   // project kernels
     std::vector<WorkItem> items_rows;   // compact / expand kernels
     std::vector<WorkItem> items_fix;    // project_fixup, weighted_fixup: the row items of the FILTER layers
-    std::vector<WorkItem> items_rest;   // weighted_fixup_pack: the row items of all other layers
+    std::vector<WorkItem> items_none;   // weighted_fixup_pack: the row items of the unconstrained layers
     std::vector<WorkItem> items_plain;  // hsadmm_project_compact: the row items of the FILTER and NONE layers
     std::vector<WorkItem> items_bfinal; // composite_final: the row items of the BOTH layers
-    std::vector<WorkItem> items_wfinal; // weighted_final: CHANNEL tiles and BOTH rows (a subset of items_proj)
     std::vector<WorkItem> items_chan;   // channel_final: the row items of the CHANNEL layers (a subset of items_rows)
     std::vector<WorkItem> items_both;   // composite_colsums: tiles of the layers under both constraints
     std::vector<int32_t> both_layers;   // their indices
@@ -103,10 +103,9 @@ struct hsadmm_plan {
     WorkItem* d_items_proj = nullptr;
     WorkItem* d_items_rows = nullptr;
     WorkItem* d_items_fix = nullptr;
-    WorkItem* d_items_rest = nullptr;
+    WorkItem* d_items_none = nullptr;
     WorkItem* d_items_plain = nullptr;
     WorkItem* d_items_bfinal = nullptr;
-    WorkItem* d_items_wfinal = nullptr;
     WorkItem* d_items_chan = nullptr;
     WorkItem* d_items_both = nullptr;
     int32_t* d_both_layers = nullptr;
@@ -247,8 +246,8 @@ hipError_t launch_channel_final(const hsadmm_plan* p, const ProjectArgs& a, int 
 // Per-layer selection once the keys (FILTER, and the filters of BOTH) or the partial column sums
 // (CHANNEL) are in place.  Layers under both constraints then take their second projection: channel
 // norms over the kept filters from the candidate held in Z, and the selection of the channels.
-hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, const float* Z, const float* U,
-                         uint8_t* mask, char* ws, hipStream_t s)
+hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, const ProjectArgs& a, uint8_t* mask,
+                         char* ws, hipStream_t s)
 {
     // the selection also leaves its index mappings in the workspace, for a compaction without a mask
     IndexMaps im;
@@ -262,7 +261,8 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
                           (const int32_t*)nullptr, 0, im, nL, (int)p->pack_align);
     if (e != hipSuccess || p->both_layers.empty()) return e;
     e = launch(p, kColsums, composite_colsums, (unsigned)p->items_both.size(), kBlock, s,
-               (const WorkItem*)p->d_items_both, Z, U, (const uint8_t*)mask, colpart);
+               (const WorkItem*)p->d_items_both, (const float*)a.Z, (const float*)a.U, a.Zg, a.Vd, a.coef,
+               (const uint8_t*)mask, colpart);
     if (e != hipSuccess) return e;
     return launch(p, kTopk, select_topk, (unsigned)p->both_layers.size(), kScanBlock, s,
                   (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
@@ -350,19 +350,17 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             cap = (cap + pack_align_elems - 1) / pack_align_elems * pack_align_elems;
             d.rows_item0 = (int32_t)p->items_rows.size();
             add_row_items(p->items_rows, l, d, x.mode);
-            if (x.mode != HSADMM_MODE_FILTER) add_row_items(p->items_rest, l, d, x.mode);
+            if (x.mode == HSADMM_MODE_NONE) add_row_items(p->items_none, l, d, x.mode);
             if (!has_colsums) add_row_items(p->items_plain, l, d, x.mode);
             d.rows_items = (int32_t)p->items_rows.size() - d.rows_item0;
             if (x.mode == HSADMM_MODE_CHANNEL) {
                 add_tile_items(p->items_proj, l, d, kChanRows);
-                add_tile_items(p->items_wfinal, l, d, kChanRows);
                 add_row_items(p->items_chan, l, d, x.mode);
             } else {
                 add_row_items(p->items_proj, l, d, x.mode);
                 if (x.mode == HSADMM_MODE_FILTER) add_row_items(p->items_fix, l, d, x.mode);
                 if (x.mode == HSADMM_MODE_BOTH) {
                     add_row_items(p->items_bfinal, l, d, x.mode);
-                    add_row_items(p->items_wfinal, l, d, x.mode);
                 }
             }
             if (both) {
@@ -427,10 +425,9 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     upload(p->items_proj, &p->d_items_proj);
     upload(p->items_rows, &p->d_items_rows);
     upload(p->items_fix, &p->d_items_fix);
-    upload(p->items_rest, &p->d_items_rest);
+    upload(p->items_none, &p->d_items_none);
     upload(p->items_plain, &p->d_items_plain);
     upload(p->items_bfinal, &p->d_items_bfinal);
-    upload(p->items_wfinal, &p->d_items_wfinal);
     upload(p->items_chan, &p->d_items_chan);
     upload(p->items_both, &p->d_items_both);
     upload(p->both_layers, &p->d_both_layers);
@@ -454,10 +451,9 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_items_proj) (void)hipFree(p->d_items_proj);
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
     if (p->d_items_fix) (void)hipFree(p->d_items_fix);
-    if (p->d_items_rest) (void)hipFree(p->d_items_rest);
+    if (p->d_items_none) (void)hipFree(p->d_items_none);
     if (p->d_items_plain) (void)hipFree(p->d_items_plain);
     if (p->d_items_bfinal) (void)hipFree(p->d_items_bfinal);
-    if (p->d_items_wfinal) (void)hipFree(p->d_items_wfinal);
     if (p->d_items_chan) (void)hipFree(p->d_items_chan);
     if (p->d_items_both) (void)hipFree(p->d_items_both);
     if (p->d_both_layers) (void)hipFree(p->d_both_layers);
@@ -520,8 +516,8 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         default: e = launch_pass1<0>(p, a, R, s); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
-    // (the candidate of a BOTH layer is its parked mean + U)
-    if (run_selection(p, a.key, a.colpart, Z, U, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
+    // (the candidate of a BOTH layer is formed again from its parked mean and U)
+    if (run_selection(p, a.key, a.colpart, a, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
     // The compaction of Z under the selection just made reads kept groups only, which FILTER layers hold in
     // final form since pass 1, so it shares a launch with the FILTER fix-up; the CHANNEL and BOTH layers are
     // packed by the pass that writes their Z.
@@ -823,6 +819,8 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     w.p.key = sqnorm ? sqnorm : reinterpret_cast<double*>(ws + p->ws.key);
     w.p.colpart = reinterpret_cast<double*>(ws + p->ws.colpart);
     w.p.inv_R = 1.0f / (float)R;
+    w.p.park_mean = R >= 3 ? 1 : 0;
+    w.p.Zg = Zg; w.p.Vd = Vd; w.p.coef = p->d_coef;
     w.Zg = Zg; w.Vd = Vd; w.coef = p->d_coef;
     const unsigned grid = (unsigned)p->items_proj.size();
     const WorkItem* items = p->d_items_proj;
@@ -835,31 +833,11 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
         default: e = launch(p, kWKeys, weighted_pass1<0>, grid, kBlock, s, items, w, (int)R); break;
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
-    // (the weighted candidate of a BOTH layer is parked in Z as it is)
-    if (run_selection(p, w.p.key, w.p.colpart, Z, nullptr, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
+    // (the weighted candidate of a BOTH layer is formed again from its parked mean, U, Zg and Vd)
+    if (run_selection(p, w.p.key, w.p.colpart, w.p, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
     const uint8_t* cm = mask;
-    // With a compaction to follow, the FILTER fix-up packs its kept rows as it forms them and shares its launch with
-    // the gather of the other layers' rows, which are final once weighted_final has run.
-    const bool fuse = out && !p->items_fix.empty();
-    if (!p->items_fix.empty() && !fuse) {
-        e = launch(p, kWFixup, weighted_fixup, (unsigned)p->items_fix.size(), kBlock, s,
-                   (const WorkItem*)p->d_items_fix, cm, U, Z, Zg, Vd, (const float*)p->d_coef);
-        if (e != hipSuccess) return HSADMM_ERR_HIP;
-    }
-    if (!p->items_wfinal.empty()) {
-        const unsigned gf = (unsigned)p->items_wfinal.size();
-        const WorkItem* fi = p->d_items_wfinal;
-        switch (R) {
-            case 1: e = launch(p, kWFinal, weighted_final<1>, gf, kBlock, s, fi, w, (int)R, cm); break;
-            case 2: e = launch(p, kWFinal, weighted_final<2>, gf, kBlock, s, fi, w, (int)R, cm); break;
-            case 4: e = launch(p, kWFinal, weighted_final<4>, gf, kBlock, s, fi, w, (int)R, cm); break;
-            case 8: e = launch(p, kWFinal, weighted_final<8>, gf, kBlock, s, fi, w, (int)R, cm); break;
-            default: e = launch(p, kWFinal, weighted_final<0>, gf, kBlock, s, fi, w, (int)R, cm); break;
-        }
-        if (e != hipSuccess) return HSADMM_ERR_HIP;
-    }
+    PackOut po{};
     if (out) {
-        PackOut po{};
         po.pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
         po.cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
         po.kept_idx = reinterpret_cast<const int32_t*>(ws + p->ws.kept_idx);
@@ -867,13 +845,47 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
         po.packed = out->packed;
         po.co = CopyOut{out->layer_off, out->kept_idx};
         po.n_layers = (int)p->layers.size();
+    }
+    // With a compaction to follow, the FILTER fix-up packs its kept rows as it forms them and shares its launch with
+    // the gather of the unconstrained layers' rows; CHANNEL and BOTH layers are packed by their final pass.
+    const bool fuse = out && !p->items_fix.empty();
+    if (!p->items_fix.empty() && !fuse) {
+        e = launch(p, kWFixup, weighted_fixup, (unsigned)p->items_fix.size(), kBlock, s,
+                   (const WorkItem*)p->d_items_fix, cm, U, Z, Zg, Vd, (const float*)p->d_coef);
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
+    // Final pass of the CHANNEL and BOTH layers: the frozen-mask kernel in its weighted form, on the parked mean
+    // where pass 1 parked it (BOTH always, CHANNEL with 3 or more replicas), else on the replicas.
+    if (!p->items_bfinal.empty()) {
+        const unsigned gb = (unsigned)p->items_bfinal.size();
+        const WorkItem* bi = p->d_items_bfinal;
+        if (out) e = launch(p, kWFinal, project_frozen<kMeanInZ, true, true>, gb, kBlock, s, bi, w.p, 0, cm, po);
+        else e = launch(p, kWFinal, project_frozen<kMeanInZ, false, true>, gb, kBlock, s, bi, w.p, 0, cm, PackOut{});
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
+    if (!p->items_chan.empty()) {
+        const unsigned gc = (unsigned)p->items_chan.size();
+        const WorkItem* ci = p->d_items_chan;
+        const int sel = w.p.park_mean ? 0 : (int)R;          // 0: parked mean; else R is 1 or 2
+        if (out) {
+            if (sel == 0) e = launch(p, kWFinal, project_frozen<kMeanInZ, true, true>, gc, kBlock, s, ci, w.p, (int)R, cm, po);
+            else if (sel == 1) e = launch(p, kWFinal, project_frozen<1, true, true>, gc, kBlock, s, ci, w.p, (int)R, cm, po);
+            else e = launch(p, kWFinal, project_frozen<2, true, true>, gc, kBlock, s, ci, w.p, (int)R, cm, po);
+        } else {
+            if (sel == 0) e = launch(p, kWFinal, project_frozen<kMeanInZ, false, true>, gc, kBlock, s, ci, w.p, (int)R, cm, PackOut{});
+            else if (sel == 1) e = launch(p, kWFinal, project_frozen<1, false, true>, gc, kBlock, s, ci, w.p, (int)R, cm, PackOut{});
+            else e = launch(p, kWFinal, project_frozen<2, false, true>, gc, kBlock, s, ci, w.p, (int)R, cm, PackOut{});
+        }
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
+    if (out) {
         if (fuse)
-            e = launch(p, kWFixupPack, weighted_fixup_pack, (unsigned)(p->items_fix.size() + p->items_rest.size()),
+            e = launch(p, kWFixupPack, weighted_fixup_pack, (unsigned)(p->items_fix.size() + p->items_none.size()),
                        kBlock, s, (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), cm, U, Z, Zg, Vd,
-                       (const float*)p->d_coef, (const WorkItem*)p->d_items_rest, po);
-        else
-            e = launch(p, kGather, compact_gather<true>, (unsigned)p->items_rows.size(), kBlock, s,
-                       (const WorkItem*)p->d_items_rows, (const float*)Z, Vd, po.pos, po.cnt, po.kept_idx,
+                       (const float*)p->d_coef, (const WorkItem*)p->d_items_none, po);
+        else if (!p->items_none.empty())
+            e = launch(p, kGather, compact_gather<true>, (unsigned)p->items_none.size(), kBlock, s,
+                       (const WorkItem*)p->d_items_none, (const float*)Z, Vd, po.pos, po.cnt, po.kept_idx,
                        po.n_layers, po.layer_off, po.packed, po.co);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }

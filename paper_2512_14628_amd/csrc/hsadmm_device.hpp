@@ -123,7 +123,11 @@ struct ProjectArgs {
     double* key;      // groups_total
     double* colpart;  // CHANNEL partial column sums
     float inv_R;
-    int park_mean;    // pass 1 parks the mean of a CHANNEL layer's replicas in Z (read back by channel_final)
+    int park_mean;    // pass 1 parks the mean of a CHANNEL layer's replicas in Z (read back by the final pass)
+    // weighted candidate of Eq. (9) (null / unused in the base projection)
+    const float* Zg;      // global consensus z
+    const float* Vd;      // inter-node dual v_i
+    const float* coef;    // per layer: a_l, b_l
 };
 
 // Streaming (touch-once) accesses.

@@ -14,9 +14,11 @@ constexpr int kMeanInZ = -1;
 // Final values of 4 adjacent elements under a known mask (Algorithm 1 Phase 3, retraining branch:
 // z = z~ (.) m): kept element Z = V, U += Wbar - V; masked-out element Z = +0, U = U + Wbar (= V).
 // PACK: d, when not null, is where the 4 elements go in the packed buffer (rows packed whole).
-template <int R, bool PACK = false>
+// WEIGHTED: the candidate is z~ = fl(fl(a t) + fl(b (Zg - Vd))), t = Wbar + U (Eq. (9)), and what is packed is
+// c = z + Vd (Section 4.4.1); else the candidate is t and what is packed is z.  The value packed is returned.
+template <int R, bool PACK = false, bool WEIGHTED = false>
 __device__ __forceinline__ v4f frozen4(const ProjectArgs& a, int Rrt, int64_t e, bool k0, bool k1, bool k2, bool k3,
-                                       float* d = nullptr)
+                                       float* d = nullptr, float al = 1.f, float bl = 0.f)
 {
     v4f wb;
     if (R == kMeanInZ) {
@@ -29,20 +31,29 @@ __device__ __forceinline__ v4f frozen4(const ProjectArgs& a, int Rrt, int64_t e,
         wb = s * a.inv_R;
     }
     const v4f u = ld4(a.U + e);
-    const v4f v = wb + u;
+    v4f v = wb + u;
+    v4f vd = {0.f, 0.f, 0.f, 0.f};
+    if (WEIGHTED) {
+        vd = ld4(a.Vd + e);
+        const v4f q = ld4(a.Zg + e) - vd;
+        const v4f at = v * al;
+        const v4f bq = q * bl;
+        v = at + bq;
+    }
     v4f z;
     z.x = k0 ? v.x : 0.f; z.y = k1 ? v.y : 0.f; z.z = k2 ? v.z : 0.f; z.w = k3 ? v.w : 0.f;
     st4(a.Z + e, z);
     st4(a.U + e, u + (wb - z));
     if (a.Wbar) st4(a.Wbar + e, wb);
-    if (PACK && d) st4u(d, z);
-    return z;
+    const v4f c = WEIGHTED ? z + vd : z;
+    if (PACK && d) st4u(d, c);
+    return c;
 }
 
 // two chunks of one row (same keep flag) with all loads issued before any store
-template <int R, bool PACK = false>
+template <int R, bool PACK = false, bool WEIGHTED = false>
 __device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, bool keep,
-                                          float* d0 = nullptr, float* d1 = nullptr)
+                                          float* d0 = nullptr, float* d1 = nullptr, float al = 1.f, float bl = 0.f)
 {
     v4f wb0, wb1;
     if (R == kMeanInZ) {
@@ -61,19 +72,30 @@ __device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t
         wb1 = s1 * a.inv_R;
     }
     const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
-    const v4f v0 = wb0 + u0, v1 = wb1 + u1;
+    v4f v0 = wb0 + u0, v1 = wb1 + u1;
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    v4f vd0 = zero4, vd1 = zero4;
+    if (WEIGHTED && keep) {         // a pruned row needs neither z nor v
+        vd0 = ld4(a.Vd + e0);
+        vd1 = ld4(a.Vd + e1);
+        const v4f q0 = ld4(a.Zg + e0) - vd0, q1 = ld4(a.Zg + e1) - vd1;
+        const v4f at0 = v0 * al, at1 = v1 * al;
+        const v4f bq0 = q0 * bl, bq1 = q1 * bl;
+        v0 = at0 + bq0;
+        v1 = at1 + bq1;
+    }
     const v4f z0 = keep ? v0 : zero4, z1 = keep ? v1 : zero4;
     st4(a.Z + e0, z0);
     st4(a.Z + e1, z1);
     st4(a.U + e0, u0 + (wb0 - z0));
     st4(a.U + e1, u1 + (wb1 - z1));
     if (a.Wbar) { st4(a.Wbar + e0, wb0); st4(a.Wbar + e1, wb1); }
-    if (PACK && d0) { st4u(d0, z0); st4u(d1, z1); }
+    if (PACK && d0) { st4u(d0, WEIGHTED ? z0 + vd0 : z0); st4u(d1, WEIGHTED ? z1 + vd1 : z1); }
 }
 
-template <int R, bool PACK = false>
-__device__ __forceinline__ float frozen1(const ProjectArgs& a, int Rrt, int64_t e, bool keep, float* d = nullptr)
+template <int R, bool PACK = false, bool WEIGHTED = false>
+__device__ __forceinline__ float frozen1(const ProjectArgs& a, int Rrt, int64_t e, bool keep, float* d = nullptr,
+                                         float al = 1.f, float bl = 0.f)
 {
     float wb;
     if (R == kMeanInZ) {
@@ -86,13 +108,22 @@ __device__ __forceinline__ float frozen1(const ProjectArgs& a, int Rrt, int64_t 
         wb = s * a.inv_R;
     }
     const float u = ld1(a.U + e);
-    const float v = wb + u;
+    float v = wb + u;
+    float vd = 0.f;
+    if (WEIGHTED) {
+        vd = ld1(a.Vd + e);
+        const float q = ld1(a.Zg + e) - vd;
+        const float at = v * al;
+        const float bq = q * bl;
+        v = at + bq;
+    }
     const float z = keep ? v : 0.f;
     st1(a.Z + e, z);
     st1(a.U + e, u + (wb - z));
     if (a.Wbar) st1(a.Wbar + e, wb);
-    if (PACK && d) *d = z;
-    return z;
+    const float c = WEIGHTED ? z + vd : z;
+    if (PACK && d) *d = c;
+    return c;
 }
 
 // pc[i] = the packed column of column col + i, or -1 if its channel is not kept (rank: the ranks of the layer's
@@ -121,11 +152,12 @@ __device__ __forceinline__ void quad_packed_cols(const int32_t* __restrict__ ran
 // PACK: what the mask keeps also goes to the packed buffer as it is formed, under the index mappings of this
 // mask (po): a kept FILTER row or a row of a NONE layer whole, at its rank; of a CHANNEL row, or a kept filter's
 // row of a BOTH layer, the columns of kept channels, each at its packed column.
-template <int R, bool PACK>
+template <int R, bool PACK, bool WEIGHTED = false>
 __device__ __forceinline__ void frozen_item(const WorkItem& it, const ProjectArgs& a, int Rrt,
                                             const uint8_t* __restrict__ mask, const PackOut& po)
 {
     const int mode = item_mode(it);
+    const float al = WEIGHTED ? a.coef[2 * it.layer] : 1.f, bl = WEIGHTED ? a.coef[2 * it.layer + 1] : 0.f;
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
     const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
@@ -163,7 +195,7 @@ __device__ __forceinline__ void frozen_item(const WorkItem& it, const ProjectArg
                     const int col = c << 2;
                     bool pr[4];
                     quad_pruned(mc, div, col, pr);
-                    const v4f z = frozen4<R>(a, Rrt, base + col, !pr[0], !pr[1], !pr[2], !pr[3]);
+                    const v4f z = frozen4<R, false, WEIGHTED>(a, Rrt, base + col, !pr[0], !pr[1], !pr[2], !pr[3], nullptr, al, bl);
                     if (PACK && drow) {
                         int pc[4];
                         quad_packed_cols(rank, div, col, pc);
@@ -176,7 +208,7 @@ __device__ __forceinline__ void frozen_item(const WorkItem& it, const ProjectArg
             } else {
                 for (int c = j; c < row_len; c += lpr) {
                     const int ch = div(c);
-                    const float z = frozen1<R>(a, Rrt, base + c, mc[ch] != 0);
+                    const float z = frozen1<R, false, WEIGHTED>(a, Rrt, base + c, mc[ch] != 0, nullptr, al, bl);
                     if (PACK && drow) {
                         const int r = rank[ch];
                         if (r >= 0) drow[r * it.khw + (c - ch * it.khw)] = z;
@@ -195,20 +227,22 @@ __device__ __forceinline__ void frozen_item(const WorkItem& it, const ProjectArg
             const int nchunk = row_len >> 2;
             int c = j;
             for (; c + lpr < nchunk; c += 2 * lpr)
-                frozen4x2<R, PACK>(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + lpr) << 2), keep,
-                                   d ? d + 4 * c : nullptr, d ? d + 4 * (c + lpr) : nullptr);
-            if (c < nchunk) frozen4<R, PACK>(a, Rrt, base + ((int64_t)c << 2), keep, keep, keep, keep, d ? d + 4 * c : nullptr);
+                frozen4x2<R, PACK, WEIGHTED>(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + lpr) << 2), keep,
+                                             d ? d + 4 * c : nullptr, d ? d + 4 * (c + lpr) : nullptr, al, bl);
+            if (c < nchunk)
+                frozen4<R, PACK, WEIGHTED>(a, Rrt, base + ((int64_t)c << 2), keep, keep, keep, keep,
+                                           d ? d + 4 * c : nullptr, al, bl);
         } else {
-            for (int c = j; c < row_len; c += lpr) frozen1<R, PACK>(a, Rrt, base + c, keep, d ? d + c : nullptr);
+            for (int c = j; c < row_len; c += lpr) frozen1<R, PACK, WEIGHTED>(a, Rrt, base + c, keep, d ? d + c : nullptr, al, bl);
         }
     }
 }
 
-template <int R, bool PACK = false>
+template <int R, bool PACK = false, bool WEIGHTED = false>
 __global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
                                                          const uint8_t* __restrict__ mask, PackOut po)
 {
-    frozen_item<R, PACK>(items[blockIdx.x], a, Rrt, mask, po);
+    frozen_item<R, PACK, WEIGHTED>(items[blockIdx.x], a, Rrt, mask, po);
 }
 
 // Eq. (14): out = OR of M masks, 0 / 1 bytes.

@@ -273,12 +273,15 @@ __global__ __launch_bounds__(kBlock) void project_pass1(const WorkItem* __restri
 
 // Second projection of a layer under both constraints (Section 3, paragraph after Eq. (10)): the
 // channel norms of the tensor whose pruned filters are already zero, i.e. column sums of V^2 over
-// the kept rows only.  After pass 1 Z holds the mean and V = Z + U is formed again, bit for bit (U given); the
-// weighted projection parks its candidate itself in Z (U null).  Tiles and the order of additions are those of
-// project_tile (rows of a pruned filter add nothing and are not read).
+// the kept rows only.  After pass 1 Z holds the mean and the candidate is formed again, bit for bit: V = Z + U, or,
+// for the weighted projection (coef given), z~ = fl(fl(a (Z + U)) + fl(b (Zg - Vd))).  Tiles and the order of
+// additions are those of project_tile (rows of a pruned filter add nothing and are not read).
 __global__ __launch_bounds__(kBlock) void composite_colsums(const WorkItem* __restrict__ items,
                                                             const float* __restrict__ Z,
                                                             const float* __restrict__ U,
+                                                            const float* __restrict__ Zg,
+                                                            const float* __restrict__ Vd,
+                                                            const float* __restrict__ coef,
                                                             const uint8_t* __restrict__ mask,
                                                             double* __restrict__ colpart)
 {
@@ -292,21 +295,32 @@ __global__ __launch_bounds__(kBlock) void composite_colsums(const WorkItem* __re
     const int col = it.col0 + lane * vw;
     const bool in = col < row_len;
     const uint8_t* mf = mask + it.g0 + it.row0;      // filter bytes of the tile's rows
+    const float al = coef ? coef[2 * it.layer] : 1.f, bl = coef ? coef[2 * it.layer + 1] : 0.f;
     double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
     if (in) {
         for (int rr = wave; rr < it.nr; rr += kWaves) {
             if (mf[rr] == 0) continue;
             const int64_t e = it.base + (int64_t)rr * row_len + col;
             if (vec) {
-                v4f v = ld4(Z + e);
-                if (U) v = v + ld4(U + e);
+                v4f v = ld4(Z + e) + ld4(U + e);
+                if (coef) {
+                    const v4f q = ld4(Zg + e) - ld4(Vd + e);
+                    const v4f at = v * al;
+                    const v4f bq = q * bl;
+                    v = at + bq;
+                }
                 acc0 = fma((double)v.x, (double)v.x, acc0);
                 acc1 = fma((double)v.y, (double)v.y, acc1);
                 acc2 = fma((double)v.z, (double)v.z, acc2);
                 acc3 = fma((double)v.w, (double)v.w, acc3);
             } else {
-                float v = ld1(Z + e);
-                if (U) v = v + ld1(U + e);
+                float v = ld1(Z + e) + ld1(U + e);
+                if (coef) {
+                    const float q = ld1(Zg + e) - ld1(Vd + e);
+                    const float at = v * al;
+                    const float bq = q * bl;
+                    v = at + bq;
+                }
                 acc0 = fma((double)v, (double)v, acc0);
             }
         }

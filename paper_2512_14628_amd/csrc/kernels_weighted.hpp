@@ -56,8 +56,9 @@ __device__ __forceinline__ void wcand1(const WeightedArgs& w, int Rrt, int64_t e
 //   FILTER   Z <- t (a stash), U <- U + (Wbar - z~) (final if kept); weighted_fixup finishes either case
 //            without reading the replicas again;
 //   NONE     everything is kept: Z <- z~ and U are final;
-//   BOTH     Z <- z~, parked where composite_colsums reads the channel norms; weighted_final writes the outputs;
-//   CHANNEL  partial column sums only; weighted_final writes the outputs.
+//   BOTH     the filter norms of z~; the mean Wbar is parked in Z and U is left alone: composite_colsums and the
+//            final pass (the frozen-mask kernel in its weighted form) form z~ again from Z, U, Zg and Vd;
+//   CHANNEL  partial column sums; with 3 or more replicas the mean is parked in Z for the final pass.
 template <int R>
 __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt)
 {
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
                         wcand4<R>(w, Rrt, base + ((int64_t)c << 2), al, bl, wb, u, zt);
                         const int64_t e = base + ((int64_t)c << 2);
                         if (park) {
-                            st4(w.p.Z + e, zt);
+                            st4(w.p.Z + e, wb);
                         } else {
                             st4(w.p.Z + e, all_kept ? zt : wb + u);
                             st4(w.p.U + e, u + (wb - zt));
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
                         float wb, u, zt;
                         wcand1<R>(w, Rrt, base + c, al, bl, wb, u, zt);
                         if (park) {
-                            st1(w.p.Z + base + c, zt);
+                            st1(w.p.Z + base + c, wb);
                         } else {
                             st1(w.p.Z + base + c, all_kept ? zt : wb + u);
                             st1(w.p.U + base + c, u + (wb - zt));
@@ -141,6 +142,7 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
                 if (vec) {
                     v4f wb, u, zt;
                     wcand4<R>(w, Rrt, e, al, bl, wb, u, zt);
+                    if (w.p.park_mean) st4(w.p.Z + e, wb);
                     acc0 = fma((double)zt.x, (double)zt.x, acc0);
                     acc1 = fma((double)zt.y, (double)zt.y, acc1);
                     acc2 = fma((double)zt.z, (double)zt.z, acc2);
@@ -148,6 +150,7 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
                 } else {
                     float wb, u, zt;
                     wcand1<R>(w, Rrt, e, al, bl, wb, u, zt);
+                    if (w.p.park_mean) st1(w.p.Z + e, wb);
                     acc0 = fma((double)zt, (double)zt, acc0);
                 }
             }
@@ -242,83 +245,6 @@ __global__ __launch_bounds__(kBlock) void weighted_fixup(const WorkItem* __restr
                                                          const float* __restrict__ coef)
 {
     weighted_fixup_rows<false>(items[blockIdx.x], mask, U, Z, Zg, Vd, coef, PackOut{});
-}
-
-// CHANNEL and BOTH layers once the mask is known: everything is formed again from the inputs;
-// Z = z~ on kept groups, +0 elsewhere; U <- U + (Wbar - Z).
-template <int R>
-__global__ __launch_bounds__(kBlock) void weighted_final(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt,
-                                                         const uint8_t* __restrict__ mask)
-{
-    const WorkItem it = items[blockIdx.x];
-    const int mode = item_mode(it);
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int row_len = it.row_len;
-    const bool vec = item_vec(it);
-    const float al = w.coef[2 * it.layer], bl = w.coef[2 * it.layer + 1];
-    auto put4 = [&](int64_t e, bool k0, bool k1, bool k2, bool k3) {
-        v4f wb, u, zt;
-        wcand4<R>(w, Rrt, e, al, bl, wb, u, zt);
-        v4f z;
-        z.x = k0 ? zt.x : 0.f; z.y = k1 ? zt.y : 0.f; z.z = k2 ? zt.z : 0.f; z.w = k3 ? zt.w : 0.f;
-        st4(w.p.Z + e, z);
-        st4(w.p.U + e, u + (wb - z));
-        if (w.p.Wbar) st4(w.p.Wbar + e, wb);
-    };
-    auto put1 = [&](int64_t e, bool keep) {
-        float wb, u, zt;
-        wcand1<R>(w, Rrt, e, al, bl, wb, u, zt);
-        const float z = keep ? zt : 0.f;
-        st1(w.p.Z + e, z);
-        st1(w.p.U + e, u + (wb - z));
-        if (w.p.Wbar) st1(w.p.Wbar + e, wb);
-    };
-    if (mode != HSADMM_MODE_CHANNEL) {
-        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
-        const int rows_at_once = kBlock / lpr;
-        const int sub = threadIdx.x / lpr;
-        const int j = threadIdx.x - sub * lpr;
-        const bool both = mode == HSADMM_MODE_BOTH;
-        const uint8_t* mc = mask + it.aux;            // BOTH: channel bytes of the layer
-        const DivKhw div(it.khw);
-        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
-            const bool keep = mode == HSADMM_MODE_NONE || mask[it.g0 + rr] != 0;
-            const int64_t base = it.base + (int64_t)rr * row_len;
-            if (both && keep) {
-                if (vec) {
-                    const int nchunk = row_len >> 2;
-                    for (int c = j; c < nchunk; c += lpr) {
-                        const int col = c << 2;
-                        bool k[4];
-                        for (int i = 0; i < 4; ++i) k[i] = mc[div(col + i)] != 0;
-                        put4(base + col, k[0], k[1], k[2], k[3]);
-                    }
-                } else {
-                    for (int c = j; c < row_len; c += lpr) put1(base + c, mc[div(c)] != 0);
-                }
-                continue;
-            }
-            if (vec) {
-                const int nchunk = row_len >> 2;
-                for (int c = j; c < nchunk; c += lpr) put4(base + ((int64_t)c << 2), keep, keep, keep, keep);
-            } else {
-                for (int c = j; c < row_len; c += lpr) put1(base + c, keep);
-            }
-        }
-    } else {
-        const int vw = vec ? 4 : 1;
-        const int col = it.col0 + lane * vw;
-        if (col >= row_len) return;
-        const DivKhw div(it.khw);
-        bool k[4] = {true, true, true, true};
-        for (int i = 0; i < vw; ++i) k[i] = mask[it.g0 + div(col + i)] != 0;
-        for (int rr = wave; rr < it.nr; rr += kWaves) {
-            const int64_t e = it.base + (int64_t)rr * row_len + col;
-            if (vec) put4(e, k[0], k[1], k[2], k[3]);
-            else put1(e, k[0]);
-        }
-    }
 }
 
 // Eq. (13): v <- v + (z_i - z) over every layer.  A row item is one contiguous span of the arena.
