@@ -320,7 +320,9 @@ int hsadmm_plan_set_node_weights(hsadmm_plan_t* plan, const float* a, const floa
  * All other arguments, alignment and aliasing rules as for hsadmm_project.
  * FILTER layers take one pass over the replicas (Z first holds Wbar + U, from
  * which either outcome of a filter is finished once the mask is known);
- * CHANNEL and BOTH layers read their inputs twice (norms, then final values).
+ * CHANNEL and BOTH layers take two passes (norms, then final values); the
+ * second reads the mean of the replicas that the first parked in Z (BOTH
+ * always, CHANNEL from 3 replicas on) instead of the replicas.
  * Errors: INVALID_ARGUMENT, WORKSPACE, UNSUPPORTED, HIP.
  */
 int hsadmm_project_weighted(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
@@ -335,8 +337,8 @@ int hsadmm_project_weighted(const hsadmm_plan_t* plan, const float* const* W_rep
  * followed by hsadmm_compact_sum(plan, Z, Vd, NULL, packed, layer_off,
  * kept_idx, ...).  The pass that finishes a kept filter's z~ already holds
  * its Vd, so it writes the packed row as well and the FILTER layers are not
- * read again; the rows of the other layers are packed by workgroups of the
- * same launch.  Arguments, alignment, ownership and errors as for
+ * read again; CHANNEL and BOTH layers are packed by their final pass, the
+ * rows of unconstrained layers by workgroups of the fix-up's launch.  Arguments, alignment, ownership and errors as for
  * hsadmm_project_weighted and hsadmm_compact_sum; all three compaction
  * outputs are required.
  */
