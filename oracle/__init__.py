@@ -69,6 +69,10 @@ def _load():
                                             ctypes.POINTER(f32p), ctypes.c_int32, f32p, f32p, f32p, f32p, f32p,
                                             f32p, f32p, u8p, f64p]
     lib.oracle_project_weighted.restype = ctypes.c_int
+    lib.oracle_project_weighted_frozen.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p,
+                                                   ctypes.POINTER(f32p), ctypes.c_int32, f32p, f32p, f32p, f32p,
+                                                   f32p, f32p, f32p, u8p]
+    lib.oracle_project_weighted_frozen.restype = ctypes.c_int
     lib.oracle_dual_inter.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, f32p, f32p, f32p]
     lib.oracle_dual_inter.restype = ctypes.c_int
     lib.oracle_add_arenas.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, f32p, f32p, f32p]
@@ -340,6 +344,40 @@ def project_weighted(table, W, U, Zg, Vd, a, b, want_wbar: bool = False):
     if rc != 0:
         raise ValueError("oracle_project_weighted failed with code %d" % rc)
     return {"U": U_new, "Z": Z, "mask": mask, "key": key, "Wbar": Wbar}
+
+
+def project_weighted_frozen(table, W, U, Zg, Vd, a, b, mask, want_wbar: bool = False):
+    """Retraining branch with the full candidate of Eq. (9): Z = z~ under a given mask, dual update.
+    Returns dict(U, Z, Wbar or None)."""
+    global last_call_seconds
+    lib = _load()
+    t = _cols(table)
+    L = len(t["c_out"])
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    R, n_arena = W.shape
+    U_new = np.array(U, dtype=np.float32, copy=True, order="C")
+    Zg = np.ascontiguousarray(Zg, dtype=np.float32)
+    Vd = np.ascontiguousarray(Vd, dtype=np.float32)
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    b = np.ascontiguousarray(b, dtype=np.float32)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    assert a.shape == (L,) and b.shape == (L,) and Zg.shape == (n_arena,) and Vd.shape == (n_arena,)
+    assert mask.shape == (groups_total(t),)
+    Z = _poisoned_arena(t, n_arena)
+    Wbar = _poisoned_arena(t, n_arena) if want_wbar else None
+    f32p = ctypes.POINTER(ctypes.c_float)
+    ptrs = (f32p * R)(*[_p(W[r], ctypes.c_float) for r in range(R)])
+    _t0 = time.perf_counter()
+    rc = lib.oracle_project_weighted_frozen(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                                            _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
+                                            _p(t["mode"], ctypes.c_int32), ptrs, R, _p(U_new, ctypes.c_float),
+                                            _p(Zg, ctypes.c_float), _p(Vd, ctypes.c_float), _p(a, ctypes.c_float),
+                                            _p(b, ctypes.c_float), _p(Z, ctypes.c_float),
+                                            _p(Wbar, ctypes.c_float) if want_wbar else None, _p(mask, ctypes.c_uint8))
+    last_call_seconds = time.perf_counter() - _t0
+    if rc != 0:
+        raise ValueError("oracle_project_weighted_frozen failed with code %d" % rc)
+    return {"U": U_new, "Z": Z, "Wbar": Wbar}
 
 
 def dual_inter(table, Zi, Zg, Vd):

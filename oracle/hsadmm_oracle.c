@@ -589,6 +589,59 @@ int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c
 }
 
 /*
+ * The retraining branch of Algorithm 1, Phase 3, with the full candidate: z_i = z~ (.) m for a given (frozen) mask m,
+ * where z~ is the dense node candidate of Eq. (9) exactly as oracle_project_weighted forms it
+ * (z~ = fl(fl(a_l t) + fl(b_l q)), t = Wbar + U, q = Zg - Vd), followed by the dual update of Eq. (12),
+ * U <- U + (Wbar - Z).  No norms and no selection.  The mask is read as in oracle_project_frozen (any nonzero byte
+ * = kept; the groups of an unconstrained layer are kept whatever their bytes say; an element of a layer under both
+ * constraints is kept iff its filter byte and its channel byte are nonzero).
+ */
+int oracle_project_weighted_frozen(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                                   const int32_t *khw, const int32_t *mode, const float *const *W, int32_t R,
+                                   float *U, const float *Zg, const float *Vd, const float *a, const float *b,
+                                   float *Z, float *Wbar, const uint8_t *mask)
+{
+    if (L < 1 || R < 1 || !W || !U || !Zg || !Vd || !a || !b || !Z || !mask) return -1;
+    const float inv_R = 1.0f / (float)R;
+    int64_t gbase = 0;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t co = c_out[l], ci = c_in[l], s = khw[l];
+        if (co < 1 || ci < 1 || s < 1) return -1;
+        const int64_t n = co * ci * s;
+        const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
+        const int64_t off = elem_off[l];
+        const uint8_t *ml = mask + gbase;
+        const float al = a[l], bl = b[l];
+        int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+        for (int64_t e = 0; e < n; ++e) {
+            float acc = W[0][off + e];
+            for (int32_t r = 1; r < R; ++r) acc = acc + W[r][off + e];
+            const float wbar = acc * inv_R;
+            const float t = wbar + U[off + e];
+            const float q = Zg[off + e] - Vd[off + e];
+            const float at = al * t;
+            const float bq = bl * q;
+            const float zt = at + bq;
+            if (!isfinite(zt)) bad = 1;
+            int64_t g;
+            if (mode[l] == ORACLE_SHAPE) g = e % (ci * s);
+            else if (mode[l] == ORACLE_CHANNEL) g = (e / s) % ci;
+            else g = e / (ci * s);
+            int keep = mode[l] == ORACLE_NONE || ml[g] != 0;          /* both: g is the filter */
+            if (mode[l] == ORACLE_BOTH) keep = keep && ml[co + (e / s) % ci] != 0;
+            const float z = keep ? zt : 0.0f;
+            Z[off + e] = z;
+            U[off + e] = U[off + e] + (wbar - z);
+            if (Wbar) Wbar[off + e] = wbar;
+        }
+        if (bad) return -2;
+        gbase += G;
+    }
+    return 0;
+}
+
+/*
  * Global consensus, Eq. (11): z = (1/M) sum_i (z_i + v_i).  The terms c_i = z_i + v_i arrive as M buffers of
  * equal length (the compacted pre-transmission buffers of Section 4.4.2, all under the same mask); the sum runs
  * left to right in fp32 in node order and is multiplied by fl32(1/M), the convention of the replica mean.

@@ -93,6 +93,12 @@ MUTATIONS = [
     ("composite_weighted_projects_filters_only",
      "return -2; }\n        if (mode[l] == ORACLE_BOTH || mode[l] == ORACLE_SHAPE) {\n            if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], k_in[l],",
      "return -2; }\n        if (mode[l] == ORACLE_BOTH || mode[l] == ORACLE_SHAPE) {\n            if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], ci,"),
+    ("weighted_frozen_drops_global_term", "const float zt = at + bq;", "const float zt = at;"),
+    ("weighted_frozen_mask_ignored", "const float z = keep ? zt : 0.0f;", "const float z = zt;"),
+    ("weighted_frozen_candidate_drops_dual", "const float t = wbar + U[off + e];", "const float t = wbar;"),
+    ("weighted_frozen_dual_uses_unmasked_candidate",
+     "const float z = keep ? zt : 0.0f;\n            Z[off + e] = z;\n            U[off + e] = U[off + e] + (wbar - z);",
+     "const float z = keep ? zt : 0.0f;\n            Z[off + e] = z;\n            U[off + e] = U[off + e] + (wbar - zt);"),
 ]
 
 PIN_FUNCS = [
@@ -119,6 +125,9 @@ PIN_FUNCS = [
     wpins.test_eq_9_printed_formula_with_per_replica_duals,
     lambda: [wpins.test_weighted_against_numpy(s) for s in range(2)],
     wpins.test_inter_node_dual_update_and_transmission_sum,
+    lambda: [wpins.test_weighted_frozen_with_its_own_mask_is_the_dynamic_weighted_projection(s) for s in range(2)],
+    lambda: [wpins.test_weighted_frozen_with_weights_one_and_zero_is_the_base_frozen_projection(s) for s in range(2)],
+    wpins.test_weighted_frozen_against_the_printed_formulas_in_float64,
     rpins.test_handworked_residuals,
     rpins.test_residuals_against_numpy_and_their_zero_cases,
     lambda: [cpins.test_handworked_composite_layer(c) for c in cpins.CASES],
@@ -152,7 +161,8 @@ def test_a_planted_mistake_in_the_oracle_fails_a_pin(name, old, new, tmp_path, m
     lib = ctypes.CDLL(str(so_file))
     for fn in ("oracle_project", "oracle_compact", "oracle_expand", "oracle_set_threads", "oracle_get_threads",
                "oracle_project_frozen", "oracle_mask_or", "oracle_node_coefficients", "oracle_project_weighted",
-               "oracle_dual_inter", "oracle_add_arenas", "oracle_residuals", "oracle_average", "oracle_mask_drift"):
+               "oracle_dual_inter", "oracle_add_arenas", "oracle_residuals", "oracle_average", "oracle_mask_drift",
+               "oracle_project_weighted_frozen"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(oracle, "_lib", lib)

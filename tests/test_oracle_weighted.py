@@ -138,3 +138,79 @@ def test_inter_node_dual_update_and_transmission_sum():
     t2 = one_layer_table(2, 2, 1, wk.MODE_FILTER, 1)
     c2 = oracle.add_arenas(t2, zi, v)
     assert oracle.dual_inter(t2, zi, c2, v).tolist() == [0, 0, 0, 0]
+
+
+# ---------------------------------------------------------------- retraining branch with the full candidate
+
+def _mixed_workload(rng, seed):
+    from tests.test_oracle_composite import random_table_with_both
+    return wk.custom_workload(random_table_with_both(rng, 8), R=int(rng.integers(1, 5)), seed=seed, sigma_replica=0.03)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_weighted_frozen_with_its_own_mask_is_the_dynamic_weighted_projection(seed):
+    """Algorithm 1, Phase 3: both branches form the same candidate; under the mask the dynamic branch selects, the
+    frozen branch must reproduce its Z, U and Wbar bit for bit."""
+    rng = np.random.default_rng(300 + seed)
+    wl = _mixed_workload(rng, seed)
+    W, U = wk.generate(wl)
+    L = len(wl.layers)
+    Zg = (rng.standard_normal(wl.n_arena) * 0.05).astype(np.float32)
+    Vd = (rng.standard_normal(wl.n_arena) * 0.01).astype(np.float32)
+    a = rng.uniform(0.3, 1.0, L).astype(np.float32)
+    b = rng.uniform(0.0, 0.7, L).astype(np.float32)
+    dyn = oracle.project_weighted(wl.table(), W, U, Zg, Vd, a, b, want_wbar=True)
+    frz = oracle.project_weighted_frozen(wl.table(), W, U, Zg, Vd, a, b, dyn["mask"] * 200, want_wbar=True)
+    for name in ("Z", "U", "Wbar"):
+        assert np.array_equal(dyn[name].view(np.uint32), frz[name].view(np.uint32)), name
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_weighted_frozen_with_weights_one_and_zero_is_the_base_frozen_projection(seed):
+    rng = np.random.default_rng(400 + seed)
+    wl = _mixed_workload(rng, seed)
+    W, U = wk.generate(wl)
+    L = len(wl.layers)
+    Zg = rng.standard_normal(wl.n_arena).astype(np.float32)
+    Vd = rng.standard_normal(wl.n_arena).astype(np.float32)
+    mask = (rng.random(wl.groups_total) < 0.5).astype(np.uint8)
+    base = oracle.project_frozen(wl.table(), W, U, mask, want_wbar=True)
+    wtd = oracle.project_weighted_frozen(wl.table(), W, U, Zg, Vd, np.ones(L), np.zeros(L), mask, want_wbar=True)
+    for name in ("Z", "U", "Wbar"):
+        assert np.array_equal(base[name], wtd[name]), name     # == : a zero may change sign through + (0 * q)
+
+
+def test_weighted_frozen_against_the_printed_formulas_in_float64():
+    """z~ = a (Wbar + U) + b (z - v) (Eq. (9)), z_i = z~ (.) m (Algorithm 1, Phase 3, retraining branch),
+    u <- u + (Wbar - z_i) (Eq. (12)), written out in NumPy float64 on values where fp32 is exact."""
+    rng = np.random.default_rng(9)
+    co, ci, s = 6, 5, 4
+    from tests.test_oracle_composite import both_table
+    t = both_table(co, ci, s, 3, 2)
+    n = co * ci * s
+    W = (rng.integers(-8, 9, (2, n)) / 4.0).astype(np.float32)          # quarters: all sums below are exact in fp32
+    U = (rng.integers(-8, 9, n) / 4.0).astype(np.float32)
+    Zg = (rng.integers(-8, 9, n) / 4.0).astype(np.float32)
+    Vd = (rng.integers(-8, 9, n) / 4.0).astype(np.float32)
+    a, b = np.float32(0.5), np.float32(0.25)
+    mask = np.array([1, 0, 1, 1, 0, 1] + [0, 1, 1, 0, 1], np.uint8)      # filters, then channels
+    out = oracle.project_weighted_frozen(t, W, U, Zg, Vd, [a], [b], mask, want_wbar=True)
+    wbar = W.astype(np.float64).mean(axis=0)
+    zt = 0.5 * (wbar + U) + 0.25 * (Zg.astype(np.float64) - Vd)
+    keep = (mask[:co, None, None] != 0) & (mask[co:][None, :, None] != 0)
+    z = np.where(np.broadcast_to(keep, (co, ci, s)).reshape(-1), zt, 0.0)
+    assert np.array_equal(out["Wbar"].astype(np.float64), wbar)
+    assert np.array_equal(out["Z"].astype(np.float64), z)
+    assert np.array_equal(out["U"].astype(np.float64), U + (wbar - z))
+    # a pruned filter's row and a pruned channel's columns are exactly +0
+    Z3 = out["Z"].reshape(co, ci, s)
+    assert not Z3[1].any() and not Z3[:, 0].any() and not np.signbit(Z3[1]).any()
+    # filter and channel masks alone
+    for mode, m in ((wk.MODE_FILTER, mask[:co]), (wk.MODE_CHANNEL, mask[co:])):
+        o = oracle.project_weighted_frozen(one_layer_table(co, ci, s, mode, 1), W, U, Zg, Vd, [a], [b], m)
+        k3 = (m[:, None, None] != 0) if mode == wk.MODE_FILTER else (m[None, :, None] != 0)
+        assert np.array_equal(o["Z"].astype(np.float64), np.where(np.broadcast_to(k3, (co, ci, s)).reshape(-1), zt, 0.0))
+    # an unconstrained layer ignores its mask bytes
+    o = oracle.project_weighted_frozen(one_layer_table(co, ci, s, wk.MODE_NONE, co), W, U, Zg, Vd, [a], [b],
+                                       np.zeros(co, np.uint8))
+    assert np.array_equal(o["Z"].astype(np.float64), zt)
