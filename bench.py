@@ -262,7 +262,7 @@ def main():
                 if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == dom:
                     roofline["traffic"] = int(parts[2])
 
-    frozen = weighted = residuals = composite = None
+    frozen = weighted = residuals = composite = retrain = None
     if not args.skip_extras:
         # ---- frozen-mask step (Algorithm 1 Phase 3 once the masks are frozen, Section 4.5): the same three calls
         #      with hsadmm_project_frozen in place of hsadmm_project, applying each buffer set's last mask
@@ -381,6 +381,47 @@ def main():
                     "value_GBps": round(w_bytes / w_elapsed / 1e9, 1),
                     "hbm_frac": round(w_bytes / w_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
                     "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in wt.items() if v[1]}}
+
+        # ---- retraining-phase iteration (Algorithm 1, Phase 3 retraining branch + Phase 4, after the masks are frozen,
+        #      Section 4.5): the full candidate under each buffer set's frozen mask, c = z_i + v_i packed by the same
+        #      pass, then decompression + Eq. (13): two calls, two kernel launches.  The mask's index mappings are
+        #      derived once per buffer set, as above.
+        for b in sets:
+            pkg.hsadmm_expand(plan, b.packed, b.mask, b.dst, b.ws, stream=stream)
+
+        def retrain_step():
+            b = sets[counter[0] % nsets]
+            counter[0] += 1
+            if one_call:
+                pkg.hsadmm_project_weighted_frozen_compact(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, True,
+                                                           b.packed, b.off, b.kept, b.ws, stream=stream)
+            else:
+                pkg.hsadmm_project_weighted_frozen(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, stream=stream)
+                pkg.hsadmm_compact_sum(plan, b.Z, b.Vd, None, b.packed, b.off, b.kept, b.ws, stream=stream)
+            pkg.hsadmm_expand_dual(plan, b.packed, None, b.dst, b.Z, b.Vd, b.ws, stream=stream)
+
+        for _ in range(3):
+            retrain_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(wsteps):
+            retrain_step()
+        torch.cuda.synchronize()
+        rt_elapsed = (time.perf_counter() - t0) / wsteps
+        pkg.hsadmm_kernel_timing_enable(plan, True)
+        for _ in range(wsteps):
+            retrain_step()
+        torch.cuda.synchronize()
+        rtt = pkg.hsadmm_kernel_timing_read(plan)
+        pkg.hsadmm_kernel_timing_enable(plan, False)
+        # project: R replicas, U, z, v in, Z, U out (R + 5 arenas); packed written (4 n_kept; as a call of its own the
+        # shrinkage first reads the kept parts of Z and v again, 8 n_kept); expand + Eq. (13) as in the weighted step
+        rt_bytes = 4 * wl.n_total * (wl.R + 9) + (8 if one_call else 16) * nk
+        retrain = {"ms_per_step": round(1e3 * rt_elapsed, 4),
+                   "algorithmic_bytes_per_step": rt_bytes,
+                   "value_GBps": round(rt_bytes / rt_elapsed / 1e9, 1),
+                   "hbm_frac": round(rt_bytes / rt_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                   "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in rtt.items() if v[1]}}
 
         # ---- both constraints on every conv layer (filter + channel; Section 2.1's intersection, projected by the two
         #      projections in sequence): the same shapes, replicas and duals under another layer table
@@ -522,6 +563,7 @@ def main():
         "three_calls_step": three_calls,
         "frozen_mask_step": frozen,
         "weighted_step": weighted,
+        "retraining_step": retrain,
         "residuals": residuals,
         "composite_step": composite,
         "verified_against_oracle": verify,

@@ -14,7 +14,7 @@
  * and, around it: the frozen-mask branch and the mask union (Section 4.5, Eq. (14)), the full node
  * candidate with its rho_2 term, the inter-node dual update and the mean of the nodes' compact
  * buffers (Eq. (9), (13), (11)), the residual norms (Section 3.4) and the mask drift (Section 4.5).
- * Each projection (hsadmm_project, _frozen, _weighted) also exists as a *_compact call that returns the
+ * Each projection (hsadmm_project, _frozen, _weighted, _weighted_frozen) also exists as a *_compact call that returns the
  * shrunk buffer as well, with the same results as the projection followed by the compaction.
  *
  * Data layout.  A layer is the row-major fp32 array W[c_out][c_in][khw]
@@ -347,6 +347,34 @@ int hsadmm_project_weighted_compact(const hsadmm_plan_t* plan, const float* cons
                                     uint8_t* mask, double* sqnorm,
                                     float* packed, int64_t* layer_off, int32_t* kept_idx,
                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The retraining branch of Algorithm 1, Phase 3, with the full candidate of
+ * Eq. (9): z_i = z~ (.) m for a given (frozen) mask m, z~ formed exactly as in
+ * hsadmm_project_weighted with the plan's node weights, then the dual update
+ * of Eq. (12).  No norms, no selection, one pass, no workspace.  The mask is
+ * read as in hsadmm_project_frozen; Zg, Vd and the other arguments as in
+ * hsadmm_project_weighted.  Errors: INVALID_ARGUMENT, UNSUPPORTED, HIP.
+ */
+int hsadmm_project_weighted_frozen(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                                   float* U, const float* Zg, const float* Vd, float* Z, float* Wbar,
+                                   const uint8_t* mask, void* hip_stream);
+
+/*
+ * The same with the shrinkage of c = z_i + v_i under the mask in the same
+ * pass (Section 4.4.1; Section 4.5): the outputs of
+ * hsadmm_project_weighted_frozen(...) followed by hsadmm_compact_sum(plan, Z,
+ * Vd, mask, packed, layer_off, kept_idx, ...), bit for bit.  mappings_cached,
+ * workspace and the compaction outputs as in hsadmm_project_frozen_compact.
+ * Together with hsadmm_expand_dual this is the whole consensus side of a
+ * retraining-phase iteration in two kernel launches.
+ * Errors: INVALID_ARGUMENT, WORKSPACE, UNSUPPORTED, HIP.
+ */
+int hsadmm_project_weighted_frozen_compact(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                                           float* U, const float* Zg, const float* Vd, float* Z, float* Wbar,
+                                           const uint8_t* mask, int32_t mappings_cached,
+                                           float* packed, int64_t* layer_off, int32_t* kept_idx,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Inter-node dual update, Eq. (13): Vd <- Vd + (Zi - Zg) on every layer

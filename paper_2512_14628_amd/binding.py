@@ -32,7 +32,8 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_project_frozen", "hsadmm_mask_or", "hsadmm_compact_sum", "hsadmm_node_coefficients",
            "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals",
            "hsadmm_average", "hsadmm_mask_drift", "hsadmm_expand_dual", "hsadmm_project_compact",
-           "hsadmm_project_weighted_compact", "hsadmm_project_frozen_compact")
+           "hsadmm_project_weighted_compact", "hsadmm_project_frozen_compact",
+           "hsadmm_project_weighted_frozen", "hsadmm_project_weighted_frozen_compact")
 KERNEL_COUNT = 21
 
 
@@ -118,6 +119,11 @@ def load_library():
     lib.hsadmm_project_weighted_compact.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp,
                                                     vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hsadmm_project_weighted_compact.restype = ctypes.c_int
+    lib.hsadmm_project_weighted_frozen.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp]
+    lib.hsadmm_project_weighted_frozen.restype = ctypes.c_int
+    lib.hsadmm_project_weighted_frozen_compact.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp,
+                                                           vp, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_project_weighted_frozen_compact.restype = ctypes.c_int
     lib.hsadmm_residuals.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hsadmm_residuals.restype = ctypes.c_int
     lib.hsadmm_dual_inter.argtypes = [vp, vp, vp, vp, vp]
@@ -369,6 +375,34 @@ def hsadmm_project_weighted_compact(plan: Plan, W_replicas: Sequence, U, Zg, Vd,
                                              _ptr(kept_idx), _ptr(workspace), wb, _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_project_weighted_compact")
+    return rc
+
+
+def hsadmm_project_weighted_frozen(plan: Plan, W_replicas: Sequence, U, Zg, Vd, Z, Wbar, mask, stream=None,
+                                   check: bool = True) -> int:
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    rc = lib.hsadmm_project_weighted_frozen(plan.handle, ptrs, R, _ptr(U), _ptr(Zg), _ptr(Vd), _ptr(Z), _ptr(Wbar),
+                                            _ptr(mask), _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_project_weighted_frozen")
+    return rc
+
+
+def hsadmm_project_weighted_frozen_compact(plan: Plan, W_replicas: Sequence, U, Zg, Vd, Z, Wbar, mask,
+                                           mappings_cached: bool, packed, layer_off, kept_idx, workspace, stream=None,
+                                           workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_project_weighted_frozen_compact(plan.handle, ptrs, R, _ptr(U), _ptr(Zg), _ptr(Vd), _ptr(Z),
+                                                    _ptr(Wbar), _ptr(mask), 1 if mappings_cached else 0,
+                                                    _ptr(packed), _ptr(layer_off), _ptr(kept_idx), _ptr(workspace),
+                                                    wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_project_weighted_frozen_compact")
     return rc
 
 

@@ -910,6 +910,87 @@ int hsadmm_project_weighted_compact(const hsadmm_plan_t* p, const float* const* 
                                  workspace_bytes, hip_stream);
 }
 
+// The retraining branch with the full candidate: one pass of the frozen-mask kernel in its weighted form over every
+// layer's row items; with `out` it also packs c = z_i + v_i under the mask's index mappings.
+static int weighted_frozen_impl(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
+                                const float* Zg, const float* Vd, float* Z, float* Wbar, const uint8_t* mask,
+                                const CompactOut* out, int32_t mappings_cached, void* workspace,
+                                size_t workspace_bytes, void* hip_stream)
+{
+    if (!p || !W_replicas || !U || !Zg || !Vd || !Z || !mask || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (out && (!out->packed || !out->layer_off || !out->kept_idx || !workspace || !is_aligned(out->packed, 16) ||
+                !is_aligned(out->layer_off, 8) || !is_aligned(out->kept_idx, 4) || !is_aligned(workspace, 256)))
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (R > HSADMM_MAX_REPLICAS) return HSADMM_ERR_UNSUPPORTED;
+    if (!is_aligned(U, 16) || !is_aligned(Z, 16) || !is_aligned(Zg, 16) || !is_aligned(Vd, 16) ||
+        (Wbar && !is_aligned(Wbar, 16)))
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    for (int r = 0; r < R; ++r)
+        if (!W_replicas[r] || !is_aligned(W_replicas[r], 16)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (out && workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    ProjectArgs a{};
+    for (int r = 0; r < R; ++r) a.W[r] = W_replicas[r];
+    a.U = U; a.Z = Z; a.Wbar = Wbar;
+    a.inv_R = 1.0f / (float)R;
+    a.Zg = Zg; a.Vd = Vd; a.coef = p->d_coef;
+    PackOut po{};
+    if (out) {
+        if (!mappings_cached) {
+            const int rc = run_scan(p, mask, ws, s);
+            if (rc != HSADMM_OK) return rc;
+        }
+        po.pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
+        po.cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
+        po.kept_idx = reinterpret_cast<const int32_t*>(ws + p->ws.kept_idx);
+        po.layer_off = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
+        po.packed = out->packed;
+        po.co = CopyOut{out->layer_off, out->kept_idx};
+        po.n_layers = (int)p->layers.size();
+    }
+    const unsigned grid = (unsigned)p->items_rows.size();
+    const WorkItem* items = p->d_items_rows;
+    hipError_t e;
+    if (out) {
+        switch (R) {
+            case 1: e = launch(p, kFrozen, project_frozen<1, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            case 2: e = launch(p, kFrozen, project_frozen<2, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            case 4: e = launch(p, kFrozen, project_frozen<4, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            case 8: e = launch(p, kFrozen, project_frozen<8, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            default: e = launch(p, kFrozen, project_frozen<0, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+        }
+    } else {
+        switch (R) {
+            case 1: e = launch(p, kFrozen, project_frozen<1, false, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            case 2: e = launch(p, kFrozen, project_frozen<2, false, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            case 4: e = launch(p, kFrozen, project_frozen<4, false, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            case 8: e = launch(p, kFrozen, project_frozen<8, false, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            default: e = launch(p, kFrozen, project_frozen<0, false, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+        }
+    }
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
+int hsadmm_project_weighted_frozen(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
+                                   const float* Zg, const float* Vd, float* Z, float* Wbar, const uint8_t* mask,
+                                   void* hip_stream)
+{
+    return weighted_frozen_impl(p, W_replicas, R, U, Zg, Vd, Z, Wbar, mask, nullptr, 0, nullptr, 0, hip_stream);
+}
+
+int hsadmm_project_weighted_frozen_compact(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R,
+                                           float* U, const float* Zg, const float* Vd, float* Z, float* Wbar,
+                                           const uint8_t* mask, int32_t mappings_cached, float* packed,
+                                           int64_t* layer_off, int32_t* kept_idx, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream)
+{
+    const CompactOut out{packed, layer_off, kept_idx};
+    return weighted_frozen_impl(p, W_replicas, R, U, Zg, Vd, Z, Wbar, mask, &out, mappings_cached, workspace,
+                                workspace_bytes, hip_stream);
+}
+
 int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, const float* Zi,
                      const float* Zi_prev, const float* Zg, const float* Zg_prev, double* out, void* workspace,
                      size_t workspace_bytes, void* hip_stream)

@@ -82,6 +82,9 @@ def test_hot_calls_reject_null_plan(lib):
                                       None) == -1
     assert lib.hsadmm_project_weighted_compact(None, None, 1, None, None, None, None, None, None, None, None, None,
                                                None, None, 0, None) == -1
+    assert lib.hsadmm_project_weighted_frozen(None, None, 1, None, None, None, None, None, None, None) == -1
+    assert lib.hsadmm_project_weighted_frozen_compact(None, None, 1, None, None, None, None, None, None, 0, None, None,
+                                                      None, None, 0, None) == -1
     assert lib.hsadmm_compact(None, None, None, None, None, None, None, 0, None) == -1
     assert lib.hsadmm_expand(None, None, None, None, None, 0, None) == -1
     assert lib.hsadmm_project_frozen(None, None, 1, None, None, None, None, None) == -1

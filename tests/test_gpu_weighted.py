@@ -171,3 +171,115 @@ def test_weighted_error_codes():
     with pytest.raises(ValueError):
         pkg.hsadmm_plan_set_node_weights(r.plan, [1.0], [0.0])
     r.close()
+
+
+# ---------------------------------------------------------------- retraining branch with the full candidate
+
+def _check_weighted_frozen(wl, W, U, a, b, Zg, Vd, mask_np, want_wbar=True, pack_align=1):
+    """hsadmm_project_weighted_frozen (+ hsadmm_compact_sum, hsadmm_expand_dual) and the one-call form, both ways of
+    getting the index mappings, against the oracle: Z, U, Wbar, packed c = z_i + v_i, offsets, kept indices, the
+    expanded z and the updated v, bit for bit."""
+    import paper_2512_14628_amd as pkg
+    from tests.gpu_harness import GpuRun, bits
+    t = wl.table()
+    ref = oracle.project_weighted_frozen(t, W, U, Zg, Vd, a, b, mask_np, want_wbar=True)
+    m01 = (mask_np != 0).astype(np.uint8)
+    refc = oracle.compact(t, oracle.add_arenas(t, ref["Z"], Vd), m01, pack_align=pack_align)
+    z_new = oracle.expand(t, refc["packed"], m01, wl.n_arena, pack_align=pack_align)
+    v_new = oracle.dual_inter(t, ref["Z"], z_new, Vd)
+    for form in ("two_calls", "one_call", "one_call_cached"):
+        r = GpuRun(wl, W, U, want_wbar=want_wbar, pack_align=pack_align)
+        dZg, dVd = torch.from_numpy(Zg).to(r.dev), torch.from_numpy(Vd).to(r.dev)
+        dm = torch.from_numpy(mask_np).to(r.dev)
+        pkg.hsadmm_plan_set_node_weights(r.plan, a, b)
+        if form == "two_calls":
+            pkg.hsadmm_project_weighted_frozen(r.plan, r.dW, r.dU, dZg, dVd, r.dZ, r.dWbar, dm)
+            pkg.hsadmm_compact_sum(r.plan, r.dZ, dVd, dm, r.dpacked, r.doff, r.dkept, r.ws)
+        else:
+            cached = form == "one_call_cached"
+            if cached:
+                pkg.hsadmm_expand(r.plan, r.dpacked, dm, r.ddst, r.ws)          # leaves this mask's mappings
+            pkg.hsadmm_project_weighted_frozen_compact(r.plan, r.dW, r.dU, dZg, dVd, r.dZ, r.dWbar, dm, cached,
+                                                       r.dpacked, r.doff, r.dkept, r.ws)
+        pkg.hsadmm_expand_dual(r.plan, r.dpacked, None, r.ddst, r.dZ, dVd, r.ws)
+        got = r.outputs()
+        gv = dVd.cpu().numpy()
+        for l in wl.layers:
+            sl = slice(l.elem_off, l.elem_off + l.n)
+            assert np.array_equal(bits(got["Z"][sl]), bits(ref["Z"][sl])), (form, "Z", l.name)
+            assert np.array_equal(bits(got["U"][sl]), bits(ref["U"][sl])), (form, "U", l.name)
+            if want_wbar:
+                assert np.array_equal(bits(got["Wbar"][sl]), bits(ref["Wbar"][sl])), (form, "Wbar", l.name)
+            assert np.array_equal(bits(got["dst"][sl]), bits(z_new[sl])), (form, "expand", l.name)
+            assert np.array_equal(bits(gv[sl]), bits(v_new[sl])), (form, "v", l.name)
+        assert np.array_equal(got["layer_off"], refc["layer_off"]), form
+        assert np.array_equal(got["kept_idx"][:refc["kept_idx"].size], refc["kept_idx"]), form
+        for li, l in enumerate(wl.layers):
+            mk = m01[l.group_base:l.group_base + l.groups]
+            if l.mode == wk.MODE_BOTH:
+                used = int(mk[:l.c_out].sum()) * int(mk[l.c_out:].sum()) * l.khw
+            elif l.mode == wk.MODE_NONE:
+                used = l.n
+            else:
+                used = int(mk.sum()) * l.group_size
+            a0 = int(refc["layer_off"][li])
+            assert np.array_equal(bits(got["packed"][a0:a0 + used]), bits(refc["packed"][a0:a0 + used])), (form, li)
+        r.close()
+
+
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 8])
+def test_weighted_frozen_ragged_shapes_every_mode(R):
+    from tests.test_gpu_composite import _shapes_with_both
+    rng = np.random.default_rng(3300 + R)
+    wl = wk.custom_workload(_shapes_with_both(rng, 12), R=R, seed=R, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    L = len(wl.layers)
+    a = rng.uniform(0.3, 1.0, L).astype(np.float32)
+    b = rng.uniform(0.0, 0.7, L).astype(np.float32)
+    Zg = (rng.standard_normal(wl.n_arena) * 0.05).astype(np.float32)
+    Vd = (rng.standard_normal(wl.n_arena) * 0.01).astype(np.float32)
+    mask = (rng.random(wl.groups_total) < 0.5).astype(np.uint8) * 9
+    _check_weighted_frozen(wl, W, U, a, b, Zg, Vd, mask, want_wbar=(R % 2 == 0), pack_align=(1, 4, 7)[R % 3])
+    # under the mask the dynamic weighted projection selects, the retraining branch reproduces it
+    own = oracle.project_weighted(wl.table(), W, U, Zg, Vd, a, b)["mask"]
+    _check_weighted_frozen(wl, W, U, a, b, Zg, Vd, own, want_wbar=False)
+
+
+@pytest.mark.parametrize("name", ["resnet18", "resnet50", "resnet152"])
+def test_weighted_frozen_named_workloads_union_mask(name):
+    """The retraining-phase step at full size: two nodes' masks OR-ed (Eq. (14)), the union applied as frozen mask."""
+    wl = wk.make_workload(name)
+    W, U = wk.generate(wl, threads=16)
+    Wb, Ub = wk.generate(wk.make_workload(name, seed=7), threads=16)
+    oracle.set_threads(16)
+    L = len(wl.layers)
+    a, b = oracle.node_coefficients([1.5e-3] * L, [1.5e-4] * L, 1e-4, 16, wl.R)
+    rng = np.random.default_rng(2)
+    Zg = (rng.standard_normal(wl.n_arena) * 0.05).astype(np.float32)
+    Vd = (rng.standard_normal(wl.n_arena) * 0.01).astype(np.float32)
+    union = oracle.mask_or([oracle.project_weighted(wl.table(), W, U, Zg, Vd, a, b)["mask"],
+                            oracle.project_weighted(wl.table(), Wb, Ub, Zg, Vd, a, b)["mask"]])
+    _check_weighted_frozen(wl, W, U, a, b, Zg, Vd, union, want_wbar=False)
+
+
+def test_weighted_frozen_error_codes():
+    import paper_2512_14628_amd as pkg
+    from tests.gpu_harness import GpuRun
+    wl = wk.make_workload("tiny")
+    W, U = wk.generate(wl)
+    r = GpuRun(wl, W, U)
+    z = torch.zeros(wl.n_arena, device=r.dev)
+    f = pkg.hsadmm_project_weighted_frozen
+    assert f(r.plan, r.dW, r.dU, None, z, r.dZ, None, r.dmask, check=False) == -1
+    assert f(r.plan, r.dW, r.dU, z, z, r.dZ, None, None, check=False) == -1
+    assert f(r.plan, r.dW, r.dU, z, z[1:], r.dZ, None, r.dmask, check=False) == -1
+    assert f(r.plan, r.dW * 17, r.dU, z, z, r.dZ, None, r.dmask, check=False) == -4
+    fc = pkg.hsadmm_project_weighted_frozen_compact
+    assert fc(r.plan, r.dW, r.dU, z, z, r.dZ, None, r.dmask, False, None, r.doff, r.dkept, r.ws, check=False) == -1
+    assert fc(r.plan, r.dW, r.dU, z, z, r.dZ, None, r.dmask, False, r.dpacked, r.doff, r.dkept, r.ws[:256],
+              check=False) == -2
+    assert fc(r.plan, r.dW, r.dU, z, z, r.dZ, None, r.dmask, False, r.dpacked, r.doff, r.dkept, None,
+              workspace_bytes=1 << 30, check=False) == -1
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(r.dZ).all())                      # nothing above was enqueued
+    r.close()
