@@ -1,4 +1,5 @@
-// hsadmm_project_frozen (cached mask applied in one pass), hsadmm_mask_or and hsadmm_mask_drift.
+// hsadmm_project_frozen / hsadmm_project_weighted_frozen (a given mask applied in one pass; the same kernel is the
+// final pass of CHANNEL and BOTH layers in the dynamic projections), hsadmm_mask_or and hsadmm_mask_drift.
 // Part of the single translation unit built from hsadmm.hip (included there, in order).
 #ifndef KERNELS_FROZEN_HPP
 #define KERNELS_FROZEN_HPP
@@ -146,7 +147,7 @@ __device__ __forceinline__ void quad_packed_cols(const int32_t* __restrict__ ran
 }
 
 // Row items of every mode (the compact / expand item table): no keys, no second pass, every byte of the
-// replicas and of U is read once and Z and U are written once, streaming along the rows.  FILTER / NONE rows
+// replicas (or of the parked mean) and of U is read once and Z and U are written once, streaming along the rows.  FILTER / NONE rows
 // share one keep flag; in CHANNEL rows and in the kept filters' rows of a BOTH layer every column takes the
 // flag of its channel.
 // PACK: what the mask keeps also goes to the packed buffer as it is formed, under the index mappings of this
