@@ -283,3 +283,63 @@ def test_weighted_frozen_error_codes():
     torch.cuda.synchronize()
     assert bool(torch.isnan(r.dZ).all())                      # nothing above was enqueued
     r.close()
+
+
+def test_a_captured_graph_replays_the_retraining_phase_iteration():
+    """The two calls of a retraining-phase iteration (full candidate under the frozen mask with c = z_i + v_i packed,
+    then decompression + Eq. (13)) captured into a HIP graph; U and v are updated in place, so the replays form a
+    sequence of iterations, each compared bit for bit with the eager sequence."""
+    import paper_2512_14628_amd as pkg
+    from tests.gpu_harness import GpuRun, bits
+    wl = wk.make_workload("resnet18")
+    W, U = wk.generate(wl, threads=8)
+    L = len(wl.layers)
+    a, b = oracle.node_coefficients([1.5e-3] * L, [1.5e-4] * L, 1e-4, 16, wl.R)
+    rng = np.random.default_rng(6)
+    Zg = (rng.standard_normal(wl.n_arena) * 0.05).astype(np.float32)
+    Vd = (rng.standard_normal(wl.n_arena) * 0.01).astype(np.float32)
+    mask = oracle.project_weighted(wl.table(), W, U, Zg, Vd, a, b)["mask"]
+
+    def setup():
+        r = GpuRun(wl, W, U, want_wbar=False, want_sqnorm=False)
+        r.dZg, r.dVd = torch.from_numpy(Zg).to(r.dev), torch.from_numpy(Vd).to(r.dev)
+        r.dm = torch.from_numpy(mask).to(r.dev)
+        pkg.hsadmm_plan_set_node_weights(r.plan, a, b)
+        pkg.hsadmm_expand(r.plan, r.dpacked, r.dm, r.ddst, r.ws)          # the frozen mask's index mappings, once
+        torch.cuda.synchronize()
+        return r
+
+    def iteration(r, stream=None):
+        pkg.hsadmm_project_weighted_frozen_compact(r.plan, r.dW, r.dU, r.dZg, r.dVd, r.dZ, None, r.dm, True, r.dpacked,
+                                                   r.doff, r.dkept, r.ws, stream=stream)
+        pkg.hsadmm_expand_dual(r.plan, r.dpacked, None, r.ddst, r.dZ, r.dVd, r.ws, stream=stream)
+
+    eager = setup()
+    expected = []
+    for _ in range(3):
+        iteration(eager)
+        torch.cuda.synchronize()
+        expected.append({"Z": eager.dZ.cpu().numpy(), "U": eager.dU.cpu().numpy(), "dst": eager.ddst.cpu().numpy(),
+                         "v": eager.dVd.cpu().numpy()})
+    run = setup()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        iteration(run, stream=side)
+    torch.cuda.synchronize()
+    assert np.array_equal(run.dU.cpu().numpy(), U)                          # capture does not execute
+    scratch = torch.zeros(1 << 20, device=run.dev)
+    for it in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {"Z": run.dZ.cpu().numpy(), "U": run.dU.cpu().numpy(), "dst": run.ddst.cpu().numpy(),
+               "v": run.dVd.cpu().numpy()}
+        for k, v in expected[it].items():
+            for l in wl.layers:
+                sl = slice(l.elem_off, l.elem_off + l.n)
+                assert np.array_equal(bits(got[k][sl]), bits(v[sl])), (it, k, l.name)
+        scratch.add_(1.0)                                                     # eager work between replays
+        assert float(scratch.sum().item()) == float((it + 1) * (1 << 20))
+    run.close()
+    eager.close()
