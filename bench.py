@@ -262,7 +262,7 @@ def main():
                 if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == dom:
                     roofline["traffic"] = int(parts[2])
 
-    frozen = weighted = residuals = composite = retrain = None
+    frozen = weighted = residuals = composite = retrain = retrain_res = None
     if not args.skip_extras:
         # ---- frozen-mask step (Algorithm 1 Phase 3 once the masks are frozen, Section 4.5): the same three calls
         #      with hsadmm_project_frozen in place of hsadmm_project, applying each buffer set's last mask
@@ -423,6 +423,39 @@ def main():
                    "hbm_frac": round(rt_bytes / rt_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
                    "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in rtt.items() if v[1]}}
 
+        # ---- the same iteration with its convergence check (Algorithm 1, Phase 5; Section 3.4): the four residual
+        #      norms accumulated by the two kernels that form z_i and z, against the iteration above followed by a
+        #      hsadmm_residuals pass.  The fused pair also reads the previous z_i and the previous z (2 arenas more
+        #      than the iteration alone); the separate pass reads R + 4 arenas.
+        def retrain_res_step():
+            b = sets[counter[0] % nsets]
+            counter[0] += 1
+            pkg.hsadmm_retrain_project(plan, b.W, b.U, b.Zg, b.Vd, b.Z, None, b.mask, True, b.packed, b.off, b.kept,
+                                       res_out, b.ws, stream=stream)
+            pkg.hsadmm_retrain_expand(plan, b.packed, None, b.dst, b.Z, b.Vd, b.Zg, res_out, b.ws, stream=stream)
+
+        for _ in range(3):
+            retrain_res_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(wsteps):
+            retrain_res_step()
+        torch.cuda.synchronize()
+        rr_elapsed = (time.perf_counter() - t0) / wsteps
+        pkg.hsadmm_kernel_timing_enable(plan, True)
+        for _ in range(wsteps):
+            retrain_res_step()
+        torch.cuda.synchronize()
+        rrt = pkg.hsadmm_kernel_timing_read(plan)
+        pkg.hsadmm_kernel_timing_enable(plan, False)
+        rr_bytes = 4 * wl.n_total * (wl.R + 11) + 8 * nk
+        retrain_res = {"ms_per_step": round(1e3 * rr_elapsed, 4),
+                       "algorithmic_bytes_per_step": rr_bytes,
+                       "value_GBps": round(rr_bytes / rr_elapsed / 1e9, 1),
+                       "hbm_frac": round(rr_bytes / rr_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                       "ms_per_step_with_a_separate_residual_pass": round(1e3 * rt_elapsed + 1e-3 * r_us, 4),
+                       "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in rrt.items() if v[1]}}
+
         # ---- both constraints on every conv layer (filter + channel; Section 2.1's intersection, projected by the two
         #      projections in sequence): the same shapes, replicas and duals under another layer table
         if args.workload == "resnet50":
@@ -564,6 +597,7 @@ def main():
         "frozen_mask_step": frozen,
         "weighted_step": weighted,
         "retraining_step": retrain,
+        "retraining_step_with_residuals": retrain_res,
         "residuals": residuals,
         "composite_step": composite,
         "verified_against_oracle": verify,

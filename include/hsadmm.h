@@ -447,6 +447,46 @@ int hsadmm_expand(const hsadmm_plan_t* plan, const float* packed, const uint8_t*
 int hsadmm_expand_dual(const hsadmm_plan_t* plan, const float* packed, const uint8_t* mask, float* dst,
                        const float* Zi, float* Vd, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * A retraining-phase iteration with its convergence check (Algorithm 1,
+ * Phases 3 to 5 under a frozen mask, Section 4.5; residual norms of Section
+ * 3.4) in two calls that touch every tensor once: the residual norms are
+ * accumulated by the kernels that form z_i and z, instead of by a pass of
+ * hsadmm_residuals over W, z_i and z afterwards.
+ *
+ * hsadmm_retrain_project: hsadmm_project_weighted_frozen_compact (same
+ * arguments, same outputs, bit for bit) except that
+ *   Z          device, in/out: holds the previous z_i on entry (zeros before
+ *              the first iteration), the new z_i on return
+ *   residuals  device, out, 4*L doubles, 8-byte aligned, laid out as
+ *              hsadmm_residuals lays out `out`: rows 0 and 1 are written,
+ *                  residuals[0*L + l] = sum over the R replicas of || W_r - z_i ||_F^2
+ *                  residuals[1*L + l] = || z_i - z_i(previous) ||_F^2
+ *              rows 2 and 3 are left as they are.
+ * hsadmm_retrain_expand: hsadmm_expand_dual (same arguments, same outputs,
+ * bit for bit) and
+ *   z_prev     device, in: the previous global consensus, a full-layout
+ *              arena other than dst (INVALID_ARGUMENT if the two overlap),
+ *              16-byte aligned
+ *   residuals  rows 2 and 3 are written,
+ *                  residuals[2*L + l] = || Zi - z ||_F^2
+ *                  residuals[3*L + l] = || z - z_prev ||_F^2
+ *              rows 0 and 1 are left as they are.
+ * The four norms equal those of hsadmm_residuals(plan, W, R, z_i, z_i
+ * (previous), z, z_prev, ...) up to the order of the fp64 additions, which is
+ * fixed here too (reproducible run to run).  Each call finishes its own two
+ * rows; nothing is carried from one call to the other.
+ * Errors: those of the calls they extend.
+ */
+int hsadmm_retrain_project(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                           float* U, const float* Zg, const float* Vd, float* Z, float* Wbar,
+                           const uint8_t* mask, int32_t mappings_cached,
+                           float* packed, int64_t* layer_off, int32_t* kept_idx, double* residuals,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+int hsadmm_retrain_expand(const hsadmm_plan_t* plan, const float* packed, const uint8_t* mask, float* dst,
+                          const float* Zi, float* Vd, const float* z_prev, double* residuals,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static string for an error code (never NULL). */
 const char* hsadmm_strerror(int code);
 
@@ -467,7 +507,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 21
+#define HSADMM_KERNEL_COUNT 23
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

@@ -33,8 +33,9 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_plan_set_node_weights", "hsadmm_project_weighted", "hsadmm_dual_inter", "hsadmm_residuals",
            "hsadmm_average", "hsadmm_mask_drift", "hsadmm_expand_dual", "hsadmm_project_compact",
            "hsadmm_project_weighted_compact", "hsadmm_project_frozen_compact",
-           "hsadmm_project_weighted_frozen", "hsadmm_project_weighted_frozen_compact")
-KERNEL_COUNT = 21
+           "hsadmm_project_weighted_frozen", "hsadmm_project_weighted_frozen_compact",
+           "hsadmm_retrain_project", "hsadmm_retrain_expand")
+KERNEL_COUNT = 23
 
 
 class HsadmmError(RuntimeError):
@@ -124,6 +125,11 @@ def load_library():
     lib.hsadmm_project_weighted_frozen_compact.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp,
                                                            vp, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hsadmm_project_weighted_frozen_compact.restype = ctypes.c_int
+    lib.hsadmm_retrain_project.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp,
+                                           ctypes.c_int32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_retrain_project.restype = ctypes.c_int
+    lib.hsadmm_retrain_expand.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_retrain_expand.restype = ctypes.c_int
     lib.hsadmm_residuals.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hsadmm_residuals.restype = ctypes.c_int
     lib.hsadmm_dual_inter.argtypes = [vp, vp, vp, vp, vp]
@@ -403,6 +409,34 @@ def hsadmm_project_weighted_frozen_compact(plan: Plan, W_replicas: Sequence, U, 
                                                     wb, _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_project_weighted_frozen_compact")
+    return rc
+
+
+def hsadmm_retrain_project(plan: Plan, W_replicas: Sequence, U, Zg, Vd, Z, Wbar, mask, mappings_cached: bool,
+                           packed, layer_off, kept_idx, residuals, workspace, stream=None,
+                           workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    """hsadmm_project_weighted_frozen_compact that also writes rows 0 and 1 of `residuals` (Z in: previous z_i)."""
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_retrain_project(plan.handle, ptrs, R, _ptr(U), _ptr(Zg), _ptr(Vd), _ptr(Z), _ptr(Wbar),
+                                    _ptr(mask), 1 if mappings_cached else 0, _ptr(packed), _ptr(layer_off),
+                                    _ptr(kept_idx), _ptr(residuals), _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_retrain_project")
+    return rc
+
+
+def hsadmm_retrain_expand(plan: Plan, packed, mask, dst, Zi, Vd, z_prev, residuals, workspace, stream=None,
+                          workspace_bytes: Optional[int] = None, check: bool = True) -> int:
+    """hsadmm_expand_dual that also writes rows 2 and 3 of `residuals` (z_prev: the previous global consensus)."""
+    lib = load_library()
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_retrain_expand(plan.handle, _ptr(packed), _ptr(mask), _ptr(dst), _ptr(Zi), _ptr(Vd), _ptr(z_prev),
+                                   _ptr(residuals), _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_retrain_expand")
     return rc
 
 

@@ -73,7 +73,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -120,6 +120,14 @@ struct hsadmm_plan {
 };
 
 namespace {
+
+// true when two buffers of n floats share an element
+bool spans_overlap(const float* a, const float* b, int64_t n)
+{
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    const uintptr_t bytes = (uintptr_t)n * sizeof(float);
+    return x < y + bytes && y < x + bytes;
+}
 
 int ceil_pow2(int x)
 {
@@ -915,9 +923,11 @@ int hsadmm_project_weighted_compact(const hsadmm_plan_t* p, const float* const* 
 static int weighted_frozen_impl(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
                                 const float* Zg, const float* Vd, float* Z, float* Wbar, const uint8_t* mask,
                                 const CompactOut* out, int32_t mappings_cached, void* workspace,
-                                size_t workspace_bytes, void* hip_stream)
+                                size_t workspace_bytes, void* hip_stream, double* residuals = nullptr,
+                                bool with_residuals = false)
 {
     if (!p || !W_replicas || !U || !Zg || !Vd || !Z || !mask || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (with_residuals && (!out || !residuals || !is_aligned(residuals, 8))) return HSADMM_ERR_INVALID_ARGUMENT;
     if (out && (!out->packed || !out->layer_off || !out->kept_idx || !workspace || !is_aligned(out->packed, 16) ||
                 !is_aligned(out->layer_off, 8) || !is_aligned(out->kept_idx, 4) || !is_aligned(workspace, 256)))
         return HSADMM_ERR_INVALID_ARGUMENT;
@@ -953,7 +963,19 @@ static int weighted_frozen_impl(const hsadmm_plan_t* p, const float* const* W_re
     const unsigned grid = (unsigned)p->items_rows.size();
     const WorkItem* items = p->d_items_rows;
     hipError_t e;
-    if (out) {
+    if (with_residuals) {
+        a.respart = reinterpret_cast<double*>(ws + p->ws.respart);
+        switch (R) {
+            case 1: e = launch(p, kRetrainProject, project_frozen<1, true, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            case 2: e = launch(p, kRetrainProject, project_frozen<2, true, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            case 4: e = launch(p, kRetrainProject, project_frozen<4, true, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            case 8: e = launch(p, kRetrainProject, project_frozen<8, true, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+            default: e = launch(p, kRetrainProject, project_frozen<0, true, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
+        }
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+        e = launch(p, kResFinish, residual_finish, (unsigned)p->layers.size(), kBlock, s, (const DevLayer*)p->d_layers,
+                   (int)p->layers.size(), (const double*)a.respart, residuals, 0, 2);
+    } else if (out) {
         switch (R) {
             case 1: e = launch(p, kFrozen, project_frozen<1, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
             case 2: e = launch(p, kFrozen, project_frozen<2, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
@@ -991,6 +1013,16 @@ int hsadmm_project_weighted_frozen_compact(const hsadmm_plan_t* p, const float* 
                                 workspace_bytes, hip_stream);
 }
 
+int hsadmm_retrain_project(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
+                           const float* Zg, const float* Vd, float* Z, float* Wbar, const uint8_t* mask,
+                           int32_t mappings_cached, float* packed, int64_t* layer_off, int32_t* kept_idx,
+                           double* residuals, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    const CompactOut out{packed, layer_off, kept_idx};
+    return weighted_frozen_impl(p, W_replicas, R, U, Zg, Vd, Z, Wbar, mask, &out, mappings_cached, workspace,
+                                workspace_bytes, hip_stream, residuals, true);
+}
+
 int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, const float* Zi,
                      const float* Zi_prev, const float* Zg, const float* Zg_prev, double* out, void* workspace,
                      size_t workspace_bytes, void* hip_stream)
@@ -1021,7 +1053,7 @@ int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     e = launch(p, kResFinish, residual_finish, (unsigned)p->layers.size(), kBlock, s,
-               (const DevLayer*)p->d_layers, (int)p->layers.size(), (const double*)a.part, out);
+               (const DevLayer*)p->d_layers, (int)p->layers.size(), (const double*)a.part, out, 0, 4);
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
@@ -1057,9 +1089,13 @@ int hsadmm_average(const hsadmm_plan_t* p, const float* const* bufs, int32_t M, 
 }
 
 static int expand_impl(const hsadmm_plan_t* p, const float* packed, const uint8_t* mask, float* dst, const float* Zi,
-                       float* Vd, bool dual, void* workspace, size_t workspace_bytes, void* hip_stream)
+                       float* Vd, bool dual, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       const float* z_prev = nullptr, double* residuals = nullptr, bool with_residuals = false)
 {
     if (!p || !packed || !dst || !workspace || (dual && (!Zi || !Vd))) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (with_residuals && (!dual || !z_prev || !residuals || !is_aligned(z_prev, 16) || !is_aligned(residuals, 8) ||
+                           spans_overlap(z_prev, dst, p->arena_elems)))
+        return HSADMM_ERR_INVALID_ARGUMENT;
     if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (!is_aligned(packed, 16) || !is_aligned(dst, 16) || !is_aligned(workspace, 256) ||
         (dual && (!is_aligned(Zi, 16) || !is_aligned(Vd, 16))))
@@ -1074,12 +1110,23 @@ static int expand_impl(const hsadmm_plan_t* p, const float* packed, const uint8_
     }   // else: the index mappings already held in this workspace are used
     const int32_t* pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
     const int32_t* cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
+    if (with_residuals) {
+        double* part = reinterpret_cast<double*>(ws + p->ws.respart);
+        hipError_t e = launch(p, kRetrainExpand, expand_scatter<true, true>, (unsigned)p->items_rows.size(), kBlock, s,
+                              (const WorkItem*)p->d_items_rows, packed, pos, cnt, (int)p->layers.size(), lo, dst, Zi, Vd,
+                              z_prev, part);
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
+        e = launch(p, kResFinish, residual_finish, (unsigned)p->layers.size(), kBlock, s, (const DevLayer*)p->d_layers,
+                   (int)p->layers.size(), (const double*)part, residuals, 2, 4);
+        return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+    }
     const hipError_t e = dual
         ? launch(p, kScatter, expand_scatter<true>, (unsigned)p->items_rows.size(), kBlock, s,
-                 (const WorkItem*)p->d_items_rows, packed, pos, cnt, (int)p->layers.size(), lo, dst, Zi, Vd)
+                 (const WorkItem*)p->d_items_rows, packed, pos, cnt, (int)p->layers.size(), lo, dst, Zi, Vd,
+                 (const float*)nullptr, (double*)nullptr)
         : launch(p, kScatter, expand_scatter<false>, (unsigned)p->items_rows.size(), kBlock, s,
                  (const WorkItem*)p->d_items_rows, packed, pos, cnt, (int)p->layers.size(), lo, dst,
-                 (const float*)nullptr, (float*)nullptr);
+                 (const float*)nullptr, (float*)nullptr, (const float*)nullptr, (double*)nullptr);
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
@@ -1093,6 +1140,14 @@ int hsadmm_expand_dual(const hsadmm_plan_t* p, const float* packed, const uint8_
                        float* Vd, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     return expand_impl(p, packed, mask, dst, Zi, Vd, true, workspace, workspace_bytes, hip_stream);
+}
+
+int hsadmm_retrain_expand(const hsadmm_plan_t* p, const float* packed, const uint8_t* mask, float* dst,
+                          const float* Zi, float* Vd, const float* z_prev, double* residuals, void* workspace,
+                          size_t workspace_bytes, void* hip_stream)
+{
+    return expand_impl(p, packed, mask, dst, Zi, Vd, true, workspace, workspace_bytes, hip_stream, z_prev,
+                       residuals, true);
 }
 
 const char* hsadmm_strerror(int code)
@@ -1169,6 +1224,8 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kMaskDrift: return "mask_drift";
         case kFixupGather: return "fixup_gather";
         case kWFixupPack: return "weighted_fixup_pack";
+        case kRetrainProject: return "retrain_project";
+        case kRetrainExpand: return "retrain_expand";
         default: return "";
     }
 }

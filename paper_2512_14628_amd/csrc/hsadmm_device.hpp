@@ -18,7 +18,7 @@ constexpr int kWideRow = 2048;                  // rows at least this long are s
 constexpr int kChanRows = 64;               // CHANNEL tiles: rows per row block
 constexpr int kBothRows = 64;               // composite_colsums tiles: rows per row block
 constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
-constexpr int kVersion = 160;
+constexpr int kVersion = 170;
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -128,6 +128,7 @@ struct ProjectArgs {
     const float* Zg;      // global consensus z
     const float* Vd;      // inter-node dual v_i
     const float* coef;    // per layer: a_l, b_l
+    double* respart;      // per row item: 4 partial sums of squared residuals (kernels that also form the norms)
 };
 
 // Streaming (touch-once) accesses.
@@ -160,6 +161,36 @@ __device__ __forceinline__ double wave_xor_sum(double a, int width)
     // butterfly over `width` adjacent lanes; every lane ends with the same bits
     for (int o = width >> 1; o > 0; o >>= 1) a += __shfl_xor(a, o, kWave);
     return a;
+}
+
+// acc + (a - b)^2 in fp64 (the terms of the squared residual norms of Section 3.4)
+__device__ __forceinline__ double sqd(double acc, float a, float b)
+{
+    const double d = (double)a - (double)b;
+    return fma(d, d, acc);
+}
+
+__device__ __forceinline__ double sqd4(double acc, const v4f& a, const v4f& b)
+{
+    acc = sqd(acc, a.x, b.x);
+    acc = sqd(acc, a.y, b.y);
+    acc = sqd(acc, a.z, b.z);
+    return sqd(acc, a.w, b.w);
+}
+
+// Two per-thread fp64 sums of a workgroup -> dst[0], dst[1]: a butterfly per wave, then the waves in order.
+__device__ __forceinline__ void block_sum_pair(double s0, double s1, double* __restrict__ dst)
+{
+    __shared__ double red[kWaves][2];
+    s0 = wave_xor_sum(s0, kWave);
+    s1 = wave_xor_sum(s1, kWave);
+    if ((threadIdx.x & (kWave - 1)) == 0) { red[threadIdx.x / kWave][0] = s0; red[threadIdx.x / kWave][1] = s1; }
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        double t = red[0][threadIdx.x];
+        for (int w = 1; w < kWaves; ++w) t += red[w][threadIdx.x];
+        dst[threadIdx.x] = t;
+    }
 }
 
 __device__ __forceinline__ int wave_sum_i32(int a)

@@ -329,28 +329,44 @@ __global__ __launch_bounds__(kBlock) void weighted_fixup_pack(const WorkItem* __
 
 // DUAL: the expanded tensor is the new global consensus z, and the inter-node dual update of Eq. (13),
 // Vd <- Vd + (Zi - z), is applied in the same pass (z is not read back from memory).
-template <bool DUAL>
+// RES (with DUAL): the item's inter-node residual sums of Section 3.4, (Zi - z)^2 and (z - z_prev)^2 in fp64,
+// also go to part[4 * item + 2, 3]; z_prev is a buffer other than dst.
+template <bool DUAL, bool RES = false>
 __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restrict__ items,
                                                          const float* __restrict__ packed,
                                                          const int32_t* __restrict__ pos,
                                                          const int32_t* __restrict__ cnt, int n_layers,
                                                          const int64_t* __restrict__ layer_off,
                                                          float* __restrict__ dst,
-                                                         const float* __restrict__ Zi, float* __restrict__ Vd)
+                                                         const float* __restrict__ Zi, float* __restrict__ Vd,
+                                                         const float* __restrict__ z_prev = nullptr,
+                                                         double* __restrict__ part = nullptr)
 {
+    static_assert(DUAL || !RES, "the residual sums are formed with the dual update");
+    double s_ro = 0.0, s_so = 0.0;
     // stores 4 (or 1) elements of z at arena element e and, with DUAL, updates Vd there
     auto put4 = [&](int64_t e, const v4f& z) {
         st4(dst + e, z);
         if (DUAL) {
-            const v4f d = ld4(Zi + e) - z;
+            const v4f zi = ld4(Zi + e);
+            const v4f d = zi - z;
             st4(Vd + e, ld4(Vd + e) + d);
+            if (RES) {
+                s_ro = sqd4(s_ro, zi, z);
+                s_so = sqd4(s_so, z, ld4(z_prev + e));
+            }
         }
     };
     auto put1 = [&](int64_t e, float z) {
         dst[e] = z;
         if (DUAL) {
-            const float d = Zi[e] - z;
+            const float zi = Zi[e];
+            const float d = zi - z;
             Vd[e] = Vd[e] + d;
+            if (RES) {
+                s_ro = sqd(s_ro, zi, z);
+                s_so = sqd(s_so, z, z_prev[e]);
+            }
         }
     };
     const WorkItem it = items[blockIdx.x];
@@ -438,6 +454,7 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
             }
         }
     }
+    if (RES) block_sum_pair(s_ro, s_so, part + (int64_t)blockIdx.x * 4 + 2);
 }
 
 }  // namespace

@@ -17,20 +17,33 @@ constexpr int kMeanInZ = -1;
 // PACK: d, when not null, is where the 4 elements go in the packed buffer (rows packed whole).
 // WEIGHTED: the candidate is z~ = fl(fl(a t) + fl(b (Zg - Vd))), t = Wbar + U (Eq. (9)), and what is packed is
 // c = z + Vd (Section 4.4.1); else the candidate is t and what is packed is z.  The value packed is returned.
-template <int R, bool PACK = false, bool WEIGHTED = false>
+// RES: Z holds the previous z_i on entry; acc[0] += sum_j (W_j - z)^2 and acc[1] += (z - z_prev)^2 over the
+// 4 elements, in fp64 (the intra-node primal and dual residuals of Section 3.4).  With a compile-time R the
+// replicas' values stay in registers for this; with a run-time R they are read a second time.
+template <int R, bool PACK = false, bool WEIGHTED = false, bool RES = false>
 __device__ __forceinline__ v4f frozen4(const ProjectArgs& a, int Rrt, int64_t e, bool k0, bool k1, bool k2, bool k3,
-                                       float* d = nullptr, float al = 1.f, float bl = 0.f)
+                                       float* d = nullptr, float al = 1.f, float bl = 0.f, double* acc = nullptr)
 {
+    static_assert(!RES || R != kMeanInZ, "the residual norms need the replicas");
+    constexpr int kHeld = (RES && R > 0) ? R : 1;
+    v4f w[kHeld];
     v4f wb;
     if (R == kMeanInZ) {
         wb = ld4(a.Z + e);
     } else {
         const int RR = R > 0 ? R : Rrt;
         v4f s = ld4(a.W[0] + e);
+        if (RES && R > 0) w[0] = s;
 #pragma unroll
-        for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+        for (int r = 1; r < RR; ++r) {
+            const v4f x = ld4(a.W[r] + e);
+            if (RES && R > 0) w[r] = x;
+            s = s + x;
+        }
         wb = s * a.inv_R;
     }
+    v4f zprev = {0.f, 0.f, 0.f, 0.f};
+    if (RES) zprev = ld4(a.Z + e);
     const v4f u = ld4(a.U + e);
     v4f v = wb + u;
     v4f vd = {0.f, 0.f, 0.f, 0.f};
@@ -48,14 +61,23 @@ __device__ __forceinline__ v4f frozen4(const ProjectArgs& a, int Rrt, int64_t e,
     if (a.Wbar) st4(a.Wbar + e, wb);
     const v4f c = WEIGHTED ? z + vd : z;
     if (PACK && d) st4u(d, c);
+    if (RES) {
+        const int RR = R > 0 ? R : Rrt;
+        acc[1] = sqd4(acc[1], z, zprev);
+#pragma unroll
+        for (int r = 0; r < RR; ++r) acc[0] = sqd4(acc[0], R > 0 ? w[r] : ld4(a.W[r] + e), z);
+    }
     return c;
 }
 
 // two chunks of one row (same keep flag) with all loads issued before any store
-template <int R, bool PACK = false, bool WEIGHTED = false>
+template <int R, bool PACK = false, bool WEIGHTED = false, bool RES = false>
 __device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, bool keep,
-                                          float* d0 = nullptr, float* d1 = nullptr, float al = 1.f, float bl = 0.f)
+                                          float* d0 = nullptr, float* d1 = nullptr, float al = 1.f, float bl = 0.f,
+                                          double* acc = nullptr)
 {
+    constexpr int kHeld = (RES && R > 0) ? R : 1;
+    v4f wa[kHeld], wc[kHeld];
     v4f wb0, wb1;
     if (R == kMeanInZ) {
         wb0 = ld4(a.Z + e0);
@@ -63,18 +85,22 @@ __device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t
     } else {
         const int RR = R > 0 ? R : Rrt;
         v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
+        if (RES && R > 0) { wa[0] = s0; wc[0] = s1; }
 #pragma unroll
         for (int r = 1; r < RR; ++r) {
             const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
+            if (RES && R > 0) { wa[r] = w0; wc[r] = w1; }
             s0 = s0 + w0;
             s1 = s1 + w1;
         }
         wb0 = s0 * a.inv_R;
         wb1 = s1 * a.inv_R;
     }
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    v4f zp0 = zero4, zp1 = zero4;
+    if (RES) { zp0 = ld4(a.Z + e0); zp1 = ld4(a.Z + e1); }
     const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
     v4f v0 = wb0 + u0, v1 = wb1 + u1;
-    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
     v4f vd0 = zero4, vd1 = zero4;
     if (WEIGHTED && keep) {         // a pruned row needs neither z nor v
         vd0 = ld4(a.Vd + e0);
@@ -92,12 +118,24 @@ __device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t
     st4(a.U + e1, u1 + (wb1 - z1));
     if (a.Wbar) { st4(a.Wbar + e0, wb0); st4(a.Wbar + e1, wb1); }
     if (PACK && d0) { st4u(d0, WEIGHTED ? z0 + vd0 : z0); st4u(d1, WEIGHTED ? z1 + vd1 : z1); }
+    if (RES) {
+        const int RR = R > 0 ? R : Rrt;
+        acc[1] = sqd4(acc[1], z0, zp0);
+        acc[1] = sqd4(acc[1], z1, zp1);
+#pragma unroll
+        for (int r = 0; r < RR; ++r) {
+            acc[0] = sqd4(acc[0], R > 0 ? wa[r] : ld4(a.W[r] + e0), z0);
+            acc[0] = sqd4(acc[0], R > 0 ? wc[r] : ld4(a.W[r] + e1), z1);
+        }
+    }
 }
 
-template <int R, bool PACK = false, bool WEIGHTED = false>
+template <int R, bool PACK = false, bool WEIGHTED = false, bool RES = false>
 __device__ __forceinline__ float frozen1(const ProjectArgs& a, int Rrt, int64_t e, bool keep, float* d = nullptr,
-                                         float al = 1.f, float bl = 0.f)
+                                         float al = 1.f, float bl = 0.f, double* acc = nullptr)
 {
+    float zprev = 0.f;
+    if (RES) zprev = ld1(a.Z + e);
     float wb;
     if (R == kMeanInZ) {
         wb = ld1(a.Z + e);
@@ -124,6 +162,11 @@ __device__ __forceinline__ float frozen1(const ProjectArgs& a, int Rrt, int64_t 
     if (a.Wbar) st1(a.Wbar + e, wb);
     const float c = WEIGHTED ? z + vd : z;
     if (PACK && d) *d = c;
+    if (RES) {
+        const int RR = R > 0 ? R : Rrt;
+        acc[1] = sqd(acc[1], z, zprev);
+        for (int r = 0; r < RR; ++r) acc[0] = sqd(acc[0], ld1(a.W[r] + e), z);
+    }
     return c;
 }
 
@@ -153,9 +196,11 @@ __device__ __forceinline__ void quad_packed_cols(const int32_t* __restrict__ ran
 // PACK: what the mask keeps also goes to the packed buffer as it is formed, under the index mappings of this
 // mask (po): a kept FILTER row or a row of a NONE layer whole, at its rank; of a CHANNEL row, or a kept filter's
 // row of a BOTH layer, the columns of kept channels, each at its packed column.
-template <int R, bool PACK, bool WEIGHTED = false>
+// RES: acc[0], acc[1] take this thread's share of the item's two intra-node residual sums (see frozen4).
+template <int R, bool PACK, bool WEIGHTED = false, bool RES = false>
 __device__ __forceinline__ void frozen_item(const WorkItem& it, const ProjectArgs& a, int Rrt,
-                                            const uint8_t* __restrict__ mask, const PackOut& po)
+                                            const uint8_t* __restrict__ mask, const PackOut& po,
+                                            double* acc = nullptr)
 {
     const int mode = item_mode(it);
     const float al = WEIGHTED ? a.coef[2 * it.layer] : 1.f, bl = WEIGHTED ? a.coef[2 * it.layer + 1] : 0.f;
@@ -196,7 +241,7 @@ __device__ __forceinline__ void frozen_item(const WorkItem& it, const ProjectArg
                     const int col = c << 2;
                     bool pr[4];
                     quad_pruned(mc, div, col, pr);
-                    const v4f z = frozen4<R, false, WEIGHTED>(a, Rrt, base + col, !pr[0], !pr[1], !pr[2], !pr[3], nullptr, al, bl);
+                    const v4f z = frozen4<R, false, WEIGHTED, RES>(a, Rrt, base + col, !pr[0], !pr[1], !pr[2], !pr[3], nullptr, al, bl, acc);
                     if (PACK && drow) {
                         int pc[4];
                         quad_packed_cols(rank, div, col, pc);
@@ -209,7 +254,7 @@ __device__ __forceinline__ void frozen_item(const WorkItem& it, const ProjectArg
             } else {
                 for (int c = j; c < row_len; c += lpr) {
                     const int ch = div(c);
-                    const float z = frozen1<R, false, WEIGHTED>(a, Rrt, base + c, mc[ch] != 0, nullptr, al, bl);
+                    const float z = frozen1<R, false, WEIGHTED, RES>(a, Rrt, base + c, mc[ch] != 0, nullptr, al, bl, acc);
                     if (PACK && drow) {
                         const int r = rank[ch];
                         if (r >= 0) drow[r * it.khw + (c - ch * it.khw)] = z;
@@ -228,22 +273,30 @@ __device__ __forceinline__ void frozen_item(const WorkItem& it, const ProjectArg
             const int nchunk = row_len >> 2;
             int c = j;
             for (; c + lpr < nchunk; c += 2 * lpr)
-                frozen4x2<R, PACK, WEIGHTED>(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + lpr) << 2), keep,
-                                             d ? d + 4 * c : nullptr, d ? d + 4 * (c + lpr) : nullptr, al, bl);
+                frozen4x2<R, PACK, WEIGHTED, RES>(a, Rrt, base + ((int64_t)c << 2), base + ((int64_t)(c + lpr) << 2), keep,
+                                                  d ? d + 4 * c : nullptr, d ? d + 4 * (c + lpr) : nullptr, al, bl, acc);
             if (c < nchunk)
-                frozen4<R, PACK, WEIGHTED>(a, Rrt, base + ((int64_t)c << 2), keep, keep, keep, keep,
-                                           d ? d + 4 * c : nullptr, al, bl);
+                frozen4<R, PACK, WEIGHTED, RES>(a, Rrt, base + ((int64_t)c << 2), keep, keep, keep, keep,
+                                                d ? d + 4 * c : nullptr, al, bl, acc);
         } else {
-            for (int c = j; c < row_len; c += lpr) frozen1<R, PACK, WEIGHTED>(a, Rrt, base + c, keep, d ? d + c : nullptr, al, bl);
+            for (int c = j; c < row_len; c += lpr)
+                frozen1<R, PACK, WEIGHTED, RES>(a, Rrt, base + c, keep, d ? d + c : nullptr, al, bl, acc);
         }
     }
 }
 
-template <int R, bool PACK = false, bool WEIGHTED = false>
+// RES: the item's two intra-node residual sums also go to a.respart[4 * item + 0, 1].
+template <int R, bool PACK = false, bool WEIGHTED = false, bool RES = false>
 __global__ __launch_bounds__(kBlock) void project_frozen(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
                                                          const uint8_t* __restrict__ mask, PackOut po)
 {
-    frozen_item<R, PACK, WEIGHTED>(items[blockIdx.x], a, Rrt, mask, po);
+    if constexpr (RES) {
+        double acc[2] = {0.0, 0.0};
+        frozen_item<R, PACK, WEIGHTED, true>(items[blockIdx.x], a, Rrt, mask, po, acc);
+        block_sum_pair(acc[0], acc[1], a.respart + (int64_t)blockIdx.x * 4);
+    } else {
+        frozen_item<R, PACK, WEIGHTED, false>(items[blockIdx.x], a, Rrt, mask, po);
+    }
 }
 
 // Eq. (14): out = OR of M masks, 0 / 1 bytes.

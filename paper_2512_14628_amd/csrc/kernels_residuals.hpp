@@ -17,12 +17,6 @@ struct ResidualArgs {
     double* part;           // per row item: 4 partial sums
 };
 
-__device__ __forceinline__ double sqd(double acc, float a, float b)
-{
-    const double d = (double)a - (double)b;
-    return fma(d, d, acc);
-}
-
 // One workgroup per row item (a contiguous span of one layer): per-thread fp64 sums of the four
 // squared differences, combined by a butterfly per wave and in wave order through LDS.
 template <int R>
@@ -81,9 +75,11 @@ __global__ __launch_bounds__(kBlock) void residual_partials(const WorkItem* __re
 }
 
 // One workgroup per layer: adds the layer's item partials (thread t takes items t, t+256, ... in
-// order; threads are combined by a butterfly per wave and in wave order), writes out[k*L + l].
+// order; threads are combined by a butterfly per wave and in wave order), writes out[k*L + l] for the
+// norms k0 <= k < k1 (the others are neither read nor written).
 __global__ __launch_bounds__(kBlock) void residual_finish(const DevLayer* __restrict__ layers, int nL,
-                                                          const double* __restrict__ part, double* __restrict__ out)
+                                                          const double* __restrict__ part, double* __restrict__ out,
+                                                          int k0, int k1)
 {
     __shared__ double red[kWaves][4];
     const int l = blockIdx.x;
@@ -92,11 +88,13 @@ __global__ __launch_bounds__(kBlock) void residual_finish(const DevLayer* __rest
     const int wave = threadIdx.x / kWave;
     double s[4] = {0.0, 0.0, 0.0, 0.0};
     for (int i = threadIdx.x; i < count; i += kBlock)
-        for (int k = 0; k < 4; ++k) s[k] += part[(int64_t)(first + i) * 4 + k];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (k >= k0 && k < k1) s[k] += part[(int64_t)(first + i) * 4 + k];
     for (int k = 0; k < 4; ++k) s[k] = wave_xor_sum(s[k], kWave);
     if (lane == 0) for (int k = 0; k < 4; ++k) red[wave][k] = s[k];
     __syncthreads();
-    if (threadIdx.x < 4) {
+    if ((int)threadIdx.x >= k0 && (int)threadIdx.x < k1) {
         double t = red[0][threadIdx.x];
         for (int w = 1; w < kWaves; ++w) t += red[w][threadIdx.x];
         out[(int64_t)threadIdx.x * nL + l] = t;

@@ -85,6 +85,9 @@ def test_hot_calls_reject_null_plan(lib):
     assert lib.hsadmm_project_weighted_frozen(None, None, 1, None, None, None, None, None, None, None) == -1
     assert lib.hsadmm_project_weighted_frozen_compact(None, None, 1, None, None, None, None, None, None, 0, None, None,
                                                       None, None, 0, None) == -1
+    assert lib.hsadmm_retrain_project(None, None, 1, None, None, None, None, None, None, 0, None, None, None, None,
+                                      None, 0, None) == -1
+    assert lib.hsadmm_retrain_expand(None, None, None, None, None, None, None, None, None, 0, None) == -1
     assert lib.hsadmm_compact(None, None, None, None, None, None, None, 0, None) == -1
     assert lib.hsadmm_expand(None, None, None, None, None, 0, None) == -1
     assert lib.hsadmm_project_frozen(None, None, 1, None, None, None, None, None) == -1
