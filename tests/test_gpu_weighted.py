@@ -320,10 +320,12 @@ def test_weighted_frozen_error_codes():
     r.close()
 
 
-def test_a_captured_graph_replays_the_retraining_phase_iteration():
+@pytest.mark.parametrize("with_residuals", [False, True])
+def test_a_captured_graph_replays_the_retraining_phase_iteration(with_residuals):
     """The two calls of a retraining-phase iteration (full candidate under the frozen mask with c = z_i + v_i packed,
     then decompression + Eq. (13)) captured into a HIP graph; U and v are updated in place, so the replays form a
-    sequence of iterations, each compared bit for bit with the eager sequence."""
+    sequence of iterations, each compared bit for bit with the eager sequence.  with_residuals: the pair that also
+    forms the four residual norms (z_i in place, so the dual residual compares consecutive replays)."""
     import paper_2512_14628_amd as pkg
     from tests.gpu_harness import GpuRun, bits
     wl = wk.make_workload("resnet18")
@@ -341,21 +343,30 @@ def test_a_captured_graph_replays_the_retraining_phase_iteration():
         r.dm = torch.from_numpy(mask).to(r.dev)
         pkg.hsadmm_plan_set_node_weights(r.plan, a, b)
         pkg.hsadmm_expand(r.plan, r.dpacked, r.dm, r.ddst, r.ws)          # the frozen mask's index mappings, once
+        r.dZ.zero_()
+        r.dres = torch.full((4 * L,), float("nan"), dtype=torch.float64, device=r.dev)
         torch.cuda.synchronize()
         return r
 
     def iteration(r, stream=None):
+        if with_residuals:
+            pkg.hsadmm_retrain_project(r.plan, r.dW, r.dU, r.dZg, r.dVd, r.dZ, None, r.dm, True, r.dpacked, r.doff,
+                                       r.dkept, r.dres, r.ws, stream=stream)
+            pkg.hsadmm_retrain_expand(r.plan, r.dpacked, None, r.ddst, r.dZ, r.dVd, r.dZg, r.dres, r.ws,
+                                      stream=stream)
+            return
         pkg.hsadmm_project_weighted_frozen_compact(r.plan, r.dW, r.dU, r.dZg, r.dVd, r.dZ, None, r.dm, True, r.dpacked,
                                                    r.doff, r.dkept, r.ws, stream=stream)
         pkg.hsadmm_expand_dual(r.plan, r.dpacked, None, r.ddst, r.dZ, r.dVd, r.ws, stream=stream)
 
     eager = setup()
-    expected = []
+    expected, expected_res = [], []
     for _ in range(3):
         iteration(eager)
         torch.cuda.synchronize()
         expected.append({"Z": eager.dZ.cpu().numpy(), "U": eager.dU.cpu().numpy(), "dst": eager.ddst.cpu().numpy(),
                          "v": eager.dVd.cpu().numpy()})
+        expected_res.append(eager.dres.cpu().numpy())
     run = setup()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -374,6 +385,10 @@ def test_a_captured_graph_replays_the_retraining_phase_iteration():
             for l in wl.layers:
                 sl = slice(l.elem_off, l.elem_off + l.n)
                 assert np.array_equal(bits(got[k][sl]), bits(v[sl])), (it, k, l.name)
+        if with_residuals:
+            res = run.dres.cpu().numpy()
+            assert not np.isnan(res).any()
+            assert np.array_equal(res.view(np.uint64), expected_res[it].view(np.uint64)), it
         scratch.add_(1.0)                                                     # eager work between replays
         assert float(scratch.sum().item()) == float((it + 1) * (1 << 20))
     run.close()
