@@ -35,6 +35,9 @@
 //   weighted_fixup_pack   weighted_fixup that also packs c = z~ + v of its kept rows, and the gather of the
 //                   other layers' rows, in one launch (hsadmm_project_weighted_compact)   [Section 4.4.1]
 //   dual_inter_kernel  Eq. (13);  residual_partials / residual_finish  Section 3.4;  mask_or_kernel  Eq. (14)
+//   retrain_project / retrain_expand   project_frozen<R, true, true, true> and expand_scatter<true, true>: the
+//                   retraining-phase iteration whose kernels also sum the squared residuals of Section 3.4
+//                   (hsadmm_retrain_project, hsadmm_retrain_expand)
 //
 // Nothing here is a dense contraction, so no MFMA is used; every kernel is bound by HBM traffic.
 // Arena data is touched once per kernel, so it is moved with non-temporal 128-bit accesses.
