@@ -84,6 +84,12 @@ def _load():
     lib.oracle_average.restype = ctypes.c_int
     lib.oracle_mask_drift.argtypes = [ctypes.c_int32, i32p, i32p, i32p, i32p, u8p, u8p, i32p]
     lib.oracle_mask_drift.restype = ctypes.c_int
+    lib.oracle_adapt_penalties.argtypes = [ctypes.c_int32, f64pp, ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
+                                           ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                           f64pp, f64pp, f32p, f32p]
+    lib.oracle_adapt_penalties.restype = ctypes.c_int
+    lib.oracle_scale_layers.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, f32p, f32p]
+    lib.oracle_scale_layers.restype = ctypes.c_int
     lib.oracle_mask_or.argtypes = [ctypes.c_int64, ctypes.POINTER(u8p), ctypes.c_int32, u8p]
     lib.oracle_mask_or.restype = ctypes.c_int
     _lib = lib
@@ -428,4 +434,42 @@ def residuals(table, W, Zi, Zi_prev=None, Zg=None, Zg_prev=None):
                               _p(out, ctypes.c_double))
     if rc != 0:
         raise ValueError("oracle_residuals failed with code %d" % rc)
+    return out
+
+
+def adapt_penalties(sq, rho1, rho2, P: int, n_out: int, mu: float, tau_incr: float, tau_decr: float,
+                    rho1_max: float, rho2_max: float):
+    """Residual balancing per layer and level (Section 3.4; Algorithm 1, Phase 5).  sq: [4, L] squared residual sums
+    as residuals() returns them.  Returns (rho1_new, rho2_new, scale_u, scale_v)."""
+    lib = _load()
+    sq = np.ascontiguousarray(sq, dtype=np.float64)
+    r1 = np.array(rho1, dtype=np.float64).ravel().copy()
+    r2 = np.array(rho2, dtype=np.float64).ravel().copy()
+    L = r1.size
+    if sq.size != 4 * L or r2.size != L:
+        raise ValueError("adapt_penalties: sizes disagree")
+    su = np.zeros(L, dtype=np.float32)
+    sv = np.zeros(L, dtype=np.float32)
+    rc = lib.oracle_adapt_penalties(L, _p(sq, ctypes.c_double), int(P), int(n_out), float(mu), float(tau_incr),
+                                    float(tau_decr), float(rho1_max), float(rho2_max), _p(r1, ctypes.c_double),
+                                    _p(r2, ctypes.c_double), _p(su, ctypes.c_float), _p(sv, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("oracle_adapt_penalties failed with code %d" % rc)
+    return r1, r2, su, sv
+
+
+def scale_layers(table, X, factor):
+    """X * factor[layer] on every layer (a new array; padding copied)."""
+    lib = _load()
+    t = _cols(table)
+    L = len(t["c_out"])
+    out = np.array(X, dtype=np.float32).copy()
+    f = np.ascontiguousarray(factor, dtype=np.float32)
+    if f.size != L:
+        raise ValueError("scale_layers: one factor per layer")
+    rc = lib.oracle_scale_layers(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                                 _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32), _p(f, ctypes.c_float),
+                                 _p(out, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("oracle_scale_layers failed with code %d" % rc)
     return out

@@ -728,3 +728,69 @@ int oracle_residuals(int32_t L, const int64_t *elem_off, const int32_t *c_out, c
     }
     return 0;
 }
+
+/*
+ * Adaptive penalty tuning (Section 3.4, last paragraph; Algorithm 1, Phase 5, last line).  The paper adopts, per
+ * layer and independently for rho_1 and rho_2, the residual-balancing rule of the ADMM reference it cites (Boyd et
+ * al., Section 3.4.1 there): with the norms ||r|| and ||s|| of the primal and dual residuals,
+ *     rho <- tau_incr * rho   if ||r|| > mu ||s||
+ *     rho <- rho / tau_decr   if ||s|| > mu ||r||
+ *     rho unchanged           otherwise,
+ * and, the duals being scaled ones (u = y / rho), a dual is multiplied by rho_old / rho_new when its rho changes.
+ * mu, tau_incr, tau_decr are not given in the paper: arguments.  The caps rho_1^max, rho_2^max are those of the
+ * paper's hyperparameter paragraph (Section 5): a raised penalty stops at its cap.
+ * Norms, from the squared sums sq[4L] laid out as oracle_residuals writes them and the residuals of Section 3.4:
+ *   intra:  ||r||^2 = sq[0L + l]  (r_intra,i,j summed over the node's P replicas);
+ *           ||s||^2 = P rho_1^2 sq[1L + l]  (s_intra,i,j = rho_1 (z_i^{k+1} - z_i^k), the same for each of the P)
+ *   inter:  ||r||^2 = sq[2L + l];  ||s||^2 = n_out rho_2^2 sq[3L + l], n_out = the number of nodes whose r_inter
+ *           were added into sq[2L + l] (1: the node's own view)
+ * rho1, rho2: in/out, L doubles;  scale_u, scale_v: out, L floats, rho_old / rho_new rounded once.
+ */
+int oracle_adapt_penalties(int32_t L, const double *sq, int32_t P, int32_t n_out, double mu, double tau_incr,
+                           double tau_decr, double rho1_max, double rho2_max, double *rho1, double *rho2,
+                           float *scale_u, float *scale_v)
+{
+    if (L < 1 || !sq || !rho1 || !rho2 || !scale_u || !scale_v || P < 1 || n_out < 1) return -1;
+    if (!(mu > 0.0) || !(tau_incr >= 1.0) || !(tau_decr >= 1.0)) return -1;
+    for (int32_t l = 0; l < L; ++l) {
+        if (!(rho1[l] > 0.0) || !(rho2[l] > 0.0) || rho1[l] > rho1_max || rho2[l] > rho2_max) return -1;
+        for (int k = 0; k < 4; ++k)
+            if (!(sq[(int64_t)k * L + l] >= 0.0)) return -1;
+    }
+    for (int32_t l = 0; l < L; ++l) {
+        for (int level = 0; level < 2; ++level) {
+            double *rho = level == 0 ? &rho1[l] : &rho2[l];
+            const double cap = level == 0 ? rho1_max : rho2_max;
+            const double copies = level == 0 ? (double)P : (double)n_out;
+            const double r = sqrt(sq[(int64_t)(2 * level) * L + l]);
+            const double s = *rho * sqrt(copies * sq[(int64_t)(2 * level + 1) * L + l]);
+            const double old = *rho;
+            double next = old;
+            if (r > mu * s) {
+                next = tau_incr * old;
+                if (next > cap) next = cap;
+            } else if (s > mu * r) {
+                next = old / tau_decr;
+            }
+            *rho = next;
+            (level == 0 ? scale_u : scale_v)[l] = (float)(old / next);
+        }
+    }
+    return 0;
+}
+
+/* X[e] <- fl(X[e] * factor[l]) on every element of every layer (the rescaling of a scaled dual after its layer's
+ * penalty has changed; arena padding untouched). */
+int oracle_scale_layers(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                        const int32_t *khw, const float *factor, float *X)
+{
+    if (L < 1 || !factor || !X) return -1;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t n = (int64_t)c_out[l] * c_in[l] * khw[l];
+        const int64_t off = elem_off[l];
+        const float f = factor[l];
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+        for (int64_t e = 0; e < n; ++e) X[off + e] = X[off + e] * f;
+    }
+    return 0;
+}

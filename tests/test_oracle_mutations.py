@@ -18,6 +18,7 @@ from tests import test_oracle_residuals as rpins
 from tests import test_oracle_composite as cpins
 from tests import test_oracle_shape as spins
 from tests import test_oracle_global as gpins
+from tests import test_oracle_penalties as ppins
 
 MUTATIONS = [
     ("tie_goes_to_higher_index", "(kl[h] == kl[g] && h < g)", "(kl[h] == kl[g] && h > g)"),
@@ -99,6 +100,15 @@ MUTATIONS = [
     ("weighted_frozen_dual_uses_unmasked_candidate",
      "const float z = keep ? zt : 0.0f;\n            Z[off + e] = z;\n            U[off + e] = U[off + e] + (wbar - z);",
      "const float z = keep ? zt : 0.0f;\n            Z[off + e] = z;\n            U[off + e] = U[off + e] + (wbar - zt);"),
+    ("penalty_rule_inverted", "if (r > mu * s) {\n                next = tau_incr * old;", "if (r < mu * s) {\n                next = tau_incr * old;"),
+    ("penalty_cap_ignored", "if (next > cap) next = cap;", "if (next > cap) next = next;"),
+    ("penalty_scale_inverted", "[l] = (float)(old / next);", "[l] = (float)(next / old);"),
+    ("penalty_dual_norm_without_rho", "const double s = *rho * sqrt(copies *", "const double s = sqrt(copies *"),
+    ("penalty_dual_norm_without_copies", "const double s = *rho * sqrt(copies * sq[", "const double s = *rho * sqrt(sq["),
+    ("penalty_reads_the_wrong_rows", "const double r = sqrt(sq[(int64_t)(2 * level) * L + l]);", "const double r = sqrt(sq[(int64_t)(level) * L + l]);"),
+    ("penalty_cut_multiplies", "next = old / tau_decr;", "next = old * tau_decr;"),
+    ("penalty_compares_squares_with_mu", "const double r = sqrt(sq[(int64_t)(2 * level) * L + l]);", "const double r = sq[(int64_t)(2 * level) * L + l];"),
+    ("scale_layers_takes_the_first_factor", "const float f = factor[l];", "const float f = factor[0];"),
 ]
 
 PIN_FUNCS = [
@@ -144,6 +154,12 @@ PIN_FUNCS = [
     spins.test_handworked_shape_layer,
     lambda: [spins.test_shape_groups_are_the_columns_of_the_gemm_view(s) for s in range(2)],
     lambda: [spins.test_shape_against_numpy(s) for s in range(2)],
+    ppins.test_handworked_balancing_both_levels_and_the_cap,
+    ppins.test_the_inequalities_are_strict_and_the_dual_norm_counts_the_copies,
+    ppins.test_repeated_raises_follow_the_closed_form_count,
+    ppins.test_layers_and_levels_are_independent_and_neutral_constants_change_nothing,
+    ppins.test_rescaled_dual_keeps_a_converged_scaled_admm_at_its_fixed_point,
+    ppins.test_scale_layers_is_a_per_layer_float32_multiply,
 ]
 
 
@@ -162,7 +178,7 @@ def test_a_planted_mistake_in_the_oracle_fails_a_pin(name, old, new, tmp_path, m
     for fn in ("oracle_project", "oracle_compact", "oracle_expand", "oracle_set_threads", "oracle_get_threads",
                "oracle_project_frozen", "oracle_mask_or", "oracle_node_coefficients", "oracle_project_weighted",
                "oracle_dual_inter", "oracle_add_arenas", "oracle_residuals", "oracle_average", "oracle_mask_drift",
-               "oracle_project_weighted_frozen"):
+               "oracle_project_weighted_frozen", "oracle_adapt_penalties", "oracle_scale_layers"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(oracle, "_lib", lib)
