@@ -302,6 +302,47 @@ int hsadmm_node_coefficients(const double* rho1, const double* rho2, int32_t L, 
                              int32_t P, float* a, float* b);
 
 /*
+ * Adaptive penalty tuning (Section 3.4, last paragraph; Algorithm 1, Phase 5,
+ * last line): the residual-balancing rule of the ADMM reference the paper
+ * cites (Boyd et al., "Varying penalty parameter"), applied per layer and
+ * independently to rho_1 (intra-node) and rho_2 (inter-node).  With ||r|| and
+ * ||s|| the norms of a level's primal and dual residuals,
+ *     rho <- min(tau_incr rho, rho_max)   if ||r|| > mu ||s||
+ *     rho <- rho / tau_decr               if ||s|| > mu ||r||
+ *     rho unchanged                       otherwise,
+ * and because u and v are scaled duals, each must be multiplied by
+ * rho_old / rho_new when its penalty changes: scale_u, scale_v (feed them to
+ * hsadmm_scale_layers; then recompute the node weights with
+ * hsadmm_node_coefficients).  HOST function, all pointers are HOST memory.
+ *   residuals  in, 4*L doubles as hsadmm_residuals / hsadmm_retrain_* write
+ *              them (copied to the host by the caller).  Norms used:
+ *                intra  ||r||^2 = residuals[0L+l],  ||s||^2 = P rho_1^2 residuals[1L+l]
+ *                       (s_intra = rho_1 (z_i - z_i_prev) once per replica)
+ *                inter  ||r||^2 = residuals[2L+l],  ||s||^2 = n_out rho_2^2 residuals[3L+l]
+ *   P          replicas per node; n_out: how many nodes' inter-node primal
+ *              sums were added into row 2 (1 for a node's own view)
+ *   mu, tau_incr, tau_decr  the rule's constants; the paper gives none (its
+ *              reference suggests 10, 2, 2).  mu > 0, tau >= 1.
+ *   rho1_max, rho2_max  the caps of Section 5 (10.0 each there)
+ *   rho1, rho2 in/out, L doubles, 0 < rho <= its cap
+ *   scale_u, scale_v  out, L floats, rho_old / rho_new rounded once
+ * Errors: INVALID_ARGUMENT (nothing is written).
+ */
+int hsadmm_adapt_penalties(const double* residuals, int32_t L, int32_t P, int32_t n_out,
+                           double mu, double tau_incr, double tau_decr, double rho1_max, double rho2_max,
+                           double* rho1, double* rho2, float* scale_u, float* scale_v);
+
+/*
+ * X <- X * factor[l] on every element of every layer l (fp32, one rounding;
+ * arena padding untouched): the rescaling of a scaled dual (U or Vd) after
+ * hsadmm_adapt_penalties.  Layers whose factor is exactly 1 are not touched.
+ *   X       device, in/out, full-layout arena, 16-byte aligned
+ *   factor  device, L floats
+ * Errors: INVALID_ARGUMENT, HIP.
+ */
+int hsadmm_scale_layers(const hsadmm_plan_t* plan, float* X, const float* factor, void* hip_stream);
+
+/*
  * Stores the per-layer weights a_l, b_l (HOST arrays of L floats) in the
  * plan; hsadmm_project_weighted uses them.  A new plan holds a = 1, b = 0.
  * Synchronous host-to-device copy: call it between steps (penalties adapt
@@ -409,9 +450,9 @@ int hsadmm_average(const hsadmm_plan_t* plan, const float* const* bufs, int32_t 
  * Zi_prev, Zg, Zg_prev may be NULL: rows whose operands are missing are 0.
  *   out   device, 4*L doubles.  The order of additions is fixed (results are
  *         reproducible run to run) but differs from a sequential sum.
- * The thresholds and the penalty adaptation that consume these norms are
- * host logic the paper leaves to its reference (Boyd et al.); not part of
- * this library.  Errors: INVALID_ARGUMENT, WORKSPACE, UNSUPPORTED, HIP.
+ * hsadmm_adapt_penalties consumes these norms; the stopping thresholds,
+ * whose tolerances the paper leaves to its reference, are the caller's
+ * comparison.  Errors: INVALID_ARGUMENT, WORKSPACE, UNSUPPORTED, HIP.
  */
 int hsadmm_residuals(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
                      const float* Zi, const float* Zi_prev, const float* Zg, const float* Zg_prev,
@@ -507,7 +548,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 23
+#define HSADMM_KERNEL_COUNT 24
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

@@ -34,8 +34,9 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_average", "hsadmm_mask_drift", "hsadmm_expand_dual", "hsadmm_project_compact",
            "hsadmm_project_weighted_compact", "hsadmm_project_frozen_compact",
            "hsadmm_project_weighted_frozen", "hsadmm_project_weighted_frozen_compact",
-           "hsadmm_retrain_project", "hsadmm_retrain_expand")
-KERNEL_COUNT = 23
+           "hsadmm_retrain_project", "hsadmm_retrain_expand",
+           "hsadmm_adapt_penalties", "hsadmm_scale_layers")
+KERNEL_COUNT = 24
 
 
 class HsadmmError(RuntimeError):
@@ -130,6 +131,13 @@ def load_library():
     lib.hsadmm_retrain_project.restype = ctypes.c_int
     lib.hsadmm_retrain_expand.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hsadmm_retrain_expand.restype = ctypes.c_int
+    dp, fp = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_float)
+    lib.hsadmm_adapt_penalties.argtypes = [dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
+                                           ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                           dp, dp, fp, fp]
+    lib.hsadmm_adapt_penalties.restype = ctypes.c_int
+    lib.hsadmm_scale_layers.argtypes = [vp, vp, vp, vp]
+    lib.hsadmm_scale_layers.restype = ctypes.c_int
     lib.hsadmm_residuals.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hsadmm_residuals.restype = ctypes.c_int
     lib.hsadmm_dual_inter.argtypes = [vp, vp, vp, vp, vp]
@@ -342,6 +350,36 @@ def hsadmm_node_coefficients(rho1, rho2, lam: float, M: int, P: int):
     if rc != 0:
         raise HsadmmError(rc, "hsadmm_node_coefficients")
     return list(a), list(b)
+
+
+def hsadmm_adapt_penalties(residuals, rho1, rho2, P: int, n_out: int, mu: float, tau_incr: float, tau_decr: float,
+                           rho1_max: float, rho2_max: float):
+    """Residual balancing per layer and level (host computation inside the library).  residuals: 4*L floats on the
+    host, rows as hsadmm_residuals writes them.  Returns (rho1, rho2, scale_u, scale_v) as lists of L numbers."""
+    lib = load_library()
+    L = len(rho1)
+    flat = [float(x) for row in residuals for x in (row if hasattr(row, "__len__") else [row])]
+    if len(flat) != 4 * L or len(rho2) != L:
+        raise ValueError("residuals need 4 entries per layer, rho1 and rho2 one")
+    sq = (ctypes.c_double * (4 * L))(*flat)
+    r1 = (ctypes.c_double * L)(*[float(x) for x in rho1])
+    r2 = (ctypes.c_double * L)(*[float(x) for x in rho2])
+    su = (ctypes.c_float * L)()
+    sv = (ctypes.c_float * L)()
+    rc = lib.hsadmm_adapt_penalties(sq, L, int(P), int(n_out), float(mu), float(tau_incr), float(tau_decr),
+                                    float(rho1_max), float(rho2_max), r1, r2, su, sv)
+    if rc != 0:
+        raise HsadmmError(rc, "hsadmm_adapt_penalties")
+    return list(r1), list(r2), list(su), list(sv)
+
+
+def hsadmm_scale_layers(plan: Plan, X, factor, stream=None, check: bool = True) -> int:
+    """X *= factor[layer] on the device (factor: L floats on the device)."""
+    lib = load_library()
+    rc = lib.hsadmm_scale_layers(plan.handle, _ptr(X), _ptr(factor), _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_scale_layers")
+    return rc
 
 
 def hsadmm_plan_set_node_weights(plan: Plan, a, b) -> None:

@@ -52,6 +52,8 @@
 
 #include <cstdint>
 #include <cstdlib>
+#include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -76,7 +78,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -788,6 +790,47 @@ int hsadmm_node_coefficients(const double* rho1, const double* rho2, int32_t L, 
     return HSADMM_OK;
 }
 
+int hsadmm_adapt_penalties(const double* residuals, int32_t L, int32_t P, int32_t n_out, double mu, double tau_incr,
+                           double tau_decr, double rho1_max, double rho2_max, double* rho1, double* rho2,
+                           float* scale_u, float* scale_v)
+{
+    if (!residuals || !rho1 || !rho2 || !scale_u || !scale_v || L < 1 || P < 1 || n_out < 1)
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!(mu > 0.0) || !(tau_incr >= 1.0) || !(tau_decr >= 1.0)) return HSADMM_ERR_INVALID_ARGUMENT;
+    const double* sq_r[2] = {residuals, residuals + 2 * (size_t)L};                   // primal rows
+    const double* sq_s[2] = {residuals + (size_t)L, residuals + 3 * (size_t)L};       // dual rows, without rho
+    for (int32_t l = 0; l < L; ++l) {
+        const bool rho_ok = rho1[l] > 0.0 && rho2[l] > 0.0 && rho1[l] <= rho1_max && rho2[l] <= rho2_max;
+        const bool sums_ok = sq_r[0][l] >= 0.0 && sq_s[0][l] >= 0.0 && sq_r[1][l] >= 0.0 && sq_s[1][l] >= 0.0;
+        if (!rho_ok || !sums_ok) return HSADMM_ERR_INVALID_ARGUMENT;                    // (NaN fails both)
+    }
+    // one penalty of one layer: the new value, and the factor its scaled dual takes
+    auto balance = [&](double rho, double sum_r, double sum_s, double copies, double cap, float* scale) {
+        const double norm_r = std::sqrt(sum_r);
+        const double norm_s = rho * std::sqrt(copies * sum_s);
+        double next = rho;
+        if (norm_r > mu * norm_s) next = std::min(tau_incr * rho, cap);
+        else if (norm_s > mu * norm_r) next = rho / tau_decr;
+        *scale = (float)(rho / next);
+        return next;
+    };
+    for (int32_t l = 0; l < L; ++l) {
+        rho1[l] = balance(rho1[l], sq_r[0][l], sq_s[0][l], (double)P, rho1_max, &scale_u[l]);
+        rho2[l] = balance(rho2[l], sq_r[1][l], sq_s[1][l], (double)n_out, rho2_max, &scale_v[l]);
+    }
+    return HSADMM_OK;
+}
+
+int hsadmm_scale_layers(const hsadmm_plan_t* p, float* X, const float* factor, void* hip_stream)
+{
+    if (!p || !X || !factor) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!is_aligned(X, 16) || !is_aligned(factor, 4)) return HSADMM_ERR_INVALID_ARGUMENT;
+    const hipError_t e = launch(p, kScaleLayers, scale_layers_kernel, (unsigned)p->items_rows.size(), kBlock,
+                                static_cast<hipStream_t>(hip_stream), (const WorkItem*)p->d_items_rows, factor, X);
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
 int hsadmm_plan_set_node_weights(hsadmm_plan_t* p, const float* a, const float* b)
 {
     if (!p || !a || !b) return HSADMM_ERR_INVALID_ARGUMENT;
@@ -1229,6 +1272,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kWFixupPack: return "weighted_fixup_pack";
         case kRetrainProject: return "retrain_project";
         case kRetrainExpand: return "retrain_expand";
+        case kScaleLayers: return "scale_layers";
         default: return "";
     }
 }

@@ -269,6 +269,26 @@ __global__ __launch_bounds__(kBlock) void dual_inter_kernel(const WorkItem* __re
     }
 }
 
+// X <- fl(X * factor[layer]) over every layer: a scaled dual follows its layer's penalty (u = y / rho is multiplied
+// by rho_old / rho_new when the adaptive tuning of Section 3.4 changes rho).  Items of a layer whose factor is 1 do
+// nothing, so an iteration that changes few penalties moves few bytes.
+__global__ __launch_bounds__(kBlock) void scale_layers_kernel(const WorkItem* __restrict__ items,
+                                                              const float* __restrict__ factor, float* __restrict__ X)
+{
+    const WorkItem it = items[blockIdx.x];
+    const float f = factor[it.layer];
+    if (f == 1.0f) return;
+    const int64_t len = (int64_t)it.nr * it.row_len;
+    if (item_vec(it)) {
+        for (int64_t c = threadIdx.x; c < (len >> 2); c += kBlock) {
+            const int64_t e = it.base + (c << 2);
+            st4(X + e, ld4(X + e) * f);
+        }
+    } else {
+        for (int64_t c = threadIdx.x; c < len; c += kBlock) X[it.base + c] = X[it.base + c] * f;
+    }
+}
+
 // Eq. (11): global consensus z = (1/M) sum_i (z_i + v_i) over M equally long buffers (the nodes' compact
 // pre-transmission buffers): fp32 sum in node order, times fl32(1/M).  Flat grid-stride stream.
 struct AverageArgs {

@@ -129,6 +129,40 @@ def test_node_coefficients_host_function_matches_the_oracle(lib):
         pkg.hsadmm_node_coefficients([-1.0], [3.0], 0.0, 1, 1)
 
 
+def test_adapt_penalties_host_function_matches_the_oracle(lib):
+    """hsadmm_adapt_penalties runs on the host: the same decisions, penalties and dual factors as the oracle's rule,
+    bit for bit, on random residual sums (many of them placed on or next to the rule's two boundaries)."""
+    import oracle
+    rng = np.random.default_rng(8)
+    for trial in range(40):
+        L = int(rng.integers(1, 60))
+        P, n_out = int(rng.integers(1, 9)), int(rng.integers(1, 5))
+        mu = float(rng.choice([2.0, 10.0, 16.0]))
+        ti, td = float(rng.choice([1.0, 1.5, 2.0])), float(rng.choice([1.0, 2.0, 3.0]))
+        rho1 = 2.0 ** rng.integers(-12, 3, L).astype(np.float64)
+        rho2 = 2.0 ** rng.integers(-14, 3, L).astype(np.float64)
+        sq = 10.0 ** rng.uniform(-9, 2, (4, L))
+        # boundary cases: ||r|| = mu ||s|| exactly representable, then nudged to either side
+        for l in range(0, L, 3):
+            s_raw = 4.0 ** float(rng.integers(-8, 2))
+            sq[1, l] = s_raw / P
+            sq[0, l] = (mu * rho1[l]) ** 2 * s_raw * (1.0 + float(rng.integers(-1, 2)) * 2.0 ** -50)
+        sq[:, L - 1] = 0.0
+        got = pkg.hsadmm_adapt_penalties(sq, rho1, rho2, P, n_out, mu, ti, td, 10.0, 10.0)
+        want = oracle.adapt_penalties(sq, rho1, rho2, P, n_out, mu, ti, td, 10.0, 10.0)
+        for g, w, dt in zip(got, want, (np.float64, np.float64, np.float32, np.float32)):
+            assert np.array_equal(np.array(g, dt), w), trial
+    ok = ([[1.0], [1.0], [1.0], [1.0]], [1.0], [1.0], 2, 1, 10.0, 2.0, 2.0, 10.0, 10.0)
+    for pos, bad in ((1, [0.0]), (1, [11.0]), (2, [float("nan")]), (3, 0), (4, 0), (5, 0.0), (6, 0.5), (7, 0.99),
+                     (0, [[1.0], [-1.0], [1.0], [1.0]])):
+        args = list(ok)
+        args[pos] = bad
+        with pytest.raises(pkg.HsadmmError):
+            pkg.hsadmm_adapt_penalties(*args)
+    assert lib.hsadmm_adapt_penalties(None, 1, 1, 1, 10.0, 2.0, 2.0, 10.0, 10.0, None, None, None, None) == -1
+    assert lib.hsadmm_scale_layers(None, None, None, None) == -1
+
+
 def test_bench_refuses_more_than_one_gpu():
     """This build has no collectives: bench.py --gpus N with N > 1 exits with a message instead of running."""
     import subprocess
