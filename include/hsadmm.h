@@ -13,7 +13,8 @@
  *
  * and, around it: the frozen-mask branch and the mask union (Section 4.5, Eq. (14)), the full node
  * candidate with its rho_2 term, the inter-node dual update and the mean of the nodes' compact
- * buffers (Eq. (9), (13), (11)), the residual norms (Section 3.4) and the mask drift (Section 4.5).
+ * buffers (Eq. (9), (13), (11)), the residual norms and the adaptive penalties they drive (Section 3.4)
+ * and the mask drift (Section 4.5).
  * Each projection (hsadmm_project, _frozen, _weighted, _weighted_frozen) also exists as a *_compact call that returns the
  * shrunk buffer as well, with the same results as the projection followed by the compaction.
  *
