@@ -508,8 +508,8 @@ int hsadmm_expand_dual(const hsadmm_plan_t* plan, const float* packed, const uin
  * hsadmm_retrain_expand: hsadmm_expand_dual (same arguments, same outputs,
  * bit for bit) and
  *   z_prev     device, in: the previous global consensus, a full-layout
- *              arena other than dst (INVALID_ARGUMENT if the two overlap),
- *              16-byte aligned
+ *              arena other than dst and Vd (INVALID_ARGUMENT if it overlaps
+ *              either), 16-byte aligned
  *   residuals  rows 2 and 3 are written,
  *                  residuals[2*L + l] = || Zi - z ||_F^2
  *                  residuals[3*L + l] = || z - z_prev ||_F^2

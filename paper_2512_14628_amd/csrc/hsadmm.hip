@@ -1140,7 +1140,7 @@ static int expand_impl(const hsadmm_plan_t* p, const float* packed, const uint8_
 {
     if (!p || !packed || !dst || !workspace || (dual && (!Zi || !Vd))) return HSADMM_ERR_INVALID_ARGUMENT;
     if (with_residuals && (!dual || !z_prev || !residuals || !is_aligned(z_prev, 16) || !is_aligned(residuals, 8) ||
-                           spans_overlap(z_prev, dst, p->arena_elems)))
+                           spans_overlap(z_prev, dst, p->arena_elems) || spans_overlap(z_prev, Vd, p->arena_elems)))
         return HSADMM_ERR_INVALID_ARGUMENT;
     if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (!is_aligned(packed, 16) || !is_aligned(dst, 16) || !is_aligned(workspace, 256) ||

@@ -314,6 +314,7 @@ def test_weighted_frozen_error_codes():
     assert re_(r.plan, r.dpacked, r.dmask, r.ddst, r.dZ, v, z, None, r.ws, check=False) == -1
     assert re_(r.plan, r.dpacked, r.dmask, r.ddst, r.dZ, v, r.ddst, res, r.ws, check=False) == -1      # z_prev is dst
     assert re_(r.plan, r.dpacked, r.dmask, r.ddst, r.dZ, v, r.ddst[4:], res, r.ws, check=False) == -1  # ... overlaps it
+    assert re_(r.plan, r.dpacked, r.dmask, r.ddst, r.dZ, v, v, res, r.ws, check=False) == -1           # z_prev is Vd
     assert re_(r.plan, r.dpacked, r.dmask, r.ddst, r.dZ, v, z, res, r.ws[:256], check=False) == -2
     torch.cuda.synchronize()
     assert bool(torch.isnan(r.dZ).all())                      # nothing above was enqueued
