@@ -517,7 +517,10 @@ int hsadmm_expand_dual(const hsadmm_plan_t* plan, const float* packed, const uin
  * The four norms equal those of hsadmm_residuals(plan, W, R, z_i, z_i
  * (previous), z, z_prev, ...) up to the order of the fp64 additions, which is
  * fixed here too (reproducible run to run).  Each call finishes its own two
- * rows; nothing is carried from one call to the other.
+ * rows; nothing is carried from one call to the other.  hsadmm_retrain_expand
+ * does not depend on the mask being frozen: after a dynamic projection
+ * (hsadmm_project_weighted_compact) it gives rows 2 and 3 in the same way,
+ * and hsadmm_residuals with Zg = NULL gives rows 0 and 1.
  * Errors: those of the calls they extend.
  */
 int hsadmm_retrain_project(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
