@@ -248,7 +248,7 @@ def _check_weighted_frozen(wl, W, U, a, b, Zg, Vd, mask_np, want_wbar=True, pack
         r.close()
 
 
-@pytest.mark.parametrize("R", [1, 2, 3, 4, 8])
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 8, 16])
 def test_weighted_frozen_ragged_shapes_every_mode(R):
     from tests.test_gpu_composite import _shapes_with_both
     rng = np.random.default_rng(3300 + R)
