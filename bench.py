@@ -414,9 +414,12 @@ def main():
         torch.cuda.synchronize()
         rtt = pkg.hsadmm_kernel_timing_read(plan)
         pkg.hsadmm_kernel_timing_enable(plan, False)
-        # project: R replicas, U, z, v in, Z, U out (R + 5 arenas); packed written (4 n_kept; as a call of its own the
-        # shrinkage first reads the kept parts of Z and v again, 8 n_kept); expand + Eq. (13) as in the weighted step
-        rt_bytes = 4 * wl.n_total * (wl.R + 9) + (8 if one_call else 16) * nk
+        # project: R replicas and U in, Z and U out (R + 3 arenas); z and v are needed on the kept groups only, since a
+        # pruned group's z_i is +0 and its dual U + Wbar whatever they hold (8 n_kept; the kernel skips the rest, and
+        # rocprofv3's FETCH_SIZE confirms it); packed written (4 n_kept; as a call of its own the shrinkage first
+        # reads the kept parts of Z and v again, 8 n_kept); expand + Eq. (13): packed read (4 n_kept), z_i and v read,
+        # z and v written (4 arenas)
+        rt_bytes = 4 * wl.n_total * (wl.R + 7) + (16 if one_call else 24) * nk
         retrain = {"ms_per_step": round(1e3 * rt_elapsed, 4),
                    "algorithmic_bytes_per_step": rt_bytes,
                    "value_GBps": round(rt_bytes / rt_elapsed / 1e9, 1),
@@ -448,7 +451,7 @@ def main():
         torch.cuda.synchronize()
         rrt = pkg.hsadmm_kernel_timing_read(plan)
         pkg.hsadmm_kernel_timing_enable(plan, False)
-        rr_bytes = 4 * wl.n_total * (wl.R + 11) + 8 * nk
+        rr_bytes = 4 * wl.n_total * (wl.R + 9) + 16 * nk
         retrain_res = {"ms_per_step": round(1e3 * rr_elapsed, 4),
                        "algorithmic_bytes_per_step": rr_bytes,
                        "value_GBps": round(rr_bytes / rr_elapsed / 1e9, 1),
