@@ -339,8 +339,8 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
                                                          const int64_t* __restrict__ layer_off,
                                                          float* __restrict__ dst,
                                                          const float* __restrict__ Zi, float* __restrict__ Vd,
-                                                         const float* __restrict__ z_prev = nullptr,
-                                                         double* __restrict__ part = nullptr)
+                                                         const float* __restrict__ z_prev /* RES only */,
+                                                         double* __restrict__ part /* RES only */)
 {
     static_assert(DUAL || !RES, "the residual sums are formed with the dual update");
     double s_ro = 0.0, s_so = 0.0;
