@@ -33,6 +33,33 @@ __device__ __forceinline__ void wcand4(const WeightedArgs& w, int Rrt, int64_t e
     zt = at + bq;
 }
 
+// the same for two chunks, with every load issued before any arithmetic
+template <int R>
+__device__ __forceinline__ void wcand4x2(const WeightedArgs& w, int Rrt, int64_t e0, int64_t e1, float al, float bl,
+                                         v4f& wb0, v4f& u0, v4f& zt0, v4f& wb1, v4f& u1, v4f& zt1)
+{
+    const int RR = R > 0 ? R : Rrt;
+    v4f s0 = ld4(w.p.W[0] + e0), s1 = ld4(w.p.W[0] + e1);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) {
+        const v4f x0 = ld4(w.p.W[r] + e0), x1 = ld4(w.p.W[r] + e1);
+        s0 = s0 + x0;
+        s1 = s1 + x1;
+    }
+    u0 = ld4(w.p.U + e0);
+    u1 = ld4(w.p.U + e1);
+    const v4f g0 = ld4(w.Zg + e0), g1 = ld4(w.Zg + e1);
+    const v4f d0 = ld4(w.Vd + e0), d1 = ld4(w.Vd + e1);
+    const v4f q0 = g0 - d0, q1 = g1 - d1;
+    wb0 = s0 * w.p.inv_R;
+    wb1 = s1 * w.p.inv_R;
+    const v4f t0 = wb0 + u0, t1 = wb1 + u1;
+    const v4f at0 = t0 * al, at1 = t1 * al;
+    const v4f bq0 = q0 * bl, bq1 = q1 * bl;
+    zt0 = at0 + bq0;
+    zt1 = at1 + bq1;
+}
+
 template <int R>
 __device__ __forceinline__ void wcand1(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
                                        float& wb, float& u, float& zt)
@@ -88,7 +115,26 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
             if (active) {
                 if (vec) {
                     const int nchunk = row_len >> 2;
-                    for (int c = j; c < nchunk; c += lpr) {
+                    int c = j;
+                    // two chunks of the row at a time: all their loads are issued before the first store
+                    for (; c + lpr < nchunk; c += 2 * lpr) {
+                        const int64_t e0 = base + ((int64_t)c << 2), e1 = base + ((int64_t)(c + lpr) << 2);
+                        v4f wb0, u0, zt0, wb1, u1, zt1;
+                        wcand4x2<R>(w, Rrt, e0, e1, al, bl, wb0, u0, zt0, wb1, u1, zt1);
+                        if (park) {
+                            st4(w.p.Z + e0, wb0);
+                            st4(w.p.Z + e1, wb1);
+                        } else {
+                            st4(w.p.Z + e0, all_kept ? zt0 : wb0 + u0);
+                            st4(w.p.Z + e1, all_kept ? zt1 : wb1 + u1);
+                            st4(w.p.U + e0, u0 + (wb0 - zt0));
+                            st4(w.p.U + e1, u1 + (wb1 - zt1));
+                            if (w.p.Wbar) { st4(w.p.Wbar + e0, wb0); st4(w.p.Wbar + e1, wb1); }
+                        }
+                        acc = sq4(acc, zt0);
+                        acc = sq4(acc, zt1);
+                    }
+                    for (; c < nchunk; c += lpr) {
                         v4f wb, u, zt;
                         wcand4<R>(w, Rrt, base + ((int64_t)c << 2), al, bl, wb, u, zt);
                         const int64_t e = base + ((int64_t)c << 2);
