@@ -56,6 +56,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "hsadmm.h"
@@ -71,6 +72,23 @@
 namespace {
 
 // ------------------------------------------------------------------ host side
+
+// Calls f(std::integral_constant<int, C>{}) with C the compiled replica count that serves R: R itself when a
+// kernel is specialised for it (1, 2, 4, 8; also 3 where WITH3), else 0, the form with a run-time loop over replicas.
+template <bool WITH3, class F>
+hipError_t for_replica_count(int R, F&& f)
+{
+    switch (R) {
+        case 1: return f(std::integral_constant<int, 1>{});
+        case 2: return f(std::integral_constant<int, 2>{});
+        case 4: return f(std::integral_constant<int, 4>{});
+        case 8: return f(std::integral_constant<int, 8>{});
+        case 3:
+            if constexpr (WITH3) return f(std::integral_constant<int, 3>{});
+            else return f(std::integral_constant<int, 0>{});
+        default: return f(std::integral_constant<int, 0>{});
+    }
+}
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -520,14 +538,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     a.inv_R = 1.0f / (float)R;
     a.park_mean = R >= 3 ? 1 : 0;
     hipError_t e;
-    switch (R) {
-        case 1: e = launch_pass1<1>(p, a, R, s); break;
-        case 2: e = launch_pass1<2>(p, a, R, s); break;
-        case 3: e = launch_pass1<3>(p, a, R, s); break;
-        case 4: e = launch_pass1<4>(p, a, R, s); break;
-        case 8: e = launch_pass1<8>(p, a, R, s); break;
-        default: e = launch_pass1<0>(p, a, R, s); break;
-    }
+    e = for_replica_count<true>(R, [&](auto c) { return launch_pass1<decltype(c)::value>(p, a, R, s); });
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     // (the candidate of a BOTH layer is formed again from its parked mean and U)
     if (run_selection(p, a.key, a.colpart, a, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
@@ -638,14 +649,7 @@ int hsadmm_project_frozen(const hsadmm_plan_t* p, const float* const* W_replicas
     a.U = U; a.Z = Z; a.Wbar = Wbar;
     a.inv_R = 1.0f / (float)R;
     hipError_t e;
-    switch (R) {
-        case 1: e = launch_frozen<1>(p, a, R, mask, s); break;
-        case 2: e = launch_frozen<2>(p, a, R, mask, s); break;
-        case 3: e = launch_frozen<3>(p, a, R, mask, s); break;
-        case 4: e = launch_frozen<4>(p, a, R, mask, s); break;
-        case 8: e = launch_frozen<8>(p, a, R, mask, s); break;
-        default: e = launch_frozen<0>(p, a, R, mask, s); break;
-    }
+    e = for_replica_count<true>(R, [&](auto c) { return launch_frozen<decltype(c)::value>(p, a, R, mask, s); });
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
@@ -683,14 +687,7 @@ int hsadmm_project_frozen_compact(const hsadmm_plan_t* p, const float* const* W_
     po.co = CopyOut{layer_off, kept_idx};
     po.n_layers = (int)p->layers.size();
     hipError_t e;
-    switch (R) {
-        case 1: e = launch_frozen_pack<1>(p, a, R, mask, po, s); break;
-        case 2: e = launch_frozen_pack<2>(p, a, R, mask, po, s); break;
-        case 3: e = launch_frozen_pack<3>(p, a, R, mask, po, s); break;
-        case 4: e = launch_frozen_pack<4>(p, a, R, mask, po, s); break;
-        case 8: e = launch_frozen_pack<8>(p, a, R, mask, po, s); break;
-        default: e = launch_frozen_pack<0>(p, a, R, mask, po, s); break;
-    }
+    e = for_replica_count<true>(R, [&](auto c) { return launch_frozen_pack<decltype(c)::value>(p, a, R, mask, po, s); });
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     return HSADMM_OK;
 }
@@ -879,13 +876,9 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     const unsigned grid = (unsigned)p->items_proj.size();
     const WorkItem* items = p->d_items_proj;
     hipError_t e;
-    switch (R) {
-        case 1: e = launch(p, kWKeys, weighted_pass1<1>, grid, kBlock, s, items, w, (int)R); break;
-        case 2: e = launch(p, kWKeys, weighted_pass1<2>, grid, kBlock, s, items, w, (int)R); break;
-        case 4: e = launch(p, kWKeys, weighted_pass1<4>, grid, kBlock, s, items, w, (int)R); break;
-        case 8: e = launch(p, kWKeys, weighted_pass1<8>, grid, kBlock, s, items, w, (int)R); break;
-        default: e = launch(p, kWKeys, weighted_pass1<0>, grid, kBlock, s, items, w, (int)R); break;
-    }
+    e = for_replica_count<false>(R, [&](auto c) {
+        return launch(p, kWKeys, weighted_pass1<decltype(c)::value>, grid, kBlock, s, items, w, (int)R);
+    });
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     // (the weighted candidate of a BOTH layer is formed again from its parked mean, U, Zg and Vd)
     if (run_selection(p, w.p.key, w.p.colpart, w.p, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
@@ -1011,32 +1004,23 @@ static int weighted_frozen_impl(const hsadmm_plan_t* p, const float* const* W_re
     hipError_t e;
     if (with_residuals) {
         a.respart = reinterpret_cast<double*>(ws + p->ws.respart);
-        switch (R) {
-            case 1: e = launch(p, kRetrainProject, project_frozen<1, true, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            case 2: e = launch(p, kRetrainProject, project_frozen<2, true, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            case 4: e = launch(p, kRetrainProject, project_frozen<4, true, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            case 8: e = launch(p, kRetrainProject, project_frozen<8, true, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            default: e = launch(p, kRetrainProject, project_frozen<0, true, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-        }
+        e = for_replica_count<false>(R, [&](auto c) {
+            return launch(p, kRetrainProject, project_frozen<decltype(c)::value, true, true, true>, grid, kBlock, s, items, a,
+                          (int)R, mask, po);
+        });
         if (e != hipSuccess) return HSADMM_ERR_HIP;
         e = launch(p, kResFinish, residual_finish, (unsigned)p->layers.size(), kBlock, s, (const DevLayer*)p->d_layers,
                    (int)p->layers.size(), (const double*)a.respart, residuals, 0, 2);
     } else if (out) {
-        switch (R) {
-            case 1: e = launch(p, kFrozen, project_frozen<1, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            case 2: e = launch(p, kFrozen, project_frozen<2, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            case 4: e = launch(p, kFrozen, project_frozen<4, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            case 8: e = launch(p, kFrozen, project_frozen<8, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            default: e = launch(p, kFrozen, project_frozen<0, true, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-        }
+        e = for_replica_count<false>(R, [&](auto c) {
+            return launch(p, kFrozen, project_frozen<decltype(c)::value, true, true>, grid, kBlock, s, items, a, (int)R, mask,
+                          po);
+        });
     } else {
-        switch (R) {
-            case 1: e = launch(p, kFrozen, project_frozen<1, false, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            case 2: e = launch(p, kFrozen, project_frozen<2, false, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            case 4: e = launch(p, kFrozen, project_frozen<4, false, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            case 8: e = launch(p, kFrozen, project_frozen<8, false, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-            default: e = launch(p, kFrozen, project_frozen<0, false, true>, grid, kBlock, s, items, a, (int)R, mask, po); break;
-        }
+        e = for_replica_count<false>(R, [&](auto c) {
+            return launch(p, kFrozen, project_frozen<decltype(c)::value, false, true>, grid, kBlock, s, items, a, (int)R, mask,
+                          po);
+        });
     }
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
@@ -1090,13 +1074,9 @@ int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int
     const unsigned grid = (unsigned)p->items_rows.size();
     const WorkItem* items = p->d_items_rows;
     hipError_t e;
-    switch (R) {
-        case 1: e = launch(p, kResPart, residual_partials<1>, grid, kBlock, s, items, a, (int)R); break;
-        case 2: e = launch(p, kResPart, residual_partials<2>, grid, kBlock, s, items, a, (int)R); break;
-        case 4: e = launch(p, kResPart, residual_partials<4>, grid, kBlock, s, items, a, (int)R); break;
-        case 8: e = launch(p, kResPart, residual_partials<8>, grid, kBlock, s, items, a, (int)R); break;
-        default: e = launch(p, kResPart, residual_partials<0>, grid, kBlock, s, items, a, (int)R); break;
-    }
+    e = for_replica_count<false>(R, [&](auto c) {
+        return launch(p, kResPart, residual_partials<decltype(c)::value>, grid, kBlock, s, items, a, (int)R);
+    });
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     e = launch(p, kResFinish, residual_finish, (unsigned)p->layers.size(), kBlock, s,
                (const DevLayer*)p->d_layers, (int)p->layers.size(), (const double*)a.part, out, 0, 4);
