@@ -76,6 +76,7 @@ extern "C" {
 #define HSADMM_ERR_WORKSPACE         -2   /* workspace_bytes smaller than hsadmm_plan_sizes reports */
 #define HSADMM_ERR_HIP               -3   /* a HIP runtime call or a kernel launch failed */
 #define HSADMM_ERR_UNSUPPORTED       -4   /* valid request beyond a compiled limit (R > HSADMM_MAX_REPLICAS, ...) */
+#define HSADMM_ERR_HOST_MEMORY       -5   /* a host allocation failed while a plan's tables were built */
 
 #define HSADMM_MODE_NONE     0
 #define HSADMM_MODE_FILTER   1
@@ -106,7 +107,8 @@ typedef struct hsadmm_plan hsadmm_plan_t;   /* opaque; its tables never change a
  * pack_align_elems >= 1: every layer's segment of the packed buffer starts
  * at a multiple of this many elements (1 = tight packing).
  * Needs a HIP device (tables are copied to the current device).
- * Errors: INVALID_ARGUMENT (table), HIP (no device / allocation failure).
+ * Errors: INVALID_ARGUMENT (table), UNSUPPORTED (more than 2^31 - 1 groups in all),
+ * HOST_MEMORY (host allocation failure), HIP (no device / device allocation failure).
  */
 int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_align_elems,
                        hsadmm_plan_t** out);

@@ -340,7 +340,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         prev_end = x.elem_off + n;
     }
     hsadmm_plan* p = new (std::nothrow) hsadmm_plan();
-    if (!p) return HSADMM_ERR_HIP;
+    if (!p) return HSADMM_ERR_HOST_MEMORY;
     std::vector<uint16_t> group_layer;
     try {
         p->pack_align = pack_align_elems;
@@ -360,6 +360,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             d.k = x.mode == HSADMM_MODE_NONE ? d.G : x.k;
             d.k_in = both ? x.k_in : 0;
             d.seg0 = seg;
+            if (gb + d.G > INT32_MAX) { delete p; return HSADMM_ERR_UNSUPPORTED; }    // group indices are int32
             d.group_base = (int32_t)gb;
             d.row_len = x.c_in * x.khw;
             const int tile_rows = both ? kBothRows : kChanRows;
@@ -407,7 +408,6 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             seg += both ? 2 : 1;
         }
         p->n_segments = seg;
-        if (gb > INT32_MAX) { delete p; return HSADMM_ERR_UNSUPPORTED; }
         p->groups_total = gb;
         p->colpart_total = cp;
         p->packed_capacity = cap;
@@ -422,7 +422,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->ws.total = off;
     } catch (...) {   // host allocation failure while building the tables
         delete p;
-        return HSADMM_ERR_HIP;
+        return HSADMM_ERR_HOST_MEMORY;
     }
 
     if (hipGetDevice(&p->device) != hipSuccess) { delete p; return HSADMM_ERR_HIP; }
@@ -442,7 +442,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         for (size_t l = 0; l < p->layers.size(); ++l) coef[2 * l] = 1.f;
     } catch (...) {
         delete p;
-        return HSADMM_ERR_HIP;
+        return HSADMM_ERR_HOST_MEMORY;
     }
     // device copies of the tables (an empty table stays a null pointer and is never launched over)
     bool ok = true;
@@ -777,12 +777,21 @@ int hsadmm_compact_sum(const hsadmm_plan_t* p, const float* src0, const float* s
 int hsadmm_node_coefficients(const double* rho1, const double* rho2, int32_t L, double lambda, int32_t M, int32_t P,
                              float* a, float* b)
 {
-    if (!rho1 || !rho2 || !a || !b || L < 1 || M < 1 || P < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (rho1 == nullptr || rho2 == nullptr || a == nullptr || b == nullptr) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (L < 1 || M < 1 || P < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    // Eq. (9): the three terms of gamma are the weight decay's share lambda / M, the P replicas' penalties and the
+    // inter-node penalty.  Every layer is checked before the first weight is written.
+    const double decay_share = lambda / static_cast<double>(M);
+    const double replicas = static_cast<double>(P);
+    auto gamma_of = [&](int32_t l) { return decay_share + replicas * rho1[l] + rho2[l]; };
     for (int32_t l = 0; l < L; ++l) {
-        const double gamma = lambda / (double)M + (double)P * rho1[l] + rho2[l];
-        if (!(gamma > 0.0) || rho1[l] < 0.0 || rho2[l] < 0.0) return HSADMM_ERR_INVALID_ARGUMENT;
-        a[l] = (float)((double)P * rho1[l] / gamma);
-        b[l] = (float)(rho2[l] / gamma);
+        const bool penalties_ok = rho1[l] >= 0.0 && rho2[l] >= 0.0;
+        if (!penalties_ok || !(gamma_of(l) > 0.0)) return HSADMM_ERR_INVALID_ARGUMENT;      // (a NaN fails one of them)
+    }
+    for (int32_t l = 0; l < L; ++l) {
+        const double gamma = gamma_of(l);
+        a[l] = static_cast<float>(replicas * rho1[l] / gamma);     // weight of Wbar + U
+        b[l] = static_cast<float>(rho2[l] / gamma);                // weight of z - v
     }
     return HSADMM_OK;
 }
@@ -837,7 +846,7 @@ int hsadmm_plan_set_node_weights(hsadmm_plan_t* p, const float* a, const float* 
     try {
         ab.resize(2 * L);
     } catch (...) {
-        return HSADMM_ERR_HIP;
+        return HSADMM_ERR_HOST_MEMORY;
     }
     for (size_t l = 0; l < L; ++l) { ab[2 * l] = a[l]; ab[2 * l + 1] = b[l]; }
     if (hipMemcpy(p->d_coef, ab.data(), sizeof(float) * ab.size(), hipMemcpyHostToDevice) != hipSuccess)
@@ -1184,6 +1193,7 @@ const char* hsadmm_strerror(int code)
         case HSADMM_ERR_WORKSPACE: return "workspace too small";
         case HSADMM_ERR_HIP: return "HIP runtime error";
         case HSADMM_ERR_UNSUPPORTED: return "unsupported size";
+        case HSADMM_ERR_HOST_MEMORY: return "host memory allocation failed";
         default: return "unknown error code";
     }
 }
@@ -1198,7 +1208,7 @@ int hsadmm_kernel_timing_enable(hsadmm_plan_t* p, int enable)
             p->ev_kernel.assign(kTimingPairs, 0);
             p->ev.reserve(2 * kTimingPairs);
         } catch (...) {
-            return HSADMM_ERR_HIP;
+            return HSADMM_ERR_HOST_MEMORY;
         }
         for (size_t i = 0; i < 2 * kTimingPairs; ++i) {
             hipEvent_t e;

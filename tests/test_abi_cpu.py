@@ -27,10 +27,12 @@ def test_header_symbols_are_all_exported(lib):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert pkg.hsadmm_version() >= 100
+    v = pkg.hsadmm_version()                     # major * 10000 + minor * 100 + patch
+    assert (v // 10000, v // 100 % 100, v % 100) >= (2, 0, 0) and v // 10000 < 100
     assert pkg.hsadmm_strerror(0) == "ok"
     assert "argument" in pkg.hsadmm_strerror(-1)
     assert "workspace" in pkg.hsadmm_strerror(-2)
+    assert "host memory" in pkg.hsadmm_strerror(-5)
     assert pkg.hsadmm_strerror(-99) == "unknown error code"
 
 
@@ -114,19 +116,43 @@ def test_no_cpu_fallback_in_the_product_package():
         assert "oracle" not in open(os.path.join(csrc, fn)).read(), fn
 
 
-def test_node_coefficients_host_function_matches_the_oracle(lib):
-    """hsadmm_node_coefficients runs on the host (no device needed): same fp32 weights as the oracle's Eq. (9)."""
-    import oracle
+def test_node_coefficients_host_function_against_eq_9_in_exact_arithmetic(lib):
+    """hsadmm_node_coefficients runs on the host (no device needed).  Its fp32 weights are checked against Eq. (9)
+    itself, a = P rho_1 / gamma and b = rho_2 / gamma with gamma = lambda / M + P rho_1 + rho_2, evaluated in exact
+    rational arithmetic from the same float64 inputs -- not against the oracle's function: the product's result must
+    be the correctly rounded float of the exact value, or its neighbour when the float64 evaluation lands within its
+    own rounding error of a float tie."""
+    from fractions import Fraction
     rng = np.random.default_rng(1)
     r1, r2 = rng.uniform(1e-4, 10, 40), rng.uniform(0, 10, 40)
-    for lam, M, P in ((1e-4, 16, 4), (0.0, 1, 1), (3e-2, 64, 8)):
+    r1[:3], r2[:3] = (1.5e-3, 10.0, 2.0 ** -20), (1.5e-4, 0.0, 10.0)      # the paper's initial penalties, edge cases
+    for lam, M, P in ((1e-4, 16, 4), (0.0, 1, 1), (3e-2, 64, 8), (5e-4, 3, 7)):
         a, b = pkg.hsadmm_node_coefficients(r1, r2, lam, M, P)
-        ao, bo = oracle.node_coefficients(r1, r2, lam, M, P)
-        assert np.array_equal(np.array(a, np.float32), ao) and np.array_equal(np.array(b, np.float32), bo)
-    with pytest.raises(pkg.HsadmmError):
-        pkg.hsadmm_node_coefficients([0.0], [0.0], 0.0, 1, 1)
-    with pytest.raises(pkg.HsadmmError):
-        pkg.hsadmm_node_coefficients([-1.0], [3.0], 0.0, 1, 1)
+        for l in range(len(r1)):
+            gamma = Fraction(float(lam)) / M + P * Fraction(float(r1[l])) + Fraction(float(r2[l]))
+            for got, exact in ((a[l], P * Fraction(float(r1[l])) / gamma), (b[l], Fraction(float(r2[l])) / gamma)):
+                got32 = np.float32(got)
+                assert float(got32) == got
+                lo, hi = np.nextafter(got32, np.float32(-1)), np.nextafter(got32, np.float32(2))
+                half_lo = (Fraction(float(lo)) + Fraction(float(got32))) / 2
+                half_hi = (Fraction(float(hi)) + Fraction(float(got32))) / 2
+                slack = abs(exact) * Fraction(1, 2 ** 50)
+                assert half_lo - slack <= exact <= half_hi + slack, (lam, M, P, l)
+            assert abs((Fraction(a[l]) + Fraction(b[l])) - (1 - Fraction(float(lam)) / M / gamma)) < Fraction(1, 2 ** 22)
+    # lambda = 0, rho_2 = 0: the plain mean (a = 1, b = 0), whatever rho_1 and P are
+    a, b = pkg.hsadmm_node_coefficients([0.3, 7.0], [0.0, 0.0], 0.0, 5, 8)
+    assert a == [1.0, 1.0] and b == [0.0, 0.0]
+    # rejected before anything is written: gamma = 0, a negative penalty (also in a later layer), NaN
+    for bad1, bad2 in (([0.0], [0.0]), ([-1.0], [3.0]), ([1.0, 1.0], [1.0, -2.0]), ([float("nan")], [1.0])):
+        with pytest.raises(pkg.HsadmmError):
+            pkg.hsadmm_node_coefficients(bad1, bad2, 0.0, 1, 1)
+    out_a = (ctypes.c_float * 2)(7.0, 7.0)
+    out_b = (ctypes.c_float * 2)(7.0, 7.0)
+    r1c, r2c = (ctypes.c_double * 2)(1.0, 1.0), (ctypes.c_double * 2)(1.0, -2.0)
+    assert lib.hsadmm_node_coefficients(r1c, r2c, 2, 0.0, 1, 1, out_a, out_b) == -1
+    assert list(out_a) == [7.0, 7.0] and list(out_b) == [7.0, 7.0]
+    assert lib.hsadmm_node_coefficients(None, r2c, 2, 0.0, 1, 1, out_a, out_b) == -1
+    assert lib.hsadmm_node_coefficients(r1c, r1c, 2, 0.0, 0, 1, out_a, out_b) == -1
 
 
 def test_adapt_penalties_host_function_matches_the_oracle(lib):
