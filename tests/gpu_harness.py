@@ -103,8 +103,23 @@ def min_relative_gap(wl, key):
     return worst
 
 
-def check_against_oracle(wl, got, ref, refc, check_float_tol=True):
-    """Bit-exact integer outputs; floats within 1e-6 of the layer's largest magnitude (and counted bitwise)."""
+def packed_segment_sizes(wl, mask):
+    """Meaningful elements of every layer's segment of the packed buffer under `mask` (without alignment padding)."""
+    sizes = []
+    for l in wl.layers:
+        m = mask[l.group_base:l.group_base + l.groups] != 0
+        if l.mode == 3:
+            sizes.append(int(m[:l.c_out].sum()) * int(m[l.c_out:].sum()) * l.khw)
+        else:
+            sizes.append(l.n if l.mode == 0 else int(m.sum()) * l.group_size)
+    return np.array(sizes)
+
+
+def check_against_oracle(wl, got, ref, refc, pack_align=1):
+    """Bit-exact integer outputs; floats within 1e-6 of the layer's largest magnitude (and counted bitwise).
+    ref / refc: what oracle.project and oracle.compact(Z, mask, pack_align) returned; the expansion is compared with
+    oracle.expand of the oracle's packed buffer."""
+    import oracle
     report = {}
     gap = min_relative_gap(wl, ref["key"])
     assert gap > 1e-10, "near-tie in the synthetic inputs (relative gap %g): unsuitable for a bit-exact mask test" % gap
@@ -131,10 +146,11 @@ def check_against_oracle(wl, got, ref, refc, check_float_tol=True):
         # compare the meaningful part of the segment (alignment padding is unspecified)
         seg_ref = refc["packed"][a:b]
         seg_got = got["packed"][a:b]
-        used = refc.get("seg_sizes", None)
-        n_used = int(used[li]) if used is not None else (b - a)
+        n_used = int(packed_segment_sizes(wl, ref["mask"])[li])
+        assert n_used <= b - a
         assert np.array_equal(bits(seg_got[:n_used]), bits(seg_ref[:n_used])), "packed segment %d differs" % li
+    ref_dst = oracle.expand(wl.table(), refc["packed"], ref["mask"], wl.n_arena, pack_align=pack_align)
     for l in wl.layers:
         sl = slice(l.elem_off, l.elem_off + l.n)
-        assert np.array_equal(bits(got["dst"][sl]), bits(got["Z"][sl])), "expand(compact(Z)) != Z in layer %s" % l.name
+        assert np.array_equal(bits(got["dst"][sl]), bits(ref_dst[sl])), "expansion differs from the oracle's in layer %s" % l.name
     return report

@@ -21,18 +21,10 @@ def _run(wl, pack_align=1, want_wbar=True, want_sqnorm=True, threads=8, determin
     t = wl.table()
     ref = oracle.project(t, W, U, want_wbar=True)
     refc = oracle.compact(t, ref["Z"], ref["mask"], pack_align=pack_align)
-    sizes = []
-    for l in wl.layers:
-        m = ref["mask"][l.group_base:l.group_base + l.groups]
-        if l.mode == wk.MODE_BOTH:
-            sizes.append(int(m[:l.c_out].sum()) * int(m[l.c_out:].sum()) * l.khw)
-        else:
-            sizes.append(l.n if l.mode == wk.MODE_NONE else int(m.sum()) * l.group_size)
-    refc["seg_sizes"] = np.array(sizes)
     run = GpuRun(wl, W, U, pack_align=pack_align, want_wbar=want_wbar, want_sqnorm=want_sqnorm, table=gpu_table)
     run.step()
     got = run.outputs()
-    rep = check_against_oracle(wl, got, ref, refc)
+    rep = check_against_oracle(wl, got, ref, refc, pack_align=pack_align)
     for name, cnt in rep.items():
         assert cnt == 0, "%s = %d" % (name, cnt)
     # untouched arena padding
