@@ -282,6 +282,28 @@ int hsadmm_project_compact(const hsadmm_plan_t* plan, const float* const* W_repl
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * hsadmm_project_compact for callers that cannot allocate device memory (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc) and so have no workspace to pass: the same arguments without
+ * `workspace` / `workspace_bytes`, the same outputs bit for bit.  Its scratch
+ * is an array of HSADMM_STATIC_SCRATCH_BYTES that the library holds statically
+ * on every device it is loaded on (until the process ends); a plan whose
+ * workspace_bytes (hsadmm_plan_sizes) exceed that is refused with UNSUPPORTED
+ * before anything is enqueued.  The call allocates and frees nothing.
+ * All calls on one device share the one array: calls that may overlap in time
+ * on a device (different streams, or different plans on different streams)
+ * race and must be ordered by the caller.  The array keeps the last call's
+ * contents; the step writes everything it reads from it, so nothing needs
+ * clearing.  The index mappings stay in that array, not in a workspace of the
+ * caller's, so a later hsadmm_compact / hsadmm_expand must be given the mask.
+ * Errors: UNSUPPORTED (plan too large), else those of hsadmm_project_compact.
+ */
+#define HSADMM_STATIC_SCRATCH_BYTES (16u << 20)
+int hsadmm_project_compact_static(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
+                                  float* U, float* Z, float* Wbar, uint8_t* mask, double* sqnorm,
+                                  float* packed, int64_t* layer_off, int32_t* kept_idx, void* hip_stream);
+
+/*
  * Tensor shrinkage of the pre-transmission buffer c = z_i + v_i (Section
  * 4.4.1; Algorithm 1, Phase 4): exactly hsadmm_compact applied to the
  * element-wise fp32 sum src0 + src1, which is formed on the fly (no full-size

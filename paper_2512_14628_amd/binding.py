@@ -17,7 +17,7 @@ SRC_PATH = os.path.join(_HERE, "csrc", "hsadmm.hip")
 INCLUDE_DIR = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "libhsadmm.so")
 
-MODE_NONE, MODE_FILTER, MODE_CHANNEL = 0, 1, 2
+MODE_NONE, MODE_FILTER, MODE_CHANNEL, MODE_BOTH = 0, 1, 2, 3
 MAX_REPLICAS = 16
 
 HIPCC_FLAGS = [
@@ -35,7 +35,7 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_project_weighted_compact", "hsadmm_project_frozen_compact",
            "hsadmm_project_weighted_frozen", "hsadmm_project_weighted_frozen_compact",
            "hsadmm_retrain_project", "hsadmm_retrain_expand",
-           "hsadmm_adapt_penalties", "hsadmm_scale_layers")
+           "hsadmm_adapt_penalties", "hsadmm_scale_layers", "hsadmm_project_compact_static")
 KERNEL_COUNT = 24
 
 
@@ -93,6 +93,9 @@ def load_library():
     lib.hsadmm_project_compact.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                            ctypes.c_size_t, vp]
     lib.hsadmm_project_compact.restype = ctypes.c_int
+    lib.hsadmm_project_compact_static.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp,
+                                                  vp, vp]
+    lib.hsadmm_project_compact_static.restype = ctypes.c_int
     lib.hsadmm_project_frozen.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp]
     lib.hsadmm_project_frozen.restype = ctypes.c_int
     lib.hsadmm_project_frozen_compact.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp,
@@ -281,6 +284,20 @@ def hsadmm_project_compact(plan: Plan, W_replicas: Sequence, U, Z, Wbar, mask, s
                                     _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_project_compact")
+    return rc
+
+
+def hsadmm_project_compact_static(plan: Plan, W_replicas: Sequence, U, Z, Wbar, mask, sqnorm, packed, layer_off,
+                                  kept_idx, stream=None, check: bool = True) -> int:
+    """hsadmm_project_compact on the library's static scratch array (no workspace argument, no allocation)."""
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    rc = lib.hsadmm_project_compact_static(plan.handle, ptrs, R, _ptr(U), _ptr(Z), _ptr(Wbar), _ptr(mask),
+                                           _ptr(sqnorm), _ptr(packed), _ptr(layer_off), _ptr(kept_idx),
+                                           _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_project_compact_static")
     return rc
 
 

@@ -100,6 +100,12 @@ enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kM
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
+// Scratch of the entry point that takes no workspace argument (hsadmm_project_compact_static): one array per
+// device, held until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the
+// device address is looked up once per plan (a plan belongs to one device) and kept in the plan.
+constexpr size_t kStaticScratchBytes = HSADMM_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 }  // namespace
 
 struct hsadmm_plan {
@@ -134,6 +140,7 @@ struct hsadmm_plan {
     int32_t* d_both_layers = nullptr;
     uint16_t* d_group_layer = nullptr;   // groups_total: scan segment of every group (bit 15: unconstrained layer)
     float* d_coef = nullptr;             // 2L: a_l, b_l of Eq. (9), set by hsadmm_plan_set_node_weights (default 1, 0)
+    void* static_ws = nullptr;           // device address of `scratch` on the plan's device
     uint16_t* d_chunk_layer = nullptr;   // per 16 groups: their segment if all 16 lie in one constrained segment, else 0xffff
     // Optional per-kernel timing (diagnostics; off by default).  Not thread-safe.
     bool timing = false;
@@ -426,6 +433,12 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     }
 
     if (hipGetDevice(&p->device) != hipSuccess) { delete p; return HSADMM_ERR_HIP; }
+    // this device's copy of the static scratch array (every device holds its own, at its own address)
+    if (hipGetSymbolAddress(&p->static_ws, HIP_SYMBOL(scratch)) != hipSuccess || p->static_ws == nullptr) {
+        (void)hipGetLastError();
+        delete p;
+        return HSADMM_ERR_HIP;
+    }
     std::vector<uint16_t> chunk_layer;
     std::vector<float> coef;
     try {
@@ -632,6 +645,17 @@ int hsadmm_project_compact(const hsadmm_plan_t* p, const float* const* W_replica
 {
     const CompactOut out{packed, layer_off, kept_idx};
     return project_impl(p, W_replicas, R, U, Z, Wbar, mask, sqnorm, &out, workspace, workspace_bytes, hip_stream);
+}
+
+int hsadmm_project_compact_static(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
+                                  float* Z, float* Wbar, uint8_t* mask, double* sqnorm, float* packed,
+                                  int64_t* layer_off, int32_t* kept_idx, void* hip_stream)
+{
+    if (!p) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (p->ws.total > kStaticScratchBytes) return HSADMM_ERR_UNSUPPORTED;     // the plan needs more scratch than the array holds
+    const CompactOut out{packed, layer_off, kept_idx};
+    // every kernel of the step writes the parts of the scratch it later reads, so nothing has to be cleared
+    return project_impl(p, W_replicas, R, U, Z, Wbar, mask, sqnorm, &out, p->static_ws, kStaticScratchBytes, hip_stream);
 }
 
 int hsadmm_project_frozen(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U, float* Z,
