@@ -556,6 +556,90 @@ int hsadmm_retrain_expand(const hsadmm_plan_t* plan, const float* packed, const 
                           const float* Zi, float* Vd, const float* z_prev, double* residuals,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * One entry point for every form of the projection step (Algorithm 1, Phases
+ * 2, 3 and 5 on one device): the calls above named hsadmm_project* and
+ * hsadmm_retrain_project are this call with some fields left NULL, and give
+ * the same results bit for bit.  Fill a zeroed hsadmm_step_args_t; a NULL
+ * field means "not wanted" / "not given".
+ *
+ *   candidate   z~ = Wbar + U                          Zg, Vd, coef all NULL   (Eq. (9), lambda = rho_2 = 0)
+ *               z~ = a_l (Wbar + U) + b_l (Zg - Vd)    Zg and Vd given         (Eq. (9))
+ *   support     selected: top-k of the group norms     mask_frozen NULL        (Eq. (10))
+ *               given:    z_i = z~ (.) mask_frozen     mask_frozen given       (Section 4.5, retraining branch)
+ *   dual        U <- U + (Wbar - z_i) in every form                            (Eq. (12))
+ *   shrinkage   of z_i (of c = z_i + Vd when Vd is given) under the support    packed, layer_off, kept_idx
+ *                                                                              all three or none (Eq. (15))
+ *
+ * Fields (device pointers unless stated; alignment and aliasing as for the
+ * named calls: arenas 16 bytes, sqnorm / layer_off / residuals 8, others 4):
+ *   struct_bytes     sizeof(hsadmm_step_args_t) as the caller was compiled (INVALID_ARGUMENT if it differs)
+ *   W_replicas, R    HOST array of R device arenas
+ *   U                in/out
+ *   Zg, Vd           in: global consensus z and the node's inter-node dual v_i
+ *   coef             in, 2L floats a_0, b_0, a_1, b_1, ... (hsadmm_node_coefficients gives a and b); NULL with Zg
+ *                    given: the weights stored in the plan.  Read by the kernels when they run, so a captured
+ *                    graph follows the buffer's contents from replay to replay.
+ *   mask_frozen      in, groups_total bytes, read as hsadmm_project_frozen reads it
+ *   sel_prev         in, optional, selected support and plain candidate only: the selection record of the
+ *                    previous outer iteration (the `sel` output of an earlier call on this plan, or
+ *                    hsadmm_selection_from_mask).  It changes no result.  It predicts which groups will be
+ *                    kept (Section 4.5: the pattern stops changing after a few iterations), and FILTER layers
+ *                    are then written in the form the prediction makes final and packed as they are formed:
+ *                    a correct prediction leaves only a zero fill of the pruned filters' rows of Z to do after
+ *                    the selection, a wrong one is repaired row by row without reading the replicas again.
+ *                    A record that no call of this library wrote for this plan (ranks repeated inside a layer)
+ *                    leaves Z, U, mask, sqnorm and sel correct and the packed buffer unspecified; no access
+ *                    leaves the buffers.  Must not overlap `sel`.
+ *   Z                out (in/out when `residuals` is given: the previous z_i on entry)
+ *   Wbar, sqnorm     out, optional
+ *   mask             out, required unless mask_frozen is given (then it must be NULL)
+ *   sel              out, optional, groups_total int32: the selection record of this call: the rank of every
+ *                    kept group among the kept groups of its layer (BOTH: of its part), -1 for a pruned group
+ *   mappings_cached  as in hsadmm_project_frozen_compact (frozen support with shrinkage only)
+ *   residuals        out, optional, 4L doubles, rows 0 and 1 as hsadmm_retrain_project writes them; only with
+ *                    mask_frozen, Zg / Vd and the shrinkage (UNSUPPORTED otherwise)
+ *   workspace, workspace_bytes, hip_stream   as for the named calls (a frozen support without shrinkage needs none)
+ * Errors: those of the named call that the fields select; UNSUPPORTED also for sel_prev with Zg / Vd.
+ */
+typedef struct {
+    size_t struct_bytes;
+    const float* const* W_replicas;
+    int32_t R;
+    int32_t mappings_cached;
+    float* U;
+    const float* Zg;
+    const float* Vd;
+    const float* coef;
+    const uint8_t* mask_frozen;
+    const int32_t* sel_prev;
+    float* Z;
+    float* Wbar;
+    uint8_t* mask;
+    double* sqnorm;
+    int32_t* sel;
+    float* packed;
+    int64_t* layer_off;
+    int32_t* kept_idx;
+    double* residuals;
+    void* workspace;
+    size_t workspace_bytes;
+    void* hip_stream;
+} hsadmm_step_args_t;
+
+int hsadmm_step(const hsadmm_plan_t* plan, const hsadmm_step_args_t* args);
+
+/*
+ * The selection record of a mask (see `sel` / `sel_prev` of hsadmm_step): sel[g] = rank of group g among the
+ * groups of its layer whose mask byte is nonzero (BOTH: among the filters, or among the channels), -1 where the
+ * byte is zero; the groups of a MODE_NONE layer are all kept.  For a caller who holds the previous iteration's
+ * mask (Algorithm 1 keeps m_i) but not its record.  Afterwards the workspace holds this mask's index mappings,
+ * as after hsadmm_compact with a mask.
+ * Errors: INVALID_ARGUMENT, WORKSPACE, HIP.
+ */
+int hsadmm_selection_from_mask(const hsadmm_plan_t* plan, const uint8_t* mask, int32_t* sel,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static string for an error code (never NULL). */
 const char* hsadmm_strerror(int code);
 
@@ -576,7 +660,7 @@ int hsadmm_version(void);
  * the plan must be used from one host thread only.  Off by default.
  * Errors: INVALID_ARGUMENT, HIP.
  */
-#define HSADMM_KERNEL_COUNT 24
+#define HSADMM_KERNEL_COUNT 26
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 /* Name of a kernel id ("" when out of range). */

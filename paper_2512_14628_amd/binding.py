@@ -35,8 +35,9 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_project_weighted_compact", "hsadmm_project_frozen_compact",
            "hsadmm_project_weighted_frozen", "hsadmm_project_weighted_frozen_compact",
            "hsadmm_retrain_project", "hsadmm_retrain_expand",
-           "hsadmm_adapt_penalties", "hsadmm_scale_layers", "hsadmm_project_compact_static")
-KERNEL_COUNT = 24
+           "hsadmm_adapt_penalties", "hsadmm_scale_layers", "hsadmm_project_compact_static",
+           "hsadmm_step", "hsadmm_selection_from_mask")
+KERNEL_COUNT = 26
 
 
 class HsadmmError(RuntimeError):
@@ -49,6 +50,28 @@ class _Layer(ctypes.Structure):
     _fields_ = [("elem_off", ctypes.c_int64), ("c_out", ctypes.c_int32), ("c_in", ctypes.c_int32),
                 ("khw", ctypes.c_int32), ("mode", ctypes.c_int32), ("k", ctypes.c_int32),
                 ("k_in", ctypes.c_int32)]
+
+
+# hsadmm_step_args_t, field by field, in declaration order: (name, C type, how the binding fills it).
+#   "dev": device buffer (torch tensor, integer address or None)
+_vp = ctypes.c_void_p
+_STEP_FIELDS = (
+    ("struct_bytes", ctypes.c_size_t, "sizeof"),
+    ("W_replicas", ctypes.POINTER(_vp), "replicas"),
+    ("R", ctypes.c_int32, "replica_count"),
+    ("mappings_cached", ctypes.c_int32, "flag"),
+    ("U", _vp, "dev"), ("Zg", _vp, "dev"), ("Vd", _vp, "dev"), ("coef", _vp, "dev"),
+    ("mask_frozen", _vp, "dev"), ("sel_prev", _vp, "dev"),
+    ("Z", _vp, "dev"), ("Wbar", _vp, "dev"), ("mask", _vp, "dev"), ("sqnorm", _vp, "dev"), ("sel", _vp, "dev"),
+    ("packed", _vp, "dev"), ("layer_off", _vp, "dev"), ("kept_idx", _vp, "dev"), ("residuals", _vp, "dev"),
+    ("workspace", _vp, "dev"),
+    ("workspace_bytes", ctypes.c_size_t, "workspace_size"),
+    ("hip_stream", _vp, "stream"),
+)
+
+
+class _StepArgs(ctypes.Structure):
+    _fields_ = [(name, ctype) for name, ctype, _ in _STEP_FIELDS]
 
 
 _lib = None
@@ -96,6 +119,10 @@ def load_library():
     lib.hsadmm_project_compact_static.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp,
                                                   vp, vp]
     lib.hsadmm_project_compact_static.restype = ctypes.c_int
+    lib.hsadmm_step.argtypes = [vp, ctypes.POINTER(_StepArgs)]
+    lib.hsadmm_step.restype = ctypes.c_int
+    lib.hsadmm_selection_from_mask.argtypes = [vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_selection_from_mask.restype = ctypes.c_int
     lib.hsadmm_project_frozen.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp, vp]
     lib.hsadmm_project_frozen.restype = ctypes.c_int
     lib.hsadmm_project_frozen_compact.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, vp, vp, vp, vp,
@@ -297,7 +324,56 @@ def hsadmm_project_compact_static(plan: Plan, W_replicas: Sequence, U, Z, Wbar, 
                                            _ptr(sqnorm), _ptr(packed), _ptr(layer_off), _ptr(kept_idx),
                                            _stream(stream))
     if check and rc != 0:
-        raise HsadmmError(rc, "hsadmm_project_compact_static")
+        raise HsadmmError(rc, "hsadmm_project_compact_static",
+           "hsadmm_step", "hsadmm_selection_from_mask")
+    return rc
+
+
+def hsadmm_step(plan: Plan, W_replicas: Sequence, stream=None, workspace_bytes: Optional[int] = None,
+                check: bool = True, **fields) -> int:
+    """hsadmm_step: every form of the projection step through one argument structure.  Keyword arguments are the
+    device-buffer fields of hsadmm_step_args_t (U, Z, mask, packed, sel_prev, ...) and the flag mappings_cached;
+    fields that are not given stay NULL."""
+    lib = load_library()
+    R = len(W_replicas)
+    ptrs = (ctypes.c_void_p * max(R, 1))(*[_ptr(w) for w in W_replicas])
+    args = _StepArgs()
+    known = {name for name, _, how in _STEP_FIELDS if how in ("dev", "flag")}
+    unknown = set(fields) - known
+    if unknown:
+        raise TypeError("hsadmm_step has no field(s) %s" % ", ".join(sorted(unknown)))
+    for name, _, how in _STEP_FIELDS:
+        if how == "sizeof":
+            value = ctypes.sizeof(_StepArgs)
+        elif how == "replicas":
+            value = ptrs
+        elif how == "replica_count":
+            value = R
+        elif how == "flag":
+            value = 1 if fields.get(name) else 0
+        elif how == "dev":
+            value = _ptr(fields.get(name))
+        elif how == "workspace_size":
+            ws = fields.get("workspace")
+            value = int(workspace_bytes) if workspace_bytes is not None else (0 if ws is None or isinstance(ws, int)
+                                                                             else _nbytes(ws))
+        else:
+            value = _stream(stream)
+        setattr(args, name, value)
+    rc = lib.hsadmm_step(plan.handle, ctypes.byref(args))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_step")
+    return rc
+
+
+def hsadmm_selection_from_mask(plan: Plan, mask, sel, workspace, stream=None, workspace_bytes: Optional[int] = None,
+                               check: bool = True) -> int:
+    """sel[g] = rank of group g among its layer's groups kept by `mask`, -1 if not kept."""
+    lib = load_library()
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_selection_from_mask(plan.handle, _ptr(mask), _ptr(sel), _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_selection_from_mask")
     return rc
 
 

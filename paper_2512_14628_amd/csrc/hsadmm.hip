@@ -96,7 +96,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kPass1Hinted, kHintedRepair, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 
@@ -191,6 +191,8 @@ void add_row_items(std::vector<WorkItem>& out, int layer, const DevLayer& d, int
         it.khw = d.khw;
         it.layer = layer;
         it.row0 = r0;
+        it.k = d.k;
+        it.packed_off = d.packed_off;
         out.push_back(it);
     }
 }
@@ -285,7 +287,7 @@ hipError_t launch_channel_final(const hsadmm_plan* p, const ProjectArgs& a, int 
 // (CHANNEL) are in place.  Layers under both constraints then take their second projection: channel
 // norms over the kept filters from the candidate held in Z, and the selection of the channels.
 hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, const ProjectArgs& a, uint8_t* mask,
-                         char* ws, hipStream_t s)
+                         char* ws, hipStream_t s, int32_t* sel_out = nullptr)
 {
     // the selection also leaves its index mappings in the workspace, for a compaction without a mask
     IndexMaps im;
@@ -293,6 +295,7 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
     im.cnt = reinterpret_cast<int32_t*>(ws + p->ws.cnt);
     im.layer_off = reinterpret_cast<int64_t*>(ws + p->ws.layer_off);
     im.kept_idx = reinterpret_cast<int32_t*>(ws + p->ws.kept_idx);
+    im.sel = sel_out;
     const int nL = (int)p->layers.size();
     hipError_t e = launch(p, kTopk, select_topk, (unsigned)p->layers.size(), kScanBlock, s,
                           (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
@@ -307,13 +310,14 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
                   (const int32_t*)p->d_both_layers, 1, im, nL, (int)p->pack_align);
 }
 
-int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, hipStream_t s)
+int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, hipStream_t s, int32_t* sel_out = nullptr)
 {
     IndexMaps o;
     o.pos = reinterpret_cast<int32_t*>(ws + p->ws.pos);
     o.cnt = reinterpret_cast<int32_t*>(ws + p->ws.cnt);
     o.layer_off = reinterpret_cast<int64_t*>(ws + p->ws.layer_off);
     o.kept_idx = reinterpret_cast<int32_t*>(ws + p->ws.kept_idx);
+    o.sel = sel_out;
     const hipError_t e = launch(p, kScan, scan_mask, (unsigned)p->layers.size(), kScanBlock, s,
                                 (const DevLayer*)p->d_layers, (int)p->layers.size(), (int)p->n_segments,
                                 (int)p->groups_total,
@@ -525,11 +529,18 @@ struct CompactOut {
     int32_t* kept_idx;
 };
 
+// sel_prev: the previous selection's record, which predicts this one (null: no prediction); sel_out: receives this
+// selection's record (may be null).
 static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U, float* Z,
                         float* Wbar, uint8_t* mask, double* sqnorm, const CompactOut* out, void* workspace,
-                        size_t workspace_bytes, void* hip_stream)
+                        size_t workspace_bytes, void* hip_stream, const int32_t* sel_prev = nullptr,
+                        int32_t* sel_out = nullptr)
 {
     if (!p || !W_replicas || !U || !Z || !mask || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!is_aligned(sel_prev, 4) || !is_aligned(sel_out, 4)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (sel_prev && sel_out &&
+        spans_overlap(reinterpret_cast<const float*>(sel_prev), reinterpret_cast<const float*>(sel_out), p->groups_total))
+        return HSADMM_ERR_INVALID_ARGUMENT;         // the repair pass reads the old record beside the new one
     if (out && (!out->packed || !out->layer_off || !out->kept_idx || !is_aligned(out->packed, 16) ||
                 !is_aligned(out->layer_off, 8) || !is_aligned(out->kept_idx, 4)))
         return HSADMM_ERR_INVALID_ARGUMENT;
@@ -551,17 +562,28 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     a.inv_R = 1.0f / (float)R;
     a.park_mean = R >= 3 ? 1 : 0;
     hipError_t e;
-    e = for_replica_count<true>(R, [&](auto c) { return launch_pass1<decltype(c)::value>(p, a, R, s); });
+    // Under a prediction pass 1 writes the FILTER rows in the form their predicted fate makes final and packs the rows
+    // it expects to be kept (and every row of the unconstrained layers).
+    const bool hinted = sel_prev != nullptr && !p->items_plain.empty();
+    if (hinted) {
+        const HintArgs h{sel_prev, out ? out->packed : nullptr};
+        e = for_replica_count<true>(R, [&](auto c) {
+            return launch(p, kPass1Hinted, project_pass1_hinted<decltype(c)::value>, (unsigned)p->items_proj.size(),
+                          kBlock, s, (const WorkItem*)p->d_items_proj, a, (int)R, h);
+        });
+    } else {
+        e = for_replica_count<true>(R, [&](auto c) { return launch_pass1<decltype(c)::value>(p, a, R, s); });
+    }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     // (the candidate of a BOTH layer is formed again from its parked mean and U)
-    if (run_selection(p, a.key, a.colpart, a, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
+    if (run_selection(p, a.key, a.colpart, a, mask, ws, s, sel_out) != hipSuccess) return HSADMM_ERR_HIP;
     // The compaction of Z under the selection just made reads kept groups only, which FILTER layers hold in
     // final form since pass 1, so it shares a launch with the FILTER fix-up; the CHANNEL and BOTH layers are
     // packed by the pass that writes their Z.
-    const bool fuse = out && !p->items_fix.empty();
+    const bool fuse = out && !hinted && !p->items_fix.empty();
     PackOut po{};
+    po.pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
     if (out) {
-        po.pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
         po.cnt = reinterpret_cast<const int32_t*>(ws + p->ws.cnt);
         po.kept_idx = reinterpret_cast<const int32_t*>(ws + p->ws.kept_idx);
         po.layer_off = reinterpret_cast<const int64_t*>(ws + p->ws.layer_off);
@@ -569,14 +591,24 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         po.co = CopyOut{out->layer_off, out->kept_idx};
         po.n_layers = (int)p->layers.size();
     }
-    if (!p->items_fix.empty() && !fuse) {
+    if (hinted) {
+        // every FILTER row from its predicted to its final form; with a compaction the launch also covers the
+        // unconstrained layers, whose first work items hand out their offsets and kept lists
+        const bool all_plain = out != nullptr;
+        const unsigned n = (unsigned)(all_plain ? p->items_plain.size() : p->items_fix.size());
+        if (n) {
+            e = launch(p, kHintedRepair, hinted_repair, n, kBlock, s,
+                       (const WorkItem*)(all_plain ? p->d_items_plain : p->d_items_fix), sel_prev, U, Z, po);
+            if (e != hipSuccess) return HSADMM_ERR_HIP;
+        }
+    } else if (!p->items_fix.empty() && !fuse) {
         e = launch(p, kFixup, project_fixup, (unsigned)p->items_fix.size(), kBlock, s,
                    (const WorkItem*)p->d_items_fix, (const uint8_t*)mask, U, Z);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
     // Without FILTER layers the gather of the plain rows (unconstrained layers) has no fix-up to share a launch
     // with; it then rides on the last final pass.
-    bool plain_pending = out && !fuse && !p->items_plain.empty();
+    bool plain_pending = out && !fuse && !hinted && !p->items_plain.empty();
     const unsigned n_plain = (unsigned)p->items_plain.size();
     if (!p->items_bfinal.empty()) {
         // layers under both constraints: final Z and U from the parked mean and U, under both selections
@@ -878,12 +910,15 @@ int hsadmm_plan_set_node_weights(hsadmm_plan_t* p, const float* a, const float* 
     return HSADMM_OK;
 }
 
+// coef_arg: device, 2L floats a_0, b_0, a_1, b_1, ... (null: the weights stored in the plan)
 static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
                                  const float* Zg, const float* Vd, float* Z, float* Wbar, uint8_t* mask,
                                  double* sqnorm, const CompactOut* out, void* workspace, size_t workspace_bytes,
-                                 void* hip_stream)
+                                 void* hip_stream, const float* coef_arg = nullptr, int32_t* sel_out = nullptr)
 {
     if (!p || !W_replicas || !U || !Zg || !Vd || !Z || !mask || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!is_aligned(coef_arg, 4) || !is_aligned(sel_out, 4)) return HSADMM_ERR_INVALID_ARGUMENT;
+    const float* const coef = coef_arg ? coef_arg : p->d_coef;
     if (out && (!out->packed || !out->layer_off || !out->kept_idx || !is_aligned(out->packed, 16) ||
                 !is_aligned(out->layer_off, 8) || !is_aligned(out->kept_idx, 4)))
         return HSADMM_ERR_INVALID_ARGUMENT;
@@ -904,8 +939,8 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     w.p.colpart = reinterpret_cast<double*>(ws + p->ws.colpart);
     w.p.inv_R = 1.0f / (float)R;
     w.p.park_mean = R >= 3 ? 1 : 0;
-    w.p.Zg = Zg; w.p.Vd = Vd; w.p.coef = p->d_coef;
-    w.Zg = Zg; w.Vd = Vd; w.coef = p->d_coef;
+    w.p.Zg = Zg; w.p.Vd = Vd; w.p.coef = coef;
+    w.Zg = Zg; w.Vd = Vd; w.coef = coef;
     const unsigned grid = (unsigned)p->items_proj.size();
     const WorkItem* items = p->d_items_proj;
     hipError_t e;
@@ -914,7 +949,7 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     });
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     // (the weighted candidate of a BOTH layer is formed again from its parked mean, U, Zg and Vd)
-    if (run_selection(p, w.p.key, w.p.colpart, w.p, mask, ws, s) != hipSuccess) return HSADMM_ERR_HIP;
+    if (run_selection(p, w.p.key, w.p.colpart, w.p, mask, ws, s, sel_out) != hipSuccess) return HSADMM_ERR_HIP;
     const uint8_t* cm = mask;
     PackOut po{};
     if (out) {
@@ -931,7 +966,7 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     const bool fuse = out && !p->items_fix.empty();
     if (!p->items_fix.empty() && !fuse) {
         e = launch(p, kWFixup, weighted_fixup, (unsigned)p->items_fix.size(), kBlock, s,
-                   (const WorkItem*)p->d_items_fix, cm, U, Z, Zg, Vd, (const float*)p->d_coef);
+                   (const WorkItem*)p->d_items_fix, cm, U, Z, Zg, Vd, coef);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
     // Final pass of the CHANNEL and BOTH layers: the frozen-mask kernel in its weighted form, on the parked mean
@@ -962,7 +997,7 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
         if (fuse)
             e = launch(p, kWFixupPack, weighted_fixup_pack, (unsigned)(p->items_fix.size() + p->items_none.size()),
                        kBlock, s, (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), cm, U, Z, Zg, Vd,
-                       (const float*)p->d_coef, (const WorkItem*)p->d_items_none, po);
+                       coef, (const WorkItem*)p->d_items_none, po);
         else if (!p->items_none.empty())
             e = launch(p, kGather, compact_gather<true>, (unsigned)p->items_none.size(), kBlock, s,
                        (const WorkItem*)p->d_items_none, (const float*)Z, Vd, po.pos, po.cnt, po.kept_idx,
@@ -996,9 +1031,10 @@ static int weighted_frozen_impl(const hsadmm_plan_t* p, const float* const* W_re
                                 const float* Zg, const float* Vd, float* Z, float* Wbar, const uint8_t* mask,
                                 const CompactOut* out, int32_t mappings_cached, void* workspace,
                                 size_t workspace_bytes, void* hip_stream, double* residuals = nullptr,
-                                bool with_residuals = false)
+                                bool with_residuals = false, const float* coef_arg = nullptr)
 {
     if (!p || !W_replicas || !U || !Zg || !Vd || !Z || !mask || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!is_aligned(coef_arg, 4)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (with_residuals && (!out || !residuals || !is_aligned(residuals, 8))) return HSADMM_ERR_INVALID_ARGUMENT;
     if (out && (!out->packed || !out->layer_off || !out->kept_idx || !workspace || !is_aligned(out->packed, 16) ||
                 !is_aligned(out->layer_off, 8) || !is_aligned(out->kept_idx, 4) || !is_aligned(workspace, 256)))
@@ -1017,7 +1053,7 @@ static int weighted_frozen_impl(const hsadmm_plan_t* p, const float* const* W_re
     for (int r = 0; r < R; ++r) a.W[r] = W_replicas[r];
     a.U = U; a.Z = Z; a.Wbar = Wbar;
     a.inv_R = 1.0f / (float)R;
-    a.Zg = Zg; a.Vd = Vd; a.coef = p->d_coef;
+    a.Zg = Zg; a.Vd = Vd; a.coef = coef_arg ? coef_arg : p->d_coef;
     PackOut po{};
     if (out) {
         if (!mappings_cached) {
@@ -1084,6 +1120,49 @@ int hsadmm_retrain_project(const hsadmm_plan_t* p, const float* const* W_replica
     const CompactOut out{packed, layer_off, kept_idx};
     return weighted_frozen_impl(p, W_replicas, R, U, Zg, Vd, Z, Wbar, mask, &out, mappings_cached, workspace,
                                 workspace_bytes, hip_stream, residuals, true);
+}
+
+int hsadmm_step(const hsadmm_plan_t* p, const hsadmm_step_args_t* x)
+{
+    if (!p || !x || x->struct_bytes != sizeof(hsadmm_step_args_t)) return HSADMM_ERR_INVALID_ARGUMENT;
+    const bool weighted = x->Zg != nullptr || x->Vd != nullptr;          // both are required then (checked below)
+    const bool frozen = x->mask_frozen != nullptr;
+    const bool pack = x->packed != nullptr || x->layer_off != nullptr || x->kept_idx != nullptr;
+    if (!weighted && x->coef) return HSADMM_ERR_INVALID_ARGUMENT;        // weights without the terms they weigh
+    const CompactOut out{x->packed, x->layer_off, x->kept_idx};         // (each impl wants all three or none)
+    if (frozen) {
+        // retraining branch: the given mask replaces the selection; nothing is selected, predicted or recorded
+        if (x->mask || x->sqnorm || x->sel_prev || x->sel) return HSADMM_ERR_INVALID_ARGUMENT;
+        if (x->residuals && !(weighted && pack)) return HSADMM_ERR_UNSUPPORTED;
+        if (weighted)
+            return weighted_frozen_impl(p, x->W_replicas, x->R, x->U, x->Zg, x->Vd, x->Z, x->Wbar, x->mask_frozen,
+                                        pack ? &out : nullptr, x->mappings_cached, x->workspace, x->workspace_bytes,
+                                        x->hip_stream, x->residuals, x->residuals != nullptr, x->coef);
+        if (pack)
+            return hsadmm_project_frozen_compact(p, x->W_replicas, x->R, x->U, x->Z, x->Wbar, x->mask_frozen,
+                                                 x->mappings_cached, x->packed, x->layer_off, x->kept_idx,
+                                                 x->workspace, x->workspace_bytes, x->hip_stream);
+        return hsadmm_project_frozen(p, x->W_replicas, x->R, x->U, x->Z, x->Wbar, x->mask_frozen, x->hip_stream);
+    }
+    if (x->mappings_cached || x->residuals) return HSADMM_ERR_UNSUPPORTED;  // (the norms of a dynamic step: hsadmm_residuals)
+    if (weighted) {
+        if (x->sel_prev) return HSADMM_ERR_UNSUPPORTED;                    // no predicted form of the weighted pass yet
+        return project_weighted_impl(p, x->W_replicas, x->R, x->U, x->Zg, x->Vd, x->Z, x->Wbar, x->mask, x->sqnorm,
+                                     pack ? &out : nullptr, x->workspace, x->workspace_bytes, x->hip_stream, x->coef,
+                                     x->sel);
+    }
+    return project_impl(p, x->W_replicas, x->R, x->U, x->Z, x->Wbar, x->mask, x->sqnorm, pack ? &out : nullptr,
+                        x->workspace, x->workspace_bytes, x->hip_stream, x->sel_prev, x->sel);
+}
+
+int hsadmm_selection_from_mask(const hsadmm_plan_t* p, const uint8_t* mask, int32_t* sel, void* workspace,
+                               size_t workspace_bytes, void* hip_stream)
+{
+    if (!p || !mask || !sel || !workspace || !is_aligned(sel, 4) || !is_aligned(workspace, 256))
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;
+    return run_scan(p, mask, static_cast<char*>(workspace), static_cast<hipStream_t>(hip_stream), sel);
 }
 
 int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, const float* Zi,
@@ -1287,6 +1366,8 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kRetrainProject: return "retrain_project";
         case kRetrainExpand: return "retrain_expand";
         case kScaleLayers: return "scale_layers";
+        case kPass1Hinted: return "project_pass1_hinted";
+        case kHintedRepair: return "hinted_repair";
         default: return "";
     }
 }

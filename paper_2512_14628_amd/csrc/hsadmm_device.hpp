@@ -55,6 +55,7 @@ struct IndexMaps {
                          // run in kept_idx, kept groups of the second segment (BOTH: channels; else 0)
     int64_t* layer_off;  // L+1
     int32_t* kept_idx;   // groups_total
+    int32_t* sel;        // null, or the caller's selection record: a second copy of pos, written by select_topk only
 };
 
 // Where the first work item of every layer copies the layer's part of the index mappings held in the workspace
@@ -106,7 +107,8 @@ struct WorkItem {
     int32_t khw;
     int32_t layer;
     int32_t row0;       // index of the item's first row inside the layer
-    int32_t pad_[3];
+    int32_t k;          // row item: groups the layer keeps under the plan's own selection (NONE: all its rows)
+    int64_t packed_off; // row item: start of the layer in the packed buffer under the plan's own selection
 };
 static_assert(sizeof(WorkItem) == 64, "WorkItem layout");
 

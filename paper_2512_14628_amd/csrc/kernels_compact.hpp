@@ -159,6 +159,7 @@ __global__ __launch_bounds__(kScanBlock) void scan_mask(const DevLayer* __restri
             const int rank = carry + block_excl_scan<kScanWaves>(m, wtot, total);
             if (g < G) {
                 o.pos[g_first + g] = m ? rank : -1;
+                if (o.sel) o.sel[g_first + g] = m ? rank : -1;
                 if (m) o.kept_idx[k_first + rank] = g;
             }
             carry += total;

@@ -60,6 +60,71 @@ struct Cand {
         if (a.Wbar) st4(a.Wbar + e, wb);
         return v;
     }
+    // HINTED forms: a previous selection predicts the row's fate.  The candidate goes to `vdst` and the dual of a
+    // kept group to `edst`: (Z, U) for a row predicted kept (final if it is kept again), (U, Z) for a row
+    // predicted pruned (U = V is final if it is pruned again, and Z holds the kept-form dual so that either
+    // outcome can be finished without the replicas).  `pk`, unless null, is the row's place in the packed buffer.
+    static __device__ __forceinline__ double two_h(const ProjectArgs& a, int Rrt, int64_t base, int o0, int o1,
+                                                   float* vdst, float* edst, float* pk, double acc)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        const int64_t e0 = base + o0, e1 = base + o1;
+        v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) {
+            const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
+            s0 = s0 + w0;
+            s1 = s1 + w1;
+        }
+        const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
+        const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
+        const v4f v0 = wb0 + u0, v1 = wb1 + u1;
+        const v4f d0 = wb0 - v0, d1 = wb1 - v1;
+        st4(vdst + e0, v0);
+        st4(vdst + e1, v1);
+        st4(edst + e0, u0 + d0);
+        st4(edst + e1, u1 + d1);
+        if (pk) { st4u(pk + o0, v0); st4u(pk + o1, v1); }
+        if (a.Wbar) { st4(a.Wbar + e0, wb0); st4(a.Wbar + e1, wb1); }
+        acc = sq4(acc, v0);
+        return sq4(acc, v1);
+    }
+    static __device__ __forceinline__ v4f one_h(const ProjectArgs& a, int Rrt, int64_t base, int o, float* vdst,
+                                                float* edst, float* pk)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        const int64_t e = base + o;
+        v4f s = ld4(a.W[0] + e);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+        const v4f u = ld4(a.U + e);
+        const v4f wb = s * a.inv_R;
+        const v4f v = wb + u;
+        const v4f d = wb - v;
+        st4(vdst + e, v);
+        st4(edst + e, u + d);
+        if (pk) st4u(pk + o, v);
+        if (a.Wbar) st4(a.Wbar + e, wb);
+        return v;
+    }
+    static __device__ __forceinline__ float scalar_h(const ProjectArgs& a, int Rrt, int64_t base, int o, float* vdst,
+                                                     float* edst, float* pk)
+    {
+        const int RR = R > 0 ? R : Rrt;
+        const int64_t e = base + o;
+        float s = ld1(a.W[0] + e);
+#pragma unroll
+        for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
+        const float u = ld1(a.U + e);
+        const float wb = s * a.inv_R;
+        const float v = wb + u;
+        const float d = wb - v;
+        st1(vdst + e, v);
+        st1(edst + e, u + d);
+        if (pk) pk[o] = v;
+        if (a.Wbar) st1(a.Wbar + e, wb);
+        return v;
+    }
     // PARK forms (layers under both constraints): the candidate for the norms, the mean parked in Z, U untouched;
     // the outputs are written once both selections are known, from the parked mean and U
     static __device__ __forceinline__ double park_two(const ProjectArgs& a, int Rrt, int64_t e0, int64_t e1, double acc)
@@ -269,6 +334,110 @@ __global__ __launch_bounds__(kBlock) void project_pass1(const WorkItem* __restri
     else project_rows<R, false>(it, a, Rrt);
 }
 
+// ------------------------------------------------------------------ project, pass 1 under a predicted selection
+
+// The sparsity pattern stops changing after a few outer iterations (Section 4.5), so the selection of the previous
+// iteration predicts this one's.  A selection record holds, for every group, its rank among the kept groups of its
+// layer (what the compaction calls its position), or -1 if it was pruned.
+struct HintArgs {
+    const int32_t* sel_prev;   // groups_total: the previous selection's record
+    float* packed;             // packed buffer of this call's compaction, or null (no compaction)
+};
+
+// pass1_row with the outputs of a row steered by its prediction (see Cand::two_h); the sum of squares is taken
+// in the same order as there, so the keys carry the same bits.
+template <int R>
+__device__ __forceinline__ double pass1_row_hinted(const ProjectArgs& a, int Rrt, int64_t base, int row_len, bool vec,
+                                                   int j, int step, float* vdst, float* edst, float* pk)
+{
+    double acc = 0.0;
+    if (vec) {
+        const int nchunk = row_len >> 2;
+        int c = j;
+        for (; c + step < nchunk; c += 2 * step)
+            acc = Cand<R>::two_h(a, Rrt, base, c << 2, (c + step) << 2, vdst, edst, pk, acc);
+        if (c < nchunk) acc = sq4(acc, Cand<R>::one_h(a, Rrt, base, c << 2, vdst, edst, pk));
+    } else {
+        for (int c = j; c < row_len; c += step) {
+            const float v = Cand<R>::scalar_h(a, Rrt, base, c, vdst, edst, pk);
+            acc = fma((double)v, (double)v, acc);
+        }
+    }
+    return acc;
+}
+
+// project_rows for FILTER / NONE row items under a predicted selection.  A row predicted kept is written as pass 1
+// always writes it (Z <- V, U <- U + (Wbar - V)) and, with a compaction to follow, also at its predicted rank in
+// the packed buffer; a row predicted pruned gets U <- V and, in Z, the kept-form dual.  The rows of an
+// unconstrained layer are always kept, at their own index.  A rank outside [0, k) cannot have come from a
+// selection of this plan: such a row is treated as kept and left for the repair pass to pack.
+template <int R>
+__device__ __forceinline__ void project_rows_hinted(const WorkItem& it, const ProjectArgs& a, int Rrt,
+                                                    const HintArgs& h)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const bool unconstrained = item_mode(it) == HSADMM_MODE_NONE;
+    float* const pk_layer = h.packed ? h.packed + it.packed_off : nullptr;
+    auto targets = [&](int rr, float*& vdst, float*& edst, float*& pk) {
+        const int hp = unconstrained ? it.row0 + rr : h.sel_prev[it.g0 + rr];
+        const bool pred_kept = hp >= 0;
+        vdst = pred_kept ? a.Z : a.U;
+        edst = pred_kept ? a.U : a.Z;
+        pk = (pk_layer && pred_kept && hp < it.k) ? pk_layer + (int64_t)hp * row_len : nullptr;
+    };
+    if (it.lpr <= kWave) {
+        const int lpr = it.lpr;
+        const int rpw = kWave / lpr;
+        const int sub = lane / lpr;
+        const int j = lane - sub * lpr;
+        for (int rb = wave * rpw; rb < it.nr; rb += kWaves * rpw) {
+            const int rr = rb + sub;
+            const bool active = rr < it.nr;
+            double acc = 0.0;
+            if (active) {
+                float *vdst, *edst, *pk;
+                targets(rr, vdst, edst, pk);
+                acc = pass1_row_hinted<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr, vdst, edst, pk);
+            }
+            acc = wave_xor_sum(acc, lpr);
+            if (active && j == 0) a.key[it.g0 + rr] = acc;
+        }
+    } else {
+        __shared__ double wsum[kWaves];
+        for (int rr = 0; rr < it.nr; ++rr) {
+            float *vdst, *edst, *pk;
+            targets(rr, vdst, edst, pk);
+            double acc = pass1_row_hinted<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, threadIdx.x, kBlock,
+                                             vdst, edst, pk);
+            acc = wave_xor_sum(acc, kWave);
+            if (lane == 0) wsum[wave] = acc;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double s = wsum[0];
+                for (int w = 1; w < kWaves; ++w) s += wsum[w];
+                a.key[it.g0 + rr] = s;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Pass 1 under a predicted selection: FILTER and NONE layers as above; CHANNEL and BOTH layers take no prediction
+// (their outputs are written after the selection anyway).
+template <int R>
+__global__ __launch_bounds__(kBlock) void project_pass1_hinted(const WorkItem* __restrict__ items, ProjectArgs a,
+                                                               int Rrt, HintArgs h)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int mode = item_mode(it);
+    if (mode == HSADMM_MODE_CHANNEL) project_tile<R>(it, a, Rrt);
+    else if (mode == HSADMM_MODE_BOTH) project_rows<R, true>(it, a, Rrt);
+    else project_rows_hinted<R>(it, a, Rrt, h);
+}
+
 // ------------------------------------------------------------------ BOTH: channel norms after the filter projection
 
 // Second projection of a layer under both constraints (Section 3, paragraph after Eq. (10)): the
@@ -403,6 +572,85 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
     fixup_rows(items[blockIdx.x], mask, U, Z);
 }
 
+// ------------------------------------------------------------------ project under a predicted selection: repair
+
+// After the selection every FILTER row goes from the form its prediction gave it to its final form, and the packed
+// buffer is completed (`packed`: the layer's segment, or null without a compaction):
+//   predicted pruned, pruned   Z <- +0 (a store only; U = V is final since pass 1)
+//   predicted pruned, kept     Z holds the kept-form dual and U the candidate: the two change places, and the
+//                              candidate goes to the packed row
+//   predicted kept,   pruned   U <- V (held in Z), Z <- +0, as without a prediction
+//   predicted kept,   kept     final; copied to the packed buffer only if its rank has changed
+// sel_prev / pos: the previous and the new selection's ranks of the item's first row onwards.
+__device__ __forceinline__ void hinted_repair_rows(const WorkItem& it, const int32_t* __restrict__ sel_prev,
+                                                   const int32_t* __restrict__ pos, float* U, float* Z, float* packed)
+{
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+    const int rows_at_once = kBlock / lpr;
+    const int sub = threadIdx.x / lpr;
+    const int j = threadIdx.x - sub * lpr;
+    const int nchunk = row_len >> 2;
+    for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+        const int hp = sel_prev[it.g0 + rr];
+        const int pn = pos[it.g0 + rr];
+        const bool pred_kept = hp >= 0, kept = pn >= 0;
+        const int64_t base = it.base + (int64_t)rr * row_len;
+        float* pk = (packed && kept) ? packed + (int64_t)pn * row_len : nullptr;
+        if (pred_kept && kept) {
+            if (!pk || pn == hp) continue;                       // packed in pass 1 already, at this rank
+            if (vec) for (int c = j; c < nchunk; c += lpr) st4u(pk + 4 * c, ld4(Z + base + 4 * c));
+            else for (int c = j; c < row_len; c += lpr) pk[c] = ld1(Z + base + c);
+        } else if (!pred_kept && !kept) {
+            if (vec) for (int c = j; c < nchunk; c += lpr) st4(Z + base + 4 * c, zero4);
+            else for (int c = j; c < row_len; c += lpr) st1(Z + base + c, 0.f);
+        } else if (pred_kept) {
+            if (vec) {
+                for (int c = j; c < nchunk; c += lpr) {
+                    const int64_t e = base + 4 * c;
+                    st4(U + e, ld4(Z + e));
+                    st4(Z + e, zero4);
+                }
+            } else {
+                for (int c = j; c < row_len; c += lpr) {
+                    st1(U + base + c, ld1(Z + base + c));
+                    st1(Z + base + c, 0.f);
+                }
+            }
+        } else {
+            if (vec) {
+                for (int c = j; c < nchunk; c += lpr) {
+                    const int64_t e = base + 4 * c;
+                    const v4f v = ld4(U + e), d = ld4(Z + e);
+                    st4(Z + e, v);
+                    st4(U + e, d);
+                    if (pk) st4u(pk + 4 * c, v);
+                }
+            } else {
+                for (int c = j; c < row_len; c += lpr) {
+                    const float v = ld1(U + base + c), d = ld1(Z + base + c);
+                    st1(Z + base + c, v);
+                    st1(U + base + c, d);
+                    if (pk) pk[c] = v;
+                }
+            }
+        }
+    }
+}
+
+// Row items of the FILTER layers (and, with a compaction, of the unconstrained layers, whose rows pass 1 has
+// packed: only their offsets and kept lists are handed to the caller here).
+__global__ __launch_bounds__(kBlock) void hinted_repair(const WorkItem* __restrict__ items,
+                                                        const int32_t* __restrict__ sel_prev, float* U, float* Z,
+                                                        PackOut po)
+{
+    const WorkItem it = items[blockIdx.x];
+    if (po.packed && it.row0 == 0) copy_out_layer(it.layer, po.cnt, po.kept_idx, po.n_layers, po.layer_off, po.co);
+    if (item_mode(it) != HSADMM_MODE_FILTER) return;
+    hinted_repair_rows(it, sel_prev, po.pos, U, Z, po.packed ? po.packed + it.packed_off : nullptr);
+}
 
 }  // namespace
 #endif

@@ -133,7 +133,7 @@ __device__ __forceinline__ bool same_prefix(unsigned long long y, unsigned long 
 
 template <bool INREG>
 __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, uint8_t* ml, int kk, TopkShared& sh,
-                                           int32_t* pos_l, int32_t* kidx_l)
+                                           int32_t* pos_l, int32_t* kidx_l, int32_t* sel_l)
 {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -269,6 +269,7 @@ __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, 
         if (g < G) {
             ml[g] = kept ? 1 : 0;
             pos_l[g] = kept ? r : -1;
+            if (sel_l) sel_l[g] = kept ? r : -1;
             if (kept) kidx_l[r] = g;
         }
         carry_kept += total_kept;
@@ -297,6 +298,7 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
     uint8_t* ml = mask + first;
     // the index mappings of this selection (what scan_mask would derive from the mask)
     int32_t* pos_l = im.pos + first;
+    int32_t* sel_l = im.sel ? im.sel + first : nullptr;      // the caller's copy of the ranks
     int32_t* kidx_l = im.kept_idx + L.kept_start + ((both && stage == 1) ? L.k : 0);
     if (tid == 0 && stage == 0) {
         const int l = blockIdx.x;
@@ -347,12 +349,15 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
     }
     const int kk = (L.mode == HSADMM_MODE_NONE) ? G : ((both && stage == 1) ? L.k_in : L.k);
     if (kk >= G) {
-        for (int g = tid; g < G; g += kScanBlock) { ml[g] = 1; pos_l[g] = g; kidx_l[g] = g; }
+        for (int g = tid; g < G; g += kScanBlock) {
+            ml[g] = 1; pos_l[g] = g; kidx_l[g] = g;
+            if (sel_l) sel_l[g] = g;
+        }
         return;
     }
     const unsigned long long* kb = reinterpret_cast<const unsigned long long*>(kl);
-    if (G <= kTopkRegs * kScanBlock) topk_layer<true>(G, kb, ml, kk, sh, pos_l, kidx_l);
-    else topk_layer<false>(G, kb, ml, kk, sh, pos_l, kidx_l);
+    if (G <= kTopkRegs * kScanBlock) topk_layer<true>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l);
+    else topk_layer<false>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l);
 }
 
 }  // namespace

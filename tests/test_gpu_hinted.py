@@ -1,0 +1,307 @@
+"""The projection step under a predicted selection (hsadmm_step with sel_prev; Section 4.5: the sparsity pattern
+stops changing after a few outer iterations, so the previous iteration's selection predicts this one's).
+
+A prediction changes no result: whatever the record says, every output must be the oracle's, bit for bit.  The
+predictions below are built on the host from the oracle's mask: right for every group, wrong for about a tenth of
+them, wrong for all of them, and degenerate records (everything pruned, everything kept, ranks out of range)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2512_14628_amd as pkg
+import workloads as wk
+
+pytestmark = pytest.mark.gpu
+
+
+def record_of(wl, mask):
+    """Selection record of a mask: rank of every kept group inside its layer (a layer under both constraints:
+    inside its filters, inside its channels), -1 for the others; unconstrained layers keep everything."""
+    sel = np.full(mask.shape, -1, np.int32)
+    for l in wl.layers:
+        parts = [(l.group_base, l.c_out), (l.group_base + l.c_out, l.c_in)] if l.mode == wk.MODE_BOTH \
+            else [(l.group_base, l.groups)]
+        for first, G in parts:
+            m = np.ones(G, bool) if l.mode == wk.MODE_NONE else mask[first:first + G] != 0
+            sel[first:first + G] = np.where(m, np.cumsum(m) - 1, -1)
+    return sel
+
+
+def degrade(wl, mask, fraction, rng):
+    """A mask with the same number of kept groups per layer in which about `fraction` of the kept groups of every
+    constrained layer have changed places with pruned ones."""
+    out = mask.copy()
+    for l in wl.layers:
+        if l.mode == wk.MODE_NONE:
+            continue
+        parts = [(l.group_base, l.c_out), (l.group_base + l.c_out, l.c_in)] if l.mode == wk.MODE_BOTH \
+            else [(l.group_base, l.groups)]
+        for first, G in parts:
+            m = out[first:first + G]
+            kept, pruned = np.flatnonzero(m != 0), np.flatnonzero(m == 0)
+            n = min(len(kept), len(pruned), max(1, int(round(fraction * len(kept)))))
+            if fraction <= 0 or n == 0:
+                continue
+            m[rng.choice(kept, n, replace=False)] = 0
+            m[rng.choice(pruned, n, replace=False)] = 1
+    return out
+
+
+SHAPES = [(96, 16, 1, wk.MODE_FILTER, 40), (80, 64, 9, wk.MODE_FILTER, 30), (40, 256, 9, wk.MODE_FILTER, 16),
+          (24, 512, 9, wk.MODE_FILTER, 9), (64, 3, 49, wk.MODE_FILTER, 20), (37, 5, 7, wk.MODE_FILTER, 36),
+          (300, 1, 1, wk.MODE_FILTER, 1), (96, 128, 1, wk.MODE_CHANNEL, 50), (48, 40, 9, wk.MODE_BOTH, 30, 21),
+          (10, 128, 1, wk.MODE_NONE, 10), (33, 7, 1, wk.MODE_NONE, 33), (70, 2100, 1, wk.MODE_FILTER, 28)]
+
+
+class _Bufs:
+    def __init__(self, wl, W, U, pack_align):
+        dev = torch.device("cuda:0")
+        self.plan = pkg.Plan(wl.table(), pack_align_elems=pack_align)
+        p = self.plan
+        n = wl.n_arena
+        nan = float("nan")
+        self.W = [torch.from_numpy(np.ascontiguousarray(W[r])).to(dev) for r in range(W.shape[0])]
+        self.U0 = torch.from_numpy(np.ascontiguousarray(U)).to(dev)
+        self.U = self.U0.clone()
+        self.Z = torch.full((n,), nan, dtype=torch.float32, device=dev)
+        self.Wbar = torch.full((n,), nan, dtype=torch.float32, device=dev)
+        self.mask = torch.full((p.groups_total,), 7, dtype=torch.uint8, device=dev)
+        self.key = torch.full((p.groups_total,), nan, dtype=torch.float64, device=dev)
+        self.sel = torch.full((p.groups_total,), -7, dtype=torch.int32, device=dev)
+        self.ws = torch.zeros(p.workspace_bytes, dtype=torch.uint8, device=dev)
+        self.packed = torch.full((max(p.packed_capacity_elems, 1),), nan, dtype=torch.float32, device=dev)
+        self.off = torch.full((p.n_layers + 1,), -1, dtype=torch.int64, device=dev)
+        self.kept = torch.full((p.groups_total,), -1, dtype=torch.int32, device=dev)
+        self.dst = torch.full((n,), nan, dtype=torch.float32, device=dev)
+
+    def reset(self):
+        self.U.copy_(self.U0)
+        nan = float("nan")
+        for t in (self.Z, self.Wbar, self.packed, self.dst, self.key):
+            t.fill_(nan)
+        self.mask.fill_(7)
+        self.sel.fill_(-7)
+        self.off.fill_(-1)
+        self.kept.fill_(-1)
+        self.ws.fill_(0xAB)
+
+    def outputs(self):
+        torch.cuda.synchronize()
+        return {"U": self.U.cpu().numpy(), "Z": self.Z.cpu().numpy(), "mask": self.mask.cpu().numpy(),
+                "packed": self.packed.cpu().numpy(), "layer_off": self.off.cpu().numpy(),
+                "kept_idx": self.kept.cpu().numpy(), "dst": self.dst.cpu().numpy(), "Wbar": self.Wbar.cpu().numpy(),
+                "key": self.key.cpu().numpy(), "sel": self.sel.cpu().numpy()}
+
+
+def _hinted_step(b, sel_prev, compaction=True):
+    extra = dict(packed=b.packed, layer_off=b.off, kept_idx=b.kept) if compaction else {}
+    pkg.hsadmm_step(b.plan, b.W, U=b.U, Z=b.Z, Wbar=b.Wbar, mask=b.mask, sqnorm=b.key, sel=b.sel, sel_prev=sel_prev,
+                    workspace=b.ws, **extra)
+    if compaction:
+        pkg.hsadmm_expand(b.plan, b.packed, None, b.dst, b.ws)
+
+
+@pytest.mark.parametrize("R,pack_align", [(4, 1), (1, 4), (5, 1), (3, 7)])
+def test_any_prediction_gives_the_oracles_outputs(R, pack_align):
+    from tests.gpu_harness import check_against_oracle
+    rng = np.random.default_rng(100 + R)
+    wl = wk.custom_workload(SHAPES, R=R, seed=20 + R, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    t = wl.table()
+    ref = oracle.project(t, W, U, want_wbar=True)
+    refc = oracle.compact(t, ref["Z"], ref["mask"], pack_align=pack_align)
+    want_sel = record_of(wl, ref["mask"])
+    b = _Bufs(wl, W, U, pack_align)
+    dev = b.U.device
+
+    # the record the library derives from a mask is the host's
+    sel_gpu = torch.full((b.plan.groups_total,), -9, dtype=torch.int32, device=dev)
+    pkg.hsadmm_selection_from_mask(b.plan, torch.from_numpy(ref["mask"]).to(dev), sel_gpu, b.ws)
+    assert np.array_equal(sel_gpu.cpu().numpy(), want_sel)
+
+    G = b.plan.groups_total
+    records = {
+        "all right": want_sel,
+        "a tenth wrong": record_of(wl, degrade(wl, ref["mask"], 0.1, rng)),
+        "half wrong": record_of(wl, degrade(wl, ref["mask"], 0.5, rng)),
+        "all wrong": record_of(wl, (ref["mask"] == 0).astype(np.uint8)),
+        "everything pruned": np.full(G, -1, np.int32),
+        "everything kept": record_of(wl, np.ones(G, np.uint8)),
+        "ranks out of range": np.where(want_sel >= 0, want_sel + 100000, -5).astype(np.int32),
+    }
+    hits = {}
+    for name, rec in records.items():
+        b.reset()
+        _hinted_step(b, torch.from_numpy(rec).to(dev))
+        got = b.outputs()
+        rep = check_against_oracle(wl, got, ref, refc, pack_align=pack_align)
+        assert all(v == 0 for v in rep.values()), (name, rep)
+        assert np.array_equal(got["sel"], want_sel), name
+        constrained = np.concatenate([np.arange(l.group_base, l.group_base + l.groups) for l in wl.layers
+                                      if l.mode != wk.MODE_NONE])
+        hits[name] = float(np.mean((rec[constrained] >= 0) == (want_sel[constrained] >= 0)))
+    assert hits["all right"] == 1.0 and hits["all wrong"] == 0.0 and 0.8 < hits["a tenth wrong"] < 1.0
+
+    # without a compaction: the projection's outputs alone
+    for name in ("all right", "a tenth wrong", "all wrong"):
+        b.reset()
+        _hinted_step(b, torch.from_numpy(records[name]).to(dev), compaction=False)
+        got = b.outputs()
+        for key in ("Z", "U", "Wbar"):
+            for l in wl.layers:
+                sl = slice(l.elem_off, l.elem_off + l.n)
+                assert np.array_equal(got[key][sl].view(np.uint32), ref[key][sl].view(np.uint32)), (name, key, l.name)
+        assert np.array_equal(got["mask"], ref["mask"]) and np.array_equal(got["sel"], want_sel)
+        assert np.all(np.isnan(got["packed"]))
+    b.plan.close()
+
+
+def test_rejects_a_record_that_overlaps_the_new_one_and_a_prediction_for_the_weighted_candidate():
+    wl = wk.custom_workload(SHAPES[:3], R=2, seed=5, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    b = _Bufs(wl, W, U, 1)
+    before = b.outputs()
+    rc = pkg.hsadmm_step(b.plan, b.W, U=b.U, Z=b.Z, mask=b.mask, sel=b.sel, sel_prev=b.sel, workspace=b.ws, check=False)
+    assert rc == -1
+    rc = pkg.hsadmm_step(b.plan, b.W, U=b.U, Z=b.Z, mask=b.mask, Zg=b.Z, Vd=b.dst, sel_prev=b.sel, workspace=b.ws,
+                         check=False)
+    assert rc == -4
+    after = b.outputs()
+    for k in before:
+        assert np.array_equal(before[k], after[k], equal_nan=True), k       # nothing was enqueued
+    b.plan.close()
+
+
+@pytest.mark.parametrize("R", [1, 4, 5])
+def test_outer_iterations_predicted_by_the_previous_selection(R):
+    """Algorithm 1's flow: every outer iteration is predicted by the selection of the one before (the first by the
+    all-ones mask the algorithm starts from), U carried in place, replicas changing between iterations so that
+    supports do change.  Every iteration matches the oracle bit for bit, and both kinds of wrong prediction occur."""
+    shapes = [(96, 16, 1, wk.MODE_FILTER, 40), (80, 64, 9, wk.MODE_FILTER, 30), (40, 256, 9, wk.MODE_FILTER, 16),
+              (24, 512, 9, wk.MODE_FILTER, 9), (64, 3, 49, wk.MODE_FILTER, 20), (96, 128, 1, wk.MODE_CHANNEL, 50),
+              (10, 128, 1, wk.MODE_NONE, 10)]
+    wl = wk.custom_workload(shapes, R=R, seed=1, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    U[:] = 0                                    # Algorithm 1 starts from u = 0
+    t = wl.table()
+    b = _Bufs(wl, W, U, 1)
+    dev = b.U.device
+    records = [torch.from_numpy(record_of(wl, np.ones(b.plan.groups_total, np.uint8))).to(dev),
+               torch.full((b.plan.groups_total,), -7, dtype=torch.int32, device=dev)]
+    Uref = U.copy()
+    prev_mask = np.ones(b.plan.groups_total, np.uint8)
+    came_back = dropped_out = unchanged_layers = 0
+    for it, seed in enumerate([1, 1, 2, 2, 2, 3, 1, 1]):
+        wl.seed = seed
+        Wn, _ = wk.generate(wl)
+        for r in range(wl.R):
+            b.W[r].copy_(torch.from_numpy(Wn[r]))
+        ref = oracle.project(t, Wn, Uref)
+        refc = oracle.compact(t, ref["Z"], ref["mask"])
+        prev, new = records[it % 2], records[(it + 1) % 2]
+        pkg.hsadmm_step(b.plan, b.W, U=b.U, Z=b.Z, mask=b.mask, sel_prev=prev, sel=new, packed=b.packed,
+                        layer_off=b.off, kept_idx=b.kept, workspace=b.ws)
+        pkg.hsadmm_expand(b.plan, b.packed, None, b.dst, b.ws)
+        got = b.outputs()
+        assert np.array_equal(got["mask"], ref["mask"]), "iteration %d" % it
+        assert np.array_equal(got["Z"].view(np.uint32), ref["Z"].view(np.uint32)), "iteration %d" % it
+        assert np.array_equal(got["U"].view(np.uint32), ref["U"].view(np.uint32)), "iteration %d" % it
+        assert np.array_equal(got["layer_off"], refc["layer_off"])
+        n_packed = int(refc["layer_off"][-1])
+        assert np.array_equal(got["packed"][:n_packed].view(np.uint32), refc["packed"].view(np.uint32)), "iteration %d" % it
+        assert np.array_equal(got["kept_idx"][:refc["kept_idx"].size], refc["kept_idx"])
+        for l in wl.layers:
+            sl = slice(l.elem_off, l.elem_off + l.n)
+            assert np.array_equal(got["dst"][sl].view(np.uint32), ref["Z"][sl].view(np.uint32))
+        assert np.array_equal(new.cpu().numpy(), record_of(wl, ref["mask"]))
+        came_back += int(np.sum((prev_mask == 0) & (ref["mask"] == 1)))
+        dropped_out += int(np.sum((prev_mask == 1) & (ref["mask"] == 0)))
+        for l in wl.layers:
+            if l.mode == wk.MODE_FILTER and it > 0:
+                sl = slice(l.group_base, l.group_base + l.groups)
+                unchanged_layers += int(np.array_equal(prev_mask[sl], ref["mask"][sl]))
+        prev_mask = ref["mask"]
+        Uref = ref["U"]
+    assert came_back > 0 and dropped_out > 0
+    b.plan.close()
+
+
+def test_the_one_entry_point_equals_the_named_calls_in_every_form():
+    """hsadmm_step with the fields of a named call gives that call's outputs, bit for bit: plain / weighted candidate,
+    selected / frozen support, with and without the shrinkage, with the residual norms; the weights of Eq. (9) come
+    from the `coef` argument in one run and from the plan in the other."""
+    rng = np.random.default_rng(3)
+    wl = wk.custom_workload(SHAPES, R=4, seed=31, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    L = len(wl.layers)
+    a, bb = pkg.hsadmm_node_coefficients(rng.uniform(1e-3, 2e-3, L), rng.uniform(1e-4, 3e-4, L), 1e-4, 16, wl.R)
+    dev = torch.device("cuda:0")
+    Zg = torch.from_numpy(rng.standard_normal(wl.n_arena).astype(np.float32) * 0.05).to(dev)
+    Vd = torch.from_numpy(rng.standard_normal(wl.n_arena).astype(np.float32) * 0.01).to(dev)
+    coef = torch.from_numpy(np.stack([a, bb], axis=1).astype(np.float32).reshape(-1).copy()).to(dev)
+    frozen = torch.from_numpy((rng.random(wl.groups_total) < 0.6).astype(np.uint8)).to(dev)
+    x, y = _Bufs(wl, W, U, 1), _Bufs(wl, W, U, 1)
+    pkg.hsadmm_plan_set_node_weights(x.plan, a, bb)          # y's plan keeps a = 1, b = 0: it must use `coef`
+    res_x = torch.zeros(4 * L, dtype=torch.float64, device=dev)
+    res_y = torch.zeros(4 * L, dtype=torch.float64, device=dev)
+    pk = lambda b: dict(packed=b.packed, layer_off=b.off, kept_idx=b.kept)        # noqa: E731
+    forms = [
+        ("project",
+         lambda: pkg.hsadmm_project(x.plan, x.W, x.U, x.Z, x.Wbar, x.mask, x.key, x.ws),
+         lambda: pkg.hsadmm_step(y.plan, y.W, U=y.U, Z=y.Z, Wbar=y.Wbar, mask=y.mask, sqnorm=y.key, workspace=y.ws)),
+        ("project_compact",
+         lambda: pkg.hsadmm_project_compact(x.plan, x.W, x.U, x.Z, x.Wbar, x.mask, x.key, x.packed, x.off, x.kept, x.ws),
+         lambda: pkg.hsadmm_step(y.plan, y.W, U=y.U, Z=y.Z, Wbar=y.Wbar, mask=y.mask, sqnorm=y.key, workspace=y.ws,
+                                 **pk(y))),
+        ("project_weighted",
+         lambda: pkg.hsadmm_project_weighted(x.plan, x.W, x.U, Zg, Vd, x.Z, x.Wbar, x.mask, x.key, x.ws),
+         lambda: pkg.hsadmm_step(y.plan, y.W, U=y.U, Zg=Zg, Vd=Vd, coef=coef, Z=y.Z, Wbar=y.Wbar, mask=y.mask,
+                                 sqnorm=y.key, workspace=y.ws)),
+        ("project_weighted_compact",
+         lambda: pkg.hsadmm_project_weighted_compact(x.plan, x.W, x.U, Zg, Vd, x.Z, x.Wbar, x.mask, x.key, x.packed,
+                                                     x.off, x.kept, x.ws),
+         lambda: pkg.hsadmm_step(y.plan, y.W, U=y.U, Zg=Zg, Vd=Vd, coef=coef, Z=y.Z, Wbar=y.Wbar, mask=y.mask,
+                                 sqnorm=y.key, workspace=y.ws, **pk(y))),
+        ("project_frozen",
+         lambda: pkg.hsadmm_project_frozen(x.plan, x.W, x.U, x.Z, x.Wbar, frozen),
+         lambda: pkg.hsadmm_step(y.plan, y.W, U=y.U, Z=y.Z, Wbar=y.Wbar, mask_frozen=frozen)),
+        ("project_frozen_compact",
+         lambda: pkg.hsadmm_project_frozen_compact(x.plan, x.W, x.U, x.Z, x.Wbar, frozen, False, x.packed, x.off,
+                                                   x.kept, x.ws),
+         lambda: pkg.hsadmm_step(y.plan, y.W, U=y.U, Z=y.Z, Wbar=y.Wbar, mask_frozen=frozen, workspace=y.ws, **pk(y))),
+        ("project_weighted_frozen",
+         lambda: pkg.hsadmm_project_weighted_frozen(x.plan, x.W, x.U, Zg, Vd, x.Z, x.Wbar, frozen),
+         lambda: pkg.hsadmm_step(y.plan, y.W, U=y.U, Zg=Zg, Vd=Vd, coef=coef, Z=y.Z, Wbar=y.Wbar, mask_frozen=frozen)),
+        ("project_weighted_frozen_compact",
+         lambda: pkg.hsadmm_project_weighted_frozen_compact(x.plan, x.W, x.U, Zg, Vd, x.Z, x.Wbar, frozen, False,
+                                                            x.packed, x.off, x.kept, x.ws),
+         lambda: pkg.hsadmm_step(y.plan, y.W, U=y.U, Zg=Zg, Vd=Vd, coef=coef, Z=y.Z, Wbar=y.Wbar, mask_frozen=frozen,
+                                 workspace=y.ws, **pk(y))),
+        ("retrain_project",
+         lambda: pkg.hsadmm_retrain_project(x.plan, x.W, x.U, Zg, Vd, x.Z, x.Wbar, frozen, False, x.packed, x.off,
+                                            x.kept, res_x, x.ws),
+         lambda: pkg.hsadmm_step(y.plan, y.W, U=y.U, Zg=Zg, Vd=Vd, coef=coef, Z=y.Z, Wbar=y.Wbar, mask_frozen=frozen,
+                                 residuals=res_y, workspace=y.ws, **pk(y))),
+    ]
+    for name, named, through_step in forms:
+        x.reset()
+        y.reset()
+        if name == "retrain_project":         # Z is in/out there: the previous z_i
+            x.Z.copy_(Zg)
+            y.Z.copy_(Zg)
+        named()
+        through_step()
+        gx, gy = x.outputs(), y.outputs()
+        for key in gx:
+            if key == "sel":
+                continue
+            assert np.array_equal(gx[key].view(np.uint8), gy[key].view(np.uint8)), (name, key)
+        assert np.array_equal(res_x.cpu().numpy(), res_y.cpu().numpy()), name
+    # what the structure cannot express is refused, not guessed
+    assert pkg.hsadmm_step(y.plan, y.W, U=y.U, Z=y.Z, mask=y.mask, coef=coef, workspace=y.ws, check=False) == -1
+    assert pkg.hsadmm_step(y.plan, y.W, U=y.U, Z=y.Z, mask=y.mask, mask_frozen=frozen, check=False) == -1
+    assert pkg.hsadmm_step(y.plan, y.W, U=y.U, Z=y.Z, mask=y.mask, residuals=res_y, workspace=y.ws, check=False) == -4
+    assert pkg.hsadmm_step(y.plan, y.W, U=y.U, Z=y.Z, mask=y.mask, packed=y.packed, workspace=y.ws, check=False) == -1
+    x.plan.close()
+    y.plan.close()
