@@ -30,6 +30,17 @@ HBM_PEAK_GBPS = 8000.0
 METRIC = "H-SADMM project+compact GB/s (fraction of HBM peak) + params/s, ResNet-50 fp32"
 
 
+def kernel_source_digest():
+    """sha256 over the HIP sources and the header the library is built from (what a counter summary is tied to)."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2512_14628_amd", "csrc")
+    for fn in sorted(os.listdir(csrc)) + [os.path.join(ROOT, "include", "hsadmm.h")]:
+        with open(fn if os.path.isabs(fn) else os.path.join(csrc, fn), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,10 +63,15 @@ def main():
                     help="time the base step only (no frozen-mask, weighted, residual and composite sections): "
                          "the form the rocprofv3 summaries under profiles/ are taken with")
     ap.add_argument("--no-hinted", action="store_true", help="skip the step under a predicted selection")
+    ap.add_argument("--print-source-digest", action="store_true",
+                    help="print the digest of the kernel sources (what profiles/ summaries record) and exit")
     ap.add_argument("--sets", type=int, default=3,
                     help="independent copies of every buffer the steps rotate over, so that no step finds "
                          "its own data from the previous step in the caches")
     args = ap.parse_args()
+    if args.print_source_digest:
+        print(kernel_source_digest())
+        return
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path has no collectives); "
@@ -275,6 +291,19 @@ def main():
 
     per_step = timed_us(step, args.steps)
     step_stats = {"median_us": round(per_step[len(per_step) // 2], 2), "min_us": round(per_step[0], 2)}
+    # A workload whose rotating buffers all fit the 256 MB memory-side cache never reaches HBM, and a step shorter
+    # than the host needs to enqueue it is timed by the enqueue, not by the device: for such workloads `value` is
+    # taken from the median of the per-step events and labelled, instead of from the wall clock.
+    resident_bytes = nsets * (4 * n * (wl.R + 3) + 4 * wl.n_kept)
+    cache_resident = resident_bytes <= 256 * 2 ** 20
+    value_from = "wall clock over the timed region"
+    if cache_resident or per_step[len(per_step) // 2] < 60.0:
+        med_s = per_step[len(per_step) // 2] * 1e-6
+        gbps = bytes_["step"] / med_s / 1e9
+        params_per_s = wl.n_total / med_s
+        ms_per_step = 1e3 * med_s
+        value_from = "median of per-step HIP events (%s)" % (
+            "cache-resident workload: not an HBM figure" if cache_resident else "step shorter than its enqueue")
 
     def call_alone(which):
         def fn():
@@ -340,14 +369,34 @@ def main():
                 "traffic": None,
                 "algorithmic_bytes_per_launch": kernel_bytes.get(dom, 0),
                 "avg_launch_us": round(dom_us, 2) if dom_us else None}
-    # HBM-side bytes per launch of that kernel, from the committed rocprofv3 --pmc summary (two counter runs)
+    # HBM-side bytes per launch of that kernel: measured by rocprofv3 --pmc (two counter runs), not by this run, and
+    # kept as text under profiles/.  The summary names the commit and the digest of the kernel sources it was taken
+    # on and the kernel's grid; the figure is only quoted when both still describe what has just been timed.
+    grids = pkg.hsadmm_kernel_grids(plan)
     traffic_file = os.path.join(ROOT, "profiles", "%s_step_hbm_traffic.md" % args.workload)
+    prof = {"traffic": {}, "grid": {}, "commit": None, "source_sha256": None}
     if os.path.exists(traffic_file):
         with open(traffic_file) as f:
             for line in f:
                 parts = line.split()
-                if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == dom:
-                    roofline["traffic"] = int(parts[2])
+                if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch":
+                    prof["traffic"][parts[1]] = int(parts[2])
+                elif len(parts) == 3 and parts[0] == "grid_workgroups":
+                    prof["grid"][parts[1]] = int(parts[2])
+                elif len(parts) == 2 and parts[0] in ("commit", "source_sha256"):
+                    prof[parts[0]] = parts[1]
+    roofline["traffic_commit"] = prof["commit"]
+    if dom not in prof["traffic"]:
+        roofline["traffic_note"] = "no committed counter summary for this kernel and workload"
+    elif prof["source_sha256"] != kernel_source_digest():
+        roofline["traffic_note"] = "kernel sources changed since the counter summary was taken: figure withheld"
+    elif prof["grid"].get(dom) != grids.get(dom):
+        roofline["traffic_note"] = "the summary's grid (%s workgroups) is not this plan's (%s): figure withheld" % (
+            prof["grid"].get(dom), grids.get(dom))
+    else:
+        roofline["traffic"] = prof["traffic"][dom]
+        roofline["traffic_note"] = "rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, profiles/%s" % os.path.basename(traffic_file)
+    roofline["grid_workgroups"] = grids.get(dom)
 
     frozen = weighted = residuals = composite = retrain = retrain_res = None
     if not args.skip_extras:
@@ -674,7 +723,8 @@ def main():
                    "buffer_sets_rotated": nsets, "expand_reuses_cached_index_mappings": not args.expand_rescan,
                    "compact_reuses_the_selections_index_mappings": not args.compact_rescan,
                    "project_and_compact_in_one_call": one_call,
-                   "algorithmic_bytes_per_step": bytes_["step"]},
+                   "algorithmic_bytes_per_step": bytes_["step"], "cache_resident": cache_resident,
+                   "value_from": value_from},
         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
         "params_per_s": round(params_per_s, 1),
         "step_us": step_stats,

@@ -39,7 +39,8 @@
  * library owns only the plan (host tables plus a device copy, allocated in
  * hsadmm_plan_create on the current device and released in
  * hsadmm_plan_destroy).  Apart from plan creation / destruction and
- * hsadmm_plan_set_node_weights, no call allocates or frees memory or
+ * hsadmm_plan_set_node_weights (a synchronous copy into the plan; the `coef`
+ * field of hsadmm_step avoids it), no call allocates or frees memory or
  * synchronises the device; each enqueues all its work on `hip_stream`
  * (a hipStream_t passed as void*; NULL is the default stream), so a sequence
  * of calls can be captured into a HIP graph.  Outputs are
@@ -56,7 +57,8 @@
  * are validated before anything is enqueued, so a call that returns an
  * argument error has had no effect on device memory.  No exceptions cross
  * the boundary.  Calls on one plan from several host threads are safe when
- * each uses its own workspace.
+ * each uses its own workspace (with the per-kernel timing diagnostics on, see
+ * hsadmm_kernel_timing_enable for what is and is not).
  *
  * Preconditions that are not checked: all input values are finite; buffers
  * do not alias except where stated.
@@ -656,13 +658,20 @@ int hsadmm_version(void);
  * launches are recorded between two reads; later launches run untimed.
  * hsadmm_kernel_timing_read waits for the recorded kernels, returns for every
  * kernel id 0..HSADMM_KERNEL_COUNT-1 the summed duration in milliseconds and
- * the number of launches, and clears the record.  While timing is enabled
- * the plan must be used from one host thread only.  Off by default.
- * Errors: INVALID_ARGUMENT, HIP.
+ * the number of launches, and clears the record.  This record is the only
+ * part of a plan that changes after its creation: launches made from several
+ * host threads claim their event pairs atomically, but enabling and reading
+ * must not run while another thread is inside a call on this plan.  Off by
+ * default.
+ * hsadmm_kernel_grid returns the number of workgroups of the latest timed
+ * launch of a kernel on this plan (0 if none was timed yet), so that a
+ * profile taken elsewhere can be matched to the plan it is quoted for.
+ * Errors: INVALID_ARGUMENT, HOST_MEMORY, HIP.
  */
 #define HSADMM_KERNEL_COUNT 26
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
+int hsadmm_kernel_grid(const hsadmm_plan_t* plan, int kernel_id);
 /* Name of a kernel id ("" when out of range). */
 const char* hsadmm_kernel_name(int kernel_id);
 

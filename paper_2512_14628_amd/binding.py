@@ -36,7 +36,7 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_project_weighted_frozen", "hsadmm_project_weighted_frozen_compact",
            "hsadmm_retrain_project", "hsadmm_retrain_expand",
            "hsadmm_adapt_penalties", "hsadmm_scale_layers", "hsadmm_project_compact_static",
-           "hsadmm_step", "hsadmm_selection_from_mask")
+           "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid")
 KERNEL_COUNT = 26
 
 
@@ -184,6 +184,8 @@ def load_library():
     lib.hsadmm_kernel_timing_enable.restype = ctypes.c_int
     lib.hsadmm_kernel_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.hsadmm_kernel_timing_read.restype = ctypes.c_int
+    lib.hsadmm_kernel_grid.argtypes = [vp, ctypes.c_int]
+    lib.hsadmm_kernel_grid.restype = ctypes.c_int
     lib.hsadmm_kernel_name.argtypes = [ctypes.c_int]
     lib.hsadmm_kernel_name.restype = ctypes.c_char_p
     _lib = lib
@@ -287,6 +289,12 @@ def hsadmm_kernel_timing_read(plan: Plan):
     return {lib.hsadmm_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(KERNEL_COUNT)}
 
 
+def hsadmm_kernel_grids(plan: Plan):
+    """{kernel name: workgroups of its latest timed launch on this plan} (0: not launched with timing on)."""
+    lib = load_library()
+    return {lib.hsadmm_kernel_name(i).decode(): int(lib.hsadmm_kernel_grid(plan.handle, i)) for i in range(KERNEL_COUNT)}
+
+
 def hsadmm_project(plan: Plan, W_replicas: Sequence, U, Z, Wbar, mask, sqnorm, workspace,
                    stream=None, workspace_bytes: Optional[int] = None, check: bool = True) -> int:
     lib = load_library()
@@ -325,7 +333,7 @@ def hsadmm_project_compact_static(plan: Plan, W_replicas: Sequence, U, Z, Wbar, 
                                            _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_project_compact_static",
-           "hsadmm_step", "hsadmm_selection_from_mask")
+           "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid")
     return rc
 
 

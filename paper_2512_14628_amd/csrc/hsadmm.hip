@@ -53,6 +53,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -142,11 +143,14 @@ struct hsadmm_plan {
     float* d_coef = nullptr;             // 2L: a_l, b_l of Eq. (9), set by hsadmm_plan_set_node_weights (default 1, 0)
     void* static_ws = nullptr;           // device address of `scratch` on the plan's device
     uint16_t* d_chunk_layer = nullptr;   // per 16 groups: their segment if all 16 lie in one constrained segment, else 0xffff
-    // Optional per-kernel timing (diagnostics; off by default).  Not thread-safe.
+    // Optional per-kernel timing (diagnostics; off by default): the only state of a plan that changes after its
+    // creation.  Launches from several host threads claim their event pairs through the atomic counter; enabling
+    // and reading are for one thread at a time, with no launch of this plan in flight on another.
     bool timing = false;
     std::vector<hipEvent_t> ev;      // pairs: start, stop
     std::vector<int> ev_kernel;      // kernel id of each recorded pair
-    size_t ev_used = 0;              // pairs recorded since the last read
+    std::atomic<size_t> ev_used{0};  // pairs claimed since the last read (may run past kTimingPairs: those launches go untimed)
+    std::atomic<unsigned> last_grid[HSADMM_KERNEL_COUNT] = {};   // workgroups of the latest timed launch of every kernel
 };
 
 namespace {
@@ -238,9 +242,11 @@ hipError_t launch(const hsadmm_plan* cp, int kid, void (*kernel)(KArgs...), unsi
                   hipStream_t s, Args... args)
 {
     hsadmm_plan* p = const_cast<hsadmm_plan*>(cp);
-    if (p->timing && p->ev_used < kTimingPairs) {
-        const size_t i = p->ev_used++;
+    size_t i = kTimingPairs;
+    if (p->timing) i = p->ev_used.fetch_add(1, std::memory_order_relaxed);
+    if (i < kTimingPairs) {
         p->ev_kernel[i] = kid;
+        p->last_grid[kid].store(grid, std::memory_order_relaxed);
         hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, s, p->ev[2 * i], p->ev[2 * i + 1], 0, args...);
     } else {
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, s, args...);
@@ -1320,7 +1326,7 @@ int hsadmm_kernel_timing_enable(hsadmm_plan_t* p, int enable)
         }
     }
     p->timing = enable != 0 && p->ev.size() == 2 * kTimingPairs;
-    p->ev_used = 0;
+    p->ev_used.store(0);
     return HSADMM_OK;
 }
 
@@ -1328,15 +1334,22 @@ int hsadmm_kernel_timing_read(hsadmm_plan_t* p, double* total_ms, int64_t* launc
 {
     if (!p || !total_ms || !launches) return HSADMM_ERR_INVALID_ARGUMENT;
     for (int k = 0; k < kKernelCount; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
-    for (size_t i = 0; i < p->ev_used; ++i) {
+    const size_t used = std::min(p->ev_used.load(), kTimingPairs);
+    for (size_t i = 0; i < used; ++i) {
         if (hipEventSynchronize(p->ev[2 * i + 1]) != hipSuccess) return HSADMM_ERR_HIP;
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, p->ev[2 * i], p->ev[2 * i + 1]) != hipSuccess) return HSADMM_ERR_HIP;
         total_ms[p->ev_kernel[i]] += (double)ms;
         launches[p->ev_kernel[i]] += 1;
     }
-    p->ev_used = 0;
+    p->ev_used.store(0);
     return HSADMM_OK;
+}
+
+int hsadmm_kernel_grid(const hsadmm_plan_t* p, int kernel_id)
+{
+    if (!p || kernel_id < 0 || kernel_id >= kKernelCount) return HSADMM_ERR_INVALID_ARGUMENT;
+    return (int)p->last_grid[kernel_id].load(std::memory_order_relaxed);
 }
 
 const char* hsadmm_kernel_name(int kernel_id)
