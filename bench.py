@@ -201,7 +201,7 @@ def main():
     #      is then predicted by its own recorded selection with the given fraction of every layer's kept groups
     #      exchanged for pruned ones (1.0: a support that has settled; 0.9: a tenth of it still moving).
     hinted = None
-    if one_call and not args.no_hinted:
+    if one_call and not args.no_hinted and any(l.mode == wk.MODE_FILTER for l in wl.layers):
         hsteps = max(1, args.steps // 2)
         hwarm = max(3, args.warmup // 2)
         T = hwarm + 2 * hsteps
@@ -214,11 +214,21 @@ def main():
                 b.U.copy_(dU0)
             counter[0] = 0
 
+        ping_pong = [False]
+        for b in sets:
+            b.U2 = torch.zeros_like(b.U)
+
         def hstep(sel_prev, sel_out):
             b = sets[counter[0] % nsets]
             counter[0] += 1
-            pkg.hsadmm_step(plan, b.W, U=b.U, Z=b.Z, mask=b.mask, sel_prev=sel_prev, sel=sel_out, packed=b.packed,
-                            layer_off=b.off, kept_idx=b.kept, workspace=b.ws, stream=stream)
+            if ping_pong[0]:
+                # the dual alternates between two buffers (U_out): nothing is stashed, nothing zero-filled afterwards
+                pkg.hsadmm_step(plan, b.W, U=b.U, U_out=b.U2, Z=b.Z, mask=b.mask, sel_prev=sel_prev, sel=sel_out,
+                                packed=b.packed, layer_off=b.off, kept_idx=b.kept, workspace=b.ws, stream=stream)
+                b.U, b.U2 = b.U2, b.U
+            else:
+                pkg.hsadmm_step(plan, b.W, U=b.U, Z=b.Z, mask=b.mask, sel_prev=sel_prev, sel=sel_out, packed=b.packed,
+                                layer_off=b.off, kept_idx=b.kept, workspace=b.ws, stream=stream)
             pkg.hsadmm_expand(plan, b.packed, None, b.dst, b.ws, stream=stream)
 
         reset_duals()
@@ -232,7 +242,8 @@ def main():
         hinted = {"what": "hsadmm_step(sel_prev = the step's own selection recorded beforehand, degraded to the hit "
                           "rate) + hsadmm_expand; same outputs and algorithmic bytes as the step `value` times",
                   "steps": hsteps}
-        for rate in (1.0, 0.9):
+        for rate, two_duals in ((1.0, False), (0.9, False), (1.0, True), (0.9, True)):
+            ping_pong[0] = two_duals
             hints_host = recs_host.copy()
             if rate < 1.0:
                 for t in range(T):
@@ -267,7 +278,7 @@ def main():
             pkg.hsadmm_kernel_timing_enable(plan, False)
             # the last step of the sequence must have made the selection the untimed pass recorded for it
             same = bool(torch.equal(sel_scratch, recs[T - 1]))
-            hinted["hit_rate_%.2f" % rate] = {
+            hinted["hit_rate_%.2f%s" % (rate, "_dual_out_of_place" if two_duals else "")] = {
                 "hit_rate": round(hit, 4), "ms_per_step": round(1e3 * h_elapsed, 4),
                 "value_GBps": round(bytes_["step"] / h_elapsed / 1e9, 1),
                 "hbm_frac": round(bytes_["step"] / h_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
@@ -276,8 +287,11 @@ def main():
             if not same:
                 print("bench.py: a predicted step selected another support than the unpredicted one", file=sys.stderr)
                 sys.exit(4)
+        ping_pong[0] = False
         reset_duals()
         del recs, hints
+        for b in sets:
+            del b.U2
 
     # ---- distribution over steps (median, min) and every call timed alone: HIP events on the stream the calls use
     def timed_us(fn, reps):

@@ -577,7 +577,12 @@ int hsadmm_retrain_expand(const hsadmm_plan_t* plan, const float* packed, const 
  * named calls: arenas 16 bytes, sqnorm / layer_off / residuals 8, others 4):
  *   struct_bytes     sizeof(hsadmm_step_args_t) as the caller was compiled (INVALID_ARGUMENT if it differs)
  *   W_replicas, R    HOST array of R device arenas
- *   U                in/out
+ *   U                in/out; with U_out given, in only
+ *   U_out            out, optional, plain candidate and selected support only (UNSUPPORTED otherwise): the
+ *                    updated dual goes here and U is left as it was (a full-layout arena that overlaps neither U
+ *                    nor Z; arena padding is not written).  Under a prediction (sel_prev) the old dual then stays
+ *                    readable, so rows predicted pruned are written in their final form at once (no zero fill
+ *                    after the selection) and a wrong prediction is repaired from the replicas and the old dual.
  *   Zg, Vd           in: global consensus z and the node's inter-node dual v_i
  *   coef             in, 2L floats a_0, b_0, a_1, b_1, ... (hsadmm_node_coefficients gives a and b); NULL with Zg
  *                    given: the weights stored in the plan.  Read by the kernels when they run, so a captured
@@ -610,6 +615,7 @@ typedef struct {
     int32_t R;
     int32_t mappings_cached;
     float* U;
+    float* U_out;
     const float* Zg;
     const float* Vd;
     const float* coef;

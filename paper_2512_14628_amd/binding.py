@@ -60,7 +60,7 @@ _STEP_FIELDS = (
     ("W_replicas", ctypes.POINTER(_vp), "replicas"),
     ("R", ctypes.c_int32, "replica_count"),
     ("mappings_cached", ctypes.c_int32, "flag"),
-    ("U", _vp, "dev"), ("Zg", _vp, "dev"), ("Vd", _vp, "dev"), ("coef", _vp, "dev"),
+    ("U", _vp, "dev"), ("U_out", _vp, "dev"), ("Zg", _vp, "dev"), ("Vd", _vp, "dev"), ("coef", _vp, "dev"),
     ("mask_frozen", _vp, "dev"), ("sel_prev", _vp, "dev"),
     ("Z", _vp, "dev"), ("Wbar", _vp, "dev"), ("mask", _vp, "dev"), ("sqnorm", _vp, "dev"), ("sel", _vp, "dev"),
     ("packed", _vp, "dev"), ("layer_off", _vp, "dev"), ("kept_idx", _vp, "dev"), ("residuals", _vp, "dev"),

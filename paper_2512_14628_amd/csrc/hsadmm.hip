@@ -308,7 +308,7 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
                           (const int32_t*)nullptr, 0, im, nL, (int)p->pack_align);
     if (e != hipSuccess || p->both_layers.empty()) return e;
     e = launch(p, kColsums, composite_colsums, (unsigned)p->items_both.size(), kBlock, s,
-               (const WorkItem*)p->d_items_both, (const float*)a.Z, (const float*)a.U, a.Zg, a.Vd, a.coef,
+               (const WorkItem*)p->d_items_both, (const float*)a.Z, a.Ur, a.Zg, a.Vd, a.coef,
                (const uint8_t*)mask, colpart);
     if (e != hipSuccess) return e;
     return launch(p, kTopk, select_topk, (unsigned)p->both_layers.size(), kScanBlock, s,
@@ -540,10 +540,12 @@ struct CompactOut {
 static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U, float* Z,
                         float* Wbar, uint8_t* mask, double* sqnorm, const CompactOut* out, void* workspace,
                         size_t workspace_bytes, void* hip_stream, const int32_t* sel_prev = nullptr,
-                        int32_t* sel_out = nullptr)
+                        int32_t* sel_out = nullptr, float* U_out = nullptr)
 {
     if (!p || !W_replicas || !U || !Z || !mask || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
-    if (!is_aligned(sel_prev, 4) || !is_aligned(sel_out, 4)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!is_aligned(sel_prev, 4) || !is_aligned(sel_out, 4) || !is_aligned(U_out, 16)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (U_out && (spans_overlap(U_out, U, p->arena_elems) || spans_overlap(U_out, Z, p->arena_elems)))
+        return HSADMM_ERR_INVALID_ARGUMENT;
     if (sel_prev && sel_out &&
         spans_overlap(reinterpret_cast<const float*>(sel_prev), reinterpret_cast<const float*>(sel_out), p->groups_total))
         return HSADMM_ERR_INVALID_ARGUMENT;         // the repair pass reads the old record beside the new one
@@ -562,7 +564,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     char* ws = static_cast<char*>(workspace);
     ProjectArgs a{};
     for (int r = 0; r < R; ++r) a.W[r] = W_replicas[r];
-    a.U = U; a.Z = Z; a.Wbar = Wbar;
+    a.Ur = U; a.U = U_out ? U_out : U; a.Z = Z; a.Wbar = Wbar;
     a.key = sqnorm ? sqnorm : reinterpret_cast<double*>(ws + p->ws.key);
     a.colpart = reinterpret_cast<double*>(ws + p->ws.colpart);
     a.inv_R = 1.0f / (float)R;
@@ -572,7 +574,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     // it expects to be kept (and every row of the unconstrained layers).
     const bool hinted = sel_prev != nullptr && !p->items_plain.empty();
     if (hinted) {
-        const HintArgs h{sel_prev, out ? out->packed : nullptr};
+        const HintArgs h{sel_prev, out ? out->packed : nullptr, U_out ? 0 : 1};
         e = for_replica_count<true>(R, [&](auto c) {
             return launch(p, kPass1Hinted, project_pass1_hinted<decltype(c)::value>, (unsigned)p->items_proj.size(),
                           kBlock, s, (const WorkItem*)p->d_items_proj, a, (int)R, h);
@@ -603,13 +605,16 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         const bool all_plain = out != nullptr;
         const unsigned n = (unsigned)(all_plain ? p->items_plain.size() : p->items_fix.size());
         if (n) {
-            e = launch(p, kHintedRepair, hinted_repair, n, kBlock, s,
-                       (const WorkItem*)(all_plain ? p->d_items_plain : p->d_items_fix), sel_prev, U, Z, po);
+            const HintArgs h{sel_prev, out ? out->packed : nullptr, U_out ? 0 : 1};
+            const WorkItem* items = all_plain ? p->d_items_plain : p->d_items_fix;
+            e = for_replica_count<true>(R, [&](auto c) {
+                return launch(p, kHintedRepair, hinted_repair<decltype(c)::value>, n, kBlock, s, items, a, (int)R, h, po);
+            });
             if (e != hipSuccess) return HSADMM_ERR_HIP;
         }
     } else if (!p->items_fix.empty() && !fuse) {
         e = launch(p, kFixup, project_fixup, (unsigned)p->items_fix.size(), kBlock, s,
-                   (const WorkItem*)p->d_items_fix, (const uint8_t*)mask, U, Z);
+                   (const WorkItem*)p->d_items_fix, (const uint8_t*)mask, a.U, Z);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
     // Without FILTER layers the gather of the plain rows (unconstrained layers) has no fix-up to share a launch
@@ -658,7 +663,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         const unsigned n_rows = (unsigned)p->items_plain.size();
         if (fuse)
             e = launch(p, kFixupGather, fixup_gather, (unsigned)p->items_fix.size() + n_rows, kBlock, s,
-                       (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), (const uint8_t*)mask, U, Z,
+                       (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), (const uint8_t*)mask, a.U, Z,
                        (const WorkItem*)p->d_items_plain, po.pos, po.cnt, po.kept_idx, po.n_layers, po.layer_off,
                        po.packed, po.co);
         else
@@ -708,7 +713,7 @@ int hsadmm_project_frozen(const hsadmm_plan_t* p, const float* const* W_replicas
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     ProjectArgs a{};
     for (int r = 0; r < R; ++r) a.W[r] = W_replicas[r];
-    a.U = U; a.Z = Z; a.Wbar = Wbar;
+    a.Ur = U; a.U = U; a.Z = Z; a.Wbar = Wbar;
     a.inv_R = 1.0f / (float)R;
     hipError_t e;
     e = for_replica_count<true>(R, [&](auto c) { return launch_frozen<decltype(c)::value>(p, a, R, mask, s); });
@@ -738,7 +743,7 @@ int hsadmm_project_frozen_compact(const hsadmm_plan_t* p, const float* const* W_
     }
     ProjectArgs a{};
     for (int r = 0; r < R; ++r) a.W[r] = W_replicas[r];
-    a.U = U; a.Z = Z; a.Wbar = Wbar;
+    a.Ur = U; a.U = U; a.Z = Z; a.Wbar = Wbar;
     a.inv_R = 1.0f / (float)R;
     PackOut po{};
     po.pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
@@ -940,7 +945,7 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     char* ws = static_cast<char*>(workspace);
     WeightedArgs w{};
     for (int r = 0; r < R; ++r) w.p.W[r] = W_replicas[r];
-    w.p.U = U; w.p.Z = Z; w.p.Wbar = Wbar;
+    w.p.Ur = U; w.p.U = U; w.p.Z = Z; w.p.Wbar = Wbar;
     w.p.key = sqnorm ? sqnorm : reinterpret_cast<double*>(ws + p->ws.key);
     w.p.colpart = reinterpret_cast<double*>(ws + p->ws.colpart);
     w.p.inv_R = 1.0f / (float)R;
@@ -1057,7 +1062,7 @@ static int weighted_frozen_impl(const hsadmm_plan_t* p, const float* const* W_re
     char* ws = static_cast<char*>(workspace);
     ProjectArgs a{};
     for (int r = 0; r < R; ++r) a.W[r] = W_replicas[r];
-    a.U = U; a.Z = Z; a.Wbar = Wbar;
+    a.Ur = U; a.U = U; a.Z = Z; a.Wbar = Wbar;
     a.inv_R = 1.0f / (float)R;
     a.Zg = Zg; a.Vd = Vd; a.coef = coef_arg ? coef_arg : p->d_coef;
     PackOut po{};
@@ -1136,6 +1141,7 @@ int hsadmm_step(const hsadmm_plan_t* p, const hsadmm_step_args_t* x)
     const bool pack = x->packed != nullptr || x->layer_off != nullptr || x->kept_idx != nullptr;
     if (!weighted && x->coef) return HSADMM_ERR_INVALID_ARGUMENT;        // weights without the terms they weigh
     const CompactOut out{x->packed, x->layer_off, x->kept_idx};         // (each impl wants all three or none)
+    if (x->U_out && (frozen || weighted)) return HSADMM_ERR_UNSUPPORTED;   // those passes update the dual in place
     if (frozen) {
         // retraining branch: the given mask replaces the selection; nothing is selected, predicted or recorded
         if (x->mask || x->sqnorm || x->sel_prev || x->sel) return HSADMM_ERR_INVALID_ARGUMENT;
@@ -1158,7 +1164,7 @@ int hsadmm_step(const hsadmm_plan_t* p, const hsadmm_step_args_t* x)
                                      x->sel);
     }
     return project_impl(p, x->W_replicas, x->R, x->U, x->Z, x->Wbar, x->mask, x->sqnorm, pack ? &out : nullptr,
-                        x->workspace, x->workspace_bytes, x->hip_stream, x->sel_prev, x->sel);
+                        x->workspace, x->workspace_bytes, x->hip_stream, x->sel_prev, x->sel, x->U_out);
 }
 
 int hsadmm_selection_from_mask(const hsadmm_plan_t* p, const uint8_t* mask, int32_t* sel, void* workspace,

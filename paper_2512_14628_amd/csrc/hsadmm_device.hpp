@@ -119,7 +119,8 @@ __device__ __forceinline__ bool item_vec(const WorkItem& it) { return (it.flags 
 
 struct ProjectArgs {
     const float* W[HSADMM_MAX_REPLICAS];
-    float* U;
+    const float* Ur;  // the dual as it is read ...
+    float* U;         // ... and where the updated dual goes (the same buffer unless the caller asked for another)
     float* Z;
     float* Wbar;      // may be null
     double* key;      // groups_total

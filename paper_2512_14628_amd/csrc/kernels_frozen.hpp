@@ -44,7 +44,7 @@ __device__ __forceinline__ v4f frozen4(const ProjectArgs& a, int Rrt, int64_t e,
     }
     v4f zprev = {0.f, 0.f, 0.f, 0.f};
     if (RES) zprev = ld4(a.Z + e);
-    const v4f u = ld4(a.U + e);
+    const v4f u = ld4(a.Ur + e);
     v4f v = wb + u;
     v4f vd = {0.f, 0.f, 0.f, 0.f};
     if (WEIGHTED) {
@@ -99,7 +99,7 @@ __device__ __forceinline__ void frozen4x2(const ProjectArgs& a, int Rrt, int64_t
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
     v4f zp0 = zero4, zp1 = zero4;
     if (RES) { zp0 = ld4(a.Z + e0); zp1 = ld4(a.Z + e1); }
-    const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
+    const v4f u0 = ld4(a.Ur + e0), u1 = ld4(a.Ur + e1);
     v4f v0 = wb0 + u0, v1 = wb1 + u1;
     v4f vd0 = zero4, vd1 = zero4;
     if (WEIGHTED && keep) {         // a pruned row needs neither z nor v
@@ -146,7 +146,7 @@ __device__ __forceinline__ float frozen1(const ProjectArgs& a, int Rrt, int64_t 
         for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
         wb = s * a.inv_R;
     }
-    const float u = ld1(a.U + e);
+    const float u = ld1(a.Ur + e);
     float v = wb + u;
     float vd = 0.f;
     if (WEIGHTED) {

@@ -33,7 +33,7 @@ struct Cand {
             s0 = s0 + w0;
             s1 = s1 + w1;
         }
-        const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
+        const v4f u0 = ld4(a.Ur + e0), u1 = ld4(a.Ur + e1);
         const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
         const v4f v0 = wb0 + u0, v1 = wb1 + u1;
         const v4f d0 = wb0 - v0, d1 = wb1 - v1;
@@ -51,7 +51,7 @@ struct Cand {
         v4f s = ld4(a.W[0] + e);
 #pragma unroll
         for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
-        const v4f u = ld4(a.U + e);
+        const v4f u = ld4(a.Ur + e);
         const v4f wb = s * a.inv_R;
         const v4f v = wb + u;
         const v4f d = wb - v;
@@ -60,12 +60,22 @@ struct Cand {
         if (a.Wbar) st4(a.Wbar + e, wb);
         return v;
     }
-    // HINTED forms: a previous selection predicts the row's fate.  The candidate goes to `vdst` and the dual of a
-    // kept group to `edst`: (Z, U) for a row predicted kept (final if it is kept again), (U, Z) for a row
-    // predicted pruned (U = V is final if it is pruned again, and Z holds the kept-form dual so that either
-    // outcome can be finished without the replicas).  `pk`, unless null, is the row's place in the packed buffer.
+    // HINTED forms: a previous selection predicts the row's fate (`kept`), and the row is written in the form that
+    // fate makes final.  Predicted kept: Z <- V, U <- U + (Wbar - V), as always.  Predicted pruned: U <- V, and
+    // Z <- the dual of a kept group when `stash` (the dual is updated in place and its old value is lost here: either
+    // outcome can then still be finished without the replicas), else Z <- +0 (the old dual stays readable in
+    // another buffer, so a wrong prediction is repaired from the inputs).  `pk`, unless null, is the row's place
+    // in the packed buffer.
+    static __device__ __forceinline__ void put_h(const ProjectArgs& a, int64_t e, const v4f& v, const v4f& dual_kept,
+                                                 bool kept, bool stash)
+    {
+        const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+        const v4f other = stash ? dual_kept : zero4;
+        st4(a.Z + e, kept ? v : other);
+        st4(a.U + e, kept ? dual_kept : v);
+    }
     static __device__ __forceinline__ double two_h(const ProjectArgs& a, int Rrt, int64_t base, int o0, int o1,
-                                                   float* vdst, float* edst, float* pk, double acc)
+                                                   bool kept, bool stash, float* pk, double acc)
     {
         const int RR = R > 0 ? R : Rrt;
         const int64_t e0 = base + o0, e1 = base + o1;
@@ -76,51 +86,49 @@ struct Cand {
             s0 = s0 + w0;
             s1 = s1 + w1;
         }
-        const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
+        const v4f u0 = ld4(a.Ur + e0), u1 = ld4(a.Ur + e1);
         const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
         const v4f v0 = wb0 + u0, v1 = wb1 + u1;
         const v4f d0 = wb0 - v0, d1 = wb1 - v1;
-        st4(vdst + e0, v0);
-        st4(vdst + e1, v1);
-        st4(edst + e0, u0 + d0);
-        st4(edst + e1, u1 + d1);
+        put_h(a, e0, v0, u0 + d0, kept, stash);
+        put_h(a, e1, v1, u1 + d1, kept, stash);
         if (pk) { st4u(pk + o0, v0); st4u(pk + o1, v1); }
         if (a.Wbar) { st4(a.Wbar + e0, wb0); st4(a.Wbar + e1, wb1); }
         acc = sq4(acc, v0);
         return sq4(acc, v1);
     }
-    static __device__ __forceinline__ v4f one_h(const ProjectArgs& a, int Rrt, int64_t base, int o, float* vdst,
-                                                float* edst, float* pk)
+    static __device__ __forceinline__ v4f one_h(const ProjectArgs& a, int Rrt, int64_t base, int o, bool kept,
+                                                bool stash, float* pk)
     {
         const int RR = R > 0 ? R : Rrt;
         const int64_t e = base + o;
         v4f s = ld4(a.W[0] + e);
 #pragma unroll
         for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
-        const v4f u = ld4(a.U + e);
+        const v4f u = ld4(a.Ur + e);
         const v4f wb = s * a.inv_R;
         const v4f v = wb + u;
         const v4f d = wb - v;
-        st4(vdst + e, v);
-        st4(edst + e, u + d);
+        put_h(a, e, v, u + d, kept, stash);
         if (pk) st4u(pk + o, v);
         if (a.Wbar) st4(a.Wbar + e, wb);
         return v;
     }
-    static __device__ __forceinline__ float scalar_h(const ProjectArgs& a, int Rrt, int64_t base, int o, float* vdst,
-                                                     float* edst, float* pk)
+    static __device__ __forceinline__ float scalar_h(const ProjectArgs& a, int Rrt, int64_t base, int o, bool kept,
+                                                     bool stash, float* pk)
     {
         const int RR = R > 0 ? R : Rrt;
         const int64_t e = base + o;
         float s = ld1(a.W[0] + e);
 #pragma unroll
         for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
-        const float u = ld1(a.U + e);
+        const float u = ld1(a.Ur + e);
         const float wb = s * a.inv_R;
         const float v = wb + u;
         const float d = wb - v;
-        st1(vdst + e, v);
-        st1(edst + e, u + d);
+        const float dual_kept = u + d;
+        st1(a.Z + e, kept ? v : (stash ? dual_kept : 0.f));
+        st1(a.U + e, kept ? dual_kept : v);
         if (pk) pk[o] = v;
         if (a.Wbar) st1(a.Wbar + e, wb);
         return v;
@@ -137,7 +145,7 @@ struct Cand {
             s0 = s0 + w0;
             s1 = s1 + w1;
         }
-        const v4f u0 = ld4(a.U + e0), u1 = ld4(a.U + e1);
+        const v4f u0 = ld4(a.Ur + e0), u1 = ld4(a.Ur + e1);
         const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
         st4(a.Z + e0, wb0);
         st4(a.Z + e1, wb1);
@@ -152,7 +160,7 @@ struct Cand {
         for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
         const v4f wb = s * a.inv_R;
         st4(a.Z + e, wb);
-        return wb + ld4(a.U + e);
+        return wb + ld4(a.Ur + e);
     }
     static __device__ __forceinline__ float park_scalar(const ProjectArgs& a, int Rrt, int64_t e)
     {
@@ -162,7 +170,7 @@ struct Cand {
         for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
         const float wb = s * a.inv_R;
         st1(a.Z + e, wb);
-        return wb + ld1(a.U + e);
+        return wb + ld1(a.Ur + e);
     }
     // the candidate alone; with park_mean the mean is parked in Z (CHANNEL layers: their outputs are written once
     // the mask is known, from the parked mean and U, so that the replicas are read once)
@@ -174,7 +182,7 @@ struct Cand {
         for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
         const v4f wb = s * a.inv_R;
         if (a.park_mean) st4(a.Z + e, wb);
-        return wb + ld4(a.U + e);
+        return wb + ld4(a.Ur + e);
     }
     static __device__ __forceinline__ float value1(const ProjectArgs& a, int Rrt, int64_t e)
     {
@@ -184,7 +192,7 @@ struct Cand {
         for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
         const float wb = s * a.inv_R;
         if (a.park_mean) st1(a.Z + e, wb);
-        return wb + ld1(a.U + e);
+        return wb + ld1(a.Ur + e);
     }
     static __device__ __forceinline__ float scalar(const ProjectArgs& a, int Rrt, int64_t e)
     {
@@ -192,7 +200,7 @@ struct Cand {
         float s = ld1(a.W[0] + e);
 #pragma unroll
         for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
-        const float u = ld1(a.U + e);
+        const float u = ld1(a.Ur + e);
         const float wb = s * a.inv_R;
         const float v = wb + u;
         const float d = wb - v;
@@ -342,24 +350,25 @@ __global__ __launch_bounds__(kBlock) void project_pass1(const WorkItem* __restri
 struct HintArgs {
     const int32_t* sel_prev;   // groups_total: the previous selection's record
     float* packed;             // packed buffer of this call's compaction, or null (no compaction)
+    int stash;                 // the dual is updated in place: rows predicted pruned keep the kept-form dual in Z
 };
 
-// pass1_row with the outputs of a row steered by its prediction (see Cand::two_h); the sum of squares is taken
-// in the same order as there, so the keys carry the same bits.
+// pass1_row with the outputs of a row written in the form its prediction makes final (see Cand::put_h); the sum of
+// squares is taken in the same order as there, so the keys carry the same bits.
 template <int R>
 __device__ __forceinline__ double pass1_row_hinted(const ProjectArgs& a, int Rrt, int64_t base, int row_len, bool vec,
-                                                   int j, int step, float* vdst, float* edst, float* pk)
+                                                   int j, int step, bool kept, bool stash, float* pk)
 {
     double acc = 0.0;
     if (vec) {
         const int nchunk = row_len >> 2;
         int c = j;
         for (; c + step < nchunk; c += 2 * step)
-            acc = Cand<R>::two_h(a, Rrt, base, c << 2, (c + step) << 2, vdst, edst, pk, acc);
-        if (c < nchunk) acc = sq4(acc, Cand<R>::one_h(a, Rrt, base, c << 2, vdst, edst, pk));
+            acc = Cand<R>::two_h(a, Rrt, base, c << 2, (c + step) << 2, kept, stash, pk, acc);
+        if (c < nchunk) acc = sq4(acc, Cand<R>::one_h(a, Rrt, base, c << 2, kept, stash, pk));
     } else {
         for (int c = j; c < row_len; c += step) {
-            const float v = Cand<R>::scalar_h(a, Rrt, base, c, vdst, edst, pk);
+            const float v = Cand<R>::scalar_h(a, Rrt, base, c, kept, stash, pk);
             acc = fma((double)v, (double)v, acc);
         }
     }
@@ -367,10 +376,10 @@ __device__ __forceinline__ double pass1_row_hinted(const ProjectArgs& a, int Rrt
 }
 
 // project_rows for FILTER / NONE row items under a predicted selection.  A row predicted kept is written as pass 1
-// always writes it (Z <- V, U <- U + (Wbar - V)) and, with a compaction to follow, also at its predicted rank in
-// the packed buffer; a row predicted pruned gets U <- V and, in Z, the kept-form dual.  The rows of an
-// unconstrained layer are always kept, at their own index.  A rank outside [0, k) cannot have come from a
-// selection of this plan: such a row is treated as kept and left for the repair pass to pack.
+// always writes it and, with a compaction to follow, also at its predicted rank in the packed buffer; a row
+// predicted pruned is written in its pruned form (see Cand::put_h).  The rows of an unconstrained layer are always
+// kept, at their own index.  A rank outside [0, k) cannot have come from a selection of this plan: such a row is
+// treated as kept and left for the repair pass to pack.
 template <int R>
 __device__ __forceinline__ void project_rows_hinted(const WorkItem& it, const ProjectArgs& a, int Rrt,
                                                     const HintArgs& h)
@@ -380,13 +389,12 @@ __device__ __forceinline__ void project_rows_hinted(const WorkItem& it, const Pr
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
     const bool unconstrained = item_mode(it) == HSADMM_MODE_NONE;
+    const bool stash = h.stash != 0;
     float* const pk_layer = h.packed ? h.packed + it.packed_off : nullptr;
-    auto targets = [&](int rr, float*& vdst, float*& edst, float*& pk) {
+    auto prediction = [&](int rr, bool& kept, float*& pk) {
         const int hp = unconstrained ? it.row0 + rr : h.sel_prev[it.g0 + rr];
-        const bool pred_kept = hp >= 0;
-        vdst = pred_kept ? a.Z : a.U;
-        edst = pred_kept ? a.U : a.Z;
-        pk = (pk_layer && pred_kept && hp < it.k) ? pk_layer + (int64_t)hp * row_len : nullptr;
+        kept = hp >= 0;
+        pk = (pk_layer && kept && hp < it.k) ? pk_layer + (int64_t)hp * row_len : nullptr;
     };
     if (it.lpr <= kWave) {
         const int lpr = it.lpr;
@@ -398,9 +406,10 @@ __device__ __forceinline__ void project_rows_hinted(const WorkItem& it, const Pr
             const bool active = rr < it.nr;
             double acc = 0.0;
             if (active) {
-                float *vdst, *edst, *pk;
-                targets(rr, vdst, edst, pk);
-                acc = pass1_row_hinted<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr, vdst, edst, pk);
+                bool kept;
+                float* pk;
+                prediction(rr, kept, pk);
+                acc = pass1_row_hinted<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr, kept, stash, pk);
             }
             acc = wave_xor_sum(acc, lpr);
             if (active && j == 0) a.key[it.g0 + rr] = acc;
@@ -408,10 +417,11 @@ __device__ __forceinline__ void project_rows_hinted(const WorkItem& it, const Pr
     } else {
         __shared__ double wsum[kWaves];
         for (int rr = 0; rr < it.nr; ++rr) {
-            float *vdst, *edst, *pk;
-            targets(rr, vdst, edst, pk);
+            bool kept;
+            float* pk;
+            prediction(rr, kept, pk);
             double acc = pass1_row_hinted<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, threadIdx.x, kBlock,
-                                             vdst, edst, pk);
+                                             kept, stash, pk);
             acc = wave_xor_sum(acc, kWave);
             if (lane == 0) wsum[wave] = acc;
             __syncthreads();
@@ -576,14 +586,16 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
 
 // After the selection every FILTER row goes from the form its prediction gave it to its final form, and the packed
 // buffer is completed (`packed`: the layer's segment, or null without a compaction):
-//   predicted pruned, pruned   Z <- +0 (a store only; U = V is final since pass 1)
-//   predicted pruned, kept     Z holds the kept-form dual and U the candidate: the two change places, and the
-//                              candidate goes to the packed row
+//   predicted pruned, pruned   stash: Z <- +0 (a store only; U = V is final since pass 1); else nothing to do
+//   predicted pruned, kept     stash: Z holds the kept-form dual and U the candidate: the two change places;
+//                              else the row is formed again from the replicas and the old dual, as pass 1 forms a
+//                              row predicted kept; either way the candidate also goes to the packed row
 //   predicted kept,   pruned   U <- V (held in Z), Z <- +0, as without a prediction
 //   predicted kept,   kept     final; copied to the packed buffer only if its rank has changed
-// sel_prev / pos: the previous and the new selection's ranks of the item's first row onwards.
-__device__ __forceinline__ void hinted_repair_rows(const WorkItem& it, const int32_t* __restrict__ sel_prev,
-                                                   const int32_t* __restrict__ pos, float* U, float* Z, float* packed)
+template <int R>
+__device__ __forceinline__ void hinted_repair_rows(const WorkItem& it, const ProjectArgs& a, int Rrt,
+                                                   const int32_t* __restrict__ sel_prev,
+                                                   const int32_t* __restrict__ pos, bool stash, float* packed)
 {
     const int row_len = it.row_len;
     const bool vec = item_vec(it);
@@ -593,6 +605,8 @@ __device__ __forceinline__ void hinted_repair_rows(const WorkItem& it, const int
     const int sub = threadIdx.x / lpr;
     const int j = threadIdx.x - sub * lpr;
     const int nchunk = row_len >> 2;
+    float* const U = a.U;
+    float* const Z = a.Z;
     for (int rr = sub; rr < it.nr; rr += rows_at_once) {
         const int hp = sel_prev[it.g0 + rr];
         const int pn = pos[it.g0 + rr];
@@ -604,6 +618,7 @@ __device__ __forceinline__ void hinted_repair_rows(const WorkItem& it, const int
             if (vec) for (int c = j; c < nchunk; c += lpr) st4u(pk + 4 * c, ld4(Z + base + 4 * c));
             else for (int c = j; c < row_len; c += lpr) pk[c] = ld1(Z + base + c);
         } else if (!pred_kept && !kept) {
+            if (!stash) continue;
             if (vec) for (int c = j; c < nchunk; c += lpr) st4(Z + base + 4 * c, zero4);
             else for (int c = j; c < row_len; c += lpr) st1(Z + base + c, 0.f);
         } else if (pred_kept) {
@@ -619,7 +634,7 @@ __device__ __forceinline__ void hinted_repair_rows(const WorkItem& it, const int
                     st1(Z + base + c, 0.f);
                 }
             }
-        } else {
+        } else if (stash) {
             if (vec) {
                 for (int c = j; c < nchunk; c += lpr) {
                     const int64_t e = base + 4 * c;
@@ -636,20 +651,24 @@ __device__ __forceinline__ void hinted_repair_rows(const WorkItem& it, const int
                     if (pk) pk[c] = v;
                 }
             }
+        } else {
+            // the same arithmetic on the same inputs as in pass 1, so the same bits (the keys are not taken again)
+            if (vec) for (int c = j; c < nchunk; c += lpr) (void)Cand<R>::one_h(a, Rrt, base, c << 2, true, false, pk);
+            else for (int c = j; c < row_len; c += lpr) (void)Cand<R>::scalar_h(a, Rrt, base, c, true, false, pk);
         }
     }
 }
 
 // Row items of the FILTER layers (and, with a compaction, of the unconstrained layers, whose rows pass 1 has
 // packed: only their offsets and kept lists are handed to the caller here).
-__global__ __launch_bounds__(kBlock) void hinted_repair(const WorkItem* __restrict__ items,
-                                                        const int32_t* __restrict__ sel_prev, float* U, float* Z,
-                                                        PackOut po)
+template <int R>
+__global__ __launch_bounds__(kBlock) void hinted_repair(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
+                                                        HintArgs h, PackOut po)
 {
     const WorkItem it = items[blockIdx.x];
     if (po.packed && it.row0 == 0) copy_out_layer(it.layer, po.cnt, po.kept_idx, po.n_layers, po.layer_off, po.co);
     if (item_mode(it) != HSADMM_MODE_FILTER) return;
-    hinted_repair_rows(it, sel_prev, po.pos, U, Z, po.packed ? po.packed + it.packed_off : nullptr);
+    hinted_repair_rows<R>(it, a, Rrt, h.sel_prev, po.pos, h.stash != 0, po.packed ? po.packed + it.packed_off : nullptr);
 }
 
 }  // namespace

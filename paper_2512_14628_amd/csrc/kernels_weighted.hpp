@@ -24,7 +24,7 @@ __device__ __forceinline__ void wcand4(const WeightedArgs& w, int Rrt, int64_t e
     v4f s = ld4(w.p.W[0] + e);
 #pragma unroll
     for (int r = 1; r < RR; ++r) s = s + ld4(w.p.W[r] + e);
-    u = ld4(w.p.U + e);
+    u = ld4(w.p.Ur + e);
     const v4f q = ld4(w.Zg + e) - ld4(w.Vd + e);
     wb = s * w.p.inv_R;
     const v4f t = wb + u;
@@ -46,8 +46,8 @@ __device__ __forceinline__ void wcand4x2(const WeightedArgs& w, int Rrt, int64_t
         s0 = s0 + x0;
         s1 = s1 + x1;
     }
-    u0 = ld4(w.p.U + e0);
-    u1 = ld4(w.p.U + e1);
+    u0 = ld4(w.p.Ur + e0);
+    u1 = ld4(w.p.Ur + e1);
     const v4f g0 = ld4(w.Zg + e0), g1 = ld4(w.Zg + e1);
     const v4f d0 = ld4(w.Vd + e0), d1 = ld4(w.Vd + e1);
     const v4f q0 = g0 - d0, q1 = g1 - d1;
@@ -68,7 +68,7 @@ __device__ __forceinline__ void wcand1(const WeightedArgs& w, int Rrt, int64_t e
     float s = ld1(w.p.W[0] + e);
 #pragma unroll
     for (int r = 1; r < RR; ++r) s = s + ld1(w.p.W[r] + e);
-    u = ld1(w.p.U + e);
+    u = ld1(w.p.Ur + e);
     const float q = ld1(w.Zg + e) - ld1(w.Vd + e);
     wb = s * w.p.inv_R;
     const float t = wb + u;

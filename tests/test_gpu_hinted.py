@@ -64,6 +64,8 @@ class _Bufs:
         self.W = [torch.from_numpy(np.ascontiguousarray(W[r])).to(dev) for r in range(W.shape[0])]
         self.U0 = torch.from_numpy(np.ascontiguousarray(U)).to(dev)
         self.U = self.U0.clone()
+        self.Uout = torch.full((n,), nan, dtype=torch.float32, device=dev)
+        self.out_of_place = False
         self.Z = torch.full((n,), nan, dtype=torch.float32, device=dev)
         self.Wbar = torch.full((n,), nan, dtype=torch.float32, device=dev)
         self.mask = torch.full((p.groups_total,), 7, dtype=torch.uint8, device=dev)
@@ -78,8 +80,9 @@ class _Bufs:
     def reset(self):
         self.U.copy_(self.U0)
         nan = float("nan")
-        for t in (self.Z, self.Wbar, self.packed, self.dst, self.key):
+        for t in (self.Z, self.Wbar, self.packed, self.dst, self.key, self.Uout):
             t.fill_(nan)
+        self.out_of_place = False
         self.mask.fill_(7)
         self.sel.fill_(-7)
         self.off.fill_(-1)
@@ -87,15 +90,22 @@ class _Bufs:
         self.ws.fill_(0xAB)
 
     def outputs(self):
+        """With the dual written out of place, "U" is the new buffer, checked to hold +NaN still outside the layers,
+        and the old one must be untouched."""
         torch.cuda.synchronize()
-        return {"U": self.U.cpu().numpy(), "Z": self.Z.cpu().numpy(), "mask": self.mask.cpu().numpy(),
+        if self.out_of_place:
+            assert torch.equal(self.U, self.U0), "the input dual was written"
+        return {"U": (self.Uout if self.out_of_place else self.U).cpu().numpy(), "Z": self.Z.cpu().numpy(), "mask": self.mask.cpu().numpy(),
                 "packed": self.packed.cpu().numpy(), "layer_off": self.off.cpu().numpy(),
                 "kept_idx": self.kept.cpu().numpy(), "dst": self.dst.cpu().numpy(), "Wbar": self.Wbar.cpu().numpy(),
                 "key": self.key.cpu().numpy(), "sel": self.sel.cpu().numpy()}
 
 
-def _hinted_step(b, sel_prev, compaction=True):
+def _hinted_step(b, sel_prev, compaction=True, out_of_place=False):
     extra = dict(packed=b.packed, layer_off=b.off, kept_idx=b.kept) if compaction else {}
+    if out_of_place:
+        extra["U_out"] = b.Uout
+        b.out_of_place = True
     pkg.hsadmm_step(b.plan, b.W, U=b.U, Z=b.Z, Wbar=b.Wbar, mask=b.mask, sqnorm=b.key, sel=b.sel, sel_prev=sel_prev,
                     workspace=b.ws, **extra)
     if compaction:
@@ -131,22 +141,32 @@ def test_any_prediction_gives_the_oracles_outputs(R, pack_align):
         "ranks out of range": np.where(want_sel >= 0, want_sel + 100000, -5).astype(np.int32),
     }
     hits = {}
+    records[None] = None                         # no prediction at all
     for name, rec in records.items():
-        b.reset()
-        _hinted_step(b, torch.from_numpy(rec).to(dev))
-        got = b.outputs()
-        rep = check_against_oracle(wl, got, ref, refc, pack_align=pack_align)
-        assert all(v == 0 for v in rep.values()), (name, rep)
-        assert np.array_equal(got["sel"], want_sel), name
+        for out_of_place in (False, True):
+            b.reset()
+            _hinted_step(b, None if rec is None else torch.from_numpy(rec).to(dev), out_of_place=out_of_place)
+            got = b.outputs()
+            rep = check_against_oracle(wl, got, ref, refc, pack_align=pack_align)
+            assert all(v == 0 for v in rep.values()), (name, out_of_place, rep)
+            assert np.array_equal(got["sel"], want_sel), (name, out_of_place)
+            pad = np.ones(wl.n_arena, bool)
+            for l in wl.layers:
+                pad[l.elem_off:l.elem_off + l.n] = False
+            assert np.all(np.isnan(got["Z"][pad]))
+            assert np.all(np.isnan(got["U"][pad])) if out_of_place else np.array_equal(got["U"][pad], U[pad])
+        if rec is None:
+            continue
         constrained = np.concatenate([np.arange(l.group_base, l.group_base + l.groups) for l in wl.layers
                                       if l.mode != wk.MODE_NONE])
         hits[name] = float(np.mean((rec[constrained] >= 0) == (want_sel[constrained] >= 0)))
     assert hits["all right"] == 1.0 and hits["all wrong"] == 0.0 and 0.8 < hits["a tenth wrong"] < 1.0
 
     # without a compaction: the projection's outputs alone
-    for name in ("all right", "a tenth wrong", "all wrong"):
+    for name, out_of_place in (("all right", False), ("a tenth wrong", False), ("all wrong", False),
+                               ("a tenth wrong", True), ("all wrong", True)):
         b.reset()
-        _hinted_step(b, torch.from_numpy(records[name]).to(dev), compaction=False)
+        _hinted_step(b, torch.from_numpy(records[name]).to(dev), compaction=False, out_of_place=out_of_place)
         got = b.outputs()
         for key in ("Z", "U", "Wbar"):
             for l in wl.layers:
@@ -167,14 +187,17 @@ def test_rejects_a_record_that_overlaps_the_new_one_and_a_prediction_for_the_wei
     rc = pkg.hsadmm_step(b.plan, b.W, U=b.U, Z=b.Z, mask=b.mask, Zg=b.Z, Vd=b.dst, sel_prev=b.sel, workspace=b.ws,
                          check=False)
     assert rc == -4
+    for bad in (b.U, b.Z):
+        assert pkg.hsadmm_step(b.plan, b.W, U=b.U, U_out=bad, Z=b.Z, mask=b.mask, workspace=b.ws, check=False) == -1
+    assert pkg.hsadmm_step(b.plan, b.W, U=b.U, U_out=b.Uout, Z=b.Z, mask_frozen=b.mask, check=False) == -4
     after = b.outputs()
     for k in before:
         assert np.array_equal(before[k], after[k], equal_nan=True), k       # nothing was enqueued
     b.plan.close()
 
 
-@pytest.mark.parametrize("R", [1, 4, 5])
-def test_outer_iterations_predicted_by_the_previous_selection(R):
+@pytest.mark.parametrize("R,ping_pong", [(1, False), (4, False), (5, False), (4, True), (3, True)])
+def test_outer_iterations_predicted_by_the_previous_selection(R, ping_pong):
     """Algorithm 1's flow: every outer iteration is predicted by the selection of the one before (the first by the
     all-ones mask the algorithm starts from), U carried in place, replicas changing between iterations so that
     supports do change.  Every iteration matches the oracle bit for bit, and both kinds of wrong prediction occur."""
@@ -200,13 +223,21 @@ def test_outer_iterations_predicted_by_the_previous_selection(R):
         ref = oracle.project(t, Wn, Uref)
         refc = oracle.compact(t, ref["Z"], ref["mask"])
         prev, new = records[it % 2], records[(it + 1) % 2]
-        pkg.hsadmm_step(b.plan, b.W, U=b.U, Z=b.Z, mask=b.mask, sel_prev=prev, sel=new, packed=b.packed,
-                        layer_off=b.off, kept_idx=b.kept, workspace=b.ws)
+        if ping_pong:
+            # the dual alternates between two buffers, as a caller who passes U_out every iteration would hold it
+            pkg.hsadmm_step(b.plan, b.W, U=b.U, U_out=b.Uout, Z=b.Z, mask=b.mask, sel_prev=prev, sel=new,
+                            packed=b.packed, layer_off=b.off, kept_idx=b.kept, workspace=b.ws)
+            b.U, b.Uout = b.Uout, b.U
+        else:
+            pkg.hsadmm_step(b.plan, b.W, U=b.U, Z=b.Z, mask=b.mask, sel_prev=prev, sel=new, packed=b.packed,
+                            layer_off=b.off, kept_idx=b.kept, workspace=b.ws)
         pkg.hsadmm_expand(b.plan, b.packed, None, b.dst, b.ws)
         got = b.outputs()
         assert np.array_equal(got["mask"], ref["mask"]), "iteration %d" % it
         assert np.array_equal(got["Z"].view(np.uint32), ref["Z"].view(np.uint32)), "iteration %d" % it
-        assert np.array_equal(got["U"].view(np.uint32), ref["U"].view(np.uint32)), "iteration %d" % it
+        for l in wl.layers:
+            sl = slice(l.elem_off, l.elem_off + l.n)
+            assert np.array_equal(got["U"][sl].view(np.uint32), ref["U"][sl].view(np.uint32)), "iteration %d" % it
         assert np.array_equal(got["layer_off"], refc["layer_off"])
         n_packed = int(refc["layer_off"][-1])
         assert np.array_equal(got["packed"][:n_packed].view(np.uint32), refc["packed"].view(np.uint32)), "iteration %d" % it
