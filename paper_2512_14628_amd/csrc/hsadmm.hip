@@ -94,12 +94,13 @@ hipError_t for_replica_count(int R, F&& f)
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct WsLayout {
-    size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, total;
+    size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, work, total;
 };
 
 enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kPass1Hinted, kHintedRepair, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
+constexpr size_t kRepairGrid = 2048;       // workgroups of the repair pass under a prediction: 8 per compute unit
 
 // Scratch of the entry point that takes no workspace argument (hsadmm_project_compact_static): one array per
 // device, held until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the
@@ -293,7 +294,7 @@ hipError_t launch_channel_final(const hsadmm_plan* p, const ProjectArgs& a, int 
 // (CHANNEL) are in place.  Layers under both constraints then take their second projection: channel
 // norms over the kept filters from the candidate held in Z, and the selection of the channels.
 hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, const ProjectArgs& a, uint8_t* mask,
-                         char* ws, hipStream_t s, int32_t* sel_out = nullptr)
+                         char* ws, hipStream_t s, int32_t* sel_out = nullptr, const WorkList& wl = WorkList{})
 {
     // the selection also leaves its index mappings in the workspace, for a compaction without a mask
     IndexMaps im;
@@ -305,7 +306,7 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
     const int nL = (int)p->layers.size();
     hipError_t e = launch(p, kTopk, select_topk, (unsigned)p->layers.size(), kScanBlock, s,
                           (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
-                          (const int32_t*)nullptr, 0, im, nL, (int)p->pack_align);
+                          (const int32_t*)nullptr, 0, im, nL, (int)p->pack_align, wl, (const WorkItem*)p->d_items_rows);
     if (e != hipSuccess || p->both_layers.empty()) return e;
     e = launch(p, kColsums, composite_colsums, (unsigned)p->items_both.size(), kBlock, s,
                (const WorkItem*)p->d_items_both, (const float*)a.Z, a.Ur, a.Zg, a.Vd, a.coef,
@@ -313,7 +314,7 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
     if (e != hipSuccess) return e;
     return launch(p, kTopk, select_topk, (unsigned)p->both_layers.size(), kScanBlock, s,
                   (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
-                  (const int32_t*)p->d_both_layers, 1, im, nL, (int)p->pack_align);
+                  (const int32_t*)p->d_both_layers, 1, im, nL, (int)p->pack_align, wl, (const WorkItem*)p->d_items_rows);
 }
 
 int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, hipStream_t s, int32_t* sel_out = nullptr)
@@ -436,6 +437,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->ws.layer_off = off;  off = align_up(off + sizeof(int64_t) * (size_t)(L + 1), 256);
         p->ws.kept_idx = off;   off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
         p->ws.respart = off;    off = align_up(off + sizeof(double) * 4 * p->items_rows.size(), 256);
+        p->ws.work = off;       off = align_up(off + sizeof(int32_t) * (kWorkHeader + p->items_rows.size()), 256);
         p->ws.total = off;
     } catch (...) {   // host allocation failure while building the tables
         delete p;
@@ -573,8 +575,12 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     // Under a prediction pass 1 writes the FILTER rows in the form their predicted fate makes final and packs the rows
     // it expects to be kept (and every row of the unconstrained layers).
     const bool hinted = sel_prev != nullptr && !p->items_plain.empty();
+    const HintArgs h{sel_prev, out ? out->packed : nullptr, U_out ? 0 : 1, reinterpret_cast<int32_t*>(ws + p->ws.work)};
+    WorkList wl{};
     if (hinted) {
-        const HintArgs h{sel_prev, out ? out->packed : nullptr, U_out ? 0 : 1};
+        // the selection lists the row items the repair pass must visit, and hands out the offsets and kept lists itself
+        wl.sel_prev = h.stash ? nullptr : sel_prev; wl.work = h.work; wl.pack = out ? 1 : 0;
+        if (out) wl.co = CopyOut{out->layer_off, out->kept_idx};
         e = for_replica_count<true>(R, [&](auto c) {
             return launch(p, kPass1Hinted, project_pass1_hinted<decltype(c)::value>, (unsigned)p->items_proj.size(),
                           kBlock, s, (const WorkItem*)p->d_items_proj, a, (int)R, h);
@@ -584,7 +590,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     }
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     // (the candidate of a BOTH layer is formed again from its parked mean and U)
-    if (run_selection(p, a.key, a.colpart, a, mask, ws, s, sel_out) != hipSuccess) return HSADMM_ERR_HIP;
+    if (run_selection(p, a.key, a.colpart, a, mask, ws, s, sel_out, wl) != hipSuccess) return HSADMM_ERR_HIP;
     // The compaction of Z under the selection just made reads kept groups only, which FILTER layers hold in
     // final form since pass 1, so it shares a launch with the FILTER fix-up; the CHANNEL and BOTH layers are
     // packed by the pass that writes their Z.
@@ -600,16 +606,22 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         po.n_layers = (int)p->layers.size();
     }
     if (hinted) {
-        // every FILTER row from its predicted to its final form; with a compaction the launch also covers the
-        // unconstrained layers, whose first work items hand out their offsets and kept lists
-        const bool all_plain = out != nullptr;
-        const unsigned n = (unsigned)(all_plain ? p->items_plain.size() : p->items_fix.size());
-        if (n) {
-            const HintArgs h{sel_prev, out ? out->packed : nullptr, U_out ? 0 : 1};
-            const WorkItem* items = all_plain ? p->d_items_plain : p->d_items_fix;
-            e = for_replica_count<true>(R, [&](auto c) {
-                return launch(p, kHintedRepair, hinted_repair<decltype(c)::value>, n, kBlock, s, items, a, (int)R, h, po);
-            });
+        // every FILTER row from its predicted to its final form.  Dual in place: all row items (most hold a stash
+        // to clear).  Dual out of place: as many workgroups as the device holds at once share the items the
+        // selection listed.
+        if (!p->items_fix.empty()) {
+            if (h.stash) {
+                e = for_replica_count<true>(R, [&](auto c) {
+                    return launch(p, kHintedRepair, hinted_repair_all<decltype(c)::value>, (unsigned)p->items_fix.size(),
+                                  kBlock, s, (const WorkItem*)p->d_items_fix, a, (int)R, h, po);
+                });
+            } else {
+                const unsigned n = (unsigned)std::min<size_t>(p->items_fix.size(), kRepairGrid);
+                e = for_replica_count<true>(R, [&](auto c) {
+                    return launch(p, kHintedRepair, hinted_repair<decltype(c)::value>, n, kBlock, s,
+                                  (const WorkItem*)p->d_items_rows, a, (int)R, h, po);
+                });
+            }
             if (e != hipSuccess) return HSADMM_ERR_HIP;
         }
     } else if (!p->items_fix.empty() && !fuse) {

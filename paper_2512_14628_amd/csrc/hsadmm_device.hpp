@@ -65,6 +65,18 @@ struct CopyOut {
     int32_t* kept_idx;
 };
 
+// What the selection needs to list the work a predicted selection leaves behind (sel_prev null: nothing is listed).
+// The list lives in the workspace: work[0] counts the listed row items (pass 1 clears it), work[kWorkHeader + i]
+// is the i-th listed item's index in the plan's table of row items.  Layers reserve their stretch of the list with
+// one atomic add each, so the order of the list varies from run to run; the items are independent of each other.
+constexpr int kWorkHeader = 64;
+struct WorkList {
+    const int32_t* sel_prev;   // the previous selection's record (the prediction); null: no list is made
+    int32_t* work;
+    int pack;                  // a compaction follows: kept rows whose rank has moved are listed as well
+    CopyOut co;                // where the selection hands the caller layer_off / kept_idx itself (nulls: it does not)
+};
+
 // What a kernel needs to pack rows as it forms them: the index mappings (in the workspace), the packed buffer
 // and where the caller wants its copies of layer_off / kept_idx.
 struct PackOut {

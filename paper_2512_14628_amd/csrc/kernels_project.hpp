@@ -351,6 +351,7 @@ struct HintArgs {
     const int32_t* sel_prev;   // groups_total: the previous selection's record
     float* packed;             // packed buffer of this call's compaction, or null (no compaction)
     int stash;                 // the dual is updated in place: rows predicted pruned keep the kept-form dual in Z
+    int32_t* work;             // the work list the selection fills for the repair pass (pass 1 clears its counter)
 };
 
 // pass1_row with the outputs of a row written in the form its prediction makes final (see Cand::put_h); the sum of
@@ -443,6 +444,7 @@ __global__ __launch_bounds__(kBlock) void project_pass1_hinted(const WorkItem* _
 {
     const WorkItem it = items[blockIdx.x];
     const int mode = item_mode(it);
+    if (blockIdx.x == 0 && threadIdx.x == 0) h.work[0] = 0;      // (the selection runs after this whole launch)
     if (mode == HSADMM_MODE_CHANNEL) project_tile<R>(it, a, Rrt);
     else if (mode == HSADMM_MODE_BOTH) project_rows<R, true>(it, a, Rrt);
     else project_rows_hinted<R>(it, a, Rrt, h);
@@ -659,16 +661,27 @@ __device__ __forceinline__ void hinted_repair_rows(const WorkItem& it, const Pro
     }
 }
 
-// Row items of the FILTER layers (and, with a compaction, of the unconstrained layers, whose rows pass 1 has
-// packed: only their offsets and kept lists are handed to the caller here).
+// The repair pass with the dual updated in place: every FILTER row item is visited (the rows predicted pruned and
+// pruned, most of them once the pattern has settled, still hold the stashed dual in Z).
 template <int R>
-__global__ __launch_bounds__(kBlock) void hinted_repair(const WorkItem* __restrict__ items, ProjectArgs a, int Rrt,
+__global__ __launch_bounds__(kBlock) void hinted_repair_all(const WorkItem* __restrict__ fix_items, ProjectArgs a,
+                                                            int Rrt, HintArgs h, PackOut po)
+{
+    const WorkItem it = fix_items[blockIdx.x];
+    hinted_repair_rows<R>(it, a, Rrt, h.sel_prev, po.pos, true, po.packed ? po.packed + it.packed_off : nullptr);
+}
+
+// The repair pass with the dual written out of place: a fixed number of workgroups share the row items the
+// selection has listed (none at all when the prediction was right everywhere).
+template <int R>
+__global__ __launch_bounds__(kBlock) void hinted_repair(const WorkItem* __restrict__ row_items, ProjectArgs a, int Rrt,
                                                         HintArgs h, PackOut po)
 {
-    const WorkItem it = items[blockIdx.x];
-    if (po.packed && it.row0 == 0) copy_out_layer(it.layer, po.cnt, po.kept_idx, po.n_layers, po.layer_off, po.co);
-    if (item_mode(it) != HSADMM_MODE_FILTER) return;
-    hinted_repair_rows<R>(it, a, Rrt, h.sel_prev, po.pos, h.stash != 0, po.packed ? po.packed + it.packed_off : nullptr);
+    const int n = h.work[0];
+    for (int i = blockIdx.x; i < n; i += gridDim.x) {
+        const WorkItem it = row_items[h.work[kWorkHeader + i]];
+        hinted_repair_rows<R>(it, a, Rrt, h.sel_prev, po.pos, false, po.packed ? po.packed + it.packed_off : nullptr);
+    }
 }
 
 }  // namespace

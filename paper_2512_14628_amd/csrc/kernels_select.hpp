@@ -133,7 +133,7 @@ __device__ __forceinline__ bool same_prefix(unsigned long long y, unsigned long 
 
 template <bool INREG>
 __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, uint8_t* ml, int kk, TopkShared& sh,
-                                           int32_t* pos_l, int32_t* kidx_l, int32_t* sel_l)
+                                           int32_t* pos_l, int32_t* kidx_l, int32_t* sel_l, int32_t* ck_l)
 {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -271,8 +271,51 @@ __device__ __forceinline__ void topk_layer(int G, const unsigned long long* kb, 
             pos_l[g] = kept ? r : -1;
             if (sel_l) sel_l[g] = kept ? r : -1;
             if (kept) kidx_l[r] = g;
+            if (kept && ck_l) ck_l[r] = g;
         }
         carry_kept += total_kept;
+    }
+}
+
+// After a FILTER layer's selection under a prediction: the layer's row items that the repair pass has to visit are
+// appended to the work list.  A row needs a visit unless its prediction was right and left it in final form:
+// predicted kept and kept (with a compaction: at the same rank), or predicted pruned and pruned.  (This list is
+// used when the dual is written out of place; updated in place, every pruned row still has to be cleared and the
+// repair pass visits all items.)  Every thread looks at the rows tid, tid + 1024, ... and marks the item a row in
+// need belongs to in `bits`; the marked items are then appended in index order.  The repair pass looks at every
+// row of a listed item again, so listing too much is harmless: a layer with more items than `bits` holds is
+// listed whole.
+constexpr int kItemBits = 3 * 256 * 32;
+__device__ __forceinline__ void list_repairs(const DevLayer& L, const WorkList& wl, const WorkItem* __restrict__ row_items,
+                                             const int32_t* pos_l, unsigned int* bits, int* wtot, int* slot)
+{
+    const int tid = threadIdx.x;
+    const int32_t* hp_l = wl.sel_prev + L.group_base;
+    const int rows_per_item = row_items[L.rows_item0].nr;        // every item of a layer but the last has this many
+    const bool all = L.rows_items > kItemBits;
+    __syncthreads();                                             // the ranks written above are visible to the workgroup
+    if (!all) {
+        for (int w = tid; w < (L.rows_items + 31) / 32; w += kScanBlock) bits[w] = 0u;
+        __syncthreads();
+        for (int r = tid; r < L.c_out; r += kScanBlock) {
+            const int hp = hp_l[r], pn = pos_l[r];
+            const bool pred_kept = hp >= 0, kept = pn >= 0;
+            const bool needs = pred_kept != kept || (kept && wl.pack && pn != hp);
+            if (needs) {
+                const int i = r / rows_per_item;
+                atomicOr(&bits[i >> 5], 1u << (i & 31));
+            }
+        }
+        __syncthreads();
+    }
+    for (int base = 0; base < L.rows_items; base += kScanBlock) {
+        const int i = base + tid;
+        const bool needs = i < L.rows_items && (all || ((bits[i >> 5] >> (i & 31)) & 1u) != 0u);
+        int total;
+        const int rank = block_excl_scan<kScanWaves>(needs, wtot, total);
+        if (tid == 0 && total > 0) *slot = atomicAdd(wl.work, total);
+        __syncthreads();
+        if (needs) wl.work[kWorkHeader + *slot + rank] = L.rows_item0 + i;
     }
 }
 
@@ -285,9 +328,11 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
                                                           const double* __restrict__ colpart,
                                                           uint8_t* __restrict__ mask,
                                                           const int32_t* __restrict__ layer_list, int stage,
-                                                          IndexMaps im, int n_layers, int pack_align)
+                                                          IndexMaps im, int n_layers, int pack_align,
+                                                          WorkList wl, const WorkItem* __restrict__ row_items)
 {
     __shared__ TopkShared sh;
+    __shared__ int work_slot;
     const DevLayer L = layers[stage == 0 ? (int)blockIdx.x : layer_list[blockIdx.x]];
     const bool both = L.mode == HSADMM_MODE_BOTH;
     const bool channels = L.mode == HSADMM_MODE_CHANNEL || (both && stage == 1);
@@ -300,6 +345,14 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
     int32_t* pos_l = im.pos + first;
     int32_t* sel_l = im.sel ? im.sel + first : nullptr;      // the caller's copy of the ranks
     int32_t* kidx_l = im.kept_idx + L.kept_start + ((both && stage == 1) ? L.k : 0);
+    int32_t* ck_l = wl.co.kept_idx ? wl.co.kept_idx + (kidx_l - im.kept_idx) : nullptr;   // the caller's copy of the kept list
+    if (tid == 0 && stage == 0 && wl.co.layer_off) {
+        const int l = blockIdx.x;
+        wl.co.layer_off[l] = L.packed_off;
+        if (l == n_layers - 1)
+            wl.co.layer_off[n_layers] = L.packed_off + packed_size(L.mode, L.unit, (L.mode == HSADMM_MODE_NONE) ? L.G : L.k,
+                                                                   L.k_in, pack_align);
+    }
     if (tid == 0 && stage == 0) {
         const int l = blockIdx.x;
         const int c0 = (L.mode == HSADMM_MODE_NONE) ? L.G : L.k;
@@ -348,16 +401,20 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
         __syncthreads();
     }
     const int kk = (L.mode == HSADMM_MODE_NONE) ? G : ((both && stage == 1) ? L.k_in : L.k);
+    const unsigned long long* kb = reinterpret_cast<const unsigned long long*>(kl);
     if (kk >= G) {
         for (int g = tid; g < G; g += kScanBlock) {
             ml[g] = 1; pos_l[g] = g; kidx_l[g] = g;
             if (sel_l) sel_l[g] = g;
+            if (ck_l) ck_l[g] = g;
         }
-        return;
+    } else if (G <= kTopkRegs * kScanBlock) {
+        topk_layer<true>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l, ck_l);
+    } else {
+        topk_layer<false>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l, ck_l);
     }
-    const unsigned long long* kb = reinterpret_cast<const unsigned long long*>(kl);
-    if (G <= kTopkRegs * kScanBlock) topk_layer<true>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l);
-    else topk_layer<false>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l);
+    if (wl.sel_prev && L.mode == HSADMM_MODE_FILTER)
+        list_repairs(L, wl, row_items, pos_l, &sh.hist[0][0], sh.wtot, &work_slot);
 }
 
 }  // namespace
