@@ -201,7 +201,9 @@ def main():
     #      is then predicted by its own recorded selection with the given fraction of every layer's kept groups
     #      exchanged for pruned ones (1.0: a support that has settled; 0.9: a tenth of it still moving).
     hinted = None
-    if one_call and not args.no_hinted and any(l.mode == wk.MODE_FILTER for l in wl.layers):
+    has_filter = any(l.mode == wk.MODE_FILTER for l in wl.layers)
+    has_channel = any(l.mode == wk.MODE_CHANNEL for l in wl.layers)
+    if one_call and not args.no_hinted and (has_filter or has_channel):
         hsteps = max(1, args.steps // 2)
         hwarm = max(3, args.warmup // 2)
         T = hwarm + 2 * hsteps
@@ -242,13 +244,15 @@ def main():
         hinted = {"what": "hsadmm_step(sel_prev = the step's own selection recorded beforehand, degraded to the hit "
                           "rate) + hsadmm_expand; same outputs and algorithmic bytes as the step `value` times",
                   "steps": hsteps}
-        for rate, two_duals in ((1.0, False), (0.9, False), (1.0, True), (0.9, True)):
+        # (CHANNEL layers take a prediction only with the dual out of place)
+        variants = ((1.0, False), (0.9, False), (1.0, True), (0.9, True)) if has_filter else ((1.0, True), (0.9, True))
+        for rate, two_duals in variants:
             ping_pong[0] = two_duals
             hints_host = recs_host.copy()
             if rate < 1.0:
                 for t in range(T):
                     for l in wl.layers:
-                        if l.mode != wk.MODE_FILTER:
+                        if l.mode not in (wk.MODE_FILTER, wk.MODE_CHANNEL):
                             continue
                         seg = hints_host[t, l.group_base:l.group_base + l.groups]
                         kept, pruned = np.flatnonzero(seg >= 0), np.flatnonzero(seg < 0)

@@ -44,6 +44,10 @@
 // fp32 arithmetic is compiled without contraction (-ffp-contract=off); the fp64 accumulation
 // uses fma(v, v, acc), which equals mul+add because the square of an fp32 value is exact in fp64.
 //
+//   project_pass1_hinted / hinted_repair   the projection under a predicted selection (hsadmm_step with sel_prev):
+//                   rows and, with the dual out of place, channels are written in the form the previous
+//                   iteration's selection makes final; after the selection only what it got wrong is touched again
+//
 // Source layout: hsadmm_device.hpp (shared device code), kernels_*.hpp (one file per call family), this file
 // (plan, launches, C ABI).  Everything is one translation unit.
 
@@ -66,6 +70,7 @@
 #include "kernels_project.hpp"
 #include "kernels_select.hpp"
 #include "kernels_frozen.hpp"
+#include "kernels_hinted.hpp"
 #include "kernels_weighted.hpp"
 #include "kernels_residuals.hpp"
 #include "kernels_compact.hpp"
@@ -222,6 +227,8 @@ void add_tile_items(std::vector<WorkItem>& out, int layer, const DevLayer& d, in
             it.khw = d.khw;
             it.layer = layer;
             it.row0 = r0;
+            it.k = d.k;
+            it.packed_off = d.packed_off;
             out.push_back(it);
         }
     }
@@ -574,7 +581,8 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     hipError_t e;
     // Under a prediction pass 1 writes the FILTER rows in the form their predicted fate makes final and packs the rows
     // it expects to be kept (and every row of the unconstrained layers).
-    const bool hinted = sel_prev != nullptr && !p->items_plain.empty();
+    const bool hinted_chan = sel_prev != nullptr && U_out != nullptr && !p->items_chan.empty();   // CHANNEL layers too
+    const bool hinted = sel_prev != nullptr && (!p->items_plain.empty() || hinted_chan);
     const HintArgs h{sel_prev, out ? out->packed : nullptr, U_out ? 0 : 1, reinterpret_cast<int32_t*>(ws + p->ws.work)};
     WorkList wl{};
     if (hinted) {
@@ -609,17 +617,18 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         // every FILTER row from its predicted to its final form.  Dual in place: all row items (most hold a stash
         // to clear).  Dual out of place: as many workgroups as the device holds at once share the items the
         // selection listed.
-        if (!p->items_fix.empty()) {
+        if (!p->items_fix.empty() || hinted_chan) {
             if (h.stash) {
                 e = for_replica_count<true>(R, [&](auto c) {
                     return launch(p, kHintedRepair, hinted_repair_all<decltype(c)::value>, (unsigned)p->items_fix.size(),
                                   kBlock, s, (const WorkItem*)p->d_items_fix, a, (int)R, h, po);
                 });
             } else {
-                const unsigned n = (unsigned)std::min<size_t>(p->items_fix.size(), kRepairGrid);
+                const unsigned n = (unsigned)std::min<size_t>(p->items_fix.size() + (hinted_chan ? p->items_chan.size() : 0),
+                                                              kRepairGrid);
                 e = for_replica_count<true>(R, [&](auto c) {
                     return launch(p, kHintedRepair, hinted_repair<decltype(c)::value>, n, kBlock, s,
-                                  (const WorkItem*)p->d_items_rows, a, (int)R, h, po);
+                                  (const WorkItem*)p->d_items_rows, a, (int)R, h, (const uint8_t*)mask, po);
                 });
             }
             if (e != hipSuccess) return HSADMM_ERR_HIP;
@@ -649,7 +658,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
                        a, 0, (const uint8_t*)mask, PackOut{});
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
-    if (!p->items_chan.empty()) {
+    if (!p->items_chan.empty() && !hinted_chan) {
         const uint8_t* cm = mask;
         const PackOut* pk = out ? &po : nullptr;
         const unsigned gc = (unsigned)p->items_chan.size();

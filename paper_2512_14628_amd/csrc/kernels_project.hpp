@@ -436,8 +436,101 @@ __device__ __forceinline__ void project_rows_hinted(const WorkItem& it, const Pr
     }
 }
 
-// Pass 1 under a predicted selection: FILTER and NONE layers as above; CHANNEL and BOTH layers take no prediction
-// (their outputs are written after the selection anyway).
+// project_tile under a predicted selection, for a dual written out of place: besides the column sums, the tile's
+// elements are written in the final form the prediction gives them -- Z <- V in the columns of channels predicted
+// kept, +0 in the others, the updated dual U + (Wbar - Z), and, with a compaction, the kept columns at their
+// predicted place in the packed row.  If the selection then keeps exactly the predicted channels the layer is
+// done; otherwise the repair pass forms the layer again from the replicas and the old dual, which is still there.
+// A lane's four columns keep their flags and packed columns for the whole tile.
+template <int R>
+__device__ __forceinline__ void project_tile_hinted(const WorkItem& it, const ProjectArgs& a, int Rrt, const HintArgs& h)
+{
+    __shared__ double part[kWaves][kWave * 4];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const int vw = vec ? 4 : 1;
+    const int col = it.col0 + lane * vw;
+    const bool in = col < row_len;
+    const int khw = it.khw;
+    const int packed_row_len = it.k * khw;
+    double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+    if (in) {
+        bool kept[4] = {false, false, false, false};
+        int pc[4] = {-1, -1, -1, -1};            // packed column, -1: not packed here
+        const DivKhw div(khw);
+        const int32_t* hp_l = h.sel_prev + it.g0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (i < vw) {
+                const int ch = div(col + i);
+                const int hp = hp_l[ch];
+                kept[i] = hp >= 0;
+                if (h.packed && hp >= 0 && hp < it.k) pc[i] = hp * khw + (col + i - ch * khw);
+            }
+        }
+        float* const pk_layer = h.packed ? h.packed + it.packed_off : nullptr;
+        for (int rr = wave; rr < it.nr; rr += kWaves) {
+            const int64_t e = it.base + (int64_t)rr * row_len + col;
+            float* drow = pk_layer ? pk_layer + (int64_t)(it.row0 + rr) * packed_row_len : nullptr;
+            const int RR = R > 0 ? R : Rrt;
+            if (vec) {
+                v4f s = ld4(a.W[0] + e);
+#pragma unroll
+                for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
+                const v4f u = ld4(a.Ur + e);
+                const v4f wb = s * a.inv_R;
+                const v4f v = wb + u;
+                v4f z;
+                z.x = kept[0] ? v.x : 0.f; z.y = kept[1] ? v.y : 0.f; z.z = kept[2] ? v.z : 0.f; z.w = kept[3] ? v.w : 0.f;
+                st4(a.Z + e, z);
+                st4(a.U + e, u + (wb - z));
+                if (a.Wbar) st4(a.Wbar + e, wb);
+                if (drow) {
+                    if (pc[0] >= 0) drow[pc[0]] = z.x;
+                    if (pc[1] >= 0) drow[pc[1]] = z.y;
+                    if (pc[2] >= 0) drow[pc[2]] = z.z;
+                    if (pc[3] >= 0) drow[pc[3]] = z.w;
+                }
+                acc0 = fma((double)v.x, (double)v.x, acc0);
+                acc1 = fma((double)v.y, (double)v.y, acc1);
+                acc2 = fma((double)v.z, (double)v.z, acc2);
+                acc3 = fma((double)v.w, (double)v.w, acc3);
+            } else {
+                float s = ld1(a.W[0] + e);
+#pragma unroll
+                for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
+                const float u = ld1(a.Ur + e);
+                const float wb = s * a.inv_R;
+                const float v = wb + u;
+                const float z = kept[0] ? v : 0.f;
+                st1(a.Z + e, z);
+                st1(a.U + e, u + (wb - z));
+                if (a.Wbar) st1(a.Wbar + e, wb);
+                if (drow && pc[0] >= 0) drow[pc[0]] = z;
+                acc0 = fma((double)v, (double)v, acc0);
+            }
+        }
+    }
+    part[wave][lane * 4 + 0] = acc0;
+    part[wave][lane * 4 + 1] = acc1;
+    part[wave][lane * 4 + 2] = acc2;
+    part[wave][lane * 4 + 3] = acc3;
+    __syncthreads();
+    if (wave == 0 && in) {
+        double* out = a.colpart + it.aux + col;
+        for (int i = 0; i < vw; ++i) {
+            double s = part[0][lane * 4 + i];
+            for (int w = 1; w < kWaves; ++w) s += part[w][lane * 4 + i];
+            out[i] = s;
+        }
+    }
+}
+
+// Pass 1 under a predicted selection: FILTER and NONE layers as above; CHANNEL layers take the prediction when the
+// dual is written out of place (else, like BOTH layers always, they only sum here and are written after the
+// selection).
 template <int R>
 __global__ __launch_bounds__(kBlock) void project_pass1_hinted(const WorkItem* __restrict__ items, ProjectArgs a,
                                                                int Rrt, HintArgs h)
@@ -445,9 +538,14 @@ __global__ __launch_bounds__(kBlock) void project_pass1_hinted(const WorkItem* _
     const WorkItem it = items[blockIdx.x];
     const int mode = item_mode(it);
     if (blockIdx.x == 0 && threadIdx.x == 0) h.work[0] = 0;      // (the selection runs after this whole launch)
-    if (mode == HSADMM_MODE_CHANNEL) project_tile<R>(it, a, Rrt);
-    else if (mode == HSADMM_MODE_BOTH) project_rows<R, true>(it, a, Rrt);
-    else project_rows_hinted<R>(it, a, Rrt, h);
+    if (mode == HSADMM_MODE_CHANNEL) {
+        if (h.stash) project_tile<R>(it, a, Rrt);
+        else project_tile_hinted<R>(it, a, Rrt, h);
+    } else if (mode == HSADMM_MODE_BOTH) {
+        project_rows<R, true>(it, a, Rrt);
+    } else {
+        project_rows_hinted<R>(it, a, Rrt, h);
+    }
 }
 
 // ------------------------------------------------------------------ BOTH: channel norms after the filter projection
@@ -584,105 +682,6 @@ __global__ __launch_bounds__(kBlock) void project_fixup(const WorkItem* __restri
     fixup_rows(items[blockIdx.x], mask, U, Z);
 }
 
-// ------------------------------------------------------------------ project under a predicted selection: repair
-
-// After the selection every FILTER row goes from the form its prediction gave it to its final form, and the packed
-// buffer is completed (`packed`: the layer's segment, or null without a compaction):
-//   predicted pruned, pruned   stash: Z <- +0 (a store only; U = V is final since pass 1); else nothing to do
-//   predicted pruned, kept     stash: Z holds the kept-form dual and U the candidate: the two change places;
-//                              else the row is formed again from the replicas and the old dual, as pass 1 forms a
-//                              row predicted kept; either way the candidate also goes to the packed row
-//   predicted kept,   pruned   U <- V (held in Z), Z <- +0, as without a prediction
-//   predicted kept,   kept     final; copied to the packed buffer only if its rank has changed
-template <int R>
-__device__ __forceinline__ void hinted_repair_rows(const WorkItem& it, const ProjectArgs& a, int Rrt,
-                                                   const int32_t* __restrict__ sel_prev,
-                                                   const int32_t* __restrict__ pos, bool stash, float* packed)
-{
-    const int row_len = it.row_len;
-    const bool vec = item_vec(it);
-    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-    const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
-    const int rows_at_once = kBlock / lpr;
-    const int sub = threadIdx.x / lpr;
-    const int j = threadIdx.x - sub * lpr;
-    const int nchunk = row_len >> 2;
-    float* const U = a.U;
-    float* const Z = a.Z;
-    for (int rr = sub; rr < it.nr; rr += rows_at_once) {
-        const int hp = sel_prev[it.g0 + rr];
-        const int pn = pos[it.g0 + rr];
-        const bool pred_kept = hp >= 0, kept = pn >= 0;
-        const int64_t base = it.base + (int64_t)rr * row_len;
-        float* pk = (packed && kept) ? packed + (int64_t)pn * row_len : nullptr;
-        if (pred_kept && kept) {
-            if (!pk || pn == hp) continue;                       // packed in pass 1 already, at this rank
-            if (vec) for (int c = j; c < nchunk; c += lpr) st4u(pk + 4 * c, ld4(Z + base + 4 * c));
-            else for (int c = j; c < row_len; c += lpr) pk[c] = ld1(Z + base + c);
-        } else if (!pred_kept && !kept) {
-            if (!stash) continue;
-            if (vec) for (int c = j; c < nchunk; c += lpr) st4(Z + base + 4 * c, zero4);
-            else for (int c = j; c < row_len; c += lpr) st1(Z + base + c, 0.f);
-        } else if (pred_kept) {
-            if (vec) {
-                for (int c = j; c < nchunk; c += lpr) {
-                    const int64_t e = base + 4 * c;
-                    st4(U + e, ld4(Z + e));
-                    st4(Z + e, zero4);
-                }
-            } else {
-                for (int c = j; c < row_len; c += lpr) {
-                    st1(U + base + c, ld1(Z + base + c));
-                    st1(Z + base + c, 0.f);
-                }
-            }
-        } else if (stash) {
-            if (vec) {
-                for (int c = j; c < nchunk; c += lpr) {
-                    const int64_t e = base + 4 * c;
-                    const v4f v = ld4(U + e), d = ld4(Z + e);
-                    st4(Z + e, v);
-                    st4(U + e, d);
-                    if (pk) st4u(pk + 4 * c, v);
-                }
-            } else {
-                for (int c = j; c < row_len; c += lpr) {
-                    const float v = ld1(U + base + c), d = ld1(Z + base + c);
-                    st1(Z + base + c, v);
-                    st1(U + base + c, d);
-                    if (pk) pk[c] = v;
-                }
-            }
-        } else {
-            // the same arithmetic on the same inputs as in pass 1, so the same bits (the keys are not taken again)
-            if (vec) for (int c = j; c < nchunk; c += lpr) (void)Cand<R>::one_h(a, Rrt, base, c << 2, true, false, pk);
-            else for (int c = j; c < row_len; c += lpr) (void)Cand<R>::scalar_h(a, Rrt, base, c, true, false, pk);
-        }
-    }
-}
-
-// The repair pass with the dual updated in place: every FILTER row item is visited (the rows predicted pruned and
-// pruned, most of them once the pattern has settled, still hold the stashed dual in Z).
-template <int R>
-__global__ __launch_bounds__(kBlock) void hinted_repair_all(const WorkItem* __restrict__ fix_items, ProjectArgs a,
-                                                            int Rrt, HintArgs h, PackOut po)
-{
-    const WorkItem it = fix_items[blockIdx.x];
-    hinted_repair_rows<R>(it, a, Rrt, h.sel_prev, po.pos, true, po.packed ? po.packed + it.packed_off : nullptr);
-}
-
-// The repair pass with the dual written out of place: a fixed number of workgroups share the row items the
-// selection has listed (none at all when the prediction was right everywhere).
-template <int R>
-__global__ __launch_bounds__(kBlock) void hinted_repair(const WorkItem* __restrict__ row_items, ProjectArgs a, int Rrt,
-                                                        HintArgs h, PackOut po)
-{
-    const int n = h.work[0];
-    for (int i = blockIdx.x; i < n; i += gridDim.x) {
-        const WorkItem it = row_items[h.work[kWorkHeader + i]];
-        hinted_repair_rows<R>(it, a, Rrt, h.sel_prev, po.pos, false, po.packed ? po.packed + it.packed_off : nullptr);
-    }
-}
 
 }  // namespace
 #endif

@@ -319,6 +319,27 @@ __device__ __forceinline__ void list_repairs(const DevLayer& L, const WorkList& 
     }
 }
 
+// After a CHANNEL layer's selection under a prediction (dual out of place): pass 1 has written the layer in the form
+// the predicted channels make final.  If the selection differs from the prediction in any channel (with a
+// compaction: or in any rank, which only a record that no selection of this plan wrote can cause), every row item
+// of the layer is listed and the repair pass forms the layer again.
+__device__ __forceinline__ void list_changed_layer(const DevLayer& L, const WorkList& wl, const int32_t* pos_l, int* slot)
+{
+    const int tid = threadIdx.x;
+    const int32_t* hp_l = wl.sel_prev + L.group_base;
+    __syncthreads();                                             // the ranks written above are visible to the workgroup
+    bool differs = false;
+    for (int g = tid; g < L.G; g += kScanBlock) {
+        const int hp = hp_l[g], pn = pos_l[g];
+        const bool pred_kept = hp >= 0, kept = pn >= 0;
+        differs = differs || pred_kept != kept || (kept && wl.pack && pn != hp);
+    }
+    if (!__syncthreads_or(differs)) return;
+    if (tid == 0) *slot = atomicAdd(wl.work, L.rows_items);
+    __syncthreads();
+    for (int i = tid; i < L.rows_items; i += kScanBlock) wl.work[kWorkHeader + *slot + i] = L.rows_item0 + i;
+}
+
 // One workgroup per layer: finish the CHANNEL keys, then write the layer's mask.
 // stage 0: workgroup b takes layer b; of a BOTH layer it selects the filters (its first c_out groups).
 // stage 1: workgroup b takes layer layer_list[b], a BOTH layer, and selects its channels (the c_in
@@ -415,6 +436,8 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
     }
     if (wl.sel_prev && L.mode == HSADMM_MODE_FILTER)
         list_repairs(L, wl, row_items, pos_l, &sh.hist[0][0], sh.wtot, &work_slot);
+    else if (wl.sel_prev && L.mode == HSADMM_MODE_CHANNEL)
+        list_changed_layer(L, wl, pos_l, &work_slot);
 }
 
 }  // namespace

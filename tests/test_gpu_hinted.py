@@ -51,7 +51,9 @@ def degrade(wl, mask, fraction, rng):
 SHAPES = [(96, 16, 1, wk.MODE_FILTER, 40), (80, 64, 9, wk.MODE_FILTER, 30), (40, 256, 9, wk.MODE_FILTER, 16),
           (24, 512, 9, wk.MODE_FILTER, 9), (64, 3, 49, wk.MODE_FILTER, 20), (37, 5, 7, wk.MODE_FILTER, 36),
           (300, 1, 1, wk.MODE_FILTER, 1), (96, 128, 1, wk.MODE_CHANNEL, 50), (48, 40, 9, wk.MODE_BOTH, 30, 21),
-          (10, 128, 1, wk.MODE_NONE, 10), (33, 7, 1, wk.MODE_NONE, 33), (70, 2100, 1, wk.MODE_FILTER, 28)]
+          (10, 128, 1, wk.MODE_NONE, 10), (33, 7, 1, wk.MODE_NONE, 33), (70, 2100, 1, wk.MODE_FILTER, 28),
+          (50, 24, 9, wk.MODE_CHANNEL, 10), (33, 7, 3, wk.MODE_CHANNEL, 3), (70, 300, 1, wk.MODE_CHANNEL, 120),
+          (130, 3, 49, wk.MODE_CHANNEL, 1)]
 
 
 class _Bufs:
