@@ -17,7 +17,9 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hsadmm_oracle.c")
-_LIB = os.path.join(_HERE, "libhsadmm_oracle.so")
+# HSADMM_ORACLE_LIB: load this build of the oracle instead (the sanitizer leg of the tests compiles one with
+# -fsanitize=address,undefined into a temporary directory)
+_LIB = os.environ.get("HSADMM_ORACLE_LIB") or os.path.join(_HERE, "libhsadmm_oracle.so")
 _lib = None
 last_call_seconds = 0.0     # wall time of the most recent C call (excludes numpy marshalling)
 
@@ -26,6 +28,8 @@ CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (a no-op when the library is newer than its source)."""
+    if os.environ.get("HSADMM_ORACLE_LIB"):
+        return _LIB                      # a build made by the caller: used as it is
     if (not force and os.path.exists(_LIB)
             and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
         return _LIB

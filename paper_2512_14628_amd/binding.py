@@ -15,7 +15,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 SRC_PATH = os.path.join(_HERE, "csrc", "hsadmm.hip")
 INCLUDE_DIR = os.path.join(_ROOT, "include")
-LIB_PATH = os.path.join(_HERE, "libhsadmm.so")
+# HSADMM_LIB: load this build of the library instead of the in-tree one (e.g. one whose host code carries sanitizers)
+LIB_PATH = os.environ.get("HSADMM_LIB") or os.path.join(_HERE, "libhsadmm.so")
 
 MODE_NONE, MODE_FILTER, MODE_CHANNEL, MODE_BOTH = 0, 1, 2, 3
 MAX_REPLICAS = 16
