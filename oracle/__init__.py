@@ -88,6 +88,11 @@ def _load():
     lib.oracle_average.restype = ctypes.c_int
     lib.oracle_mask_drift.argtypes = [ctypes.c_int32, i32p, i32p, i32p, i32p, u8p, u8p, i32p]
     lib.oracle_mask_drift.restype = ctypes.c_int
+    lib.oracle_layer_sqnorms.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, f32p, f64p]
+    lib.oracle_layer_sqnorms.restype = ctypes.c_int
+    lib.oracle_stopping_test.argtypes = [ctypes.c_int32, i64p, ctypes.c_int32, ctypes.c_int32, f64p, f64p, f64p, f64p,
+                                         ctypes.c_double, ctypes.c_double, i32p, i32p]
+    lib.oracle_stopping_test.restype = ctypes.c_int
     lib.oracle_adapt_penalties.argtypes = [ctypes.c_int32, f64pp, ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
                                            ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                            f64pp, f64pp, f32p, f32p]
@@ -477,3 +482,40 @@ def scale_layers(table, X, factor):
     if rc != 0:
         raise ValueError("oracle_scale_layers failed with code %d" % rc)
     return out
+
+
+def layer_sqnorms(table, X):
+    """Squared Frobenius norm of every layer of the arena X, float64[L] (sequential fp64 sums)."""
+    lib = _load()
+    t = _cols(table)
+    L = len(t["c_out"])
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    out = np.zeros(L, dtype=np.float64)
+    rc = lib.oracle_layer_sqnorms(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
+                                  _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32), _p(X, ctypes.c_float),
+                                  _p(out, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("oracle_layer_sqnorms failed with code %d" % rc)
+    return out
+
+
+def stopping_test(n_elems, P: int, n_out: int, rho1, rho2, sq, mag, eps_abs: float, eps_rel: float):
+    """Section 3.4's stopping test per layer.  sq: 4 x L squared residual sums, mag: 5 x L squared magnitudes
+    (sum_j ||theta_j||^2, ||z_i||^2, ||z||^2, sum_j ||u_j||^2, ||v_i||^2).  Returns (done int32[L], all_done bool)."""
+    lib = _load()
+    n_elems = np.ascontiguousarray(n_elems, dtype=np.int64)
+    L = n_elems.size
+    rho1 = np.ascontiguousarray(rho1, dtype=np.float64)
+    rho2 = np.ascontiguousarray(rho2, dtype=np.float64)
+    sq = np.ascontiguousarray(sq, dtype=np.float64).reshape(-1)
+    mag = np.ascontiguousarray(mag, dtype=np.float64).reshape(-1)
+    if rho1.size != L or rho2.size != L or sq.size != 4 * L or mag.size != 5 * L:
+        raise ValueError("one rho per layer, 4 residual sums and 5 magnitudes per layer")
+    done = np.zeros(L, dtype=np.int32)
+    every = ctypes.c_int32(0)
+    rc = lib.oracle_stopping_test(L, _p(n_elems, ctypes.c_int64), int(P), int(n_out), _p(rho1, ctypes.c_double),
+                                  _p(rho2, ctypes.c_double), _p(sq, ctypes.c_double), _p(mag, ctypes.c_double),
+                                  float(eps_abs), float(eps_rel), _p(done, ctypes.c_int32), ctypes.byref(every))
+    if rc != 0:
+        raise ValueError("oracle_stopping_test failed with code %d" % rc)
+    return done, bool(every.value)

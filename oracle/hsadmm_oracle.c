@@ -794,3 +794,74 @@ int oracle_scale_layers(int32_t L, const int64_t *elem_off, const int32_t *c_out
     }
     return 0;
 }
+
+/*
+ * Layer-wise squared Frobenius norms of one arena, in fp64, accumulated sequentially in memory order:
+ *     out[l] = sum over layer l of (double)X[e]^2
+ * (the magnitudes the feasibility thresholds of Section 3.4 are relative to).
+ */
+int oracle_layer_sqnorms(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
+                         const int32_t *khw, const float *X, double *out)
+{
+    if (L < 1 || !X || !out) return -1;
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t n = (int64_t)c_out[l] * c_in[l] * khw[l];
+        const int64_t off = elem_off[l];
+        double s = 0.0;
+        for (int64_t e = 0; e < n; ++e) {
+            const double x = (double)X[off + e];
+            s += x * x;
+        }
+        out[l] = s;
+    }
+    return 0;
+}
+
+/*
+ * Stopping test (Section 3.4, last paragraph; Algorithm 1, Phase 5: "if R_pri < eps_pri and R_dual < eps_dual then
+ * break").  The paper declares a layer converged once its total primal and dual residual norms fall below
+ * feasibility thresholds built from an absolute and a relative tolerance as in the ADMM reference it cites (Boyd
+ * et al., Section 3.3.1 there):
+ *     eps_pri  = sqrt(p) eps_abs + eps_rel max(||A x||, ||B z||),      eps_dual = sqrt(p) eps_abs + eps_rel ||A^T y||.
+ * Written out for the two consensus levels of this method, for one layer of n elements, P replicas per node and the
+ * contributions of n_out nodes added up (1: a node's own view).  The constraints are theta_ij - z_i = 0 (P per node)
+ * and z_i - z = 0 (one per node), p = (P + 1) n n_out scalars in all; "A x" stacks theta_i1..theta_iP and z_i, "B z"
+ * stacks P copies of z_i and one of z, and y stacks the unscaled duals rho_1 u_ij and rho_2 v_i:
+ *     R_pri^2  = sq[0L + l] + sq[2L + l]                          (all primal residuals of Section 3.4)
+ *     R_dual^2 = P rho_1^2 sq[1L + l] + n_out rho_2^2 sq[3L + l]  (all dual residuals; s_intra is the same for each replica)
+ *     ||A x||^2   = mag[0L + l] + mag[1L + l]                     (sum_j ||theta_j||^2 ; ||z_i||^2)
+ *     ||B z||^2   = P mag[1L + l] + n_out mag[2L + l]             (||z||^2)
+ *     ||A^T y||^2 = rho_1^2 mag[3L + l] + rho_2^2 mag[4L + l]     (sum_j ||u_j||^2 ; ||v_i||^2)
+ * sq: 4L squared residual sums as oracle_residuals writes them; mag: 5L squared magnitudes (sum_j ||theta_j||^2,
+ * ||z_i||^2, ||z||^2, sum_j ||u_j||^2, ||v_i||^2; with several nodes each summed over them, ||z||^2 excepted).
+ * done[l] = 1 iff R_pri < eps_pri and R_dual < eps_dual (strictly, as Algorithm 1 prints it); *all_done = 1 iff every
+ * layer is done.  eps_abs, eps_rel >= 0 are arguments: the paper gives neither.
+ */
+int oracle_stopping_test(int32_t L, const int64_t *n_elems, int32_t P, int32_t n_out, const double *rho1,
+                         const double *rho2, const double *sq, const double *mag, double eps_abs, double eps_rel,
+                         int32_t *done, int32_t *all_done)
+{
+    if (L < 1 || !n_elems || !rho1 || !rho2 || !sq || !mag || !done || !all_done || P < 1 || n_out < 1) return -1;
+    if (!(eps_abs >= 0.0) || !(eps_rel >= 0.0)) return -1;
+    for (int32_t l = 0; l < L; ++l) {
+        if (n_elems[l] < 1 || !(rho1[l] > 0.0) || !(rho2[l] > 0.0)) return -1;
+        for (int k = 0; k < 4; ++k) if (!(sq[(int64_t)k * L + l] >= 0.0)) return -1;
+        for (int k = 0; k < 5; ++k) if (!(mag[(int64_t)k * L + l] >= 0.0)) return -1;
+    }
+    int32_t every = 1;
+    for (int32_t l = 0; l < L; ++l) {
+        const double r_pri = sqrt(sq[0 * (int64_t)L + l] + sq[2 * (int64_t)L + l]);
+        const double r_dual = sqrt((double)P * rho1[l] * rho1[l] * sq[1 * (int64_t)L + l] +
+                                   (double)n_out * rho2[l] * rho2[l] * sq[3 * (int64_t)L + l]);
+        const double p = (double)(P + 1) * (double)n_elems[l] * (double)n_out;
+        const double ax = sqrt(mag[0 * (int64_t)L + l] + mag[1 * (int64_t)L + l]);
+        const double bz = sqrt((double)P * mag[1 * (int64_t)L + l] + (double)n_out * mag[2 * (int64_t)L + l]);
+        const double aty = sqrt(rho1[l] * rho1[l] * mag[3 * (int64_t)L + l] + rho2[l] * rho2[l] * mag[4 * (int64_t)L + l]);
+        const double eps_pri = sqrt(p) * eps_abs + eps_rel * (ax > bz ? ax : bz);
+        const double eps_dual = sqrt(p) * eps_abs + eps_rel * aty;
+        done[l] = (r_pri < eps_pri && r_dual < eps_dual) ? 1 : 0;
+        if (!done[l]) every = 0;
+    }
+    *all_done = every;
+    return 0;
+}

@@ -338,3 +338,64 @@ def test_the_one_entry_point_equals_the_named_calls_in_every_form():
     assert pkg.hsadmm_step(y.plan, y.W, U=y.U, Z=y.Z, mask=y.mask, packed=y.packed, workspace=y.ws, check=False) == -1
     x.plan.close()
     y.plan.close()
+
+
+def test_a_captured_graph_follows_coefficients_that_change_between_replays():
+    """An outer iteration's consensus side with the weights of Eq. (9) as a call argument (`coef`, a device buffer):
+    dynamic weighted projection + shrinkage, decompression + Eq. (13), captured once into a HIP graph.  Between
+    replays the penalties adapt, i.e. the buffer's contents change (an ordinary device copy, no call on the plan);
+    every replay must equal the eager iteration that was given the same weights through the plan's setter."""
+    rng = np.random.default_rng(12)
+    wl = wk.custom_workload(SHAPES, R=4, seed=41, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    L = len(wl.layers)
+    dev = torch.device("cuda:0")
+    Zg0 = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.05
+    Vd0 = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.01
+    penalties = [(rng.uniform(1e-3, 2e-3, L) * 2.0 ** it, rng.uniform(1e-4, 3e-4, L) / 2.0 ** it) for it in range(3)]
+    weights = [pkg.hsadmm_node_coefficients(r1, r2, 1e-4, 16, wl.R) for r1, r2 in penalties]
+
+    def coef_of(ab):
+        return torch.from_numpy(np.stack(ab, axis=1).astype(np.float32).reshape(-1).copy()).to(dev)
+
+    # eager reference: the weights go into the plan before every iteration
+    x = _Bufs(wl, W, U, 1)
+    xZg, xVd = torch.from_numpy(Zg0).to(dev), torch.from_numpy(Vd0).to(dev)
+    expected = []
+    for it in range(3):
+        pkg.hsadmm_plan_set_node_weights(x.plan, *weights[it])
+        pkg.hsadmm_project_weighted_compact(x.plan, x.W, x.U, xZg, xVd, x.Z, None, x.mask, None, x.packed, x.off,
+                                            x.kept, x.ws)
+        pkg.hsadmm_expand_dual(x.plan, x.packed, None, x.dst, x.Z, xVd, x.ws)
+        torch.cuda.synchronize()
+        expected.append({"U": x.U.cpu().numpy(), "Z": x.Z.cpu().numpy(), "mask": x.mask.cpu().numpy(),
+                         "dst": x.dst.cpu().numpy(), "v": xVd.cpu().numpy()})
+
+    y = _Bufs(wl, W, U, 1)                       # its plan keeps a = 1, b = 0 throughout
+    yZg, yVd = torch.from_numpy(Zg0).to(dev), torch.from_numpy(Vd0).to(dev)
+    coef = coef_of(weights[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pkg.hsadmm_step(y.plan, y.W, U=y.U, Zg=yZg, Vd=yVd, coef=coef, Z=y.Z, mask=y.mask, packed=y.packed,
+                        layer_off=y.off, kept_idx=y.kept, workspace=y.ws, stream=side)
+        pkg.hsadmm_expand_dual(y.plan, y.packed, None, y.dst, y.Z, yVd, y.ws, stream=side)
+    torch.cuda.synchronize()
+    assert torch.equal(y.U, y.U0)                # capture does not execute
+    scratch = torch.zeros(1 << 18, device=dev)
+    for it in range(3):
+        coef.copy_(coef_of(weights[it]))         # this iteration's weights: only the buffer changes
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {"U": y.U.cpu().numpy(), "Z": y.Z.cpu().numpy(), "mask": y.mask.cpu().numpy(),
+               "dst": y.dst.cpu().numpy(), "v": yVd.cpu().numpy()}
+        assert np.array_equal(got["mask"], expected[it]["mask"]), it
+        for k in ("U", "Z", "dst", "v"):
+            for l in wl.layers:
+                sl = slice(l.elem_off, l.elem_off + l.n)
+                assert np.array_equal(got[k][sl].view(np.uint32), expected[it][k][sl].view(np.uint32)), (it, k, l.name)
+        scratch.add_(1.0)                        # eager work between replays
+        assert float(scratch.sum().item()) == float((it + 1) * (1 << 18))
+    x.plan.close()
+    y.plan.close()

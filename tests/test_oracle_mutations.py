@@ -19,6 +19,7 @@ from tests import test_oracle_composite as cpins
 from tests import test_oracle_shape as spins
 from tests import test_oracle_global as gpins
 from tests import test_oracle_penalties as ppins
+from tests import test_oracle_stopping as tpins
 
 MUTATIONS = [
     ("tie_goes_to_higher_index", "(kl[h] == kl[g] && h < g)", "(kl[h] == kl[g] && h > g)"),
@@ -109,6 +110,19 @@ MUTATIONS = [
     ("penalty_cut_multiplies", "next = old / tau_decr;", "next = old * tau_decr;"),
     ("penalty_compares_squares_with_mu", "const double r = sqrt(sq[(int64_t)(2 * level) * L + l]);", "const double r = sq[(int64_t)(2 * level) * L + l];"),
     ("scale_layers_takes_the_first_factor", "const float f = factor[l];", "const float f = factor[0];"),
+    ("stop_primal_not_strict", "done[l] = (r_pri < eps_pri && r_dual < eps_dual) ? 1 : 0;", "done[l] = (r_pri <= eps_pri && r_dual < eps_dual) ? 1 : 0;"),
+    ("stop_dual_not_strict", "done[l] = (r_pri < eps_pri && r_dual < eps_dual) ? 1 : 0;", "done[l] = (r_pri < eps_pri && r_dual <= eps_dual) ? 1 : 0;"),
+    ("stop_either_side_suffices", "done[l] = (r_pri < eps_pri && r_dual < eps_dual) ? 1 : 0;", "done[l] = (r_pri < eps_pri || r_dual < eps_dual) ? 1 : 0;"),
+    ("stop_takes_the_smaller_stack", "eps_rel * (ax > bz ? ax : bz);", "eps_rel * (ax < bz ? ax : bz);"),
+    ("stop_dual_norm_forgets_P", "const double r_dual = sqrt((double)P * rho1[l] * rho1[l] * sq[1 * (int64_t)L + l] +", "const double r_dual = sqrt(rho1[l] * rho1[l] * sq[1 * (int64_t)L + l] +"),
+    ("stop_dual_norm_rho_not_squared", "const double r_dual = sqrt((double)P * rho1[l] * rho1[l] * sq[1 * (int64_t)L + l] +", "const double r_dual = sqrt((double)P * rho1[l] * sq[1 * (int64_t)L + l] +"),
+    ("stop_primal_drops_inter_level", "const double r_pri = sqrt(sq[0 * (int64_t)L + l] + sq[2 * (int64_t)L + l]);", "const double r_pri = sqrt(sq[0 * (int64_t)L + l]);"),
+    ("stop_scaled_duals_in_threshold", "const double aty = sqrt(rho1[l] * rho1[l] * mag[3 * (int64_t)L + l] + rho2[l] * rho2[l] * mag[4 * (int64_t)L + l]);", "const double aty = sqrt(mag[3 * (int64_t)L + l] + mag[4 * (int64_t)L + l]);"),
+    ("stop_dimension_forgets_the_inter_block", "const double p = (double)(P + 1) * (double)n_elems[l] * (double)n_out;", "const double p = (double)P * (double)n_elems[l] * (double)n_out;"),
+    ("stop_bz_forgets_copies_of_zi", "const double bz = sqrt((double)P * mag[1 * (int64_t)L + l] +", "const double bz = sqrt(mag[1 * (int64_t)L + l] +"),
+    ("stop_overall_flag_is_any", "if (!done[l]) every = 0;", "if (done[l]) every = 1; else if (l == 0) every = 0;"),
+    ("layer_sqnorm_in_fp32", "const double x = (double)X[off + e];\n            s += x * x;", "const float x = X[off + e];\n            s += (double)(x * x);"),
+    ("layer_sqnorm_reads_padding", "for (int64_t e = 0; e < n; ++e) {\n            const double x = (double)X[off + e];", "for (int64_t e = 0; e < n + 1; ++e) {\n            const double x = (double)X[off + e];"),
 ]
 
 PIN_FUNCS = [
@@ -160,6 +174,13 @@ PIN_FUNCS = [
     ppins.test_layers_and_levels_are_independent_and_neutral_constants_change_nothing,
     ppins.test_rescaled_dual_keeps_a_converged_scaled_admm_at_its_fixed_point,
     ppins.test_scale_layers_is_a_per_layer_float32_multiply,
+    tpins.test_handworked_thresholds_one_layer,
+    tpins.test_both_comparisons_are_strict,
+    tpins.test_relative_part_takes_the_larger_of_the_two_stacks_and_the_unscaled_duals,
+    tpins.test_the_residual_totals_count_replicas_and_nodes,
+    tpins.test_layers_are_judged_separately_and_the_overall_flag_needs_all_of_them,
+    tpins.test_against_the_formulas_in_numpy_on_random_inputs,
+    tpins.test_layer_sqnorms_handworked_and_against_numpy,
 ]
 
 
@@ -178,7 +199,8 @@ def test_a_planted_mistake_in_the_oracle_fails_a_pin(name, old, new, tmp_path, m
     for fn in ("oracle_project", "oracle_compact", "oracle_expand", "oracle_set_threads", "oracle_get_threads",
                "oracle_project_frozen", "oracle_mask_or", "oracle_node_coefficients", "oracle_project_weighted",
                "oracle_dual_inter", "oracle_add_arenas", "oracle_residuals", "oracle_average", "oracle_mask_drift",
-               "oracle_project_weighted_frozen", "oracle_adapt_penalties", "oracle_scale_layers"):
+               "oracle_project_weighted_frozen", "oracle_adapt_penalties", "oracle_scale_layers", "oracle_layer_sqnorms",
+               "oracle_stopping_test"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(oracle, "_lib", lib)
