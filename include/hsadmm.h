@@ -477,13 +477,52 @@ int hsadmm_average(const hsadmm_plan_t* plan, const float* const* bufs, int32_t 
  * Zi_prev, Zg, Zg_prev may be NULL: rows whose operands are missing are 0.
  *   out   device, 4*L doubles.  The order of additions is fixed (results are
  *         reproducible run to run) but differs from a sequential sum.
- * hsadmm_adapt_penalties consumes these norms; the stopping thresholds,
- * whose tolerances the paper leaves to its reference, are the caller's
- * comparison.  Errors: INVALID_ARGUMENT, WORKSPACE, UNSUPPORTED, HIP.
+ * hsadmm_adapt_penalties and hsadmm_stopping_test consume these norms.
+ * Errors: INVALID_ARGUMENT, WORKSPACE, UNSUPPORTED, HIP.
  */
 int hsadmm_residuals(const hsadmm_plan_t* plan, const float* const* W_replicas, int32_t R,
                      const float* Zi, const float* Zi_prev, const float* Zg, const float* Zg_prev,
                      double* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Layer-wise squared Frobenius norms of one full-layout arena, accumulated in
+ * fp64 from the fp32 values: out[l] = || X_l ||_F^2 (the magnitudes the
+ * thresholds of the stopping test are relative to).  The order of additions is
+ * fixed, as in hsadmm_residuals.
+ *   X    device, full-layout arena, 16-byte aligned;  out  device, L doubles
+ * Errors: INVALID_ARGUMENT, WORKSPACE, HIP.
+ */
+int hsadmm_layer_sqnorms(const hsadmm_plan_t* plan, const float* X, double* out,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Stopping test (Section 3.4, last paragraph; Algorithm 1, Phase 5: break once
+ * R_pri < eps_pri and R_dual < eps_dual).  Per layer, the total primal and dual
+ * residual norms over both consensus levels against the feasibility
+ * thresholds of the ADMM reference the paper cites (Boyd et al., "Stopping
+ * criteria"), built from an absolute and a relative tolerance.  For a layer of
+ * n elements, P replicas per node and the sums of n_out nodes (1: a node's own
+ * view), the constraints are theta_ij - z_i = 0 and z_i - z = 0:
+ *     R_pri^2  = residuals[0L+l] + residuals[2L+l]
+ *     R_dual^2 = P rho_1^2 residuals[1L+l] + n_out rho_2^2 residuals[3L+l]
+ *     eps_pri  = sqrt((P+1) n n_out) eps_abs
+ *                + eps_rel max( sqrt(mag[0L+l] + mag[1L+l]), sqrt(P mag[1L+l] + n_out mag[2L+l]) )
+ *     eps_dual = sqrt((P+1) n n_out) eps_abs + eps_rel sqrt(rho_1^2 mag[3L+l] + rho_2^2 mag[4L+l])
+ * (all in fp64; the duals enter unscaled, rho u and rho v).  HOST function,
+ * all pointers are HOST memory; it needs neither a plan nor a device.
+ *   n_elems     n_layers int64: elements of every layer (c_out * c_in * khw)
+ *   residuals   4*L doubles as hsadmm_residuals / hsadmm_retrain_* write them
+ *   magnitudes  5*L doubles, squared norms per layer (hsadmm_layer_sqnorms):
+ *               sum_j ||theta_j||^2, ||z_i||^2, ||z||^2, sum_j ||u_j||^2 (P ||U||^2
+ *               for a caller who holds the replica-mean dual only), ||v_i||^2
+ *   rho1, rho2  L doubles, > 0;  eps_abs, eps_rel >= 0: the paper gives neither
+ *   layer_done  out, L int32: 1 iff both comparisons hold strictly
+ *   all_done    out: 1 iff every layer is done
+ * Errors: INVALID_ARGUMENT (nothing is written).
+ */
+int hsadmm_stopping_test(const int64_t* n_elems, int32_t n_layers, int32_t P, int32_t n_out,
+                         const double* rho1, const double* rho2, const double* residuals, const double* magnitudes,
+                         double eps_abs, double eps_rel, int32_t* layer_done, int32_t* all_done);
 
 /*
  * Step (e2), recovery: the inverse scatter.  Every element of every layer of
@@ -674,7 +713,7 @@ int hsadmm_version(void);
  * profile taken elsewhere can be matched to the plan it is quoted for.
  * Errors: INVALID_ARGUMENT, HOST_MEMORY, HIP.
  */
-#define HSADMM_KERNEL_COUNT 26
+#define HSADMM_KERNEL_COUNT 27
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 int hsadmm_kernel_grid(const hsadmm_plan_t* plan, int kernel_id);

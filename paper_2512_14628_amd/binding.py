@@ -37,8 +37,9 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_project_weighted_frozen", "hsadmm_project_weighted_frozen_compact",
            "hsadmm_retrain_project", "hsadmm_retrain_expand",
            "hsadmm_adapt_penalties", "hsadmm_scale_layers", "hsadmm_project_compact_static",
-           "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid")
-KERNEL_COUNT = 26
+           "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid",
+           "hsadmm_layer_sqnorms", "hsadmm_stopping_test")
+KERNEL_COUNT = 27
 
 
 class HsadmmError(RuntimeError):
@@ -185,6 +186,12 @@ def load_library():
     lib.hsadmm_kernel_timing_enable.restype = ctypes.c_int
     lib.hsadmm_kernel_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.hsadmm_kernel_timing_read.restype = ctypes.c_int
+    lib.hsadmm_layer_sqnorms.argtypes = [vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hsadmm_layer_sqnorms.restype = ctypes.c_int
+    lib.hsadmm_stopping_test.argtypes = [ctypes.POINTER(ctypes.c_int64), ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                         dp, dp, dp, dp, ctypes.c_double,
+                                         ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+    lib.hsadmm_stopping_test.restype = ctypes.c_int
     lib.hsadmm_kernel_grid.argtypes = [vp, ctypes.c_int]
     lib.hsadmm_kernel_grid.restype = ctypes.c_int
     lib.hsadmm_kernel_name.argtypes = [ctypes.c_int]
@@ -334,7 +341,8 @@ def hsadmm_project_compact_static(plan: Plan, W_replicas: Sequence, U, Z, Wbar, 
                                            _stream(stream))
     if check and rc != 0:
         raise HsadmmError(rc, "hsadmm_project_compact_static",
-           "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid")
+           "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid",
+           "hsadmm_layer_sqnorms", "hsadmm_stopping_test")
     return rc
 
 
@@ -473,6 +481,43 @@ def hsadmm_adapt_penalties(residuals, rho1, rho2, P: int, n_out: int, mu: float,
     if rc != 0:
         raise HsadmmError(rc, "hsadmm_adapt_penalties")
     return list(r1), list(r2), list(su), list(sv)
+
+
+def hsadmm_layer_sqnorms(plan: Plan, X, out, workspace, stream=None, workspace_bytes: Optional[int] = None,
+                         check: bool = True) -> int:
+    """out[l] = squared Frobenius norm of layer l of the arena X (fp64, on the device)."""
+    lib = load_library()
+    wb = _nbytes(workspace) if workspace_bytes is None else int(workspace_bytes)
+    rc = lib.hsadmm_layer_sqnorms(plan.handle, _ptr(X), _ptr(out), _ptr(workspace), wb, _stream(stream))
+    if check and rc != 0:
+        raise HsadmmError(rc, "hsadmm_layer_sqnorms")
+    return rc
+
+
+def hsadmm_stopping_test(n_elems, P: int, n_out: int, rho1, rho2, residuals, magnitudes, eps_abs: float,
+                         eps_rel: float):
+    """Section 3.4's stopping test on the host.  n_elems: elements per layer; residuals: 4*L numbers, magnitudes:
+    5*L numbers (rows as in the header).  Returns (list of L flags, all_done)."""
+    lib = load_library()
+    L = len(n_elems)
+    ne = (ctypes.c_int64 * L)(*[int(x) for x in n_elems])
+
+    def flat(x, rows):
+        v = [float(y) for r in x for y in (r if hasattr(r, "__len__") else [r])]
+        if len(v) != rows * L:
+            raise ValueError("%d numbers per layer expected" % rows)
+        return (ctypes.c_double * len(v))(*v)
+    if len(rho1) != L or len(rho2) != L:
+        raise ValueError("one penalty per layer and level")
+    r1 = (ctypes.c_double * L)(*[float(x) for x in rho1])
+    r2 = (ctypes.c_double * L)(*[float(x) for x in rho2])
+    done = (ctypes.c_int32 * L)()
+    every = ctypes.c_int32(-1)
+    rc = lib.hsadmm_stopping_test(ne, L, int(P), int(n_out), r1, r2, flat(residuals, 4), flat(magnitudes, 5),
+                                  float(eps_abs), float(eps_rel), done, ctypes.byref(every))
+    if rc != 0:
+        raise HsadmmError(rc, "hsadmm_stopping_test")
+    return list(done), bool(every.value)
 
 
 def hsadmm_scale_layers(plan: Plan, X, factor, stream=None, check: bool = True) -> int:

@@ -102,7 +102,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, work, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kPass1Hinted, kHintedRepair, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kPass1Hinted, kHintedRepair, kSqnormPart, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 constexpr size_t kRepairGrid = 2048;       // workgroups of the repair pass under a prediction: 8 per compute unit
@@ -1228,6 +1228,61 @@ int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int
     return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
 }
 
+int hsadmm_layer_sqnorms(const hsadmm_plan_t* p, const float* X, double* out, void* workspace, size_t workspace_bytes,
+                         void* hip_stream)
+{
+    if (!p || !X || !out || !workspace) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!on_plan_device(p)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!is_aligned(X, 16) || !is_aligned(out, 8) || !is_aligned(workspace, 256)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (workspace_bytes < p->ws.total) return HSADMM_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    double* part = reinterpret_cast<double*>(static_cast<char*>(workspace) + p->ws.respart);
+    hipError_t e = launch(p, kSqnormPart, sqnorm_partials, (unsigned)p->items_rows.size(), kBlock, s,
+                          (const WorkItem*)p->d_items_rows, X, part);
+    if (e != hipSuccess) return HSADMM_ERR_HIP;
+    e = launch(p, kResFinish, residual_finish, (unsigned)p->layers.size(), kBlock, s, (const DevLayer*)p->d_layers,
+               (int)p->layers.size(), (const double*)part, out, 0, 1);
+    return e == hipSuccess ? HSADMM_OK : HSADMM_ERR_HIP;
+}
+
+int hsadmm_stopping_test(const int64_t* n_elems, int32_t n_layers, int32_t P, int32_t n_out, const double* rho1,
+                         const double* rho2, const double* residuals, const double* magnitudes, double eps_abs,
+                         double eps_rel, int32_t* layer_done, int32_t* all_done)
+{
+    if (!n_elems || !rho1 || !rho2 || !residuals || !magnitudes || !layer_done || !all_done || n_layers < 1 || P < 1 ||
+        n_out < 1)
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!(eps_abs >= 0.0) || !(eps_rel >= 0.0)) return HSADMM_ERR_INVALID_ARGUMENT;
+    const size_t L = (size_t)n_layers;
+    auto row = [L](const double* table, int r, size_t l) { return table[(size_t)r * L + l]; };
+    for (size_t l = 0; l < L; ++l) {                       // everything is checked before the first flag is written
+        bool ok = n_elems[l] >= 1 && rho1[l] > 0.0 && rho2[l] > 0.0;
+        for (int r = 0; r < 4 && ok; ++r) ok = row(residuals, r, l) >= 0.0;
+        for (int r = 0; r < 5 && ok; ++r) ok = row(magnitudes, r, l) >= 0.0;
+        if (!ok) return HSADMM_ERR_INVALID_ARGUMENT;       // (a NaN fails its comparison)
+    }
+    const double replicas = (double)P, nodes = (double)n_out;
+    int32_t open_layers = 0;
+    for (size_t l = 0; l < L; ++l) {
+        const double elems = (double)n_elems[l];
+        const double w1 = rho1[l] * rho1[l], w2 = rho2[l] * rho2[l];
+        // squared norms of the stacked residuals of both consensus levels, and of the stacks the tolerances scale with
+        const double primal_sq = row(residuals, 0, l) + row(residuals, 2, l);
+        const double dual_sq = replicas * w1 * row(residuals, 1, l) + nodes * w2 * row(residuals, 3, l);
+        const double first_vars_sq = row(magnitudes, 0, l) + row(magnitudes, 1, l);                   // theta_j's and z_i
+        const double second_vars_sq = replicas * row(magnitudes, 1, l) + nodes * row(magnitudes, 2, l);  // z_i per replica, z
+        const double duals_sq = w1 * row(magnitudes, 3, l) + w2 * row(magnitudes, 4, l);              // rho_1 u_j, rho_2 v_i
+        const double absolute = std::sqrt((replicas + 1.0) * elems * nodes) * eps_abs;
+        const double tol_primal = absolute + eps_rel * std::sqrt(std::max(first_vars_sq, second_vars_sq));
+        const double tol_dual = absolute + eps_rel * std::sqrt(duals_sq);
+        const bool done = std::sqrt(primal_sq) < tol_primal && std::sqrt(dual_sq) < tol_dual;
+        layer_done[l] = done ? 1 : 0;
+        open_layers += done ? 0 : 1;
+    }
+    *all_done = open_layers == 0 ? 1 : 0;
+    return HSADMM_OK;
+}
+
 int hsadmm_dual_inter(const hsadmm_plan_t* p, const float* Zi, const float* Zg, float* Vd, void* hip_stream)
 {
     if (!p || !Zi || !Zg || !Vd) return HSADMM_ERR_INVALID_ARGUMENT;
@@ -1408,6 +1463,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kScaleLayers: return "scale_layers";
         case kPass1Hinted: return "project_pass1_hinted";
         case kHintedRepair: return "hinted_repair";
+        case kSqnormPart: return "sqnorm_partials";
         default: return "";
     }
 }

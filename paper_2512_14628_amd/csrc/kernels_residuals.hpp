@@ -74,6 +74,41 @@ __global__ __launch_bounds__(kBlock) void residual_partials(const WorkItem* __re
     }
 }
 
+// Squared norm of one arena per row item, in fp64: part[4 * item] (the other three slots of the item are left alone).
+// Same per-thread strides and the same order of combination as residual_partials.
+__global__ __launch_bounds__(kBlock) void sqnorm_partials(const WorkItem* __restrict__ items, const float* __restrict__ X,
+                                                          double* __restrict__ part)
+{
+    __shared__ double red[kWaves];
+    const WorkItem it = items[blockIdx.x];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t len = (int64_t)it.nr * it.row_len;
+    double s = 0.0;
+    if (item_vec(it)) {
+        for (int64_t c = threadIdx.x; c < (len >> 2); c += kBlock) {
+            const v4f x = ld4(X + it.base + (c << 2));
+            s = fma((double)x.x, (double)x.x, s);
+            s = fma((double)x.y, (double)x.y, s);
+            s = fma((double)x.z, (double)x.z, s);
+            s = fma((double)x.w, (double)x.w, s);
+        }
+    } else {
+        for (int64_t c = threadIdx.x; c < len; c += kBlock) {
+            const double x = (double)X[it.base + c];
+            s = fma(x, x, s);
+        }
+    }
+    s = wave_xor_sum(s, kWave);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = red[0];
+        for (int w = 1; w < kWaves; ++w) t += red[w];
+        part[(int64_t)blockIdx.x * 4] = t;
+    }
+}
+
 // One workgroup per layer: adds the layer's item partials (thread t takes items t, t+256, ... in
 // order; threads are combined by a butterfly per wave and in wave order), writes out[k*L + l] for the
 // norms k0 <= k < k1 (the others are neither read nor written).

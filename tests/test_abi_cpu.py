@@ -189,6 +189,60 @@ def test_adapt_penalties_host_function_matches_the_oracle(lib):
     assert lib.hsadmm_scale_layers(None, None, None, None) == -1
 
 
+def test_stopping_test_host_function_against_the_printed_thresholds_and_the_oracle(lib):
+    """hsadmm_stopping_test runs on the host: checked against the thresholds written out in exact rational arithmetic
+    on cases whose roots are exact (powers of two), including both boundaries, and against the oracle's decisions on
+    random inputs that are not within rounding of a boundary."""
+    import oracle
+    from fractions import Fraction
+    # one layer, n = 8, P = 1, n_out = 1: p = 16; eps_abs = 1 -> absolute part 4; eps_rel = 1/4
+    # magnitudes: theta 48, z_i 16, z 9, u 4, v 1; rho_1 = 2, rho_2 = 4
+    #   ||A x|| = sqrt(64) = 8, ||B z|| = sqrt(16 + 9) = 5 -> eps_pri = 4 + 2 = 6
+    #   ||A^T y|| = sqrt(4 * 4 + 16 * 1) = sqrt(32): not exact; take u = 9, v = 4: sqrt(36 + 64) = 10 -> eps_dual = 6.5
+    mag = [[48.0], [16.0], [9.0], [9.0], [4.0]]
+    done, every = pkg.hsadmm_stopping_test([8], 1, 1, [2.0], [4.0], [[20.0], [0.0], [16.0], [0.0]], mag, 1.0, 0.25)
+    assert done == [0] and not every                          # R_pri = 6 = eps_pri, and 6 < 6 is false
+    done, every = pkg.hsadmm_stopping_test([8], 1, 1, [2.0], [4.0], [[20.0], [0.0], [15.0], [0.0]], mag, 1.0, 0.25)
+    assert done == [1] and every                              # sqrt(35) < 6
+    # dual side: R_dual^2 = 1 * 4 * sq_1 + 1 * 16 * sq_3; sq_1 = 4, sq_3 = 1.640625 -> 16 + 26.25 = 42.25 = 6.5^2
+    done, _ = pkg.hsadmm_stopping_test([8], 1, 1, [2.0], [4.0], [[0.0], [4.0], [0.0], [1.640625]], mag, 1.0, 0.25)
+    assert done == [0]                                        # 6.5 < 6.5 is false
+    done, _ = pkg.hsadmm_stopping_test([8], 1, 1, [2.0], [4.0], [[0.0], [4.0], [0.0], [1.64]], mag, 1.0, 0.25)
+    assert done == [1]
+    assert Fraction(4 * 4) + Fraction(16) * Fraction(1.640625) == Fraction(13, 2) ** 2
+    rng = np.random.default_rng(15)
+    for trial in range(60):
+        L = int(rng.integers(1, 30))
+        P, n_out = int(rng.integers(1, 9)), int(rng.integers(1, 4))
+        n = rng.integers(1, 10 ** 7, L)
+        rho1, rho2 = 10.0 ** rng.uniform(-3, 1, L), 10.0 ** rng.uniform(-4, 1, L)
+        sq, mag = 10.0 ** rng.uniform(-8, 2, (4, L)), 10.0 ** rng.uniform(-2, 4, (5, L))
+        ea, er = float(10.0 ** rng.uniform(-6, -2)), float(10.0 ** rng.uniform(-5, -1))
+        got, got_all = pkg.hsadmm_stopping_test(n, P, n_out, rho1, rho2, sq, mag, ea, er)
+        want, want_all = oracle.stopping_test(n, P, n_out, rho1, rho2, sq, mag, ea, er)
+        # (a margin of 1e-12 around either threshold: the two sides may group the products differently)
+        r_pri, r_dual = np.sqrt(sq[0] + sq[2]), np.sqrt(P * rho1 ** 2 * sq[1] + n_out * rho2 ** 2 * sq[3])
+        root_p = np.sqrt((P + 1.0) * n * n_out)
+        e_pri = root_p * ea + er * np.maximum(np.sqrt(mag[0] + mag[1]), np.sqrt(P * mag[1] + n_out * mag[2]))
+        e_dual = root_p * ea + er * np.sqrt(rho1 ** 2 * mag[3] + rho2 ** 2 * mag[4])
+        clear = (np.abs(r_pri - e_pri) > 1e-12 * e_pri) & (np.abs(r_dual - e_dual) > 1e-12 * e_dual)
+        assert np.array_equal(np.array(got)[clear], want[clear]), trial
+        if clear.all():
+            assert got_all == want_all
+    ok = dict(n_elems=[4], P=1, n_out=1, rho1=[1.0], rho2=[1.0], residuals=[[0.0]] * 4, magnitudes=[[1.0]] * 5,
+              eps_abs=1e-3, eps_rel=1e-3)
+    assert pkg.hsadmm_stopping_test(**ok) == ([1], True)
+    for key, bad in (("P", 0), ("n_out", 0), ("rho1", [0.0]), ("rho2", [-1.0]), ("eps_abs", -1.0),
+                     ("eps_rel", float("nan")), ("n_elems", [0]), ("residuals", [[-1.0]] * 4),
+                     ("magnitudes", [[float("nan")]] * 5)):
+        args = dict(ok)
+        args[key] = bad
+        with pytest.raises(pkg.HsadmmError):
+            pkg.hsadmm_stopping_test(**args)
+    assert lib.hsadmm_stopping_test(None, 1, 1, 1, None, None, None, None, 0.0, 0.0, None, None) == -1
+    assert lib.hsadmm_layer_sqnorms(None, None, None, None, 0, None) == -1
+
+
 def test_bench_refuses_more_than_one_gpu():
     """This build has no collectives: bench.py --gpus N with N > 1 exits with a message instead of running."""
     import subprocess

@@ -112,3 +112,95 @@ def test_outer_iterations_dynamic_then_frozen_with_adaptive_penalties(seed, R):
             r.dW[j].copy_(torch.from_numpy(W[j]))
         dZg, dZg_next = dZg_next, dZg
     r.close()
+
+
+def test_the_device_loop_stops_at_the_iteration_the_oracle_loop_stops_at():
+    """Algorithm 1 Phase 5's break test on the device path: dynamic outer iterations (full candidate, selection,
+    shrinkage, decompression + Eq. (13)), each followed by the four residual norms, the five magnitudes the
+    thresholds are relative to (hsadmm_layer_sqnorms) and the stopping test, against the same loop of oracle calls.
+    The replicas are pulled towards z_i - u between iterations, as the theta-step of Eq. (7) pulls them, so the
+    residuals do decay.  Both loops must flag the same layers in every iteration and stop at the same one."""
+    import paper_2512_14628_amd as pkg
+    from tests.gpu_harness import GpuRun, bits
+    R, EPS_ABS, EPS_REL = 3, 1e-5, 3e-2
+    shapes = [(48, 16, 9, wk.MODE_FILTER, 20), (64, 32, 1, wk.MODE_CHANNEL, 12), (24, 64, 9, wk.MODE_FILTER, 10),
+              (10, 64, 1, wk.MODE_NONE, 10), (40, 24, 9, wk.MODE_CHANNEL, 9), (32, 40, 1, wk.MODE_FILTER, 8)]
+    wl = wk.custom_workload(shapes, R=R, seed=5, sigma_replica=0.03)
+    t = wl.table()
+    L = len(wl.layers)
+    n_elems = [l.n for l in wl.layers]
+    W, U = wk.generate(wl)
+    W = np.array(W, dtype=np.float32)
+    rng = np.random.default_rng(3)
+    rho1, rho2 = np.full(L, 1.5e-3), np.full(L, 1.5e-4)          # the paper's initial penalties (Section 5.1)
+    a, b = oracle.node_coefficients(rho1, rho2, LAM, M_NODES, R)
+    Zg = (rng.standard_normal(wl.n_arena) * 0.05).astype(np.float32)
+    Vd = np.zeros(wl.n_arena, np.float32)
+    Zi = np.zeros(wl.n_arena, np.float32)
+
+    r = GpuRun(wl, W, U, want_wbar=False, want_sqnorm=False)
+    dev = r.dev
+    coef = torch.from_numpy(np.stack([a, b], axis=1).astype(np.float32).reshape(-1).copy()).to(dev)
+    dZg, dZg_next = torch.from_numpy(Zg).to(dev), torch.empty(wl.n_arena, dtype=torch.float32, device=dev)
+    dVd = torch.from_numpy(Vd).to(dev)
+    r.dZ.zero_()
+    dres = torch.zeros(4 * L, dtype=torch.float64, device=dev)
+    dmag = torch.zeros(L, dtype=torch.float64, device=dev)
+
+    def device_norms(x):
+        pkg.hsadmm_layer_sqnorms(r.plan, x, dmag, r.ws)
+        return dmag.cpu().numpy().copy()
+
+    stopped_oracle = stopped_device = None
+    for it in range(12):
+        # ---- oracle iteration
+        ref = oracle.project_weighted(t, W, U, Zg, Vd, a, b)
+        refc = oracle.compact(t, oracle.add_arenas(t, ref["Z"], Vd), ref["mask"])
+        z_new = oracle.expand(t, refc["packed"], ref["mask"], wl.n_arena)
+        v_new = oracle.dual_inter(t, ref["Z"], z_new, Vd)
+        sq = oracle.residuals(t, W, ref["Z"], Zi, z_new, Zg)
+        mag = np.stack([sum(oracle.layer_sqnorms(t, W[j]) for j in range(R)), oracle.layer_sqnorms(t, ref["Z"]),
+                        oracle.layer_sqnorms(t, z_new), R * oracle.layer_sqnorms(t, ref["U"]),
+                        oracle.layer_sqnorms(t, v_new)])
+        done, every = oracle.stopping_test(n_elems, R, 1, rho1, rho2, sq, mag, EPS_ABS, EPS_REL)
+        # no decision may hang on the last bits (the device sums in another order)
+        r_pri, r_dual = np.sqrt(sq[0] + sq[2]), np.sqrt(R * rho1 ** 2 * sq[1] + rho2 ** 2 * sq[3])
+        root_p = np.sqrt((R + 1.0) * np.array(n_elems))
+        e_pri = root_p * EPS_ABS + EPS_REL * np.maximum(np.sqrt(mag[0] + mag[1]), np.sqrt(R * mag[1] + mag[2]))
+        e_dual = root_p * EPS_ABS + EPS_REL * np.sqrt(rho1 ** 2 * mag[3] + rho2 ** 2 * mag[4])
+        assert (np.abs(r_pri - e_pri) > 1e-6 * e_pri).all() and (np.abs(r_dual - e_dual) > 1e-6 * e_dual).all()
+        # ---- device iteration
+        dprev = r.dZ.clone()
+        pkg.hsadmm_step(r.plan, r.dW, U=r.dU, Zg=dZg, Vd=dVd, coef=coef, Z=r.dZ, mask=r.dmask, packed=r.dpacked,
+                        layer_off=r.doff, kept_idx=r.dkept, workspace=r.ws)
+        pkg.hsadmm_expand_dual(r.plan, r.dpacked, None, dZg_next, r.dZ, dVd, r.ws)
+        pkg.hsadmm_residuals(r.plan, r.dW, r.dZ, dprev, dZg_next, dZg, dres, r.ws)
+        torch.cuda.synchronize()
+        got_sq = dres.cpu().numpy().reshape(4, L)
+        got_mag = np.stack([sum(device_norms(w) for w in r.dW), device_norms(r.dZ), device_norms(dZg_next),
+                            R * device_norms(r.dU), device_norms(dVd)])
+        for li, l in enumerate(wl.layers):
+            tol = max(1e-12, l.n * R * 2.0 ** -53)
+            np.testing.assert_allclose(got_sq[:, li], sq[:, li], rtol=tol, atol=0, err_msg=(it, l.name))
+            np.testing.assert_allclose(got_mag[:, li], mag[:, li], rtol=tol, atol=0, err_msg=(it, l.name))
+        gdone, gevery = pkg.hsadmm_stopping_test(n_elems, R, 1, rho1, rho2, got_sq, got_mag, EPS_ABS, EPS_REL)
+        assert gdone == done.tolist() and gevery == every, it
+        for k, (g, w) in {"Z": (r.dZ, ref["Z"]), "U": (r.dU, ref["U"]), "v": (dVd, v_new), "z": (dZg_next, z_new)}.items():
+            gn = g.cpu().numpy()
+            for l in wl.layers:
+                sl = slice(l.elem_off, l.elem_off + l.n)
+                assert np.array_equal(bits(gn[sl]), bits(w[sl])), (it, k, l.name)
+        if every and stopped_oracle is None:
+            stopped_oracle = it
+        if gevery and stopped_device is None:
+            stopped_device = it
+        if stopped_oracle is not None:
+            break
+        # ---- next iteration: the theta-step's pull towards z_i - u
+        U, Vd, Zi, Zg = ref["U"], v_new, ref["Z"], z_new
+        W = (W + 0.6 * ((ref["Z"] - ref["U"])[None, :] - W)).astype(np.float32)
+        for j in range(R):
+            r.dW[j].copy_(torch.from_numpy(W[j]))
+        dZg, dZg_next = dZg_next, dZg
+    assert stopped_oracle == stopped_device and stopped_oracle is not None and 2 <= stopped_oracle <= 10
+    r.close()
