@@ -416,7 +416,7 @@ def main():
         roofline["traffic_note"] = "rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, profiles/%s" % os.path.basename(traffic_file)
     roofline["grid_workgroups"] = grids.get(dom)
 
-    frozen = weighted = residuals = composite = retrain = retrain_res = None
+    frozen = weighted = residuals = composite = retrain = retrain_res = dynamic_res = None
     if not args.skip_extras:
         # ---- frozen-mask step (Algorithm 1 Phase 3 once the masks are frozen, Section 4.5): the same three calls
         #      with hsadmm_project_frozen in place of hsadmm_project, applying each buffer set's last mask
@@ -535,6 +535,46 @@ def main():
                     "value_GBps": round(w_bytes / w_elapsed / 1e9, 1),
                     "hbm_frac": round(w_bytes / w_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
                     "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in wt.items() if v[1]}}
+
+        # ---- the dynamic iteration with its convergence check (Algorithm 1, Phases 2-5 before the masks freeze): the
+        #      weighted step above with the intra-node residual sums taken by pass 1 for either outcome of every row
+        #      and picked after the selection (hsadmm_step with `residuals` and `Zi_prev`), and the inter-node sums by
+        #      the pass that writes z (hsadmm_retrain_expand) -- against the weighted step followed by a
+        #      hsadmm_residuals pass over R + 4 arenas.
+        for b in sets:
+            b.Zp = torch.randn(n, dtype=torch.float32, device=dev) * 0.05
+        coef_dev = torch.tensor([x for ab in zip(wa, wb_) for x in ab], dtype=torch.float32, device=dev)
+
+        def dynamic_res_step():
+            b = sets[counter[0] % nsets]
+            counter[0] += 1
+            pkg.hsadmm_step(plan, b.W, U=b.U, Zg=b.Zg, Vd=b.Vd, coef=coef_dev, Z=b.Z, mask=b.mask, packed=b.packed,
+                            layer_off=b.off, kept_idx=b.kept, residuals=res_out, Zi_prev=b.Zp, workspace=b.ws,
+                            stream=stream)
+            pkg.hsadmm_retrain_expand(plan, b.packed, None, b.dst, b.Z, b.Vd, b.Zg, res_out, b.ws, stream=stream)
+
+        for _ in range(3):
+            dynamic_res_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(wsteps):
+            dynamic_res_step()
+        torch.cuda.synchronize()
+        dr_elapsed = (time.perf_counter() - t0) / wsteps
+        pkg.hsadmm_kernel_timing_enable(plan, True)
+        for _ in range(wsteps):
+            dynamic_res_step()
+        torch.cuda.synchronize()
+        drt = pkg.hsadmm_kernel_timing_read(plan)
+        pkg.hsadmm_kernel_timing_enable(plan, False)
+        # the weighted step's bytes plus the previous z_i (pass 1) and the previous z (the expansion): two arenas more
+        dr_bytes = w_bytes + 8 * wl.n_total
+        dynamic_res = {"ms_per_step": round(1e3 * dr_elapsed, 4),
+                       "algorithmic_bytes_per_step": dr_bytes,
+                       "value_GBps": round(dr_bytes / dr_elapsed / 1e9, 1),
+                       "hbm_frac": round(dr_bytes / dr_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                       "ms_per_step_with_a_separate_residual_pass": round(1e3 * w_elapsed + 1e-3 * r_us, 4),
+                       "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in drt.items() if v[1]}}
 
         # ---- retraining-phase iteration (Algorithm 1, Phase 3 retraining branch + Phase 4, after the masks are frozen,
         #      Section 4.5): the full candidate under each buffer set's frozen mask, c = z_i + v_i packed by the same
@@ -755,6 +795,7 @@ def main():
         "hinted_step": hinted,
         "frozen_mask_step": frozen,
         "weighted_step": weighted,
+        "dynamic_step_with_residuals": dynamic_res,
         "retraining_step": retrain,
         "retraining_step_with_residuals": retrain_res,
         "residuals": residuals,

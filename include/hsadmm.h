@@ -643,8 +643,17 @@ int hsadmm_retrain_expand(const hsadmm_plan_t* plan, const float* packed, const 
  *   sel              out, optional, groups_total int32: the selection record of this call: the rank of every
  *                    kept group among the kept groups of its layer (BOTH: of its part), -1 for a pruned group
  *   mappings_cached  as in hsadmm_project_frozen_compact (frozen support with shrinkage only)
- *   residuals        out, optional, 4L doubles, rows 0 and 1 as hsadmm_retrain_project writes them; only with
- *                    mask_frozen, Zg / Vd and the shrinkage (UNSUPPORTED otherwise)
+ *   residuals        out, optional, 4L doubles: rows 0 and 1 of the residual norms of Section 3.4 (sum over the
+ *                    replicas of ||W_r - z_i||^2, and ||z_i - z_i(previous)||^2), taken by the passes that form
+ *                    z_i; rows 2 and 3 are left as they are (hsadmm_retrain_expand writes those).  Only with the
+ *                    full candidate (Zg / Vd; UNSUPPORTED otherwise).  Given support: as hsadmm_retrain_project
+ *                    (needs the shrinkage; Z brings the previous z_i).  Selected support: the previous z_i comes
+ *                    in Zi_prev, and every FILTER row's sums are taken for either outcome while its replicas are
+ *                    in registers and picked once the selection is known; CHANNEL and BOTH layers take theirs
+ *                    from one more pass over their own replicas and final z_i.  The order of the fp64 additions
+ *                    is fixed (reproducible) and differs from hsadmm_residuals'.
+ *   Zi_prev          in, with `residuals` and a selected support only: the previous z_i, a full-layout arena
+ *                    that overlaps neither Z nor U
  *   workspace, workspace_bytes, hip_stream   as for the named calls (a frozen support without shrinkage needs none)
  * Errors: those of the named call that the fields select; UNSUPPORTED also for sel_prev with Zg / Vd.
  */
@@ -658,6 +667,7 @@ typedef struct {
     const float* Zg;
     const float* Vd;
     const float* coef;
+    const float* Zi_prev;
     const uint8_t* mask_frozen;
     const int32_t* sel_prev;
     float* Z;
@@ -713,7 +723,7 @@ int hsadmm_version(void);
  * profile taken elsewhere can be matched to the plan it is quoted for.
  * Errors: INVALID_ARGUMENT, HOST_MEMORY, HIP.
  */
-#define HSADMM_KERNEL_COUNT 27
+#define HSADMM_KERNEL_COUNT 28
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 int hsadmm_kernel_grid(const hsadmm_plan_t* plan, int kernel_id);

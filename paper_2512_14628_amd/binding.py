@@ -39,7 +39,7 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_adapt_penalties", "hsadmm_scale_layers", "hsadmm_project_compact_static",
            "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid",
            "hsadmm_layer_sqnorms", "hsadmm_stopping_test")
-KERNEL_COUNT = 27
+KERNEL_COUNT = 28
 
 
 class HsadmmError(RuntimeError):
@@ -63,7 +63,7 @@ _STEP_FIELDS = (
     ("R", ctypes.c_int32, "replica_count"),
     ("mappings_cached", ctypes.c_int32, "flag"),
     ("U", _vp, "dev"), ("U_out", _vp, "dev"), ("Zg", _vp, "dev"), ("Vd", _vp, "dev"), ("coef", _vp, "dev"),
-    ("mask_frozen", _vp, "dev"), ("sel_prev", _vp, "dev"),
+    ("Zi_prev", _vp, "dev"), ("mask_frozen", _vp, "dev"), ("sel_prev", _vp, "dev"),
     ("Z", _vp, "dev"), ("Wbar", _vp, "dev"), ("mask", _vp, "dev"), ("sqnorm", _vp, "dev"), ("sel", _vp, "dev"),
     ("packed", _vp, "dev"), ("layer_off", _vp, "dev"), ("kept_idx", _vp, "dev"), ("residuals", _vp, "dev"),
     ("workspace", _vp, "dev"),

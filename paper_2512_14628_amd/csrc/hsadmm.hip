@@ -99,10 +99,10 @@ hipError_t for_replica_count(int R, F&& f)
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct WsLayout {
-    size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, work, total;
+    size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, work, rowres, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kPass1Hinted, kHintedRepair, kSqnormPart, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kPass1Hinted, kHintedRepair, kSqnormPart, kResPick, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 constexpr size_t kRepairGrid = 2048;       // workgroups of the repair pass under a prediction: 8 per compute unit
@@ -445,6 +445,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->ws.kept_idx = off;   off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
         p->ws.respart = off;    off = align_up(off + sizeof(double) * 4 * p->items_rows.size(), 256);
         p->ws.work = off;       off = align_up(off + sizeof(int32_t) * (kWorkHeader + p->items_rows.size()), 256);
+        p->ws.rowres = off;     off = align_up(off + sizeof(double) * 4 * (size_t)gb, 256);
         p->ws.total = off;
     } catch (...) {   // host allocation failure while building the tables
         delete p;
@@ -946,10 +947,16 @@ int hsadmm_plan_set_node_weights(hsadmm_plan_t* p, const float* a, const float* 
 static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_replicas, int32_t R, float* U,
                                  const float* Zg, const float* Vd, float* Z, float* Wbar, uint8_t* mask,
                                  double* sqnorm, const CompactOut* out, void* workspace, size_t workspace_bytes,
-                                 void* hip_stream, const float* coef_arg = nullptr, int32_t* sel_out = nullptr)
+                                 void* hip_stream, const float* coef_arg = nullptr, int32_t* sel_out = nullptr,
+                                 const float* Zi_prev = nullptr, double* residuals = nullptr)
 {
     if (!p || !W_replicas || !U || !Zg || !Vd || !Z || !mask || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
     if (!is_aligned(coef_arg, 4) || !is_aligned(sel_out, 4)) return HSADMM_ERR_INVALID_ARGUMENT;
+    // the intra-node residual norms on the way: both or neither of the previous z_i and the place for the norms
+    if ((Zi_prev == nullptr) != (residuals == nullptr)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (residuals && (!is_aligned(Zi_prev, 16) || !is_aligned(residuals, 8) || spans_overlap(Zi_prev, Z, p->arena_elems) ||
+                      spans_overlap(Zi_prev, U, p->arena_elems)))
+        return HSADMM_ERR_INVALID_ARGUMENT;
     const float* const coef = coef_arg ? coef_arg : p->d_coef;
     if (out && (!out->packed || !out->layer_off || !out->kept_idx || !is_aligned(out->packed, 16) ||
                 !is_aligned(out->layer_off, 8) || !is_aligned(out->kept_idx, 4)))
@@ -973,15 +980,24 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     w.p.park_mean = R >= 3 ? 1 : 0;
     w.p.Zg = Zg; w.p.Vd = Vd; w.p.coef = coef;
     w.Zg = Zg; w.Vd = Vd; w.coef = coef;
+    w.Zi_prev = Zi_prev;
+    w.rowres = reinterpret_cast<double*>(ws + p->ws.rowres);
     const unsigned grid = (unsigned)p->items_proj.size();
     const WorkItem* items = p->d_items_proj;
     hipError_t e;
-    e = for_replica_count<false>(R, [&](auto c) {
-        return launch(p, kWKeys, weighted_pass1<decltype(c)::value>, grid, kBlock, s, items, w, (int)R);
-    });
+    if (residuals)
+        e = for_replica_count<false>(R, [&](auto c) {
+            return launch(p, kWKeys, weighted_pass1<decltype(c)::value, true>, grid, kBlock, s, items, w, (int)R);
+        });
+    else
+        e = for_replica_count<false>(R, [&](auto c) {
+            return launch(p, kWKeys, weighted_pass1<decltype(c)::value>, grid, kBlock, s, items, w, (int)R);
+        });
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     // (the weighted candidate of a BOTH layer is formed again from its parked mean, U, Zg and Vd)
-    if (run_selection(p, w.p.key, w.p.colpart, w.p, mask, ws, s, sel_out) != hipSuccess) return HSADMM_ERR_HIP;
+    WorkList wl{};
+    if (residuals) { wl.rowres = w.rowres; wl.res_out = residuals; }       // FILTER / unconstrained layers: rows 0 and 1
+    if (run_selection(p, w.p.key, w.p.colpart, w.p, mask, ws, s, sel_out, wl) != hipSuccess) return HSADMM_ERR_HIP;
     const uint8_t* cm = mask;
     PackOut po{};
     if (out) {
@@ -1035,6 +1051,25 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
                        (const WorkItem*)p->d_items_none, (const float*)Z, Vd, po.pos, po.cnt, po.kept_idx,
                        po.n_layers, po.layer_off, po.packed, po.co);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
+    }
+    if (residuals) {
+        // (the selection has added up rows 0 and 1 of the FILTER and unconstrained layers)
+        // CHANNEL and BOTH layers: their share of rows 0 and 1 from a pass over their final values
+        double* part = reinterpret_cast<double*>(ws + p->ws.respart);
+        if (!p->items_chan.empty() || !p->items_bfinal.empty()) {
+            ResidualArgs ra{};
+            for (int r = 0; r < R; ++r) ra.W[r] = W_replicas[r];
+            ra.Zi = Z; ra.Zi_prev = Zi_prev; ra.part = part;
+            e = for_replica_count<false>(R, [&](auto c) {
+                return launch(p, kResPart, residual_partials<decltype(c)::value>, (unsigned)p->items_rows.size(), kBlock,
+                              s, (const WorkItem*)p->d_items_rows, ra, (int)R,
+                              (1 << HSADMM_MODE_CHANNEL) | (1 << HSADMM_MODE_BOTH));
+            });
+            if (e != hipSuccess) return HSADMM_ERR_HIP;
+            e = launch(p, kResPick, residual_pick, (unsigned)p->layers.size(), kBlock, s, (const DevLayer*)p->d_layers,
+                       (int)p->layers.size(), (const double*)part, residuals);
+            if (e != hipSuccess) return HSADMM_ERR_HIP;
+        }
     }
     return HSADMM_OK;
 }
@@ -1167,6 +1202,7 @@ int hsadmm_step(const hsadmm_plan_t* p, const hsadmm_step_args_t* x)
         // retraining branch: the given mask replaces the selection; nothing is selected, predicted or recorded
         if (x->mask || x->sqnorm || x->sel_prev || x->sel) return HSADMM_ERR_INVALID_ARGUMENT;
         if (x->residuals && !(weighted && pack)) return HSADMM_ERR_UNSUPPORTED;
+        if (x->Zi_prev) return HSADMM_ERR_INVALID_ARGUMENT;              // (under a frozen support Z itself brings the previous z_i)
         if (weighted)
             return weighted_frozen_impl(p, x->W_replicas, x->R, x->U, x->Zg, x->Vd, x->Z, x->Wbar, x->mask_frozen,
                                         pack ? &out : nullptr, x->mappings_cached, x->workspace, x->workspace_bytes,
@@ -1177,12 +1213,13 @@ int hsadmm_step(const hsadmm_plan_t* p, const hsadmm_step_args_t* x)
                                                  x->workspace, x->workspace_bytes, x->hip_stream);
         return hsadmm_project_frozen(p, x->W_replicas, x->R, x->U, x->Z, x->Wbar, x->mask_frozen, x->hip_stream);
     }
-    if (x->mappings_cached || x->residuals) return HSADMM_ERR_UNSUPPORTED;  // (the norms of a dynamic step: hsadmm_residuals)
+    if (x->mappings_cached) return HSADMM_ERR_UNSUPPORTED;
+    if (x->residuals && !weighted) return HSADMM_ERR_UNSUPPORTED;          // (for the plain candidate: hsadmm_residuals)
     if (weighted) {
         if (x->sel_prev) return HSADMM_ERR_UNSUPPORTED;                    // no predicted form of the weighted pass yet
         return project_weighted_impl(p, x->W_replicas, x->R, x->U, x->Zg, x->Vd, x->Z, x->Wbar, x->mask, x->sqnorm,
                                      pack ? &out : nullptr, x->workspace, x->workspace_bytes, x->hip_stream, x->coef,
-                                     x->sel);
+                                     x->sel, x->Zi_prev, x->residuals);
     }
     return project_impl(p, x->W_replicas, x->R, x->U, x->Z, x->Wbar, x->mask, x->sqnorm, pack ? &out : nullptr,
                         x->workspace, x->workspace_bytes, x->hip_stream, x->sel_prev, x->sel, x->U_out);
@@ -1220,7 +1257,7 @@ int hsadmm_residuals(const hsadmm_plan_t* p, const float* const* W_replicas, int
     const WorkItem* items = p->d_items_rows;
     hipError_t e;
     e = for_replica_count<false>(R, [&](auto c) {
-        return launch(p, kResPart, residual_partials<decltype(c)::value>, grid, kBlock, s, items, a, (int)R);
+        return launch(p, kResPart, residual_partials<decltype(c)::value>, grid, kBlock, s, items, a, (int)R, 0xf);
     });
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     e = launch(p, kResFinish, residual_finish, (unsigned)p->layers.size(), kBlock, s,
@@ -1464,6 +1501,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kPass1Hinted: return "project_pass1_hinted";
         case kHintedRepair: return "hinted_repair";
         case kSqnormPart: return "sqnorm_partials";
+        case kResPick: return "residual_pick";
         default: return "";
     }
 }

@@ -75,6 +75,10 @@ struct WorkList {
     int32_t* work;
     int pack;                  // a compaction follows: kept rows whose rank has moved are listed as well
     CopyOut co;                // where the selection hands the caller layer_off / kept_idx itself (nulls: it does not)
+    // residual norms taken on the way by the weighted pass 1 (null: none): for FILTER and unconstrained layers the
+    // selection adds up, per layer, the sums of the outcome every group got, rows 0 and 1 of res_out
+    const double* rowres;
+    double* res_out;
 };
 
 // What a kernel needs to pack rows as it forms them: the index mappings (in the workspace), the packed buffer

@@ -19,12 +19,16 @@ struct ResidualArgs {
 
 // One workgroup per row item (a contiguous span of one layer): per-thread fp64 sums of the four
 // squared differences, combined by a butterfly per wave and in wave order through LDS.
+// modes: bit m set = the items of layers of mode m are processed (the others return at once and leave their
+// partial sums alone).
 template <int R>
-__global__ __launch_bounds__(kBlock) void residual_partials(const WorkItem* __restrict__ items, ResidualArgs a, int Rrt)
+__global__ __launch_bounds__(kBlock) void residual_partials(const WorkItem* __restrict__ items, ResidualArgs a, int Rrt,
+                                                            int modes)
 {
     __shared__ double red[kWaves][4];
     const int RR = R > 0 ? R : Rrt;
     const WorkItem it = items[blockIdx.x];
+    if (((modes >> item_mode(it)) & 1) == 0) return;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int64_t len = (int64_t)it.nr * it.row_len;
@@ -130,6 +134,34 @@ __global__ __launch_bounds__(kBlock) void residual_finish(const DevLayer* __rest
     if (lane == 0) for (int k = 0; k < 4; ++k) red[wave][k] = s[k];
     __syncthreads();
     if ((int)threadIdx.x >= k0 && (int)threadIdx.x < k1) {
+        double t = red[0][threadIdx.x];
+        for (int w = 1; w < kWaves; ++w) t += red[w][threadIdx.x];
+        out[(int64_t)threadIdx.x * nL + l] = t;
+    }
+}
+
+// Rows 0 and 1 of the residual norms of the CHANNEL and BOTH layers after a dynamic projection that took the norms
+// on the way (the selection itself finishes the FILTER and unconstrained layers): one workgroup per layer adds the
+// partial sums of the layer's row items, as residual_finish does; workgroups of other layers return at once.
+__global__ __launch_bounds__(kBlock) void residual_pick(const DevLayer* __restrict__ layers, int nL,
+                                                        const double* __restrict__ part, double* __restrict__ out)
+{
+    __shared__ double red[kWaves][2];
+    const int l = blockIdx.x;
+    const DevLayer L = layers[l];
+    if (L.mode == HSADMM_MODE_FILTER || L.mode == HSADMM_MODE_NONE) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    double s0 = 0.0, s1 = 0.0;
+    for (int i = threadIdx.x; i < L.rows_items; i += kBlock) {
+        s0 += part[(int64_t)(L.rows_item0 + i) * 4 + 0];
+        s1 += part[(int64_t)(L.rows_item0 + i) * 4 + 1];
+    }
+    s0 = wave_xor_sum(s0, kWave);
+    s1 = wave_xor_sum(s1, kWave);
+    if (lane == 0) { red[wave][0] = s0; red[wave][1] = s1; }
+    __syncthreads();
+    if (threadIdx.x < 2) {
         double t = red[0][threadIdx.x];
         for (int w = 1; w < kWaves; ++w) t += red[w][threadIdx.x];
         out[(int64_t)threadIdx.x * nL + l] = t;

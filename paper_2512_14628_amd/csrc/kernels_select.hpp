@@ -340,6 +340,34 @@ __device__ __forceinline__ void list_changed_layer(const DevLayer& L, const Work
     for (int i = tid; i < L.rows_items; i += kScanBlock) wl.work[kWorkHeader + *slot + i] = L.rows_item0 + i;
 }
 
+// Rows 0 and 1 of the residual norms of a FILTER or unconstrained layer whose pass 1 took, per group, the sums of
+// either outcome: rowres[4g + 0, 2] if group g is kept, rowres[4g + 1, 3] if it is pruned.  Thread t adds the groups
+// t, t + 1024, ... in order; threads are combined by a butterfly per wave and the waves in order: a fixed order.
+__device__ __forceinline__ void pick_residuals(const DevLayer& L, int l, int n_layers, const uint8_t* ml,
+                                               const WorkList& wl, double (*red)[2])
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    __syncthreads();                                             // the mask written above is visible to the workgroup
+    double s0 = 0.0, s1 = 0.0;
+    for (int g = tid; g < L.G; g += kScanBlock) {
+        const bool kept = ml[g] != 0;
+        const double* r = wl.rowres + 4 * (int64_t)(L.group_base + g);
+        s0 += kept ? r[0] : r[1];
+        s1 += kept ? r[2] : r[3];
+    }
+    s0 = wave_xor_sum(s0, kWave);
+    s1 = wave_xor_sum(s1, kWave);
+    if (lane == 0) { red[wave][0] = s0; red[wave][1] = s1; }
+    __syncthreads();
+    if (tid < 2) {
+        double t = red[0][tid];
+        for (int w = 1; w < kScanWaves; ++w) t += red[w][tid];
+        wl.res_out[(int64_t)tid * n_layers + l] = t;
+    }
+}
+
 // One workgroup per layer: finish the CHANNEL keys, then write the layer's mask.
 // stage 0: workgroup b takes layer b; of a BOTH layer it selects the filters (its first c_out groups).
 // stage 1: workgroup b takes layer layer_list[b], a BOTH layer, and selects its channels (the c_in
@@ -354,6 +382,7 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
 {
     __shared__ TopkShared sh;
     __shared__ int work_slot;
+    __shared__ double res_red[kScanWaves][2];
     const DevLayer L = layers[stage == 0 ? (int)blockIdx.x : layer_list[blockIdx.x]];
     const bool both = L.mode == HSADMM_MODE_BOTH;
     const bool channels = L.mode == HSADMM_MODE_CHANNEL || (both && stage == 1);
@@ -434,6 +463,8 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
     } else {
         topk_layer<false>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l, ck_l);
     }
+    if (wl.res_out && stage == 0 && (L.mode == HSADMM_MODE_FILTER || L.mode == HSADMM_MODE_NONE))
+        pick_residuals(L, (int)blockIdx.x, n_layers, ml, wl, res_red);
     if (wl.sel_prev && L.mode == HSADMM_MODE_FILTER)
         list_repairs(L, wl, row_items, pos_l, &sh.hist[0][0], sh.wtot, &work_slot);
     else if (wl.sel_prev && L.mode == HSADMM_MODE_CHANNEL)

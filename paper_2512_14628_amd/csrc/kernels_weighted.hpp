@@ -13,6 +13,9 @@ struct WeightedArgs {
     const float* Zg;      // global consensus z
     const float* Vd;      // inter-node dual v_i
     const float* coef;    // per layer: a_l, b_l
+    // weighted_pass1<R, true> (the pass that also takes the intra-node residual sums of Section 3.4):
+    const float* Zi_prev; // the previous z_i, a buffer other than Z
+    double* rowres;       // 4 doubles per group of the FILTER and unconstrained layers, see weighted_pass1
 };
 
 // z~ = fl(fl(a t) + fl(b q)) with t = Wbar + U, q = z - v, for 4 (or 1) adjacent elements; no stores.
@@ -60,6 +63,69 @@ __device__ __forceinline__ void wcand4x2(const WeightedArgs& w, int Rrt, int64_t
     zt1 = at1 + bq1;
 }
 
+// wcand4 that also adds the element's terms of the intra-node residual sums for either outcome of its row:
+//   acc[0] += sum_j (W_j - z~)^2   acc[2] += (z~ - z_prev)^2      if the row is kept (z_i = z~)
+//   acc[1] += sum_j W_j^2          acc[3] += z_prev^2             if it is pruned (z_i = 0)
+// in fp64 from the fp32 values.  With a compile-time R the replicas' values stay in registers, else they are read
+// a second time.
+template <int R>
+__device__ __forceinline__ void wcand4_res(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
+                                           v4f& wb, v4f& u, v4f& zt, double acc[4])
+{
+    const int RR = R > 0 ? R : Rrt;
+    constexpr int kHeld = R > 0 ? R : 1;
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    v4f held[kHeld];
+    v4f s = ld4(w.p.W[0] + e);
+    if (R > 0) held[0] = s;
+#pragma unroll
+    for (int r = 1; r < RR; ++r) {
+        const v4f x = ld4(w.p.W[r] + e);
+        if (R > 0) held[r] = x;
+        s = s + x;
+    }
+    u = ld4(w.p.Ur + e);
+    const v4f q = ld4(w.Zg + e) - ld4(w.Vd + e);
+    const v4f zp = ld4(w.Zi_prev + e);
+    wb = s * w.p.inv_R;
+    const v4f t = wb + u;
+    const v4f at = t * al;
+    const v4f bq = q * bl;
+    zt = at + bq;
+#pragma unroll
+    for (int r = 0; r < RR; ++r) {
+        const v4f x = R > 0 ? held[r] : ld4(w.p.W[r] + e);
+        acc[0] = sqd4(acc[0], x, zt);
+        acc[1] = sqd4(acc[1], x, zero4);
+    }
+    acc[2] = sqd4(acc[2], zt, zp);
+    acc[3] = sqd4(acc[3], zero4, zp);
+}
+
+template <int R>
+__device__ __forceinline__ void wcand1_res(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
+                                           float& wb, float& u, float& zt, double acc[4])
+{
+    const int RR = R > 0 ? R : Rrt;
+    float s = ld1(w.p.W[0] + e);
+    for (int r = 1; r < RR; ++r) s = s + ld1(w.p.W[r] + e);
+    u = ld1(w.p.Ur + e);
+    const float q = ld1(w.Zg + e) - ld1(w.Vd + e);
+    const float zp = ld1(w.Zi_prev + e);
+    wb = s * w.p.inv_R;
+    const float t = wb + u;
+    const float at = t * al;
+    const float bq = q * bl;
+    zt = at + bq;
+    for (int r = 0; r < RR; ++r) {
+        const float x = ld1(w.p.W[r] + e);
+        acc[0] = sqd(acc[0], x, zt);
+        acc[1] = sqd(acc[1], x, 0.f);
+    }
+    acc[2] = sqd(acc[2], zt, zp);
+    acc[3] = sqd(acc[3], 0.f, zp);
+}
+
 template <int R>
 __device__ __forceinline__ void wcand1(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
                                        float& wb, float& u, float& zt)
@@ -86,10 +152,15 @@ __device__ __forceinline__ void wcand1(const WeightedArgs& w, int Rrt, int64_t e
 //   BOTH     the filter norms of z~; the mean Wbar is parked in Z and U is left alone: composite_colsums and the
 //            final pass (the frozen-mask kernel in its weighted form) form z~ again from Z, U, Zg and Vd;
 //   CHANNEL  partial column sums; with 3 or more replicas the mean is parked in Z for the final pass.
-template <int R>
+// RES: the pass also takes, per row of a FILTER or unconstrained layer, the row's share of the intra-node residual
+// sums of Section 3.4 for either outcome of the row (see wcand4_res) and leaves them in rowres[4 * group ..]; after
+// the selection select_topk adds up, per layer, the sums of the outcome every row got.  The previous z_i is read
+// from a buffer of its own (Z receives the stash).  CHANNEL and BOTH layers take no part in this here: their sums
+// come from a pass over their final values (residual_partials on their row items).
+template <int R, bool RES = false>
 __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt)
 {
-    __shared__ double wsum[kWaves];
+    __shared__ double wsum[kWaves][5];
     __shared__ double part[kWaves][kWave * 4];
     const WorkItem it = items[blockIdx.x];
     const int lane = threadIdx.x & (kWave - 1);
@@ -112,12 +183,15 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
             const bool active = rr < it.nr;
             const int64_t base = it.base + (int64_t)rr * row_len;
             double acc = 0.0;
+            double res[4] = {0.0, 0.0, 0.0, 0.0};
+            const bool take_res = RES && !park;
             if (active) {
                 if (vec) {
                     const int nchunk = row_len >> 2;
                     int c = j;
                     // two chunks of the row at a time: all their loads are issued before the first store
-                    for (; c + lpr < nchunk; c += 2 * lpr) {
+                    // (one at a time when the residual sums are taken: the replicas' values stay live then)
+                    for (; !take_res && c + lpr < nchunk; c += 2 * lpr) {
                         const int64_t e0 = base + ((int64_t)c << 2), e1 = base + ((int64_t)(c + lpr) << 2);
                         v4f wb0, u0, zt0, wb1, u1, zt1;
                         wcand4x2<R>(w, Rrt, e0, e1, al, bl, wb0, u0, zt0, wb1, u1, zt1);
@@ -136,8 +210,9 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
                     }
                     for (; c < nchunk; c += lpr) {
                         v4f wb, u, zt;
-                        wcand4<R>(w, Rrt, base + ((int64_t)c << 2), al, bl, wb, u, zt);
                         const int64_t e = base + ((int64_t)c << 2);
+                        if (take_res) wcand4_res<R>(w, Rrt, e, al, bl, wb, u, zt, res);
+                        else wcand4<R>(w, Rrt, e, al, bl, wb, u, zt);
                         if (park) {
                             st4(w.p.Z + e, wb);
                         } else {
@@ -150,7 +225,8 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
                 } else {
                     for (int c = j; c < row_len; c += lpr) {
                         float wb, u, zt;
-                        wcand1<R>(w, Rrt, base + c, al, bl, wb, u, zt);
+                        if (take_res) wcand1_res<R>(w, Rrt, base + c, al, bl, wb, u, zt, res);
+                        else wcand1<R>(w, Rrt, base + c, al, bl, wb, u, zt);
                         if (park) {
                             st1(w.p.Z + base + c, wb);
                         } else {
@@ -165,14 +241,29 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
             if (!wide) {
                 acc = wave_xor_sum(acc, lpr);
                 if (active && j == 0) w.p.key[it.g0 + rr] = acc;
+                if (take_res) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        res[k] = wave_xor_sum(res[k], lpr);
+                        if (active && j == 0) w.rowres[4 * (int64_t)(it.g0 + rr) + k] = res[k];
+                    }
+                }
             } else {
                 acc = wave_xor_sum(acc, kWave);
-                if (lane == 0) wsum[wave] = acc;
+                if (take_res) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) res[k] = wave_xor_sum(res[k], kWave);
+                }
+                if (lane == 0) {
+                    wsum[wave][0] = acc;
+                    if (take_res) { wsum[wave][1] = res[0]; wsum[wave][2] = res[1]; wsum[wave][3] = res[2]; wsum[wave][4] = res[3]; }
+                }
                 __syncthreads();
-                if (threadIdx.x == 0) {
-                    double s = wsum[0];
-                    for (int v = 1; v < kWaves; ++v) s += wsum[v];
-                    w.p.key[it.g0 + rr] = s;
+                if (threadIdx.x < (take_res ? 5 : 1)) {
+                    double s = wsum[0][threadIdx.x];
+                    for (int v = 1; v < kWaves; ++v) s += wsum[v][threadIdx.x];
+                    if (threadIdx.x == 0) w.p.key[it.g0 + rr] = s;
+                    else w.rowres[4 * (int64_t)(it.g0 + rr) + (threadIdx.x - 1)] = s;
                 }
                 __syncthreads();
             }

@@ -160,3 +160,111 @@ def test_phase_5_on_the_device_residuals_then_penalties_then_rescaled_duals():
         assert np.array_equal(bits(gU[sl]), bits(oU[sl])), l.name
         assert np.array_equal(bits(gV[sl]), bits(oV[sl])), l.name
     r.close()
+
+
+def _dynamic_with_norms(wl, seed):
+    """A dynamic outer iteration that takes the intra-node residual norms on the way (hsadmm_step with Zg / Vd,
+    `residuals` and `Zi_prev`) against the plain calls it extends and the oracle: every other output the bits of
+    hsadmm_project_weighted_compact, rows 0 and 1 within the summation tolerance of oracle.residuals, rows 2 and 3
+    untouched; then hsadmm_retrain_expand completes the four norms."""
+    import paper_2512_14628_amd as pkg
+    rng = np.random.default_rng(seed)
+    W, U = wk.generate(wl, threads=8)
+    t = wl.table()
+    L = len(wl.layers)
+    a, b = oracle.node_coefficients(rng.uniform(1e-3, 2e-3, L), rng.uniform(1e-4, 3e-4, L), 1e-4, 16, wl.R)
+    Zg = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.05
+    Vd = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.01
+    Zp = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.05
+    Zp[rng.random(wl.n_arena) < 0.5] = 0.0                       # a previous z_i is sparse
+    ref = oracle.project_weighted(t, W, U, Zg, Vd, a, b)
+    refc = oracle.compact(t, oracle.add_arenas(t, ref["Z"], Vd), ref["mask"])
+    z_new = oracle.expand(t, refc["packed"], ref["mask"], wl.n_arena)
+    sq = oracle.residuals(t, W, ref["Z"], Zp, z_new, Zg)
+    dev = torch.device("cuda:0")
+    coef = torch.from_numpy(np.stack([a, b], axis=1).astype(np.float32).reshape(-1).copy()).to(dev)
+
+    def bufs():
+        plan = pkg.Plan(t)
+        d = {"plan": plan, "W": [torch.from_numpy(W[r]).to(dev) for r in range(wl.R)],
+             "U": torch.from_numpy(U).to(dev), "Zg": torch.from_numpy(Zg).to(dev), "Vd": torch.from_numpy(Vd).to(dev),
+             "Z": torch.full((wl.n_arena,), float("nan"), dtype=torch.float32, device=dev),
+             "mask": torch.full((plan.groups_total,), 7, dtype=torch.uint8, device=dev),
+             "ws": torch.full((plan.workspace_bytes,), 0xCD, dtype=torch.uint8, device=dev),
+             "packed": torch.full((plan.packed_capacity_elems,), float("nan"), dtype=torch.float32, device=dev),
+             "off": torch.zeros(L + 1, dtype=torch.int64, device=dev),
+             "kept": torch.full((plan.groups_total,), -1, dtype=torch.int32, device=dev)}
+        return d
+
+    x, y = bufs(), bufs()
+    pkg.hsadmm_step(x["plan"], x["W"], U=x["U"], Zg=x["Zg"], Vd=x["Vd"], coef=coef, Z=x["Z"], mask=x["mask"],
+                    packed=x["packed"], layer_off=x["off"], kept_idx=x["kept"], workspace=x["ws"])
+    res = torch.full((4 * L,), -7.0, dtype=torch.float64, device=dev)
+    dZp = torch.from_numpy(Zp).to(dev)
+    pkg.hsadmm_step(y["plan"], y["W"], U=y["U"], Zg=y["Zg"], Vd=y["Vd"], coef=coef, Z=y["Z"], mask=y["mask"],
+                    packed=y["packed"], layer_off=y["off"], kept_idx=y["kept"], workspace=y["ws"], residuals=res,
+                    Zi_prev=dZp)
+    torch.cuda.synchronize()
+    assert np.array_equal(y["mask"].cpu().numpy(), ref["mask"])
+    for k in ("U", "Z", "mask", "packed", "off", "kept"):
+        assert np.array_equal(x[k].cpu().numpy().view(np.uint8), y[k].cpu().numpy().view(np.uint8)), k
+    for l in wl.layers:
+        sl = slice(l.elem_off, l.elem_off + l.n)
+        assert np.array_equal(y["Z"].cpu().numpy()[sl].view(np.uint32), ref["Z"][sl].view(np.uint32)), l.name
+    got = res.cpu().numpy().reshape(4, L)
+    assert np.all(got[2:] == -7.0)
+    for li, l in enumerate(wl.layers):
+        tol = max(1e-12, l.n * wl.R * 2.0 ** -53)
+        np.testing.assert_allclose(got[:2, li], sq[:2, li], rtol=tol, atol=0, err_msg=l.name)
+    # a second run gives the same bits
+    y2 = bufs()
+    res2 = torch.full_like(res, -7.0)
+    pkg.hsadmm_step(y2["plan"], y2["W"], U=y2["U"], Zg=y2["Zg"], Vd=y2["Vd"], coef=coef, Z=y2["Z"], mask=y2["mask"],
+                    packed=y2["packed"], layer_off=y2["off"], kept_idx=y2["kept"], workspace=y2["ws"], residuals=res2,
+                    Zi_prev=dZp)
+    # the inter-node half on top: decompression + Eq. (13) with rows 2 and 3
+    dz = torch.full((wl.n_arena,), float("nan"), dtype=torch.float32, device=dev)
+    pkg.hsadmm_retrain_expand(y2["plan"], y2["packed"], None, dz, y2["Z"], y2["Vd"], y2["Zg"], res2, y2["ws"])
+    torch.cuda.synchronize()
+    got2 = res2.cpu().numpy().reshape(4, L)
+    assert np.array_equal(got2[:2].view(np.uint64), got[:2].view(np.uint64))
+    for li, l in enumerate(wl.layers):
+        tol = max(1e-12, l.n * wl.R * 2.0 ** -53)
+        np.testing.assert_allclose(got2[:, li], sq[:, li], rtol=tol, atol=0, err_msg=l.name)
+    for d in (x, y, y2):
+        d["plan"].close()
+
+
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 8])
+def test_dynamic_iteration_takes_its_intra_node_norms_on_the_way(R):
+    shapes = [(96, 16, 1, wk.MODE_FILTER, 40), (80, 64, 9, wk.MODE_FILTER, 30), (24, 512, 9, wk.MODE_FILTER, 9),
+              (64, 3, 49, wk.MODE_FILTER, 20), (37, 5, 7, wk.MODE_FILTER, 36), (300, 1, 1, wk.MODE_FILTER, 1),
+              (96, 128, 1, wk.MODE_CHANNEL, 50), (48, 40, 9, wk.MODE_BOTH, 30, 21), (10, 128, 1, wk.MODE_NONE, 10),
+              (33, 7, 1, wk.MODE_NONE, 33), (70, 2100, 1, wk.MODE_FILTER, 28), (50, 24, 9, wk.MODE_CHANNEL, 10)]
+    _dynamic_with_norms(wk.custom_workload(shapes, R=R, seed=60 + R, sigma_replica=0.03), 70 + R)
+
+
+def test_dynamic_iteration_with_norms_on_resnet50_shapes():
+    oracle.set_threads(8)
+    _dynamic_with_norms(wk.make_workload("resnet50"), 3)
+
+
+def test_dynamic_norms_want_both_the_previous_consensus_and_a_place_for_the_norms():
+    import paper_2512_14628_amd as pkg
+    wl = wk.custom_workload([(16, 8, 1, wk.MODE_FILTER, 4)], R=2, seed=1, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    dev = torch.device("cuda:0")
+    plan = pkg.Plan(wl.table())
+    n = wl.n_arena
+    f = lambda: torch.zeros(n, dtype=torch.float32, device=dev)        # noqa: E731
+    dW, dU, dZ, dZg, dVd, dZp = [f(), f()], f(), f(), f(), f(), f()
+    mask = torch.zeros(plan.groups_total, dtype=torch.uint8, device=dev)
+    ws = torch.zeros(plan.workspace_bytes, dtype=torch.uint8, device=dev)
+    res = torch.zeros(4, dtype=torch.float64, device=dev)
+    common = dict(U=dU, Zg=dZg, Vd=dVd, Z=dZ, mask=mask, workspace=ws)
+    assert pkg.hsadmm_step(plan, dW, residuals=res, check=False, **common) == -1          # no Zi_prev
+    assert pkg.hsadmm_step(plan, dW, Zi_prev=dZp, check=False, **common) == -1            # no place for the norms
+    assert pkg.hsadmm_step(plan, dW, residuals=res, Zi_prev=dZ, check=False, **common) == -1   # Zi_prev is Z
+    assert pkg.hsadmm_step(plan, dW, U=dU, Z=dZ, mask=mask, workspace=ws, residuals=res, Zi_prev=dZp, check=False) == -4
+    assert pkg.hsadmm_step(plan, dW, residuals=res, Zi_prev=dZp, **common) == 0
+    plan.close()
