@@ -399,3 +399,30 @@ def test_a_captured_graph_follows_coefficients_that_change_between_replays():
         assert float(scratch.sum().item()) == float((it + 1) * (1 << 18))
     x.plan.close()
     y.plan.close()
+
+
+@pytest.mark.parametrize("name", ["resnet50", "resnet152", "wrn50_2"])
+def test_named_workloads_at_full_size_under_predictions(name):
+    """The benchmark's workloads at full size, in the launch configuration bench.py times for `hinted_step`: the step
+    predicted by the right selection and by one with a tenth of every layer's kept groups exchanged, dual in place
+    and out of place, every element of every output against the oracle."""
+    from tests.gpu_harness import check_against_oracle
+    oracle.set_threads(16)
+    wl = wk.make_workload(name)
+    W, U = wk.generate(wl, threads=16)
+    t = wl.table()
+    ref = oracle.project(t, W, U, want_wbar=True)
+    refc = oracle.compact(t, ref["Z"], ref["mask"])
+    want_sel = record_of(wl, ref["mask"])
+    rng = np.random.default_rng(77)
+    b = _Bufs(wl, W, U, 1)
+    dev = b.U.device
+    for rec in (want_sel, record_of(wl, degrade(wl, ref["mask"], 0.1, rng))):
+        for out_of_place in (False, True):
+            b.reset()
+            _hinted_step(b, torch.from_numpy(rec).to(dev), out_of_place=out_of_place)
+            got = b.outputs()
+            rep = check_against_oracle(wl, got, ref, refc)
+            assert all(v == 0 for v in rep.values()), rep
+            assert np.array_equal(got["sel"], want_sel)
+    b.plan.close()
