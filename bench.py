@@ -416,7 +416,7 @@ def main():
         roofline["traffic_note"] = "rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, profiles/%s" % os.path.basename(traffic_file)
     roofline["grid_workgroups"] = grids.get(dom)
 
-    frozen = weighted = residuals = composite = retrain = retrain_res = dynamic_res = None
+    frozen = weighted = residuals = composite = retrain = retrain_res = dynamic_res = weighted_hinted = None
     if not args.skip_extras:
         # ---- frozen-mask step (Algorithm 1 Phase 3 once the masks are frozen, Section 4.5): the same three calls
         #      with hsadmm_project_frozen in place of hsadmm_project, applying each buffer set's last mask
@@ -535,6 +535,74 @@ def main():
                     "value_GBps": round(w_bytes / w_elapsed / 1e9, 1),
                     "hbm_frac": round(w_bytes / w_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
                     "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in wt.items() if v[1]}}
+
+        # ---- the weighted step under a predicted selection with the dual out of place (hsadmm_step with sel_prev and
+        #      U_out; Section 4.5): prepared as for `hinted_step` -- one untimed pass records every step's selection,
+        #      U and v are reset, step t is then predicted by its own recorded selection
+        weighted_hinted = None
+        if one_call and any(l.mode == wk.MODE_FILTER for l in wl.layers):
+            Tw = 3 + 2 * wsteps
+            G = plan.groups_total
+            wrecs = torch.zeros((Tw, G), dtype=torch.int32, device=dev)
+            wscratch = torch.zeros(G, dtype=torch.int32, device=dev)
+            coef_w = torch.tensor([x for ab in zip(wa, wb_) for x in ab], dtype=torch.float32, device=dev)
+            for b in sets:
+                b.Vd0 = b.Vd.clone()
+                b.U2 = torch.zeros_like(b.U)
+
+            def reset_wstate():
+                for b in sets:
+                    b.U.copy_(dU0)
+                    b.Vd.copy_(b.Vd0)
+                counter[0] = 0
+
+            def wh_step(sel_prev, sel_out, out_of_place):
+                b = sets[counter[0] % nsets]
+                counter[0] += 1
+                if out_of_place:
+                    pkg.hsadmm_step(plan, b.W, U=b.U, U_out=b.U2, Zg=b.Zg, Vd=b.Vd, coef=coef_w, Z=b.Z, mask=b.mask,
+                                    sel_prev=sel_prev, sel=sel_out, packed=b.packed, layer_off=b.off, kept_idx=b.kept,
+                                    workspace=b.ws, stream=stream)
+                    b.U, b.U2 = b.U2, b.U
+                else:
+                    pkg.hsadmm_step(plan, b.W, U=b.U, Zg=b.Zg, Vd=b.Vd, coef=coef_w, Z=b.Z, mask=b.mask, sel=sel_out,
+                                    packed=b.packed, layer_off=b.off, kept_idx=b.kept, workspace=b.ws, stream=stream)
+                pkg.hsadmm_expand_dual(plan, b.packed, None, b.dst, b.Z, b.Vd, b.ws, stream=stream)
+
+            reset_wstate()
+            for t in range(Tw):
+                wh_step(None, wrecs[t], False)
+            torch.cuda.synchronize()
+            reset_wstate()
+            for t in range(3):
+                wh_step(wrecs[t], wscratch, True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for t in range(3, 3 + wsteps):
+                wh_step(wrecs[t], wscratch, True)
+            torch.cuda.synchronize()
+            wh_elapsed = (time.perf_counter() - t0) / wsteps
+            pkg.hsadmm_kernel_timing_enable(plan, True)
+            for t in range(3 + wsteps, Tw):
+                wh_step(wrecs[t], wscratch, True)
+            torch.cuda.synchronize()
+            wht = pkg.hsadmm_kernel_timing_read(plan)
+            pkg.hsadmm_kernel_timing_enable(plan, False)
+            same = bool(torch.equal(wscratch, wrecs[Tw - 1]))
+            if not same:
+                print("bench.py: a predicted weighted step selected another support than the unpredicted one",
+                      file=sys.stderr)
+                sys.exit(4)
+            weighted_hinted = {"hit_rate": 1.0, "ms_per_step": round(1e3 * wh_elapsed, 4),
+                               "algorithmic_bytes_per_step": w_bytes,
+                               "value_GBps": round(w_bytes / wh_elapsed / 1e9, 1),
+                               "hbm_frac": round(w_bytes / wh_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                               "selection_equals_the_unpredicted_run": same,
+                               "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in wht.items() if v[1]}}
+            reset_wstate()
+            for b in sets:
+                del b.U2, b.Vd0
+            del wrecs
 
         # ---- the dynamic iteration with its convergence check (Algorithm 1, Phases 2-5 before the masks freeze): the
         #      weighted step above with the intra-node residual sums taken by pass 1 for either outcome of every row
@@ -795,6 +863,7 @@ def main():
         "hinted_step": hinted,
         "frozen_mask_step": frozen,
         "weighted_step": weighted,
+        "weighted_step_predicted_dual_out_of_place": weighted_hinted,
         "dynamic_step_with_residuals": dynamic_res,
         "retraining_step": retrain,
         "retraining_step_with_residuals": retrain_res,

@@ -617,7 +617,7 @@ int hsadmm_retrain_expand(const hsadmm_plan_t* plan, const float* packed, const 
  *   struct_bytes     sizeof(hsadmm_step_args_t) as the caller was compiled (INVALID_ARGUMENT if it differs)
  *   W_replicas, R    HOST array of R device arenas
  *   U                in/out; with U_out given, in only
- *   U_out            out, optional, plain candidate and selected support only (UNSUPPORTED otherwise): the
+ *   U_out            out, optional, selected support only (UNSUPPORTED with mask_frozen): the
  *                    updated dual goes here and U is left as it was (a full-layout arena that overlaps neither U
  *                    nor Z; arena padding is not written).  Under a prediction (sel_prev) the old dual then stays
  *                    readable, so rows predicted pruned are written in their final form at once (no zero fill
@@ -627,7 +627,8 @@ int hsadmm_retrain_expand(const hsadmm_plan_t* plan, const float* packed, const 
  *                    given: the weights stored in the plan.  Read by the kernels when they run, so a captured
  *                    graph follows the buffer's contents from replay to replay.
  *   mask_frozen      in, groups_total bytes, read as hsadmm_project_frozen reads it
- *   sel_prev         in, optional, selected support and plain candidate only: the selection record of the
+ *   sel_prev         in, optional, selected support only (with Zg / Vd it needs U_out: UNSUPPORTED without, and
+ *                    together with `residuals`): the selection record of the
  *                    previous outer iteration (the `sel` output of an earlier call on this plan, or
  *                    hsadmm_selection_from_mask).  It changes no result.  It predicts which groups will be
  *                    kept (Section 4.5: the pattern stops changing after a few iterations), and FILTER layers
@@ -655,7 +656,7 @@ int hsadmm_retrain_expand(const hsadmm_plan_t* plan, const float* packed, const 
  *   Zi_prev          in, with `residuals` and a selected support only: the previous z_i, a full-layout arena
  *                    that overlaps neither Z nor U
  *   workspace, workspace_bytes, hip_stream   as for the named calls (a frozen support without shrinkage needs none)
- * Errors: those of the named call that the fields select; UNSUPPORTED also for sel_prev with Zg / Vd.
+ * Errors: those of the named call that the fields select, and UNSUPPORTED for the combinations named above.
  */
 typedef struct {
     size_t struct_bytes;
@@ -723,7 +724,7 @@ int hsadmm_version(void);
  * profile taken elsewhere can be matched to the plan it is quoted for.
  * Errors: INVALID_ARGUMENT, HOST_MEMORY, HIP.
  */
-#define HSADMM_KERNEL_COUNT 28
+#define HSADMM_KERNEL_COUNT 29
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 int hsadmm_kernel_grid(const hsadmm_plan_t* plan, int kernel_id);

@@ -39,7 +39,7 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_adapt_penalties", "hsadmm_scale_layers", "hsadmm_project_compact_static",
            "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid",
            "hsadmm_layer_sqnorms", "hsadmm_stopping_test")
-KERNEL_COUNT = 28
+KERNEL_COUNT = 29
 
 
 class HsadmmError(RuntimeError):

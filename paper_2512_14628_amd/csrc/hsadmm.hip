@@ -102,7 +102,7 @@ struct WsLayout {
     size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, work, rowres, total;
 };
 
-enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kPass1Hinted, kHintedRepair, kSqnormPart, kResPick, kKernelCount };
+enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kPass1Hinted, kHintedRepair, kSqnormPart, kResPick, kWHintedRepair, kKernelCount };
 static_assert(kKernelCount == HSADMM_KERNEL_COUNT, "kernel id table");
 constexpr size_t kTimingPairs = 8192;
 constexpr size_t kRepairGrid = 2048;       // workgroups of the repair pass under a prediction: 8 per compute unit
@@ -589,6 +589,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     if (hinted) {
         // the selection lists the row items the repair pass must visit, and hands out the offsets and kept lists itself
         wl.sel_prev = h.stash ? nullptr : sel_prev; wl.work = h.work; wl.pack = out ? 1 : 0;
+        wl.channels = hinted_chan ? 1 : 0;
         if (out) wl.co = CopyOut{out->layer_off, out->kept_idx};
         e = for_replica_count<true>(R, [&](auto c) {
             return launch(p, kPass1Hinted, project_pass1_hinted<decltype(c)::value>, (unsigned)p->items_proj.size(),
@@ -948,10 +949,21 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
                                  const float* Zg, const float* Vd, float* Z, float* Wbar, uint8_t* mask,
                                  double* sqnorm, const CompactOut* out, void* workspace, size_t workspace_bytes,
                                  void* hip_stream, const float* coef_arg = nullptr, int32_t* sel_out = nullptr,
-                                 const float* Zi_prev = nullptr, double* residuals = nullptr)
+                                 const float* Zi_prev = nullptr, double* residuals = nullptr,
+                                 const int32_t* sel_prev = nullptr, float* U_out = nullptr)
 {
     if (!p || !W_replicas || !U || !Zg || !Vd || !Z || !mask || !workspace || R < 1) return HSADMM_ERR_INVALID_ARGUMENT;
-    if (!is_aligned(coef_arg, 4) || !is_aligned(sel_out, 4)) return HSADMM_ERR_INVALID_ARGUMENT;
+    if (!is_aligned(coef_arg, 4) || !is_aligned(sel_out, 4) || !is_aligned(sel_prev, 4) || !is_aligned(U_out, 16))
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    if (U_out && (spans_overlap(U_out, U, p->arena_elems) || spans_overlap(U_out, Z, p->arena_elems) ||
+                  spans_overlap(U_out, Zg, p->arena_elems) || spans_overlap(U_out, Vd, p->arena_elems)))
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    if (sel_prev && sel_out &&
+        spans_overlap(reinterpret_cast<const float*>(sel_prev), reinterpret_cast<const float*>(sel_out), p->groups_total))
+        return HSADMM_ERR_INVALID_ARGUMENT;
+    // a prediction needs the old dual to stay readable (a wrong one is repaired from the inputs), and the pass that
+    // takes the residual norms has no predicted form
+    if (sel_prev && (!U_out || residuals)) return HSADMM_ERR_UNSUPPORTED;
     // the intra-node residual norms on the way: both or neither of the previous z_i and the place for the norms
     if ((Zi_prev == nullptr) != (residuals == nullptr)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (residuals && (!is_aligned(Zi_prev, 16) || !is_aligned(residuals, 8) || spans_overlap(Zi_prev, Z, p->arena_elems) ||
@@ -973,7 +985,7 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     char* ws = static_cast<char*>(workspace);
     WeightedArgs w{};
     for (int r = 0; r < R; ++r) w.p.W[r] = W_replicas[r];
-    w.p.Ur = U; w.p.U = U; w.p.Z = Z; w.p.Wbar = Wbar;
+    w.p.Ur = U; w.p.U = U_out ? U_out : U; w.p.Z = Z; w.p.Wbar = Wbar;
     w.p.key = sqnorm ? sqnorm : reinterpret_cast<double*>(ws + p->ws.key);
     w.p.colpart = reinterpret_cast<double*>(ws + p->ws.colpart);
     w.p.inv_R = 1.0f / (float)R;
@@ -985,7 +997,16 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     const unsigned grid = (unsigned)p->items_proj.size();
     const WorkItem* items = p->d_items_proj;
     hipError_t e;
-    if (residuals)
+    const bool hinted = sel_prev != nullptr && !p->items_plain.empty();
+    const WeightedHint wh{sel_prev, out ? out->packed : nullptr, reinterpret_cast<int32_t*>(ws + p->ws.work)};
+    WorkList wl{};
+    if (hinted) {
+        wl.sel_prev = sel_prev; wl.work = wh.work; wl.pack = out ? 1 : 0;
+        if (out) wl.co = CopyOut{out->layer_off, out->kept_idx};
+        e = for_replica_count<false>(R, [&](auto c) {
+            return launch(p, kWKeys, weighted_pass1_hinted<decltype(c)::value>, grid, kBlock, s, items, w, (int)R, wh);
+        });
+    } else if (residuals)
         e = for_replica_count<false>(R, [&](auto c) {
             return launch(p, kWKeys, weighted_pass1<decltype(c)::value, true>, grid, kBlock, s, items, w, (int)R);
         });
@@ -995,7 +1016,6 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
         });
     if (e != hipSuccess) return HSADMM_ERR_HIP;
     // (the weighted candidate of a BOTH layer is formed again from its parked mean, U, Zg and Vd)
-    WorkList wl{};
     if (residuals) { wl.rowres = w.rowres; wl.res_out = residuals; }       // FILTER / unconstrained layers: rows 0 and 1
     if (run_selection(p, w.p.key, w.p.colpart, w.p, mask, ws, s, sel_out, wl) != hipSuccess) return HSADMM_ERR_HIP;
     const uint8_t* cm = mask;
@@ -1011,10 +1031,21 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     }
     // With a compaction to follow, the FILTER fix-up packs its kept rows as it forms them and shares its launch with
     // the gather of the unconstrained layers' rows; CHANNEL and BOTH layers are packed by their final pass.
-    const bool fuse = out && !p->items_fix.empty();
-    if (!p->items_fix.empty() && !fuse) {
+    const bool fuse = out && !hinted && !p->items_fix.empty();
+    if (hinted) {
+        // FILTER rows are final unless their prediction was wrong (or, packed, their rank moved): the listed ones
+        if (!p->items_fix.empty()) {
+            const unsigned n = (unsigned)std::min<size_t>(p->items_fix.size(), kRepairGrid);
+            const int32_t* pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
+            e = for_replica_count<false>(R, [&](auto c) {
+                return launch(p, kWHintedRepair, weighted_hinted_repair<decltype(c)::value>, n, kBlock, s,
+                              (const WorkItem*)p->d_items_rows, w, (int)R, wh, pos);
+            });
+            if (e != hipSuccess) return HSADMM_ERR_HIP;
+        }
+    } else if (!p->items_fix.empty() && !fuse) {
         e = launch(p, kWFixup, weighted_fixup, (unsigned)p->items_fix.size(), kBlock, s,
-                   (const WorkItem*)p->d_items_fix, cm, U, Z, Zg, Vd, coef);
+                   (const WorkItem*)p->d_items_fix, cm, w.p.U, Z, Zg, Vd, coef);
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
     // Final pass of the CHANNEL and BOTH layers: the frozen-mask kernel in its weighted form, on the parked mean
@@ -1041,10 +1072,10 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
         }
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
-    if (out) {
+    if (out && !hinted) {
         if (fuse)
             e = launch(p, kWFixupPack, weighted_fixup_pack, (unsigned)(p->items_fix.size() + p->items_none.size()),
-                       kBlock, s, (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), cm, U, Z, Zg, Vd,
+                       kBlock, s, (const WorkItem*)p->d_items_fix, (int)p->items_fix.size(), cm, w.p.U, Z, Zg, Vd,
                        coef, (const WorkItem*)p->d_items_none, po);
         else if (!p->items_none.empty())
             e = launch(p, kGather, compact_gather<true>, (unsigned)p->items_none.size(), kBlock, s,
@@ -1197,7 +1228,7 @@ int hsadmm_step(const hsadmm_plan_t* p, const hsadmm_step_args_t* x)
     const bool pack = x->packed != nullptr || x->layer_off != nullptr || x->kept_idx != nullptr;
     if (!weighted && x->coef) return HSADMM_ERR_INVALID_ARGUMENT;        // weights without the terms they weigh
     const CompactOut out{x->packed, x->layer_off, x->kept_idx};         // (each impl wants all three or none)
-    if (x->U_out && (frozen || weighted)) return HSADMM_ERR_UNSUPPORTED;   // those passes update the dual in place
+    if (x->U_out && frozen) return HSADMM_ERR_UNSUPPORTED;               // that pass updates the dual in place
     if (frozen) {
         // retraining branch: the given mask replaces the selection; nothing is selected, predicted or recorded
         if (x->mask || x->sqnorm || x->sel_prev || x->sel) return HSADMM_ERR_INVALID_ARGUMENT;
@@ -1215,12 +1246,10 @@ int hsadmm_step(const hsadmm_plan_t* p, const hsadmm_step_args_t* x)
     }
     if (x->mappings_cached) return HSADMM_ERR_UNSUPPORTED;
     if (x->residuals && !weighted) return HSADMM_ERR_UNSUPPORTED;          // (for the plain candidate: hsadmm_residuals)
-    if (weighted) {
-        if (x->sel_prev) return HSADMM_ERR_UNSUPPORTED;                    // no predicted form of the weighted pass yet
+    if (weighted)
         return project_weighted_impl(p, x->W_replicas, x->R, x->U, x->Zg, x->Vd, x->Z, x->Wbar, x->mask, x->sqnorm,
                                      pack ? &out : nullptr, x->workspace, x->workspace_bytes, x->hip_stream, x->coef,
-                                     x->sel, x->Zi_prev, x->residuals);
-    }
+                                     x->sel, x->Zi_prev, x->residuals, x->sel_prev, x->U_out);
     return project_impl(p, x->W_replicas, x->R, x->U, x->Z, x->Wbar, x->mask, x->sqnorm, pack ? &out : nullptr,
                         x->workspace, x->workspace_bytes, x->hip_stream, x->sel_prev, x->sel, x->U_out);
 }
@@ -1502,6 +1531,7 @@ const char* hsadmm_kernel_name(int kernel_id)
         case kHintedRepair: return "hinted_repair";
         case kSqnormPart: return "sqnorm_partials";
         case kResPick: return "residual_pick";
+        case kWHintedRepair: return "weighted_hinted_repair";
         default: return "";
     }
 }

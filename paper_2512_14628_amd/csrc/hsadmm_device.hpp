@@ -74,6 +74,7 @@ struct WorkList {
     const int32_t* sel_prev;   // the previous selection's record (the prediction); null: no list is made
     int32_t* work;
     int pack;                  // a compaction follows: kept rows whose rank has moved are listed as well
+    int channels;              // CHANNEL layers were written under the prediction too: a changed layer is listed whole
     CopyOut co;                // where the selection hands the caller layer_off / kept_idx itself (nulls: it does not)
     // residual norms taken on the way by the weighted pass 1 (null: none): for FILTER and unconstrained layers the
     // selection adds up, per layer, the sums of the outcome every group got, rows 0 and 1 of res_out

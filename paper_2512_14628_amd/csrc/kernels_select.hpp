@@ -467,7 +467,7 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
         pick_residuals(L, (int)blockIdx.x, n_layers, ml, wl, res_red);
     if (wl.sel_prev && L.mode == HSADMM_MODE_FILTER)
         list_repairs(L, wl, row_items, pos_l, &sh.hist[0][0], sh.wtot, &work_slot);
-    else if (wl.sel_prev && L.mode == HSADMM_MODE_CHANNEL)
+    else if (wl.sel_prev && wl.channels && L.mode == HSADMM_MODE_CHANNEL)
         list_changed_layer(L, wl, pos_l, &work_slot);
 }
 

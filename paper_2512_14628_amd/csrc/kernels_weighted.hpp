@@ -158,11 +158,10 @@ __device__ __forceinline__ void wcand1(const WeightedArgs& w, int Rrt, int64_t e
 // from a buffer of its own (Z receives the stash).  CHANNEL and BOTH layers take no part in this here: their sums
 // come from a pass over their final values (residual_partials on their row items).
 template <int R, bool RES = false>
-__global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt)
+__device__ __forceinline__ void weighted_item(const WorkItem& it, const WeightedArgs& w, int Rrt)
 {
     __shared__ double wsum[kWaves][5];
     __shared__ double part[kWaves][kWave * 4];
-    const WorkItem it = items[blockIdx.x];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int row_len = it.row_len;
@@ -303,6 +302,190 @@ __global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restr
                 double s = part[0][lane * 4 + i];
                 for (int v = 1; v < kWaves; ++v) s += part[v][lane * 4 + i];
                 out[i] = s;
+            }
+        }
+    }
+}
+
+template <int R, bool RES = false>
+__global__ __launch_bounds__(kBlock) void weighted_pass1(const WorkItem* __restrict__ items, WeightedArgs w, int Rrt)
+{
+    weighted_item<R, RES>(items[blockIdx.x], w, Rrt);
+}
+
+// ------------------------------------------------------------------ the weighted projection under a predicted selection
+
+// The candidate of Eq. (9) with everything a final row needs, for 4 (or 1) adjacent elements: the mean, the old
+// dual, z~ and the inter-node dual v (what is packed is c = z~ + v).  The arithmetic of wcand4.
+template <int R>
+__device__ __forceinline__ void wcand4_v(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
+                                         v4f& wb, v4f& u, v4f& zt, v4f& vd)
+{
+    const int RR = R > 0 ? R : Rrt;
+    v4f s = ld4(w.p.W[0] + e);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) s = s + ld4(w.p.W[r] + e);
+    u = ld4(w.p.Ur + e);
+    vd = ld4(w.Vd + e);
+    const v4f q = ld4(w.Zg + e) - vd;
+    wb = s * w.p.inv_R;
+    const v4f t = wb + u;
+    const v4f at = t * al;
+    const v4f bq = q * bl;
+    zt = at + bq;
+}
+
+template <int R>
+__device__ __forceinline__ void wcand1_v(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
+                                         float& wb, float& u, float& zt, float& vd)
+{
+    const int RR = R > 0 ? R : Rrt;
+    float s = ld1(w.p.W[0] + e);
+#pragma unroll
+    for (int r = 1; r < RR; ++r) s = s + ld1(w.p.W[r] + e);
+    u = ld1(w.p.Ur + e);
+    vd = ld1(w.Vd + e);
+    const float q = ld1(w.Zg + e) - vd;
+    wb = s * w.p.inv_R;
+    const float t = wb + u;
+    const float at = t * al;
+    const float bq = q * bl;
+    zt = at + bq;
+}
+
+// One row in the final form of the outcome `kept` (the dual goes to a buffer of its own, so the old dual stays
+// readable and either form is final): kept: Z <- z~, U <- U + (Wbar - z~), and c = z~ + v to the packed row `pk`
+// unless that is null; pruned: Z <- +0, U <- Wbar + U.  Returns the lane's share of the row's key (the squares of z~
+// in the order of weighted_item).
+template <int R>
+__device__ __forceinline__ double weighted_row_final(const WeightedArgs& w, int Rrt, int64_t base, int row_len, bool vec,
+                                                     int j, int step, float al, float bl, bool kept, float* pk)
+{
+    double acc = 0.0;
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    if (vec) {
+        const int nchunk = row_len >> 2;
+        for (int c = j; c < nchunk; c += step) {
+            const int64_t e = base + ((int64_t)c << 2);
+            v4f wb, u, zt, vd;
+            wcand4_v<R>(w, Rrt, e, al, bl, wb, u, zt, vd);
+            st4(w.p.Z + e, kept ? zt : zero4);
+            st4(w.p.U + e, kept ? u + (wb - zt) : wb + u);
+            if (pk) st4u(pk + 4 * c, zt + vd);
+            if (w.p.Wbar) st4(w.p.Wbar + e, wb);
+            acc = sq4(acc, zt);
+        }
+    } else {
+        for (int c = j; c < row_len; c += step) {
+            float wb, u, zt, vd;
+            wcand1_v<R>(w, Rrt, base + c, al, bl, wb, u, zt, vd);
+            st1(w.p.Z + base + c, kept ? zt : 0.f);
+            st1(w.p.U + base + c, kept ? u + (wb - zt) : wb + u);
+            if (pk) pk[c] = zt + vd;
+            if (w.p.Wbar) st1(w.p.Wbar + base + c, wb);
+            acc = fma((double)zt, (double)zt, acc);
+        }
+    }
+    return acc;
+}
+
+// What the weighted pass 1 needs under a prediction (see HintArgs in kernels_project.hpp for the records).
+struct WeightedHint {
+    const int32_t* sel_prev;
+    float* packed;      // null: no compaction
+    int32_t* work;      // the work list's counter is cleared here
+};
+
+// Row items of FILTER and unconstrained layers under a predicted selection, dual out of place: every row is written
+// in the final form of its predicted outcome and, if predicted kept, packed at its predicted rank (ranks outside
+// [0, k) are left for the repair pass).  The keys are taken with the lane mapping of weighted_item; its sums run
+// two chunks at a time where this loop takes one, in the same order of additions.
+template <int R>
+__device__ __forceinline__ void weighted_rows_hinted(const WorkItem& it, const WeightedArgs& w, int Rrt,
+                                                     const WeightedHint& h)
+{
+    __shared__ double wsum[kWaves];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int row_len = it.row_len;
+    const bool vec = item_vec(it);
+    const float al = w.coef[2 * it.layer], bl = w.coef[2 * it.layer + 1];
+    const bool unconstrained = item_mode(it) == HSADMM_MODE_NONE;
+    const bool wide = it.lpr > kWave;
+    const int lpr = wide ? kBlock : it.lpr;
+    const int rows_at_once = kBlock / lpr;
+    const int sub = threadIdx.x / lpr;
+    const int j = threadIdx.x - sub * lpr;
+    const int rounds = (it.nr + rows_at_once - 1) / rows_at_once;
+    float* const pk_layer = h.packed ? h.packed + it.packed_off : nullptr;
+    for (int rd = 0; rd < rounds; ++rd) {
+        const int rr = rd * rows_at_once + sub;
+        const bool active = rr < it.nr;
+        double acc = 0.0;
+        if (active) {
+            const int hp = unconstrained ? it.row0 + rr : h.sel_prev[it.g0 + rr];
+            const bool kept = hp >= 0;
+            float* pk = (pk_layer && kept && hp < it.k) ? pk_layer + (int64_t)hp * row_len : nullptr;
+            acc = weighted_row_final<R>(w, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr, al, bl, kept, pk);
+        }
+        if (!wide) {
+            acc = wave_xor_sum(acc, lpr);
+            if (active && j == 0) w.p.key[it.g0 + rr] = acc;
+        } else {
+            acc = wave_xor_sum(acc, kWave);
+            if (lane == 0) wsum[wave] = acc;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double s = wsum[0];
+                for (int v = 1; v < kWaves; ++v) s += wsum[v];
+                w.p.key[it.g0 + rr] = s;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+template <int R>
+__global__ __launch_bounds__(kBlock) void weighted_pass1_hinted(const WorkItem* __restrict__ items, WeightedArgs w,
+                                                                int Rrt, WeightedHint h)
+{
+    const WorkItem it = items[blockIdx.x];
+    const int mode = item_mode(it);
+    if (blockIdx.x == 0 && threadIdx.x == 0) h.work[0] = 0;      // (the selection runs after this whole launch)
+    if (mode == HSADMM_MODE_FILTER || mode == HSADMM_MODE_NONE) weighted_rows_hinted<R>(it, w, Rrt, h);
+    else weighted_item<R, false>(it, w, Rrt);
+}
+
+// The repair pass of the weighted projection under a prediction: a fixed grid shares the FILTER row items the
+// selection has listed.  A row whose prediction was wrong is formed again from the inputs in the form of its real
+// outcome; a kept row whose rank has moved is copied to its new place in the packed buffer as c = Z + v.
+template <int R>
+__global__ __launch_bounds__(kBlock) void weighted_hinted_repair(const WorkItem* __restrict__ row_items, WeightedArgs w,
+                                                                 int Rrt, WeightedHint h, const int32_t* __restrict__ pos)
+{
+    const int n = h.work[0];
+    for (int i = blockIdx.x; i < n; i += gridDim.x) {
+        const WorkItem it = row_items[h.work[kWorkHeader + i]];
+        if (item_mode(it) != HSADMM_MODE_FILTER) continue;       // (only FILTER layers are listed for this pass)
+        const int row_len = it.row_len;
+        const bool vec = item_vec(it);
+        const float al = w.coef[2 * it.layer], bl = w.coef[2 * it.layer + 1];
+        const int lpr = it.lpr <= kWave ? it.lpr : kBlock;
+        const int rows_at_once = kBlock / lpr;
+        const int sub = threadIdx.x / lpr;
+        const int j = threadIdx.x - sub * lpr;
+        float* const pk_layer = h.packed ? h.packed + it.packed_off : nullptr;
+        for (int rr = sub; rr < it.nr; rr += rows_at_once) {
+            const int hp = h.sel_prev[it.g0 + rr];
+            const int pn = pos[it.g0 + rr];
+            const bool pred_kept = hp >= 0, kept = pn >= 0;
+            const int64_t base = it.base + (int64_t)rr * row_len;
+            float* pk = (pk_layer && kept) ? pk_layer + (int64_t)pn * row_len : nullptr;
+            if (pred_kept != kept) {
+                (void)weighted_row_final<R>(w, Rrt, base, row_len, vec, j, lpr, al, bl, kept, pk);
+            } else if (pk && pn != hp) {
+                if (vec) for (int c = j; c < (row_len >> 2); c += lpr) st4u(pk + 4 * c, ld4(w.p.Z + base + 4 * c) + ld4(w.Vd + base + 4 * c));
+                else for (int c = j; c < row_len; c += lpr) pk[c] = ld1(w.p.Z + base + c) + ld1(w.Vd + base + c);
             }
         }
     }

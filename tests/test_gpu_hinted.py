@@ -426,3 +426,67 @@ def test_named_workloads_at_full_size_under_predictions(name):
             assert all(v == 0 for v in rep.values()), rep
             assert np.array_equal(got["sel"], want_sel)
     b.plan.close()
+
+
+@pytest.mark.parametrize("R,pack_align", [(4, 1), (1, 4), (5, 1), (2, 7)])
+def test_weighted_candidate_under_any_prediction(R, pack_align):
+    """The full candidate of Eq. (9) with the dual written out of place, un-predicted and under right, partly wrong,
+    wrong and degenerate predictions: every output is oracle.project_weighted's, the packed buffer the shrinkage of
+    c = z_i + v_i, bit for bit; the input dual is left untouched."""
+    rng = np.random.default_rng(300 + R)
+    wl = wk.custom_workload(SHAPES, R=R, seed=50 + R, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    t = wl.table()
+    L = len(wl.layers)
+    a, bb = oracle.node_coefficients(rng.uniform(1e-3, 2e-3, L), rng.uniform(1e-4, 3e-4, L), 1e-4, 16, R)
+    Zg = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.05
+    Vd = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.01
+    ref = oracle.project_weighted(t, W, U, Zg, Vd, a, bb, want_wbar=True)
+    refc = oracle.compact(t, oracle.add_arenas(t, ref["Z"], Vd), ref["mask"], pack_align=pack_align)
+    want_sel = record_of(wl, ref["mask"])
+    from tests.gpu_harness import packed_segment_sizes
+    sizes = packed_segment_sizes(wl, ref["mask"])
+    b = _Bufs(wl, W, U, pack_align)
+    dev = b.U.device
+    dZg, dVd = torch.from_numpy(Zg).to(dev), torch.from_numpy(Vd).to(dev)
+    coef = torch.from_numpy(np.stack([a, bb], axis=1).astype(np.float32).reshape(-1).copy()).to(dev)
+    G = b.plan.groups_total
+    records = {None: None, "all right": want_sel,
+               "a tenth wrong": record_of(wl, degrade(wl, ref["mask"], 0.1, rng)),
+               "all wrong": record_of(wl, (ref["mask"] == 0).astype(np.uint8)),
+               "everything pruned": np.full(G, -1, np.int32),
+               "everything kept": record_of(wl, np.ones(G, np.uint8)),
+               "ranks out of range": np.where(want_sel >= 0, want_sel + 100000, -5).astype(np.int32)}
+    for name, rec in records.items():
+        for compaction in (True, False):
+            b.reset()
+            b.out_of_place = True
+            extra = dict(packed=b.packed, layer_off=b.off, kept_idx=b.kept) if compaction else {}
+            pkg.hsadmm_step(b.plan, b.W, U=b.U, U_out=b.Uout, Zg=dZg, Vd=dVd, coef=coef, Z=b.Z, Wbar=b.Wbar, mask=b.mask,
+                            sqnorm=b.key, sel=b.sel, sel_prev=None if rec is None else torch.from_numpy(rec).to(dev),
+                            workspace=b.ws, **extra)
+            got = b.outputs()
+            assert np.array_equal(got["mask"], ref["mask"]), name
+            assert np.array_equal(got["sel"], want_sel), name
+            np.testing.assert_allclose(got["key"], ref["key"], rtol=1e-12)
+            for key in ("Z", "U", "Wbar"):
+                for l in wl.layers:
+                    sl = slice(l.elem_off, l.elem_off + l.n)
+                    assert np.array_equal(got[key][sl].view(np.uint32), ref[key][sl].view(np.uint32)), (name, key, l.name)
+            if not compaction:
+                assert np.all(np.isnan(got["packed"]))
+                continue
+            assert np.array_equal(got["layer_off"], refc["layer_off"]), name
+            assert np.array_equal(got["kept_idx"][:refc["kept_idx"].size], refc["kept_idx"]), name
+            for li in range(L):
+                lo = int(refc["layer_off"][li])
+                assert np.array_equal(got["packed"][lo:lo + sizes[li]].view(np.uint32),
+                                      refc["packed"][lo:lo + sizes[li]].view(np.uint32)), (name, li)
+    # in place, a prediction for the weighted candidate is refused; with the residual norms as well
+    rec = torch.from_numpy(want_sel).to(dev)
+    assert pkg.hsadmm_step(b.plan, b.W, U=b.U, Zg=dZg, Vd=dVd, coef=coef, Z=b.Z, mask=b.mask, sel_prev=rec,
+                           workspace=b.ws, check=False) == -4
+    res = torch.zeros(4 * L, dtype=torch.float64, device=dev)
+    assert pkg.hsadmm_step(b.plan, b.W, U=b.U, U_out=b.Uout, Zg=dZg, Vd=dVd, coef=coef, Z=b.Z, mask=b.mask,
+                           sel_prev=rec, residuals=res, Zi_prev=b.dst, workspace=b.ws, check=False) == -4
+    b.plan.close()
