@@ -243,6 +243,38 @@ def test_stopping_test_host_function_against_the_printed_thresholds_and_the_orac
     assert lib.hsadmm_layer_sqnorms(None, None, None, None, 0, None) == -1
 
 
+def test_step_argument_structure_has_the_layout_the_binding_fills(tmp_path):
+    """hsadmm_step_args_t as a C compiler lays it out (size and the offset of every field, printed by a small program
+    built from include/hsadmm.h) against the ctypes structure the binding generates from its field table."""
+    import subprocess
+    fields = [name for name, _, _ in binding._STEP_FIELDS]
+    src = ["#include <stdio.h>", "#include <stddef.h>", '#include "hsadmm.h"', "int main(void) {",
+           '  printf("%zu\\n", sizeof(hsadmm_step_args_t));']
+    src += ['  printf("%%zu\\n", offsetof(hsadmm_step_args_t, %s));' % f for f in fields]
+    src += ["  return 0;", "}"]
+    c = tmp_path / "layout.c"
+    c.write_text("\n".join(src))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(c), "-o", str(exe)])
+    out = [int(x) for x in subprocess.check_output([str(exe)], text=True).split()]
+    assert out[0] == ctypes.sizeof(binding._StepArgs)
+    assert out[1:] == [getattr(binding._StepArgs, f).offset for f in fields]
+    # every field of the header's structure is in the table (a field the binding forgot would shift nothing but stay NULL)
+    header = open(os.path.join(ROOT, "include", "hsadmm.h")).read()
+    body = header[header.index("typedef struct {\n    size_t struct_bytes;"):header.index("} hsadmm_step_args_t;")]
+    declared = re.findall(r"([A-Za-z_0-9]+);", body)
+    assert declared == fields
+    # a structure of another size is refused before anything is read from it
+    args = binding._StepArgs()
+    args.struct_bytes = ctypes.sizeof(binding._StepArgs) - 8
+    assert lib_handle().hsadmm_step(ctypes.c_void_p(1), ctypes.byref(args)) == -1
+    assert lib_handle().hsadmm_step(None, ctypes.byref(args)) == -1
+
+
+def lib_handle():
+    return pkg.load_library()
+
+
 def test_bench_refuses_more_than_one_gpu():
     """This build has no collectives: bench.py --gpus N with N > 1 exits with a message instead of running."""
     import subprocess
