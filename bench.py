@@ -416,7 +416,7 @@ def main():
         roofline["traffic_note"] = "rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, profiles/%s" % os.path.basename(traffic_file)
     roofline["grid_workgroups"] = grids.get(dom)
 
-    frozen = weighted = residuals = composite = retrain = retrain_res = dynamic_res = weighted_hinted = None
+    frozen = weighted = residuals = composite = retrain = retrain_res = dynamic_res = weighted_hinted = dynamic_hinted_res = None
     if not args.skip_extras:
         # ---- frozen-mask step (Algorithm 1 Phase 3 once the masks are frozen, Section 4.5): the same three calls
         #      with hsadmm_project_frozen in place of hsadmm_project, applying each buffer set's last mask
@@ -540,6 +540,8 @@ def main():
         #      U_out; Section 4.5): prepared as for `hinted_step` -- one untimed pass records every step's selection,
         #      U and v are reset, step t is then predicted by its own recorded selection
         weighted_hinted = None
+        for b in sets:
+            b.Zp = torch.randn(n, dtype=torch.float32, device=dev) * 0.05      # a previous z_i for the residual norms
         if one_call and any(l.mode == wk.MODE_FILTER for l in wl.layers):
             Tw = 3 + 2 * wsteps
             G = plan.groups_total
@@ -556,18 +558,22 @@ def main():
                     b.Vd.copy_(b.Vd0)
                 counter[0] = 0
 
-            def wh_step(sel_prev, sel_out, out_of_place):
+            def wh_step(sel_prev, sel_out, out_of_place, norms=False):
                 b = sets[counter[0] % nsets]
                 counter[0] += 1
+                extra = dict(residuals=res_out, Zi_prev=b.Zp) if norms else {}
                 if out_of_place:
                     pkg.hsadmm_step(plan, b.W, U=b.U, U_out=b.U2, Zg=b.Zg, Vd=b.Vd, coef=coef_w, Z=b.Z, mask=b.mask,
                                     sel_prev=sel_prev, sel=sel_out, packed=b.packed, layer_off=b.off, kept_idx=b.kept,
-                                    workspace=b.ws, stream=stream)
+                                    workspace=b.ws, stream=stream, **extra)
                     b.U, b.U2 = b.U2, b.U
                 else:
                     pkg.hsadmm_step(plan, b.W, U=b.U, Zg=b.Zg, Vd=b.Vd, coef=coef_w, Z=b.Z, mask=b.mask, sel=sel_out,
                                     packed=b.packed, layer_off=b.off, kept_idx=b.kept, workspace=b.ws, stream=stream)
-                pkg.hsadmm_expand_dual(plan, b.packed, None, b.dst, b.Z, b.Vd, b.ws, stream=stream)
+                if norms:   # decompression + Eq. (13) with the inter-node sums (the same z and v as hsadmm_expand_dual)
+                    pkg.hsadmm_retrain_expand(plan, b.packed, None, b.dst, b.Z, b.Vd, b.Zg, res_out, b.ws, stream=stream)
+                else:
+                    pkg.hsadmm_expand_dual(plan, b.packed, None, b.dst, b.Z, b.Vd, b.ws, stream=stream)
 
             reset_wstate()
             for t in range(Tw):
@@ -599,6 +605,35 @@ def main():
                                "hbm_frac": round(w_bytes / wh_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
                                "selection_equals_the_unpredicted_run": same,
                                "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in wht.items() if v[1]}}
+            # the same iteration with all four residual norms taken on the way (the dynamic phase's convergence
+            # check at a settled support): the state evolves as above, so the recorded selections still predict it
+            reset_wstate()
+            for t in range(3):
+                wh_step(wrecs[t], wscratch, True, True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for t in range(3, 3 + wsteps):
+                wh_step(wrecs[t], wscratch, True, True)
+            torch.cuda.synchronize()
+            whr_elapsed = (time.perf_counter() - t0) / wsteps
+            pkg.hsadmm_kernel_timing_enable(plan, True)
+            for t in range(3 + wsteps, Tw):
+                wh_step(wrecs[t], wscratch, True, True)
+            torch.cuda.synchronize()
+            whrt = pkg.hsadmm_kernel_timing_read(plan)
+            pkg.hsadmm_kernel_timing_enable(plan, False)
+            same = bool(torch.equal(wscratch, wrecs[Tw - 1]))
+            if not same:
+                print("bench.py: a predicted weighted step with norms selected another support than the unpredicted one",
+                      file=sys.stderr)
+                sys.exit(4)
+            whr_bytes = w_bytes + 8 * wl.n_total
+            dynamic_hinted_res = {"hit_rate": 1.0, "ms_per_step": round(1e3 * whr_elapsed, 4),
+                                  "algorithmic_bytes_per_step": whr_bytes,
+                                  "value_GBps": round(whr_bytes / whr_elapsed / 1e9, 1),
+                                  "hbm_frac": round(whr_bytes / whr_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                                  "selection_equals_the_unpredicted_run": same,
+                                  "kernel_us_per_launch": {k: round(1e3 * v[0] / v[1], 2) for k, v in whrt.items() if v[1]}}
             reset_wstate()
             for b in sets:
                 del b.U2, b.Vd0
@@ -609,8 +644,6 @@ def main():
         #      and picked after the selection (hsadmm_step with `residuals` and `Zi_prev`), and the inter-node sums by
         #      the pass that writes z (hsadmm_retrain_expand) -- against the weighted step followed by a
         #      hsadmm_residuals pass over R + 4 arenas.
-        for b in sets:
-            b.Zp = torch.randn(n, dtype=torch.float32, device=dev) * 0.05
         coef_dev = torch.tensor([x for ab in zip(wa, wb_) for x in ab], dtype=torch.float32, device=dev)
 
         def dynamic_res_step():
@@ -865,6 +898,7 @@ def main():
         "weighted_step": weighted,
         "weighted_step_predicted_dual_out_of_place": weighted_hinted,
         "dynamic_step_with_residuals": dynamic_res,
+        "dynamic_step_with_residuals_predicted_dual_out_of_place": dynamic_hinted_res,
         "retraining_step": retrain,
         "retraining_step_with_residuals": retrain_res,
         "residuals": residuals,

@@ -627,8 +627,8 @@ int hsadmm_retrain_expand(const hsadmm_plan_t* plan, const float* packed, const 
  *                    given: the weights stored in the plan.  Read by the kernels when they run, so a captured
  *                    graph follows the buffer's contents from replay to replay.
  *   mask_frozen      in, groups_total bytes, read as hsadmm_project_frozen reads it
- *   sel_prev         in, optional, selected support only (with Zg / Vd it needs U_out: UNSUPPORTED without, and
- *                    together with `residuals`): the selection record of the
+ *   sel_prev         in, optional, selected support only (with Zg / Vd it needs U_out: UNSUPPORTED without;
+ *                    `residuals` may be taken in the same call): the selection record of the
  *                    previous outer iteration (the `sel` output of an earlier call on this plan, or
  *                    hsadmm_selection_from_mask).  It changes no result.  It predicts which groups will be
  *                    kept (Section 4.5: the pattern stops changing after a few iterations), and FILTER layers
@@ -654,7 +654,7 @@ int hsadmm_retrain_expand(const hsadmm_plan_t* plan, const float* packed, const 
  *                    from one more pass over their own replicas and final z_i.  The order of the fp64 additions
  *                    is fixed (reproducible) and differs from hsadmm_residuals'.
  *   Zi_prev          in, with `residuals` and a selected support only: the previous z_i, a full-layout arena
- *                    that overlaps neither Z nor U
+ *                    that overlaps neither Z nor U nor U_out
  *   workspace, workspace_bytes, hip_stream   as for the named calls (a frozen support without shrinkage needs none)
  * Errors: those of the named call that the fields select, and UNSUPPORTED for the combinations named above.
  */

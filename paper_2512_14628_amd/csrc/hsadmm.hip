@@ -961,13 +961,12 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     if (sel_prev && sel_out &&
         spans_overlap(reinterpret_cast<const float*>(sel_prev), reinterpret_cast<const float*>(sel_out), p->groups_total))
         return HSADMM_ERR_INVALID_ARGUMENT;
-    // a prediction needs the old dual to stay readable (a wrong one is repaired from the inputs), and the pass that
-    // takes the residual norms has no predicted form
-    if (sel_prev && (!U_out || residuals)) return HSADMM_ERR_UNSUPPORTED;
+    // a prediction needs the old dual to stay readable (a wrong one is repaired from the inputs)
+    if (sel_prev && !U_out) return HSADMM_ERR_UNSUPPORTED;
     // the intra-node residual norms on the way: both or neither of the previous z_i and the place for the norms
     if ((Zi_prev == nullptr) != (residuals == nullptr)) return HSADMM_ERR_INVALID_ARGUMENT;
     if (residuals && (!is_aligned(Zi_prev, 16) || !is_aligned(residuals, 8) || spans_overlap(Zi_prev, Z, p->arena_elems) ||
-                      spans_overlap(Zi_prev, U, p->arena_elems)))
+                      spans_overlap(Zi_prev, U, p->arena_elems) || (U_out && spans_overlap(Zi_prev, U_out, p->arena_elems))))
         return HSADMM_ERR_INVALID_ARGUMENT;
     const float* const coef = coef_arg ? coef_arg : p->d_coef;
     if (out && (!out->packed || !out->layer_off || !out->kept_idx || !is_aligned(out->packed, 16) ||
@@ -1003,9 +1002,14 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     if (hinted) {
         wl.sel_prev = sel_prev; wl.work = wh.work; wl.pack = out ? 1 : 0;
         if (out) wl.co = CopyOut{out->layer_off, out->kept_idx};
-        e = for_replica_count<false>(R, [&](auto c) {
-            return launch(p, kWKeys, weighted_pass1_hinted<decltype(c)::value>, grid, kBlock, s, items, w, (int)R, wh);
-        });
+        if (residuals)
+            e = for_replica_count<false>(R, [&](auto c) {
+                return launch(p, kWKeys, weighted_pass1_hinted<decltype(c)::value, true>, grid, kBlock, s, items, w, (int)R, wh);
+            });
+        else
+            e = for_replica_count<false>(R, [&](auto c) {
+                return launch(p, kWKeys, weighted_pass1_hinted<decltype(c)::value>, grid, kBlock, s, items, w, (int)R, wh);
+            });
     } else if (residuals)
         e = for_replica_count<false>(R, [&](auto c) {
             return launch(p, kWKeys, weighted_pass1<decltype(c)::value, true>, grid, kBlock, s, items, w, (int)R);

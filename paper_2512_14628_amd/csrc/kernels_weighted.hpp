@@ -70,7 +70,7 @@ __device__ __forceinline__ void wcand4x2(const WeightedArgs& w, int Rrt, int64_t
 // a second time.
 template <int R>
 __device__ __forceinline__ void wcand4_res(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
-                                           v4f& wb, v4f& u, v4f& zt, double acc[4])
+                                           v4f& wb, v4f& u, v4f& zt, v4f& vd, double acc[4])
 {
     const int RR = R > 0 ? R : Rrt;
     constexpr int kHeld = R > 0 ? R : 1;
@@ -85,7 +85,8 @@ __device__ __forceinline__ void wcand4_res(const WeightedArgs& w, int Rrt, int64
         s = s + x;
     }
     u = ld4(w.p.Ur + e);
-    const v4f q = ld4(w.Zg + e) - ld4(w.Vd + e);
+    vd = ld4(w.Vd + e);
+    const v4f q = ld4(w.Zg + e) - vd;
     const v4f zp = ld4(w.Zi_prev + e);
     wb = s * w.p.inv_R;
     const v4f t = wb + u;
@@ -104,13 +105,14 @@ __device__ __forceinline__ void wcand4_res(const WeightedArgs& w, int Rrt, int64
 
 template <int R>
 __device__ __forceinline__ void wcand1_res(const WeightedArgs& w, int Rrt, int64_t e, float al, float bl,
-                                           float& wb, float& u, float& zt, double acc[4])
+                                           float& wb, float& u, float& zt, float& vd, double acc[4])
 {
     const int RR = R > 0 ? R : Rrt;
     float s = ld1(w.p.W[0] + e);
     for (int r = 1; r < RR; ++r) s = s + ld1(w.p.W[r] + e);
     u = ld1(w.p.Ur + e);
-    const float q = ld1(w.Zg + e) - ld1(w.Vd + e);
+    vd = ld1(w.Vd + e);
+    const float q = ld1(w.Zg + e) - vd;
     const float zp = ld1(w.Zi_prev + e);
     wb = s * w.p.inv_R;
     const float t = wb + u;
@@ -208,9 +210,9 @@ __device__ __forceinline__ void weighted_item(const WorkItem& it, const Weighted
                         acc = sq4(acc, zt1);
                     }
                     for (; c < nchunk; c += lpr) {
-                        v4f wb, u, zt;
+                        v4f wb, u, zt, vd;
                         const int64_t e = base + ((int64_t)c << 2);
-                        if (take_res) wcand4_res<R>(w, Rrt, e, al, bl, wb, u, zt, res);
+                        if (take_res) wcand4_res<R>(w, Rrt, e, al, bl, wb, u, zt, vd, res);
                         else wcand4<R>(w, Rrt, e, al, bl, wb, u, zt);
                         if (park) {
                             st4(w.p.Z + e, wb);
@@ -223,8 +225,8 @@ __device__ __forceinline__ void weighted_item(const WorkItem& it, const Weighted
                     }
                 } else {
                     for (int c = j; c < row_len; c += lpr) {
-                        float wb, u, zt;
-                        if (take_res) wcand1_res<R>(w, Rrt, base + c, al, bl, wb, u, zt, res);
+                        float wb, u, zt, vd;
+                        if (take_res) wcand1_res<R>(w, Rrt, base + c, al, bl, wb, u, zt, vd, res);
                         else wcand1<R>(w, Rrt, base + c, al, bl, wb, u, zt);
                         if (park) {
                             st1(w.p.Z + base + c, wb);
@@ -356,10 +358,12 @@ __device__ __forceinline__ void wcand1_v(const WeightedArgs& w, int Rrt, int64_t
 // One row in the final form of the outcome `kept` (the dual goes to a buffer of its own, so the old dual stays
 // readable and either form is final): kept: Z <- z~, U <- U + (Wbar - z~), and c = z~ + v to the packed row `pk`
 // unless that is null; pruned: Z <- +0, U <- Wbar + U.  Returns the lane's share of the row's key (the squares of z~
-// in the order of weighted_item).
-template <int R>
+// in the order of weighted_item).  RES: res[0..3] also take the lane's share of the row's residual sums for either
+// outcome (see wcand4_res).
+template <int R, bool RES = false>
 __device__ __forceinline__ double weighted_row_final(const WeightedArgs& w, int Rrt, int64_t base, int row_len, bool vec,
-                                                     int j, int step, float al, float bl, bool kept, float* pk)
+                                                     int j, int step, float al, float bl, bool kept, float* pk,
+                                                     double* res = nullptr)
 {
     double acc = 0.0;
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
@@ -368,7 +372,8 @@ __device__ __forceinline__ double weighted_row_final(const WeightedArgs& w, int 
         for (int c = j; c < nchunk; c += step) {
             const int64_t e = base + ((int64_t)c << 2);
             v4f wb, u, zt, vd;
-            wcand4_v<R>(w, Rrt, e, al, bl, wb, u, zt, vd);
+            if (RES) wcand4_res<R>(w, Rrt, e, al, bl, wb, u, zt, vd, res);
+            else wcand4_v<R>(w, Rrt, e, al, bl, wb, u, zt, vd);
             st4(w.p.Z + e, kept ? zt : zero4);
             st4(w.p.U + e, kept ? u + (wb - zt) : wb + u);
             if (pk) st4u(pk + 4 * c, zt + vd);
@@ -378,7 +383,8 @@ __device__ __forceinline__ double weighted_row_final(const WeightedArgs& w, int 
     } else {
         for (int c = j; c < row_len; c += step) {
             float wb, u, zt, vd;
-            wcand1_v<R>(w, Rrt, base + c, al, bl, wb, u, zt, vd);
+            if (RES) wcand1_res<R>(w, Rrt, base + c, al, bl, wb, u, zt, vd, res);
+            else wcand1_v<R>(w, Rrt, base + c, al, bl, wb, u, zt, vd);
             st1(w.p.Z + base + c, kept ? zt : 0.f);
             st1(w.p.U + base + c, kept ? u + (wb - zt) : wb + u);
             if (pk) pk[c] = zt + vd;
@@ -399,12 +405,14 @@ struct WeightedHint {
 // Row items of FILTER and unconstrained layers under a predicted selection, dual out of place: every row is written
 // in the final form of its predicted outcome and, if predicted kept, packed at its predicted rank (ranks outside
 // [0, k) are left for the repair pass).  The keys are taken with the lane mapping of weighted_item; its sums run
-// two chunks at a time where this loop takes one, in the same order of additions.
-template <int R>
+// two chunks at a time where this loop takes one, in the same order of additions.  RES: as in weighted_item, the
+// residual sums of either outcome of every row go to rowres (the selection picks by the real outcome, so a wrong
+// prediction costs them nothing).
+template <int R, bool RES>
 __device__ __forceinline__ void weighted_rows_hinted(const WorkItem& it, const WeightedArgs& w, int Rrt,
                                                      const WeightedHint& h)
 {
-    __shared__ double wsum[kWaves];
+    __shared__ double wsum[kWaves][5];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int row_len = it.row_len;
@@ -422,38 +430,55 @@ __device__ __forceinline__ void weighted_rows_hinted(const WorkItem& it, const W
         const int rr = rd * rows_at_once + sub;
         const bool active = rr < it.nr;
         double acc = 0.0;
+        double res[4] = {0.0, 0.0, 0.0, 0.0};
         if (active) {
             const int hp = unconstrained ? it.row0 + rr : h.sel_prev[it.g0 + rr];
             const bool kept = hp >= 0;
             float* pk = (pk_layer && kept && hp < it.k) ? pk_layer + (int64_t)hp * row_len : nullptr;
-            acc = weighted_row_final<R>(w, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr, al, bl, kept, pk);
+            acc = weighted_row_final<R, RES>(w, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr, al, bl, kept,
+                                             pk, res);
         }
         if (!wide) {
             acc = wave_xor_sum(acc, lpr);
             if (active && j == 0) w.p.key[it.g0 + rr] = acc;
+            if (RES) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    res[k] = wave_xor_sum(res[k], lpr);
+                    if (active && j == 0) w.rowres[4 * (int64_t)(it.g0 + rr) + k] = res[k];
+                }
+            }
         } else {
             acc = wave_xor_sum(acc, kWave);
-            if (lane == 0) wsum[wave] = acc;
+            if (RES) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) res[k] = wave_xor_sum(res[k], kWave);
+            }
+            if (lane == 0) {
+                wsum[wave][0] = acc;
+                if (RES) { wsum[wave][1] = res[0]; wsum[wave][2] = res[1]; wsum[wave][3] = res[2]; wsum[wave][4] = res[3]; }
+            }
             __syncthreads();
-            if (threadIdx.x == 0) {
-                double s = wsum[0];
-                for (int v = 1; v < kWaves; ++v) s += wsum[v];
-                w.p.key[it.g0 + rr] = s;
+            if (threadIdx.x < (RES ? 5 : 1)) {
+                double s = wsum[0][threadIdx.x];
+                for (int v = 1; v < kWaves; ++v) s += wsum[v][threadIdx.x];
+                if (threadIdx.x == 0) w.p.key[it.g0 + rr] = s;
+                else w.rowres[4 * (int64_t)(it.g0 + rr) + (threadIdx.x - 1)] = s;
             }
             __syncthreads();
         }
     }
 }
 
-template <int R>
+template <int R, bool RES = false>
 __global__ __launch_bounds__(kBlock) void weighted_pass1_hinted(const WorkItem* __restrict__ items, WeightedArgs w,
                                                                 int Rrt, WeightedHint h)
 {
     const WorkItem it = items[blockIdx.x];
     const int mode = item_mode(it);
     if (blockIdx.x == 0 && threadIdx.x == 0) h.work[0] = 0;      // (the selection runs after this whole launch)
-    if (mode == HSADMM_MODE_FILTER || mode == HSADMM_MODE_NONE) weighted_rows_hinted<R>(it, w, Rrt, h);
-    else weighted_item<R, false>(it, w, Rrt);
+    if (mode == HSADMM_MODE_FILTER || mode == HSADMM_MODE_NONE) weighted_rows_hinted<R, RES>(it, w, Rrt, h);
+    else weighted_item<R, false>(it, w, Rrt);                    // (CHANNEL and BOTH layers take no residual sums here)
 }
 
 // The repair pass of the weighted projection under a prediction: a fixed grid shares the FILTER row items the

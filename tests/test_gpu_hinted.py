@@ -432,7 +432,8 @@ def test_named_workloads_at_full_size_under_predictions(name):
 def test_weighted_candidate_under_any_prediction(R, pack_align):
     """The full candidate of Eq. (9) with the dual written out of place, un-predicted and under right, partly wrong,
     wrong and degenerate predictions: every output is oracle.project_weighted's, the packed buffer the shrinkage of
-    c = z_i + v_i, bit for bit; the input dual is left untouched."""
+    c = z_i + v_i, bit for bit; the input dual is left untouched.  With the intra-node residual norms taken in the
+    same call (Section 3.4) nothing else changes and the norms are oracle.residuals' whatever the prediction."""
     rng = np.random.default_rng(300 + R)
     wl = wk.custom_workload(SHAPES, R=R, seed=50 + R, sigma_replica=0.03)
     W, U = wk.generate(wl)
@@ -444,11 +445,14 @@ def test_weighted_candidate_under_any_prediction(R, pack_align):
     ref = oracle.project_weighted(t, W, U, Zg, Vd, a, bb, want_wbar=True)
     refc = oracle.compact(t, oracle.add_arenas(t, ref["Z"], Vd), ref["mask"], pack_align=pack_align)
     want_sel = record_of(wl, ref["mask"])
+    Zp = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.05
+    Zp[rng.random(wl.n_arena) < 0.5] = 0.0                       # a previous z_i is sparse
+    sq = oracle.residuals(t, W, ref["Z"], Zp)
     from tests.gpu_harness import packed_segment_sizes
     sizes = packed_segment_sizes(wl, ref["mask"])
     b = _Bufs(wl, W, U, pack_align)
     dev = b.U.device
-    dZg, dVd = torch.from_numpy(Zg).to(dev), torch.from_numpy(Vd).to(dev)
+    dZg, dVd, dZp = torch.from_numpy(Zg).to(dev), torch.from_numpy(Vd).to(dev), torch.from_numpy(Zp).to(dev)
     coef = torch.from_numpy(np.stack([a, bb], axis=1).astype(np.float32).reshape(-1).copy()).to(dev)
     G = b.plan.groups_total
     records = {None: None, "all right": want_sel,
@@ -458,14 +462,23 @@ def test_weighted_candidate_under_any_prediction(R, pack_align):
                "everything kept": record_of(wl, np.ones(G, np.uint8)),
                "ranks out of range": np.where(want_sel >= 0, want_sel + 100000, -5).astype(np.int32)}
     for name, rec in records.items():
-        for compaction in (True, False):
+        for compaction, norms in ((True, False), (False, False), (True, True), (False, True)):
             b.reset()
             b.out_of_place = True
             extra = dict(packed=b.packed, layer_off=b.off, kept_idx=b.kept) if compaction else {}
+            res = torch.full((4 * L,), -7.0, dtype=torch.float64, device=dev)
+            if norms:
+                extra.update(residuals=res, Zi_prev=dZp)
             pkg.hsadmm_step(b.plan, b.W, U=b.U, U_out=b.Uout, Zg=dZg, Vd=dVd, coef=coef, Z=b.Z, Wbar=b.Wbar, mask=b.mask,
                             sqnorm=b.key, sel=b.sel, sel_prev=None if rec is None else torch.from_numpy(rec).to(dev),
                             workspace=b.ws, **extra)
             got = b.outputs()
+            got_res = res.cpu().numpy().reshape(4, L)
+            assert np.all(got_res[2:] == -7.0) and (norms or np.all(got_res == -7.0)), name
+            if norms:
+                for li, l in enumerate(wl.layers):
+                    tol = max(1e-12, l.n * R * 2.0 ** -53)
+                    np.testing.assert_allclose(got_res[:2, li], sq[:2, li], rtol=tol, atol=0, err_msg="%s %s" % (name, l.name))
             assert np.array_equal(got["mask"], ref["mask"]), name
             assert np.array_equal(got["sel"], want_sel), name
             np.testing.assert_allclose(got["key"], ref["key"], rtol=1e-12)
@@ -482,11 +495,11 @@ def test_weighted_candidate_under_any_prediction(R, pack_align):
                 lo = int(refc["layer_off"][li])
                 assert np.array_equal(got["packed"][lo:lo + sizes[li]].view(np.uint32),
                                       refc["packed"][lo:lo + sizes[li]].view(np.uint32)), (name, li)
-    # in place, a prediction for the weighted candidate is refused; with the residual norms as well
+    # in place, a prediction for the weighted candidate is refused; the previous z_i may not be the new dual's buffer
     rec = torch.from_numpy(want_sel).to(dev)
     assert pkg.hsadmm_step(b.plan, b.W, U=b.U, Zg=dZg, Vd=dVd, coef=coef, Z=b.Z, mask=b.mask, sel_prev=rec,
                            workspace=b.ws, check=False) == -4
     res = torch.zeros(4 * L, dtype=torch.float64, device=dev)
     assert pkg.hsadmm_step(b.plan, b.W, U=b.U, U_out=b.Uout, Zg=dZg, Vd=dVd, coef=coef, Z=b.Z, mask=b.mask,
-                           sel_prev=rec, residuals=res, Zi_prev=b.dst, workspace=b.ws, check=False) == -4
+                           sel_prev=rec, residuals=res, Zi_prev=b.Uout, workspace=b.ws, check=False) == -1
     b.plan.close()
