@@ -816,6 +816,60 @@ def main():
                          "value_GBps": round(c_bytes / c_elapsed / 1e9, 1),
                          "hbm_frac": round(c_bytes / c_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
                          "kernel_us_per_step": {k: round(1e3 * v[0] / csteps, 2) for k, v in ct.items() if v[1]}}
+            # the same step under a predicted selection with the dual out of place (both selections of every layer
+            # predicted; prepared as for `hinted_step`: an untimed pass records every step's selection first)
+            if one_call:
+                Tc = 3 + 2 * csteps
+                G2 = plan2.groups_total
+                crecs = torch.zeros((Tc, G2), dtype=torch.int32, device=dev)
+                cscratch = torch.zeros(G2, dtype=torch.int32, device=dev)
+                for b in sets:
+                    b.U.copy_(dU0)
+                    b.U2 = torch.zeros_like(b.U)
+                counter[0] = 0
+
+                def ch_step(sel_prev, sel_out):
+                    b = sets[counter[0] % nsets]
+                    counter[0] += 1
+                    pkg.hsadmm_step(plan2, b.W, U=b.U, U_out=b.U2, Z=b.Z, mask=b.mask2, sel_prev=sel_prev, sel=sel_out,
+                                    packed=b.packed, layer_off=b.off, kept_idx=b.kept2, workspace=b.ws2, stream=stream)
+                    b.U, b.U2 = b.U2, b.U
+                    pkg.hsadmm_expand(plan2, b.packed, None, b.dst, b.ws2, stream=stream)
+
+                for t in range(Tc):
+                    ch_step(None, crecs[t])
+                torch.cuda.synchronize()
+                for b in sets:
+                    b.U.copy_(dU0)
+                counter[0] = 0
+                for t in range(3):
+                    ch_step(crecs[t], cscratch)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for t in range(3, 3 + csteps):
+                    ch_step(crecs[t], cscratch)
+                torch.cuda.synchronize()
+                ch_elapsed = (time.perf_counter() - t0) / csteps
+                pkg.hsadmm_kernel_timing_enable(plan2, True)
+                for t in range(3 + csteps, Tc):
+                    ch_step(crecs[t], cscratch)
+                torch.cuda.synchronize()
+                cht = pkg.hsadmm_kernel_timing_read(plan2)
+                pkg.hsadmm_kernel_timing_enable(plan2, False)
+                if not bool(torch.equal(cscratch, crecs[Tc - 1])):
+                    print("bench.py: a predicted composite step selected another support than the unpredicted one",
+                          file=sys.stderr)
+                    sys.exit(4)
+                composite["predicted_dual_out_of_place"] = {
+                    "hit_rate": 1.0, "ms_per_step": round(1e3 * ch_elapsed, 4),
+                    "value_GBps": round(c_bytes / ch_elapsed / 1e9, 1),
+                    "hbm_frac": round(c_bytes / ch_elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+                    "selection_equals_the_unpredicted_run": True,
+                    "kernel_us_per_step": {k: round(1e3 * v[0] / csteps, 2) for k, v in cht.items() if v[1]}}
+                for b in sets:
+                    b.U.copy_(dU0)
+                    del b.U2
+                del crecs
             plan2.close()
 
     # ---- context: a plain device copy of the same size class (practical streaming ceiling)

@@ -315,9 +315,14 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
                           (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
                           (const int32_t*)nullptr, 0, im, nL, (int)p->pack_align, wl, (const WorkItem*)p->d_items_rows);
     if (e != hipSuccess || p->both_layers.empty()) return e;
-    e = launch(p, kColsums, composite_colsums, (unsigned)p->items_both.size(), kBlock, s,
-               (const WorkItem*)p->d_items_both, (const float*)a.Z, a.Ur, a.Zg, a.Vd, a.coef,
-               (const uint8_t*)mask, colpart);
+    if (wl.both)    // pass 1 wrote these layers under the prediction: the candidate is read back from its outputs
+        e = launch(p, kColsums, composite_colsums_hinted, (unsigned)p->items_both.size(), kBlock, s,
+                   (const WorkItem*)p->d_items_both, (const DevLayer*)p->d_layers, (const float*)a.Z,
+                   (const float*)a.U, wl.sel_prev, (const uint8_t*)mask, colpart);
+    else
+        e = launch(p, kColsums, composite_colsums, (unsigned)p->items_both.size(), kBlock, s,
+                   (const WorkItem*)p->d_items_both, (const float*)a.Z, a.Ur, a.Zg, a.Vd, a.coef,
+                   (const uint8_t*)mask, colpart);
     if (e != hipSuccess) return e;
     return launch(p, kTopk, select_topk, (unsigned)p->both_layers.size(), kScanBlock, s,
                   (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
@@ -583,18 +588,27 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     // Under a prediction pass 1 writes the FILTER rows in the form their predicted fate makes final and packs the rows
     // it expects to be kept (and every row of the unconstrained layers).
     const bool hinted_chan = sel_prev != nullptr && U_out != nullptr && !p->items_chan.empty();   // CHANNEL layers too
-    const bool hinted = sel_prev != nullptr && (!p->items_plain.empty() || hinted_chan);
-    const HintArgs h{sel_prev, out ? out->packed : nullptr, U_out ? 0 : 1, reinterpret_cast<int32_t*>(ws + p->ws.work)};
+    const bool hinted_both = sel_prev != nullptr && U_out != nullptr && !p->items_bfinal.empty(); // ... and BOTH layers
+    const bool hinted = sel_prev != nullptr && (!p->items_plain.empty() || hinted_chan || hinted_both);
+    const HintArgs h{sel_prev, out ? out->packed : nullptr, U_out ? 0 : 1, reinterpret_cast<int32_t*>(ws + p->ws.work),
+                     p->d_layers};
     WorkList wl{};
     if (hinted) {
         // the selection lists the row items the repair pass must visit, and hands out the offsets and kept lists itself
         wl.sel_prev = h.stash ? nullptr : sel_prev; wl.work = h.work; wl.pack = out ? 1 : 0;
         wl.channels = hinted_chan ? 1 : 0;
+        wl.both = hinted_both ? 1 : 0;
         if (out) wl.co = CopyOut{out->layer_off, out->kept_idx};
-        e = for_replica_count<true>(R, [&](auto c) {
-            return launch(p, kPass1Hinted, project_pass1_hinted<decltype(c)::value>, (unsigned)p->items_proj.size(),
-                          kBlock, s, (const WorkItem*)p->d_items_proj, a, (int)R, h);
-        });
+        if (hinted_both)
+            e = for_replica_count<true>(R, [&](auto c) {
+                return launch(p, kPass1Hinted, project_pass1_hinted<decltype(c)::value, true>, (unsigned)p->items_proj.size(),
+                              kBlock, s, (const WorkItem*)p->d_items_proj, a, (int)R, h);
+            });
+        else
+            e = for_replica_count<true>(R, [&](auto c) {
+                return launch(p, kPass1Hinted, project_pass1_hinted<decltype(c)::value>, (unsigned)p->items_proj.size(),
+                              kBlock, s, (const WorkItem*)p->d_items_proj, a, (int)R, h);
+            });
     } else {
         e = for_replica_count<true>(R, [&](auto c) { return launch_pass1<decltype(c)::value>(p, a, R, s); });
     }
@@ -619,15 +633,15 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         // every FILTER row from its predicted to its final form.  Dual in place: all row items (most hold a stash
         // to clear).  Dual out of place: as many workgroups as the device holds at once share the items the
         // selection listed.
-        if (!p->items_fix.empty() || hinted_chan) {
+        if (!p->items_fix.empty() || hinted_chan || hinted_both) {
             if (h.stash) {
                 e = for_replica_count<true>(R, [&](auto c) {
                     return launch(p, kHintedRepair, hinted_repair_all<decltype(c)::value>, (unsigned)p->items_fix.size(),
                                   kBlock, s, (const WorkItem*)p->d_items_fix, a, (int)R, h, po);
                 });
             } else {
-                const unsigned n = (unsigned)std::min<size_t>(p->items_fix.size() + (hinted_chan ? p->items_chan.size() : 0),
-                                                              kRepairGrid);
+                const unsigned n = (unsigned)std::min<size_t>(p->items_fix.size() + (hinted_chan ? p->items_chan.size() : 0) +
+                                                                  (hinted_both ? p->items_bfinal.size() : 0), kRepairGrid);
                 e = for_replica_count<true>(R, [&](auto c) {
                     return launch(p, kHintedRepair, hinted_repair<decltype(c)::value>, n, kBlock, s,
                                   (const WorkItem*)p->d_items_rows, a, (int)R, h, (const uint8_t*)mask, po);
@@ -644,7 +658,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     // with; it then rides on the last final pass.
     bool plain_pending = out && !fuse && !hinted && !p->items_plain.empty();
     const unsigned n_plain = (unsigned)p->items_plain.size();
-    if (!p->items_bfinal.empty()) {
+    if (!p->items_bfinal.empty() && !hinted_both) {
         // layers under both constraints: final Z and U from the parked mean and U, under both selections
         const unsigned gb = (unsigned)p->items_bfinal.size();
         if (out && plain_pending && p->items_chan.empty()) {

@@ -75,6 +75,7 @@ struct WorkList {
     int32_t* work;
     int pack;                  // a compaction follows: kept rows whose rank has moved are listed as well
     int channels;              // CHANNEL layers were written under the prediction too: a changed layer is listed whole
+    int both;                  // ... and so were the layers under both constraints
     CopyOut co;                // where the selection hands the caller layer_off / kept_idx itself (nulls: it does not)
     // residual norms taken on the way by the weighted pass 1 (null: none): for FILTER and unconstrained layers the
     // selection adds up, per layer, the sums of the outcome every group got, rows 0 and 1 of res_out

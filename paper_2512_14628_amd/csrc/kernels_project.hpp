@@ -352,6 +352,7 @@ struct HintArgs {
     float* packed;             // packed buffer of this call's compaction, or null (no compaction)
     int stash;                 // the dual is updated in place: rows predicted pruned keep the kept-form dual in Z
     int32_t* work;             // the work list the selection fills for the repair pass (pass 1 clears its counter)
+    const DevLayer* layers;    // the plan's layer table
 };
 
 // pass1_row with the outputs of a row written in the form its prediction makes final (see Cand::put_h); the sum of
@@ -525,26 +526,6 @@ __device__ __forceinline__ void project_tile_hinted(const WorkItem& it, const Pr
             for (int w = 1; w < kWaves; ++w) s += part[w][lane * 4 + i];
             out[i] = s;
         }
-    }
-}
-
-// Pass 1 under a predicted selection: FILTER and NONE layers as above; CHANNEL layers take the prediction when the
-// dual is written out of place (else, like BOTH layers always, they only sum here and are written after the
-// selection).
-template <int R>
-__global__ __launch_bounds__(kBlock) void project_pass1_hinted(const WorkItem* __restrict__ items, ProjectArgs a,
-                                                               int Rrt, HintArgs h)
-{
-    const WorkItem it = items[blockIdx.x];
-    const int mode = item_mode(it);
-    if (blockIdx.x == 0 && threadIdx.x == 0) h.work[0] = 0;      // (the selection runs after this whole launch)
-    if (mode == HSADMM_MODE_CHANNEL) {
-        if (h.stash) project_tile<R>(it, a, Rrt);
-        else project_tile_hinted<R>(it, a, Rrt, h);
-    } else if (mode == HSADMM_MODE_BOTH) {
-        project_rows<R, true>(it, a, Rrt);
-    } else {
-        project_rows_hinted<R>(it, a, Rrt, h);
     }
 }
 

@@ -322,7 +322,8 @@ __device__ __forceinline__ void list_repairs(const DevLayer& L, const WorkList& 
 // After a CHANNEL layer's selection under a prediction (dual out of place): pass 1 has written the layer in the form
 // the predicted channels make final.  If the selection differs from the prediction in any channel (with a
 // compaction: or in any rank, which only a record that no selection of this plan wrote can cause), every row item
-// of the layer is listed and the repair pass forms the layer again.
+// of the layer is listed and the repair pass forms the layer again.  The same after the second selection of a layer
+// under both constraints, over its filters and its channels (pos_l: the ranks of the layer's first group on).
 __device__ __forceinline__ void list_changed_layer(const DevLayer& L, const WorkList& wl, const int32_t* pos_l, int* slot)
 {
     const int tid = threadIdx.x;
@@ -469,6 +470,8 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
         list_repairs(L, wl, row_items, pos_l, &sh.hist[0][0], sh.wtot, &work_slot);
     else if (wl.sel_prev && wl.channels && L.mode == HSADMM_MODE_CHANNEL)
         list_changed_layer(L, wl, pos_l, &work_slot);
+    else if (wl.sel_prev && wl.both && both && stage == 1)
+        list_changed_layer(L, wl, im.pos + L.group_base, &work_slot);       // filters (an earlier launch) and channels
 }
 
 }  // namespace

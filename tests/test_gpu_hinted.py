@@ -53,7 +53,20 @@ SHAPES = [(96, 16, 1, wk.MODE_FILTER, 40), (80, 64, 9, wk.MODE_FILTER, 30), (40,
           (300, 1, 1, wk.MODE_FILTER, 1), (96, 128, 1, wk.MODE_CHANNEL, 50), (48, 40, 9, wk.MODE_BOTH, 30, 21),
           (10, 128, 1, wk.MODE_NONE, 10), (33, 7, 1, wk.MODE_NONE, 33), (70, 2100, 1, wk.MODE_FILTER, 28),
           (50, 24, 9, wk.MODE_CHANNEL, 10), (33, 7, 3, wk.MODE_CHANNEL, 3), (70, 300, 1, wk.MODE_CHANNEL, 120),
-          (130, 3, 49, wk.MODE_CHANNEL, 1)]
+          (130, 3, 49, wk.MODE_CHANNEL, 1), (64, 96, 1, wk.MODE_BOTH, 30, 40), (20, 7, 3, wk.MODE_BOTH, 10, 3),
+          (12, 2100, 1, wk.MODE_BOTH, 5, 900), (70, 12, 49, wk.MODE_BOTH, 69, 11)]
+
+
+def degrade_part(wl, mask, fraction, rng, filters):
+    """degrade() on one part only of every layer under both constraints (its filters, or its channels); the other
+    layers keep the right prediction."""
+    worse = degrade(wl, mask, fraction, rng)
+    out = mask.copy()
+    for l in wl.layers:
+        if l.mode == wk.MODE_BOTH:
+            lo, hi = (l.group_base, l.group_base + l.c_out) if filters else (l.group_base + l.c_out, l.group_base + l.groups)
+            out[lo:hi] = worse[lo:hi]
+    return out
 
 
 class _Bufs:
@@ -137,6 +150,8 @@ def test_any_prediction_gives_the_oracles_outputs(R, pack_align):
         "all right": want_sel,
         "a tenth wrong": record_of(wl, degrade(wl, ref["mask"], 0.1, rng)),
         "half wrong": record_of(wl, degrade(wl, ref["mask"], 0.5, rng)),
+        "both constraints: filters right, a fifth of the channels wrong": record_of(wl, degrade_part(wl, ref["mask"], 0.2, rng, False)),
+        "both constraints: channels right, a fifth of the filters wrong": record_of(wl, degrade_part(wl, ref["mask"], 0.2, rng, True)),
         "all wrong": record_of(wl, (ref["mask"] == 0).astype(np.uint8)),
         "everything pruned": np.full(G, -1, np.int32),
         "everything kept": record_of(wl, np.ones(G, np.uint8)),
@@ -176,6 +191,35 @@ def test_any_prediction_gives_the_oracles_outputs(R, pack_align):
                 assert np.array_equal(got[key][sl].view(np.uint32), ref[key][sl].view(np.uint32)), (name, key, l.name)
         assert np.array_equal(got["mask"], ref["mask"]) and np.array_equal(got["sel"], want_sel)
         assert np.all(np.isnan(got["packed"]))
+    b.plan.close()
+
+
+def test_a_predicted_step_with_the_dual_out_of_place_writes_no_layer_twice():
+    """Which kernels a predicted step runs (launch counts of the timing diagnostics): with the dual out of place every
+    mode takes the prediction, so after pass 1 there are only the selections (with the column sums of the layers under
+    both constraints between them) and the list-driven repair -- no fix-up, no final pass, no gather."""
+    wl = wk.custom_workload(SHAPES, R=4, seed=31, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    ref = oracle.project(wl.table(), W, U)
+    b = _Bufs(wl, W, U, 1)
+    rec = torch.from_numpy(record_of(wl, ref["mask"])).to(b.U.device)
+    pkg.hsadmm_kernel_timing_enable(b.plan, True)
+    _hinted_step(b, rec, out_of_place=True)
+    got = b.outputs()
+    launches = {k: v[1] for k, v in pkg.hsadmm_kernel_timing_read(b.plan).items() if v[1]}
+    pkg.hsadmm_kernel_timing_enable(b.plan, False)
+    assert launches == {"project_pass1_hinted": 1, "select_topk": 2, "composite_colsums": 1, "hinted_repair": 1,
+                        "expand_scatter": 1}, launches
+    assert np.array_equal(got["mask"], ref["mask"])
+    # in place only the FILTER layers are predicted: the others keep their final passes
+    b.reset()
+    pkg.hsadmm_kernel_timing_enable(b.plan, True)
+    _hinted_step(b, rec, out_of_place=False)
+    b.outputs()
+    launches = {k: v[1] for k, v in pkg.hsadmm_kernel_timing_read(b.plan).items() if v[1]}
+    pkg.hsadmm_kernel_timing_enable(b.plan, False)
+    assert launches == {"project_pass1_hinted": 1, "select_topk": 2, "composite_colsums": 1, "hinted_repair": 1,
+                        "composite_final": 1, "channel_final": 1, "expand_scatter": 1}, launches
     b.plan.close()
 
 
