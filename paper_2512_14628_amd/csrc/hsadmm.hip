@@ -599,7 +599,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         wl.channels = hinted_chan ? 1 : 0;
         wl.both = hinted_both ? 1 : 0;
         if (out) wl.co = CopyOut{out->layer_off, out->kept_idx};
-        if (hinted_both)
+        if (hinted_chan || hinted_both)      // (either implies the other where the plan has both kinds of layer)
             e = for_replica_count<true>(R, [&](auto c) {
                 return launch(p, kPass1Hinted, project_pass1_hinted<decltype(c)::value, true>, (unsigned)p->items_proj.size(),
                               kBlock, s, (const WorkItem*)p->d_items_proj, a, (int)R, h);

@@ -261,12 +261,10 @@ __global__ __launch_bounds__(kBlock) void composite_colsums_hinted(const WorkIte
     }
 }
 
-// Pass 1 under a predicted selection: FILTER and NONE layers by project_rows_hinted; CHANNEL and BOTH layers take
-// the prediction when the dual is written out of place (else they only sum here and are written after the
-// selection).
-// BOTH: an instantiation of its own for plans with such layers under a prediction, so that the other plans' kernel
-// keeps its registers.
-template <int R, bool BOTH = false>
+// Pass 1 under a predicted selection: FILTER and NONE layers by project_rows_hinted.  CHANNEL and BOTH layers take
+// the prediction when the dual is written out of place (TILES: an instantiation of its own for plans with such layers,
+// so that the other plans' kernel keeps its registers); else they only sum here and are written after the selection.
+template <int R, bool TILES = false>
 __global__ __launch_bounds__(kBlock) void project_pass1_hinted(const WorkItem* __restrict__ items, ProjectArgs a,
                                                                int Rrt, HintArgs h)
 {
@@ -274,10 +272,10 @@ __global__ __launch_bounds__(kBlock) void project_pass1_hinted(const WorkItem* _
     const int mode = item_mode(it);
     if (blockIdx.x == 0 && threadIdx.x == 0) h.work[0] = 0;      // (the selection runs after this whole launch)
     if (mode == HSADMM_MODE_CHANNEL) {
-        if (h.stash) project_tile<R>(it, a, Rrt);
-        else project_tile_hinted<R>(it, a, Rrt, h);
+        if constexpr (TILES) project_tile_hinted<R>(it, a, Rrt, h);
+        else project_tile<R>(it, a, Rrt);
     } else if (mode == HSADMM_MODE_BOTH) {
-        if constexpr (BOTH) project_rows_both_hinted<R>(it, a, Rrt, h);
+        if constexpr (TILES) project_rows_both_hinted<R>(it, a, Rrt, h);
         else project_rows<R, true>(it, a, Rrt);
     } else {
         project_rows_hinted<R>(it, a, Rrt, h);

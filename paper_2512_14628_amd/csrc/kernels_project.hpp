@@ -472,33 +472,56 @@ __device__ __forceinline__ void project_tile_hinted(const WorkItem& it, const Pr
             }
         }
         float* const pk_layer = h.packed ? h.packed + it.packed_off : nullptr;
-        for (int rr = wave; rr < it.nr; rr += kWaves) {
-            const int64_t e = it.base + (int64_t)rr * row_len + col;
+        const int RR = R > 0 ? R : Rrt;
+        // the outputs of one row's quad and its share of the column sums
+        auto finish4 = [&](int rr, int64_t e, const v4f& s, const v4f& u) {
             float* drow = pk_layer ? pk_layer + (int64_t)(it.row0 + rr) * packed_row_len : nullptr;
-            const int RR = R > 0 ? R : Rrt;
-            if (vec) {
+            const v4f wb = s * a.inv_R;
+            const v4f v = wb + u;
+            v4f z;
+            z.x = kept[0] ? v.x : 0.f; z.y = kept[1] ? v.y : 0.f; z.z = kept[2] ? v.z : 0.f; z.w = kept[3] ? v.w : 0.f;
+            st4(a.Z + e, z);
+            st4(a.U + e, u + (wb - z));
+            if (a.Wbar) st4(a.Wbar + e, wb);
+            if (drow) {
+                if (pc[0] >= 0) drow[pc[0]] = z.x;
+                if (pc[1] >= 0) drow[pc[1]] = z.y;
+                if (pc[2] >= 0) drow[pc[2]] = z.z;
+                if (pc[3] >= 0) drow[pc[3]] = z.w;
+            }
+            acc0 = fma((double)v.x, (double)v.x, acc0);
+            acc1 = fma((double)v.y, (double)v.y, acc1);
+            acc2 = fma((double)v.z, (double)v.z, acc2);
+            acc3 = fma((double)v.w, (double)v.w, acc3);
+        };
+        if (vec) {
+            int rr = wave;
+            // two of the wave's rows at a time (all their loads before the first store), in ascending order
+            for (; rr + kWaves < it.nr; rr += 2 * kWaves) {
+                const int64_t e0 = it.base + (int64_t)rr * row_len + col, e1 = e0 + (int64_t)kWaves * row_len;
+                v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
+#pragma unroll
+                for (int r = 1; r < RR; ++r) {
+                    const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
+                    s0 = s0 + w0;
+                    s1 = s1 + w1;
+                }
+                const v4f u0 = ld4(a.Ur + e0), u1 = ld4(a.Ur + e1);
+                finish4(rr, e0, s0, u0);
+                finish4(rr + kWaves, e1, s1, u1);
+            }
+            if (rr < it.nr) {
+                const int64_t e = it.base + (int64_t)rr * row_len + col;
                 v4f s = ld4(a.W[0] + e);
 #pragma unroll
                 for (int r = 1; r < RR; ++r) s = s + ld4(a.W[r] + e);
                 const v4f u = ld4(a.Ur + e);
-                const v4f wb = s * a.inv_R;
-                const v4f v = wb + u;
-                v4f z;
-                z.x = kept[0] ? v.x : 0.f; z.y = kept[1] ? v.y : 0.f; z.z = kept[2] ? v.z : 0.f; z.w = kept[3] ? v.w : 0.f;
-                st4(a.Z + e, z);
-                st4(a.U + e, u + (wb - z));
-                if (a.Wbar) st4(a.Wbar + e, wb);
-                if (drow) {
-                    if (pc[0] >= 0) drow[pc[0]] = z.x;
-                    if (pc[1] >= 0) drow[pc[1]] = z.y;
-                    if (pc[2] >= 0) drow[pc[2]] = z.z;
-                    if (pc[3] >= 0) drow[pc[3]] = z.w;
-                }
-                acc0 = fma((double)v.x, (double)v.x, acc0);
-                acc1 = fma((double)v.y, (double)v.y, acc1);
-                acc2 = fma((double)v.z, (double)v.z, acc2);
-                acc3 = fma((double)v.w, (double)v.w, acc3);
-            } else {
+                finish4(rr, e, s, u);
+            }
+        } else {
+            for (int rr = wave; rr < it.nr; rr += kWaves) {
+                const int64_t e = it.base + (int64_t)rr * row_len + col;
+                float* drow = pk_layer ? pk_layer + (int64_t)(it.row0 + rr) * packed_row_len : nullptr;
                 float s = ld1(a.W[0] + e);
 #pragma unroll
                 for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);

@@ -445,7 +445,7 @@ def test_a_captured_graph_follows_coefficients_that_change_between_replays():
     y.plan.close()
 
 
-@pytest.mark.parametrize("name", ["resnet50", "resnet152", "wrn50_2"])
+@pytest.mark.parametrize("name", ["resnet50", "resnet152", "wrn50_2", "resnet50_both"])
 def test_named_workloads_at_full_size_under_predictions(name):
     """The benchmark's workloads at full size, in the launch configuration bench.py times for `hinted_step`: the step
     predicted by the right selection and by one with a tenth of every layer's kept groups exchanged, dual in place
