@@ -445,6 +445,76 @@ def test_a_captured_graph_follows_coefficients_that_change_between_replays():
     y.plan.close()
 
 
+def test_captured_graphs_of_the_predicted_step_alternate_the_dual_buffers():
+    """The predicted step with the dual out of place, captured: two HIP graphs, one per direction of the dual's two
+    buffers and of the two selection records, replayed in turn (the work list's counter is cleared by a kernel, the
+    repair's grid is fixed, nothing is allocated or synchronised, so the step can be captured).  The replicas stay
+    and the dual accumulates, so the supports move from step to step and the repairs have work to do.  Every replay
+    must equal the same sequence of eager calls."""
+    wl = wk.custom_workload(SHAPES, R=4, seed=43, sigma_replica=0.03)
+    W, U = wk.generate(wl)
+    dev = torch.device("cuda:0")
+
+    def fresh():
+        b = _Bufs(wl, W, U, 1)
+        b.sel2 = torch.full_like(b.sel, -7)
+        b.Uout.copy_(b.U0)                       # (both dual buffers hold finite values from the start)
+        return b
+
+    def step(b, forward, predicted, stream=None):
+        u_in, u_out = (b.U, b.Uout) if forward else (b.Uout, b.U)
+        s_prev, s_new = (b.sel2, b.sel) if forward else (b.sel, b.sel2)
+        pkg.hsadmm_step(b.plan, b.W, U=u_in, U_out=u_out, Z=b.Z, mask=b.mask, sel=s_new,
+                        sel_prev=s_prev if predicted else None, packed=b.packed, layer_off=b.off, kept_idx=b.kept,
+                        workspace=b.ws, stream=stream)
+        pkg.hsadmm_expand(b.plan, b.packed, None, b.dst, b.ws, stream=stream)
+
+    def snapshot(b, forward):
+        torch.cuda.synchronize()
+        return {"U": (b.Uout if forward else b.U).cpu().numpy(), "Z": b.Z.cpu().numpy(), "mask": b.mask.cpu().numpy(),
+                "sel": (b.sel if forward else b.sel2).cpu().numpy(), "dst": b.dst.cpu().numpy(),
+                "packed": b.packed.cpu().numpy(), "off": b.off.cpu().numpy(), "kept": b.kept.cpu().numpy()}
+
+    x = fresh()
+    expected = []
+    for it in range(7):
+        step(x, it % 2 == 0, it > 0)
+        expected.append(snapshot(x, it % 2 == 0))
+    assert any(not np.array_equal(expected[i]["mask"], expected[i + 1]["mask"]) for i in range(6))
+
+    y = fresh()
+    step(y, True, False)                         # the first iteration has no record to go by
+    got0 = snapshot(y, True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graphs = {}
+    for forward in (False, True):
+        graphs[forward] = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graphs[forward], stream=side):
+            step(y, forward, True, stream=side)
+    after_capture = snapshot(y, True)
+    for k in got0:
+        assert np.array_equal(got0[k], after_capture[k], equal_nan=True), k      # capture does not execute
+    scratch = torch.zeros(1 << 18, device=dev)
+    for it in range(1, 7):
+        forward = it % 2 == 0
+        graphs[forward].replay()
+        got = snapshot(y, forward)
+        assert np.array_equal(got["mask"], expected[it]["mask"]), it
+        for k in ("sel", "off", "kept"):
+            assert np.array_equal(got[k], expected[it][k]), (it, k)
+        for k in ("U", "Z", "dst"):
+            for l in wl.layers:
+                sl = slice(l.elem_off, l.elem_off + l.n)
+                assert np.array_equal(got[k][sl].view(np.uint32), expected[it][k][sl].view(np.uint32)), (it, k, l.name)
+        n_packed = int(got["off"][-1])
+        assert np.array_equal(got["packed"][:n_packed].view(np.uint32), expected[it]["packed"][:n_packed].view(np.uint32)), it
+        scratch.add_(1.0)                        # eager work between replays
+        assert float(scratch.sum().item()) == float(it * (1 << 18))
+    x.plan.close()
+    y.plan.close()
+
+
 @pytest.mark.parametrize("name", ["resnet50", "resnet152", "wrn50_2", "resnet50_both"])
 def test_named_workloads_at_full_size_under_predictions(name):
     """The benchmark's workloads at full size, in the launch configuration bench.py times for `hinted_step`: the step
