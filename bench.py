@@ -202,7 +202,7 @@ def main():
     #      exchanged for pruned ones (1.0: a support that has settled; 0.9: a tenth of it still moving).
     hinted = None
     has_filter = any(l.mode == wk.MODE_FILTER for l in wl.layers)
-    has_channel = any(l.mode == wk.MODE_CHANNEL for l in wl.layers)
+    has_channel = any(l.mode in (wk.MODE_CHANNEL, wk.MODE_BOTH) for l in wl.layers)
     if one_call and not args.no_hinted and (has_filter or has_channel):
         hsteps = max(1, args.steps // 2)
         hwarm = max(3, args.warmup // 2)
@@ -244,7 +244,7 @@ def main():
         hinted = {"what": "hsadmm_step(sel_prev = the step's own selection recorded beforehand, degraded to the hit "
                           "rate) + hsadmm_expand; same outputs and algorithmic bytes as the step `value` times",
                   "steps": hsteps}
-        # (CHANNEL layers take a prediction only with the dual out of place)
+        # (CHANNEL layers and layers under both constraints take a prediction only with the dual out of place)
         variants = ((1.0, False), (0.9, False), (1.0, True), (0.9, True)) if has_filter else ((1.0, True), (0.9, True))
         for rate, two_duals in variants:
             ping_pong[0] = two_duals
@@ -252,17 +252,20 @@ def main():
             if rate < 1.0:
                 for t in range(T):
                     for l in wl.layers:
-                        if l.mode not in (wk.MODE_FILTER, wk.MODE_CHANNEL):
+                        if l.mode == wk.MODE_NONE:
                             continue
-                        seg = hints_host[t, l.group_base:l.group_base + l.groups]
-                        kept, pruned = np.flatnonzero(seg >= 0), np.flatnonzero(seg < 0)
-                        m = min(len(kept), len(pruned), int(round((1.0 - rate) * l.groups / 2.0)))
-                        if m == 0:
-                            continue
-                        keep = seg >= 0
-                        keep[rng.choice(kept, m, replace=False)] = False
-                        keep[rng.choice(pruned, m, replace=False)] = True
-                        seg[:] = np.where(keep, np.cumsum(keep) - 1, -1)
+                        parts = [(l.group_base, l.c_out), (l.group_base + l.c_out, l.c_in)] if l.mode == wk.MODE_BOTH \
+                            else [(l.group_base, l.groups)]
+                        for first, ng in parts:
+                            seg = hints_host[t, first:first + ng]
+                            kept, pruned = np.flatnonzero(seg >= 0), np.flatnonzero(seg < 0)
+                            m = min(len(kept), len(pruned), int(round((1.0 - rate) * ng / 2.0)))
+                            if m == 0:
+                                continue
+                            keep = seg >= 0
+                            keep[rng.choice(kept, m, replace=False)] = False
+                            keep[rng.choice(pruned, m, replace=False)] = True
+                            seg[:] = np.where(keep, np.cumsum(keep) - 1, -1)
             hit = float(np.mean((hints_host[:, constrained] >= 0) == (recs_host[:, constrained] >= 0)))
             hints = torch.from_numpy(hints_host).to(dev)
             reset_duals()
