@@ -545,7 +545,7 @@ def main():
         weighted_hinted = None
         for b in sets:
             b.Zp = torch.randn(n, dtype=torch.float32, device=dev) * 0.05      # a previous z_i for the residual norms
-        if one_call and any(l.mode == wk.MODE_FILTER for l in wl.layers):
+        if one_call and any(l.mode != wk.MODE_NONE for l in wl.layers):
             Tw = 3 + 2 * wsteps
             G = plan.groups_total
             wrecs = torch.zeros((Tw, G), dtype=torch.int32, device=dev)

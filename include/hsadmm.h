@@ -622,9 +622,9 @@ int hsadmm_retrain_expand(const hsadmm_plan_t* plan, const float* packed, const 
  *                    nor Z; arena padding is not written).  Under a prediction (sel_prev) the old dual then stays
  *                    readable, so rows predicted pruned are written in their final form at once (no zero fill
  *                    after the selection) and a wrong prediction is repaired from the replicas and the old dual.
- *                    With the plain candidate (no Zg / Vd) CHANNEL layers and layers under both constraints then
- *                    take the prediction too: written once, in the form the record makes final, and formed again
- *                    only where a layer's selection differs from its record.
+ *                    CHANNEL layers and layers under both constraints then take the prediction too: written once,
+ *                    in the form the record makes final, and formed again only where a layer's selection differs
+ *                    from its record.
  *   Zg, Vd           in: global consensus z and the node's inter-node dual v_i
  *   coef             in, 2L floats a_0, b_0, a_1, b_1, ... (hsadmm_node_coefficients gives a and b); NULL with Zg
  *                    given: the weights stored in the plan.  Read by the kernels when they run, so a captured

@@ -318,7 +318,7 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
     if (wl.both)    // pass 1 wrote these layers under the prediction: the candidate is read back from its outputs
         e = launch(p, kColsums, composite_colsums_hinted, (unsigned)p->items_both.size(), kBlock, s,
                    (const WorkItem*)p->d_items_both, (const DevLayer*)p->d_layers, (const float*)a.Z,
-                   (const float*)a.U, wl.sel_prev, (const uint8_t*)mask, colpart);
+                   (const float*)a.U, a.Zg, a.Vd, a.coef, wl.sel_prev, (const uint8_t*)mask, colpart);
     else
         e = launch(p, kColsums, composite_colsums, (unsigned)p->items_both.size(), kBlock, s,
                    (const WorkItem*)p->d_items_both, (const float*)a.Z, a.Ur, a.Zg, a.Vd, a.coef,
@@ -1010,20 +1010,25 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     const unsigned grid = (unsigned)p->items_proj.size();
     const WorkItem* items = p->d_items_proj;
     hipError_t e;
-    const bool hinted = sel_prev != nullptr && !p->items_plain.empty();
-    const WeightedHint wh{sel_prev, out ? out->packed : nullptr, reinterpret_cast<int32_t*>(ws + p->ws.work)};
+    // (a prediction comes with the dual out of place here, so every mode can take it)
+    const bool hinted_tiles = sel_prev != nullptr && (!p->items_chan.empty() || !p->items_bfinal.empty());
+    const bool hinted = sel_prev != nullptr && (!p->items_plain.empty() || hinted_tiles);
+    const WeightedHint wh{sel_prev, out ? out->packed : nullptr, reinterpret_cast<int32_t*>(ws + p->ws.work), p->d_layers};
     WorkList wl{};
     if (hinted) {
         wl.sel_prev = sel_prev; wl.work = wh.work; wl.pack = out ? 1 : 0;
+        wl.channels = wl.both = hinted_tiles ? 1 : 0;
         if (out) wl.co = CopyOut{out->layer_off, out->kept_idx};
-        if (residuals)
-            e = for_replica_count<false>(R, [&](auto c) {
-                return launch(p, kWKeys, weighted_pass1_hinted<decltype(c)::value, true>, grid, kBlock, s, items, w, (int)R, wh);
-            });
-        else
-            e = for_replica_count<false>(R, [&](auto c) {
-                return launch(p, kWKeys, weighted_pass1_hinted<decltype(c)::value>, grid, kBlock, s, items, w, (int)R, wh);
-            });
+        const int form = (residuals ? 1 : 0) | (hinted_tiles ? 2 : 0);
+        e = for_replica_count<false>(R, [&](auto c) {
+            constexpr int RC = decltype(c)::value;
+            switch (form) {
+                case 0: return launch(p, kWKeys, weighted_pass1_hinted<RC, false, false>, grid, kBlock, s, items, w, (int)R, wh);
+                case 1: return launch(p, kWKeys, weighted_pass1_hinted<RC, true, false>, grid, kBlock, s, items, w, (int)R, wh);
+                case 2: return launch(p, kWKeys, weighted_pass1_hinted<RC, false, true>, grid, kBlock, s, items, w, (int)R, wh);
+                default: return launch(p, kWKeys, weighted_pass1_hinted<RC, true, true>, grid, kBlock, s, items, w, (int)R, wh);
+            }
+        });
     } else if (residuals)
         e = for_replica_count<false>(R, [&](auto c) {
             return launch(p, kWKeys, weighted_pass1<decltype(c)::value, true>, grid, kBlock, s, items, w, (int)R);
@@ -1051,13 +1056,15 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     // the gather of the unconstrained layers' rows; CHANNEL and BOTH layers are packed by their final pass.
     const bool fuse = out && !hinted && !p->items_fix.empty();
     if (hinted) {
-        // FILTER rows are final unless their prediction was wrong (or, packed, their rank moved): the listed ones
-        if (!p->items_fix.empty()) {
-            const unsigned n = (unsigned)std::min<size_t>(p->items_fix.size(), kRepairGrid);
+        // FILTER rows are final unless their prediction was wrong (or, packed, their rank moved), CHANNEL and BOTH
+        // layers unless their selection differs from the record: the listed items
+        if (!p->items_fix.empty() || hinted_tiles) {
+            const unsigned n = (unsigned)std::min<size_t>(p->items_fix.size() + p->items_chan.size() + p->items_bfinal.size(),
+                                                          kRepairGrid);
             const int32_t* pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
             e = for_replica_count<false>(R, [&](auto c) {
                 return launch(p, kWHintedRepair, weighted_hinted_repair<decltype(c)::value>, n, kBlock, s,
-                              (const WorkItem*)p->d_items_rows, w, (int)R, wh, pos);
+                              (const WorkItem*)p->d_items_rows, w, (int)R, wh, pos, cm, po);
             });
             if (e != hipSuccess) return HSADMM_ERR_HIP;
         }
@@ -1068,14 +1075,14 @@ static int project_weighted_impl(const hsadmm_plan_t* p, const float* const* W_r
     }
     // Final pass of the CHANNEL and BOTH layers: the frozen-mask kernel in its weighted form, on the parked mean
     // where pass 1 parked it (BOTH always, CHANNEL with 3 or more replicas), else on the replicas.
-    if (!p->items_bfinal.empty()) {
+    if (!p->items_bfinal.empty() && !hinted_tiles) {
         const unsigned gb = (unsigned)p->items_bfinal.size();
         const WorkItem* bi = p->d_items_bfinal;
         if (out) e = launch(p, kWFinal, project_frozen<kMeanInZ, true, true>, gb, kBlock, s, bi, w.p, 0, cm, po);
         else e = launch(p, kWFinal, project_frozen<kMeanInZ, false, true>, gb, kBlock, s, bi, w.p, 0, cm, PackOut{});
         if (e != hipSuccess) return HSADMM_ERR_HIP;
     }
-    if (!p->items_chan.empty()) {
+    if (!p->items_chan.empty() && !hinted_tiles) {
         const unsigned gc = (unsigned)p->items_chan.size();
         const WorkItem* ci = p->d_items_chan;
         const int sel = w.p.park_mean ? 0 : (int)R;          // 0: parked mean; else R is 1 or 2

@@ -39,9 +39,11 @@ __device__ __forceinline__ void quad_predicted_cols(const int32_t* __restrict__ 
 
 // The outputs of 4 adjacent elements of a layer under both constraints in the form the two predicted selections make
 // final: kept (its filter and its channel are predicted kept) Z <- V, else Z <- +0; U + (Wbar - Z) to the new dual;
-// a kept element of a row that is packed (drow) also to its packed column.
+// a kept element of a row that is packed (drow) also to its packed column (vd: the inter-node dual that is added to
+// what is packed when the candidate is the weighted one; unused otherwise: z is packed bit for bit).
+template <bool WEIGHTED>
 __device__ __forceinline__ void both_put(const ProjectArgs& a, int64_t e, const v4f& wb, const v4f& u, const v4f& v,
-                                         bool row_kept, const bool kept[4], const int pc[4], float* drow)
+                                         const v4f& vd, bool row_kept, const bool kept[4], const int pc[4], float* drow)
 {
     v4f z;
     z.x = (row_kept && kept[0]) ? v.x : 0.f;
@@ -52,20 +54,39 @@ __device__ __forceinline__ void both_put(const ProjectArgs& a, int64_t e, const 
     st4(a.U + e, u + (wb - z));
     if (a.Wbar) st4(a.Wbar + e, wb);
     if (drow) {
-        if (pc[0] >= 0) drow[pc[0]] = z.x;
-        if (pc[1] >= 0) drow[pc[1]] = z.y;
-        if (pc[2] >= 0) drow[pc[2]] = z.z;
-        if (pc[3] >= 0) drow[pc[3]] = z.w;
+        const v4f c = WEIGHTED ? z + vd : z;
+        if (pc[0] >= 0) drow[pc[0]] = c.x;
+        if (pc[1] >= 0) drow[pc[1]] = c.y;
+        if (pc[2] >= 0) drow[pc[2]] = c.z;
+        if (pc[3] >= 0) drow[pc[3]] = c.w;
     }
+}
+
+// The candidate of 4 adjacent elements from the mean and the old dual: Wbar + U, or (WEIGHTED) Eq. (9)'s
+// z~ = fl(fl(a t) + fl(b (Zg - Vd))), t = Wbar + U, with the arithmetic of the un-predicted weighted pass; vd: Vd.
+template <bool WEIGHTED>
+__device__ __forceinline__ v4f both_candidate(const ProjectArgs& a, int64_t e, const v4f& wb, const v4f& u, float al,
+                                              float bl, v4f& vd)
+{
+    v4f v = wb + u;
+    vd = v4f{0.f, 0.f, 0.f, 0.f};
+    if (WEIGHTED) {
+        vd = ld4(a.Vd + e);
+        const v4f q = ld4(a.Zg + e) - vd;
+        const v4f at = v * al;
+        const v4f bq = q * bl;
+        v = at + bq;
+    }
+    return v;
 }
 
 // pass1_row<R, true> (the row's share of its filter norm: squares of the whole candidate row, same chunks, same
 // order) with the row written in its predicted final form instead of the parked mean.
-template <int R>
+template <int R, bool WEIGHTED>
 __device__ __forceinline__ double pass1_row_both_hinted(const ProjectArgs& a, int Rrt, int64_t base, int row_len,
                                                         bool vec, int j, int step, bool row_kept,
                                                         const int32_t* __restrict__ hp_c, const DivKhw& div, int k_in,
-                                                        float* drow)
+                                                        float* drow, float al, float bl)
 {
     const int RR = R > 0 ? R : Rrt;
     double acc = 0.0;
@@ -88,9 +109,11 @@ __device__ __forceinline__ double pass1_row_both_hinted(const ProjectArgs& a, in
             quad_predicted_cols(hp_c, div, col0, k_in, k0, p0);
             quad_predicted_cols(hp_c, div, col1, k_in, k1, p1);
             const v4f wb0 = s0 * a.inv_R, wb1 = s1 * a.inv_R;
-            const v4f v0 = wb0 + u0, v1 = wb1 + u1;
-            both_put(a, e0, wb0, u0, v0, row_kept, k0, p0, drow);
-            both_put(a, e1, wb1, u1, v1, row_kept, k1, p1, drow);
+            v4f vd0, vd1;
+            const v4f v0 = both_candidate<WEIGHTED>(a, e0, wb0, u0, al, bl, vd0);
+            const v4f v1 = both_candidate<WEIGHTED>(a, e1, wb1, u1, al, bl, vd1);
+            both_put<WEIGHTED>(a, e0, wb0, u0, v0, vd0, row_kept, k0, p0, drow);
+            both_put<WEIGHTED>(a, e1, wb1, u1, v1, vd1, row_kept, k1, p1, drow);
             acc = sq4(acc, v0);
             acc = sq4(acc, v1);
         }
@@ -105,8 +128,9 @@ __device__ __forceinline__ double pass1_row_both_hinted(const ProjectArgs& a, in
             int p[4];
             quad_predicted_cols(hp_c, div, col, k_in, k, p);
             const v4f wb = s * a.inv_R;
-            const v4f v = wb + u;
-            both_put(a, e, wb, u, v, row_kept, k, p, drow);
+            v4f vd;
+            const v4f v = both_candidate<WEIGHTED>(a, e, wb, u, al, bl, vd);
+            both_put<WEIGHTED>(a, e, wb, u, v, vd, row_kept, k, p, drow);
             acc = sq4(acc, v);
         }
     } else {
@@ -116,14 +140,22 @@ __device__ __forceinline__ double pass1_row_both_hinted(const ProjectArgs& a, in
             for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
             const float u = ld1(a.Ur + e);
             const float wb = s * a.inv_R;
-            const float v = wb + u;
+            float v = wb + u;
+            float vd = 0.f;
+            if (WEIGHTED) {
+                vd = ld1(a.Vd + e);
+                const float q = ld1(a.Zg + e) - vd;
+                const float at = v * al;
+                const float bq = q * bl;
+                v = at + bq;
+            }
             const int ch = div(c);
             const int r = hp_c[ch];
             const float z = (row_kept && r >= 0) ? v : 0.f;
             st1(a.Z + e, z);
             st1(a.U + e, u + (wb - z));
             if (a.Wbar) st1(a.Wbar + e, wb);
-            if (drow && r >= 0 && r < k_in) drow[r * div.khw + (c - ch * div.khw)] = z;
+            if (drow && r >= 0 && r < k_in) drow[r * div.khw + (c - ch * div.khw)] = WEIGHTED ? z + vd : z;
             acc = fma((double)v, (double)v, acc);
         }
     }
@@ -136,10 +168,12 @@ __device__ __forceinline__ double pass1_row_both_hinted(const ProjectArgs& a, in
 // in [0, k) also go to the packed buffer, their kept columns at the predicted packed columns.  The channel norms of
 // the second selection are then taken from these outputs (composite_colsums_hinted); if both selections turn out as
 // predicted the layer is done, else the repair pass forms it again from the replicas and the old dual.
-template <int R>
+// WEIGHTED: the candidate of Eq. (9) (its norms, and c = z + Vd packed), see both_candidate.
+template <int R, bool WEIGHTED = false>
 __device__ __forceinline__ void project_rows_both_hinted(const WorkItem& it, const ProjectArgs& a, int Rrt,
                                                          const HintArgs& h)
 {
+    const float al = WEIGHTED ? a.coef[2 * it.layer] : 1.f, bl = WEIGHTED ? a.coef[2 * it.layer + 1] : 0.f;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int row_len = it.row_len;
@@ -167,8 +201,8 @@ __device__ __forceinline__ void project_rows_both_hinted(const WorkItem& it, con
                 bool kept;
                 float* drow;
                 prediction(rr, kept, drow);
-                acc = pass1_row_both_hinted<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr, kept, hp_c,
-                                               div, k_in, drow);
+                acc = pass1_row_both_hinted<R, WEIGHTED>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, j, lpr,
+                                                         kept, hp_c, div, k_in, drow, al, bl);
             }
             acc = wave_xor_sum(acc, lpr);
             if (active && j == 0) a.key[it.g0 + rr] = acc;
@@ -179,8 +213,8 @@ __device__ __forceinline__ void project_rows_both_hinted(const WorkItem& it, con
             bool kept;
             float* drow;
             prediction(rr, kept, drow);
-            double acc = pass1_row_both_hinted<R>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec, threadIdx.x,
-                                                  kBlock, kept, hp_c, div, k_in, drow);
+            double acc = pass1_row_both_hinted<R, WEIGHTED>(a, Rrt, it.base + (int64_t)rr * row_len, row_len, vec,
+                                                            threadIdx.x, kBlock, kept, hp_c, div, k_in, drow, al, bl);
             acc = wave_xor_sum(acc, kWave);
             if (lane == 0) wsum[wave] = acc;
             __syncthreads();
@@ -197,11 +231,15 @@ __device__ __forceinline__ void project_rows_both_hinted(const WorkItem& it, con
 // composite_colsums for layers that pass 1 wrote under a prediction: the candidate of a kept filter's row is read
 // back from the outputs -- Z where the element was predicted kept, the new dual where it was not (a pruned element's
 // dual is U + Wbar, the candidate bit for bit) -- whatever the filter selection turned out to be.  Tiles and the
-// order of additions are those of composite_colsums.
+// order of additions are those of composite_colsums.  With coef (the weighted candidate of Eq. (9)) a pruned
+// element's dual is t = Wbar + U and its candidate is formed again as fl(fl(a t) + fl(b (Zg - Vd))).
 __global__ __launch_bounds__(kBlock) void composite_colsums_hinted(const WorkItem* __restrict__ items,
                                                                    const DevLayer* __restrict__ layers,
                                                                    const float* __restrict__ Z,
                                                                    const float* __restrict__ Unew,
+                                                                   const float* __restrict__ Zg,
+                                                                   const float* __restrict__ Vd,
+                                                                   const float* __restrict__ coef,
                                                                    const int32_t* __restrict__ sel_prev,
                                                                    const uint8_t* __restrict__ mask,
                                                                    double* __restrict__ colpart)
@@ -218,6 +256,7 @@ __global__ __launch_bounds__(kBlock) void composite_colsums_hinted(const WorkIte
     const uint8_t* mf = mask + it.g0 + it.row0;                  // filter bytes of the tile's rows
     const int32_t* hp_f = sel_prev + it.g0 + it.row0;            // ... and their predictions
     const int32_t* hp_c = sel_prev + it.g0 + layers[it.layer].c_out;
+    const float al = coef ? coef[2 * it.layer] : 1.f, bl = coef ? coef[2 * it.layer + 1] : 0.f;
     double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
     if (in) {
         const DivKhw div(it.khw);
@@ -230,7 +269,14 @@ __global__ __launch_bounds__(kBlock) void composite_colsums_hinted(const WorkIte
             const bool rk = hp_f[rr] >= 0;
             const int64_t e = it.base + (int64_t)rr * row_len + col;
             if (vec) {
-                const v4f z = ld4(Z + e), u = ld4(Unew + e);
+                const v4f z = ld4(Z + e);
+                v4f u = ld4(Unew + e);
+                if (coef) {
+                    const v4f q = ld4(Zg + e) - ld4(Vd + e);
+                    const v4f at = u * al;
+                    const v4f bq = q * bl;
+                    u = at + bq;
+                }
                 v4f v;
                 v.x = (rk && ck[0]) ? z.x : u.x;
                 v.y = (rk && ck[1]) ? z.y : u.y;
@@ -241,7 +287,14 @@ __global__ __launch_bounds__(kBlock) void composite_colsums_hinted(const WorkIte
                 acc2 = fma((double)v.z, (double)v.z, acc2);
                 acc3 = fma((double)v.w, (double)v.w, acc3);
             } else {
-                const float v = (rk && ck[0]) ? ld1(Z + e) : ld1(Unew + e);
+                float u = ld1(Unew + e);
+                if (coef) {
+                    const float q = ld1(Zg + e) - ld1(Vd + e);
+                    const float at = u * al;
+                    const float bq = q * bl;
+                    u = at + bq;
+                }
+                const float v = (rk && ck[0]) ? ld1(Z + e) : u;
                 acc0 = fma((double)v, (double)v, acc0);
             }
         }

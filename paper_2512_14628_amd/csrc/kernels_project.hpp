@@ -443,7 +443,9 @@ __device__ __forceinline__ void project_rows_hinted(const WorkItem& it, const Pr
 // predicted place in the packed row.  If the selection then keeps exactly the predicted channels the layer is
 // done; otherwise the repair pass forms the layer again from the replicas and the old dual, which is still there.
 // A lane's four columns keep their flags and packed columns for the whole tile.
-template <int R>
+// WEIGHTED: the candidate is z~ = fl(fl(a t) + fl(b (Zg - Vd))), t = Wbar + U (Eq. (9)); the column sums are those of
+// z~ and what is packed is c = z + Vd (Section 4.4.1).
+template <int R, bool WEIGHTED = false>
 __device__ __forceinline__ void project_tile_hinted(const WorkItem& it, const ProjectArgs& a, int Rrt, const HintArgs& h)
 {
     __shared__ double part[kWaves][kWave * 4];
@@ -473,21 +475,31 @@ __device__ __forceinline__ void project_tile_hinted(const WorkItem& it, const Pr
         }
         float* const pk_layer = h.packed ? h.packed + it.packed_off : nullptr;
         const int RR = R > 0 ? R : Rrt;
+        const float al = WEIGHTED ? a.coef[2 * it.layer] : 1.f, bl = WEIGHTED ? a.coef[2 * it.layer + 1] : 0.f;
         // the outputs of one row's quad and its share of the column sums
         auto finish4 = [&](int rr, int64_t e, const v4f& s, const v4f& u) {
             float* drow = pk_layer ? pk_layer + (int64_t)(it.row0 + rr) * packed_row_len : nullptr;
             const v4f wb = s * a.inv_R;
-            const v4f v = wb + u;
+            v4f v = wb + u;
+            v4f vd = {0.f, 0.f, 0.f, 0.f};
+            if (WEIGHTED) {
+                vd = ld4(a.Vd + e);
+                const v4f q = ld4(a.Zg + e) - vd;
+                const v4f at = v * al;
+                const v4f bq = q * bl;
+                v = at + bq;
+            }
             v4f z;
             z.x = kept[0] ? v.x : 0.f; z.y = kept[1] ? v.y : 0.f; z.z = kept[2] ? v.z : 0.f; z.w = kept[3] ? v.w : 0.f;
             st4(a.Z + e, z);
             st4(a.U + e, u + (wb - z));
             if (a.Wbar) st4(a.Wbar + e, wb);
             if (drow) {
-                if (pc[0] >= 0) drow[pc[0]] = z.x;
-                if (pc[1] >= 0) drow[pc[1]] = z.y;
-                if (pc[2] >= 0) drow[pc[2]] = z.z;
-                if (pc[3] >= 0) drow[pc[3]] = z.w;
+                const v4f c = WEIGHTED ? z + vd : z;
+                if (pc[0] >= 0) drow[pc[0]] = c.x;
+                if (pc[1] >= 0) drow[pc[1]] = c.y;
+                if (pc[2] >= 0) drow[pc[2]] = c.z;
+                if (pc[3] >= 0) drow[pc[3]] = c.w;
             }
             acc0 = fma((double)v.x, (double)v.x, acc0);
             acc1 = fma((double)v.y, (double)v.y, acc1);
@@ -527,12 +539,20 @@ __device__ __forceinline__ void project_tile_hinted(const WorkItem& it, const Pr
                 for (int r = 1; r < RR; ++r) s = s + ld1(a.W[r] + e);
                 const float u = ld1(a.Ur + e);
                 const float wb = s * a.inv_R;
-                const float v = wb + u;
+                float v = wb + u;
+                float vd = 0.f;
+                if (WEIGHTED) {
+                    vd = ld1(a.Vd + e);
+                    const float q = ld1(a.Zg + e) - vd;
+                    const float at = v * al;
+                    const float bq = q * bl;
+                    v = at + bq;
+                }
                 const float z = kept[0] ? v : 0.f;
                 st1(a.Z + e, z);
                 st1(a.U + e, u + (wb - z));
                 if (a.Wbar) st1(a.Wbar + e, wb);
-                if (drow && pc[0] >= 0) drow[pc[0]] = z;
+                if (drow && pc[0] >= 0) drow[pc[0]] = WEIGHTED ? z + vd : z;
                 acc0 = fma((double)v, (double)v, acc0);
             }
         }

@@ -400,6 +400,7 @@ struct WeightedHint {
     const int32_t* sel_prev;
     float* packed;      // null: no compaction
     int32_t* work;      // the work list's counter is cleared here
+    const DevLayer* layers;
 };
 
 // Row items of FILTER and unconstrained layers under a predicted selection, dual out of place: every row is written
@@ -470,28 +471,46 @@ __device__ __forceinline__ void weighted_rows_hinted(const WorkItem& it, const W
     }
 }
 
-template <int R, bool RES = false>
+// TILES: CHANNEL and BOTH layers take the prediction as well (the weighted forms of project_tile_hinted and
+// project_rows_both_hinted; an instantiation of its own for plans with such layers, so that the other plans' kernel
+// keeps its registers); else they only sum here (and park) and are written after the selection.
+template <int R, bool RES = false, bool TILES = false>
 __global__ __launch_bounds__(kBlock) void weighted_pass1_hinted(const WorkItem* __restrict__ items, WeightedArgs w,
                                                                 int Rrt, WeightedHint h)
 {
     const WorkItem it = items[blockIdx.x];
     const int mode = item_mode(it);
     if (blockIdx.x == 0 && threadIdx.x == 0) h.work[0] = 0;      // (the selection runs after this whole launch)
-    if (mode == HSADMM_MODE_FILTER || mode == HSADMM_MODE_NONE) weighted_rows_hinted<R, RES>(it, w, Rrt, h);
-    else weighted_item<R, false>(it, w, Rrt);                    // (CHANNEL and BOTH layers take no residual sums here)
+    if (mode == HSADMM_MODE_FILTER || mode == HSADMM_MODE_NONE) {
+        weighted_rows_hinted<R, RES>(it, w, Rrt, h);
+    } else if constexpr (TILES) {                                // (CHANNEL and BOTH layers take no residual sums here)
+        const HintArgs hh{h.sel_prev, h.packed, 0, h.work, h.layers};
+        if (mode == HSADMM_MODE_CHANNEL) project_tile_hinted<R, true>(it, w.p, Rrt, hh);
+        else project_rows_both_hinted<R, true>(it, w.p, Rrt, hh);
+    } else {
+        weighted_item<R, false>(it, w, Rrt);
+    }
 }
 
-// The repair pass of the weighted projection under a prediction: a fixed grid shares the FILTER row items the
-// selection has listed.  A row whose prediction was wrong is formed again from the inputs in the form of its real
-// outcome; a kept row whose rank has moved is copied to its new place in the packed buffer as c = Z + v.
+// The repair pass of the weighted projection under a prediction: a fixed grid shares the row items the selection has
+// listed.  A FILTER row whose prediction was wrong is formed again from the inputs in the form of its real outcome; a
+// kept row whose rank has moved is copied to its new place in the packed buffer as c = Z + v.  A listed item of a
+// CHANNEL or BOTH layer belongs to a layer whose selection differs from its record: its rows are formed again under
+// the mask just selected (the frozen-mask pass in its weighted form; po.packed null: no compaction).
 template <int R>
 __global__ __launch_bounds__(kBlock) void weighted_hinted_repair(const WorkItem* __restrict__ row_items, WeightedArgs w,
-                                                                 int Rrt, WeightedHint h, const int32_t* __restrict__ pos)
+                                                                 int Rrt, WeightedHint h, const int32_t* __restrict__ pos,
+                                                                 const uint8_t* __restrict__ mask, PackOut po)
 {
     const int n = h.work[0];
     for (int i = blockIdx.x; i < n; i += gridDim.x) {
         const WorkItem it = row_items[h.work[kWorkHeader + i]];
-        if (item_mode(it) != HSADMM_MODE_FILTER) continue;       // (only FILTER layers are listed for this pass)
+        if (mode_has_channels(item_mode(it))) {
+            if (po.packed) frozen_item<R, true, true>(it, w.p, Rrt, mask, po);
+            else frozen_item<R, false, true>(it, w.p, Rrt, mask, po);
+            continue;
+        }
+        if (item_mode(it) != HSADMM_MODE_FILTER) continue;
         const int row_len = it.row_len;
         const bool vec = item_vec(it);
         const float al = w.coef[2 * it.layer], bl = w.coef[2 * it.layer + 1];

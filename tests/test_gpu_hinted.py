@@ -571,6 +571,8 @@ def test_weighted_candidate_under_any_prediction(R, pack_align):
     G = b.plan.groups_total
     records = {None: None, "all right": want_sel,
                "a tenth wrong": record_of(wl, degrade(wl, ref["mask"], 0.1, rng)),
+               "both constraints: filters right, a fifth of the channels wrong": record_of(wl, degrade_part(wl, ref["mask"], 0.2, rng, False)),
+               "both constraints: channels right, a fifth of the filters wrong": record_of(wl, degrade_part(wl, ref["mask"], 0.2, rng, True)),
                "all wrong": record_of(wl, (ref["mask"] == 0).astype(np.uint8)),
                "everything pruned": np.full(G, -1, np.int32),
                "everything kept": record_of(wl, np.ones(G, np.uint8)),
@@ -609,8 +611,17 @@ def test_weighted_candidate_under_any_prediction(R, pack_align):
                 lo = int(refc["layer_off"][li])
                 assert np.array_equal(got["packed"][lo:lo + sizes[li]].view(np.uint32),
                                       refc["packed"][lo:lo + sizes[li]].view(np.uint32)), (name, li)
-    # in place, a prediction for the weighted candidate is refused; the previous z_i may not be the new dual's buffer
+    # a right prediction leaves no layer to be written twice: no fix-up, no final pass, no gather
     rec = torch.from_numpy(want_sel).to(dev)
+    b.reset()
+    pkg.hsadmm_kernel_timing_enable(b.plan, True)
+    pkg.hsadmm_step(b.plan, b.W, U=b.U, U_out=b.Uout, Zg=dZg, Vd=dVd, coef=coef, Z=b.Z, mask=b.mask, sel_prev=rec,
+                    packed=b.packed, layer_off=b.off, kept_idx=b.kept, workspace=b.ws)
+    torch.cuda.synchronize()
+    launches = {k: v[1] for k, v in pkg.hsadmm_kernel_timing_read(b.plan).items() if v[1]}
+    pkg.hsadmm_kernel_timing_enable(b.plan, False)
+    assert launches == {"weighted_pass1": 1, "select_topk": 2, "composite_colsums": 1, "weighted_hinted_repair": 1}, launches
+    # in place, a prediction for the weighted candidate is refused; the previous z_i may not be the new dual's buffer
     assert pkg.hsadmm_step(b.plan, b.W, U=b.U, Zg=dZg, Vd=dVd, coef=coef, Z=b.Z, mask=b.mask, sel_prev=rec,
                            workspace=b.ws, check=False) == -4
     res = torch.zeros(4 * L, dtype=torch.float64, device=dev)
