@@ -159,6 +159,7 @@ def test_any_prediction_gives_the_oracles_outputs(R, pack_align):
     }
     hits = {}
     records[None] = None                         # no prediction at all
+    keys = None
     for name, rec in records.items():
         for out_of_place in (False, True):
             b.reset()
@@ -167,6 +168,9 @@ def test_any_prediction_gives_the_oracles_outputs(R, pack_align):
             rep = check_against_oracle(wl, got, ref, refc, pack_align=pack_align)
             assert all(v == 0 for v in rep.values()), (name, out_of_place, rep)
             assert np.array_equal(got["sel"], want_sel), (name, out_of_place)
+            # the group norms carry the same bits whatever the prediction (same lanes, same order of additions)
+            keys = got["key"] if keys is None else keys
+            assert np.array_equal(got["key"].view(np.uint64), keys.view(np.uint64)), (name, out_of_place)
             pad = np.ones(wl.n_arena, bool)
             for l in wl.layers:
                 pad[l.elem_off:l.elem_off + l.n] = False
