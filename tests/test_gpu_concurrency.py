@@ -1,0 +1,85 @@
+"""Two host threads call into one plan at the same time, each on a stream, buffers and workspace of its own (what the
+header allows: a plan is read-only after creation, every call's scratch lives in the caller's workspace).  Each
+thread's outputs must be those of the same calls made alone."""
+import threading
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_14628_amd as pkg
+import workloads as wk
+
+pytestmark = pytest.mark.gpu
+
+
+class _Set:
+    def __init__(self, plan, W, U, dev):
+        n = U.size
+        self.W = [torch.from_numpy(np.ascontiguousarray(W[r])).to(dev) for r in range(W.shape[0])]
+        self.U = torch.from_numpy(np.ascontiguousarray(U)).to(dev)
+        self.U2 = torch.zeros_like(self.U)
+        self.Z = torch.zeros(n, dtype=torch.float32, device=dev)
+        self.dst = torch.zeros(n, dtype=torch.float32, device=dev)
+        self.mask = torch.zeros(plan.groups_total, dtype=torch.uint8, device=dev)
+        self.sel = [torch.zeros(plan.groups_total, dtype=torch.int32, device=dev) for _ in range(2)]
+        self.ws = torch.zeros(plan.workspace_bytes, dtype=torch.uint8, device=dev)
+        self.packed = torch.zeros(max(plan.packed_capacity_elems, 1), dtype=torch.float32, device=dev)
+        self.off = torch.zeros(plan.n_layers + 1, dtype=torch.int64, device=dev)
+        self.kept = torch.zeros(plan.groups_total, dtype=torch.int32, device=dev)
+        self.stream = torch.cuda.Stream()
+
+    def iterate(self, plan, steps):
+        """Outer iterations on fixed replicas: the dual alternates between two buffers, every step after the first
+        is predicted by the one before; the supports move as the dual accumulates."""
+        for it in range(steps):
+            pkg.hsadmm_step(plan, self.W, U=self.U, U_out=self.U2, Z=self.Z, mask=self.mask, sel=self.sel[it % 2],
+                            sel_prev=self.sel[(it + 1) % 2] if it else None, packed=self.packed, layer_off=self.off,
+                            kept_idx=self.kept, workspace=self.ws, stream=self.stream)
+            self.U, self.U2 = self.U2, self.U
+            pkg.hsadmm_expand(plan, self.packed, None, self.dst, self.ws, stream=self.stream)
+        self.stream.synchronize()
+
+    def snapshot(self):
+        return [t.cpu().numpy().copy() for t in (self.U, self.Z, self.dst, self.mask, self.packed, self.off, self.kept)]
+
+
+def test_two_threads_share_a_plan():
+    from tests.test_gpu_hinted import SHAPES
+    dev = torch.device("cuda:0")
+    wl = wk.custom_workload(SHAPES, R=4, seed=77, sigma_replica=0.03)
+    plan = pkg.Plan(wl.table())
+    inputs = []
+    for seed in (1, 2):
+        w = wk.custom_workload(SHAPES, R=4, seed=seed, sigma_replica=0.03)
+        inputs.append(wk.generate(w))
+    steps = 25
+    # alone, one after the other
+    alone = []
+    for W, U in inputs:
+        s = _Set(plan, W, U, dev)
+        s.iterate(plan, steps)
+        alone.append(s.snapshot())
+    # together
+    sets = [_Set(plan, W, U, dev) for W, U in inputs]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(s):
+        try:
+            s.iterate(plan, steps)
+        except Exception as e:      # noqa: BLE001  (reported by the main thread)
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(s,)) for s in sets]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads), "a thread did not finish"
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for s, want in zip(sets, alone):
+        for got, w in zip(s.snapshot(), want):
+            assert np.array_equal(got.view(np.uint8), w.view(np.uint8))
+    plan.close()
