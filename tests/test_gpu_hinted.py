@@ -632,3 +632,53 @@ def test_weighted_candidate_under_any_prediction(R, pack_align):
     assert pkg.hsadmm_step(b.plan, b.W, U=b.U, U_out=b.Uout, Zg=dZg, Vd=dVd, coef=coef, Z=b.Z, mask=b.mask,
                            sel_prev=rec, residuals=res, Zi_prev=b.Uout, workspace=b.ws, check=False) == -1
     b.plan.close()
+
+
+@pytest.mark.parametrize("name", ["resnet50", "resnet152", "resnet50_both"])
+def test_named_workloads_at_full_size_weighted_under_predictions(name):
+    """The candidate of Eq. (9) on the benchmark's workloads at full size under the right record and one with a tenth
+    of every layer's kept groups exchanged (dual out of place, shrinkage of c = z_i + v_i, residual norms on the way):
+    every element of every output against the oracle."""
+    from tests.gpu_harness import packed_segment_sizes
+    oracle.set_threads(16)
+    wl = wk.make_workload(name)
+    W, U = wk.generate(wl, threads=16)
+    t = wl.table()
+    L = len(wl.layers)
+    rng = np.random.default_rng(91)
+    a, bb = oracle.node_coefficients(np.full(L, 1.5e-3), np.full(L, 1.5e-4), 1e-4, 16, wl.R)
+    Zg = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.05
+    Vd = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.01
+    Zp = rng.standard_normal(wl.n_arena).astype(np.float32) * 0.05
+    ref = oracle.project_weighted(t, W, U, Zg, Vd, a, bb)
+    refc = oracle.compact(t, oracle.add_arenas(t, ref["Z"], Vd), ref["mask"])
+    sq = oracle.residuals(t, W, ref["Z"], Zp)
+    sizes = packed_segment_sizes(wl, ref["mask"])
+    want_sel = record_of(wl, ref["mask"])
+    b = _Bufs(wl, W, U, 1)
+    dev = b.U.device
+    dZg, dVd, dZp = torch.from_numpy(Zg).to(dev), torch.from_numpy(Vd).to(dev), torch.from_numpy(Zp).to(dev)
+    coef = torch.from_numpy(np.stack([a, bb], axis=1).astype(np.float32).reshape(-1).copy()).to(dev)
+    for rec in (want_sel, record_of(wl, degrade(wl, ref["mask"], 0.1, rng))):
+        b.reset()
+        b.out_of_place = True
+        res = torch.full((4 * L,), -7.0, dtype=torch.float64, device=dev)
+        pkg.hsadmm_step(b.plan, b.W, U=b.U, U_out=b.Uout, Zg=dZg, Vd=dVd, coef=coef, Z=b.Z, mask=b.mask, sel=b.sel,
+                        sel_prev=torch.from_numpy(rec).to(dev), packed=b.packed, layer_off=b.off, kept_idx=b.kept,
+                        residuals=res, Zi_prev=dZp, workspace=b.ws)
+        got = b.outputs()
+        assert np.array_equal(got["mask"], ref["mask"]) and np.array_equal(got["sel"], want_sel)
+        for key in ("Z", "U"):
+            for l in wl.layers:
+                sl = slice(l.elem_off, l.elem_off + l.n)
+                assert np.array_equal(got[key][sl].view(np.uint32), ref[key][sl].view(np.uint32)), (key, l.name)
+        assert np.array_equal(got["layer_off"], refc["layer_off"])
+        for li in range(L):
+            lo = int(refc["layer_off"][li])
+            assert np.array_equal(got["packed"][lo:lo + sizes[li]].view(np.uint32),
+                                  refc["packed"][lo:lo + sizes[li]].view(np.uint32)), li
+        got_res = res.cpu().numpy().reshape(4, L)
+        for li, l in enumerate(wl.layers):
+            tol = max(1e-12, l.n * wl.R * 2.0 ** -53)
+            np.testing.assert_allclose(got_res[:2, li], sq[:2, li], rtol=tol, atol=0, err_msg=l.name)
+    b.plan.close()
