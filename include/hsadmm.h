@@ -17,6 +17,11 @@
  * and the mask drift (Section 4.5).
  * Each projection (hsadmm_project, _frozen, _weighted, _weighted_frozen) also exists as a *_compact call that returns the
  * shrunk buffer as well, with the same results as the projection followed by the compaction.
+ * hsadmm_step is the one entry point behind all of these forms (an argument structure; the named calls are it with
+ * fields left NULL).  It also takes the previous outer iteration's selection as a prediction (Section 4.5: the
+ * pattern stops changing after a few iterations), which changes no result and makes a step whose selection comes
+ * out as predicted touch every element once; and it forms the intra-node residual norms on the way.
+ * hsadmm_stopping_test (host) is the break test of Algorithm 1's Phase 5.
  *
  * Data layout.  A layer is the row-major fp32 array W[c_out][c_in][khw]
  * (Section 2, first paragraph; khw = K_H*K_W, 1 for linear layers).  A
