@@ -949,6 +949,9 @@ def main():
                    "buffer_sets_rotated": nsets, "expand_reuses_cached_index_mappings": not args.expand_rescan,
                    "compact_reuses_the_selections_index_mappings": not args.compact_rescan,
                    "project_and_compact_in_one_call": one_call,
+                   # no prediction is given to the step `value` times; for large plans of filter groups the library
+                   # forms one inside pass 1 from the keys of every layer's first rows (hsadmm_plan_estimates)
+                   "within_call_estimate": bool(pkg.hsadmm_plan_estimates(plan)),
                    "algorithmic_bytes_per_step": bytes_["step"], "cache_resident": cache_resident,
                    "value_from": value_from},
         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),

@@ -736,6 +736,20 @@ int hsadmm_version(void);
 int hsadmm_kernel_timing_enable(hsadmm_plan_t* plan, int enable);
 int hsadmm_kernel_timing_read(hsadmm_plan_t* plan, double* total_ms, int64_t* launches);
 int hsadmm_kernel_grid(const hsadmm_plan_t* plan, int kernel_id);
+/*
+ * 1 if the un-predicted projection of this plan (hsadmm_project, hsadmm_project_compact, hsadmm_step without sel_prev,
+ * dual in place) forms a prediction inside its first pass, else 0 (also for a NULL plan).  It does so for plans of
+ * FILTER and unconstrained layers of 20 Mi elements or more: every FILTER layer's first rows (a sixteenth, 16 to 128)
+ * are processed ahead of the rest, the key that the layer's keep ratio of them exceed estimates the layer's selection
+ * threshold (Eq. (10) keeps the k largest norms), and every later row is written in the form its own key suggests --
+ * kept, or pruned with the kept-form dual held in Z -- before the selection has been made.  The selection and the
+ * pass after it then give every output its exact value whatever was estimated; an estimate only decides how many
+ * rows that pass has to touch a second time.  Results do not depend on it; the time of a call does, a little, on how
+ * the norms are ordered inside a layer.  Smaller plans and plans with CHANNEL or BOTH layers write every row in the
+ * kept form and repair the pruned ones.  Environment, read by hsadmm_plan_create: HSADMM_NO_ESTIMATE (any value)
+ * switches the estimate off, HSADMM_FORCE_ESTIMATE takes it whatever the size.
+ */
+int hsadmm_plan_estimates(const hsadmm_plan_t* plan);
 /* Name of a kernel id ("" when out of range). */
 const char* hsadmm_kernel_name(int kernel_id);
 

@@ -37,7 +37,7 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_project_weighted_frozen", "hsadmm_project_weighted_frozen_compact",
            "hsadmm_retrain_project", "hsadmm_retrain_expand",
            "hsadmm_adapt_penalties", "hsadmm_scale_layers", "hsadmm_project_compact_static",
-           "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid",
+           "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid", "hsadmm_plan_estimates",
            "hsadmm_layer_sqnorms", "hsadmm_stopping_test")
 KERNEL_COUNT = 29
 
@@ -194,6 +194,8 @@ def load_library():
     lib.hsadmm_stopping_test.restype = ctypes.c_int
     lib.hsadmm_kernel_grid.argtypes = [vp, ctypes.c_int]
     lib.hsadmm_kernel_grid.restype = ctypes.c_int
+    lib.hsadmm_plan_estimates.argtypes = [vp]
+    lib.hsadmm_plan_estimates.restype = ctypes.c_int
     lib.hsadmm_kernel_name.argtypes = [ctypes.c_int]
     lib.hsadmm_kernel_name.restype = ctypes.c_char_p
     _lib = lib
@@ -297,6 +299,11 @@ def hsadmm_kernel_timing_read(plan: Plan):
     return {lib.hsadmm_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(KERNEL_COUNT)}
 
 
+def hsadmm_plan_estimates(plan: Plan) -> bool:
+    """Whether this plan's un-predicted projection forms a prediction inside pass 1 (see include/hsadmm.h)."""
+    return bool(load_library().hsadmm_plan_estimates(plan.handle))
+
+
 def hsadmm_kernel_grids(plan: Plan):
     """{kernel name: workgroups of its latest timed launch on this plan} (0: not launched with timing on)."""
     lib = load_library()
@@ -340,9 +347,7 @@ def hsadmm_project_compact_static(plan: Plan, W_replicas: Sequence, U, Z, Wbar, 
                                            _ptr(sqnorm), _ptr(packed), _ptr(layer_off), _ptr(kept_idx),
                                            _stream(stream))
     if check and rc != 0:
-        raise HsadmmError(rc, "hsadmm_project_compact_static",
-           "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid",
-           "hsadmm_layer_sqnorms", "hsadmm_stopping_test")
+        raise HsadmmError(rc, "hsadmm_project_compact_static")
     return rc
 
 

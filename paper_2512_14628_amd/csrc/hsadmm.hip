@@ -71,6 +71,7 @@
 #include "kernels_select.hpp"
 #include "kernels_frozen.hpp"
 #include "kernels_hinted.hpp"
+#include "kernels_estimate.hpp"
 #include "kernels_weighted.hpp"
 #include "kernels_residuals.hpp"
 #include "kernels_compact.hpp"
@@ -99,7 +100,7 @@ hipError_t for_replica_count(int R, F&& f)
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct WsLayout {
-    size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, work, rowres, total;
+    size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, work, rowres, pred, est_cnt, est_keys, est_thr, est_thr_tag, total;
 };
 
 enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kPass1Hinted, kHintedRepair, kSqnormPart, kResPick, kWHintedRepair, kKernelCount };
@@ -119,6 +120,7 @@ struct hsadmm_plan {
     std::vector<hsadmm_layer_t> layers;
     std::vector<DevLayer> dev_layers;
     std::vector<WorkItem> items_proj;   // project kernels
+    std::vector<WorkItem> items_est;    // project_pass1_est: items_proj with every FILTER layer's first items ahead of the rest
     std::vector<WorkItem> items_rows;   // compact / expand kernels
     std::vector<WorkItem> items_fix;    // project_fixup, weighted_fixup: the row items of the FILTER layers
     std::vector<WorkItem> items_none;   // weighted_fixup_pack: the row items of the unconstrained layers
@@ -137,6 +139,7 @@ struct hsadmm_plan {
     int device = -1;
     DevLayer* d_layers = nullptr;
     WorkItem* d_items_proj = nullptr;
+    WorkItem* d_items_est = nullptr;
     WorkItem* d_items_rows = nullptr;
     WorkItem* d_items_fix = nullptr;
     WorkItem* d_items_none = nullptr;
@@ -148,6 +151,8 @@ struct hsadmm_plan {
     uint16_t* d_group_layer = nullptr;   // groups_total: scan segment of every group (bit 15: unconstrained layer)
     float* d_coef = nullptr;             // 2L: a_l, b_l of Eq. (9), set by hsadmm_plan_set_node_weights (default 1, 0)
     void* static_ws = nullptr;           // device address of `scratch` on the plan's device
+    bool use_estimate = false;           // the un-predicted projection forms a prediction inside pass 1 (kernels_estimate.hpp)
+    std::atomic<unsigned> est_calls{0};  // numbers those calls (the estimate's counts carry the number of their call)
     uint16_t* d_chunk_layer = nullptr;   // per 16 groups: their segment if all 16 lie in one constrained segment, else 0xffff
     // Optional per-kernel timing (diagnostics; off by default): the only state of a plan that changes after its
     // creation.  Launches from several host threads claim their event pairs through the atomic counter; enabling
@@ -451,7 +456,41 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->ws.respart = off;    off = align_up(off + sizeof(double) * 4 * p->items_rows.size(), 256);
         p->ws.work = off;       off = align_up(off + sizeof(int32_t) * (kWorkHeader + p->items_rows.size()), 256);
         p->ws.rowres = off;     off = align_up(off + sizeof(double) * 4 * (size_t)gb, 256);
+        p->ws.pred = off;       off = align_up(off + sizeof(int32_t) * (size_t)gb, 256);
+        p->ws.est_cnt = off;    off = align_up(off + sizeof(unsigned int) * (size_t)L * kSampleKeys, 256);
+        p->ws.est_keys = off;   off = align_up(off + sizeof(double) * (size_t)L * kSampleKeys, 256);
+        p->ws.est_thr = off;    off = align_up(off + sizeof(double) * (size_t)L, 256);
+        p->ws.est_thr_tag = off; off = align_up(off + sizeof(unsigned int) * (size_t)L, 256);
         p->ws.total = off;
+        // The estimate's item order: of every FILTER layer the items that cover its first rows (a sixteenth of them,
+        // 16 at least, kSampleKeys at most), then everything else in the usual order.
+        bool only_rows = true, any_filter = false;
+        for (int32_t l = 0; l < L; ++l) {
+            only_rows = only_rows && (layers[l].mode == HSADMM_MODE_FILTER || layers[l].mode == HSADMM_MODE_NONE);
+            any_filter = any_filter || layers[l].mode == HSADMM_MODE_FILTER;
+        }
+        // (the first rows' detour costs a few microseconds per launch whatever the size: measured a loss on plans of
+        // 12 M elements and less, a gain from 25 M on)
+        int64_t n_elems_total = 0;
+        for (int32_t l = 0; l < L; ++l) n_elems_total += (int64_t)layers[l].c_out * layers[l].c_in * layers[l].khw;
+        // (environment, read here once per plan: HSADMM_NO_ESTIMATE switches the path off, HSADMM_FORCE_ESTIMATE takes
+        // it whatever the size, which is how the tests reach it with small tables)
+        p->use_estimate = only_rows && any_filter && std::getenv("HSADMM_NO_ESTIMATE") == nullptr &&
+                          (n_elems_total >= kEstimateMinElems || std::getenv("HSADMM_FORCE_ESTIMATE") != nullptr);
+        if (p->use_estimate) {
+            std::vector<WorkItem> rest;
+            for (WorkItem it : p->items_proj) {
+                const DevLayer& d = p->dev_layers[it.layer];
+                const bool filter = (it.flags & 3) == HSADMM_MODE_FILTER;
+                const bool holds = filter && (it.flags & 4) != 0 && (int64_t)it.nr * it.row_len <= kStageElems &&
+                                   it.nr <= kStageRows;
+                const int sample_rows = sample_rows_of(d.G);
+                it.col0 = !holds ? kEstPlain : (it.row0 < sample_rows ? kEstSample : kEstUse);
+                if (it.col0 == kEstSample) p->items_est.push_back(it);
+                else rest.push_back(it);
+            }
+            p->items_est.insert(p->items_est.end(), rest.begin(), rest.end());
+        }
     } catch (...) {   // host allocation failure while building the tables
         delete p;
         return HSADMM_ERR_HOST_MEMORY;
@@ -495,6 +534,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
     upload(p->items_rows, &p->d_items_rows);
     upload(p->items_fix, &p->d_items_fix);
     upload(p->items_none, &p->d_items_none);
+    upload(p->items_est, &p->d_items_est);
     upload(p->items_plain, &p->d_items_plain);
     upload(p->items_bfinal, &p->d_items_bfinal);
     upload(p->items_chan, &p->d_items_chan);
@@ -521,6 +561,7 @@ void hsadmm_plan_destroy(hsadmm_plan_t* p)
     if (p->d_items_rows) (void)hipFree(p->d_items_rows);
     if (p->d_items_fix) (void)hipFree(p->d_items_fix);
     if (p->d_items_none) (void)hipFree(p->d_items_none);
+    if (p->d_items_est) (void)hipFree(p->d_items_est);
     if (p->d_items_plain) (void)hipFree(p->d_items_plain);
     if (p->d_items_bfinal) (void)hipFree(p->d_items_bfinal);
     if (p->d_items_chan) (void)hipFree(p->d_items_chan);
@@ -592,6 +633,19 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     const bool hinted = sel_prev != nullptr && (!p->items_plain.empty() || hinted_chan || hinted_both);
     const HintArgs h{sel_prev, out ? out->packed : nullptr, U_out ? 0 : 1, reinterpret_cast<int32_t*>(ws + p->ws.work),
                      p->d_layers};
+    // Without a caller's prediction, a plan of FILTER and unconstrained layers whose dual is updated in place forms
+    // one inside pass 1 (kernels_estimate.hpp).
+    const bool est = !hinted && sel_prev == nullptr && U_out == nullptr && p->use_estimate;
+    EstArgs ex{};
+    if (est) {
+        ex.pred = reinterpret_cast<int32_t*>(ws + p->ws.pred);
+        ex.tag = reinterpret_cast<unsigned int*>(ws + p->ws.est_cnt);
+        ex.keys = reinterpret_cast<double*>(ws + p->ws.est_keys);
+        ex.thr = reinterpret_cast<double*>(ws + p->ws.est_thr);
+        ex.thr_tag = reinterpret_cast<unsigned int*>(ws + p->ws.est_thr_tag);
+        ex.layers = p->d_layers;
+        ex.gen = const_cast<hsadmm_plan*>(p)->est_calls.fetch_add(1, std::memory_order_relaxed) + 1u;
+    }
     WorkList wl{};
     if (hinted) {
         // the selection lists the row items the repair pass must visit, and hands out the offsets and kept lists itself
@@ -609,6 +663,14 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
                 return launch(p, kPass1Hinted, project_pass1_hinted<decltype(c)::value>, (unsigned)p->items_proj.size(),
                               kBlock, s, (const WorkItem*)p->d_items_proj, a, (int)R, h);
             });
+    } else if (est) {
+        // the prediction is formed inside pass 1 and recorded for the repair pass; the selection hands out the offsets
+        // and kept lists itself
+        if (out) wl.co = CopyOut{out->layer_off, out->kept_idx};
+        e = for_replica_count<true>(R, [&](auto c) {
+            return launch(p, kPass1, project_pass1_est<decltype(c)::value>, (unsigned)p->items_est.size(), kBlock, s,
+                          (const WorkItem*)p->d_items_est, a, (int)R, ex);
+        });
     } else {
         e = for_replica_count<true>(R, [&](auto c) { return launch_pass1<decltype(c)::value>(p, a, R, s); });
     }
@@ -618,7 +680,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     // The compaction of Z under the selection just made reads kept groups only, which FILTER layers hold in
     // final form since pass 1, so it shares a launch with the FILTER fix-up; the CHANNEL and BOTH layers are
     // packed by the pass that writes their Z.
-    const bool fuse = out && !hinted && !p->items_fix.empty();
+    const bool fuse = out && !hinted && !est && !p->items_fix.empty();
     PackOut po{};
     po.pos = reinterpret_cast<const int32_t*>(ws + p->ws.pos);
     if (out) {
@@ -649,6 +711,22 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
             }
             if (e != hipSuccess) return HSADMM_ERR_HIP;
         }
+    } else if (est) {
+        // every FILTER row from the form pass 1 chose to its final form (kept rows packed on the way) and, with a
+        // compaction, the rows of the unconstrained layers gathered, in one launch
+        const unsigned n_fix = (unsigned)p->items_fix.size();
+        if (out)
+            e = for_replica_count<true>(R, [&](auto c) {
+                return launch(p, kFixupGather, fixup_gather_est<decltype(c)::value>, n_fix + (unsigned)p->items_none.size(),
+                              kBlock, s, (const WorkItem*)p->d_items_fix, (int)n_fix, a, (int)R, (const int32_t*)ex.pred,
+                              (const WorkItem*)p->d_items_none, po);
+            });
+        else
+            e = for_replica_count<true>(R, [&](auto c) {
+                return launch(p, kFixup, project_fixup_est<decltype(c)::value>, n_fix, kBlock, s,
+                              (const WorkItem*)p->d_items_fix, a, (int)R, (const int32_t*)ex.pred, po.pos);
+            });
+        if (e != hipSuccess) return HSADMM_ERR_HIP;
     } else if (!p->items_fix.empty() && !fuse) {
         e = launch(p, kFixup, project_fixup, (unsigned)p->items_fix.size(), kBlock, s,
                    (const WorkItem*)p->d_items_fix, (const uint8_t*)mask, a.U, Z);
@@ -656,7 +734,7 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
     }
     // Without FILTER layers the gather of the plain rows (unconstrained layers) has no fix-up to share a launch
     // with; it then rides on the last final pass.
-    bool plain_pending = out && !fuse && !hinted && !p->items_plain.empty();
+    bool plain_pending = out && !fuse && !hinted && !est && !p->items_plain.empty();
     const unsigned n_plain = (unsigned)p->items_plain.size();
     if (!p->items_bfinal.empty() && !hinted_both) {
         // layers under both constraints: final Z and U from the parked mean and U, under both selections
@@ -1518,6 +1596,8 @@ int hsadmm_kernel_timing_read(hsadmm_plan_t* p, double* total_ms, int64_t* launc
     p->ev_used.store(0);
     return HSADMM_OK;
 }
+
+int hsadmm_plan_estimates(const hsadmm_plan_t* p) { return (p && p->use_estimate) ? 1 : 0; }
 
 int hsadmm_kernel_grid(const hsadmm_plan_t* p, int kernel_id)
 {

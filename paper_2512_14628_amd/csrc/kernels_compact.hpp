@@ -295,6 +295,33 @@ __global__ __launch_bounds__(kBlock) void fixup_gather(const WorkItem* __restric
                            packed, co);
 }
 
+// After the selection of a step whose pass 1 formed its own prediction (kernels_estimate.hpp): every FILTER row from
+// the form pass 1 gave it (pred, a prediction record without ranks) to its final form (hinted_repair_rows with the
+// dual in place).  project_fixup_est: the projection alone.  fixup_gather_est: with a compaction, kept rows are packed
+// on the way and the rows of the unconstrained layers gathered in the same launch; workgroups [0, n_fix) take the
+// FILTER row items, the rest those of the unconstrained layers.
+template <int R>
+__global__ __launch_bounds__(kBlock) void project_fixup_est(const WorkItem* __restrict__ fix_items, ProjectArgs a, int Rrt,
+                                                            const int32_t* __restrict__ pred,
+                                                            const int32_t* __restrict__ pos)
+{
+    hinted_repair_rows<R>(fix_items[blockIdx.x], a, Rrt, pred, pos, true, nullptr);
+}
+
+template <int R>
+__global__ __launch_bounds__(kBlock) void fixup_gather_est(const WorkItem* __restrict__ fix_items, int n_fix,
+                                                           ProjectArgs a, int Rrt, const int32_t* __restrict__ pred,
+                                                           const WorkItem* __restrict__ none_items, PackOut po)
+{
+    if ((int)blockIdx.x < n_fix) {
+        const WorkItem it = fix_items[blockIdx.x];
+        hinted_repair_rows<R>(it, a, Rrt, pred, po.pos, true, po.packed + it.packed_off);
+    } else {
+        gather_item<false>(none_items[(int)blockIdx.x - n_fix], a.Z, nullptr, po.pos, po.cnt, po.kept_idx, po.n_layers,
+                           po.layer_off, po.packed, po.co);
+    }
+}
+
 // The final pass of CHANNEL or BOTH layers with its packing (project_frozen<R, true>) and the gather of the plain
 // layers' rows (FILTER / NONE, final before this launch) in one launch: workgroups [0, n_final) take the final-pass
 // items, the rest the plain row items.  The two kinds of workgroup touch different layers.
