@@ -746,7 +746,11 @@ int hsadmm_kernel_grid(const hsadmm_plan_t* plan, int kernel_id);
  * pass after it then give every output its exact value whatever was estimated; an estimate only decides how many
  * rows that pass has to touch a second time.  Results do not depend on it; the time of a call does, a little, on how
  * the norms are ordered inside a layer.  Smaller plans and plans with CHANNEL or BOTH layers write every row in the
- * kept form and repair the pruned ones.  Environment, read by hsadmm_plan_create: HSADMM_NO_ESTIMATE (any value)
+ * kept form and repair the pruned ones.  The published keys live in the caller's workspace, tagged with the number
+ * of their call; that number comes from an atomic counter in the plan (the one thing besides the timing record that
+ * a call changes in a plan), so calls from several threads stay safe.  A captured graph replays its call number: a
+ * replay may then use the estimate an earlier replay left, which again changes no result.  Environment, read by
+ * hsadmm_plan_create: HSADMM_NO_ESTIMATE (any value)
  * switches the estimate off, HSADMM_FORCE_ESTIMATE takes it whatever the size.
  */
 int hsadmm_plan_estimates(const hsadmm_plan_t* plan);

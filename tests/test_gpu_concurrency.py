@@ -44,14 +44,25 @@ class _Set:
         return [t.cpu().numpy().copy() for t in (self.U, self.Z, self.dst, self.mask, self.packed, self.off, self.kept)]
 
 
-def test_two_threads_share_a_plan():
+FILTER_SHAPES = [(384, 128, 9, wk.MODE_FILTER, 150), (512, 256, 1, wk.MODE_FILTER, 200), (100, 512, 1, wk.MODE_NONE, 100),
+                 (1024, 64, 1, wk.MODE_FILTER, 300), (300, 147, 1, wk.MODE_FILTER, 100)]
+
+
+@pytest.mark.parametrize("estimate", [False, True])
+def test_two_threads_share_a_plan(estimate, monkeypatch):
+    """estimate: a plan of filter groups whose un-predicted first step forms its prediction inside pass 1 (the keys it
+    publishes live in each caller's workspace; only the call counter is the plan's, and it is atomic)."""
     from tests.test_gpu_hinted import SHAPES
+    if estimate:
+        monkeypatch.setenv("HSADMM_FORCE_ESTIMATE", "1")
+    shapes = FILTER_SHAPES if estimate else SHAPES
     dev = torch.device("cuda:0")
-    wl = wk.custom_workload(SHAPES, R=4, seed=77, sigma_replica=0.03)
+    wl = wk.custom_workload(shapes, R=4, seed=77, sigma_replica=0.03)
     plan = pkg.Plan(wl.table())
+    assert pkg.hsadmm_plan_estimates(plan) == estimate
     inputs = []
     for seed in (1, 2):
-        w = wk.custom_workload(SHAPES, R=4, seed=seed, sigma_replica=0.03)
+        w = wk.custom_workload(shapes, R=4, seed=seed, sigma_replica=0.03)
         inputs.append(wk.generate(w))
     steps = 25
     # alone, one after the other
