@@ -53,7 +53,7 @@ def _load():
     lib.oracle_set_threads.argtypes = [ctypes.c_int]
     lib.oracle_set_threads.restype = None
     lib.oracle_get_threads.restype = ctypes.c_int
-    lib.oracle_project.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p, i32p, i32p,
+    lib.oracle_project.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p, i32p, i32p, i32p,
                                    ctypes.POINTER(f32p), ctypes.c_int32, f32p, f32p, f32p, u8p, f64p]
     lib.oracle_project.restype = ctypes.c_int
     lib.oracle_compact.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p, ctypes.c_int32,
@@ -69,7 +69,7 @@ def _load():
     lib.oracle_node_coefficients.argtypes = [ctypes.c_int32, f64pp, f64pp, ctypes.c_double, ctypes.c_int32,
                                              ctypes.c_int32, f32p, f32p]
     lib.oracle_node_coefficients.restype = ctypes.c_int
-    lib.oracle_project_weighted.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p, i32p, i32p,
+    lib.oracle_project_weighted.argtypes = [ctypes.c_int32, i64p, i32p, i32p, i32p, i32p, i32p, i32p, i32p,
                                             ctypes.POINTER(f32p), ctypes.c_int32, f32p, f32p, f32p, f32p, f32p,
                                             f32p, f32p, u8p, f64p]
     lib.oracle_project_weighted.restype = ctypes.c_int
@@ -125,6 +125,9 @@ def _cols(table):
     # channels kept by a layer under both constraints (mode 3); tables without such layers may omit it
     out["k_in"] = (np.ascontiguousarray(table["k_in"], dtype=np.int32) if "k_in" in table
                    else np.zeros(len(out["k"]), dtype=np.int32))
+    # shape groups kept by a layer of mode 5 or 6 (after its channels); tables without such layers may omit it
+    out["k_kern"] = (np.ascontiguousarray(table["k_kern"], dtype=np.int32) if "k_kern" in table
+                     else np.zeros(len(out["k"]), dtype=np.int32))
     return out
 
 
@@ -141,6 +144,8 @@ def groups_total(table) -> int:
     t = _cols(table)
     g = np.where(t["mode"] == 2, t["c_in"], t["c_out"]) + np.where(t["mode"] == 3, t["c_in"], 0)
     g = np.where(t["mode"] == 4, t["c_in"] * t["khw"], g)
+    g = np.where(t["mode"] == 5, t["c_in"] + t["c_in"] * t["khw"], g)
+    g = np.where(t["mode"] == 6, t["c_out"] + t["c_in"] + t["c_in"] * t["khw"], g)
     return int(g.sum())
 
 
@@ -169,7 +174,7 @@ def project(table, W, U, want_wbar: bool = False):
     rc = lib.oracle_project(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
                             _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
                             _p(t["mode"], ctypes.c_int32), _p(t["k"], ctypes.c_int32),
-                            _p(t["k_in"], ctypes.c_int32),
+                            _p(t["k_in"], ctypes.c_int32), _p(t["k_kern"], ctypes.c_int32),
                             ptrs, R, _p(U_new, ctypes.c_float), _p(Z, ctypes.c_float),
                             _p(Wbar, ctypes.c_float) if want_wbar else None,
                             _p(mask, ctypes.c_uint8), _p(key, ctypes.c_double))
@@ -350,7 +355,7 @@ def project_weighted(table, W, U, Zg, Vd, a, b, want_wbar: bool = False):
     rc = lib.oracle_project_weighted(L, _p(t["elem_off"], ctypes.c_int64), _p(t["c_out"], ctypes.c_int32),
                                      _p(t["c_in"], ctypes.c_int32), _p(t["khw"], ctypes.c_int32),
                                      _p(t["mode"], ctypes.c_int32), _p(t["k"], ctypes.c_int32),
-                                     _p(t["k_in"], ctypes.c_int32), ptrs, R,
+                                     _p(t["k_in"], ctypes.c_int32), _p(t["k_kern"], ctypes.c_int32), ptrs, R,
                                      _p(U_new, ctypes.c_float), _p(Zg, ctypes.c_float), _p(Vd, ctypes.c_float),
                                      _p(a, ctypes.c_float), _p(b, ctypes.c_float), _p(Z, ctypes.c_float),
                                      _p(Wbar, ctypes.c_float) if want_wbar else None,

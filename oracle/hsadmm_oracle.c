@@ -22,6 +22,16 @@
  *     mode 3, both:       the intersection S_f ^ S_c of Section 2.1: c_out filter
  *                         groups followed by c_in channel groups (G = c_out + c_in);
  *                         k filters and k_in channels are kept.
+ *     mode 5, channel ^ shape:  S_c ^ S_s of Section 2.1: c_in channel groups followed by c_in*khw
+ *                         shape groups (G = c_in + c_in*khw); k_in channels and k_kern shape groups
+ *                         are kept.
+ *     mode 6, all three:  S_f ^ S_c ^ S_s, the composite set of Section 2.1 in full: c_out filter
+ *                         groups, c_in channel groups, c_in*khw shape groups (G = their sum);
+ *                         k filters, k_in channels, k_kern shape groups are kept.
+ *                         Modes 5 and 6 are defined for the projection (oracle_project,
+ *                         oracle_project_weighted) only: the other functions take such a layer
+ *                         through its GEMM view, where the shape groups are the columns (mode 2,
+ *                         or mode 3 with the filters), and refuse these two modes.
  * Mask and key arrays hold the groups of all layers, concatenated in table
  * order.
  *
@@ -42,7 +52,8 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_NONE = 0, ORACLE_FILTER = 1, ORACLE_CHANNEL = 2, ORACLE_BOTH = 3, ORACLE_SHAPE = 4 };
+enum { ORACLE_NONE = 0, ORACLE_FILTER = 1, ORACLE_CHANNEL = 2, ORACLE_BOTH = 3, ORACLE_SHAPE = 4,
+       ORACLE_CHANNEL_SHAPE = 5, ORACLE_ALL = 6 };
 
 static int g_threads = 1;
 
@@ -61,7 +72,24 @@ static int64_t n_groups(int mode, int c_out, int c_in, int khw)
 {
     if (mode == ORACLE_SHAPE) return (int64_t)c_in * khw;
     if (mode == ORACLE_BOTH) return (int64_t)c_out + c_in;
+    if (mode == ORACLE_CHANNEL_SHAPE) return (int64_t)c_in + (int64_t)c_in * khw;
+    if (mode == ORACLE_ALL) return (int64_t)c_out + c_in + (int64_t)c_in * khw;
     return mode == ORACLE_CHANNEL ? c_in : c_out;
+}
+
+/* The counts of a layer are in range for its mode (k_kern may be NULL when the mode does not read it). */
+static int counts_ok(int mode, int64_t co, int64_t ci, int64_t s, int64_t k, int64_t k_in, const int32_t *k_kern,
+                     int32_t l)
+{
+    if (mode == ORACLE_NONE) return 1;
+    if (mode == ORACLE_BOTH) return k >= 1 && k <= co && k_in >= 1 && k_in <= ci;
+    if (mode == ORACLE_CHANNEL_SHAPE || mode == ORACLE_ALL) {
+        if (!k_kern) return 0;
+        if (mode == ORACLE_ALL && (k < 1 || k > co)) return 0;
+        return k_in >= 1 && k_in <= ci && k_kern[l] >= 1 && k_kern[l] <= k_in * s;
+    }
+    if (mode < ORACLE_NONE || mode > ORACLE_ALL) return 0;
+    return k >= 1 && k <= n_groups(mode, (int)co, (int)ci, (int)s);
 }
 
 /*
@@ -129,8 +157,64 @@ static void project_composite(float *x, int64_t co, int64_t ci, int64_t s, int64
 }
 
 /*
+ * The shape projection when a channel projection has gone before it (S_c ^ S_s, Section 2.1; the
+ * projections one after the other, Section 3, paragraph after Eq. (10)): the positions of a pruned
+ * channel are zero already and are not candidates; of the positions of the kept channels (cm[b] != 0),
+ * the kk of largest norm are kept (equal norms: lower index first).  The norms are those of x as it
+ * stands; key and m get all ci*s entries (m = 0 for a position of a pruned channel).
+ * Applying the plain shape projection to x instead would give the same x: a position of a pruned
+ * channel has norm 0, so where the plain ranking prefers it to a candidate, that candidate is zero
+ * too.  Only the mask can differ then (it would name positions of pruned channels); this form keeps
+ * the mask inside the support of the channel projection.
+ */
+static void project_shapes_within(float *x, int64_t co, int64_t ci, int64_t s, int64_t kk, const uint8_t *cm,
+                                  double *key, uint8_t *m)
+{
+    const int64_t G = ci * s;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < G; ++g) {
+        double acc = 0.0;
+        for (int64_t o = 0; o < co; ++o) {
+            const double y = (double)x[o * G + g];
+            acc += y * y;
+        }
+        key[g] = acc;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < G; ++g) {
+        int64_t before = 0;
+        if (!cm[g / s]) { m[g] = 0; continue; }
+        for (int64_t h = 0; h < G; ++h)
+            if (cm[h / s] && (key[h] > key[g] || (key[h] == key[g] && h < g))) ++before;
+        m[g] = before < kk ? 1 : 0;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < co * G; ++e)
+        if (!m[e % G]) x[e] = 0.0f;
+}
+
+/*
+ * Composite projection for S_c ^ S_s (filters = 0) and S_f ^ S_c ^ S_s (filters = 1), Section 2.1:
+ * the individual projections one after the other in the order the paper lists the sets, filters,
+ * then channels, then shape groups, each on the output of the one before.
+ * key, m: (c_out filter entries,) c_in channel entries, c_in*s shape entries.
+ */
+static void project_nested(float *x, int64_t co, int64_t ci, int64_t s, int filters, int64_t k_out, int64_t k_in,
+                           int64_t k_kern, double *key, uint8_t *m)
+{
+    if (filters) {
+        project_in_place(x, co, ci, s, 0, k_out, key, m);
+        key += co;
+        m += co;
+    }
+    project_in_place(x, co, ci, s, 1, k_in, key, m);
+    project_shapes_within(x, co, ci, s, k_kern, m, key + ci, m + ci);
+}
+
+/*
  * Steps (a)-(d) for every layer.  (A layer under both constraints takes (b) and (c) from
- * project_composite above; k_in is read for such layers only.)
+ * project_composite above; k_in is read for such layers only.  k_kern is read for layers of modes 5
+ * and 6 only and may be NULL when the table has none.)
  *
  *  (a) consensus average: Eq. (9) with lambda = 0 and rho_2 = 0 is the plain
  *      mean over the node's replicas; summed left to right in fp32, then
@@ -150,7 +234,7 @@ static void project_composite(float *x, int64_t co, int64_t ci, int64_t s, int64
  */
 int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
                    const int32_t *khw, const int32_t *mode, const int32_t *k, const int32_t *k_in,
-                   const float *const *W, int32_t R, float *U, float *Z, float *Wbar,
+                   const int32_t *k_kern, const float *const *W, int32_t R, float *U, float *Z, float *Wbar,
                    uint8_t *mask, double *key)
 {
     if (L < 1 || R < 1 || !W || !U || !Z || !mask || !key || !k_in) return -1;
@@ -161,9 +245,7 @@ int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
         const int64_t n = co * ci * s;
         const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
         if (co < 1 || ci < 1 || s < 1) return -1;
-        if (mode[l] == ORACLE_BOTH) {
-            if (k[l] < 1 || k[l] > co || k_in[l] < 1 || k_in[l] > ci) return -1;
-        } else if (mode[l] != ORACLE_NONE && (k[l] < 1 || k[l] > G)) return -1;
+        if (!counts_ok(mode[l], co, ci, s, k[l], k_in[l], k_kern, l)) return -1;
         const int64_t off = elem_off[l];
         float *wbar = (float *)malloc(sizeof(float) * (size_t)n);
         float *v = (float *)malloc(sizeof(float) * (size_t)n);
@@ -181,10 +263,11 @@ int oracle_project(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
         }
         if (bad) { free(wbar); free(v); return -2; }
 
-        if (mode[l] == ORACLE_BOTH || mode[l] == ORACLE_SHAPE) {
-            /* (b), (c) under both constraints, or under shape sparsity: v becomes Pi_S(v); then (d) */
+        if (mode[l] >= ORACLE_BOTH) {
+            /* (b), (c) under several constraints, or under shape sparsity: v becomes Pi_S(v); then (d) */
             if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], k_in[l], key + gbase, mask + gbase);
-            else project_in_place(v, co, ci, s, 2, k[l], key + gbase, mask + gbase);
+            else if (mode[l] == ORACLE_SHAPE) project_in_place(v, co, ci, s, 2, k[l], key + gbase, mask + gbase);
+            else project_nested(v, co, ci, s, mode[l] == ORACLE_ALL, k[l], k_in[l], k_kern[l], key + gbase, mask + gbase);
 #pragma omp parallel for schedule(static)
             for (int64_t e = 0; e < n; ++e) {
                 Z[off + e] = v[e];
@@ -299,6 +382,7 @@ int oracle_compact(int32_t L, const int64_t *elem_off, const int32_t *c_out, con
         int64_t ci = c_in[l], s = khw[l];
         int lm = mode[l];
         const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
+        if (mode[l] > ORACLE_SHAPE) return -1;            /* modes 5, 6: through the GEMM view only */
         if (lm == ORACLE_SHAPE) {
             /* shape groups are the columns of the [c_out][c_in*khw] view: packed like channels of width 1 */
             ci *= s;
@@ -349,6 +433,7 @@ int oracle_expand(int32_t L, const int64_t *elem_off, const int32_t *c_out, cons
         int64_t ci = c_in[l], s = khw[l];
         int lm = mode[l];
         const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
+        if (mode[l] > ORACLE_SHAPE) return -1;            /* modes 5, 6: through the GEMM view only */
         if (lm == ORACLE_SHAPE) { ci *= s; s = 1; lm = ORACLE_CHANNEL; }     /* as in oracle_compact */
         int32_t *k_out = (int32_t *)malloc(sizeof(int32_t) * (size_t)co);
         int32_t *k_in = (int32_t *)malloc(sizeof(int32_t) * (size_t)ci);
@@ -399,6 +484,7 @@ int oracle_project_frozen(int32_t L, const int64_t *elem_off, const int32_t *c_o
         if (co < 1 || ci < 1 || s < 1) return -1;
         const int64_t n = co * ci * s;
         const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
+        if (mode[l] > ORACLE_SHAPE) return -1;            /* modes 5, 6: through the GEMM view only */
         const int64_t off = elem_off[l];
         const uint8_t *ml = mask + gbase;
         int bad = 0;
@@ -453,6 +539,7 @@ int oracle_mask_drift(int32_t L, const int32_t *c_out, const int32_t *c_in, cons
     int64_t gbase = 0;
     for (int32_t l = 0; l < L; ++l) {
         const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
+        if (mode[l] > ORACLE_SHAPE) return -1;            /* modes 5, 6: through the GEMM view only */
         int32_t d = 0;
         if (mode[l] != ORACLE_NONE)
             for (int64_t g = 0; g < G; ++g) d += ((a[gbase + g] != 0) != (b[gbase + g] != 0)) ? 1 : 0;
@@ -493,7 +580,7 @@ int oracle_node_coefficients(int32_t L, const double *rho1, const double *rho2, 
  */
 int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c_out, const int32_t *c_in,
                             const int32_t *khw, const int32_t *mode, const int32_t *k, const int32_t *k_in,
-                            const float *const *W, int32_t R, float *U, const float *Zg, const float *Vd,
+                            const int32_t *k_kern, const float *const *W, int32_t R, float *U, const float *Zg, const float *Vd,
                             const float *a, const float *b, float *Z, float *Wbar, uint8_t *mask, double *key)
 {
     if (L < 1 || R < 1 || !W || !U || !Zg || !Vd || !a || !b || !Z || !mask || !key || !k_in) return -1;
@@ -504,9 +591,7 @@ int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c
         if (co < 1 || ci < 1 || s < 1) return -1;
         const int64_t n = co * ci * s;
         const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
-        if (mode[l] == ORACLE_BOTH) {
-            if (k[l] < 1 || k[l] > co || k_in[l] < 1 || k_in[l] > ci) return -1;
-        } else if (mode[l] != ORACLE_NONE && (k[l] < 1 || k[l] > G)) return -1;
+        if (!counts_ok(mode[l], co, ci, s, k[l], k_in[l], k_kern, l)) return -1;
         const int64_t off = elem_off[l];
         float *wbar = (float *)malloc(sizeof(float) * (size_t)n);
         float *v = (float *)malloc(sizeof(float) * (size_t)n);
@@ -526,9 +611,10 @@ int oracle_project_weighted(int32_t L, const int64_t *elem_off, const int32_t *c
             if (!isfinite(v[e])) bad = 1;
         }
         if (bad) { free(wbar); free(v); return -2; }
-        if (mode[l] == ORACLE_BOTH || mode[l] == ORACLE_SHAPE) {
+        if (mode[l] >= ORACLE_BOTH) {
             if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], k_in[l], key + gbase, mask + gbase);
-            else project_in_place(v, co, ci, s, 2, k[l], key + gbase, mask + gbase);
+            else if (mode[l] == ORACLE_SHAPE) project_in_place(v, co, ci, s, 2, k[l], key + gbase, mask + gbase);
+            else project_nested(v, co, ci, s, mode[l] == ORACLE_ALL, k[l], k_in[l], k_kern[l], key + gbase, mask + gbase);
 #pragma omp parallel for schedule(static)
             for (int64_t e = 0; e < n; ++e) {
                 Z[off + e] = v[e];
@@ -609,6 +695,7 @@ int oracle_project_weighted_frozen(int32_t L, const int64_t *elem_off, const int
         if (co < 1 || ci < 1 || s < 1) return -1;
         const int64_t n = co * ci * s;
         const int64_t G = n_groups(mode[l], c_out[l], c_in[l], khw[l]);
+        if (mode[l] > ORACLE_SHAPE) return -1;            /* modes 5, 6: through the GEMM view only */
         const int64_t off = elem_off[l];
         const uint8_t *ml = mask + gbase;
         const float al = a[l], bl = b[l];

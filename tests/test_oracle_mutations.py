@@ -20,6 +20,7 @@ from tests import test_oracle_shape as spins
 from tests import test_oracle_global as gpins
 from tests import test_oracle_penalties as ppins
 from tests import test_oracle_stopping as tpins
+from tests import test_oracle_nested as npins
 
 MUTATIONS = [
     ("tie_goes_to_higher_index", "(kl[h] == kl[g] && h < g)", "(kl[h] == kl[g] && h > g)"),
@@ -93,8 +94,8 @@ MUTATIONS = [
     ("composite_frozen_or_instead_of_and", "keep = keep && ml[co + (e / s) % ci] != 0;", "keep = keep || ml[co + (e / s) % ci] != 0;"),
     ("composite_frozen_channel_byte_offset", "keep = keep && ml[co + (e / s) % ci] != 0;", "keep = keep && ml[(e / s) % ci] != 0;"),
     ("composite_weighted_projects_filters_only",
-     "return -2; }\n        if (mode[l] == ORACLE_BOTH || mode[l] == ORACLE_SHAPE) {\n            if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], k_in[l],",
-     "return -2; }\n        if (mode[l] == ORACLE_BOTH || mode[l] == ORACLE_SHAPE) {\n            if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], ci,"),
+     "return -2; }\n        if (mode[l] >= ORACLE_BOTH) {\n            if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], k_in[l],",
+     "return -2; }\n        if (mode[l] >= ORACLE_BOTH) {\n            if (mode[l] == ORACLE_BOTH) project_composite(v, co, ci, s, k[l], ci,"),
     ("weighted_frozen_drops_global_term", "const float zt = at + bq;", "const float zt = at;"),
     ("weighted_frozen_mask_ignored", "const float z = keep ? zt : 0.0f;", "const float z = zt;"),
     ("weighted_frozen_candidate_drops_dual", "const float t = wbar + U[off + e];", "const float t = wbar;"),
@@ -122,6 +123,18 @@ MUTATIONS = [
     ("stop_bz_forgets_copies_of_zi", "const double bz = sqrt((double)P * mag[1 * (int64_t)L + l] +", "const double bz = sqrt(mag[1 * (int64_t)L + l] +"),
     ("stop_overall_flag_is_any", "if (!done[l]) every = 0;", "if (done[l]) every = 1; else if (l == 0) every = 0;"),
     ("layer_sqnorm_in_fp32", "const double x = (double)X[off + e];\n            s += x * x;", "const float x = X[off + e];\n            s += (double)(x * x);"),
+    ("nested_ranks_positions_of_pruned_channels", "if (cm[h / s] && (key[h] > key[g] ||", "if ((key[h] > key[g] ||"),
+    ("nested_keeps_positions_of_pruned_channels", "if (!cm[g / s]) { m[g] = 0; continue; }", "if (0) { m[g] = 0; continue; }"),
+    ("nested_channel_of_position_wrong", "if (!cm[g / s]) { m[g] = 0; continue; }", "if (!cm[g % ci]) { m[g] = 0; continue; }"),
+    ("nested_tie_rule", "(key[h] > key[g] || (key[h] == key[g] && h < g))) ++before;", "(key[h] > key[g] || (key[h] == key[g] && h > g))) ++before;"),
+    ("nested_shape_key_stride_wrong", "const double y = (double)x[o * G + g];", "const double y = (double)x[o * ci + g];"),
+    ("nested_shapes_before_channels", "    project_in_place(x, co, ci, s, 1, k_in, key, m);\n    project_shapes_within(x, co, ci, s, k_kern, m, key + ci, m + ci);",
+     "    for (int64_t c = 0; c < ci; ++c) m[c] = 1;\n    project_shapes_within(x, co, ci, s, k_kern, m, key + ci, m + ci);\n    project_in_place(x, co, ci, s, 1, k_in, key, m);"),
+    ("nested_filters_skipped", "    if (filters) {\n        project_in_place(x, co, ci, s, 0, k_out, key, m);", "    if (filters) {\n        project_in_place(x, co, ci, s, 0, co, key, m);"),
+    ("nested_counts_swapped", "project_shapes_within(x, co, ci, s, k_kern, m, key + ci, m + ci);\n}", "project_shapes_within(x, co, ci, s, k_in, m, key + ci, m + ci);\n}"),
+    ("nested_zeroes_wrong_position", "if (!m[e % G]) x[e] = 0.0f;", "if (!m[e / co % G]) x[e] = 0.0f;"),
+    ("nested_weighted_takes_the_base_candidate_counts", "else project_nested(v, co, ci, s, mode[l] == ORACLE_ALL, k[l], k_in[l], k_kern[l], key + gbase, mask + gbase);\n#pragma omp parallel for schedule(static)\n            for (int64_t e = 0; e < n; ++e) {\n                Z[off + e] = v[e];\n                U[off + e] = U[off + e] + (wbar[e] - v[e]);\n                if (Wbar) Wbar[off + e] = wbar[e];\n            }\n            free(wbar);\n            free(v);\n            gbase += G;\n            continue;\n        }\n        double *kl = key + gbase;\n#pragma omp parallel for schedule(static)\n        for (int64_t g = 0; g < G; ++g) {\n            double acc = 0.0;\n            if (mode[l] == ORACLE_CHANNEL) {",
+     "else project_nested(v, co, ci, s, mode[l] == ORACLE_ALL, k[l], ci, k_kern[l], key + gbase, mask + gbase);\n#pragma omp parallel for schedule(static)\n            for (int64_t e = 0; e < n; ++e) {\n                Z[off + e] = v[e];\n                U[off + e] = U[off + e] + (wbar[e] - v[e]);\n                if (Wbar) Wbar[off + e] = wbar[e];\n            }\n            free(wbar);\n            free(v);\n            gbase += G;\n            continue;\n        }\n        double *kl = key + gbase;\n#pragma omp parallel for schedule(static)\n        for (int64_t g = 0; g < G; ++g) {\n            double acc = 0.0;\n            if (mode[l] == ORACLE_CHANNEL) {"),
     ("layer_sqnorm_reads_padding", "for (int64_t e = 0; e < n; ++e) {\n            const double x = (double)X[off + e];", "for (int64_t e = 0; e < n + 1; ++e) {\n            const double x = (double)X[off + e];"),
 ]
 
@@ -181,6 +194,12 @@ PIN_FUNCS = [
     tpins.test_layers_are_judged_separately_and_the_overall_flag_needs_all_of_them,
     tpins.test_against_the_formulas_in_numpy_on_random_inputs,
     tpins.test_layer_sqnorms_handworked_and_against_numpy,
+    lambda: [npins.test_handworked_nested_layer(c) for c in npins.CASES],
+    lambda: [npins.test_special_cases_reduce_to_the_modes_pinned_elsewhere(s) for s in range(2)],
+    lambda: [npins.test_against_the_single_projections_applied_literally_with_numpy(s) for s in range(2)],
+    npins.test_the_shape_selection_is_the_best_one_inside_the_kept_channels_by_brute_force,
+    npins.test_ties_between_identical_channels_and_positions_go_to_the_lower_index,
+    npins.test_weighted_candidate_under_the_nested_modes,
 ]
 
 

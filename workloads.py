@@ -27,6 +27,8 @@ MODE_FILTER = 1    # groups are output filters  W[g, :, :, :]
 MODE_CHANNEL = 2   # groups are input channels  W[:, g, :, :]
 MODE_BOTH = 3      # both constraints: c_out filter groups followed by c_in channel groups
 MODE_SHAPE = 4     # groups are the spatial positions of the input channels  W[:, b, u, v]  (c_in * khw groups)
+MODE_CHANNEL_SHAPE = 5   # channels and shape groups: c_in channel groups followed by c_in * khw shape groups
+MODE_ALL = 6       # filters, channels and shape groups: c_out + c_in + c_in * khw groups
 
 _TENSOR_W = 0
 _TENSOR_U = 1
@@ -43,7 +45,8 @@ class Layer:
     khw: int
     mode: int = MODE_NONE
     k: int = 0
-    k_in: int = 0              # MODE_BOTH only: channels kept (k is then the number of filters kept)
+    k_in: int = 0              # MODE_BOTH, MODE_CHANNEL_SHAPE, MODE_ALL: channels kept (k is the number of filters kept)
+    k_kern: int = 0            # MODE_CHANNEL_SHAPE, MODE_ALL: shape groups kept, all of them inside kept channels
     elem_off: int = 0          # offset, in elements, inside every full-layout arena
     group_base: int = 0        # offset of this layer's groups in mask / sqnorm
 
@@ -57,6 +60,10 @@ class Layer:
             return self.c_out + self.c_in
         if self.mode == MODE_SHAPE:
             return self.c_in * self.khw
+        if self.mode == MODE_CHANNEL_SHAPE:
+            return self.c_in + self.c_in * self.khw
+        if self.mode == MODE_ALL:
+            return self.c_out + self.c_in + self.c_in * self.khw
         return self.c_in if self.mode == MODE_CHANNEL else self.c_out
 
     @property
@@ -76,6 +83,10 @@ class Layer:
             return self.n
         if self.mode == MODE_BOTH:
             return self.k * self.k_in * self.khw
+        if self.mode == MODE_CHANNEL_SHAPE:
+            return self.c_out * self.k_kern
+        if self.mode == MODE_ALL:
+            return self.k * self.k_kern
         return self.k * self.group_size
 
 
@@ -110,6 +121,7 @@ class Workload:
             "mode": np.array([l.mode for l in self.layers], dtype=np.int32),
             "k": np.array([l.k for l in self.layers], dtype=np.int32),
             "k_in": np.array([l.k_in for l in self.layers], dtype=np.int32),
+            "k_kern": np.array([l.k_kern for l in self.layers], dtype=np.int32),
         }
         return cols
 
@@ -118,11 +130,33 @@ class Workload:
         a MODE_CHANNEL layer of c_in*khw channels with khw = 1 (its groups are that view's columns).  Element
         offsets, group order and k do not change."""
         cols = self.table()
-        shape = cols["mode"] == MODE_SHAPE
+        mode = cols["mode"]
+        cs, al = mode == MODE_CHANNEL_SHAPE, mode == MODE_ALL
+        shape = (mode == MODE_SHAPE) | cs | al
+        # a layer that also limits its channels: the view's columns come in runs of khw per channel, of which
+        # k_in runs may hold kept columns (columns "span" and "k_coarse" of the table)
+        cols["span"] = np.where(cs | al, cols["khw"], 0).astype(np.int32)
+        cols["k_coarse"] = np.where(cs | al, cols["k_in"], 0).astype(np.int32)
+        cols["k"] = np.where(cs, cols["k_kern"], cols["k"]).astype(np.int32)
+        cols["k_in"] = np.where(al, cols["k_kern"], cols["k_in"]).astype(np.int32)
         cols["c_in"] = np.where(shape, cols["c_in"] * cols["khw"], cols["c_in"]).astype(np.int32)
         cols["khw"] = np.where(shape, 1, cols["khw"]).astype(np.int32)
-        cols["mode"] = np.where(shape, MODE_CHANNEL, cols["mode"]).astype(np.int32)
+        cols["mode"] = np.where(al, MODE_BOTH, np.where(shape, MODE_CHANNEL, mode)).astype(np.int32)
+        del cols["k_kern"]
         return cols
+
+    def view_groups(self, per_group):
+        """An array over the groups of table() as an array over the groups of gemm_view_table(): the channel
+        entries of the layers of MODE_CHANNEL_SHAPE and MODE_ALL are dropped (the view has no groups for them)."""
+        parts = []
+        for l in self.layers:
+            g = per_group[l.group_base:l.group_base + l.groups]
+            if l.mode == MODE_CHANNEL_SHAPE:
+                g = g[l.c_in:]
+            elif l.mode == MODE_ALL:
+                g = np.concatenate([g[:l.c_out], g[l.c_out + l.c_in:]])
+            parts.append(g)
+        return np.concatenate(parts)
 
     def algorithmic_bytes(self):
         """Bytes the method must move: each unique input read once, each output written once."""
@@ -276,7 +310,8 @@ def make_workload(name: str, seed: int = 0, prune_fc: Optional[bool] = None) -> 
 
 
 def custom_workload(shapes, R=1, seed=0, sigma_replica=0.0, name="custom") -> Workload:
-    """shapes: list of (c_out, c_in, khw, mode, k) or, for MODE_BOTH, (c_out, c_in, khw, mode, k, k_in).
+    """shapes: list of (c_out, c_in, khw, mode, k) or, for MODE_BOTH, (c_out, c_in, khw, mode, k, k_in), or, for
+    MODE_CHANNEL_SHAPE and MODE_ALL, (c_out, c_in, khw, mode, k, k_in, k_kern).
     For tests of odd shapes and edge cases."""
     layers = [Layer("l%d" % i, *sh) for i, sh in enumerate(shapes)]
     for l in layers:
