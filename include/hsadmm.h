@@ -120,6 +120,40 @@ typedef struct hsadmm_plan hsadmm_plan_t;   /* opaque; its tables never change a
 int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_align_elems,
                        hsadmm_plan_t** out);
 
+/*
+ * Shape groups inside input channels (Section 2.1: the composite set's S_c ^ S_s and
+ * S_f ^ S_c ^ S_s; the projections one after the other, Section 3, paragraph after
+ * Eq. (10), in the order the sets are listed: filters, channels, shape groups).
+ *
+ * A shape group W[:, b, u, v] is a column of the layer's [c_out][c_in*K_H*K_W] GEMM view, so a
+ * layer under shape sparsity is declared through that view: c_in = C_in*K_H*K_W channels with
+ * khw = 1, MODE_CHANNEL (or MODE_BOTH with the filters), k (k_in) = shape groups kept.  The
+ * columns of one input channel are then a run of `span` = K_H*K_W consecutive channels of the
+ * view.  An entry with span >= 1 limits the runs as well: the selection first ranks the runs by
+ * the sum of their channels' squared norms (the input channel's norm; MODE_BOTH: over the kept
+ * filters) and keeps k_coarse of them, lower index first among equals, then ranks the channels
+ * of the kept runs alone and keeps k (k_in) of them.  Channels of a pruned run are never
+ * candidates, so exactly k (k_in) channels are kept and all of them lie in kept runs; the
+ * values equal those of the plain shape projection applied after the channel projection.
+ * mask, sqnorm, sel and the index mappings keep the layout of the layer as declared (one entry
+ * per channel of the view; the runs have no entries of their own: a run is kept iff one of its
+ * channels is); sqnorm reports 0 for a channel of a pruned run, its norm once the run is zero.
+ * Every call that takes the plan works as for any CHANNEL / BOTH layer.
+ *
+ * nest: NULL (then this is hsadmm_plan_create), or L entries, host memory, copied.  An entry
+ * with span <= 0 sets no limit (k_coarse is ignored).  An entry with span >= 1 needs
+ * MODE_CHANNEL or MODE_BOTH, khw == 1, c_in a multiple of span, 1 <= k_coarse <= c_in / span
+ * and k (MODE_BOTH: k_in) <= k_coarse * span, else INVALID_ARGUMENT.  Other arguments and
+ * errors as for hsadmm_plan_create.
+ */
+typedef struct {
+    int32_t span;       /* channels of the view per run (K_H*K_W; 1 for a 1x1 layer); <= 0: no limit on runs */
+    int32_t k_coarse;   /* runs that may hold kept channels (the paper's alpha_in) */
+} hsadmm_nest_t;
+
+int hsadmm_plan_create_nested(const hsadmm_layer_t* layers, const hsadmm_nest_t* nest, int32_t L,
+                              int32_t pack_align_elems, hsadmm_plan_t** out);
+
 /* Releases the plan's host and device memory.  NULL is ignored.  The caller
  * must have synchronised every stream that still runs work of this plan. */
 void hsadmm_plan_destroy(hsadmm_plan_t* plan);

@@ -38,7 +38,7 @@ EXPORTS = ("hsadmm_plan_create", "hsadmm_plan_destroy", "hsadmm_plan_sizes", "hs
            "hsadmm_retrain_project", "hsadmm_retrain_expand",
            "hsadmm_adapt_penalties", "hsadmm_scale_layers", "hsadmm_project_compact_static",
            "hsadmm_step", "hsadmm_selection_from_mask", "hsadmm_kernel_grid", "hsadmm_plan_estimates",
-           "hsadmm_layer_sqnorms", "hsadmm_stopping_test")
+           "hsadmm_layer_sqnorms", "hsadmm_stopping_test", "hsadmm_plan_create_nested")
 KERNEL_COUNT = 29
 
 
@@ -52,6 +52,10 @@ class _Layer(ctypes.Structure):
     _fields_ = [("elem_off", ctypes.c_int64), ("c_out", ctypes.c_int32), ("c_in", ctypes.c_int32),
                 ("khw", ctypes.c_int32), ("mode", ctypes.c_int32), ("k", ctypes.c_int32),
                 ("k_in", ctypes.c_int32)]
+
+
+class _Nest(ctypes.Structure):
+    _fields_ = [("span", ctypes.c_int32), ("k_coarse", ctypes.c_int32)]
 
 
 # hsadmm_step_args_t, field by field, in declaration order: (name, C type, how the binding fills it).
@@ -107,6 +111,9 @@ def load_library():
     lib.hsadmm_plan_create.argtypes = [ctypes.POINTER(_Layer), ctypes.c_int32, ctypes.c_int32,
                                        ctypes.POINTER(vp)]
     lib.hsadmm_plan_create.restype = ctypes.c_int
+    lib.hsadmm_plan_create_nested.argtypes = [ctypes.POINTER(_Layer), ctypes.POINTER(_Nest), ctypes.c_int32,
+                                              ctypes.c_int32, ctypes.POINTER(vp)]
+    lib.hsadmm_plan_create_nested.restype = ctypes.c_int
     lib.hsadmm_plan_destroy.argtypes = [vp]
     lib.hsadmm_plan_destroy.restype = None
     lib.hsadmm_plan_sizes.argtypes = [vp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
@@ -240,7 +247,8 @@ def _stream(stream) -> Optional[int]:
 
 class Plan:
     """Owner of an hsadmm_plan_t*.  `table` has the columns elem_off, c_out, c_in, khw, mode, k and, when it
-    holds layers under both constraints (mode 3), k_in."""
+    holds layers under both constraints (mode 3), k_in.  With the columns span and k_coarse (runs of channels,
+    hsadmm_nest_t) the plan is made by hsadmm_plan_create_nested."""
 
     def __init__(self, table, pack_align_elems: int = 1):
         lib = load_library()
@@ -255,10 +263,19 @@ class Plan:
             arr[i].k = int(table["k"][i])
             arr[i].k_in = int(table["k_in"][i]) if "k_in" in table else 0
         handle = ctypes.c_void_p()
-        rc = lib.hsadmm_plan_create(arr, L, int(pack_align_elems), ctypes.byref(handle))
         self.handle = None
-        if rc != 0:
-            raise HsadmmError(rc, "hsadmm_plan_create")
+        if "span" in table:
+            nest = (_Nest * max(L, 1))()
+            for i in range(L):
+                nest[i].span = int(table["span"][i])
+                nest[i].k_coarse = int(table["k_coarse"][i])
+            rc = lib.hsadmm_plan_create_nested(arr, nest, L, int(pack_align_elems), ctypes.byref(handle))
+            if rc != 0:
+                raise HsadmmError(rc, "hsadmm_plan_create_nested")
+        else:
+            rc = lib.hsadmm_plan_create(arr, L, int(pack_align_elems), ctypes.byref(handle))
+            if rc != 0:
+                raise HsadmmError(rc, "hsadmm_plan_create")
         self.handle = handle
         self.n_layers = L
         self.pack_align_elems = int(pack_align_elems)

@@ -100,7 +100,7 @@ hipError_t for_replica_count(int R, F&& f)
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct WsLayout {
-    size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, work, rowres, pred, est_cnt, est_keys, est_thr, est_thr_tag, total;
+    size_t key, colpart, pos, cnt, layer_off, kept_idx, respart, work, rowres, pred, est_cnt, est_keys, est_thr, est_thr_tag, nest, total;
 };
 
 enum KernelId { kPass1 = 0, kTopk, kFixup, kScan, kGather, kScatter, kFrozen, kMaskOr, kWKeys, kWFinal, kDualInter, kResPart, kResFinish, kColsums, kChanFinal, kWFixup, kBothFinal, kAverage, kMaskDrift, kFixupGather, kWFixupPack, kRetrainProject, kRetrainExpand, kScaleLayers, kPass1Hinted, kHintedRepair, kSqnormPart, kResPick, kWHintedRepair, kKernelCount };
@@ -151,6 +151,7 @@ struct hsadmm_plan {
     uint16_t* d_group_layer = nullptr;   // groups_total: scan segment of every group (bit 15: unconstrained layer)
     float* d_coef = nullptr;             // 2L: a_l, b_l of Eq. (9), set by hsadmm_plan_set_node_weights (default 1, 0)
     void* static_ws = nullptr;           // device address of `scratch` on the plan's device
+    bool any_nested = false;             // some layer's channels come in runs (hsadmm_plan_create_nested)
     bool use_estimate = false;           // the un-predicted projection forms a prediction inside pass 1 (kernels_estimate.hpp)
     std::atomic<unsigned> est_calls{0};  // numbers those calls (the estimate's counts carry the number of their call)
     uint16_t* d_chunk_layer = nullptr;   // per 16 groups: their segment if all 16 lie in one constrained segment, else 0xffff
@@ -316,9 +317,11 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
     im.kept_idx = reinterpret_cast<int32_t*>(ws + p->ws.kept_idx);
     im.sel = sel_out;
     const int nL = (int)p->layers.size();
-    hipError_t e = launch(p, kTopk, select_topk, (unsigned)p->layers.size(), kScanBlock, s,
+    auto* const select = p->any_nested ? select_topk<true> : select_topk<false>;
+    hipError_t e = launch(p, kTopk, select, (unsigned)p->layers.size(), kScanBlock, s,
                           (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
-                          (const int32_t*)nullptr, 0, im, nL, (int)p->pack_align, wl, (const WorkItem*)p->d_items_rows);
+                          (const int32_t*)nullptr, 0, im, nL, (int)p->pack_align, wl, (const WorkItem*)p->d_items_rows,
+                          reinterpret_cast<unsigned char*>(ws + p->ws.nest));
     if (e != hipSuccess || p->both_layers.empty()) return e;
     if (wl.both)    // pass 1 wrote these layers under the prediction: the candidate is read back from its outputs
         e = launch(p, kColsums, composite_colsums_hinted, (unsigned)p->items_both.size(), kBlock, s,
@@ -329,9 +332,10 @@ hipError_t run_selection(const hsadmm_plan* p, double* key, double* colpart, con
                    (const WorkItem*)p->d_items_both, (const float*)a.Z, a.Ur, a.Zg, a.Vd, a.coef,
                    (const uint8_t*)mask, colpart);
     if (e != hipSuccess) return e;
-    return launch(p, kTopk, select_topk, (unsigned)p->both_layers.size(), kScanBlock, s,
+    return launch(p, kTopk, select, (unsigned)p->both_layers.size(), kScanBlock, s,
                   (const DevLayer*)p->d_layers, key, (const double*)colpart, mask,
-                  (const int32_t*)p->d_both_layers, 1, im, nL, (int)p->pack_align, wl, (const WorkItem*)p->d_items_rows);
+                  (const int32_t*)p->d_both_layers, 1, im, nL, (int)p->pack_align, wl, (const WorkItem*)p->d_items_rows,
+                  reinterpret_cast<unsigned char*>(ws + p->ws.nest));
 }
 
 int run_scan(const hsadmm_plan* p, const uint8_t* mask, char* ws, hipStream_t s, int32_t* sel_out = nullptr)
@@ -356,11 +360,27 @@ extern "C" {
 
 int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_align_elems, hsadmm_plan_t** out)
 {
+    return hsadmm_plan_create_nested(layers, nullptr, L, pack_align_elems, out);
+}
+
+int hsadmm_plan_create_nested(const hsadmm_layer_t* layers, const hsadmm_nest_t* nest, int32_t L,
+                              int32_t pack_align_elems, hsadmm_plan_t** out)
+{
     if (!layers || !out || L < 1 || L > HSADMM_MAX_LAYERS || pack_align_elems < 1) return HSADMM_ERR_INVALID_ARGUMENT;
     *out = nullptr;
     int64_t prev_end = 0;
     for (int32_t l = 0; l < L; ++l) {
         const hsadmm_layer_t& x = layers[l];
+        if (nest && nest[l].span >= 1) {
+            // runs of channels: a layer whose groups are columns of its GEMM view, cut into whole runs, with room
+            // in the kept runs for every kept column
+            const hsadmm_nest_t& q = nest[l];
+            if ((x.mode != HSADMM_MODE_CHANNEL && x.mode != HSADMM_MODE_BOTH) || x.khw != 1 || x.c_in < 1 ||
+                (x.c_in % q.span) != 0 || q.k_coarse < 1 || q.k_coarse > x.c_in / q.span)
+                return HSADMM_ERR_INVALID_ARGUMENT;
+            const int64_t cols = x.mode == HSADMM_MODE_BOTH ? x.k_in : x.k;
+            if (cols > (int64_t)q.k_coarse * q.span) return HSADMM_ERR_INVALID_ARGUMENT;
+        }
         if (x.c_out < 1 || x.c_in < 1 || x.khw < 1) return HSADMM_ERR_INVALID_ARGUMENT;
         if (x.mode != HSADMM_MODE_NONE && x.mode != HSADMM_MODE_FILTER && x.mode != HSADMM_MODE_CHANNEL &&
             x.mode != HSADMM_MODE_BOTH)
@@ -381,7 +401,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->pack_align = pack_align_elems;
         p->layers.assign(layers, layers + L);
         p->arena_elems = prev_end;
-        int64_t gb = 0, cp = 0, cap = 0, poff = 0;
+        int64_t gb = 0, cp = 0, cap = 0, poff = 0, nest_bytes = 0;
         int32_t seg = 0, kstart = 0;
         group_layer.clear();
         for (int32_t l = 0; l < L; ++l) {
@@ -395,6 +415,16 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
             d.k = x.mode == HSADMM_MODE_NONE ? d.G : x.k;
             d.k_in = both ? x.k_in : 0;
             d.seg0 = seg;
+            if (nest && nest[l].span >= 1) {
+                // the selection's notes about the runs: their keys, the channels' shifted key patterns (8 bytes
+                // each), the runs' ranks and kept list (4 bytes each), the runs' mask
+                const int64_t runs = x.c_in / nest[l].span;
+                d.span = nest[l].span;
+                d.k_coarse = nest[l].k_coarse;
+                d.nest_off = nest_bytes;
+                p->any_nested = true;
+                nest_bytes += (int64_t)align_up((size_t)(8 * runs + 8 * (int64_t)x.c_in + 8 * runs + runs), 8);
+            }
             if (gb + d.G > INT32_MAX) { delete p; return HSADMM_ERR_UNSUPPORTED; }    // group indices are int32
             d.group_base = (int32_t)gb;
             d.row_len = x.c_in * x.khw;
@@ -461,6 +491,7 @@ int hsadmm_plan_create(const hsadmm_layer_t* layers, int32_t L, int32_t pack_ali
         p->ws.est_keys = off;   off = align_up(off + sizeof(double) * (size_t)L * kSampleKeys, 256);
         p->ws.est_thr = off;    off = align_up(off + sizeof(double) * (size_t)L, 256);
         p->ws.est_thr_tag = off; off = align_up(off + sizeof(unsigned int) * (size_t)L, 256);
+        p->ws.nest = off;       off = align_up(off + (size_t)nest_bytes, 256);
         p->ws.total = off;
         // The estimate's item order: of every FILTER layer the items that cover its first rows (a sixteenth of them,
         // 16 at least, kSampleKeys at most), then everything else in the usual order.

@@ -36,8 +36,13 @@ struct DevLayer {
     int32_t k_in;           // BOTH: channels kept
     int32_t seg0;           // first scan segment of the layer (a BOTH layer has two: filters, channels)
     int32_t kept_start;     // start of the layer's run in kept_idx when exactly k (and k_in) groups are kept
+    // Channel groups that come in runs (CHANNEL / BOTH with khw = 1): `span` >= 1 consecutive channels make one run,
+    // only k_coarse runs may hold kept channels, and nest_off is where the selection keeps its notes about the runs
+    // (bytes, in the workspace's region for them).  span = 0: no such limit.
+    int32_t span, k_coarse;
+    int64_t nest_off;
 };
-static_assert(sizeof(DevLayer) == 88, "DevLayer layout");
+static_assert(sizeof(DevLayer) == 104, "DevLayer layout");
 
 // Packed elements of a layer that keeps c0 groups (BOTH: c0 filters and c1 channels), rounded up to pack_align.
 __host__ __device__ __forceinline__ long long packed_size(int mode, long long unit, int c0, int c1, int pack_align)

@@ -213,6 +213,10 @@ __device__ __forceinline__ void project_rows_staged(const WorkItem& it, const Pr
     const bool kept_default = 2 * L.k >= L.G;
     if (it.col0 == kEstUse) {
         if (threadIdx.x == 0) {
+            if (thr_tag != x.gen) {                              // not there when this item began: one more look
+                thr_tag = __hip_atomic_load(&x.thr_tag[it.layer], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                thr_val = __hip_atomic_load(&x.thr[it.layer], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
             sthr[0] = thr_val;
             sthr[1] = thr_tag == x.gen ? 1.0 : 0.0;
         }

@@ -373,13 +373,17 @@ __device__ __forceinline__ void pick_residuals(const DevLayer& L, int l, int n_l
 // stage 0: workgroup b takes layer b; of a BOTH layer it selects the filters (its first c_out groups).
 // stage 1: workgroup b takes layer layer_list[b], a BOTH layer, and selects its channels (the c_in
 //          groups after the filters) from the column sums composite_colsums left in colpart.
+// NEST: the plan has layers whose channels come in runs (a kernel of its own, so that plans without such layers run
+// the plain selection unchanged).
+template <bool NEST>
 __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __restrict__ layers,
                                                           double* __restrict__ key,
                                                           const double* __restrict__ colpart,
                                                           uint8_t* __restrict__ mask,
                                                           const int32_t* __restrict__ layer_list, int stage,
                                                           IndexMaps im, int n_layers, int pack_align,
-                                                          WorkList wl, const WorkItem* __restrict__ row_items)
+                                                          WorkList wl, const WorkItem* __restrict__ row_items,
+                                                          unsigned char* __restrict__ nest)
 {
     __shared__ TopkShared sh;
     __shared__ int work_slot;
@@ -453,16 +457,70 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
     }
     const int kk = (L.mode == HSADMM_MODE_NONE) ? G : ((both && stage == 1) ? L.k_in : L.k);
     const unsigned long long* kb = reinterpret_cast<const unsigned long long*>(kl);
-    if (kk >= G) {
-        for (int g = tid; g < G; g += kScanBlock) {
-            ml[g] = 1; pos_l[g] = g; kidx_l[g] = g;
-            if (sel_l) sel_l[g] = g;
-            if (ck_l) ck_l[g] = g;
+    // Channels that come in runs of `span` (shape groups inside input channels, Section 2.1): first the runs are
+    // ranked by the sum of their channels' keys and k_coarse of them stay; then the channels of those runs alone are
+    // ranked.  The second ranking sees key pattern + 1 for a channel of a kept run and 0 for any other, so no channel
+    // of a pruned run can be taken, whatever ties at zero there are; such a channel's key is reported as 0, the norm
+    // it has once its run is pruned.
+    const bool nested = NEST && channels && L.span >= 1;
+    const int C = nested ? G / L.span : 0;
+    double* run_key = nested ? reinterpret_cast<double*>(nest + L.nest_off) : nullptr;
+    unsigned long long* shifted = reinterpret_cast<unsigned long long*>(run_key + C);
+    int32_t* run_pos = reinterpret_cast<int32_t*>(shifted + G);
+    int32_t* run_kidx = run_pos + C;
+    uint8_t* run_mask = reinterpret_cast<uint8_t*>(run_kidx + C);
+    if (nested) {
+        for (int j = tid; j < C; j += kScanBlock) {
+            double acc = 0.0;
+            for (int t = 0; t < L.span; ++t) acc += kl[(int64_t)j * L.span + t];
+            run_key[j] = acc;
         }
-    } else if (G <= kTopkRegs * kScanBlock) {
-        topk_layer<true>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l, ck_l);
-    } else {
-        topk_layer<false>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l, ck_l);
+        __syncthreads();
+    }
+    if constexpr (!NEST) {
+        if (kk >= G) {
+            for (int g = tid; g < G; g += kScanBlock) {
+                ml[g] = 1; pos_l[g] = g; kidx_l[g] = g;
+                if (sel_l) sel_l[g] = g;
+                if (ck_l) ck_l[g] = g;
+            }
+        } else if (G <= kTopkRegs * kScanBlock) {
+            topk_layer<true>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l, ck_l);
+        } else {
+            topk_layer<false>(G, kb, ml, kk, sh, pos_l, kidx_l, sel_l, ck_l);
+        }
+    } else
+    for (int phase = nested ? 0 : 1; phase < 2; ++phase) {
+        const bool runs = phase == 0;
+        const int Gp = runs ? C : G;
+        const int kp = runs ? L.k_coarse : kk;
+        const unsigned long long* kbp = runs ? reinterpret_cast<const unsigned long long*>(run_key) : kb;
+        uint8_t* mlp = runs ? run_mask : ml;
+        int32_t* posp = runs ? run_pos : pos_l;
+        int32_t* kidxp = runs ? run_kidx : kidx_l;
+        int32_t* selp = runs ? nullptr : sel_l;
+        int32_t* ckp = runs ? nullptr : ck_l;
+        if (kp >= Gp) {
+            for (int g = tid; g < Gp; g += kScanBlock) {
+                mlp[g] = 1; posp[g] = g; kidxp[g] = g;
+                if (selp) selp[g] = g;
+                if (ckp) ckp[g] = g;
+            }
+        } else if (Gp <= kTopkRegs * kScanBlock) {
+            topk_layer<true>(Gp, kbp, mlp, kp, sh, posp, kidxp, selp, ckp);
+        } else {
+            topk_layer<false>(Gp, kbp, mlp, kp, sh, posp, kidxp, selp, ckp);
+        }
+        if (runs) {
+            __syncthreads();                                 // the runs' mask is complete
+            for (int g = tid; g < G; g += kScanBlock) {
+                const bool in = run_mask[g / L.span] != 0;
+                shifted[g] = in ? kb[g] + 1ull : 0ull;
+                if (!in) kl[g] = 0.0;
+            }
+            __syncthreads();
+            kb = shifted;
+        }
     }
     if (wl.res_out && stage == 0 && (L.mode == HSADMM_MODE_FILTER || L.mode == HSADMM_MODE_NONE))
         pick_residuals(L, (int)blockIdx.x, n_layers, ml, wl, res_red);

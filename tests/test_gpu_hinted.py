@@ -70,9 +70,9 @@ def degrade_part(wl, mask, fraction, rng, filters):
 
 
 class _Bufs:
-    def __init__(self, wl, W, U, pack_align):
+    def __init__(self, wl, W, U, pack_align, table=None):
         dev = torch.device("cuda:0")
-        self.plan = pkg.Plan(wl.table(), pack_align_elems=pack_align)
+        self.plan = pkg.Plan(wl.table() if table is None else table, pack_align_elems=pack_align)
         p = self.plan
         n = wl.n_arena
         nan = float("nan")
