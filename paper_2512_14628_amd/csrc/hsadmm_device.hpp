@@ -18,7 +18,7 @@ constexpr int kWideRow = 2048;                  // rows at least this long are s
 constexpr int kChanRows = 64;               // CHANNEL tiles: rows per row block
 constexpr int kBothRows = 64;               // composite_colsums tiles: rows per row block
 constexpr int kTopkRegs = 8;                // the selection keeps up to 8 keys per thread in registers
-constexpr int kVersion = 20000;          // 2.0.0 (major * 10000 + minor * 100 + patch)
+constexpr int kVersion = 20100;          // 2.1.0 (major * 10000 + minor * 100 + patch)
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
