@@ -39,6 +39,9 @@
  * position) needs no mode of its own: such a group is a column of the
  * [c_out][c_in*khw] view, so declare the layer as CHANNEL with c_in*khw
  * channels and khw = 1 (BOTH, the same way, for filters together with shapes).
+ * Shape groups together with channel groups (S_c ^ S_s, S_f ^ S_c ^ S_s) are such a
+ * layer plus a limit on the runs of K_H*K_W columns that may hold kept columns:
+ * hsadmm_plan_create_nested.
  *
  * Ownership.  The caller owns every device buffer and the stream.  The
  * library owns only the plan (host tables plus a device copy, allocated in

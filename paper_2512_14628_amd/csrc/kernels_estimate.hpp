@@ -123,8 +123,9 @@ __device__ __forceinline__ void publish_threshold(const EstArgs& x, int l, doubl
     }
     const int m = __syncthreads_count(valid ? 1 : 0);            // (also: sk is complete)
     const DevLayer& L = x.layers[l];
-    // only a workgroup that finds all of the layer's first rows published goes on: the last to arrive (its own keys
-    // were acknowledged before it looked, so of two that finish together at least one sees both)
+    // only a workgroup that finds all of the layer's first rows published goes on: the last to arrive (it looks
+    // after the barrier that follows its own stores; should two that finish together both miss each other's keys,
+    // the layer gets no estimate in this call and its rows take the likelier form, as before any estimate exists)
     const int expected = min(sample_rows_of(L.G), L.G);
     if (m < 8 || m < expected) return;
     const int r = (int)(((long long)m * L.k + L.G / 2) / L.G);
