@@ -77,6 +77,28 @@ def test_plan_create_rejects_bad_scalars(lib):
     lib.hsadmm_plan_destroy(None)               # must be a no-op
 
 
+def test_plan_create_nested_rejects_bad_entries(lib):
+    """Runs of channels (hsadmm_nest_t): the table is checked before any device is touched."""
+    def create(mode, ci, khw, k, k_in, span, k_coarse):
+        arr = (binding._Layer * 1)()
+        arr[0].elem_off, arr[0].c_out, arr[0].c_in, arr[0].khw = 0, 8, ci, khw
+        arr[0].mode, arr[0].k, arr[0].k_in = mode, k, k_in
+        nest = (binding._Nest * 1)()
+        nest[0].span, nest[0].k_coarse = span, k_coarse
+        out = ctypes.c_void_p()
+        return lib.hsadmm_plan_create_nested(arr, nest, 1, 1, ctypes.byref(out))
+    for bad in ((1, 36, 1, 4, 0, 9, 2),       # FILTER layers have no channels to nest
+                (2, 4, 9, 2, 0, 9, 2),        # not declared through the GEMM view (khw != 1)
+                (2, 35, 1, 10, 0, 9, 2),      # c_in not a multiple of span
+                (2, 36, 1, 10, 0, 9, 0),      # no run kept
+                (2, 36, 1, 10, 0, 9, 5),      # more runs than there are
+                (2, 36, 1, 19, 0, 9, 2),      # more columns than the kept runs hold
+                (3, 36, 1, 4, 19, 9, 2)):     # the same for the channels of a layer under both constraints
+        assert create(*bad) == -1, bad
+    out = ctypes.c_void_p()
+    assert lib.hsadmm_plan_create_nested(None, None, 1, 1, ctypes.byref(out)) == -1
+
+
 def test_hot_calls_reject_null_plan(lib):
     assert lib.hsadmm_plan_sizes(None, None, None, None, None) == -1
     assert lib.hsadmm_project(None, None, 1, None, None, None, None, None, None, 0, None) == -1
