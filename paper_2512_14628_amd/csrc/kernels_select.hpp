@@ -373,6 +373,39 @@ __device__ __forceinline__ void pick_residuals(const DevLayer& L, int l, int n_l
 // stage 0: workgroup b takes layer b; of a BOTH layer it selects the filters (its first c_out groups).
 // stage 1: workgroup b takes layer layer_list[b], a BOTH layer, and selects its channels (the c_in
 //          groups after the filters) from the column sums composite_colsums left in colpart.
+// out[j] = sum over the row blocks (ascending) of part[rb * row_len + j] for the columns j < ncols: a thread takes
+// the columns tid, tid + 1024, ..., four of them at a time and four row blocks each (sixteen loads in flight).
+constexpr int kColChunk = 4096;             // columns of the channel keys' LDS staging
+__device__ __forceinline__ void sum_rowblocks(const double* __restrict__ part, int ncols, int row_len, int n_rowblocks,
+                                              double* out)
+{
+    for (int j0 = threadIdx.x; j0 < ncols; j0 += 4 * kScanBlock) {
+        const int nc = (ncols - j0 + kScanBlock - 1) / kScanBlock;           // columns of this round (4 or fewer)
+        const double* c0 = part + j0;
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        int rb = 0;
+        for (; rb + 4 <= n_rowblocks; rb += 4) {
+            double x[4][4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    x[c][b] = (c < nc) ? c0[c * kScanBlock + (int64_t)(rb + b) * row_len] : 0.0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[c] += x[c][b];
+        }
+        for (; rb < n_rowblocks; ++rb)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (c < nc) acc[c] += c0[c * kScanBlock + (int64_t)rb * row_len];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (c < nc) out[j0 + c * kScanBlock] = acc[c];
+    }
+}
+
 // NEST: the plan has layers whose channels come in runs (a kernel of its own, so that plans without such layers run
 // the plain selection unchanged).
 template <bool NEST>
@@ -386,6 +419,7 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
                                                           unsigned char* __restrict__ nest)
 {
     __shared__ TopkShared sh;
+    __shared__ double colsum[kColChunk];
     __shared__ int work_slot;
     __shared__ double res_red[kScanWaves][2];
     const DevLayer L = layers[stage == 0 ? (int)blockIdx.x : layer_list[blockIdx.x]];
@@ -418,8 +452,27 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
         if (l == n_layers - 1) im.layer_off[n_layers] = L.packed_off + packed_size(L.mode, L.unit, c0, L.k_in, pack_align);
     }
     if (channels) {
-        // key[c] = sum over row blocks (ascending), then over the channel's khw columns (ascending)
+        // key[c]: every column of the channel summed over the row blocks (ascending), then the channel's khw column
+        // sums added (ascending); the same order for every channel of a layer, wherever it lies
         const double* cp = colpart + L.colpart_off;
+        if (L.khw == 1 && G > kScanBlock) {
+            sum_rowblocks(cp, G, L.row_len, L.n_rowblocks, kl);
+        } else if (L.khw > 1 && L.khw <= kColChunk) {
+            // the columns of the view first (coalesced: a thread per column, as above), a chunk of whole channels at
+            // a time into LDS, then every channel's khw column sums in ascending order
+            const int chunk_ch = kColChunk / L.khw;
+            for (int ch0 = 0; ch0 < G; ch0 += chunk_ch) {
+                const int nch = min(chunk_ch, G - ch0);
+                sum_rowblocks(cp + (int64_t)ch0 * L.khw, nch * L.khw, L.row_len, L.n_rowblocks, colsum);
+                __syncthreads();
+                for (int g = tid; g < nch; g += kScanBlock) {
+                    double acc = 0.0;
+                    for (int t = 0; t < L.khw; ++t) acc += colsum[g * L.khw + t];
+                    kl[ch0 + g] = acc;
+                }
+                __syncthreads();
+            }
+        } else
         for (int g = tid; g < G; g += kScanBlock) {
             double acc = 0.0;
             const double* cg = cp + (int64_t)g * L.khw;
@@ -432,21 +485,6 @@ __global__ __launch_bounds__(kScanBlock) void select_topk(const DevLayer* __rest
                     for (int b = 0; b < 16; ++b) x[b] = cg[(int64_t)(rb + b) * L.row_len];
 #pragma unroll
                     for (int b = 0; b < 16; ++b) acc += x[b];
-                }
-            }
-            if (L.khw <= 9) {
-                for (; rb + 4 <= L.n_rowblocks; rb += 4) {
-                    double x[4][9];
-#pragma unroll
-                    for (int b4 = 0; b4 < 4; ++b4)
-#pragma unroll
-                        for (int t = 0; t < 9; ++t)
-                            x[b4][t] = (t < L.khw) ? cg[(int64_t)(rb + b4) * L.row_len + t] : 0.0;
-#pragma unroll
-                    for (int b4 = 0; b4 < 4; ++b4)
-#pragma unroll
-                        for (int t = 0; t < 9; ++t)
-                            if (t < L.khw) acc += x[b4][t];
                 }
             }
             for (; rb < L.n_rowblocks; ++rb)
