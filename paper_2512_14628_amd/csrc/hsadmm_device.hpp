@@ -182,6 +182,24 @@ struct DivKhw {
     }
 };
 
+// How the four waves of a workgroup share an item's rows when a wave walks a row 64 lanes at a time: with four rows
+// or more a wave takes whole rows; an item of one or two rows (rows of 1024 floats and more) is shared so that no
+// wave idles, four or two waves per row, each taking every fourth or second group of 64 lanes' columns.
+struct WaveShare {
+    int row;            // the first row this wave takes
+    int rows_at_once;   // rows the workgroup works on at once (the wave's next row is this many further)
+    int first;          // lane 0's first column group
+    int stride;         // column groups (of one per lane) from one of the wave's steps to the next
+    __device__ __forceinline__ WaveShare(int nr, int wave)
+    {
+        const int per_row = nr == 1 ? kWaves : (nr == 2 ? kWaves / 2 : 1);    // waves per row
+        rows_at_once = kWaves / per_row;
+        row = wave / per_row;
+        first = (wave - row * per_row) * kWave;
+        stride = per_row * kWave;
+    }
+};
+
 __device__ __forceinline__ double wave_xor_sum(double a, int width)
 {
     // butterfly over `width` adjacent lanes; every lane ends with the same bits

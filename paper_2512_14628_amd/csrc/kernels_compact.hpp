@@ -217,12 +217,13 @@ __device__ __forceinline__ void gather_item(const WorkItem& it, const float* src
         const DivKhw div(khw);
         const int quads = out_len >> 2;
         constexpr int kRows = 2;      // rows a wave keeps in flight: their loads are issued together
-        for (int rr0 = wave; rr0 < it.nr; rr0 += kRows * kWaves) {
+        const WaveShare ws(it.nr, wave);
+        for (int rr0 = ws.row; rr0 < it.nr; rr0 += kRows * ws.rows_at_once) {
             int prow[kRows];
             int64_t ro[kRows];
 #pragma unroll
             for (int u = 0; u < kRows; ++u) {
-                const int rr = rr0 + u * kWaves;
+                const int rr = rr0 + u * ws.rows_at_once;
                 prow[u] = -1;
                 if (rr < it.nr) prow[u] = both ? pos[it.g0 + rr] : it.row0 + rr;
                 ro[u] = it.base + (int64_t)rr * row_len;
@@ -230,7 +231,7 @@ __device__ __forceinline__ void gather_item(const WorkItem& it, const float* src
             auto at = [&](int u, int idx) -> float {
                 return SUM ? ld1(src + ro[u] + idx) + ld1(src1 + ro[u] + idx) : ld1(src + ro[u] + idx);
             };
-            for (int j4 = lane; j4 < quads; j4 += kWave) {
+            for (int j4 = lane + ws.first; j4 < quads; j4 += ws.stride) {
                 const int j = j4 << 2;
                 int4 c;
                 if (khw == 1) {
@@ -252,7 +253,7 @@ __device__ __forceinline__ void gather_item(const WorkItem& it, const float* src
                 for (int u = 0; u < kRows; ++u)
                     if (prow[u] >= 0) st4u(out + (int64_t)prow[u] * out_len + j, v[u]);
             }
-            for (int j = (quads << 2) + lane; j < out_len; j += kWave) {
+            for (int j = (quads << 2) + lane + ws.first; j < out_len; j += ws.stride) {
                 const int q = div(j);
                 const int cs = kl[q] * khw + (j - q * khw);
 #pragma unroll
@@ -432,53 +433,65 @@ __global__ __launch_bounds__(kBlock) void expand_scatter(const WorkItem* __restr
         const DivKhw div(khw);
         const int32_t* pl = pos + (both ? it.aux : (int64_t)it.g0);
         const int quads = item_vec(it) ? (row_len >> 2) : 0;
-        constexpr int kRows = 2;      // rows a wave keeps in flight
-        for (int rr0 = wave; rr0 < it.nr; rr0 += kRows * kWaves) {
-            int prow[kRows];
-            bool live[kRows];
-            const float* srow[kRows];
+        // Two 128-bit stores in flight per lane: of two rows of the wave, or, when only one row is left for it, of two
+        // column groups of that row.
+        constexpr int kSlots = 2;
+        const WaveShare ws(it.nr, wave);
+        auto cols = [&](int c) -> int4 {          // packed column of each of the dst columns c .. c + 3, -1: pruned channel
+            int4 p;
+            if (khw == 1) {
+                __builtin_memcpy(&p, pl + c, 16);
+            } else {
+                const int h0 = div(c), h1 = div(c + 1), h2 = div(c + 2), h3 = div(c + 3);
+                const int p0 = pl[h0], p1 = pl[h1], p2 = pl[h2], p3 = pl[h3];
+                p.x = p0 >= 0 ? p0 * khw + (c - h0 * khw) : -1;
+                p.y = p1 >= 0 ? p1 * khw + (c + 1 - h1 * khw) : -1;
+                p.z = p2 >= 0 ? p2 * khw + (c + 2 - h2 * khw) : -1;
+                p.w = p3 >= 0 ? p3 * khw + (c + 3 - h3 * khw) : -1;
+            }
+            return p;
+        };
+        for (int rr0 = ws.row; rr0 < it.nr; rr0 += kSlots * ws.rows_at_once) {
+            const bool one_row = rr0 + ws.rows_at_once >= it.nr;
+            int prow[kSlots], coff[kSlots];
+            const float* srow[kSlots];
+            int64_t drow[kSlots];
 #pragma unroll
-            for (int u = 0; u < kRows; ++u) {
-                const int rr = rr0 + u * kWaves;
-                live[u] = rr < it.nr;
-                prow[u] = -1;
-                if (live[u]) prow[u] = both ? pos[it.g0 + rr] : it.row0 + rr;
+            for (int u = 0; u < kSlots; ++u) {
+                const int rr = one_row ? rr0 : rr0 + u * ws.rows_at_once;
+                prow[u] = both ? pos[it.g0 + rr] : it.row0 + rr;
                 srow[u] = in + (int64_t)(prow[u] < 0 ? 0 : prow[u]) * in_len;
+                drow[u] = it.base + (int64_t)rr * row_len;
+                coff[u] = one_row ? u * ws.stride : 0;
             }
-            for (int c4 = lane; c4 < quads; c4 += kWave) {
-                const int c = c4 << 2;
-                int4 p;                       // packed column of each dst column, -1: pruned channel
-                if (khw == 1) {
-                    __builtin_memcpy(&p, pl + c, 16);
-                } else {
-                    const int h0 = div(c), h1 = div(c + 1), h2 = div(c + 2), h3 = div(c + 3);
-                    const int p0 = pl[h0], p1 = pl[h1], p2 = pl[h2], p3 = pl[h3];
-                    p.x = p0 >= 0 ? p0 * khw + (c - h0 * khw) : -1;
-                    p.y = p1 >= 0 ? p1 * khw + (c + 1 - h1 * khw) : -1;
-                    p.z = p2 >= 0 ? p2 * khw + (c + 2 - h2 * khw) : -1;
-                    p.w = p3 >= 0 ? p3 * khw + (c + 3 - h3 * khw) : -1;
-                }
-                v4f v[kRows];
+            const int step = one_row ? kSlots * ws.stride : ws.stride;
+            for (int c4 = lane + ws.first; c4 < quads; c4 += step) {
+                int4 p[kSlots];
+                bool on[kSlots];
+                v4f v[kSlots];
 #pragma unroll
-                for (int u = 0; u < kRows; ++u) {
-                    const bool k = prow[u] >= 0;
-                    v[u].x = (k && p.x >= 0) ? srow[u][p.x] : 0.f;
-                    v[u].y = (k && p.y >= 0) ? srow[u][p.y] : 0.f;
-                    v[u].z = (k && p.z >= 0) ? srow[u][p.z] : 0.f;
-                    v[u].w = (k && p.w >= 0) ? srow[u][p.w] : 0.f;
+                for (int u = 0; u < kSlots; ++u) {
+                    on[u] = c4 + coff[u] < quads;
+                    p[u] = (on[u] && prow[u] >= 0) ? cols((c4 + coff[u]) << 2) : int4{-1, -1, -1, -1};
                 }
 #pragma unroll
-                for (int u = 0; u < kRows; ++u)
-                    if (live[u]) put4(it.base + (int64_t)(rr0 + u * kWaves) * row_len + c, v[u]);
+                for (int u = 0; u < kSlots; ++u) {
+                    v[u].x = p[u].x >= 0 ? srow[u][p[u].x] : 0.f;
+                    v[u].y = p[u].y >= 0 ? srow[u][p[u].y] : 0.f;
+                    v[u].z = p[u].z >= 0 ? srow[u][p[u].z] : 0.f;
+                    v[u].w = p[u].w >= 0 ? srow[u][p[u].w] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < kSlots; ++u)
+                    if (on[u]) put4(drow[u] + ((int64_t)(c4 + coff[u]) << 2), v[u]);
             }
-            for (int c = (quads << 2) + lane; c < row_len; c += kWave) {
+            for (int c = (quads << 2) + lane + ws.first; c < row_len; c += ws.stride) {
                 const int ch = div(c);
                 const int p0 = pl[ch];
                 const int pc = p0 >= 0 ? p0 * khw + (c - ch * khw) : -1;
 #pragma unroll
-                for (int u = 0; u < kRows; ++u)
-                    if (live[u])
-                        put1(it.base + (int64_t)(rr0 + u * kWaves) * row_len + c, (prow[u] >= 0 && pc >= 0) ? srow[u][pc] : 0.f);
+                for (int u = 0; u < (one_row ? 1 : kSlots); ++u)
+                    put1(drow[u] + c, (prow[u] >= 0 && pc >= 0) ? srow[u][pc] : 0.f);
             }
         }
     }
