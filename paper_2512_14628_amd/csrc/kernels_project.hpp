@@ -303,7 +303,37 @@ __device__ __forceinline__ void project_tile(const WorkItem& it, const ProjectAr
     const bool in = col < row_len;
     double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
     if (in) {
-        for (int rr = wave; rr < it.nr; rr += kWaves) {
+        int rr = wave;
+        // Two of the wave's rows at a time (all their loads before the first store), summed in ascending order.  Not
+        // with one replica or a replica count known only at run time: the registers this takes would lower the
+        // occupancy of the kernel's other branches there.
+        if constexpr (R >= 2) {
+            if (vec) {
+                auto finish4 = [&](int64_t e, const v4f& s, const v4f& u) {
+                    const v4f wb = s * a.inv_R;
+                    if (a.park_mean) st4(a.Z + e, wb);
+                    const v4f v = wb + u;
+                    acc0 = fma((double)v.x, (double)v.x, acc0);
+                    acc1 = fma((double)v.y, (double)v.y, acc1);
+                    acc2 = fma((double)v.z, (double)v.z, acc2);
+                    acc3 = fma((double)v.w, (double)v.w, acc3);
+                };
+                for (; rr + kWaves < it.nr; rr += 2 * kWaves) {
+                    const int64_t e0 = it.base + (int64_t)rr * row_len + col, e1 = e0 + (int64_t)kWaves * row_len;
+                    v4f s0 = ld4(a.W[0] + e0), s1 = ld4(a.W[0] + e1);
+#pragma unroll
+                    for (int r = 1; r < R; ++r) {
+                        const v4f w0 = ld4(a.W[r] + e0), w1 = ld4(a.W[r] + e1);
+                        s0 = s0 + w0;
+                        s1 = s1 + w1;
+                    }
+                    const v4f u0 = ld4(a.Ur + e0), u1 = ld4(a.Ur + e1);
+                    finish4(e0, s0, u0);
+                    finish4(e1, s1, u1);
+                }
+            }
+        }
+        for (; rr < it.nr; rr += kWaves) {
             const int64_t e = it.base + (int64_t)rr * row_len + col;
             if (vec) {
                 const v4f v = Cand<R>::value4(a, Rrt, e);
