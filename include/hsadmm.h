@@ -785,7 +785,8 @@ int hsadmm_kernel_grid(const hsadmm_plan_t* plan, int kernel_id);
  * the norms are ordered inside a layer.  Smaller plans and plans with CHANNEL or BOTH layers write every row in the
  * kept form and repair the pruned ones.  The published keys live in the caller's workspace, tagged with the number
  * of their call; that number comes from an atomic counter in the plan (the one thing besides the timing record that
- * a call changes in a plan), so calls from several threads stay safe.  A captured graph replays its call number: a
+ * a call changes in a plan; every plan counts from a start of its own), so calls from several threads stay safe and
+ * plans that take turns on one workspace do not read each other's keys.  A captured graph replays its call number: a
  * replay may then use the estimate an earlier replay left, which again changes no result.  Environment, read by
  * hsadmm_plan_create: HSADMM_NO_ESTIMATE (any value)
  * switches the estimate off, HSADMM_FORCE_ESTIMATE takes it whatever the size.

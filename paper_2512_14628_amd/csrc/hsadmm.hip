@@ -396,6 +396,10 @@ int hsadmm_plan_create_nested(const hsadmm_layer_t* layers, const hsadmm_nest_t*
     }
     hsadmm_plan* p = new (std::nothrow) hsadmm_plan();
     if (!p) return HSADMM_ERR_HOST_MEMORY;
+    // every plan numbers its estimating calls from a start of its own, far from the others', so that plans which take
+    // turns on one workspace (the static scratch above all) do not take each other's published keys for their own
+    static std::atomic<unsigned> plans_made{0};
+    p->est_calls.store((plans_made.fetch_add(1, std::memory_order_relaxed) + 1u) * 0x9E3779B1u, std::memory_order_relaxed);
     std::vector<uint16_t> group_layer;
     try {
         p->pack_align = pack_align_elems;
@@ -676,6 +680,8 @@ static int project_impl(const hsadmm_plan_t* p, const float* const* W_replicas, 
         ex.thr_tag = reinterpret_cast<unsigned int*>(ws + p->ws.est_thr_tag);
         ex.layers = p->d_layers;
         ex.gen = const_cast<hsadmm_plan*>(p)->est_calls.fetch_add(1, std::memory_order_relaxed) + 1u;
+        if (ex.gen == 0u)       // (the tag of a zeroed workspace: skipped when the counter wraps)
+            ex.gen = const_cast<hsadmm_plan*>(p)->est_calls.fetch_add(1, std::memory_order_relaxed) + 1u;
     }
     WorkList wl{};
     if (hinted) {
