@@ -171,11 +171,13 @@ def test_under_predictions_in_place_and_out_of_place():
 
 def test_ties_zero_columns_and_more_columns_than_the_selection_holds_in_registers():
     """Identical channels and positions (every key ties: lower index first at both levels), columns of zeros (so
-    that fewer nonzero candidates than k_kern remain: only positions of kept channels may fill up), and a view of
-    1100 * 9 = 9900 channels, beyond what the selection ranks from registers."""
+    that fewer nonzero candidates than k_kern remain: only positions of kept channels may fill up), and views of
+    1100 * 9 = 9900 and 9000 * 2 = 18000 channels (the latter in 9000 runs), beyond what the selection ranks from
+    registers."""
     from tests.gpu_harness import GpuRun
     shapes = [(6, 8, 4, 5, 0, 3, 7), (5, 6, 9, 6, 3, 2, 11), (4, 10, 4, 5, 0, 4, 16), (3, 1100, 9, 5, 0, 500, 2000),
-              (9, 12, 9, 6, 9, 12, 108), (7, 5, 1, 5, 0, 3, 2)]
+              (9, 12, 9, 6, 9, 12, 108), (7, 5, 1, 5, 0, 3, 2),
+              (2, 9000, 2, 5, 0, 4000, 5000)]      # more runs, too, than the selection holds in registers
     wl = wk.custom_workload(shapes, R=2, seed=3, sigma_replica=0.0)
     W, U = wk.generate(wl)
     U[:] = 0
